@@ -1,0 +1,124 @@
+/*
+ * mnnq - W4A8 / W4A16 quantized linear layer for AMD MI355X (gfx950).
+ *
+ * C-ABI boundary of the library.  The operation is the quantized Linear layer
+ * of the MNN-LLM paper (arXiv 2506.10443): weights [h, l] are quantized once,
+ * at load time, to asymmetric int4 (Section 4.2, Eq. 1); activations [e, l]
+ * arrive at run time and are quantized to int8 (Section 4.2); the result is
+ * [e, h] (Section 5.1).  Below: M = e (tokens), K = l (reduction), N = h
+ * (output features), G = K / 64 quantization groups along K.
+ *
+ * Conventions for every call
+ *   - Every pointer is a DEVICE pointer, 16-byte aligned, owned by the caller.
+ *     The library never allocates, frees or synchronises.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work; buffers must stay valid until the stream has
+ *     passed that work.
+ *   - Return value: MNNQ_OK (0) or a negative mnnq_status.  All argument
+ *     checks run before the first HIP call, so they also work on a machine
+ *     without a GPU.  NaN / Inf in W or x: undefined result, no error.
+ *   - Only group == 64 and mode == MNNQ_W4_ZP_INT are implemented.  K must be
+ *     a multiple of 64 and N a multiple of 16.
+ */
+#ifndef MNNQ_H
+#define MNNQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MNNQ_OK = 0,
+    MNNQ_ERR_NULL = -1,        /* a required pointer is NULL */
+    MNNQ_ERR_SHAPE = -2,       /* M, N or K <= 0, or K not a multiple of the group */
+    MNNQ_ERR_UNSUPPORTED = -3, /* group != 64, unknown mode, N not a multiple of 16 */
+    MNNQ_ERR_SIZE = -4,        /* packed / workspace buffer too small */
+    MNNQ_ERR_ALIGN = -5,       /* a pointer is not 16-byte aligned */
+    MNNQ_ERR_HIP = -6          /* a HIP call failed; see mnnq_last_hip_error() */
+} mnnq_status;
+
+typedef enum {
+    /* int4 codes 0..15, fp32 scale and integer zero point per (row, group):
+     * scale = (max - min) / 15, zero = round(-min / scale),
+     * q = clamp(round(w / scale) + zero, 0, 15), w^ = (q - zero) * scale.
+     * This is Eq. 1 of Section 4.2 with the offset rounded to the code grid. */
+    MNNQ_W4_ZP_INT = 0
+} mnnq_mode;
+
+/* Text for a status code (static storage). */
+const char *mnnq_status_string(int status);
+
+/* Raw hipError_t of the last MNNQ_ERR_HIP returned on the calling thread. */
+int mnnq_last_hip_error(void);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int mnnq_version(void);
+
+/* Bytes of the packed form of an [N, K] weight matrix; 0 if the arguments are
+ * not supported.  For K a multiple of 128 this is exactly N*K/2 + 5*N*K/64
+ * (codes + fp32 scale + one-byte zero point); for K = 64 * odd, one padding
+ * group per row tile is added. */
+size_t mnnq_packed_size(int64_t N, int64_t K, int group, int mode);
+
+/* Bytes of scratch the linear calls need for these shapes (split-K partial
+ * sums).  May be 0; then `workspace` may be NULL. */
+size_t mnnq_workspace_size(int64_t M, int64_t N, int64_t K, int group, int mode);
+
+/* Load-time step (Section 4.2 Eq. 1, Section 5.1 "rearranged at model loading
+ * phase"): quantize W and store it in the layout the decode and prefill kernels
+ * read.  W: device fp32 [N, K] row-major.  packed: device buffer of at least
+ * mnnq_packed_size() bytes, opaque; position independent, may be copied. */
+int mnnq_pack_weights(const float *W, int64_t N, int64_t K, int group, int mode,
+                      void *packed, size_t packed_bytes, void *stream);
+
+/* Canonical view of a packed matrix (for tests and export): q [N, K] one code
+ * per byte, scale [N, G] fp32, zero [N, G] u8.  Any output may be NULL. */
+int mnnq_unpack_weights(const void *packed, int64_t N, int64_t K, int group, int mode,
+                        uint8_t *q, float *scale, uint8_t *zero, void *stream);
+
+/* Run-time activation quantizer (Section 4.2: activations are quantized to
+ * int8 during calculation), per token, symmetric: sx[m] = max_k |x[m,k]| / 127,
+ * xq = clamp(round(x / sx), -127, 127); a zero row gives sx = 0, xq = 0.
+ * x: fp32 [M, K]; xq: int8 [M, K]; sx: fp32 [M]; xsum: int32 [M, G] sums of xq
+ * per group, or NULL. */
+int mnnq_quant_act(const float *x, int64_t M, int64_t K, int group,
+                   int8_t *xq, float *sx, int32_t *xsum, void *stream);
+
+/* Decode step, one token (Section 2.1: memory-bound phase):
+ *   y[n] = sx * sum_g scale[n,g] * sum_{k in g} xq[k] * (q[n,k] - zero[n,g]) (+ bias[n]).
+ * xq: int8 [K]; sx: fp32 [1]; bias: fp32 [N] or NULL; y: fp32 [N]. */
+int mnnq_linear_decode(const void *packed, int64_t N, int64_t K, int group, int mode,
+                       const int8_t *xq, const float *sx, const float *bias, float *y,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* Prefill, M tokens (Section 2.1: compute-bound phase): the same formula for
+ * every row m with its own sx[m].  xq: int8 [M, K]; sx: fp32 [M];
+ * y: fp32 [M, N] row-major. */
+int mnnq_linear_prefill(const void *packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                        const int8_t *xq, const float *sx, const float *bias, float *y,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* W4A16 variants (Section 4.2: int4 weights with fp16 activations on GPUs):
+ *   y[m,n] = sum_k float(x16[m,k]) * (q[n,k] - zero[n,g]) * scale[n,g] (+ bias[n]),
+ * fp32 accumulation.  x16: IEEE binary16 bits, [K] resp. [M, K]. */
+int mnnq_linear_decode_f16(const void *packed, int64_t N, int64_t K, int group, int mode,
+                           const uint16_t *x16, const float *bias, float *y,
+                           void *workspace, size_t workspace_bytes, void *stream);
+int mnnq_linear_prefill_f16(const void *packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                            const uint16_t *x16, const float *bias, float *y,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/* Integer group accumulators of the W4A8 kernels, for bit-exact checks:
+ *   acc[m, n, g] = sum_{k in g} xq[m,k] * (q[n,k] - zero[n,g])      (int32 [M, N, G]).
+ * use_prefill_kernel = 0 runs the decode kernel's inner loop row by row (any M),
+ * 1 runs the prefill kernel's MFMA loop. */
+int mnnq_linear_acc_debug(const void *packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                          const int8_t *xq, int32_t *acc, int use_prefill_kernel, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MNNQ_H */

@@ -1,0 +1,192 @@
+"""Thin Python binding of libmnnq.so: argument marshalling only.
+
+Every function has the name of the C-ABI entry point it calls (include/mnnq.h)
+and takes torch tensors that already live on the GPU; torch supplies device
+memory and the current stream, nothing else.  No step of the path runs in
+Python or on the CPU: if the library is missing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch  # noqa: F401  (must be imported first: the library binds to the HIP runtime torch loaded)
+
+GROUP = 64
+MODE_W4_ZP_INT = 0
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libmnnq.so")
+
+EXPORTS = (
+    "mnnq_status_string", "mnnq_last_hip_error", "mnnq_version", "mnnq_packed_size", "mnnq_workspace_size",
+    "mnnq_pack_weights", "mnnq_unpack_weights", "mnnq_quant_act", "mnnq_linear_decode",
+    "mnnq_linear_prefill", "mnnq_linear_decode_f16", "mnnq_linear_prefill_f16", "mnnq_linear_acc_debug",
+)
+
+
+class MnnqError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__("%s failed: %s (status %d, hip error %d)" % (
+            what, lib().mnnq_status_string(status).decode(), status, lib().mnnq_last_hip_error()))
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library.  Raises if it has not been built: there is no fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libmnnq.so is not built (%s); run `python -c 'import __graft_entry__ as g; g.build()'`" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        i64, i32, vp, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+        L.mnnq_status_string.restype = ctypes.c_char_p
+        L.mnnq_status_string.argtypes = [i32]
+        L.mnnq_last_hip_error.restype = i32
+        L.mnnq_version.restype = i32
+        L.mnnq_packed_size.restype = sz
+        L.mnnq_packed_size.argtypes = [i64, i64, i32, i32]
+        L.mnnq_workspace_size.restype = sz
+        L.mnnq_workspace_size.argtypes = [i64, i64, i64, i32, i32]
+        L.mnnq_pack_weights.argtypes = [vp, i64, i64, i32, i32, vp, sz, vp]
+        L.mnnq_unpack_weights.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
+        L.mnnq_quant_act.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp]
+        L.mnnq_linear_decode.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.mnnq_linear_prefill.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.mnnq_linear_decode_f16.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.mnnq_linear_prefill_f16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.mnnq_linear_acc_debug.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, i32, vp]
+        for name in EXPORTS[5:]:
+            getattr(L, name).restype = i32
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise MnnqError(status, what)
+
+
+def _dev(t, dtype, what):
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous %s tensor on the GPU" % (what, dtype))
+    return t
+
+
+def mnnq_packed_size(N: int, K: int, group: int = GROUP, mode: int = MODE_W4_ZP_INT) -> int:
+    return int(lib().mnnq_packed_size(N, K, group, mode))
+
+
+def mnnq_workspace_size(M: int, N: int, K: int, group: int = GROUP, mode: int = MODE_W4_ZP_INT) -> int:
+    return int(lib().mnnq_workspace_size(M, N, K, group, mode))
+
+
+def mnnq_pack_weights(W: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """W fp32 [N, K] on the GPU -> packed uint8 buffer."""
+    _dev(W, torch.float32, "W")
+    N, K = W.shape
+    size = mnnq_packed_size(N, K)
+    if size == 0:
+        _check(lib().mnnq_pack_weights(_ptr(W), N, K, GROUP, MODE_W4_ZP_INT, _ptr(W), 0, _stream()),
+               "mnnq_pack_weights")
+    if out is None:
+        out = torch.empty(size, dtype=torch.uint8, device=W.device)
+    _check(lib().mnnq_pack_weights(_ptr(W), N, K, GROUP, MODE_W4_ZP_INT, _ptr(out), out.numel(), _stream()),
+           "mnnq_pack_weights")
+    return out
+
+
+def mnnq_unpack_weights(packed: torch.Tensor, N: int, K: int):
+    """Canonical view: (q u8 [N,K], scale f32 [N,G], zero u8 [N,G])."""
+    _dev(packed, torch.uint8, "packed")
+    G = K // GROUP
+    q = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
+    s = torch.empty((N, G), dtype=torch.float32, device=packed.device)
+    z = torch.empty((N, G), dtype=torch.uint8, device=packed.device)
+    _check(lib().mnnq_unpack_weights(_ptr(packed), N, K, GROUP, MODE_W4_ZP_INT, _ptr(q), _ptr(s), _ptr(z),
+                                     _stream()), "mnnq_unpack_weights")
+    return q, s, z
+
+
+def mnnq_quant_act(x: torch.Tensor, want_xsum: bool = True, out=None):
+    """x fp32 [M, K] -> (xq i8 [M,K], sx f32 [M], xsum i32 [M,G] or None)."""
+    _dev(x, torch.float32, "x")
+    M, K = x.shape
+    if out is None:
+        xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+        sx = torch.empty((M,), dtype=torch.float32, device=x.device)
+        xsum = torch.empty((M, max(K // GROUP, 1)), dtype=torch.int32, device=x.device) if want_xsum else None
+    else:
+        xq, sx, xsum = out
+    _check(lib().mnnq_quant_act(_ptr(x), M, K, GROUP, _ptr(xq), _ptr(sx), _ptr(xsum), _stream()),
+           "mnnq_quant_act")
+    return xq, sx, xsum
+
+
+def mnnq_linear_decode(packed, N: int, K: int, xq, sx, bias=None, out=None):
+    """One token: xq i8 [K] (or [1,K]), sx f32 [1] -> y f32 [N]."""
+    _dev(packed, torch.uint8, "packed"); _dev(xq, torch.int8, "xq"); _dev(sx, torch.float32, "sx")
+    if xq.numel() != K:
+        raise ValueError("xq must hold K values")
+    y = torch.empty((N,), dtype=torch.float32, device=packed.device) if out is None else out
+    _check(lib().mnnq_linear_decode(_ptr(packed), N, K, GROUP, MODE_W4_ZP_INT, _ptr(xq), _ptr(sx), _ptr(bias),
+                                    _ptr(y), None, 0, _stream()), "mnnq_linear_decode")
+    return y
+
+
+def mnnq_linear_prefill(packed, N: int, K: int, xq, sx, bias=None, out=None):
+    """M tokens: xq i8 [M,K], sx f32 [M] -> y f32 [M,N]."""
+    _dev(packed, torch.uint8, "packed"); _dev(xq, torch.int8, "xq"); _dev(sx, torch.float32, "sx")
+    M = xq.shape[0]
+    if xq.shape[1] != K or sx.numel() != M:
+        raise ValueError("xq must be [M,K] and sx [M]")
+    y = torch.empty((M, N), dtype=torch.float32, device=packed.device) if out is None else out
+    _check(lib().mnnq_linear_prefill(_ptr(packed), M, N, K, GROUP, MODE_W4_ZP_INT, _ptr(xq), _ptr(sx),
+                                     _ptr(bias), _ptr(y), None, 0, _stream()), "mnnq_linear_prefill")
+    return y
+
+
+def mnnq_linear_decode_f16(packed, N: int, K: int, x16, bias=None, out=None):
+    """One token, W4A16: x16 fp16 [K] -> y f32 [N]."""
+    _dev(packed, torch.uint8, "packed"); _dev(x16, torch.float16, "x16")
+    if x16.numel() != K:
+        raise ValueError("x16 must hold K values")
+    y = torch.empty((N,), dtype=torch.float32, device=packed.device) if out is None else out
+    _check(lib().mnnq_linear_decode_f16(_ptr(packed), N, K, GROUP, MODE_W4_ZP_INT, _ptr(x16), _ptr(bias),
+                                        _ptr(y), None, 0, _stream()), "mnnq_linear_decode_f16")
+    return y
+
+
+def mnnq_linear_prefill_f16(packed, N: int, K: int, x16, bias=None, out=None):
+    """M tokens, W4A16: x16 fp16 [M,K] -> y f32 [M,N]."""
+    _dev(packed, torch.uint8, "packed"); _dev(x16, torch.float16, "x16")
+    M = x16.shape[0]
+    if x16.shape[1] != K:
+        raise ValueError("x16 must be [M,K]")
+    y = torch.empty((M, N), dtype=torch.float32, device=packed.device) if out is None else out
+    _check(lib().mnnq_linear_prefill_f16(_ptr(packed), M, N, K, GROUP, MODE_W4_ZP_INT, _ptr(x16), _ptr(bias),
+                                         _ptr(y), None, 0, _stream()), "mnnq_linear_prefill_f16")
+    return y
+
+
+def mnnq_linear_acc_debug(packed, N: int, K: int, xq, use_prefill_kernel: bool):
+    """Integer group accumulators I[m,n,g] (int32 [M,N,G]) from the decode or the prefill kernel."""
+    _dev(packed, torch.uint8, "packed"); _dev(xq, torch.int8, "xq")
+    xq2 = xq.reshape(-1, K)
+    M = xq2.shape[0]
+    acc = torch.empty((M, N, K // GROUP), dtype=torch.int32, device=packed.device)
+    _check(lib().mnnq_linear_acc_debug(_ptr(packed), M, N, K, GROUP, MODE_W4_ZP_INT, _ptr(xq2), _ptr(acc),
+                                       1 if use_prefill_kernel else 0, _stream()), "mnnq_linear_acc_debug")
+    return acc

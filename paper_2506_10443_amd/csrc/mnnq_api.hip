@@ -1,0 +1,179 @@
+// C-ABI entry points of libmnnq.so: argument validation (all of it before the
+// first HIP call), then the kernel launchers.
+#include "mnnq_common.h"
+
+namespace mnnq {
+
+static thread_local int t_last_hip_error = 0;
+
+int record_hip_error(hipError_t e)
+{
+    t_last_hip_error = (int)e;
+    return MNNQ_ERR_HIP;
+}
+
+namespace {
+
+constexpr int64_t kMaxDecodeK = 49152;     // int8 row + block sums in LDS: 160 B per 128 k, under 64 KiB
+constexpr int64_t kMaxDecodeKF16 = 30720;  // fp16 row in LDS: 256 B per 128 k, under 64 KiB
+constexpr int64_t kMaxM = 65535;
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// Shape / mode checks shared by every call.  Returns MNNQ_OK or the error.
+int check_shape(int64_t N, int64_t K, int group, int mode)
+{
+    if (N <= 0 || K <= 0) return MNNQ_ERR_SHAPE;
+    if (group != kGroup || mode != MNNQ_W4_ZP_INT) return MNNQ_ERR_UNSUPPORTED;
+    if (K % group != 0) return MNNQ_ERR_SHAPE;
+    if (N % kTileN != 0) return MNNQ_ERR_UNSUPPORTED;
+    if (N > (int64_t)1 << 24 || K > (int64_t)1 << 24) return MNNQ_ERR_UNSUPPORTED;
+    return MNNQ_OK;
+}
+
+}  // namespace
+}  // namespace mnnq
+
+using namespace mnnq;
+
+extern "C" {
+
+const char* mnnq_status_string(int status)
+{
+    switch (status) {
+        case MNNQ_OK: return "ok";
+        case MNNQ_ERR_NULL: return "null pointer";
+        case MNNQ_ERR_SHAPE: return "bad shape";
+        case MNNQ_ERR_UNSUPPORTED: return "unsupported group, mode or size";
+        case MNNQ_ERR_SIZE: return "buffer too small";
+        case MNNQ_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case MNNQ_ERR_HIP: return "HIP call failed";
+        default: return "unknown status";
+    }
+}
+
+int mnnq_last_hip_error(void) { return t_last_hip_error; }
+
+int mnnq_version(void) { return 100; }
+
+size_t mnnq_packed_size(int64_t N, int64_t K, int group, int mode)
+{
+    if (check_shape(N, K, group, mode) != MNNQ_OK) return 0;
+    return make_layout(N, K).total();
+}
+
+size_t mnnq_workspace_size(int64_t M, int64_t N, int64_t K, int group, int mode)
+{
+    (void)M;
+    if (check_shape(N, K, group, mode) != MNNQ_OK) return 0;
+    return 0;  // partial sums of split rows are combined inside a workgroup
+}
+
+int mnnq_pack_weights(const float* W, int64_t N, int64_t K, int group, int mode, void* packed,
+                      size_t packed_bytes, void* stream)
+{
+    if (!W || !packed) return MNNQ_ERR_NULL;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    if (misaligned(W) || misaligned(packed)) return MNNQ_ERR_ALIGN;
+    const Layout L = make_layout(N, K);
+    if (packed_bytes < L.total()) return MNNQ_ERR_SIZE;
+    return launch_pack(W, L, static_cast<uint8_t*>(packed), static_cast<hipStream_t>(stream));
+}
+
+int mnnq_unpack_weights(const void* packed, int64_t N, int64_t K, int group, int mode, uint8_t* q,
+                        float* scale, uint8_t* zero, void* stream)
+{
+    if (!packed) return MNNQ_ERR_NULL;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    if (misaligned(packed) || misaligned(q) || misaligned(scale) || misaligned(zero)) return MNNQ_ERR_ALIGN;
+    if (!q && !scale && !zero) return MNNQ_OK;
+    return launch_unpack(static_cast<const uint8_t*>(packed), make_layout(N, K), q, scale, zero,
+                         static_cast<hipStream_t>(stream));
+}
+
+int mnnq_quant_act(const float* x, int64_t M, int64_t K, int group, int8_t* xq, float* sx, int32_t* xsum,
+                   void* stream)
+{
+    if (!x || !xq || !sx) return MNNQ_ERR_NULL;
+    if (M <= 0 || K <= 0) return MNNQ_ERR_SHAPE;
+    if (group != kGroup) return MNNQ_ERR_UNSUPPORTED;
+    if (K % group != 0) return MNNQ_ERR_SHAPE;
+    if (M > ((int64_t)1 << 31) - 1) return MNNQ_ERR_UNSUPPORTED;
+    // sx and xsum are arrays of 4-byte items; only the vector-accessed buffers need 16 bytes.
+    if (misaligned(x) || misaligned(xq)) return MNNQ_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(sx) & 3u) || (reinterpret_cast<uintptr_t>(xsum) & 3u)) return MNNQ_ERR_ALIGN;
+    return launch_quant_act(x, M, K, xq, sx, xsum, static_cast<hipStream_t>(stream));
+}
+
+int mnnq_linear_decode(const void* packed, int64_t N, int64_t K, int group, int mode, const int8_t* xq,
+                       const float* sx, const float* bias, float* y, void* workspace, size_t workspace_bytes,
+                       void* stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    if (!packed || !xq || !sx || !y) return MNNQ_ERR_NULL;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    if (K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
+    if (misaligned(packed) || misaligned(xq) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(sx) & 3u) return MNNQ_ERR_ALIGN;
+    return launch_decode(static_cast<const uint8_t*>(packed), make_layout(N, K), xq, sx, bias, y,
+                         static_cast<hipStream_t>(stream));
+}
+
+int mnnq_linear_prefill(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                        const int8_t* xq, const float* sx, const float* bias, float* y, void* workspace,
+                        size_t workspace_bytes, void* stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    if (!packed || !xq || !sx || !y) return MNNQ_ERR_NULL;
+    if (M <= 0) return MNNQ_ERR_SHAPE;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    if (M > ((int64_t)1 << 24)) return MNNQ_ERR_UNSUPPORTED;
+    if (misaligned(packed) || misaligned(xq) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(sx) & 3u) return MNNQ_ERR_ALIGN;
+    return launch_prefill(static_cast<const uint8_t*>(packed), make_layout(N, K), M, xq, sx, bias, y, nullptr,
+                          static_cast<hipStream_t>(stream));
+}
+
+int mnnq_linear_decode_f16(const void* packed, int64_t N, int64_t K, int group, int mode, const uint16_t* x16,
+                           const float* bias, float* y, void* workspace, size_t workspace_bytes, void* stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    if (!packed || !x16 || !y) return MNNQ_ERR_NULL;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    if (K > kMaxDecodeKF16) return MNNQ_ERR_UNSUPPORTED;
+    if (misaligned(packed) || misaligned(x16) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
+    return launch_decode_f16(static_cast<const uint8_t*>(packed), make_layout(N, K), x16, bias, y,
+                             static_cast<hipStream_t>(stream));
+}
+
+int mnnq_linear_prefill_f16(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                            const uint16_t* x16, const float* bias, float* y, void* workspace,
+                            size_t workspace_bytes, void* stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    if (!packed || !x16 || !y) return MNNQ_ERR_NULL;
+    if (M <= 0) return MNNQ_ERR_SHAPE;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    if (M > ((int64_t)1 << 24)) return MNNQ_ERR_UNSUPPORTED;
+    if (misaligned(packed) || misaligned(x16) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
+    return launch_prefill_f16(static_cast<const uint8_t*>(packed), make_layout(N, K), M, x16, bias, y,
+                              static_cast<hipStream_t>(stream));
+}
+
+int mnnq_linear_acc_debug(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                          const int8_t* xq, int32_t* acc, int use_prefill_kernel, void* stream)
+{
+    if (!packed || !xq || !acc) return MNNQ_ERR_NULL;
+    if (M <= 0) return MNNQ_ERR_SHAPE;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    if (M > kMaxM) return MNNQ_ERR_UNSUPPORTED;
+    if (!use_prefill_kernel && K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
+    if (misaligned(packed) || misaligned(xq) || misaligned(acc)) return MNNQ_ERR_ALIGN;
+    const Layout L = make_layout(N, K);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (use_prefill_kernel)
+        return launch_prefill(static_cast<const uint8_t*>(packed), L, M, xq, nullptr, nullptr, nullptr, acc, st);
+    return launch_decode_acc(static_cast<const uint8_t*>(packed), L, M, xq, acc, st);
+}
+
+}  // extern "C"

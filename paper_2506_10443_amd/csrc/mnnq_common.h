@@ -1,0 +1,90 @@
+// Shared definitions of the mnnq HIP library (gfx950 only).
+//
+// Packed weight layout ("chunk layout").  The paper rearranges weights once at
+// load so that the inner loop reads exactly what one instruction consumes
+// (Section 5.1); on CDNA4 the unit is one 128-bit load per lane of a 64-wide
+// wavefront:
+//
+//   row tile  t = n / 16            (16 output rows)
+//   chunk     c = g / 2             (two quantization groups = 128 values of K)
+//   C = ceil(G / 2) chunks per row tile; an odd G gets one zero padding group.
+//
+//   codes  : [T][C][64 lanes][16 B]   at byte 0
+//            lane l serves row 16 t + (l % 16), k-block kb = l / 16;
+//            bytes 0..7  = its 16 codes of group 2c   (k = 64 (2c)   + 16 kb + j),
+//            bytes 8..15 = its 16 codes of group 2c+1 (k = 64 (2c+1) + 16 kb + j).
+//            Inside 8 bytes, dword d, byte b holds code j = 8 d + b in the low
+//            nibble and code j = 8 d + 4 + b in the high nibble, so that
+//            `w & 0x0f0f0f0f` and `(w >> 4) & 0x0f0f0f0f` give codes 8d..8d+3
+//            and 8d+4..8d+7 in byte order.
+//   scales : [T][C][16 rows][2] fp32  at byte T*C*1024
+//   zeros  : [T][C][16 rows][2] u8    at byte T*C*1024 + T*C*128
+//
+// One chunk is exactly one wave-wide 128-bit load (1 KiB) for the decode GEMV,
+// and lane l's 16 bytes are exactly its B operands of two 16x16x64 int8 MFMAs
+// (one per group) for the prefill GEMM.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/mnnq.h"
+
+namespace mnnq {
+
+constexpr int kGroup = 64;
+constexpr int kTileN = 16;
+constexpr int kChunkBytes = 1024;
+
+struct Layout {
+    int64_t N, K;
+    int64_t T;  // row tiles
+    int64_t G;  // groups per row
+    int64_t C;  // chunks per row tile
+    size_t codes_bytes, scales_bytes, zeros_bytes;
+    __host__ __device__ size_t scales_off() const { return codes_bytes; }
+    __host__ __device__ size_t zeros_off() const { return codes_bytes + scales_bytes; }
+    __host__ __device__ size_t total() const { return codes_bytes + scales_bytes + zeros_bytes; }
+};
+
+inline __host__ __device__ Layout make_layout(int64_t N, int64_t K)
+{
+    Layout L;
+    L.N = N; L.K = K;
+    L.T = N / kTileN;
+    L.G = K / kGroup;
+    L.C = (L.G + 1) / 2;
+    L.codes_bytes = (size_t)L.T * L.C * kChunkBytes;
+    L.scales_bytes = (size_t)L.T * L.C * 32 * sizeof(float);
+    L.zeros_bytes = (size_t)L.T * L.C * 32;
+    return L;
+}
+
+// Records a failing HIP call for mnnq_last_hip_error() and maps it to a status.
+int record_hip_error(hipError_t e);
+
+#define MNNQ_HIP_TRY(expr)                                   \
+    do {                                                     \
+        hipError_t e_ = (expr);                              \
+        if (e_ != hipSuccess) return ::mnnq::record_hip_error(e_); \
+    } while (0)
+
+// Kernel launchers (one translation unit each).  All return a status.
+int launch_pack(const float* W, const Layout& L, uint8_t* packed, hipStream_t st);
+int launch_unpack(const uint8_t* packed, const Layout& L, uint8_t* q, float* scale, uint8_t* zero,
+                  hipStream_t st);
+int launch_quant_act(const float* x, int64_t M, int64_t K, int8_t* xq, float* sx, int32_t* xsum,
+                     hipStream_t st);
+int launch_decode(const uint8_t* packed, const Layout& L, const int8_t* xq, const float* sx,
+                  const float* bias, float* y, hipStream_t st);
+int launch_decode_acc(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq,
+                      int32_t* acc, hipStream_t st);
+int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq,
+                   const float* sx, const float* bias, float* y, int32_t* acc_debug, hipStream_t st);
+int launch_decode_f16(const uint8_t* packed, const Layout& L, const uint16_t* x16, const float* bias,
+                      float* y, hipStream_t st);
+int launch_prefill_f16(const uint8_t* packed, const Layout& L, int64_t M, const uint16_t* x16,
+                       const float* bias, float* y, hipStream_t st);
+
+}  // namespace mnnq

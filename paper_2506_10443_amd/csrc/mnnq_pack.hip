@@ -1,0 +1,135 @@
+// Load-time step: quantize fp32 weights to asymmetric int4 (Section 4.2, Eq. 1,
+// integer zero point, groups of 64 along K) and store them in the chunk layout
+// described in mnnq_common.h; plus the inverse view used by tests and export.
+//
+// This file is compiled with -ffp-contract=off: the quantizer is a fixed
+// sequence of IEEE binary32 operations (subtract, divide, round-to-nearest-even,
+// add, clamp) and must not be fused.
+#include "mnnq_common.h"
+
+namespace mnnq {
+
+namespace {
+
+constexpr int kTeam = 16;           // lanes per (row, group): 16 x float4 = 64 weights
+constexpr int kPackThreads = 256;   // 16 teams per workgroup
+
+__global__ __launch_bounds__(kPackThreads) void pack_kernel(const float* __restrict__ W, Layout L,
+                                                            uint8_t* __restrict__ packed)
+{
+    const int64_t team = (int64_t)blockIdx.x * (kPackThreads / kTeam) + threadIdx.x / kTeam;
+    const int li = threadIdx.x % kTeam;
+    const int64_t total = L.N * L.G;
+    // Whole teams leave together, so the 16-lane shuffles below stay convergent.
+    if (team >= total) return;
+    const int64_t n = team / L.G;
+    const int64_t g = team % L.G;
+
+    const float4 w = reinterpret_cast<const float4*>(W + team * kGroup)[li];
+    float mn = fminf(fminf(w.x, w.y), fminf(w.z, w.w));
+    float mx = fmaxf(fmaxf(w.x, w.y), fmaxf(w.z, w.w));
+#pragma unroll
+    for (int o = 1; o < kTeam; o <<= 1) {
+        mn = fminf(mn, __shfl_xor(mn, o, kTeam));
+        mx = fmaxf(mx, __shfl_xor(mx, o, kTeam));
+    }
+    // A group that does not straddle zero gets its range widened to contain it.
+    mn = fminf(mn, 0.0f);
+    mx = fmaxf(mx, 0.0f);
+
+    float scale = 1.0f, zero = 0.0f;
+    uint32_t c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+    if (mx != mn) {
+        scale = (mx - mn) / 15.0f;
+        zero = rintf((-mn) / scale);
+        c0 = (uint32_t)fminf(fmaxf(rintf(w.x / scale) + zero, 0.0f), 15.0f);
+        c1 = (uint32_t)fminf(fmaxf(rintf(w.y / scale) + zero, 0.0f), 15.0f);
+        c2 = (uint32_t)fminf(fmaxf(rintf(w.z / scale) + zero, 0.0f), 15.0f);
+        c3 = (uint32_t)fminf(fmaxf(rintf(w.w / scale) + zero, 0.0f), 15.0f);
+    }
+    // Lane li holds codes j = 4 (li % 4) .. +3 of k-block kb = li / 4.  Codes
+    // j % 8 < 4 go to low nibbles, the others to high nibbles of the same bytes.
+    uint32_t v = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+    if (li & 1) v <<= 4;
+    v |= __shfl_xor(v, 1, kTeam);
+
+    const int64_t t = n / kTileN;
+    const int r = (int)(n % kTileN);
+    const int64_t c = g / 2;
+    const int half = (int)(g & 1);
+    const int kb = li / 4;
+    const int d = (li % 4) / 2;
+    const int64_t chunk = t * L.C + c;
+    uint32_t* slot = reinterpret_cast<uint32_t*>(packed + chunk * kChunkBytes + (16 * kb + r) * 16);
+    float* sc = reinterpret_cast<float*>(packed + L.scales_off()) + (chunk * 16 + r) * 2;
+    uint8_t* zp = packed + L.zeros_off() + (chunk * 16 + r) * 2;
+    if ((li & 1) == 0) slot[half * 2 + d] = v;
+    if (li == 0) {
+        sc[half] = scale;
+        zp[half] = (uint8_t)zero;
+    }
+    // Odd number of groups: the second half of the last chunk is padding that
+    // contributes nothing (codes 0, scale 0, zero 0).
+    if ((L.G & 1) && g == L.G - 1) {
+        if ((li & 1) == 0) slot[2 + d] = 0u;
+        if (li == 0) {
+            sc[1] = 0.0f;
+            zp[1] = 0;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void unpack_kernel(const uint8_t* __restrict__ packed, Layout L,
+                                                     uint8_t* __restrict__ q, float* __restrict__ scale,
+                                                     uint8_t* __restrict__ zero)
+{
+    // One thread per (row, group, k-block): 8 packed bytes -> 16 codes.
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t total = L.N * L.G * 4;
+    if (idx >= total) return;
+    const int kb = (int)(idx % 4);
+    const int64_t g = (idx / 4) % L.G;
+    const int64_t n = idx / (4 * L.G);
+    const int64_t t = n / kTileN;
+    const int r = (int)(n % kTileN);
+    const int64_t chunk = t * L.C + g / 2;
+    const int half = (int)(g & 1);
+    if (q) {
+        const uint2 w = *reinterpret_cast<const uint2*>(packed + chunk * kChunkBytes +
+                                                        (16 * kb + r) * 16 + half * 8);
+        uint4 o;
+        o.x = w.x & 0x0f0f0f0fu;
+        o.y = (w.x >> 4) & 0x0f0f0f0fu;
+        o.z = w.y & 0x0f0f0f0fu;
+        o.w = (w.y >> 4) & 0x0f0f0f0fu;
+        *reinterpret_cast<uint4*>(q + n * L.K + g * kGroup + 16 * kb) = o;
+    }
+    if (kb == 0) {
+        const int64_t mi = (chunk * 16 + r) * 2 + half;
+        if (scale) scale[n * L.G + g] = reinterpret_cast<const float*>(packed + L.scales_off())[mi];
+        if (zero) zero[n * L.G + g] = (packed + L.zeros_off())[mi];
+    }
+}
+
+}  // namespace
+
+int launch_pack(const float* W, const Layout& L, uint8_t* packed, hipStream_t st)
+{
+    const int64_t teams = L.N * L.G;
+    const int64_t blocks = (teams + (kPackThreads / kTeam) - 1) / (kPackThreads / kTeam);
+    hipLaunchKernelGGL(pack_kernel, dim3((unsigned)blocks), dim3(kPackThreads), 0, st, W, L, packed);
+    MNNQ_HIP_TRY(hipGetLastError());
+    return MNNQ_OK;
+}
+
+int launch_unpack(const uint8_t* packed, const Layout& L, uint8_t* q, float* scale, uint8_t* zero,
+                  hipStream_t st)
+{
+    const int64_t total = L.N * L.G * 4;
+    const int64_t blocks = (total + 255) / 256;
+    hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)blocks), dim3(256), 0, st, packed, L, q, scale, zero);
+    MNNQ_HIP_TRY(hipGetLastError());
+    return MNNQ_OK;
+}
+
+}  // namespace mnnq

@@ -1,0 +1,120 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol include/mnnq.h declares, and rejects bad arguments before touching
+HIP.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2506_10443_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # non-NULL, 16-byte aligned; never dereferenced because validation fails first
+ODD = 0x10004   # 4-byte aligned only
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return binding.lib()
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "mnnq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mnnq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_exports_match_header(L):
+    names = _declared()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_packed_size(L):
+    # K multiple of 128: exactly codes + fp32 scale + one-byte zero
+    for N, K in [(8960, 1536), (3584, 18944), (152064, 3584), (16, 128)]:
+        assert binding.mnnq_packed_size(N, K) == N * K // 2 + 5 * N * (K // 64)
+    # odd number of groups: one padding group per row
+    assert binding.mnnq_packed_size(32, 192) == 32 * 256 // 2 + 5 * 32 * 4
+    assert binding.mnnq_packed_size(32, 64) == 32 * 128 // 2 + 5 * 32 * 2
+    # unsupported arguments
+    assert binding.mnnq_packed_size(8, 128) == 0       # N not a multiple of 16
+    assert binding.mnnq_packed_size(16, 100) == 0      # K not a multiple of 64
+    assert binding.mnnq_packed_size(16, 128, 32) == 0  # group
+    assert binding.mnnq_packed_size(16, 128, 64, 1) == 0  # mode
+    assert binding.mnnq_packed_size(0, 128) == 0 and binding.mnnq_packed_size(16, -64) == 0
+    assert binding.mnnq_workspace_size(1, 16, 128) == 0
+
+
+def test_status_strings(L):
+    seen = set()
+    for s in range(0, -7, -1):
+        txt = L.mnnq_status_string(s).decode()
+        assert txt and txt != "unknown status"
+        seen.add(txt)
+    assert len(seen) == 7
+    assert L.mnnq_status_string(-99).decode() == "unknown status"
+    assert L.mnnq_version() >= 100
+
+
+def test_argument_validation_precedes_hip(L):
+    i64 = ctypes.c_int64
+    OK, NULL, SHAPE, UNSUP, SIZE, ALIGN = 0, -1, -2, -3, -4, -5
+    pw = L.mnnq_pack_weights
+    assert pw(None, 16, 128, 64, 0, FAKE, 10**9, None) == NULL
+    assert pw(FAKE, 16, 128, 64, 0, None, 10**9, None) == NULL
+    assert pw(FAKE, 0, 128, 64, 0, FAKE, 10**9, None) == SHAPE
+    assert pw(FAKE, 16, 100, 64, 0, FAKE, 10**9, None) == SHAPE
+    assert pw(FAKE, 16, 128, 32, 0, FAKE, 10**9, None) == UNSUP
+    assert pw(FAKE, 16, 128, 64, 7, FAKE, 10**9, None) == UNSUP
+    assert pw(FAKE, 24, 128, 64, 0, FAKE, 10**9, None) == UNSUP
+    assert pw(ODD, 16, 128, 64, 0, FAKE, 10**9, None) == ALIGN
+    assert pw(FAKE, 16, 128, 64, 0, FAKE, binding.mnnq_packed_size(16, 128) - 1, None) == SIZE
+
+    qa = L.mnnq_quant_act
+    assert qa(None, 1, 128, 64, FAKE, FAKE, None, None) == NULL
+    assert qa(FAKE, 1, 128, 64, None, FAKE, None, None) == NULL
+    assert qa(FAKE, 0, 128, 64, FAKE, FAKE, None, None) == SHAPE
+    assert qa(FAKE, 1, 96, 64, FAKE, FAKE, None, None) == SHAPE
+    assert qa(FAKE, 1, 128, 16, FAKE, FAKE, None, None) == UNSUP
+    assert qa(ODD, 1, 128, 64, FAKE, FAKE, None, None) == ALIGN
+
+    ld = L.mnnq_linear_decode
+    assert ld(None, 16, 128, 64, 0, FAKE, FAKE, None, FAKE, None, 0, None) == NULL
+    assert ld(FAKE, 16, 128, 64, 0, FAKE, None, None, FAKE, None, 0, None) == NULL
+    assert ld(FAKE, 16, 128, 64, 0, FAKE, FAKE, None, None, None, 0, None) == NULL
+    assert ld(FAKE, 16, 192 + 32, 64, 0, FAKE, FAKE, None, FAKE, None, 0, None) == SHAPE
+    assert ld(FAKE, 20, 128, 64, 0, FAKE, FAKE, None, FAKE, None, 0, None) == UNSUP
+    assert ld(FAKE, 16, 64 * 1024, 64, 0, FAKE, FAKE, None, FAKE, None, 0, None) == UNSUP  # row too long for LDS
+    assert ld(FAKE, 16, 128, 64, 0, ODD, FAKE, None, FAKE, None, 0, None) == ALIGN
+    assert ld(FAKE, 16, 128, 64, 0, FAKE, FAKE, ODD, FAKE, None, 0, None) == ALIGN
+
+    lp = L.mnnq_linear_prefill
+    assert lp(FAKE, 0, 16, 128, 64, 0, FAKE, FAKE, None, FAKE, None, 0, None) == SHAPE
+    assert lp(FAKE, 4, 16, 128, 64, 0, None, FAKE, None, FAKE, None, 0, None) == NULL
+    assert lp(FAKE, 4, 16, 128, 64, 1, FAKE, FAKE, None, FAKE, None, 0, None) == UNSUP
+    assert lp(FAKE, 4, 16, 128, 64, 0, FAKE, FAKE, None, ODD, None, 0, None) == ALIGN
+
+    assert L.mnnq_linear_decode_f16(FAKE, 16, 128, 64, 0, None, None, FAKE, None, 0, None) == NULL
+    assert L.mnnq_linear_decode_f16(FAKE, 16, 100, 64, 0, FAKE, None, FAKE, None, 0, None) == SHAPE
+    assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 128, 64, 0, FAKE, None, None, None, 0, None) == NULL
+    assert L.mnnq_linear_prefill_f16(FAKE, -1, 16, 128, 64, 0, FAKE, None, FAKE, None, 0, None) == SHAPE
+    assert L.mnnq_linear_acc_debug(FAKE, 1, 16, 128, 64, 0, FAKE, None, 0, None) == NULL
+    assert L.mnnq_linear_acc_debug(FAKE, 70000, 16, 128, 64, 0, FAKE, FAKE, 0, None) == UNSUP
+    assert L.mnnq_unpack_weights(None, 16, 128, 64, 0, FAKE, FAKE, FAKE, None) == NULL
+    assert L.mnnq_unpack_weights(FAKE, 16, 128, 64, 0, None, None, None, None) == OK  # nothing asked for
+    assert L.mnnq_last_hip_error() == 0
+    del i64
+
+
+def test_binding_refuses_cpu_tensors(L):
+    import torch
+    with pytest.raises(TypeError):
+        binding.mnnq_pack_weights(torch.zeros(16, 128))
+    with pytest.raises(TypeError):
+        binding.mnnq_quant_act(torch.zeros(1, 128))
