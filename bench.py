@@ -1,0 +1,311 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A8 quantized linear hot path on one MI355X.
+
+Workload (default): the Qwen2-7B-shaped configuration - 28 blocks of
+q|k|v 3584->4608, o 3584->3584, gate|up 3584->37888, down 18944->3584 plus the
+lm_head 3584->152064 - as one decode step (batch 1) and one prefill pass
+(M = 1024 tokens, 28 blocks).  One "step" = activation quantization + linear
+for every projection of the decode pass, then of the prefill pass.  Inputs are
+synthetic and resident in HBM before the timed region; every block has its own
+packed buffer (3.8 GB in total, far beyond the 256 MB Infinity Cache), so the
+decode pass streams weights from HBM.
+
+Prints ONE JSON line.  `value` is the decode GEMV rate in GB/s of algorithmic
+bytes; the prefill rate in int8 TOPS is in `prefill_value`.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published (5.0 POP/s)
+G = 64
+
+
+def decode_bytes(N, K):
+    """Algorithmic bytes of one decode GEMV: codes + fp32 scale + 1-byte zero
+    per group, the int8 activation row, and the fp32 output."""
+    return N * K // 2 + 5 * N * (K // G) + K + 4 * N
+
+
+def prefill_ops(M, N, K):
+    return 2 * M * N * K
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--model", default="qwen2-7b", choices=["qwen2-1.5b", "qwen2-7b", "llama3-8b"])
+    ap.add_argument("--phase", default="both", choices=["both", "decode", "prefill"])
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; the path shards by output rows (see DESIGN.md) "
+              "but no multi-GPU figure is produced.  Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2506_10443_amd import binding as B, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    B.lib()  # fail loudly if the HIP library is not built
+
+    spec = synth.MODELS[args.model]
+    n_blocks = spec["blocks"]
+    M_pre = spec["prefill_m"]
+    layers = synth.block_layers(args.model, fused=True)   # q|k|v and gate|up share their input
+
+    # ---- weights: one block drawn on the host (seeded), packed into n_blocks distinct buffers
+    t0 = time.time()
+    packed = {name: [] for name, _, _ in layers}
+    pack_bytes_in = 0
+    pack_ms = 0.0
+    for name, N, K in layers:
+        parts = [synth.weights(*spec["layers"][p], synth.layer_seed(args.model, 0, p))
+                 for p in synth.fused_parts(name)]
+        W = torch.from_numpy(np.concatenate(parts) if len(parts) > 1 else parts[0]).to(dev)
+        del parts
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n_blocks):
+            packed[name].append(B.mnnq_pack_weights(W))
+        e1.record()
+        torch.cuda.synchronize()
+        pack_ms += e0.elapsed_time(e1)
+        pack_bytes_in += n_blocks * N * K * 4
+        del W
+    lm = None
+    if spec["lm_head"] is not None:
+        N, K = spec["lm_head"]
+        W = torch.from_numpy(synth.weights(N, K, synth.layer_seed(args.model, 0, "lm_head"))).to(dev)
+        lm = (B.mnnq_pack_weights(W), N, K)
+        del W
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    # ---- activations (fp32, resident) and static outputs
+    def act(M, K, seed):
+        return torch.from_numpy(synth.activations(M, K, seed, outliers=True)).to(dev)
+
+    io_dec, io_pre = {}, {}
+    for i, (name, N, K) in enumerate(layers):
+        for M, io in ((1, io_dec), (M_pre, io_pre)):
+            x = act(M, K, 9000 + 10 * i + (0 if M == 1 else 1))
+            xq = torch.empty((M, K), dtype=torch.int8, device=dev)
+            sx = torch.empty((M,), dtype=torch.float32, device=dev)
+            y = torch.empty((M, N), dtype=torch.float32, device=dev)
+            io[name] = (x, xq, sx, y)
+    if lm is not None:
+        x = act(1, lm[2], 9990)
+        io_dec["lm_head"] = (x, torch.empty((1, lm[2]), dtype=torch.int8, device=dev),
+                             torch.empty((1,), dtype=torch.float32, device=dev),
+                             torch.empty((1, lm[1]), dtype=torch.float32, device=dev))
+
+    def decode_pass():
+        for b in range(n_blocks):
+            for name, N, K in layers:
+                x, xq, sx, y = io_dec[name]
+                B.mnnq_quant_act(x, want_xsum=False, out=(xq, sx, None))
+                B.mnnq_linear_decode(packed[name][b], N, K, xq, sx, out=y)
+        if lm is not None:
+            x, xq, sx, y = io_dec["lm_head"]
+            B.mnnq_quant_act(x, want_xsum=False, out=(xq, sx, None))
+            B.mnnq_linear_decode(lm[0], lm[1], lm[2], xq, sx, out=y)
+
+    def prefill_pass():
+        for b in range(n_blocks):
+            for name, N, K in layers:
+                x, xq, sx, y = io_pre[name]
+                B.mnnq_quant_act(x, want_xsum=False, out=(xq, sx, None))
+                B.mnnq_linear_prefill(packed[name][b], N, K, xq, sx, out=y)
+
+    do_dec = args.phase in ("both", "decode")
+    do_pre = args.phase in ("both", "prefill")
+
+    # ---- HIP graphs of the two passes (no memset nodes are recorded: the library issues kernels only)
+    graphs = {}
+    if not args.no_graph:
+        side = torch.cuda.Stream()
+        for key, fn, on in (("decode", decode_pass, do_dec), ("prefill", prefill_pass, do_pre)):
+            if not on:
+                continue
+            with torch.cuda.stream(side):
+                fn()                       # eager run first (also warms the code objects)
+            side.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                fn()
+            graphs[key] = g
+    run_dec = graphs["decode"].replay if "decode" in graphs else decode_pass
+    run_pre = graphs["prefill"].replay if "prefill" in graphs else prefill_pass
+
+    def step(evs=None):
+        if evs is not None:
+            evs[0].record()
+        if do_dec:
+            run_dec()
+        if evs is not None:
+            evs[1].record()
+        if do_pre:
+            run_pre()
+        if evs is not None:
+            evs[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_start) * 1e3
+    dec_ms = [e[0].elapsed_time(e[1]) for e in events]
+    pre_ms = [e[1].elapsed_time(e[2]) for e in events]
+    ms_per_step = wall_ms / args.steps
+
+    # ---- algorithmic work of one pass
+    dec_bytes = n_blocks * sum(decode_bytes(N, K) for _, N, K in layers)
+    if lm is not None:
+        dec_bytes += decode_bytes(lm[1], lm[2])
+    pre_ops = n_blocks * sum(prefill_ops(M_pre, N, K) for _, N, K in layers)
+    dec_mean = float(np.mean(dec_ms)) if do_dec else None
+    pre_mean = float(np.mean(pre_ms)) if do_pre else None
+    dec_gbs = dec_bytes / (dec_mean * 1e-3) / 1e9 if do_dec else None
+    pre_tops = pre_ops / (pre_mean * 1e-3) / 1e12 if do_pre else None
+
+    # ---- per-kernel timing with HIP events on the launch stream, one launch at a time,
+    #      cycling through the per-block buffers so that weights come from HBM
+    def time_launches(fn_list, reps):
+        tot = 0.0
+        n = 0
+        for _ in range(reps):
+            evs = []
+            for fn in fn_list:
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(); fn(); b.record()
+                evs.append((a, b))
+            torch.cuda.synchronize()
+            tot += sum(a.elapsed_time(b) for a, b in evs)
+            n += len(evs)
+        return tot / n  # mean ms per launch
+
+    roof_pre = roof_dec = None
+    per_layer = {}
+    if do_pre:
+        fns, ops = [], 0
+        for name, N, K in layers:
+            x, xq, sx, y = io_pre[name]
+            lay = [(lambda p=packed[name][b], N=N, K=K, xq=xq, sx=sx, y=y:
+                    B.mnnq_linear_prefill(p, N, K, xq, sx, out=y)) for b in range(n_blocks)]
+            t = time_launches(lay, 2)
+            per_layer["prefill_" + name] = {"us": round(t * 1e3, 2),
+                                            "tops": round(prefill_ops(M_pre, N, K) / (t * 1e-3) / 1e12, 1)}
+            fns += lay
+            ops += n_blocks * prefill_ops(M_pre, N, K)
+        t = time_launches(fns, 2)
+        ach = ops / len(fns) / (t * 1e-3) / 1e12
+        roof_pre = {"kernel": "prefill_kernel (W4A8 int8 MFMA GEMM), all %d launches of a pass" % len(fns),
+                    "bound": "mfma", "achieved": round(ach, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+                    "frac": round(ach / INT8_PEAK_TOPS, 4), "traffic": None,
+                    "avg_launch_us": round(t * 1e3, 2)}
+    if do_dec:
+        fns, byt = [], 0
+        for name, N, K in layers:
+            x, xq, sx, y = io_dec[name]
+            lay = [(lambda p=packed[name][b], N=N, K=K, xq=xq, sx=sx, y=y:
+                    B.mnnq_linear_decode(p, N, K, xq, sx, out=y)) for b in range(n_blocks)]
+            t = time_launches(lay, 2)
+            per_layer["decode_" + name] = {"us": round(t * 1e3, 2),
+                                           "gbs": round(decode_bytes(N, K) / (t * 1e-3) / 1e9, 1)}
+            fns += lay
+            byt += n_blocks * decode_bytes(N, K)
+        t = time_launches(fns, 2)
+        ach = byt / len(fns) / (t * 1e-3) / 1e9
+        roof_dec = {"kernel": "decode_kernel (W4A8 GEMV), all %d block launches of a pass" % len(fns),
+                    "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                    "avg_launch_us": round(t * 1e3, 2)}
+        if lm is not None:
+            x, xq, sx, y = io_dec["lm_head"]
+            t = time_launches([lambda: B.mnnq_linear_decode(lm[0], lm[1], lm[2], xq, sx, out=y)], 5)
+            per_layer["decode_lm_head"] = {"us": round(t * 1e3, 2),
+                                           "gbs": round(decode_bytes(lm[1], lm[2]) / (t * 1e-3) / 1e9, 1)}
+
+    # ---- CPU baseline: the oracle, as it stands, on the host cores, on a bounded sample
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        cores = len(os.sched_getaffinity(0))
+        oracle.set_threads(cores)
+        name, N, K = max(layers, key=lambda l: l[1] * l[2])          # the largest projection of a block
+        Nc = min(N, 4096)
+        Wc = synth.weights(Nc, K, 4242)
+        q, s, z = oracle.quant_weights(Wc)
+        xs = synth.activations(16, K, 4243)
+        xq_o, sx_o, _ = oracle.quant_act(xs)
+        oracle.linear_w4a8(xq_o[:1], sx_o[:1], q, s, z, want_acc=False)   # warm
+        t1 = time.perf_counter(); reps = 0
+        while time.perf_counter() - t1 < 4.0:
+            oracle.linear_w4a8(xq_o[:1], sx_o[:1], q, s, z, want_acc=False); reps += 1
+        cpu_dec_s = (time.perf_counter() - t1) / reps
+        t1 = time.perf_counter(); reps = 0
+        while time.perf_counter() - t1 < 8.0:
+            oracle.linear_w4a8(xq_o, sx_o, q, s, z, want_acc=False); reps += 1
+        cpu_pre_s = (time.perf_counter() - t1) / reps
+        cpu = {"value": round(decode_bytes(Nc, K) / cpu_dec_s / 1e9, 3), "unit": "GB/s", "cores": cores,
+               "kind": "oracle",
+               "prefill_value": round(prefill_ops(16, Nc, K) / cpu_pre_s / 1e12, 5), "prefill_unit": "TOP/s",
+               "sample": "oracle O4 (scalar C, OpenMP over rows) on %d rows of a [%d x %d] layer: "
+                         "decode M=1 for 4 s, prefill M=16 for 8 s" % (Nc, N, K)}
+
+    out = {
+        "metric": "decode GEMV HBM GB/s (% peak); prefill W4A8 GEMM int8 TOPS (% MFMA peak)",
+        "value": round(dec_gbs, 1) if do_dec else round(pre_tops, 1),
+        "unit": "GB/s" if do_dec else "TOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8 x int4 -> int32, fp32 epilogue",
+        "data": "synthetic: N(0,0.02) weights of one block drawn on the host (seeded) and packed into "
+                "%d distinct buffers, N(0,1) activations with 0.1%% outlier channels x20" % n_blocks,
+        "config": {"workload": "%s-shaped W4A8 linears: decode batch 1 (%d blocks%s) + prefill M=%d (%d blocks), "
+                               "q|k|v and gate|up concatenated along N" %
+                               (args.model, n_blocks, " + lm_head" if lm else "", M_pre, n_blocks),
+                   "group": 64, "graph": not args.no_graph, "phase": args.phase},
+        "decode_ms": round(dec_mean, 4) if do_dec else None,
+        "decode_gbs": round(dec_gbs, 1) if do_dec else None,
+        "decode_frac_of_hbm_peak": round(dec_gbs / HBM_PEAK_GBS, 4) if do_dec else None,
+        "prefill_ms": round(pre_mean, 4) if do_pre else None,
+        "prefill_value": round(pre_tops, 1) if do_pre else None, "prefill_unit": "TOP/s",
+        "prefill_frac_of_int8_peak": round(pre_tops / INT8_PEAK_TOPS, 4) if do_pre else None,
+        "roofline": roof_pre if roof_pre is not None else roof_dec,
+        "roofline_decode": roof_dec,
+        "per_layer": per_layer,
+        "cpu_baseline": cpu,
+        "pack_gbs_fp32_in": round(pack_bytes_in / (pack_ms * 1e-3) / 1e9, 1),
+        "setup_s": round(setup_s, 1),
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

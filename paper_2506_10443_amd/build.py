@@ -16,6 +16,8 @@ SOURCES = ["mnnq_api.hip", "mnnq_pack.hip", "mnnq_quant_act.hip", "mnnq_decode.h
            "mnnq_prefill.hip", "mnnq_f16.hip"]
 # The quantizers are fixed sequences of IEEE binary32 operations: no contraction.
 STRICT_FP = {"mnnq_pack.hip", "mnnq_quant_act.hip"}
+# MFMA results stay in architectural VGPRs so that the VALU epilogue reads them directly.
+MFMA_VGPR = {"mnnq_prefill.hip"}
 
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
           "-fhip-fp32-correctly-rounded-divide-sqrt",
@@ -34,6 +36,7 @@ def hipcc() -> str:
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
     cmd = [hipcc()] + COMMON + (["-ffp-contract=off"] if src in STRICT_FP else []) + \
+        (["-mllvm", "-amdgpu-mfma-vgpr-form"] if src in MFMA_VGPR else []) + \
         ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

@@ -31,6 +31,14 @@ int check_shape(int64_t N, int64_t K, int group, int mode)
     return MNNQ_OK;
 }
 
+// The prefill kernel addresses the activations and the packed weights with
+// 32-bit buffer offsets.
+bool prefill_fits(int64_t M, int64_t N, int64_t K)
+{
+    const int64_t lim = ((int64_t)1 << 31) - 1;
+    return M <= ((int64_t)1 << 24) && (M + 256) * K <= lim && (int64_t)make_layout(N, K).total() <= lim;
+}
+
 }  // namespace
 }  // namespace mnnq
 
@@ -127,7 +135,7 @@ int mnnq_linear_prefill(const void* packed, int64_t M, int64_t N, int64_t K, int
     if (!packed || !xq || !sx || !y) return MNNQ_ERR_NULL;
     if (M <= 0) return MNNQ_ERR_SHAPE;
     if (int s = check_shape(N, K, group, mode)) return s;
-    if (M > ((int64_t)1 << 24)) return MNNQ_ERR_UNSUPPORTED;
+    if (!prefill_fits(M, N, K)) return MNNQ_ERR_UNSUPPORTED;
     if (misaligned(packed) || misaligned(xq) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(sx) & 3u) return MNNQ_ERR_ALIGN;
     return launch_prefill(static_cast<const uint8_t*>(packed), make_layout(N, K), M, xq, sx, bias, y, nullptr,
@@ -168,6 +176,7 @@ int mnnq_linear_acc_debug(const void* packed, int64_t M, int64_t N, int64_t K, i
     if (int s = check_shape(N, K, group, mode)) return s;
     if (M > kMaxM) return MNNQ_ERR_UNSUPPORTED;
     if (!use_prefill_kernel && K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
+    if (use_prefill_kernel && !prefill_fits(M, N, K)) return MNNQ_ERR_UNSUPPORTED;
     if (misaligned(packed) || misaligned(xq) || misaligned(acc)) return MNNQ_ERR_ALIGN;
     const Layout L = make_layout(N, K);
     hipStream_t st = static_cast<hipStream_t>(stream);

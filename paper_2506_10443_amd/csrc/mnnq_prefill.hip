@@ -6,12 +6,22 @@
 //
 //   y[m,n] = sx[m] * sum_g scale[n,g] * I[m,n,g] (+ bias[n])
 //
-// Data movement per workgroup and chunk (128 values of K):
-//   A (activations, int8): global -> registers -> LDS (double buffered, rows
-//     padded to 144 B so that the 128-bit fragment reads are conflict free).
-//   B (weights, int4): one 128-bit global load per lane and row tile straight
-//     into registers - the chunk layout already is the MFMA B-operand order -
-//     then nibbles -> int8 and the zero point is subtracted per byte.
+// The epilogue needs two VALU operations (convert, fused multiply-add) per
+// output and group - 8 per MFMA and lane, 32 cycles of the vector pipe against
+// 16 cycles of the matrix pipe - so the kernel is bound by the vector ALU, not
+// by the MFMA rate.  Everything else is arranged to add as little VALU work as
+// possible and to let it overlap the MFMAs:
+//   * all operands reach LDS with direct buffer loads (buffer_load ... lds): no
+//     staging registers, no address arithmetic in the vector pipe (the buffer
+//     resource and the per-chunk offsets are scalar), out-of-range rows read 0;
+//   * a wave owns TM x TN tiles of 16 x 16 (TM = 8 where M allows), so the
+//     nibble -> int8 unpack of a B fragment is shared by TM MFMAs;
+//   * the chunk layout of the weights already is the MFMA B-operand order, so a
+//     weight chunk is copied to LDS verbatim and read back with one conflict
+//     free 128-bit read per lane;
+//   * A rows are 128 B in LDS with their 16-byte units XOR-swizzled by the row,
+//     which makes the 128-bit fragment reads conflict free without padding;
+//   * the epilogue of one tile is issued behind the MFMA of the next.
 //
 // Lane mapping of the 16x16x64 int8 MFMA (A: 16 x 64, B: 64 x 16, D: 16 x 16):
 //   A operand: lane l holds row l % 16, 16 consecutive k of block l / 16;
@@ -19,49 +29,66 @@
 //   D:         lane l holds column l % 16, rows 4 (l / 16) + r, r = 0..3.
 #include "mnnq_common.h"
 
+#include <stdlib.h>
+
 namespace mnnq {
 
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
 
-constexpr int kAStride = 144;  // bytes per LDS row of A: 128 + 16 padding
+#define MNNQ_LDS(p) ((__attribute__((address_space(3))) void*)(p))
 
-// q - z per byte for four codes (0..15) in the bytes of v; z4 = z * 0x01010101.
-// Setting bit 7 of every byte first keeps the borrow inside its byte.
-__device__ __forceinline__ int sub_zero(uint32_t v, uint32_t z4)
+constexpr int kBufFlags = 0x00020000;  // raw buffer, 32-bit data format (gfx9 family)
+
+// q - z per byte for four codes (0..15) in the bytes of v.  c4 holds 0x80 - z in
+// every byte: adding it keeps each byte in [0x71, 0x8f], so no carry or borrow
+// crosses a byte, and flipping bit 7 afterwards leaves q - z as a signed byte.
+__device__ __forceinline__ int sub_zero(uint32_t v, uint32_t c4)
 {
-    return (int)(((v | 0x80808080u) - z4) ^ 0x80808080u);
+    return (int)((v + c4) ^ 0x80808080u);
 }
 
-__device__ __forceinline__ v4i unpack_b(uint32_t w0, uint32_t w1, uint32_t z4)
+__device__ __forceinline__ v4i unpack_b(uint32_t w0, uint32_t w1, uint32_t c4)
 {
     v4i b;
-    b.x = sub_zero(w0 & 0x0f0f0f0fu, z4);
-    b.y = sub_zero((w0 >> 4) & 0x0f0f0f0fu, z4);
-    b.z = sub_zero(w1 & 0x0f0f0f0fu, z4);
-    b.w = sub_zero((w1 >> 4) & 0x0f0f0f0fu, z4);
+    b.x = sub_zero(w0 & 0x0f0f0f0fu, c4);
+    b.y = sub_zero((w0 >> 4) & 0x0f0f0f0fu, c4);
+    b.z = sub_zero(w1 & 0x0f0f0f0fu, c4);
+    b.w = sub_zero((w1 >> 4) & 0x0f0f0f0fu, c4);
     return b;
 }
 
-template <int BM, int BN, int WGM, int WGN, bool ACC>
-__global__ __launch_bounds__(WGM * WGN * 64) void prefill_kernel(const uint8_t* __restrict__ packed, Layout L,
-                                                                 int64_t M, const int8_t* __restrict__ xq,
-                                                                 const float* __restrict__ sx,
-                                                                 const float* __restrict__ bias,
-                                                                 float* __restrict__ y,
-                                                                 int32_t* __restrict__ acc_out,
-                                                                 int MT, int NT)
-{
-    constexpr int THREADS = WGM * WGN * 64;
-    constexpr int WM = BM / WGM, WN = BN / WGN;
-    constexpr int TM = WM / 16, TN = WN / 16;
-    constexpr int A_UNITS = BM * 8;                 // 16-byte units of one A stage
-    constexpr int A_PER_THREAD = A_UNITS / THREADS;
-    static_assert(A_UNITS % THREADS == 0, "A tile must split evenly");
+// LDS map of a workgroup: the A tile is double buffered, the B tile (codes, scales,
+// zeros of one chunk) is single buffered - it is copied into registers before
+// the next chunk is loaded over it.
+template <int BM, int BN>
+struct Lds {
+    static constexpr int NT16 = BN / 16;                 // row tiles of B per workgroup
+    static constexpr int A_BYTES = BM * 128;             // [BM][128] int8, swizzled
+    static constexpr int A_OFF = 0;                      // two A buffers
+    static constexpr int B_OFF = 2 * A_BYTES;            // [NT16][1024] packed codes
+    static constexpr int S_OFF = B_OFF + NT16 * 1024;    // [NT16][16][2] fp32 scales
+    static constexpr int Z_OFF = S_OFF + NT16 * 128;     // [NT16][16][2] u8 zeros
+    static constexpr int BYTES = Z_OFF + NT16 * 32;
+};
 
-    __shared__ __align__(16) uint8_t lds_a[2][BM * kAStride];
+template <int BM, int BN, bool ACC>
+__global__ __launch_bounds__(256, ACC ? 1 : 2) void prefill_kernel(const uint8_t* __restrict__ packed, Layout L, int64_t M,
+                                                         const int8_t* __restrict__ xq,
+                                                         const float* __restrict__ sx,
+                                                         const float* __restrict__ bias, float* __restrict__ y,
+                                                         int32_t* __restrict__ acc_out, int MT, int NT)
+{
+    using St = Lds<BM, BN>;
+    constexpr int WM = BM / 2, WN = BN / 2;      // 2 x 2 waves
+    constexpr int TM = WM / 16, TN = WN / 16;
+    constexpr int NT16 = St::NT16;
+    constexpr int A_INSTR = BM / 8 / 4;          // 1 KiB direct loads of A per wave and stage
+    static_assert(NT16 == 8, "B side is written for 8 row tiles per workgroup");
+
+    extern __shared__ __align__(16) uint8_t lds[];   // St::BYTES
 
     // Workgroups are dealt to the 8 XCDs round-robin by their linear id.  Give
     // each XCD whole columns of output tiles (one weight row block, all token
@@ -74,61 +101,51 @@ __global__ __launch_bounds__(WGM * WGN * 64) void prefill_kernel(const uint8_t* 
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int wm = wave / WGN, wn = wave % WGN;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
     const int col = lane & 15;
     const int kb = lane >> 4;
     const int64_t m0 = (int64_t)tile_m * BM;
-    const int64_t C = L.C;
+    const int C = (int)L.C;
+    const int K = (int)L.K;
 
-    // B side: TN row tiles of 16 weight rows each.
-    const int64_t rt0 = ((int64_t)tile_n * BN + wn * WN) / 16;
-    bool b_ok[TN];
-    const u32x4* wp[TN];
-    const float2* sp[TN];
-    const uint16_t* zp[TN];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int64_t rt = rt0 + j;
-        b_ok[j] = rt < L.T;
-        const int64_t rtc = b_ok[j] ? rt : 0;
-        wp[j] = reinterpret_cast<const u32x4*>(packed) + rtc * C * 64 + lane;
-        sp[j] = reinterpret_cast<const float2*>(packed + L.scales_off()) + rtc * C * 16 + col;
-        zp[j] = reinterpret_cast<const uint16_t*>(packed + L.zeros_off()) + rtc * C * 16 + col;
-    }
+    // Buffer resources: out-of-range reads (rows past M, row tiles past N) return zero.
+    const __amdgpu_buffer_rsrc_t rs_x =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(xq), 0, (int)(M * L.K), kBufFlags);
+    const __amdgpu_buffer_rsrc_t rs_w =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(packed), 0, (int)L.total(), kBufFlags);
 
-    u32x4 bw[TN], bw_n[TN];
-    float2 bs[TN], bs_n[TN];
-    uint32_t bz[TN], bz_n[TN];
-    uint4 areg[A_PER_THREAD];
+    const int rt0 = tile_n * NT16;               // first row tile of this workgroup
+    // Per-lane offsets of the direct loads (constant over the K loop).
+    const int a_voff = (lane >> 3) * K + (((lane & 7) ^ (lane >> 3)) << 4);
+    const int b_voff = lane * 16;
+    const int s_voff = (lane >> 5) * C * 128 + (lane & 31) * 4;
+    const int z_voff = (lane >> 3) * C * 32 + (lane & 7) * 4;
+    const int scales_off = (int)L.scales_off();
+    const int zeros_off = (int)L.zeros_off();
 
-    auto load_a = [&](int64_t c) {
+    auto issue_stage = [&](int c, int buf) {
+        // A: this wave's A_INSTR blocks of 8 rows x 128 B.
 #pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i) {
-            const int u = tid + i * THREADS;
-            const int r = u / 8, cu = u % 8;
-            const int64_t m = m0 + r;
-            const int64_t k = c * 128 + cu * 16;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (m < M && k < L.K) v = *reinterpret_cast<const uint4*>(xq + m * L.K + k);
-            areg[i] = v;
+        for (int i = 0; i < A_INSTR; ++i) {
+            const int q = wave * A_INSTR + i;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rs_x, MNNQ_LDS(lds + St::A_OFF + buf * St::A_BYTES + q * 1024), 16, a_voff,
+                ((int)m0 + q * 8) * K + c * 128, 0, 0);
         }
-    };
-    auto store_a = [&](int buf) {
+        // B codes: two row tiles per wave, one chunk block (1 KiB) each.
 #pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i) {
-            const int u = tid + i * THREADS;
-            const int r = u / 8, cu = u % 8;
-            *reinterpret_cast<uint4*>(&lds_a[buf][r * kAStride + cu * 16]) = areg[i];
+        for (int i = 0; i < 2; ++i) {
+            const int j = wave * 2 + i;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::B_OFF + j * 1024), 16, b_voff,
+                                                     ((rt0 + j) * C + c) * 1024, 0, 0);
         }
-    };
-    auto load_b = [&](int64_t c, u32x4* w, float2* s, uint32_t* z) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            w[j] = wp[j][c * 64];
-            s[j] = sp[j][c * 16];
-            z[j] = zp[j][c * 16];
-        }
+        // Scales: one load covers two row tiles (2 x 128 B); zeros: one load covers all eight (8 x 32 B).
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::S_OFF + wave * 256), 4, s_voff,
+                                                 scales_off + ((rt0 + wave * 2) * C + c) * 128, 0, 0);
+        if (wave == 0)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::Z_OFF), 4, z_voff,
+                                                     zeros_off + (rt0 * C + c) * 32, 0, 0);
     };
 
     float yacc[TM][TN][4];
@@ -139,63 +156,116 @@ __global__ __launch_bounds__(WGM * WGN * 64) void prefill_kernel(const uint8_t* 
 #pragma unroll
             for (int r = 0; r < 4; ++r) yacc[i][j][r] = 0.0f;
 
-    load_a(0);
-    load_b(0, bw, bs, bz);
-    store_a(0);
+    // Fragment read offsets.
+    const int a_row_off = St::A_OFF + (wm * WM + col) * 128;   // + i * 2048 per m-tile
+    const int a_sw = col & 7;                                   // swizzle key: row & 7 == col & 7
+    const int b_frag_off = St::B_OFF + wn * TN * 1024 + lane * 16;
+    const int s_frag_off = St::S_OFF + wn * TN * 128 + col * 8;
+    const int z_frag_off = St::Z_OFF + wn * TN * 32 + col * 2;
 
-    for (int64_t c = 0; c < C; ++c) {
-        const int buf = (int)(c & 1);
-        __syncthreads();
-        const bool more = c + 1 < C;
-        if (more) {
-            load_a(c + 1);
-            load_b(c + 1, bw_n, bs_n, bz_n);
+    v4i bw[TN];
+    v2i bsv[TN];
+    uint32_t bz[TN];
+    auto read_b = [&]() {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            bw[j] = *reinterpret_cast<const v4i*>(lds + b_frag_off + j * 1024);
+            bsv[j] = *reinterpret_cast<const v2i*>(lds + s_frag_off + j * 128);
+            bz[j] = *reinterpret_cast<const uint16_t*>(lds + z_frag_off + j * 32);
         }
+    };
+
+    issue_stage(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __syncthreads();
+    read_b();
+
+    for (int c = 0; c < C; ++c) {
+        const int buf = c & 1;
+        // Every wave holds the B fragments of chunk c in registers and has finished
+        // chunk c - 1: the B tile and the other A buffer may be overwritten.
+        __syncthreads();
+        if (c + 1 < C) issue_stage(c + 1, buf ^ 1);
+
+        const uint8_t* st = lds + buf * St::A_BYTES;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             v4i b[TN];
             float sc[TN];
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const uint32_t zz = h ? (bz[j] >> 8) : (bz[j] & 0xffu);
-                const uint32_t z4 = zz * 0x01010101u;
-                b[j] = h ? unpack_b(bw[j].z, bw[j].w, z4) : unpack_b(bw[j].x, bw[j].y, z4);
-                sc[j] = h ? bs[j].y : bs[j].x;
+                // 0x80 - zero point of this group in each of the four bytes
+                const uint32_t c4 = 0x80808080u - __builtin_amdgcn_perm(bz[j], bz[j], h ? 0x01010101u : 0u);
+                b[j] = h ? unpack_b((uint32_t)bw[j].z, (uint32_t)bw[j].w, c4)
+                         : unpack_b((uint32_t)bw[j].x, (uint32_t)bw[j].y, c4);
+                sc[j] = __int_as_float(h ? bsv[j].y : bsv[j].x);
             }
-            const int64_t g = 2 * c + h;
+            const int g = 2 * c + h;
+            const uint8_t* ap = st + a_row_off + (((h * 4 + kb) ^ a_sw) << 4);
+            const v4i zero = {0, 0, 0, 0};
+            if (ACC) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int r = wm * WM + i * 16 + col;
-                const v4i a = *reinterpret_cast<const v4i*>(&lds_a[buf][r * kAStride + h * 64 + kb * 16]);
+                for (int i = 0; i < TM; ++i) {
+                    const v4i a = *reinterpret_cast<const v4i*>(ap + i * 2048);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const v4i zero = {0, 0, 0, 0};
-                    const v4i d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[j], zero, 0, 0, 0);
-                    if (ACC) {
-                        if (b_ok[j] && g < L.G) {
-                            const int64_t n = (rt0 + j) * 16 + col;
+                    for (int j = 0; j < TN; ++j) {
+                        const v4i d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[j], zero, 0, 0, 0);
+                        const int64_t n = (int64_t)(rt0 + wn * TN + j) * 16 + col;
+                        if (n < L.N && g < L.G) {
 #pragma unroll
                             for (int rr = 0; rr < 4; ++rr) {
                                 const int64_t m = m0 + wm * WM + i * 16 + kb * 4 + rr;
                                 if (m < M) acc_out[(m * L.N + n) * L.G + g] = d[rr];
                             }
                         }
-                    } else {
-#pragma unroll
-                        for (int rr = 0; rr < 4; ++rr)
-                            yacc[i][j][rr] = fmaf(sc[j], (float)d[rr], yacc[i][j][rr]);
                     }
+                }
+            } else {
+                // Software pipeline over the TM x TN tiles of this group: the MFMA of
+                // tile t + 1 is issued before the eight VALU operations that fold tile
+                // t into the running sums.  The empty asm statements emit nothing; they
+                // only tie values together so that this order survives the compiler's
+                // schedulers: MFMA(t+1) < epilogue(t) < MFMA(t+2).
+                v4i a = *reinterpret_cast<const v4i*>(ap);
+                v4i a_nxt = a;
+                if (TM > 1) a_nxt = *reinterpret_cast<const v4i*>(ap + 2048);
+                v4i d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[0], zero, 0, 0, 0);
+#pragma unroll
+                for (int t = 0; t < TM * TN; ++t) {
+                    const int i = t / TN, j = t % TN;
+                    v4i d_nxt = d;
+                    if (t + 1 < TM * TN) {
+                        const int i1 = (t + 1) / TN, j1 = (t + 1) % TN;
+                        if (j1 == 0) {
+                            a = a_nxt;
+                            if (i1 + 1 < TM) a_nxt = *reinterpret_cast<const v4i*>(ap + (i1 + 1) * 2048);
+                        }
+                        d_nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[j1], zero, 0, 0, 0);
+                        asm volatile("" : "+v"(d), "+v"(d_nxt));
+                    }
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr)
+                        yacc[i][j][rr] = fmaf(sc[j], (float)d[rr], yacc[i][j][rr]);
+                    if (t + 2 < TM * TN) {
+                        const int j2 = (t + 2) % TN;
+                        asm volatile(""
+                                     : "+v"(b[j2]), "+v"(yacc[i][j][0]), "+v"(yacc[i][j][1]), "+v"(yacc[i][j][2]),
+                                       "+v"(yacc[i][j][3]));
+                    } else {
+                        asm volatile(""
+                                     : "+v"(yacc[i][j][0]), "+v"(yacc[i][j][1]), "+v"(yacc[i][j][2]),
+                                       "+v"(yacc[i][j][3]));
+                    }
+                    d = d_nxt;
                 }
             }
         }
-        if (more) {
-            store_a(buf ^ 1);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                bw[j] = bw_n[j];
-                bs[j] = bs_n[j];
-                bz[j] = bz_n[j];
-            }
+        if (c + 1 < C) {
+            // The loads of chunk c + 1 were issued before this chunk's arithmetic; wait for
+            // this wave's part, make every wave's part visible, fetch the B fragments.
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+            __syncthreads();
+            read_b();
         }
     }
     if (ACC) return;
@@ -209,8 +279,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void prefill_kernel(const uint8_t* 
             const float sxm = sx[m];
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                if (!b_ok[j]) continue;
-                const int64_t n = (rt0 + j) * 16 + col;
+                const int64_t n = (int64_t)(rt0 + wn * TN + j) * 16 + col;
+                if (n >= L.N) continue;
                 float v = yacc[i][j][rr] * sxm;
                 if (bias) v += bias[n];
                 y[m * L.N + n] = v;
@@ -219,17 +289,48 @@ __global__ __launch_bounds__(WGM * WGN * 64) void prefill_kernel(const uint8_t* 
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool ACC>
+template <int BM, int BN, bool ACC>
 int launch_tiles(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
                  const float* bias, float* y, int32_t* acc, hipStream_t st)
 {
     const int MT = (int)((M + BM - 1) / BM);
     const int NT = (int)((L.N + BN - 1) / BN);
     const int64_t blocks = (int64_t)MT * ((NT + 7) / 8) * 8;
-    hipLaunchKernelGGL((prefill_kernel<BM, BN, WGM, WGN, ACC>), dim3((unsigned)blocks), dim3(WGM * WGN * 64),
-                       0, st, packed, L, M, xq, sx, bias, y, acc, MT, NT);
+    constexpr size_t smem = (size_t)Lds<BM, BN>::BYTES;
+    auto kern = prefill_kernel<BM, BN, ACC>;
+    if (smem > 64 * 1024) {
+        // More than 64 KiB of dynamic LDS has to be allowed once per kernel and device.
+        static thread_local int allowed_dev = -1;
+        int dev = 0;
+        MNNQ_HIP_TRY(hipGetDevice(&dev));
+        if (allowed_dev != dev) {
+            MNNQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+            allowed_dev = dev;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), smem, st, packed, L, M, xq, sx, bias, y, acc, MT,
+                       NT);
     MNNQ_HIP_TRY(hipGetLastError());
     return MNNQ_OK;
+}
+
+// Output tiles are dealt to 256 CUs; the cost of a shape is the number of
+// rounds of workgroups times the size of the tile.  Larger tiles amortise the
+// B unpack better (weight 0.85), smaller ones fill the last round.
+bool use_big_tile(const Layout& L, int64_t M)
+{
+    if (const char* e = getenv("MNNQ_PREFILL_TILE")) {
+        if (e[0] == 'b') return true;
+        if (e[0] == 's') return false;
+    }
+    auto rounds = [&](int bm, int bn) {
+        const int64_t tiles = ((M + bm - 1) / bm) * ((L.N + bn - 1) / bn);
+        return (double)((tiles + 255) / 256);
+    };
+    const double big = rounds(256, 128) * 256 * 128 * 0.85;
+    const double small = rounds(128, 128) * 128 * 128;
+    return big <= small;
 }
 
 }  // namespace
@@ -237,9 +338,13 @@ int launch_tiles(const uint8_t* packed, const Layout& L, int64_t M, const int8_t
 int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
                    const float* bias, float* y, int32_t* acc_debug, hipStream_t st)
 {
-    if (acc_debug)
-        return launch_tiles<128, 128, 2, 2, true>(packed, L, M, xq, sx, bias, y, acc_debug, st);
-    return launch_tiles<128, 128, 2, 2, false>(packed, L, M, xq, sx, bias, y, nullptr, st);
+    const bool big = use_big_tile(L, M);
+    if (acc_debug) {
+        if (big) return launch_tiles<256, 128, true>(packed, L, M, xq, sx, bias, y, acc_debug, st);
+        return launch_tiles<128, 128, true>(packed, L, M, xq, sx, bias, y, acc_debug, st);
+    }
+    if (big) return launch_tiles<256, 128, false>(packed, L, M, xq, sx, bias, y, nullptr, st);
+    return launch_tiles<128, 128, false>(packed, L, M, xq, sx, bias, y, nullptr, st);
 }
 
 }  // namespace mnnq
