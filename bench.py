@@ -28,6 +28,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published (5.0 POP/s)
 G = 64
+# HBM traffic per launch (bytes, mean over a pass) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this file, scaled by a copy kernel of known size; see profiles/ for the runs.  None = not measured
+# for the current kernels.
+PREFILL_TRAFFIC_BYTES = 170.3e6   # profiles/bench_qwen2-7b_hbm_traffic.txt
+DECODE_TRAFFIC_BYTES = 33.8e6     # same file
 
 
 def decode_bytes(N, K):
@@ -49,6 +54,11 @@ def main() -> int:
     ap.add_argument("--phase", default="both", choices=["both", "decode", "prefill"])
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 512 MiB device copy, as the known-size reference for rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--fused-decode", action="store_true",
+                    help="decode pass calls mnnq_linear_decode_fused (quantizer inside the GEMV kernel)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; the path shards by output rows (see DESIGN.md) "
@@ -118,16 +128,20 @@ def main() -> int:
                              torch.empty((1,), dtype=torch.float32, device=dev),
                              torch.empty((1, lm[1]), dtype=torch.float32, device=dev))
 
+    def decode_layer(p, N, K, io):
+        x, xq, sx, y = io
+        if args.fused_decode:
+            B.mnnq_linear_decode_fused(p, N, K, x, out=y)
+        else:
+            B.mnnq_quant_act(x, want_xsum=False, out=(xq, sx, None))
+            B.mnnq_linear_decode(p, N, K, xq, sx, out=y)
+
     def decode_pass():
         for b in range(n_blocks):
             for name, N, K in layers:
-                x, xq, sx, y = io_dec[name]
-                B.mnnq_quant_act(x, want_xsum=False, out=(xq, sx, None))
-                B.mnnq_linear_decode(packed[name][b], N, K, xq, sx, out=y)
+                decode_layer(packed[name][b], N, K, io_dec[name])
         if lm is not None:
-            x, xq, sx, y = io_dec["lm_head"]
-            B.mnnq_quant_act(x, want_xsum=False, out=(xq, sx, None))
-            B.mnnq_linear_decode(lm[0], lm[1], lm[2], xq, sx, out=y)
+            decode_layer(lm[0], lm[1], lm[2], io_dec["lm_head"])
 
     def prefill_pass():
         for b in range(n_blocks):
@@ -191,21 +205,29 @@ def main() -> int:
     dec_gbs = dec_bytes / (dec_mean * 1e-3) / 1e9 if do_dec else None
     pre_tops = pre_ops / (pre_mean * 1e-3) / 1e12 if do_pre else None
 
-    # ---- per-kernel timing with HIP events on the launch stream, one launch at a time,
-    #      cycling through the per-block buffers so that weights come from HBM
+    # ---- per-kernel timing: HIP events on the launch stream around a back-to-back run of
+    #      launches of ONE kernel, cycling through the per-block buffers so that weights
+    #      come from HBM.  The small gaps between launches are included (conservative).
     def time_launches(fn_list, reps):
-        tot = 0.0
-        n = 0
-        for _ in range(reps):
-            evs = []
+        # replayed as a HIP graph so that the host's launch rate does not limit short kernels
+        side2 = torch.cuda.Stream()
+        with torch.cuda.stream(side2):
+            for fn in fn_list[:4]:
+                fn()
+        side2.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side2):
             for fn in fn_list:
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record(); fn(); b.record()
-                evs.append((a, b))
-            torch.cuda.synchronize()
-            tot += sum(a.elapsed_time(b) for a, b in evs)
-            n += len(evs)
-        return tot / n  # mean ms per launch
+                fn()
+        g.replay()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            g.replay()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / (reps * len(fn_list))  # mean ms per launch
 
     roof_pre = roof_dec = None
     per_layer = {}
@@ -224,30 +246,38 @@ def main() -> int:
         ach = ops / len(fns) / (t * 1e-3) / 1e12
         roof_pre = {"kernel": "prefill_kernel (W4A8 int8 MFMA GEMM), all %d launches of a pass" % len(fns),
                     "bound": "mfma", "achieved": round(ach, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                    "frac": round(ach / INT8_PEAK_TOPS, 4), "traffic": None,
-                    "avg_launch_us": round(t * 1e3, 2)}
+                    "frac": round(ach / INT8_PEAK_TOPS, 4), "traffic": PREFILL_TRAFFIC_BYTES,
+                    "algorithmic_ops_per_launch": ops // len(fns), "avg_launch_us": round(t * 1e3, 2)}
     if do_dec:
         fns, byt = [], 0
         for name, N, K in layers:
             x, xq, sx, y = io_dec[name]
             lay = [(lambda p=packed[name][b], N=N, K=K, xq=xq, sx=sx, y=y:
                     B.mnnq_linear_decode(p, N, K, xq, sx, out=y)) for b in range(n_blocks)]
-            t = time_launches(lay, 2)
+            t = time_launches(lay, 4)
             per_layer["decode_" + name] = {"us": round(t * 1e3, 2),
                                            "gbs": round(decode_bytes(N, K) / (t * 1e-3) / 1e9, 1)}
             fns += lay
             byt += n_blocks * decode_bytes(N, K)
-        t = time_launches(fns, 2)
+        t = time_launches(fns, 4)
         ach = byt / len(fns) / (t * 1e-3) / 1e9
         roof_dec = {"kernel": "decode_kernel (W4A8 GEMV), all %d block launches of a pass" % len(fns),
                     "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
-                    "avg_launch_us": round(t * 1e3, 2)}
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": DECODE_TRAFFIC_BYTES,
+                    "algorithmic_bytes_per_launch": byt // len(fns), "avg_launch_us": round(t * 1e3, 2)}
         if lm is not None:
             x, xq, sx, y = io_dec["lm_head"]
-            t = time_launches([lambda: B.mnnq_linear_decode(lm[0], lm[1], lm[2], xq, sx, out=y)], 5)
+            t = time_launches([lambda: B.mnnq_linear_decode(lm[0], lm[1], lm[2], xq, sx, out=y)] * 4, 4)
             per_layer["decode_lm_head"] = {"us": round(t * 1e3, 2),
                                            "gbs": round(decode_bytes(lm[1], lm[2]) / (t * 1e-3) / 1e9, 1)}
+
+    if args.calibrate_copy:
+        src = torch.empty(128 * 1024 * 1024, dtype=torch.int32, device=dev).fill_(7)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- CPU baseline: the oracle, as it stands, on the host cores, on a bounded sample
     cpu = None
@@ -289,7 +319,8 @@ def main() -> int:
         "config": {"workload": "%s-shaped W4A8 linears: decode batch 1 (%d blocks%s) + prefill M=%d (%d blocks), "
                                "q|k|v and gate|up concatenated along N" %
                                (args.model, n_blocks, " + lm_head" if lm else "", M_pre, n_blocks),
-                   "group": 64, "graph": not args.no_graph, "phase": args.phase},
+                   "group": 64, "graph": not args.no_graph, "phase": args.phase,
+                   "fused_decode_quant": bool(args.fused_decode)},
         "decode_ms": round(dec_mean, 4) if do_dec else None,
         "decode_gbs": round(dec_gbs, 1) if do_dec else None,
         "decode_frac_of_hbm_peak": round(dec_gbs / HBM_PEAK_GBS, 4) if do_dec else None,

@@ -94,6 +94,15 @@ int mnnq_linear_decode(const void *packed, int64_t N, int64_t K, int group, int 
                        const int8_t *xq, const float *sx, const float *bias, float *y,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* Decode step with the activation quantizer fused in: takes the fp32 activation
+ * row x [K] and quantizes it inside the kernel exactly as mnnq_quant_act does
+ * (Section 4.2: activations are quantized to int8 during calculation), then
+ * computes the same y as mnnq_linear_decode.  Saves one launch and the round
+ * trip of xq through memory on the latency-critical decode path. */
+int mnnq_linear_decode_fused(const void *packed, int64_t N, int64_t K, int group, int mode,
+                             const float *x, const float *bias, float *y,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
 /* Prefill, M tokens (Section 2.1: compute-bound phase): the same formula for
  * every row m with its own sx[m].  xq: int8 [M, K]; sx: fp32 [M];
  * y: fp32 [M, N] row-major. */

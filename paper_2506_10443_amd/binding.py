@@ -21,6 +21,7 @@ LIB_PATH = os.path.join(_HERE, "lib", "libmnnq.so")
 EXPORTS = (
     "mnnq_status_string", "mnnq_last_hip_error", "mnnq_version", "mnnq_packed_size", "mnnq_workspace_size",
     "mnnq_pack_weights", "mnnq_unpack_weights", "mnnq_quant_act", "mnnq_linear_decode",
+    "mnnq_linear_decode_fused",
     "mnnq_linear_prefill", "mnnq_linear_decode_f16", "mnnq_linear_prefill_f16", "mnnq_linear_acc_debug",
 )
 
@@ -56,6 +57,7 @@ def lib() -> ctypes.CDLL:
         L.mnnq_unpack_weights.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
         L.mnnq_quant_act.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp]
         L.mnnq_linear_decode.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.mnnq_linear_decode_fused.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
         L.mnnq_linear_prefill.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.mnnq_linear_decode_f16.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
         L.mnnq_linear_prefill_f16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
@@ -143,6 +145,17 @@ def mnnq_linear_decode(packed, N: int, K: int, xq, sx, bias=None, out=None):
     y = torch.empty((N,), dtype=torch.float32, device=packed.device) if out is None else out
     _check(lib().mnnq_linear_decode(_ptr(packed), N, K, GROUP, MODE_W4_ZP_INT, _ptr(xq), _ptr(sx), _ptr(bias),
                                     _ptr(y), None, 0, _stream()), "mnnq_linear_decode")
+    return y
+
+
+def mnnq_linear_decode_fused(packed, N: int, K: int, x, bias=None, out=None):
+    """One token, activation quantizer fused in: x f32 [K] (or [1,K]) -> y f32 [N]."""
+    _dev(packed, torch.uint8, "packed"); _dev(x, torch.float32, "x")
+    if x.numel() != K:
+        raise ValueError("x must hold K values")
+    y = torch.empty((N,), dtype=torch.float32, device=packed.device) if out is None else out
+    _check(lib().mnnq_linear_decode_fused(_ptr(packed), N, K, GROUP, MODE_W4_ZP_INT, _ptr(x), _ptr(bias),
+                                          _ptr(y), None, 0, _stream()), "mnnq_linear_decode_fused")
     return y
 
 

@@ -15,7 +15,7 @@ LIB = os.path.join(LIB_DIR, "libmnnq.so")
 SOURCES = ["mnnq_api.hip", "mnnq_pack.hip", "mnnq_quant_act.hip", "mnnq_decode.hip",
            "mnnq_prefill.hip", "mnnq_f16.hip"]
 # The quantizers are fixed sequences of IEEE binary32 operations: no contraction.
-STRICT_FP = {"mnnq_pack.hip", "mnnq_quant_act.hip"}
+STRICT_FP = {"mnnq_pack.hip", "mnnq_quant_act.hip", "mnnq_decode.hip"}
 # MFMA results stay in architectural VGPRs so that the VALU epilogue reads them directly.
 MFMA_VGPR = {"mnnq_prefill.hip"}
 

@@ -127,6 +127,18 @@ int mnnq_linear_decode(const void* packed, int64_t N, int64_t K, int group, int 
                          static_cast<hipStream_t>(stream));
 }
 
+int mnnq_linear_decode_fused(const void* packed, int64_t N, int64_t K, int group, int mode, const float* x,
+                             const float* bias, float* y, void* workspace, size_t workspace_bytes, void* stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    if (!packed || !x || !y) return MNNQ_ERR_NULL;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    if (K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
+    if (misaligned(packed) || misaligned(x) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
+    return launch_decode_fused(static_cast<const uint8_t*>(packed), make_layout(N, K), x, bias, y,
+                               static_cast<hipStream_t>(stream));
+}
+
 int mnnq_linear_prefill(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
                         const int8_t* xq, const float* sx, const float* bias, float* y, void* workspace,
                         size_t workspace_bytes, void* stream)

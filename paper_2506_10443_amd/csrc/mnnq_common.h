@@ -78,6 +78,8 @@ int launch_quant_act(const float* x, int64_t M, int64_t K, int8_t* xq, float* sx
                      hipStream_t st);
 int launch_decode(const uint8_t* packed, const Layout& L, const int8_t* xq, const float* sx,
                   const float* bias, float* y, hipStream_t st);
+int launch_decode_fused(const uint8_t* packed, const Layout& L, const float* x, const float* bias, float* y,
+                        hipStream_t st);
 int launch_decode_acc(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq,
                       int32_t* acc, hipStream_t st);
 int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq,

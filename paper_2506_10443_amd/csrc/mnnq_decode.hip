@@ -9,8 +9,21 @@
 // Work split: a wave owns one row tile (16 rows) and a contiguous range of
 // chunks; KSPLIT waves of a workgroup share a row tile and their partial sums
 // are added in a fixed order through LDS, so results are run-to-run identical.
+// A layer is a few MB to a few tens of MB, i.e. microseconds of HBM time, so
+// the kernel is built to have every byte in flight as early as possible: the
+// host picks KSPLIT so that a wave's whole chunk range fits in registers, and
+// the wave issues all its loads before it touches the activations.
+//
+// The activation row takes one of two routes into the workgroup's LDS:
+//   XQ    - already quantized int8 (mnnq_quant_act ran before);
+//   FUSED - fp32 input, quantized here: per-token symmetric int8 (Section 4.2),
+//           scale = max|x| / 127, the same IEEE operations as mnnq_quant_act.
+//           Every workgroup repeats this for the whole row, so workgroups are
+//           made large (several row tiles each) to keep the repetition small.
+// This file is compiled with -ffp-contract=off for that reason.
 #include "mnnq_common.h"
 
+#include <stdio.h>
 #include <stdlib.h>
 
 namespace mnnq {
@@ -18,6 +31,8 @@ namespace mnnq {
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+enum Mode { kXQ = 0, kFused = 1, kAcc = 2 };
 
 struct ChunkRegs {
     u32x4 w;      // 32 codes: .x,.y group 2c ; .z,.w group 2c+1
@@ -44,42 +59,31 @@ __device__ __forceinline__ int dot16(uint32_t wa, uint32_t wb, const int4& x)
     return d;
 }
 
-// LDS image of the activation row: K int8 padded with zeros to C*128 bytes,
-// followed by the sums of every 16-byte block, stored as [c][kb][half].
-__device__ __forceinline__ void stage_x(const int8_t* __restrict__ xq, int64_t K, int64_t C,
-                                        int4* lds_x, int* lds_xs, int tid, int nthreads)
+__device__ __forceinline__ int quant1(float v, float scale)
 {
-    const int64_t units = C * 8;       // 16-byte units, padded
-    const int64_t valid = K / 16;
-    for (int64_t u = tid; u < units; u += nthreads) {
-        int4 v = make_int4(0, 0, 0, 0);
-        if (u < valid) v = reinterpret_cast<const int4*>(xq)[u];
-        lds_x[u] = v;
-        int s = __builtin_amdgcn_sdot4(v.x, 0x01010101, 0, false);
-        s = __builtin_amdgcn_sdot4(v.y, 0x01010101, s, false);
-        s = __builtin_amdgcn_sdot4(v.z, 0x01010101, s, false);
-        s = __builtin_amdgcn_sdot4(v.w, 0x01010101, s, false);
-        const int64_t c = u / 8;
-        const int half = (int)(u % 8) / 4;
-        const int kb = (int)(u % 4);
-        lds_xs[c * 8 + kb * 2 + half] = s;
-    }
+    return (int)fminf(fmaxf(rintf(v / scale), -127.0f), 127.0f);
 }
 
-template <int WAVES, int KSPLIT, int UNROLL, bool ACC>
+__device__ __forceinline__ int quant4(float4 v, float scale)
+{
+    const int c0 = quant1(v.x, scale), c1 = quant1(v.y, scale), c2 = quant1(v.z, scale), c3 = quant1(v.w, scale);
+    return (c0 & 0xff) | ((c1 & 0xff) << 8) | ((c2 & 0xff) << 16) | ((c3 & 0xff) << 24);
+}
+
+// LDS of a workgroup: the activation row (K int8, zero padded to C * 128 bytes),
+// the sums of its 16-byte blocks stored as [chunk][kb][half], the partial sums
+// of the split rows and the per-wave maxima of the fused quantizer.
+template <int WAVES, int KSPLIT, int UNROLL, int MODE, bool PREFETCH>
 __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __restrict__ packed, Layout L,
-                                                            const int8_t* __restrict__ xq,
+                                                            const void* __restrict__ xin,
                                                             const float* __restrict__ sx,
                                                             const float* __restrict__ bias,
                                                             float* __restrict__ y,
-                                                            int32_t* __restrict__ acc)
+                                                            int32_t* __restrict__ acc, int PW)
 {
     extern __shared__ __align__(16) uint8_t smem[];
+    constexpr int THREADS = WAVES * 64;
     const int64_t C = L.C;
-    int4* lds_x = reinterpret_cast<int4*>(smem);
-    int* lds_xs = reinterpret_cast<int*>(smem + C * 128);
-    float* lds_part = reinterpret_cast<float*>(smem + C * 160);  // [WAVES][16]
-
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -88,8 +92,21 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
     constexpr int TILES_PER_WG = WAVES / KSPLIT;
     const int64_t tile = (int64_t)blockIdx.x * TILES_PER_WG + wave / KSPLIT;
     const int ks = wave % KSPLIT;
-    const int64_t m = ACC ? blockIdx.y : 0;
+    const int64_t m = (MODE == kAcc) ? blockIdx.y : 0;
     const bool active = tile < L.T;
+
+    // Fused mode: one image of the whole row per workgroup.  Otherwise every wave
+    // stages just the chunk range it consumes into a private region (PW chunks),
+    // which needs no barrier.
+    constexpr bool SHARED = (MODE == kFused);
+    const size_t x_bytes = SHARED ? (size_t)C * 160 : (size_t)WAVES * PW * 160;
+    uint8_t* xbase = SHARED ? smem : smem + (size_t)wave * PW * 160;
+    const size_t xs_off = SHARED ? (size_t)C * 128 : (size_t)PW * 128;
+    int* lds_xd = reinterpret_cast<int*>(xbase);                        // row as dwords
+    const int4* lds_x = reinterpret_cast<const int4*>(xbase);           // row as 16-byte units
+    int* lds_xs = reinterpret_cast<int*>(xbase + xs_off);
+    float* lds_part = reinterpret_cast<float*>(smem + x_bytes);         // [WAVES][16]
+    float* lds_amax = lds_part + WAVES * 16;                            // [WAVES]
 
     const int64_t c0 = C * ks / KSPLIT;
     const int64_t c1 = C * (ks + 1) / KSPLIT;
@@ -98,8 +115,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
     const uint16_t* zp = reinterpret_cast<const uint16_t*>(packed + L.zeros_off()) + (tile * C + c0) * 16 + row;
     const int64_t n_chunks = active ? (c1 - c0) : 0;
 
-    // Start the weight stream before the activation row is staged: the first
-    // batch does not depend on x.
+    // Start the weight stream before the activation row is touched: it does not depend on x.
     ChunkRegs cur[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
@@ -107,28 +123,83 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
         else cur[u] = ChunkRegs{};
     }
 
-    stage_x(xq + m * L.K, L.K, C, lds_x, lds_xs, tid, WAVES * 64);
-    __syncthreads();
+    // ---- activation row -> LDS, one dword (four int8) per thread and step
+    const int64_t dwords = C * 32;                       // padded row
+    const int64_t valid = L.K / 4;
+    float scale = 0.0f;
+    if (MODE == kFused) {
+        const float4* x4 = reinterpret_cast<const float4*>(static_cast<const float*>(xin));
+        float4 first = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (tid < valid) first = x4[tid];
+        float amax = fmaxf(fmaxf(fabsf(first.x), fabsf(first.y)), fmaxf(fabsf(first.z), fabsf(first.w)));
+        for (int64_t i = tid + THREADS; i < valid; i += THREADS) {
+            const float4 v = x4[i];
+            amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+        }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
+        if (lane == 0) lds_amax[wave] = amax;
+        __syncthreads();
+        amax = lds_amax[0];
+#pragma unroll
+        for (int w = 1; w < WAVES; ++w) amax = fmaxf(amax, lds_amax[w]);
+        scale = (amax == 0.0f) ? 0.0f : amax / 127.0f;
+        for (int64_t i = tid; i < dwords; i += THREADS) {
+            int v = 0;
+            if (i < valid && scale != 0.0f) v = quant4(i == tid ? first : x4[i], scale);
+            lds_xd[i] = v;
+            // sum of the 16-byte block: its four dwords sit in four neighbouring lanes
+            int sum = __builtin_amdgcn_sdot4(v, 0x01010101, 0, false);
+            sum += __shfl_xor(sum, 1, 64);
+            sum += __shfl_xor(sum, 2, 64);
+            if ((tid & 3) == 0) {
+                const int64_t u = i / 4, c = u / 8;
+                lds_xs[c * 8 + (int)(u % 4) * 2 + (int)(u % 8) / 4] = sum;
+            }
+        }
+        __syncthreads();
+    } else {
+        // This wave's chunks only, in 16-byte units: unit u of the region is unit c0 * 8 + u of the row.
+        const int4* xq16 = reinterpret_cast<const int4*>(static_cast<const int8_t*>(xin) + m * L.K);
+        int4* lds_xw = reinterpret_cast<int4*>(xbase);
+        const int64_t own = (c1 - c0) * 8;
+        for (int64_t u = lane; u < own; u += 64) {
+            const int64_t gu = c0 * 8 + u;
+            int4 v = make_int4(0, 0, 0, 0);
+            if (gu * 4 < valid) v = xq16[gu];
+            lds_xw[u] = v;
+            int sum = __builtin_amdgcn_sdot4(v.x, 0x01010101, 0, false);
+            sum = __builtin_amdgcn_sdot4(v.y, 0x01010101, sum, false);
+            sum = __builtin_amdgcn_sdot4(v.z, 0x01010101, sum, false);
+            sum = __builtin_amdgcn_sdot4(v.w, 0x01010101, sum, false);
+            lds_xs[(u / 8) * 8 + (int)(u % 4) * 2 + (int)(u % 8) / 4] = sum;
+        }
+        // The region is private to the wave; LDS operations of one wave complete in order.
+    }
+    const int64_t cbase = SHARED ? c0 : 0;    // chunk index of the wave's first chunk inside its LDS image
 
     float accf = 0.0f;
     for (int64_t i = 0; i < n_chunks; i += UNROLL) {
-        ChunkRegs nxt[UNROLL];
+        ChunkRegs nxt[PREFETCH ? UNROLL : 1];
+        if (PREFETCH) {
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            if (i + UNROLL + u < n_chunks) nxt[u] = load_chunk(wp, sp, zp, i + UNROLL + u);
-            else nxt[u] = ChunkRegs{};
+            for (int u = 0; u < UNROLL; ++u) {
+                if (i + UNROLL + u < n_chunks) nxt[u] = load_chunk(wp, sp, zp, i + UNROLL + u);
+                else nxt[u] = ChunkRegs{};
+            }
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             if (i + u < n_chunks) {
                 const int64_t c = c0 + i + u;
-                const int4 xa = lds_x[c * 8 + kb];
-                const int4 xb = lds_x[c * 8 + 4 + kb];
-                const int2 xs = *reinterpret_cast<const int2*>(lds_xs + c * 8 + kb * 2);
+                const int64_t cl = cbase + i + u;
+                const int4 xa = lds_x[cl * 8 + kb];
+                const int4 xb = lds_x[cl * 8 + 4 + kb];
+                const int2 xs = *reinterpret_cast<const int2*>(lds_xs + cl * 8 + kb * 2);
                 const ChunkRegs& r = cur[u];
                 int i0 = dot16(r.w.x, r.w.y, xa) - (int)(r.z & 0xffu) * xs.x;
                 int i1 = dot16(r.w.z, r.w.w, xb) - (int)(r.z >> 8) * xs.y;
-                if (ACC) {
+                if (MODE == kAcc) {
                     i0 += __shfl_xor(i0, 16, 64); i0 += __shfl_xor(i0, 32, 64);
                     i1 += __shfl_xor(i1, 16, 64); i1 += __shfl_xor(i1, 32, 64);
                     if (kb == 0) {
@@ -142,10 +213,11 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
                 }
             }
         }
+        if (!PREFETCH) break;   // the host guarantees n_chunks <= UNROLL
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) cur[u] = nxt[u];
     }
-    if (ACC) return;
+    if (MODE == kAcc) return;
 
     // Sum over the four k-blocks of the row, then over the KSPLIT waves.
     accf += __shfl_xor(accf, 16, 64);
@@ -160,36 +232,69 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
     }
     if (active && kb == 0) {
         const int64_t n = tile * kTileN + row;
-        float r = accf * sx[0];
+        float r = accf * ((MODE == kFused) ? scale : sx[0]);
         if (bias) r += bias[n];
         y[n] = r;
     }
 }
 
-template <int WAVES, int KSPLIT, int UNROLL, bool ACC>
-int launch_cfg(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
+template <int WAVES, int KSPLIT, int UNROLL, int MODE, bool PREFETCH>
+int launch_cfg(const uint8_t* packed, const Layout& L, int64_t M, const void* xin, const float* sx,
                const float* bias, float* y, int32_t* acc, hipStream_t st)
 {
     constexpr int tiles_per_wg = WAVES / KSPLIT;
     const int64_t blocks = (L.T + tiles_per_wg - 1) / tiles_per_wg;
-    const size_t smem = (size_t)L.C * 160 + WAVES * 16 * sizeof(float);
-    hipLaunchKernelGGL((decode_kernel<WAVES, KSPLIT, UNROLL, ACC>), dim3((unsigned)blocks, (unsigned)M),
-                       dim3(WAVES * 64), smem, st, packed, L, xq, sx, bias, y, acc);
+    const int PW = (int)((L.C + KSPLIT - 1) / KSPLIT);
+    const size_t smem = (MODE == kFused ? (size_t)L.C * 160 : (size_t)WAVES * PW * 160) + WAVES * 17 * sizeof(float);
+    if (smem > 64 * 1024) return MNNQ_ERR_UNSUPPORTED;   // only reachable with a forced split
+    hipLaunchKernelGGL((decode_kernel<WAVES, KSPLIT, UNROLL, MODE, PREFETCH>), dim3((unsigned)blocks, (unsigned)M),
+                       dim3(WAVES * 64), smem, st, packed, L, xin, sx, bias, y, acc, PW);
     MNNQ_HIP_TRY(hipGetLastError());
     return MNNQ_OK;
 }
 
-// Waves that share one row tile.  Enough waves to keep every CU streaming
-// (about 8 per CU on 256 CUs), but at least two chunks per wave.
-int pick_ksplit(const Layout& L)
+// Configuration: the smallest number of waves per row tile for which a wave's
+// chunk range fits in its registers (8, else 12 chunks), so that all loads of
+// the layer are issued at once; very long rows fall back to a prefetching loop.
+// WAVES is the workgroup size: larger workgroups repeat the staging of the
+// activation row less often.
+template <int MODE>
+int dispatch(const uint8_t* packed, const Layout& L, int64_t M, const void* xin, const float* sx,
+             const float* bias, float* y, int32_t* acc, hipStream_t st)
 {
-    if (const char* e = getenv("MNNQ_DECODE_KSPLIT")) {
-        const int v = atoi(e);
-        if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16) return v;
-    }
     int ks = 1;
-    while (ks < 16 && L.T * ks < 2048 && L.C / (ks * 2) >= 2) ks *= 2;
-    return ks;
+    while (ks < 16 && (L.C + ks - 1) / ks > 8) ks *= 2;
+    int unroll = 8, prefetch = 0;
+    if ((L.C + ks - 1) / ks > 8) {
+        if ((L.C + 15) / 16 <= 12) unroll = 12;
+        else prefetch = 1;
+    }
+    if (const char* e = getenv("MNNQ_DECODE_KSPLIT")) {   // tests and tuning: force the split
+        const int v = atoi(e);
+        if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16) {
+            ks = v;
+            const int64_t pw = (L.C + ks - 1) / ks;
+            unroll = pw <= 8 ? 8 : (pw <= 12 && ks == 16 ? 12 : 8);
+            prefetch = pw > unroll;
+        }
+    }
+    int waves = (MODE == kFused) ? (ks > 8 ? 16 : 8) : (ks > 4 ? ks : 4);
+    if (const char* e = getenv("MNNQ_DECODE_WAVES")) {    // tuning only
+        const int v = atoi(e);
+        if ((v == 4 || v == 8 || v == 16) && v >= ks) waves = v;
+    }
+    if (waves < ks) waves = ks;
+#define MNNQ_CFG(W, K, U, P)                                                    \
+    if (waves == W && ks == K && unroll == U && prefetch == P)                  \
+        return launch_cfg<W, K, U, MODE, (P != 0)>(packed, L, M, xin, sx, bias, y, acc, st);
+#define MNNQ_CFG_W(K, U, P) MNNQ_CFG(4, K, U, P) MNNQ_CFG(8, K, U, P) MNNQ_CFG(16, K, U, P)
+    MNNQ_CFG_W(1, 8, 0) MNNQ_CFG_W(2, 8, 0) MNNQ_CFG_W(4, 8, 0)
+    MNNQ_CFG(8, 8, 8, 0) MNNQ_CFG(16, 8, 8, 0) MNNQ_CFG(16, 16, 8, 0) MNNQ_CFG(16, 16, 12, 0)
+    MNNQ_CFG_W(1, 8, 1) MNNQ_CFG_W(2, 8, 1) MNNQ_CFG_W(4, 8, 1)
+    MNNQ_CFG(8, 8, 8, 1) MNNQ_CFG(16, 8, 8, 1) MNNQ_CFG(16, 16, 8, 1)
+#undef MNNQ_CFG_W
+#undef MNNQ_CFG
+    return MNNQ_ERR_UNSUPPORTED;
 }
 
 }  // namespace
@@ -197,20 +302,20 @@ int pick_ksplit(const Layout& L)
 int launch_decode(const uint8_t* packed, const Layout& L, const int8_t* xq, const float* sx,
                   const float* bias, float* y, hipStream_t st)
 {
-    switch (pick_ksplit(L)) {
-        case 1:  return launch_cfg<4, 1, 4, false>(packed, L, 1, xq, sx, bias, y, nullptr, st);
-        case 2:  return launch_cfg<4, 2, 4, false>(packed, L, 1, xq, sx, bias, y, nullptr, st);
-        case 4:  return launch_cfg<4, 4, 4, false>(packed, L, 1, xq, sx, bias, y, nullptr, st);
-        case 8:  return launch_cfg<8, 8, 4, false>(packed, L, 1, xq, sx, bias, y, nullptr, st);
-        default: return launch_cfg<16, 16, 4, false>(packed, L, 1, xq, sx, bias, y, nullptr, st);
-    }
+    return dispatch<kXQ>(packed, L, 1, xq, sx, bias, y, nullptr, st);
+}
+
+int launch_decode_fused(const uint8_t* packed, const Layout& L, const float* x, const float* bias, float* y,
+                        hipStream_t st)
+{
+    return dispatch<kFused>(packed, L, 1, x, nullptr, bias, y, nullptr, st);
 }
 
 int launch_decode_acc(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, int32_t* acc,
                       hipStream_t st)
 {
     // Same inner loop as the decode kernel, one grid row per token.
-    return launch_cfg<4, 2, 4, true>(packed, L, M, xq, nullptr, nullptr, nullptr, acc, st);
+    return dispatch<kAcc>(packed, L, M, xq, nullptr, nullptr, nullptr, acc, st);
 }
 
 }  // namespace mnnq

@@ -21,6 +21,12 @@ __global__ __launch_bounds__(kQThreads) void quant_act_kernel(const float* __res
     const int tid = threadIdx.x;
     const int64_t K4 = K / 4;  // a multiple of 16: teams of 16 lanes cover whole groups
     const float4* xr = reinterpret_cast<const float4*>(x + m * K);
+    // With few rows (decode) a row is split over gridDim.y workgroups: each finds the
+    // row maximum itself and quantizes its own slice of the row.
+    const int64_t per = (K4 + gridDim.y - 1) / gridDim.y;
+    const int64_t per16 = (per + 15) / 16 * 16;          // slices hold whole groups
+    const int64_t i0 = per16 * blockIdx.y;
+    const int64_t i1 = (i0 + per16 < K4) ? i0 + per16 : K4;
 
     float amax = 0.0f;
     for (int64_t i = tid; i < K4; i += kQThreads) {
@@ -35,11 +41,11 @@ __global__ __launch_bounds__(kQThreads) void quant_act_kernel(const float* __res
 
     const bool zero_row = (amax == 0.0f);
     const float scale = zero_row ? 0.0f : amax / 127.0f;
-    if (tid == 0) sx[m] = scale;
+    if (tid == 0 && blockIdx.y == 0) sx[m] = scale;
 
     uint32_t* out = reinterpret_cast<uint32_t*>(xq + m * K);
     const int64_t G = K / kGroup;
-    for (int64_t i = tid; i < K4; i += kQThreads) {
+    for (int64_t i = i0 + tid; i < i1; i += kQThreads) {
         int c0 = 0, c1 = 0, c2 = 0, c3 = 0;
         if (!zero_row) {
             const float4 v = xr[i];
@@ -64,7 +70,13 @@ __global__ __launch_bounds__(kQThreads) void quant_act_kernel(const float* __res
 int launch_quant_act(const float* x, int64_t M, int64_t K, int8_t* xq, float* sx, int32_t* xsum,
                      hipStream_t st)
 {
-    hipLaunchKernelGGL(quant_act_kernel, dim3((unsigned)M), dim3(kQThreads), 0, st, x, K, xq, sx, xsum);
+    // Decode-sized calls are latency bound: spread a row over several workgroups.
+    unsigned slices = 1;
+    if (M <= 16) {
+        slices = (unsigned)((K / 4 + kQThreads - 1) / kQThreads);
+        if (slices > 32) slices = 32;
+    }
+    hipLaunchKernelGGL(quant_act_kernel, dim3((unsigned)M, slices), dim3(kQThreads), 0, st, x, K, xq, sx, xsum);
     MNNQ_HIP_TRY(hipGetLastError());
     return MNNQ_OK;
 }

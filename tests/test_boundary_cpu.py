@@ -94,6 +94,11 @@ def test_argument_validation_precedes_hip(L):
     assert ld(FAKE, 16, 128, 64, 0, ODD, FAKE, None, FAKE, None, 0, None) == ALIGN
     assert ld(FAKE, 16, 128, 64, 0, FAKE, FAKE, ODD, FAKE, None, 0, None) == ALIGN
 
+    lf = L.mnnq_linear_decode_fused
+    assert lf(FAKE, 16, 128, 64, 0, None, None, FAKE, None, 0, None) == NULL
+    assert lf(FAKE, 16, 128, 64, 0, ODD, None, FAKE, None, 0, None) == ALIGN
+    assert lf(FAKE, 16, 100, 64, 0, FAKE, None, FAKE, None, 0, None) == SHAPE
+
     lp = L.mnnq_linear_prefill
     assert lp(FAKE, 0, 16, 128, 64, 0, FAKE, FAKE, None, FAKE, None, 0, None) == SHAPE
     assert lp(FAKE, 4, 16, 128, 64, 0, None, FAKE, None, FAKE, None, 0, None) == NULL

@@ -128,6 +128,18 @@ def test_decode_matches_oracle(N, K):
         results.append(y)
     y2 = host(B.mnnq_linear_decode(packed, N, K, xqd, sxd))
     assert np.array_equal(results[0], y2)          # run-to-run identical
+    # fused activation quantizer: same codes, same kernel arithmetic -> identical output
+    xd = dev(x)
+    for ks in ("", "1", "4", "16"):
+        if ks:
+            os.environ["MNNQ_DECODE_KSPLIT"] = ks
+        try:
+            yf = host(B.mnnq_linear_decode_fused(packed, N, K, xd))
+            yu = host(B.mnnq_linear_decode(packed, N, K, xqd, sxd))
+        finally:
+            os.environ.pop("MNNQ_DECODE_KSPLIT", None)
+        assert np.abs(yf - y_o[0]).max() <= tol, (ks, np.abs(yf - y_o[0]).max(), tol)
+        assert np.array_equal(yf, yu), ks
 
 
 def test_config1_single_layer_seed0():
@@ -141,6 +153,21 @@ def test_config1_single_layer_seed0():
     y = host(B.mnnq_linear_decode(packed, 8960, 1536, xq, sx))
     assert np.array_equal(host(xq), xq_o)
     assert np.array_equal(host(B.mnnq_linear_acc_debug(packed, 8960, 1536, xq, False)), acc_o)
+    assert np.abs(y - y_o[0]).max() <= TOL_A8 * np.abs(y_o).max()
+
+
+def test_decode_fused_zero_row_and_bias():
+    N, K = 48, 320
+    W = synth.weights(N, K, 43)
+    packed = B.mnnq_pack_weights(dev(W))
+    bias = np.linspace(-2, 2, N).astype(np.float32)
+    y = host(B.mnnq_linear_decode_fused(packed, N, K, dev(np.zeros((1, K), np.float32)), bias=dev(bias)))
+    assert np.array_equal(y, bias)
+    x = synth.activations(1, K, 44)
+    q, s, z = oracle.quant_weights(W)
+    xq, sx, _ = oracle.quant_act(x)
+    _, y_o = oracle.linear_w4a8(xq, sx, q, s, z, bias=bias)
+    y = host(B.mnnq_linear_decode_fused(packed, N, K, dev(x), bias=dev(bias)))
     assert np.abs(y - y_o[0]).max() <= TOL_A8 * np.abs(y_o).max()
 
 
