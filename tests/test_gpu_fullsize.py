@@ -1,0 +1,140 @@
+"""GPU parity at the benchmark's full layer sizes, in the launch configuration
+bench.py times (same entry points, same shapes, q|k|v and gate|up concatenated).
+
+Codes, zero points, scales and int8 activations are compared in full (bit-exact).
+Prefill outputs are compared on sampled (m, n) pairs the oracle computes one by
+one, decode outputs in full; integer group accumulators on a subset of token
+rows.  Tolerances: 1e-5 * max|y| (W4A8), 1e-3 * max|y| (W4A16)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2506_10443_amd import binding as B, synth
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def note(*a):
+    print(*a, flush=True)
+
+
+def fused_weights(model, name):
+    parts = [synth.weights(*synth.MODELS[model]["layers"][p], synth.layer_seed(model, 0, p))
+             for p in synth.fused_parts(name)]
+    return np.concatenate(parts) if len(parts) > 1 else parts[0]
+
+
+def check_w4a8_layer(model, name, M, seed, n_samples=4096, acc_rows=8):
+    W = fused_weights(model, name)
+    N, K = W.shape
+    note("full-size W4A8", model, name, "M", M, "N", N, "K", K)
+    x = synth.activations(M, K, seed, outliers=True)
+    q, s, z = oracle.quant_weights(W)
+    xq_o, sx_o, _ = oracle.quant_act(x)
+
+    packed = B.mnnq_pack_weights(dev(W))
+    del W
+    qg, sg, zg = B.mnnq_unpack_weights(packed, N, K)
+    assert np.array_equal(zg.cpu().numpy(), z)
+    assert np.array_equal(sg.cpu().numpy().view(np.uint32), s.view(np.uint32))
+    assert np.array_equal(qg.cpu().numpy(), q)
+    del qg, sg, zg
+    xq, sx, _ = B.mnnq_quant_act(dev(x), want_xsum=False)
+    assert np.array_equal(xq.cpu().numpy(), xq_o)
+    assert np.array_equal(sx.cpu().numpy().view(np.uint32), sx_o.view(np.uint32))
+
+    # prefill: sampled outputs, plus the corners and the last tile
+    y = B.mnnq_linear_prefill(packed, N, K, xq, sx).cpu().numpy()
+    rng = np.random.default_rng(seed)
+    ms = np.concatenate([rng.integers(0, M, n_samples), [0, 0, M - 1, M - 1]])
+    ns = np.concatenate([rng.integers(0, N, n_samples), [0, N - 1, 0, N - 1]])
+    _, y_s = oracle.linear_w4a8_sampled(xq_o, sx_o, q, s, z, ms, ns, want_acc=False)
+    ymax = np.abs(y).max()
+    err = np.abs(y[ms, ns] - y_s).max()
+    assert err <= 1e-5 * ymax, (err, ymax)
+    assert np.isfinite(y).all()
+
+    # integer accumulators of the MFMA loop on a few token rows, all n and g
+    rows = np.sort(rng.choice(M, size=min(acc_rows, M), replace=False))
+    acc = B.mnnq_linear_acc_debug(packed, N, K, dev(xq_o[rows]), True).cpu().numpy()
+    pm = np.repeat(np.arange(len(rows)), 512)
+    pn = rng.integers(0, N, len(pm))
+    acc_s, _ = oracle.linear_w4a8_sampled(xq_o[rows], sx_o[rows], q, s, z, pm, pn)
+    assert np.array_equal(acc[pm, pn], acc_s)
+
+    # decode: row 0 in full, through both the two-call and the fused entry point
+    _, y0 = oracle.linear_w4a8(xq_o[:1], sx_o[:1], q, s, z, want_acc=False)
+    yd = B.mnnq_linear_decode(packed, N, K, xq[0].contiguous(), sx[:1].contiguous()).cpu().numpy()
+    tol0 = 1e-5 * np.abs(y0).max()
+    assert np.abs(yd - y0[0]).max() <= tol0
+    yf = B.mnnq_linear_decode_fused(packed, N, K, dev(x[0])).cpu().numpy()
+    assert np.abs(yf - y0[0]).max() <= tol0
+    # the same row out of the prefill kernel agrees with the decode kernel to the same bound
+    assert np.abs(y[0] - y0[0]).max() <= tol0
+
+
+@pytest.mark.parametrize("name", ["qkv", "o", "gateup", "down"])
+def test_qwen2_7b_block_layers(name):
+    check_w4a8_layer("qwen2-7b", name, 1024, {"qkv": 11, "o": 12, "gateup": 13, "down": 14}[name])
+
+
+@pytest.mark.parametrize("name", ["qkv", "gateup", "down"])
+def test_qwen2_1p5b_block_layers(name):
+    check_w4a8_layer("qwen2-1.5b", name, 512, {"qkv": 21, "gateup": 23, "down": 24}[name])
+
+
+def test_qwen2_7b_lm_head_decode():
+    N, K = synth.MODELS["qwen2-7b"]["lm_head"]
+    note("full-size lm_head decode", N, K)
+    W = synth.weights(N, K, synth.layer_seed("qwen2-7b", 0, "lm_head"))
+    x = synth.activations(1, K, 31)
+    q, s, z = oracle.quant_weights(W)
+    xq_o, sx_o, _ = oracle.quant_act(x)
+    _, y_o = oracle.linear_w4a8(xq_o, sx_o, q, s, z, want_acc=False)
+    packed = B.mnnq_pack_weights(dev(W))
+    del W
+    xq, sx, _ = B.mnnq_quant_act(dev(x), want_xsum=False)
+    y = B.mnnq_linear_decode(packed, N, K, xq, sx).cpu().numpy()
+    assert np.abs(y - y_o[0]).max() <= 1e-5 * np.abs(y_o).max()
+    rng = np.random.default_rng(5)
+    pn = rng.integers(0, N, 4096)
+    acc = B.mnnq_linear_acc_debug(packed, N, K, xq, False).cpu().numpy()
+    acc_s, _ = oracle.linear_w4a8_sampled(xq_o, sx_o, q, s, z, np.zeros_like(pn), pn)
+    assert np.array_equal(acc[0, pn], acc_s)
+
+
+@pytest.mark.parametrize("name", ["qkv", "gateup", "down"])
+def test_llama3_8b_w4a16_and_w4a8_side_by_side(name):
+    model, M = "llama3-8b", 2048
+    W = fused_weights(model, name)
+    N, K = W.shape
+    note("full-size W4A16 + W4A8", model, name, "M", M, "N", N, "K", K)
+    x = synth.activations(M, K, 41, outliers=False)
+    x16 = x.astype(np.float16)
+    q, s, z = oracle.quant_weights(W)
+    packed = B.mnnq_pack_weights(dev(W))
+    del W
+    rng = np.random.default_rng(42)
+    ms = np.concatenate([rng.integers(0, M, 2048), [0, M - 1]])
+    ns = np.concatenate([rng.integers(0, N, 2048), [N - 1, 0]])
+    # W4A16
+    y16 = B.mnnq_linear_prefill_f16(packed, N, K, dev(x16)).cpu().numpy()
+    y16_s = oracle.linear_w4a16_sampled(x16, q, s, z, ms, ns)
+    assert np.abs(y16[ms, ns] - y16_s).max() <= 1e-3 * np.abs(y16).max()
+    y16_0 = oracle.linear_w4a16(x16[:1], q, s, z)
+    yd = B.mnnq_linear_decode_f16(packed, N, K, dev(x16[0])).cpu().numpy()
+    assert np.abs(yd - y16_0[0]).max() <= 1e-3 * np.abs(y16_0).max()
+    # W4A8 on the same activations
+    xq_o, sx_o, _ = oracle.quant_act(x)
+    xq, sx, _ = B.mnnq_quant_act(dev(x), want_xsum=False)
+    assert np.array_equal(xq.cpu().numpy(), xq_o)
+    y8 = B.mnnq_linear_prefill(packed, N, K, xq, sx).cpu().numpy()
+    _, y8_s = oracle.linear_w4a8_sampled(xq_o, sx_o, q, s, z, ms, ns, want_acc=False)
+    assert np.abs(y8[ms, ns] - y8_s).max() <= 1e-5 * np.abs(y8).max()
+    # the two variants see the same weights: they differ only by the activation rounding
+    assert np.abs(y8[ms, ns] - y16[ms, ns]).max() < 0.05 * np.abs(y16).max()
