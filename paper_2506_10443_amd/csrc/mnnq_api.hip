@@ -74,7 +74,7 @@ size_t mnnq_workspace_size(int64_t M, int64_t N, int64_t K, int group, int mode)
 {
     (void)M;
     if (check_shape(N, K, group, mode) != MNNQ_OK) return 0;
-    return 0;  // partial sums of split rows are combined inside a workgroup
+    return 0;  // split rows are combined inside a workgroup (decode) or directly in y (prefill)
 }
 
 int mnnq_pack_weights(const float* W, int64_t N, int64_t K, int group, int mode, void* packed,
@@ -143,12 +143,13 @@ int mnnq_linear_prefill(const void* packed, int64_t M, int64_t N, int64_t K, int
                         const int8_t* xq, const float* sx, const float* bias, float* y, void* workspace,
                         size_t workspace_bytes, void* stream)
 {
-    (void)workspace; (void)workspace_bytes;
+    (void)workspace_bytes;
     if (!packed || !xq || !sx || !y) return MNNQ_ERR_NULL;
     if (M <= 0) return MNNQ_ERR_SHAPE;
     if (int s = check_shape(N, K, group, mode)) return s;
     if (!prefill_fits(M, N, K)) return MNNQ_ERR_UNSUPPORTED;
-    if (misaligned(packed) || misaligned(xq) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
+    if (misaligned(packed) || misaligned(xq) || misaligned(y) || misaligned(bias) || misaligned(workspace))
+        return MNNQ_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(sx) & 3u) return MNNQ_ERR_ALIGN;
     return launch_prefill(static_cast<const uint8_t*>(packed), make_layout(N, K), M, xq, sx, bias, y, nullptr,
                           static_cast<hipStream_t>(stream));

@@ -74,12 +74,17 @@ struct Lds {
     static constexpr int BYTES = Z_OFF + NT16 * 32;
 };
 
+// Work distribution: one workgroup per output tile and K split.  Shapes with few
+// output tiles and a long K (e.g. N = 3584, K = 18944 at M = 1024) cannot fill 256
+// CUs with whole tiles, so their K range is cut in two; both halves add their part
+// to a zeroed y with fp32 atomics.  Two addends commute, so the result does not
+// depend on which half arrives first.
 template <int BM, int BN, bool ACC>
 __global__ __launch_bounds__(256, ACC ? 1 : 2) void prefill_kernel(const uint8_t* __restrict__ packed, Layout L, int64_t M,
                                                          const int8_t* __restrict__ xq,
                                                          const float* __restrict__ sx,
                                                          const float* __restrict__ bias, float* __restrict__ y,
-                                                         int32_t* __restrict__ acc_out, int MT, int NT)
+                                                         int32_t* __restrict__ acc_out, int MT, int NT, int S)
 {
     using St = Lds<BM, BN>;
     constexpr int WM = BM / 2, WN = BN / 2;      // 2 x 2 waves
@@ -90,24 +95,27 @@ __global__ __launch_bounds__(256, ACC ? 1 : 2) void prefill_kernel(const uint8_t
 
     extern __shared__ __align__(16) uint8_t lds[];   // St::BYTES
 
-    // Workgroups are dealt to the 8 XCDs round-robin by their linear id.  Give
-    // each XCD whole columns of output tiles (one weight row block, all token
-    // blocks) so that a weight block is fetched into one L2 only.
-    const int xcd = blockIdx.x % 8;
-    const int seq = blockIdx.x / 8;
-    const int tile_m = seq % MT;
-    const int tile_n = (seq / MT) * 8 + xcd;
-    if (tile_n >= NT) return;
-
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int col = lane & 15;
     const int kb = lane >> 4;
-    const int64_t m0 = (int64_t)tile_m * BM;
     const int C = (int)L.C;
     const int K = (int)L.K;
+
+    // Workgroups are dealt to the 8 XCDs round-robin by their linear id.  Give each
+    // XCD whole columns of output tiles (one weight row block, all token blocks and
+    // K splits), so that a weight block is fetched into one L2 only.
+    const int xcd = blockIdx.x % 8;
+    const int seq = blockIdx.x / 8;
+    const int split = seq % S;
+    const int tile_m = (seq / S) % MT;
+    const int tile_n = (seq / (S * MT)) * 8 + xcd;
+    if (tile_n >= NT) return;
+    const int cb = C * split / S, ce = C * (split + 1) / S;   // this workgroup's chunks
+    const int64_t m0 = (int64_t)tile_m * BM;
+    const int rt0 = tile_n * NT16;               // first row tile of this output tile
 
     // Buffer resources: out-of-range reads (rows past M, row tiles past N) return zero.
     const __amdgpu_buffer_rsrc_t rs_x =
@@ -115,46 +123,18 @@ __global__ __launch_bounds__(256, ACC ? 1 : 2) void prefill_kernel(const uint8_t
     const __amdgpu_buffer_rsrc_t rs_w =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(packed), 0, (int)L.total(), kBufFlags);
 
-    const int rt0 = tile_n * NT16;               // first row tile of this workgroup
-    // Per-lane offsets of the direct loads (constant over the K loop).
+    // A zero the compiler cannot see through: casting a compile-time-constant LDS
+    // address to the LDS address space trips a code generation error in this toolchain.
+    int opaque_zero = 0;
+    asm volatile("" : "+s"(opaque_zero));
+
+    // Per-lane offsets of the direct loads (constant over the whole kernel).
     const int a_voff = (lane >> 3) * K + (((lane & 7) ^ (lane >> 3)) << 4);
     const int b_voff = lane * 16;
     const int s_voff = (lane >> 5) * C * 128 + (lane & 31) * 4;
     const int z_voff = (lane >> 3) * C * 32 + (lane & 7) * 4;
     const int scales_off = (int)L.scales_off();
     const int zeros_off = (int)L.zeros_off();
-
-    auto issue_stage = [&](int c, int buf) {
-        // A: this wave's A_INSTR blocks of 8 rows x 128 B.
-#pragma unroll
-        for (int i = 0; i < A_INSTR; ++i) {
-            const int q = wave * A_INSTR + i;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rs_x, MNNQ_LDS(lds + St::A_OFF + buf * St::A_BYTES + q * 1024), 16, a_voff,
-                ((int)m0 + q * 8) * K + c * 128, 0, 0);
-        }
-        // B codes: two row tiles per wave, one chunk block (1 KiB) each.
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int j = wave * 2 + i;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::B_OFF + j * 1024), 16, b_voff,
-                                                     ((rt0 + j) * C + c) * 1024, 0, 0);
-        }
-        // Scales: one load covers two row tiles (2 x 128 B); zeros: one load covers all eight (8 x 32 B).
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::S_OFF + wave * 256), 4, s_voff,
-                                                 scales_off + ((rt0 + wave * 2) * C + c) * 128, 0, 0);
-        if (wave == 0)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::Z_OFF), 4, z_voff,
-                                                     zeros_off + (rt0 * C + c) * 32, 0, 0);
-    };
-
-    float yacc[TM][TN][4];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) yacc[i][j][r] = 0.0f;
 
     // Fragment read offsets.
     const int a_row_off = St::A_OFF + (wm * WM + col) * 128;   // + i * 2048 per m-tile
@@ -163,139 +143,193 @@ __global__ __launch_bounds__(256, ACC ? 1 : 2) void prefill_kernel(const uint8_t
     const int s_frag_off = St::S_OFF + wn * TN * 128 + col * 8;
     const int z_frag_off = St::Z_OFF + wn * TN * 32 + col * 2;
 
-    v4i bw[TN];
-    v2i bsv[TN];
-    uint32_t bz[TN];
-    auto read_b = [&]() {
+    {
+        auto issue_stage = [&](int c, int buf) {
+            // A: this wave's A_INSTR blocks of 8 rows x 128 B.
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            bw[j] = *reinterpret_cast<const v4i*>(lds + b_frag_off + j * 1024);
-            bsv[j] = *reinterpret_cast<const v2i*>(lds + s_frag_off + j * 128);
-            bz[j] = *reinterpret_cast<const uint16_t*>(lds + z_frag_off + j * 32);
-        }
-    };
-
-    issue_stage(0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-    __syncthreads();
-    read_b();
-
-    for (int c = 0; c < C; ++c) {
-        const int buf = c & 1;
-        // Every wave holds the B fragments of chunk c in registers and has finished
-        // chunk c - 1: the B tile and the other A buffer may be overwritten.
-        __syncthreads();
-        if (c + 1 < C) issue_stage(c + 1, buf ^ 1);
-
-        const uint8_t* st = lds + buf * St::A_BYTES;
+            for (int i = 0; i < A_INSTR; ++i) {
+                const int q = wave * A_INSTR + i;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    rs_x, MNNQ_LDS(lds + St::A_OFF + buf * St::A_BYTES + q * 1024), 16, a_voff,
+                    ((int)m0 + q * 8) * K + c * 128, 0, 0);
+            }
+            // B codes: two row tiles per wave, one chunk block (1 KiB) each.
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            v4i b[TN];
-            float sc[TN];
+            for (int i = 0; i < 2; ++i) {
+                const int j = wave * 2 + i;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::B_OFF + j * 1024), 16, b_voff,
+                                                         ((rt0 + j) * C + c) * 1024, 0, 0);
+            }
+            // Scales: one load covers two row tiles (2 x 128 B); zeros: one load covers all eight (8 x 32 B).
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::S_OFF + wave * 256), 4, s_voff,
+                                                     scales_off + ((rt0 + wave * 2) * C + c) * 128, 0, 0);
+            if (wave == 0)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::Z_OFF + opaque_zero), 4, z_voff,
+                                                         zeros_off + (rt0 * C + c) * 32, 0, 0);
+        };
+
+        float yacc[TM][TN][4];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) yacc[i][j][r] = 0.0f;
+
+        v4i bw[TN];
+        v2i bsv[TN];
+        uint32_t bz[TN];
+        auto read_b = [&]() {
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                // 0x80 - zero point of this group in each of the four bytes
-                const uint32_t c4 = 0x80808080u - __builtin_amdgcn_perm(bz[j], bz[j], h ? 0x01010101u : 0u);
-                b[j] = h ? unpack_b((uint32_t)bw[j].z, (uint32_t)bw[j].w, c4)
-                         : unpack_b((uint32_t)bw[j].x, (uint32_t)bw[j].y, c4);
-                sc[j] = __int_as_float(h ? bsv[j].y : bsv[j].x);
+                bw[j] = *reinterpret_cast<const v4i*>(lds + b_frag_off + j * 1024);
+                bsv[j] = *reinterpret_cast<const v2i*>(lds + s_frag_off + j * 128);
+                bz[j] = *reinterpret_cast<const uint16_t*>(lds + z_frag_off + j * 32);
             }
-            const int g = 2 * c + h;
-            const uint8_t* ap = st + a_row_off + (((h * 4 + kb) ^ a_sw) << 4);
-            const v4i zero = {0, 0, 0, 0};
-            if (ACC) {
+        };
+
+        issue_stage(cb, 0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        __syncthreads();
+        read_b();
+
+        for (int c = cb; c < ce; ++c) {
+            const int buf = (c - cb) & 1;
+            // Every wave holds the B fragments of chunk c in registers and has finished
+            // chunk c - 1: the B tile and the other A buffer may be overwritten.
+            __syncthreads();
+            if (c + 1 < ce) issue_stage(c + 1, buf ^ 1);
+
+            const uint8_t* st = lds + buf * St::A_BYTES;
 #pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    const v4i a = *reinterpret_cast<const v4i*>(ap + i * 2048);
+            for (int h = 0; h < 2; ++h) {
+                v4i b[TN];
+                float sc[TN];
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        const v4i d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[j], zero, 0, 0, 0);
-                        const int64_t n = (int64_t)(rt0 + wn * TN + j) * 16 + col;
-                        if (n < L.N && g < L.G) {
+                for (int j = 0; j < TN; ++j) {
+                    // 0x80 - zero point of this group in each of the four bytes
+                    const uint32_t c4 = 0x80808080u - __builtin_amdgcn_perm(bz[j], bz[j], h ? 0x01010101u : 0u);
+                    b[j] = h ? unpack_b((uint32_t)bw[j].z, (uint32_t)bw[j].w, c4)
+                             : unpack_b((uint32_t)bw[j].x, (uint32_t)bw[j].y, c4);
+                    sc[j] = __int_as_float(h ? bsv[j].y : bsv[j].x);
+                }
+                const int g = 2 * c + h;
+                const uint8_t* ap = st + a_row_off + (((h * 4 + kb) ^ a_sw) << 4);
+                const v4i zero = {0, 0, 0, 0};
+                if (ACC) {
 #pragma unroll
-                            for (int rr = 0; rr < 4; ++rr) {
-                                const int64_t m = m0 + wm * WM + i * 16 + kb * 4 + rr;
-                                if (m < M) acc_out[(m * L.N + n) * L.G + g] = d[rr];
+                    for (int i = 0; i < TM; ++i) {
+                        const v4i a = *reinterpret_cast<const v4i*>(ap + i * 2048);
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) {
+                            const v4i d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[j], zero, 0, 0, 0);
+                            const int64_t n = (int64_t)(rt0 + wn * TN + j) * 16 + col;
+                            if (n < L.N && g < L.G) {
+#pragma unroll
+                                for (int rr = 0; rr < 4; ++rr) {
+                                    const int64_t m = m0 + wm * WM + i * 16 + kb * 4 + rr;
+                                    if (m < M) acc_out[(m * L.N + n) * L.G + g] = d[rr];
+                                }
                             }
                         }
                     }
-                }
-            } else {
-                // Software pipeline over the TM x TN tiles of this group: the MFMA of
-                // tile t + 1 is issued before the eight VALU operations that fold tile
-                // t into the running sums.  The empty asm statements emit nothing; they
-                // only tie values together so that this order survives the compiler's
-                // schedulers: MFMA(t+1) < epilogue(t) < MFMA(t+2).
-                v4i a = *reinterpret_cast<const v4i*>(ap);
-                v4i a_nxt = a;
-                if (TM > 1) a_nxt = *reinterpret_cast<const v4i*>(ap + 2048);
-                v4i d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[0], zero, 0, 0, 0);
+                } else {
+                    // Software pipeline over the TM x TN tiles of this group: the MFMA of
+                    // tile t + 1 is issued before the eight VALU operations that fold tile
+                    // t into the running sums.  The empty asm statements emit nothing; they
+                    // only tie values together so that this order survives the compiler's
+                    // schedulers: MFMA(t+1) < epilogue(t) < MFMA(t+2).
+                    v4i a = *reinterpret_cast<const v4i*>(ap);
+                    v4i a_nxt = a;
+                    if (TM > 1) a_nxt = *reinterpret_cast<const v4i*>(ap + 2048);
+                    v4i d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[0], zero, 0, 0, 0);
 #pragma unroll
-                for (int t = 0; t < TM * TN; ++t) {
-                    const int i = t / TN, j = t % TN;
-                    v4i d_nxt = d;
-                    if (t + 1 < TM * TN) {
-                        const int i1 = (t + 1) / TN, j1 = (t + 1) % TN;
-                        if (j1 == 0) {
-                            a = a_nxt;
-                            if (i1 + 1 < TM) a_nxt = *reinterpret_cast<const v4i*>(ap + (i1 + 1) * 2048);
+                    for (int tt = 0; tt < TM * TN; ++tt) {
+                        const int i = tt / TN, j = tt % TN;
+                        v4i d_nxt = d;
+                        if (tt + 1 < TM * TN) {
+                            const int i1 = (tt + 1) / TN, j1 = (tt + 1) % TN;
+                            if (j1 == 0) {
+                                a = a_nxt;
+                                if (i1 + 1 < TM) a_nxt = *reinterpret_cast<const v4i*>(ap + (i1 + 1) * 2048);
+                            }
+                            d_nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[j1], zero, 0, 0, 0);
+                            asm volatile("" : "+v"(d), "+v"(d_nxt));
                         }
-                        d_nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[j1], zero, 0, 0, 0);
-                        asm volatile("" : "+v"(d), "+v"(d_nxt));
-                    }
 #pragma unroll
-                    for (int rr = 0; rr < 4; ++rr)
-                        yacc[i][j][rr] = fmaf(sc[j], (float)d[rr], yacc[i][j][rr]);
-                    if (t + 2 < TM * TN) {
-                        const int j2 = (t + 2) % TN;
-                        asm volatile(""
-                                     : "+v"(b[j2]), "+v"(yacc[i][j][0]), "+v"(yacc[i][j][1]), "+v"(yacc[i][j][2]),
-                                       "+v"(yacc[i][j][3]));
-                    } else {
-                        asm volatile(""
-                                     : "+v"(yacc[i][j][0]), "+v"(yacc[i][j][1]), "+v"(yacc[i][j][2]),
-                                       "+v"(yacc[i][j][3]));
+                        for (int rr = 0; rr < 4; ++rr)
+                            yacc[i][j][rr] = fmaf(sc[j], (float)d[rr], yacc[i][j][rr]);
+                        if (tt + 2 < TM * TN) {
+                            const int j2 = (tt + 2) % TN;
+                            asm volatile(""
+                                         : "+v"(b[j2]), "+v"(yacc[i][j][0]), "+v"(yacc[i][j][1]),
+                                           "+v"(yacc[i][j][2]), "+v"(yacc[i][j][3]));
+                        } else {
+                            asm volatile(""
+                                         : "+v"(yacc[i][j][0]), "+v"(yacc[i][j][1]), "+v"(yacc[i][j][2]),
+                                           "+v"(yacc[i][j][3]));
+                        }
+                        d = d_nxt;
                     }
-                    d = d_nxt;
                 }
             }
+            if (c + 1 < ce) {
+                // The loads of chunk c + 1 were issued before this chunk's arithmetic; wait for
+                // this wave's part, make every wave's part visible, fetch the B fragments.
+                __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+                __syncthreads();
+                read_b();
+            }
         }
-        if (c + 1 < C) {
-            // The loads of chunk c + 1 were issued before this chunk's arithmetic; wait for
-            // this wave's part, make every wave's part visible, fetch the B fragments.
-            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-            __syncthreads();
-            read_b();
-        }
-    }
-    if (ACC) return;
-
+        if (!ACC) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+            for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            const int64_t m = m0 + wm * WM + i * 16 + kb * 4 + rr;
-            if (m >= M) continue;
-            const float sxm = sx[m];
+                for (int rr = 0; rr < 4; ++rr) {
+                    const int64_t m = m0 + wm * WM + i * 16 + kb * 4 + rr;
+                    if (m >= M) continue;
+                    const float sxm = sx[m];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int64_t n = (int64_t)(rt0 + wn * TN + j) * 16 + col;
-                if (n >= L.N) continue;
-                float v = yacc[i][j][rr] * sxm;
-                if (bias) v += bias[n];
-                y[m * L.N + n] = v;
+                    for (int j = 0; j < TN; ++j) {
+                        const int64_t n = (int64_t)(rt0 + wn * TN + j) * 16 + col;
+                        if (n >= L.N) continue;
+                        float v = yacc[i][j][rr] * sxm;
+                        if (bias && split == 0) v += bias[n];
+                        if (S == 1) y[m * L.N + n] = v;
+                        else atomicAdd(&y[m * L.N + n], v);
+                    }
+                }
             }
         }
     }
 }
 
+__global__ void zero_f4_kernel(float4* p, int64_t n4)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n4) p[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+}
+
+int num_cus()
+{
+    static thread_local int cached_dev = -1, cached = 0;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (dev != cached_dev) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached = n;
+        cached_dev = dev;
+    }
+    return cached;
+}
+
 template <int BM, int BN, bool ACC>
 int launch_tiles(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
-                 const float* bias, float* y, int32_t* acc, hipStream_t st)
+                 const float* bias, float* y, int32_t* acc, int S, hipStream_t st)
 {
     const int MT = (int)((M + BM - 1) / BM);
     const int NT = (int)((L.N + BN - 1) / BN);
-    const int64_t blocks = (int64_t)MT * ((NT + 7) / 8) * 8;
     constexpr size_t smem = (size_t)Lds<BM, BN>::BYTES;
     auto kern = prefill_kernel<BM, BN, ACC>;
     if (smem > 64 * 1024) {
@@ -309,28 +343,41 @@ int launch_tiles(const uint8_t* packed, const Layout& L, int64_t M, const int8_t
             allowed_dev = dev;
         }
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), smem, st, packed, L, M, xq, sx, bias, y, acc, MT,
-                       NT);
+    if (S > 1) {
+        const int64_t n4 = M * L.N / 4;      // N is a multiple of 16
+        hipLaunchKernelGGL(zero_f4_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st,
+                           reinterpret_cast<float4*>(y), n4);
+        MNNQ_HIP_TRY(hipGetLastError());
+    }
+    const int64_t blocks = (int64_t)MT * S * ((NT + 7) / 8) * 8;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), smem, st, packed, L, M, xq, sx, bias, y, acc, MT, NT,
+                       S);
     MNNQ_HIP_TRY(hipGetLastError());
     return MNNQ_OK;
 }
 
-// Output tiles are dealt to 256 CUs; the cost of a shape is the number of
-// rounds of workgroups times the size of the tile.  Larger tiles amortise the
-// B unpack better (weight 0.85), smaller ones fill the last round.
-bool use_big_tile(const Layout& L, int64_t M)
+// Tile and split choice.  256-row tiles share one B unpack between 8 MFMAs and are
+// preferred when they give every CU work; otherwise 128-row tiles, and a K split in
+// two when even those leave CUs with less than two workgroups.
+struct TilePlan {
+    bool big;
+    int S;
+};
+
+TilePlan plan_tiles(const Layout& L, int64_t M)
 {
-    if (const char* e = getenv("MNNQ_PREFILL_TILE")) {
-        if (e[0] == 'b') return true;
-        if (e[0] == 's') return false;
+    TilePlan p{true, 1};
+    const int cus = num_cus();
+    auto tiles = [&](int bm) { return ((M + bm - 1) / bm) * ((L.N + 127) / 128); };
+    p.big = M > 128 && tiles(256) >= 2 * (int64_t)cus;
+    const int64_t t = tiles(p.big ? 256 : 128);
+    if (t < 2 * (int64_t)cus && L.C >= 64) p.S = 2;   // pays only for long rows: the atomics are not free
+    if (const char* e = getenv("MNNQ_PREFILL_TILE")) {   // tuning only: "b" / "s" [+ split digit]
+        if (e[0] == 'b') p.big = true;
+        if (e[0] == 's') p.big = false;
+        if (e[1] == '1' || e[1] == '2' || e[1] == '4') p.S = e[1] - '0';
     }
-    auto rounds = [&](int bm, int bn) {
-        const int64_t tiles = ((M + bm - 1) / bm) * ((L.N + bn - 1) / bn);
-        return (double)((tiles + 255) / 256);
-    };
-    const double big = rounds(256, 128) * 256 * 128 * 0.85;
-    const double small = rounds(128, 128) * 128 * 128;
-    return big <= small;
+    return p;
 }
 
 }  // namespace
@@ -338,13 +385,13 @@ bool use_big_tile(const Layout& L, int64_t M)
 int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
                    const float* bias, float* y, int32_t* acc_debug, hipStream_t st)
 {
-    const bool big = use_big_tile(L, M);
     if (acc_debug) {
-        if (big) return launch_tiles<256, 128, true>(packed, L, M, xq, sx, bias, y, acc_debug, st);
-        return launch_tiles<128, 128, true>(packed, L, M, xq, sx, bias, y, acc_debug, st);
+        if (M > 128) return launch_tiles<256, 128, true>(packed, L, M, xq, sx, bias, y, acc_debug, 1, st);
+        return launch_tiles<128, 128, true>(packed, L, M, xq, sx, bias, y, acc_debug, 1, st);
     }
-    if (big) return launch_tiles<256, 128, false>(packed, L, M, xq, sx, bias, y, nullptr, st);
-    return launch_tiles<128, 128, false>(packed, L, M, xq, sx, bias, y, nullptr, st);
+    const TilePlan p = plan_tiles(L, M);
+    if (p.big) return launch_tiles<256, 128, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
+    return launch_tiles<128, 128, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
 }
 
 }  // namespace mnnq

@@ -208,6 +208,16 @@ def test_prefill_matches_oracle(M, N, K):
     assert np.abs(y - y_o).max() <= tol, (np.abs(y - y_o).max(), tol)
     y2 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=dev(bias)))
     assert np.array_equal(y, y2)
+    # every tile / split choice gives the same result to the same tolerance
+    for cfg in ("b1", "b2", "s1", "s2"):
+        os.environ["MNNQ_PREFILL_TILE"] = cfg
+        try:
+            y3 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=dev(bias)))
+            y4 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=dev(bias)))
+        finally:
+            os.environ.pop("MNNQ_PREFILL_TILE", None)
+        assert np.abs(y3 - y_o).max() <= tol, cfg
+        assert np.array_equal(y3, y4), cfg           # two commuting addends: still reproducible
     # decode of row 0 agrees with prefill row 0 to the same tolerance
     y0 = host(B.mnnq_linear_decode(packed, N, K, xqd[0].contiguous(), sxd[:1].contiguous(), bias=dev(bias)))
     assert np.abs(y0 - y_o[0]).max() <= tol
