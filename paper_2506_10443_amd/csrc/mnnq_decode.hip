@@ -18,8 +18,9 @@
 //   XQ    - already quantized int8 (mnnq_quant_act ran before);
 //   FUSED - fp32 input, quantized here: per-token symmetric int8 (Section 4.2),
 //           scale = max|x| / 127, the same IEEE operations as mnnq_quant_act.
-//           Every workgroup repeats this for the whole row, so workgroups are
-//           made large (several row tiles each) to keep the repetition small.
+//           Every workgroup repeats this for the whole row; the rounding is done
+//           with a multiply and falls back to the division only next to a tie
+//           (see quant1_fast), which gives the same codes at a third of the cost.
 // This file is compiled with -ffp-contract=off for that reason.
 #include "mnnq_common.h"
 
@@ -59,14 +60,26 @@ __device__ __forceinline__ int dot16(uint32_t wa, uint32_t wb, const int4& x)
     return d;
 }
 
-__device__ __forceinline__ int quant1(float v, float scale)
+// Quantization must give exactly rint(fl(x / scale)) as mnnq_quant_act does, but
+// a correctly rounded division per element is what makes the repeated row
+// quantization expensive.  r = x * fl(1 / scale) differs from fl(x / scale) by
+// less than 3 * 2^-24 * 127.5 < 2.3e-5, so both round to the same integer unless
+// r is within that distance of a half-integer; only then (about one element in
+// ten thousand) the division is done.
+// (thr is 6e-5 normally; 2 - "always divide" - when 1 / scale is not a normal number.)
+__device__ __forceinline__ int quant1_fast(float v, float scale, float inv, float thr)
 {
-    return (int)fminf(fmaxf(rintf(v / scale), -127.0f), 127.0f);
+    const float r = v * inv;
+    float t = rintf(r);
+    const float frac = r - floorf(r);                    // exact
+    if (!(fabsf(frac - 0.5f) >= thr)) t = rintf(v / scale);
+    return (int)fminf(fmaxf(t, -127.0f), 127.0f);
 }
 
-__device__ __forceinline__ int quant4(float4 v, float scale)
+__device__ __forceinline__ int quant4_fast(float4 v, float scale, float inv, float thr)
 {
-    const int c0 = quant1(v.x, scale), c1 = quant1(v.y, scale), c2 = quant1(v.z, scale), c3 = quant1(v.w, scale);
+    const int c0 = quant1_fast(v.x, scale, inv, thr), c1 = quant1_fast(v.y, scale, inv, thr);
+    const int c2 = quant1_fast(v.z, scale, inv, thr), c3 = quant1_fast(v.w, scale, inv, thr);
     return (c0 & 0xff) | ((c1 & 0xff) << 8) | ((c2 & 0xff) << 16) | ((c3 & 0xff) << 24);
 }
 
@@ -144,9 +157,11 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
 #pragma unroll
         for (int w = 1; w < WAVES; ++w) amax = fmaxf(amax, lds_amax[w]);
         scale = (amax == 0.0f) ? 0.0f : amax / 127.0f;
+        const float inv = (amax == 0.0f) ? 0.0f : 1.0f / scale;
+        const float thr = (inv < 1.0e37f && scale > 1.0e-30f) ? 6.0e-5f : 2.0f;
         for (int64_t i = tid; i < dwords; i += THREADS) {
             int v = 0;
-            if (i < valid && scale != 0.0f) v = quant4(i == tid ? first : x4[i], scale);
+            if (i < valid && scale != 0.0f) v = quant4_fast(i == tid ? first : x4[i], scale, inv, thr);
             lds_xd[i] = v;
             // sum of the 16-byte block: its four dwords sit in four neighbouring lanes
             int sum = __builtin_amdgcn_sdot4(v, 0x01010101, 0, false);
