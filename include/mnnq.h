@@ -116,8 +116,13 @@ int mnnq_linear_prefill(const void *packed, int64_t M, int64_t N, int64_t K, int
 int mnnq_linear_decode_f16(const void *packed, int64_t N, int64_t K, int group, int mode,
                            const uint16_t *x16, const float *bias, float *y,
                            void *workspace, size_t workspace_bytes, void *stream);
+/* row_scale: fp32 [M] or NULL; when given, row m of the sums is multiplied by
+ * row_scale[m] before the bias is added.  With x16 holding the int8 activation
+ * codes as fp16 (exact) and row_scale = sx this is the W4A8 result of
+ * mnnq_linear_prefill, computed on the fp16 matrix cores: every group sum is an
+ * integer below 2^24 and so exact in fp32. */
 int mnnq_linear_prefill_f16(const void *packed, int64_t M, int64_t N, int64_t K, int group, int mode,
-                            const uint16_t *x16, const float *bias, float *y,
+                            const uint16_t *x16, const float *row_scale, const float *bias, float *y,
                             void *workspace, size_t workspace_bytes, void *stream);
 
 /* Integer group accumulators of the W4A8 kernels, for bit-exact checks:

@@ -60,7 +60,7 @@ def lib() -> ctypes.CDLL:
         L.mnnq_linear_decode_fused.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
         L.mnnq_linear_prefill.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.mnnq_linear_decode_f16.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
-        L.mnnq_linear_prefill_f16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.mnnq_linear_prefill_f16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.mnnq_linear_acc_debug.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, i32, vp]
         for name in EXPORTS[5:]:
             getattr(L, name).restype = i32
@@ -182,15 +182,15 @@ def mnnq_linear_decode_f16(packed, N: int, K: int, x16, bias=None, out=None):
     return y
 
 
-def mnnq_linear_prefill_f16(packed, N: int, K: int, x16, bias=None, out=None):
-    """M tokens, W4A16: x16 fp16 [M,K] -> y f32 [M,N]."""
+def mnnq_linear_prefill_f16(packed, N: int, K: int, x16, bias=None, out=None, row_scale=None):
+    """M tokens, W4A16: x16 fp16 [M,K] -> y f32 [M,N]; row_scale f32 [M] optional."""
     _dev(packed, torch.uint8, "packed"); _dev(x16, torch.float16, "x16")
     M = x16.shape[0]
     if x16.shape[1] != K:
         raise ValueError("x16 must be [M,K]")
     y = torch.empty((M, N), dtype=torch.float32, device=packed.device) if out is None else out
-    _check(lib().mnnq_linear_prefill_f16(_ptr(packed), M, N, K, GROUP, MODE_W4_ZP_INT, _ptr(x16), _ptr(bias),
-                                         _ptr(y), None, 0, _stream()), "mnnq_linear_prefill_f16")
+    _check(lib().mnnq_linear_prefill_f16(_ptr(packed), M, N, K, GROUP, MODE_W4_ZP_INT, _ptr(x16), _ptr(row_scale),
+                                         _ptr(bias), _ptr(y), None, 0, _stream()), "mnnq_linear_prefill_f16")
     return y
 
 

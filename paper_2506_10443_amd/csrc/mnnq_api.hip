@@ -168,16 +168,17 @@ int mnnq_linear_decode_f16(const void* packed, int64_t N, int64_t K, int group, 
 }
 
 int mnnq_linear_prefill_f16(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
-                            const uint16_t* x16, const float* bias, float* y, void* workspace,
-                            size_t workspace_bytes, void* stream)
+                            const uint16_t* x16, const float* row_scale, const float* bias, float* y,
+                            void* workspace, size_t workspace_bytes, void* stream)
 {
     (void)workspace; (void)workspace_bytes;
     if (!packed || !x16 || !y) return MNNQ_ERR_NULL;
     if (M <= 0) return MNNQ_ERR_SHAPE;
     if (int s = check_shape(N, K, group, mode)) return s;
-    if (M > ((int64_t)1 << 24)) return MNNQ_ERR_UNSUPPORTED;
+    if (!prefill_fits(M, N, 2 * K)) return MNNQ_ERR_UNSUPPORTED;   // byte offsets of fp16 rows
     if (misaligned(packed) || misaligned(x16) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
-    return launch_prefill_f16(static_cast<const uint8_t*>(packed), make_layout(N, K), M, x16, bias, y,
+    if (reinterpret_cast<uintptr_t>(row_scale) & 3u) return MNNQ_ERR_ALIGN;
+    return launch_prefill_f16(static_cast<const uint8_t*>(packed), make_layout(N, K), M, x16, row_scale, bias, y,
                               static_cast<hipStream_t>(stream));
 }
 

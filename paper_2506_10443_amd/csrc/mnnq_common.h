@@ -86,7 +86,11 @@ int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8
                    const float* sx, const float* bias, float* y, int32_t* acc_debug, hipStream_t st);
 int launch_decode_f16(const uint8_t* packed, const Layout& L, const uint16_t* x16, const float* bias,
                       float* y, hipStream_t st);
+// rs: optional per-row factor applied to the fp32 sums before the bias (NULL = none).
 int launch_prefill_f16(const uint8_t* packed, const Layout& L, int64_t M, const uint16_t* x16,
-                       const float* bias, float* y, hipStream_t st);
+                       const float* rs, const float* bias, float* y, hipStream_t st);
+
+// Compute units of the current device (cached per thread and device).
+int num_cus();
 
 }  // namespace mnnq

@@ -1,8 +1,8 @@
-// W4A16 variants (Section 4.2: on GPUs the int4 weights are combined with
+// W4A16 decode step (Section 4.2: on GPUs the int4 weights are combined with
 // fp16 activations to use the floating-point units): same packed weights,
-// activations stay fp16, accumulation in fp32.
+// the activation row stays fp16, accumulation in fp32 with v_dot2_f32_f16.
 //
-//   y[m,n] = sum_g scale[n,g] * sum_{k in g} float(x16[m,k]) * (q[n,k] - zero[n,g]) (+ bias[n])
+//   y[n] = sum_g scale[n,g] * sum_{k in g} float(x16[k]) * (q[n,k] - zero[n,g]) (+ bias[n])
 //
 // The integer q - z (|.| <= 15) is exact in fp16, so the weights enter the
 // contraction without rounding and the group scale is applied once per group
@@ -98,22 +98,28 @@ __device__ __forceinline__ float dot16_f16(uint32_t w0, uint32_t w1, uint32_t z,
     return p;
 }
 
-template <int WAVES, int KSPLIT, int UNROLL>
+// A wave owns one row tile and a contiguous chunk range; KSPLIT waves share a row
+// tile and add their partial sums in a fixed order through LDS.  As in the W4A8
+// decode kernel the host picks KSPLIT so that a wave's whole chunk range fits in
+// registers: all weight loads are issued before the activations are touched, and
+// each wave stages only the slice of x it consumes into a private LDS region (no
+// barrier).
+template <int WAVES, int KSPLIT, int UNROLL, bool PREFETCH>
 __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* __restrict__ packed, Layout L,
                                                                 const uint16_t* __restrict__ x16,
                                                                 const float* __restrict__ bias,
-                                                                float* __restrict__ y)
+                                                                float* __restrict__ y, int PW)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     const int64_t C = L.C;
-    uint4* lds_x = reinterpret_cast<uint4*>(smem);                 // C * 128 halves, permuted by 8
-    float* lds_part = reinterpret_cast<float*>(smem + C * 256);    // [WAVES][16]
-
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int row = lane & 15;
     const int kb = lane >> 4;
+    uint4* lds_x = reinterpret_cast<uint4*>(smem + (size_t)wave * PW * 256);   // PW * 128 halves, permuted by 8
+    float* lds_part = reinterpret_cast<float*>(smem + (size_t)WAVES * PW * 256);  // [WAVES][16]
+
     constexpr int TILES_PER_WG = WAVES / KSPLIT;
     const int64_t tile = (int64_t)blockIdx.x * TILES_PER_WG + wave / KSPLIT;
     const int ks = wave % KSPLIT;
@@ -132,32 +138,35 @@ __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* _
         else cur[u] = ChunkRegs{};
     }
 
-    // Stage x: units of 8 halves (16 B), zero padded to C * 16 units.
+    // This wave's slice of x in units of 8 halves (16 B): unit u of the region is unit
+    // c0 * 16 + u of the row; units past K are zero.
     {
-        const int64_t units = C * 16;
+        const int64_t own = (c1 - c0) * 16;
         const int64_t valid = L.K / 8;
-        for (int64_t u = tid; u < units; u += WAVES * 64) {
+        for (int64_t u = lane; u < own; u += 64) {
+            const int64_t gu = c0 * 16 + u;
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (u < valid) v = reinterpret_cast<const uint4*>(x16)[u];
+            if (gu < valid) v = reinterpret_cast<const uint4*>(x16)[gu];
             lds_x[u] = permute8(v);
         }
+        // The region is private to the wave; LDS operations of one wave complete in order.
     }
-    __syncthreads();
 
     float accf = 0.0f;
     for (int64_t i = 0; i < n_chunks; i += UNROLL) {
-        ChunkRegs nxt[UNROLL];
+        ChunkRegs nxt[PREFETCH ? UNROLL : 1];
+        if (PREFETCH) {
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            if (i + UNROLL + u < n_chunks) nxt[u] = load_chunk(wp, sp, zp, i + UNROLL + u);
-            else nxt[u] = ChunkRegs{};
+            for (int u = 0; u < UNROLL; ++u) {
+                if (i + UNROLL + u < n_chunks) nxt[u] = load_chunk(wp, sp, zp, i + UNROLL + u);
+                else nxt[u] = ChunkRegs{};
+            }
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             if (i + u < n_chunks) {
-                const int64_t c = c0 + i + u;
-                // 16-byte unit index of x[128 c + 64 h + 16 kb]: (128 c + 64 h + 16 kb) / 8
-                const uint4* xp = lds_x + c * 16 + kb * 2;
+                // 16-byte unit of x[128 c + 64 h + 16 kb] inside the region: 16 (i + u) + 8 h + 2 kb
+                const uint4* xp = lds_x + (i + u) * 16 + kb * 2;
                 const ChunkRegs& r = cur[u];
                 const float p0 = dot16_f16(r.w.x, r.w.y, r.z & 0xffu, xp[0], xp[1]);
                 const float p1 = dot16_f16(r.w.z, r.w.w, r.z >> 8, xp[8], xp[9]);
@@ -165,6 +174,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* _
                 accf = fmaf(r.s.y, p1, accf);
             }
         }
+        if (!PREFETCH) break;   // the host guarantees n_chunks <= UNROLL
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) cur[u] = nxt[u];
     }
@@ -187,224 +197,52 @@ __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* _
     }
 }
 
-template <int WAVES, int KSPLIT, int UNROLL>
+template <int WAVES, int KSPLIT, int UNROLL, bool PREFETCH>
 int launch_decode_cfg(const uint8_t* packed, const Layout& L, const uint16_t* x16, const float* bias,
                       float* y, hipStream_t st)
 {
     constexpr int tiles_per_wg = WAVES / KSPLIT;
     const int64_t blocks = (L.T + tiles_per_wg - 1) / tiles_per_wg;
-    const size_t smem = (size_t)L.C * 256 + WAVES * 16 * sizeof(float);
-    hipLaunchKernelGGL((decode_f16_kernel<WAVES, KSPLIT, UNROLL>), dim3((unsigned)blocks), dim3(WAVES * 64),
-                       smem, st, packed, L, x16, bias, y);
+    const int PW = (int)((L.C + KSPLIT - 1) / KSPLIT);
+    const size_t smem = (size_t)WAVES * PW * 256 + WAVES * 16 * sizeof(float);
+    if (smem > 64 * 1024) return MNNQ_ERR_UNSUPPORTED;   // only reachable with a forced split
+    hipLaunchKernelGGL((decode_f16_kernel<WAVES, KSPLIT, UNROLL, PREFETCH>), dim3((unsigned)blocks),
+                       dim3(WAVES * 64), smem, st, packed, L, x16, bias, y, PW);
     MNNQ_HIP_TRY(hipGetLastError());
     return MNNQ_OK;
-}
-
-// ---------------------------------------------------------------- prefill
-
-constexpr int kAStride = 144;  // bytes per LDS row: 64 halves + 16 B padding
-
-template <int BM, int BN, int WGM, int WGN>
-__global__ __launch_bounds__(WGM * WGN * 64) void prefill_f16_kernel(const uint8_t* __restrict__ packed,
-                                                                     Layout L, int64_t M,
-                                                                     const uint16_t* __restrict__ x16,
-                                                                     const float* __restrict__ bias,
-                                                                     float* __restrict__ y, int MT, int NT)
-{
-    constexpr int THREADS = WGM * WGN * 64;
-    constexpr int WM = BM / WGM, WN = BN / WGN;
-    constexpr int TM = WM / 16, TN = WN / 16;
-    constexpr int A_UNITS = BM * 8;  // one stage = one group: 64 halves = 8 units of 16 B per row
-    constexpr int A_PER_THREAD = A_UNITS / THREADS;
-    static_assert(A_UNITS % THREADS == 0, "A tile must split evenly");
-
-    __shared__ __align__(16) uint8_t lds_a[2][BM * kAStride];
-
-    const int xcd = blockIdx.x % 8;
-    const int seq = blockIdx.x / 8;
-    const int tile_m = seq % MT;
-    const int tile_n = (seq / MT) * 8 + xcd;
-    if (tile_n >= NT) return;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int wm = wave / WGN, wn = wave % WGN;
-    const int col = lane & 15;
-    const int kb = lane >> 4;
-    const int64_t m0 = (int64_t)tile_m * BM;
-    const int64_t C = L.C;
-    const int64_t S = 2 * C;  // stages (groups, including a padding group)
-
-    const int64_t rt0 = ((int64_t)tile_n * BN + wn * WN) / 16;
-    bool b_ok[TN];
-    const u32x4* wp[TN];
-    const float2* sp[TN];
-    const uint16_t* zp[TN];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int64_t rt = rt0 + j;
-        b_ok[j] = rt < L.T;
-        const int64_t rtc = b_ok[j] ? rt : 0;
-        wp[j] = reinterpret_cast<const u32x4*>(packed) + rtc * C * 64 + lane;
-        sp[j] = reinterpret_cast<const float2*>(packed + L.scales_off()) + rtc * C * 16 + col;
-        zp[j] = reinterpret_cast<const uint16_t*>(packed + L.zeros_off()) + rtc * C * 16 + col;
-    }
-
-    u32x4 bw[TN], bw_n[TN];
-    float2 bs[TN], bs_n[TN];
-    uint32_t bz[TN], bz_n[TN];
-    uint4 areg[A_PER_THREAD];
-
-    auto load_a = [&](int64_t s) {
-#pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i) {
-            const int u = tid + i * THREADS;
-            const int r = u / 8, cu = u % 8;
-            const int64_t m = m0 + r;
-            const int64_t k = s * 64 + cu * 8;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (m < M && k < L.K) v = *reinterpret_cast<const uint4*>(x16 + m * L.K + k);
-            areg[i] = permute8(v);
-        }
-    };
-    auto store_a = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i) {
-            const int u = tid + i * THREADS;
-            const int r = u / 8, cu = u % 8;
-            *reinterpret_cast<uint4*>(&lds_a[buf][r * kAStride + cu * 16]) = areg[i];
-        }
-    };
-    auto load_b = [&](int64_t c, u32x4* w, float2* s, uint32_t* z) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            w[j] = wp[j][c * 64];
-            s[j] = sp[j][c * 16];
-            z[j] = zp[j][c * 16];
-        }
-    };
-
-    float yacc[TM][TN][4];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) yacc[i][j][r] = 0.0f;
-
-    load_a(0);
-    load_b(0, bw, bs, bz);
-    store_a(0);
-
-    for (int64_t s = 0; s < S; ++s) {
-        const int buf = (int)(s & 1);
-        const int h = buf;
-        __syncthreads();
-        const bool more = s + 1 < S;
-        if (more) load_a(s + 1);
-        if (h == 1 && more) load_b((s + 1) / 2, bw_n, bs_n, bz_n);
-
-        h8 b0[TN], b1[TN];
-        float sc[TN];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const uint32_t zz = h ? (bz[j] >> 8) : (bz[j] & 0xffu);
-            const _Float16 zh = (_Float16)(float)(1024u + zz);
-            const h2 zb = {zh, zh};
-            const uint32_t w0 = h ? bw[j].z : bw[j].x;
-            const uint32_t w1 = h ? bw[j].w : bw[j].y;
-            h2 p;
-            p = code_pair(w0, 0, zb); b0[j][0] = p[0]; b0[j][1] = p[1];
-            p = code_pair(w0, 1, zb); b0[j][2] = p[0]; b0[j][3] = p[1];
-            p = code_pair(w0, 2, zb); b0[j][4] = p[0]; b0[j][5] = p[1];
-            p = code_pair(w0, 3, zb); b0[j][6] = p[0]; b0[j][7] = p[1];
-            p = code_pair(w1, 0, zb); b1[j][0] = p[0]; b1[j][1] = p[1];
-            p = code_pair(w1, 1, zb); b1[j][2] = p[0]; b1[j][3] = p[1];
-            p = code_pair(w1, 2, zb); b1[j][4] = p[0]; b1[j][5] = p[1];
-            p = code_pair(w1, 3, zb); b1[j][6] = p[0]; b1[j][7] = p[1];
-            sc[j] = h ? bs[j].y : bs[j].x;
-        }
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int r = wm * WM + i * 16 + col;
-            // The lane's 16 activations of this group: halves 16 kb .. 16 kb + 15.
-            const h8 a0 = *reinterpret_cast<const h8*>(&lds_a[buf][r * kAStride + kb * 32]);
-            const h8 a1 = *reinterpret_cast<const h8*>(&lds_a[buf][r * kAStride + kb * 32 + 16]);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                v4f d = {0.0f, 0.0f, 0.0f, 0.0f};
-                d = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, b0[j], d, 0, 0, 0);
-                d = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, b1[j], d, 0, 0, 0);
-#pragma unroll
-                for (int rr = 0; rr < 4; ++rr) yacc[i][j][rr] = fmaf(sc[j], d[rr], yacc[i][j][rr]);
-            }
-        }
-        if (more) store_a(buf ^ 1);
-        if (h == 1 && more) {
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                bw[j] = bw_n[j];
-                bs[j] = bs_n[j];
-                bz[j] = bz_n[j];
-            }
-        }
-    }
-
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            const int64_t m = m0 + wm * WM + i * 16 + kb * 4 + rr;
-            if (m >= M) continue;
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                if (!b_ok[j]) continue;
-                const int64_t n = (rt0 + j) * 16 + col;
-                float v = yacc[i][j][rr];
-                if (bias) v += bias[n];
-                y[m * L.N + n] = v;
-            }
-        }
-    }
-}
-
-int pick_ksplit(const Layout& L)
-{
-    if (const char* e = getenv("MNNQ_DECODE_KSPLIT")) {
-        const int v = atoi(e);
-        if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16) return v;
-    }
-    int ks = 1;
-    while (ks < 16 && L.T * ks < 2048 && L.C / (ks * 2) >= 2) ks *= 2;
-    return ks;
 }
 
 }  // namespace
 
+// The smallest number of waves per row tile for which a wave's chunk range fits in
+// its registers (8, else 12 chunks); very long rows fall back to a prefetching loop.
 int launch_decode_f16(const uint8_t* packed, const Layout& L, const uint16_t* x16, const float* bias,
                       float* y, hipStream_t st)
 {
-    switch (pick_ksplit(L)) {
-        case 1:  return launch_decode_cfg<4, 1, 4>(packed, L, x16, bias, y, st);
-        case 2:  return launch_decode_cfg<4, 2, 4>(packed, L, x16, bias, y, st);
-        case 4:  return launch_decode_cfg<4, 4, 4>(packed, L, x16, bias, y, st);
-        case 8:  return launch_decode_cfg<8, 8, 4>(packed, L, x16, bias, y, st);
-        default: return launch_decode_cfg<16, 16, 4>(packed, L, x16, bias, y, st);
+    int ks = 1;
+    while (ks < 16 && (L.C + ks - 1) / ks > 8) ks *= 2;
+    int unroll = 8, prefetch = 0;
+    if ((L.C + ks - 1) / ks > 8) {
+        if ((L.C + 15) / 16 <= 12) unroll = 12;
+        else prefetch = 1;
     }
-}
-
-int launch_prefill_f16(const uint8_t* packed, const Layout& L, int64_t M, const uint16_t* x16,
-                       const float* bias, float* y, hipStream_t st)
-{
-    constexpr int BM = 128, BN = 128;
-    const int MT = (int)((M + BM - 1) / BM);
-    const int NT = (int)((L.N + BN - 1) / BN);
-    const int64_t blocks = (int64_t)MT * ((NT + 7) / 8) * 8;
-    hipLaunchKernelGGL((prefill_f16_kernel<BM, BN, 2, 2>), dim3((unsigned)blocks), dim3(256), 0, st, packed, L,
-                       M, x16, bias, y, MT, NT);
-    MNNQ_HIP_TRY(hipGetLastError());
-    return MNNQ_OK;
+    if (const char* e = getenv("MNNQ_DECODE_KSPLIT")) {   // tests and tuning: force the split
+        const int v = atoi(e);
+        if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16) {
+            ks = v;
+            const int64_t pw = (L.C + ks - 1) / ks;
+            unroll = pw <= 8 ? 8 : (pw <= 12 && ks == 16 ? 12 : 8);
+            prefetch = pw > unroll;
+        }
+    }
+#define MNNQ_CFG(W, K, U, P)                      \
+    if (ks == K && unroll == U && prefetch == P)  \
+        return launch_decode_cfg<W, K, U, (P != 0)>(packed, L, x16, bias, y, st);
+    MNNQ_CFG(4, 1, 8, 0) MNNQ_CFG(4, 2, 8, 0) MNNQ_CFG(4, 4, 8, 0) MNNQ_CFG(8, 8, 8, 0)
+    MNNQ_CFG(16, 16, 8, 0) MNNQ_CFG(16, 16, 12, 0)
+    MNNQ_CFG(4, 1, 8, 1) MNNQ_CFG(4, 2, 8, 1) MNNQ_CFG(4, 4, 8, 1) MNNQ_CFG(8, 8, 8, 1) MNNQ_CFG(16, 16, 8, 1)
+#undef MNNQ_CFG
+    return MNNQ_ERR_UNSUPPORTED;
 }
 
 }  // namespace mnnq

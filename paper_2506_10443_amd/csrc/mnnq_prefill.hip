@@ -310,20 +310,6 @@ __global__ void zero_f4_kernel(float4* p, int64_t n4)
     if (i < n4) p[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 }
 
-int num_cus()
-{
-    static thread_local int cached_dev = -1, cached = 0;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 256;
-    if (dev != cached_dev) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached = n;
-        cached_dev = dev;
-    }
-    return cached;
-}
-
 template <int BM, int BN, bool ACC>
 int launch_tiles(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
                  const float* bias, float* y, int32_t* acc, int S, hipStream_t st)
@@ -381,6 +367,20 @@ TilePlan plan_tiles(const Layout& L, int64_t M)
 }
 
 }  // namespace
+
+int num_cus()
+{
+    static thread_local int cached_dev = -1, cached = 0;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (dev != cached_dev) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached = n;
+        cached_dev = dev;
+    }
+    return cached;
+}
 
 int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
                    const float* bias, float* y, int32_t* acc_debug, hipStream_t st)

@@ -1,0 +1,347 @@
+// Prefill GEMM with fp16 activations on the gfx950 fp16 matrix cores (Section 4.2:
+// on GPUs the int4 weights are combined with fp16 activations, W4A16).
+//
+//   y[m,n] = rs[m] * sum_g scale[n,g] * sum_{k in g} float(x16[m,k]) * (q[n,k] - zero[n,g]) (+ bias[n])
+//
+// rs is an optional per-row factor (1 when absent).  The integer q - z (|.| <= 15)
+// is exact in fp16, so the weights enter the contraction unrounded and the group
+// scale is applied once per group in fp32: two v_mfma_f32_16x16x32_f16 with a
+// zero C operand contract one quantization group (K = 64) of a 16 x 16 tile, and
+// four fused multiply-adds per lane fold the fp32 group sum into the running sum.
+//
+// When the activations are integer codes |x| <= 127 stored as fp16, every product
+// (<= 1905) and every partial sum of a group (<= 121920) is an integer below 2^24
+// and therefore exact in fp32 whatever the summation order: the group sums equal
+// the int32 accumulators of the int8 kernel, and no int -> float conversion is
+// needed in the epilogue.
+//
+// The structure is that of the int8 prefill kernel: operands reach LDS with
+// direct buffer loads, an A stage is one group (BM rows x 64 halves = 128 B per
+// row, 16-byte units XOR-swizzled by the row), a B chunk (two groups) is copied
+// verbatim and held in registers while it is used, and the epilogue of one tile
+// is issued behind the MFMAs of the next.
+//
+// Lane mapping of the 16x16x32 fp16 MFMA (A: 16 x 32, B: 32 x 16, D: 16 x 16):
+//   A operand: lane l holds row l % 16, 8 consecutive k of block l / 16;
+//   B operand: lane l holds column l % 16, the same 8 k;
+//   D:         lane l holds column l % 16, rows 4 (l / 16) + r, r = 0..3.
+// The packed layout gives lane l the 16 codes k = 16 (l / 16) + j of a group.  The
+// first MFMA of a group takes j = 0..7 and the second j = 8..15 on both operands;
+// which k meets which MFMA slot does not matter as long as A and B agree.
+#include "mnnq_common.h"
+
+#include <stdlib.h>
+
+namespace mnnq {
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+
+#define MNNQ_LDS(p) ((__attribute__((address_space(3))) void*)(p))
+
+constexpr int kBufFlags = 0x00020000;  // raw buffer, 32-bit data format (gfx9 family)
+
+union H8Bits {
+    uint32_t u[4];
+    h8 h;
+};
+
+union H2Bits {
+    uint32_t u;
+    h2 h;
+};
+
+// Two codes (bytes b0, b1 of v, each 0..15) -> the halves (c0 - z, c1 - z).
+// A byte c under the high byte 0x64 is the half 1024 + c; subtracting the half
+// 1024 + z (zb, twice) leaves c - z exactly.
+template <uint32_t SEL>
+__device__ __forceinline__ uint32_t code_pair(uint32_t v, h2 zb)
+{
+    H2Bits p;
+    p.u = __builtin_amdgcn_perm(0x64646464u, v, SEL);
+    p.h = p.h - zb;
+    return p.u;
+}
+
+// The eight codes of dword w in natural order (low nibbles of bytes 0..3 are codes
+// 0..3, high nibbles codes 4..7) as eight halves q - z.
+__device__ __forceinline__ h8 unpack8(uint32_t w, h2 zb)
+{
+    const uint32_t lo = w & 0x0f0f0f0fu;
+    const uint32_t hi = (w >> 4) & 0x0f0f0f0fu;
+    H8Bits r;
+    r.u[0] = code_pair<0x04010400u>(lo, zb);
+    r.u[1] = code_pair<0x04030402u>(lo, zb);
+    r.u[2] = code_pair<0x04010400u>(hi, zb);
+    r.u[3] = code_pair<0x04030402u>(hi, zb);
+    return r.h;
+}
+
+template <int BM, int BN>
+struct Lds {
+    static constexpr int NT16 = BN / 16;                 // row tiles of B per workgroup
+    static constexpr int A_BYTES = BM * 128;             // [BM][64] halves, swizzled
+    static constexpr int A_OFF = 0;                      // two A buffers (even / odd group)
+    static constexpr int B_OFF = 2 * A_BYTES;            // [NT16][1024] packed codes
+    static constexpr int S_OFF = B_OFF + NT16 * 1024;    // [NT16][16][2] fp32 scales
+    static constexpr int Z_OFF = S_OFF + NT16 * 128;     // [NT16][16][2] u8 zeros
+    static constexpr int BYTES = Z_OFF + NT16 * 32;
+};
+
+template <int BM, int BN>
+__global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __restrict__ packed, Layout L, int64_t M,
+                                                             const uint16_t* __restrict__ x16,
+                                                             const float* __restrict__ rs,
+                                                             const float* __restrict__ bias, float* __restrict__ y,
+                                                             int MT, int NT)
+{
+    using St = Lds<BM, BN>;
+    constexpr int WM = BM / 2, WN = BN / 2;      // 2 x 2 waves
+    constexpr int TM = WM / 16, TN = WN / 16;
+    constexpr int NT16 = St::NT16;
+    constexpr int A_INSTR = BM / 8 / 4;          // 1 KiB direct loads of A per wave and stage
+    static_assert(NT16 == 8, "B side is written for 8 row tiles per workgroup");
+
+    extern __shared__ __align__(16) uint8_t lds[];   // St::BYTES
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int col = lane & 15;
+    const int kb = lane >> 4;
+    const int C = (int)L.C;
+    const int K2 = (int)L.K * 2;                 // bytes per activation row
+
+    // Each XCD gets whole columns of output tiles, so that a weight block is fetched
+    // into one L2 only.
+    const int xcd = blockIdx.x % 8;
+    const int seq = blockIdx.x / 8;
+    const int tile_m = seq % MT;
+    const int tile_n = (seq / MT) * 8 + xcd;
+    if (tile_n >= NT) return;
+    const int64_t m0 = (int64_t)tile_m * BM;
+    const int rt0 = tile_n * NT16;
+
+    // Out-of-range reads (rows past M, row tiles past N) return zero.
+    const __amdgpu_buffer_rsrc_t rs_x =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(x16), 0, (int)(M * L.K * 2), kBufFlags);
+    const __amdgpu_buffer_rsrc_t rs_w =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(packed), 0, (int)L.total(), kBufFlags);
+
+    // A zero the compiler cannot see through: casting a compile-time-constant LDS
+    // address to the LDS address space trips a code generation error in this toolchain.
+    int opaque_zero = 0;
+    asm volatile("" : "+s"(opaque_zero));
+
+    const int a_voff = (lane >> 3) * K2 + (((lane & 7) ^ (lane >> 3)) << 4);
+    const int b_voff = lane * 16;
+    const int s_voff = (lane >> 5) * C * 128 + (lane & 31) * 4;
+    const int z_voff = (lane >> 3) * C * 32 + (lane & 7) * 4;
+    const int scales_off = (int)L.scales_off();
+    const int zeros_off = (int)L.zeros_off();
+
+    const int a_row_off = St::A_OFF + (wm * WM + col) * 128;   // + i * 2048 per m-tile
+    const int a_sw = col & 7;
+    const int a_u0 = ((2 * kb) ^ a_sw) << 4;                    // unit of halves 16 kb .. 16 kb + 7
+    const int a_u1 = ((2 * kb + 1) ^ a_sw) << 4;                // unit of halves 16 kb + 8 .. 16 kb + 15
+    const int b_frag_off = St::B_OFF + wn * TN * 1024 + lane * 16;
+    const int s_frag_off = St::S_OFF + wn * TN * 128 + col * 8;
+    const int z_frag_off = St::Z_OFF + wn * TN * 32 + col * 2;
+
+    // A stage: group g of this workgroup's BM rows.
+    auto issue_a = [&](int g, int buf) {
+#pragma unroll
+        for (int i = 0; i < A_INSTR; ++i) {
+            const int q = wave * A_INSTR + i;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, MNNQ_LDS(lds + St::A_OFF + buf * St::A_BYTES + q * 1024),
+                                                     16, a_voff, ((int)m0 + q * 8) * K2 + g * 128, 0, 0);
+        }
+    };
+    auto issue_b = [&](int c) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int j = wave * 2 + i;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::B_OFF + j * 1024), 16, b_voff,
+                                                     ((rt0 + j) * C + c) * 1024, 0, 0);
+        }
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::S_OFF + wave * 256), 4, s_voff,
+                                                 scales_off + ((rt0 + wave * 2) * C + c) * 128, 0, 0);
+        if (wave == 0)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::Z_OFF + opaque_zero), 4, z_voff,
+                                                     zeros_off + (rt0 * C + c) * 32, 0, 0);
+    };
+
+    float yacc[TM][TN][4];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) yacc[i][j][r] = 0.0f;
+
+    v4i bw[TN];
+    v2i bsv[TN];
+    uint32_t bz[TN];
+    auto read_b = [&]() {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            bw[j] = *reinterpret_cast<const v4i*>(lds + b_frag_off + j * 1024);
+            bsv[j] = *reinterpret_cast<const v2i*>(lds + s_frag_off + j * 128);
+            bz[j] = *reinterpret_cast<const uint16_t*>(lds + z_frag_off + j * 32);
+        }
+    };
+
+    // One group of the wave's TM x TN tiles: MFMA pair (t+1) < epilogue (t) < MFMA pair (t+2).
+    // The empty asm statements emit nothing; they tie values together so that this
+    // order survives the compiler's schedulers.
+    auto compute = [&](int h, int buf) {
+        h8 b0[TN], b1[TN];
+        float sc[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            H2Bits zb;   // the half 1024 + zero point, twice
+            zb.u = __builtin_amdgcn_perm(0x64646464u, bz[j], h ? 0x04010401u : 0x04000400u);
+            b0[j] = unpack8((uint32_t)(h ? bw[j].z : bw[j].x), zb.h);
+            b1[j] = unpack8((uint32_t)(h ? bw[j].w : bw[j].y), zb.h);
+            sc[j] = __int_as_float(h ? bsv[j].y : bsv[j].x);
+        }
+        const uint8_t* ap = lds + buf * St::A_BYTES + a_row_off;
+        const v4f zero = {0.0f, 0.0f, 0.0f, 0.0f};
+        h8 a0 = *reinterpret_cast<const h8*>(ap + a_u0);
+        h8 a1 = *reinterpret_cast<const h8*>(ap + a_u1);
+        h8 a0_nxt = a0, a1_nxt = a1;
+        if (TM > 1) {
+            a0_nxt = *reinterpret_cast<const h8*>(ap + 2048 + a_u0);
+            a1_nxt = *reinterpret_cast<const h8*>(ap + 2048 + a_u1);
+        }
+        v4f d = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, b0[0], zero, 0, 0, 0);
+        d = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, b1[0], d, 0, 0, 0);
+#pragma unroll
+        for (int tt = 0; tt < TM * TN; ++tt) {
+            const int i = tt / TN, j = tt % TN;
+            v4f d_nxt = d;
+            if (tt + 1 < TM * TN) {
+                const int i1 = (tt + 1) / TN, j1 = (tt + 1) % TN;
+                if (j1 == 0) {
+                    a0 = a0_nxt;
+                    a1 = a1_nxt;
+                    if (i1 + 1 < TM) {
+                        a0_nxt = *reinterpret_cast<const h8*>(ap + (i1 + 1) * 2048 + a_u0);
+                        a1_nxt = *reinterpret_cast<const h8*>(ap + (i1 + 1) * 2048 + a_u1);
+                    }
+                }
+                d_nxt = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, b0[j1], zero, 0, 0, 0);
+                d_nxt = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, b1[j1], d_nxt, 0, 0, 0);
+                asm volatile("" : "+v"(d), "+v"(d_nxt));
+            }
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) yacc[i][j][rr] = fmaf(sc[j], d[rr], yacc[i][j][rr]);
+            if (tt + 2 < TM * TN) {
+                const int j2 = (tt + 2) % TN;
+                asm volatile(""
+                             : "+v"(b0[j2]), "+v"(yacc[i][j][0]), "+v"(yacc[i][j][1]), "+v"(yacc[i][j][2]),
+                               "+v"(yacc[i][j][3]));
+            } else {
+                asm volatile("" : "+v"(yacc[i][j][0]), "+v"(yacc[i][j][1]), "+v"(yacc[i][j][2]), "+v"(yacc[i][j][3]));
+            }
+            d = d_nxt;
+        }
+    };
+
+    issue_a(0, 0);
+    issue_b(0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __syncthreads();
+    read_b();
+
+    for (int c = 0; c < C; ++c) {
+        const bool more = c + 1 < C;
+        // Every wave has finished group 2c - 1 and holds chunk c's B fragments in
+        // registers: the odd A buffer and the B tile may be overwritten.
+        __syncthreads();
+        // The padding group of an odd G is skipped: its activations would be the next
+        // row's, and 0 * x is not 0 for every x.
+        const bool odd_group = 2 * c + 1 < (int)L.G;
+        if (odd_group) issue_a(2 * c + 1, 1);
+        if (more) issue_b(c + 1);
+        compute(0, 0);
+        // Group 2c + 1 (and chunk c + 1's B tile) has landed for every wave, and every
+        // wave has finished reading the even A buffer.
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        if (more) issue_a(2 * c + 2, 0);
+        if (odd_group) compute(1, 1);
+        if (more) {
+            read_b();
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+        }
+    }
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            const int64_t m = m0 + wm * WM + i * 16 + kb * 4 + rr;
+            if (m >= M) continue;
+            const float rsm = rs ? rs[m] : 1.0f;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int64_t n = (int64_t)(rt0 + wn * TN + j) * 16 + col;
+                if (n >= L.N) continue;
+                float v = yacc[i][j][rr];
+                if (rs) v *= rsm;
+                if (bias) v += bias[n];
+                y[m * L.N + n] = v;
+            }
+        }
+    }
+}
+
+template <int BM, int BN>
+int launch_tiles(const uint8_t* packed, const Layout& L, int64_t M, const uint16_t* x16, const float* rs,
+                 const float* bias, float* y, hipStream_t st)
+{
+    const int MT = (int)((M + BM - 1) / BM);
+    const int NT = (int)((L.N + BN - 1) / BN);
+    constexpr size_t smem = (size_t)Lds<BM, BN>::BYTES;
+    auto kern = prefill_f16_kernel<BM, BN>;
+    if (smem > 64 * 1024) {
+        // More than 64 KiB of dynamic LDS has to be allowed once per kernel and device.
+        static thread_local int allowed_dev = -1;
+        int dev = 0;
+        MNNQ_HIP_TRY(hipGetDevice(&dev));
+        if (allowed_dev != dev) {
+            MNNQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+            allowed_dev = dev;
+        }
+    }
+    const int64_t blocks = (int64_t)MT * ((NT + 7) / 8) * 8;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), smem, st, packed, L, M, x16, rs, bias, y, MT, NT);
+    MNNQ_HIP_TRY(hipGetLastError());
+    return MNNQ_OK;
+}
+
+}  // namespace
+
+int launch_prefill_f16(const uint8_t* packed, const Layout& L, int64_t M, const uint16_t* x16, const float* rs,
+                       const float* bias, float* y, hipStream_t st)
+{
+    const int cus = num_cus();
+    const int64_t tiles_big = ((M + 255) / 256) * ((L.N + 127) / 128);
+    bool big = M > 128 && tiles_big >= 2 * (int64_t)cus;
+    if (const char* e = getenv("MNNQ_PREFILL_TILE")) {   // tuning only
+        if (e[0] == 'b') big = true;
+        if (e[0] == 's') big = false;
+    }
+    if (big) return launch_tiles<256, 128>(packed, L, M, x16, rs, bias, y, st);
+    return launch_tiles<128, 128>(packed, L, M, x16, rs, bias, y, st);
+}
+
+}  // namespace mnnq

@@ -107,8 +107,8 @@ def test_argument_validation_precedes_hip(L):
 
     assert L.mnnq_linear_decode_f16(FAKE, 16, 128, 64, 0, None, None, FAKE, None, 0, None) == NULL
     assert L.mnnq_linear_decode_f16(FAKE, 16, 100, 64, 0, FAKE, None, FAKE, None, 0, None) == SHAPE
-    assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 128, 64, 0, FAKE, None, None, None, 0, None) == NULL
-    assert L.mnnq_linear_prefill_f16(FAKE, -1, 16, 128, 64, 0, FAKE, None, FAKE, None, 0, None) == SHAPE
+    assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 128, 64, 0, FAKE, None, None, None, None, 0, None) == NULL
+    assert L.mnnq_linear_prefill_f16(FAKE, -1, 16, 128, 64, 0, FAKE, None, None, FAKE, None, 0, None) == SHAPE
     assert L.mnnq_linear_acc_debug(FAKE, 1, 16, 128, 64, 0, FAKE, None, 0, None) == NULL
     assert L.mnnq_linear_acc_debug(FAKE, 70000, 16, 128, 64, 0, FAKE, FAKE, 0, None) == UNSUP
     assert L.mnnq_unpack_weights(None, 16, 128, 64, 0, FAKE, FAKE, FAKE, None) == NULL

@@ -261,7 +261,7 @@ def test_prefill_extreme_codes_accumulator_bound():
     assert np.abs(y - y_o).max() <= TOL_A8 * np.abs(y_o).max()
 
 
-F16_SHAPES = [(1, 16, 64), (9, 48, 192), (130, 272, 1536), (64, 1024, 4096)]
+F16_SHAPES = [(1, 16, 64), (9, 48, 192), (130, 272, 1536), (64, 1024, 4096), (300, 272, 448), (700, 144, 1600)]
 
 
 @pytest.mark.parametrize("M,N,K", F16_SHAPES)
@@ -285,6 +285,43 @@ def test_w4a16_matches_oracle(M, N, K):
         finally:
             os.environ.pop("MNNQ_DECODE_KSPLIT", None)
         assert np.abs(y0 - y_o[0]).max() <= TOL_A16 * np.abs(y_o[0]).max(), ks
+
+
+@pytest.mark.parametrize("M,N,K", [(17, 16, 64), (300, 272, 448), (513, 400, 1536), (1024, 512, 3584)])
+@pytest.mark.parametrize("tile", ["", "b", "s"])
+def test_prefill_f16_with_integer_codes_equals_int8_prefill(M, N, K, tile):
+    # int8 codes are exact in fp16 and every group sum is an integer below 2^24: the fp16
+    # matrix cores give the int32 accumulators exactly, hence bit-identical y.
+    note("f16 == int8", M, N, K, tile)
+    W = synth.weights(N, K, 900 + M)
+    x = synth.activations(M, K, 901 + M, outliers=True)
+    packed = B.mnnq_pack_weights(dev(W))
+    xq, sx, _ = B.mnnq_quant_act(dev(x), want_xsum=False)
+    bias = dev(synth.weights(1, N, 7)[0] * 10)
+    y8 = B.mnnq_linear_prefill(packed, N, K, xq, sx, bias=bias)
+    if tile:
+        os.environ["MNNQ_PREFILL_TILE"] = tile
+    try:
+        y16 = B.mnnq_linear_prefill_f16(packed, N, K, xq.to(torch.float16), bias=bias, row_scale=sx)
+    finally:
+        os.environ.pop("MNNQ_PREFILL_TILE", None)
+    assert torch.equal(y8, y16)
+
+
+def test_prefill_f16_rows_do_not_leak_into_each_other():
+    # Odd number of groups: the padding group of a row must not pick up the next row's data.
+    M, N, K = 40, 32, 192
+    W = synth.weights(N, K, 910)
+    x16 = synth.activations_f16(M, K, 911)
+    q, s, z = oracle.quant_weights(W)
+    y_o = oracle.linear_w4a16(x16, q, s, z)
+    bad = x16.copy()
+    bad[7, :] = np.float16(np.inf)
+    packed = B.mnnq_pack_weights(dev(W))
+    y = host(B.mnnq_linear_prefill_f16(packed, N, K, dev(bad)))
+    keep = np.arange(M) != 7
+    assert np.isfinite(y[keep]).all()
+    assert np.abs(y[keep] - y_o[keep]).max() <= TOL_A16 * np.abs(y_o).max()
 
 
 def test_w4a16_one_hot_exact_weights():
