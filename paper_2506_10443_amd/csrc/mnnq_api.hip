@@ -36,7 +36,9 @@ int check_shape(int64_t N, int64_t K, int group, int mode)
 bool prefill_fits(int64_t M, int64_t N, int64_t K)
 {
     const int64_t lim = ((int64_t)1 << 31) - 1;
-    return M <= ((int64_t)1 << 24) && (M + 256) * K <= lim && (int64_t)make_layout(N, K).total() <= lim;
+    // 32-bit byte offsets: activation rows of a whole tile, the packed weights, the output.
+    return M <= ((int64_t)1 << 24) && (M + 256) * K <= lim && (int64_t)make_layout(N, K).total() <= lim &&
+           (M + 256) * N * 4 <= lim;
 }
 
 }  // namespace

@@ -282,21 +282,42 @@ __global__ __launch_bounds__(256, ACC ? 1 : 2) void prefill_kernel(const uint8_t
             }
         }
         if (!ACC) {
+            // Output: y = yacc * sx[m] + bias[n].  Buffer accesses keep this free of
+            // branches and 64-bit address arithmetic: rows past M fall outside the
+            // buffers (loads give 0, stores are dropped), a NULL bias is an empty buffer.
+            const __amdgpu_buffer_rsrc_t rs_sx =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(sx), 0, (int)(M * 4), kBufFlags);
+            const __amdgpu_buffer_rsrc_t rs_bias = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<float*>(bias), 0, (bias && split == 0) ? (int)(L.N * 4) : 0, kBufFlags);
+            const __amdgpu_buffer_rsrc_t rs_y =
+                __builtin_amdgcn_make_buffer_rsrc(y, 0, (int)(uint32_t)(M * L.N * 4), kBufFlags);
+            const int Nb = (int)L.N * 4;                       // bytes per output row
+            const int row0 = (int)m0 + wm * WM;                // first row of this wave
+            const int nt0 = rt0 + wn * TN;                     // first row tile (16 outputs) of this wave
+            float bj[TN];
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                bj[j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_bias, col * 4, (nt0 + j) * 64, 0));
+            const int y_voff = kb * 4 * Nb + col * 4;
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
+                float sxr[4];
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr)
+                    sxr[rr] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_sx, kb * 16, (row0 + i * 16 + rr) * 4, 0));
 #pragma unroll
                 for (int rr = 0; rr < 4; ++rr) {
-                    const int64_t m = m0 + wm * WM + i * 16 + kb * 4 + rr;
-                    if (m >= M) continue;
-                    const float sxm = sx[m];
 #pragma unroll
                     for (int j = 0; j < TN; ++j) {
-                        const int64_t n = (int64_t)(rt0 + wn * TN + j) * 16 + col;
-                        if (n >= L.N) continue;
-                        float v = yacc[i][j][rr] * sxm;
-                        if (bias && split == 0) v += bias[n];
-                        if (S == 1) y[m * L.N + n] = v;
-                        else atomicAdd(&y[m * L.N + n], v);
+                        if (nt0 + j >= (int)L.T) continue;     // wave-uniform
+                        const float v = fmaf(yacc[i][j][rr], sxr[rr], bj[j]);
+                        if (S == 1) {
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs_y, y_voff,
+                                                                      (row0 + i * 16 + rr) * Nb + (nt0 + j) * 64, 0);
+                        } else {
+                            const int64_t m = (int64_t)row0 + i * 16 + kb * 4 + rr;
+                            if (m < M) atomicAdd(&y[m * L.N + (int64_t)(nt0 + j) * 16 + col], v);
+                        }
                     }
                 }
             }

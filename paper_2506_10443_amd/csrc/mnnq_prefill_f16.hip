@@ -283,21 +283,39 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
         }
     }
 
+    // Output: y = yacc * rs[m] + bias[n].  Buffer accesses keep this free of branches
+    // and 64-bit address arithmetic: rows past M fall outside the buffers (loads give 0,
+    // stores are dropped), a NULL bias is an empty buffer.
+    const __amdgpu_buffer_rsrc_t rs_rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(rs), 0, rs ? (int)(M * 4) : 0, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rs_bias =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(bias), 0, bias ? (int)(L.N * 4) : 0, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rs_y =
+        __builtin_amdgcn_make_buffer_rsrc(y, 0, (int)(uint32_t)(M * L.N * 4), kBufFlags);
+    const int Nb = (int)L.N * 4;                       // bytes per output row
+    const int row0 = (int)m0 + wm * WM;                // first row of this wave
+    const int nt0 = rt0 + wn * TN;                     // first row tile (16 outputs) of this wave
+    float bj[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+        bj[j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_bias, col * 4, (nt0 + j) * 64, 0));
+    const int y_voff = kb * 4 * Nb + col * 4;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+        float rsr[4];
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-            const int64_t m = m0 + wm * WM + i * 16 + kb * 4 + rr;
-            if (m >= M) continue;
-            const float rsm = rs ? rs[m] : 1.0f;
+            rsr[rr] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_rs, kb * 16, (row0 + i * 16 + rr) * 4, 0));
+            if (!rs) rsr[rr] = 1.0f;
+        }
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const int64_t n = (int64_t)(rt0 + wn * TN + j) * 16 + col;
-                if (n >= L.N) continue;
-                float v = yacc[i][j][rr];
-                if (rs) v *= rsm;
-                if (bias) v += bias[n];
-                y[m * L.N + n] = v;
+                if (nt0 + j >= (int)L.T) continue;     // wave-uniform
+                const float v = fmaf(yacc[i][j][rr], rsr[rr], bj[j]);
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs_y, y_voff,
+                                                      (row0 + i * 16 + rr) * Nb + (nt0 + j) * 64, 0);
             }
         }
     }
