@@ -79,8 +79,8 @@ struct Lds {
 // CUs with whole tiles, so their K range is cut in two; both halves add their part
 // to a zeroed y with fp32 atomics.  Two addends commute, so the result does not
 // depend on which half arrives first.
-template <int BM, int BN, bool ACC>
-__global__ __launch_bounds__(256, ACC ? 1 : 2) void prefill_kernel(const uint8_t* __restrict__ packed, Layout L, int64_t M,
+template <int BM, int BN, int KS, bool ACC>
+__global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_kernel(const uint8_t* __restrict__ packed, Layout L, int64_t M,
                                                          const int8_t* __restrict__ xq,
                                                          const float* __restrict__ sx,
                                                          const float* __restrict__ bias, float* __restrict__ y,
@@ -92,12 +92,17 @@ __global__ __launch_bounds__(256, ACC ? 1 : 2) void prefill_kernel(const uint8_t
     constexpr int NT16 = St::NT16;
     constexpr int A_INSTR = BM / 8 / 4;          // 1 KiB direct loads of A per wave and stage
     static_assert(NT16 == 8, "B side is written for 8 row tiles per workgroup");
+    static_assert(KS == 1 || 4 * TM * TN * 4 * 64 * 4 <= KS * St::BYTES, "the K parts' sums must fit in LDS");
+    static_assert(KS == 1 || !ACC, "the accumulator dump runs unsplit");
 
-    extern __shared__ __align__(16) uint8_t lds[];   // St::BYTES
+    extern __shared__ __align__(16) uint8_t lds_all[];   // KS * St::BYTES
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = wave_id & 3;                // position in the 2 x 2 wave grid of its K part
+    const int kh = wave_id >> 2;                 // K part of this wave (0 .. KS-1)
+    uint8_t* const lds = lds_all + kh * St::BYTES;
     const int wm = wave >> 1, wn = wave & 1;
     const int col = lane & 15;
     const int kb = lane >> 4;
@@ -113,7 +118,10 @@ __global__ __launch_bounds__(256, ACC ? 1 : 2) void prefill_kernel(const uint8_t
     const int tile_m = (seq / S) % MT;
     const int tile_n = (seq / (S * MT)) * 8 + xcd;
     if (tile_n >= NT) return;
-    const int cb = C * split / S, ce = C * (split + 1) / S;   // this workgroup's chunks
+    const int wcb = C * split / S, wce = C * (split + 1) / S;   // this workgroup's chunks
+    // ... of which each K part of the workgroup takes a contiguous share
+    const int cb = wcb + (wce - wcb) * kh / KS, ce = wcb + (wce - wcb) * (kh + 1) / KS;
+    const int n_iter = (wce - wcb + KS - 1) / KS;                // the longest share: all waves run the same barriers
     const int64_t m0 = (int64_t)tile_m * BM;
     const int rt0 = tile_n * NT16;               // first row tile of this output tile
 
@@ -188,13 +196,14 @@ __global__ __launch_bounds__(256, ACC ? 1 : 2) void prefill_kernel(const uint8_t
             }
         };
 
-        issue_stage(cb, 0);
+        if (cb < ce) issue_stage(cb, 0);
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         __syncthreads();
         read_b();
 
-        for (int c = cb; c < ce; ++c) {
-            const int buf = (c - cb) & 1;
+        for (int it = 0; it < n_iter; ++it) {
+            const int c = cb + it;
+            const int buf = it & 1;
             // Every wave holds the B fragments of chunk c in registers and has finished
             // chunk c - 1: the B tile and the other A buffer may be overwritten.
             __syncthreads();
@@ -203,6 +212,7 @@ __global__ __launch_bounds__(256, ACC ? 1 : 2) void prefill_kernel(const uint8_t
             const uint8_t* st = lds + buf * St::A_BYTES;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
+                if (KS > 1 && c >= ce) break;   // the shorter share idles through the last round
                 v4i b[TN];
                 float sc[TN];
 #pragma unroll
@@ -273,13 +283,41 @@ __global__ __launch_bounds__(256, ACC ? 1 : 2) void prefill_kernel(const uint8_t
                     }
                 }
             }
-            if (c + 1 < ce) {
+            if (it + 1 < n_iter) {
                 // The loads of chunk c + 1 were issued before this chunk's arithmetic; wait for
                 // this wave's part, make every wave's part visible, fetch the B fragments.
                 __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
                 __syncthreads();
-                read_b();
+                if (c + 1 < ce) read_b();
             }
+        }
+        if (KS > 1) {
+            // Add the K parts in a fixed order: part kh > 0 leaves its sums in LDS (one
+            // conflict-free float per lane and accumulator), part 0 adds them.
+            float* red = reinterpret_cast<float*>(lds_all);
+            const int slot = wave * (TM * TN * 4 * 64) + lane;
+#pragma unroll
+            for (int p = 1; p < KS; ++p) {
+                __syncthreads();                 // staging buffers (or the previous part's sums) are dead
+                if (kh == p) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) red[slot + ((i * TN + j) * 4 + r) * 64] = yacc[i][j][r];
+                }
+                __syncthreads();
+                if (kh == 0) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) yacc[i][j][r] += red[slot + ((i * TN + j) * 4 + r) * 64];
+                }
+            }
+            if (kh != 0) return;
         }
         if (!ACC) {
             // Output: y = yacc * sx[m] + bias[n].  Buffer accesses keep this free of
@@ -331,14 +369,14 @@ __global__ void zero_f4_kernel(float4* p, int64_t n4)
     if (i < n4) p[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 }
 
-template <int BM, int BN, bool ACC>
+template <int BM, int BN, int KS, bool ACC>
 int launch_tiles(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
                  const float* bias, float* y, int32_t* acc, int S, hipStream_t st)
 {
     const int MT = (int)((M + BM - 1) / BM);
     const int NT = (int)((L.N + BN - 1) / BN);
-    constexpr size_t smem = (size_t)Lds<BM, BN>::BYTES;
-    auto kern = prefill_kernel<BM, BN, ACC>;
+    constexpr size_t smem = (size_t)KS * Lds<BM, BN>::BYTES;
+    auto kern = prefill_kernel<BM, BN, KS, ACC>;
     if (smem > 64 * 1024) {
         // More than 64 KiB of dynamic LDS has to be allowed once per kernel and device.
         static thread_local int allowed_dev = -1;
@@ -357,32 +395,54 @@ int launch_tiles(const uint8_t* packed, const Layout& L, int64_t M, const int8_t
         MNNQ_HIP_TRY(hipGetLastError());
     }
     const int64_t blocks = (int64_t)MT * S * ((NT + 7) / 8) * 8;
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), smem, st, packed, L, M, xq, sx, bias, y, acc, MT, NT,
-                       S);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256 * KS), smem, st, packed, L, M, xq, sx, bias, y, acc, MT,
+                       NT, S);
     MNNQ_HIP_TRY(hipGetLastError());
     return MNNQ_OK;
 }
 
-// Tile and split choice.  256-row tiles share one B unpack between 8 MFMAs and are
-// preferred when they give every CU work; otherwise 128-row tiles, and a K split in
-// two when even those leave CUs with less than two workgroups.
+// Tile, K-part and split choice.  A compute unit is full with two waves per SIMD:
+// two workgroups of four waves, or one workgroup of eight whose halves take one half
+// of K each (KS = 2) and add their sums through LDS.
+//   * 256-row tiles share one B unpack between 8 MFMAs and are preferred when they
+//     alone give every CU two workgroups;
+//   * with at most one 128-row tile per CU, the tile's K range is split inside the
+//     workgroup, which fills the SIMDs without any traffic through memory;
+//   * in between (more 128-row tiles than CUs, fewer than two each) a second round of
+//     workgroups would run on a few CUs only; 256-row tiles with a K split inside the
+//     workgroup use fewer CUs but use them fully;
+//   * a split of K over two workgroups (S = 2, fp32 atomics onto a zeroed y) is left
+//     for long rows with so few tiles that most CUs would idle.
 struct TilePlan {
     bool big;
+    int KS;
     int S;
 };
 
 TilePlan plan_tiles(const Layout& L, int64_t M)
 {
-    TilePlan p{true, 1};
-    const int cus = num_cus();
+    TilePlan p{true, 1, 1};
+    const int64_t cus = num_cus();
     auto tiles = [&](int bm) { return ((M + bm - 1) / bm) * ((L.N + 127) / 128); };
-    p.big = M > 128 && tiles(256) >= 2 * (int64_t)cus;
-    const int64_t t = tiles(p.big ? 256 : 128);
-    if (t < 2 * (int64_t)cus && L.C >= 64) p.S = 2;   // pays only for long rows: the atomics are not free
-    if (const char* e = getenv("MNNQ_PREFILL_TILE")) {   // tuning only: "b" / "s" [+ split digit]
+    if (M > 128 && tiles(256) >= 2 * cus) {
+        p.big = true;
+    } else if (tiles(128) <= cus) {
+        p.big = false;
+        p.KS = 2;
+        if (tiles(128) * 2 <= cus && L.C >= 64) p.S = 2;
+    } else if (tiles(128) < 2 * cus) {
+        p.big = M > 128;
+        p.KS = p.big ? 2 : 1;
+    } else {
+        p.big = false;
+    }
+    if (const char* e = getenv("MNNQ_PREFILL_TILE")) {   // tuning and tests: "b"/"s", split digit, "k" = K parts
         if (e[0] == 'b') p.big = true;
         if (e[0] == 's') p.big = false;
-        if (e[1] == '1' || e[1] == '2' || e[1] == '4') p.S = e[1] - '0';
+        if (e[0] && (e[1] == '1' || e[1] == '2' || e[1] == '4')) {
+            p.S = e[1] - '0';
+            p.KS = (e[2] == 'k') ? 2 : 1;
+        }
     }
     return p;
 }
@@ -407,12 +467,14 @@ int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8
                    const float* bias, float* y, int32_t* acc_debug, hipStream_t st)
 {
     if (acc_debug) {
-        if (M > 128) return launch_tiles<256, 128, true>(packed, L, M, xq, sx, bias, y, acc_debug, 1, st);
-        return launch_tiles<128, 128, true>(packed, L, M, xq, sx, bias, y, acc_debug, 1, st);
+        if (M > 128) return launch_tiles<256, 128, 1, true>(packed, L, M, xq, sx, bias, y, acc_debug, 1, st);
+        return launch_tiles<128, 128, 1, true>(packed, L, M, xq, sx, bias, y, acc_debug, 1, st);
     }
     const TilePlan p = plan_tiles(L, M);
-    if (p.big) return launch_tiles<256, 128, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
-    return launch_tiles<128, 128, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
+    if (p.big && p.KS == 2) return launch_tiles<256, 128, 2, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
+    if (p.big) return launch_tiles<256, 128, 1, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
+    if (p.KS == 2) return launch_tiles<128, 128, 2, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
+    return launch_tiles<128, 128, 1, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
 }
 
 }  // namespace mnnq

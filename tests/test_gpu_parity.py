@@ -228,7 +228,7 @@ def test_prefill_matches_oracle(M, N, K):
     y2 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=dev(bias)))
     assert np.array_equal(y, y2)
     # every tile / split choice gives the same result to the same tolerance
-    for cfg in ("b1", "b2", "s1", "s2"):
+    for cfg in ("b1", "b2", "s1", "s2", "b1k", "s1k", "b2k", "s2k"):
         os.environ["MNNQ_PREFILL_TILE"] = cfg
         try:
             y3 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=dev(bias)))
@@ -298,7 +298,11 @@ def test_prefill_f16_with_integer_codes_equals_int8_prefill(M, N, K, tile):
     packed = B.mnnq_pack_weights(dev(W))
     xq, sx, _ = B.mnnq_quant_act(dev(x), want_xsum=False)
     bias = dev(synth.weights(1, N, 7)[0] * 10)
-    y8 = B.mnnq_linear_prefill(packed, N, K, xq, sx, bias=bias)
+    os.environ["MNNQ_PREFILL_TILE"] = "s1"       # groups summed in order by one wave, as the fp16 kernel does
+    try:
+        y8 = B.mnnq_linear_prefill(packed, N, K, xq, sx, bias=bias)
+    finally:
+        os.environ.pop("MNNQ_PREFILL_TILE", None)
     if tile:
         os.environ["MNNQ_PREFILL_TILE"] = tile
     try:
