@@ -57,9 +57,11 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy, as the known-size reference for rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters")
-    ap.add_argument("--fused-decode", action="store_true",
-                    help="decode pass calls mnnq_linear_decode_fused (quantizer inside the GEMV kernel)")
+    ap.add_argument("--two-call-decode", action="store_true",
+                    help="decode pass calls mnnq_quant_act + mnnq_linear_decode per layer instead of "
+                         "mnnq_linear_decode_fused (fp32 row in, quantizer inside the call)")
     args = ap.parse_args()
+    args.fused_decode = not args.two_call_decode
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; the path shards by output rows (see DESIGN.md) "
               "but no multi-GPU figure is produced.  Run with --gpus 1.", file=sys.stderr)
@@ -128,20 +130,25 @@ def main() -> int:
                              torch.empty((1,), dtype=torch.float32, device=dev),
                              torch.empty((1, lm[1]), dtype=torch.float32, device=dev))
 
-    def decode_layer(p, N, K, io):
+    # scratch of the fused decode call (quantized row + scale), shared by all layers of the pass
+    ws_dec = torch.empty(max(B.mnnq_workspace_size(1, N, K) for _, N, K in
+                             layers + ([("lm_head", lm[1], lm[2])] if lm else [])),
+                         dtype=torch.uint8, device=dev)
+
+    def decode_layer(p, N, K, io, fused=None):
         x, xq, sx, y = io
-        if args.fused_decode:
-            B.mnnq_linear_decode_fused(p, N, K, x, out=y)
+        if args.fused_decode if fused is None else fused:
+            B.mnnq_linear_decode_fused(p, N, K, x, out=y, workspace=ws_dec)
         else:
             B.mnnq_quant_act(x, want_xsum=False, out=(xq, sx, None))
             B.mnnq_linear_decode(p, N, K, xq, sx, out=y)
 
-    def decode_pass():
+    def decode_pass(fused=None):
         for b in range(n_blocks):
             for name, N, K in layers:
-                decode_layer(packed[name][b], N, K, io_dec[name])
+                decode_layer(packed[name][b], N, K, io_dec[name], fused)
         if lm is not None:
-            decode_layer(lm[0], lm[1], lm[2], io_dec["lm_head"])
+            decode_layer(lm[0], lm[1], lm[2], io_dec["lm_head"], fused)
 
     def prefill_pass():
         for b in range(n_blocks):
@@ -271,6 +278,29 @@ def main() -> int:
             per_layer["decode_lm_head"] = {"us": round(t * 1e3, 2),
                                            "gbs": round(decode_bytes(lm[1], lm[2]) / (t * 1e-3) / 1e9, 1)}
 
+    # ---- the same decode pass through the fused entry point (quantizer inside the GEMV), for comparison
+    dec_other = None
+    if do_dec and not args.no_graph:
+        other_fused = not args.fused_decode
+        side3 = torch.cuda.Stream()
+        with torch.cuda.stream(side3):
+            decode_pass(other_fused)
+        side3.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side3):
+            decode_pass(other_fused)
+        g.replay()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(10):
+            g.replay()
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / 10
+        dec_other = {"path": "fused" if other_fused else "two-call", "ms": round(ms, 4),
+                     "gbs": round(dec_bytes / (ms * 1e-3) / 1e9, 1)}
+
     if args.calibrate_copy:
         src = torch.empty(128 * 1024 * 1024, dtype=torch.int32, device=dev).fill_(7)
         dst = torch.empty_like(src)
@@ -324,6 +354,7 @@ def main() -> int:
         "decode_ms": round(dec_mean, 4) if do_dec else None,
         "decode_gbs": round(dec_gbs, 1) if do_dec else None,
         "decode_frac_of_hbm_peak": round(dec_gbs / HBM_PEAK_GBS, 4) if do_dec else None,
+        "decode_other_path": dec_other,
         "prefill_ms": round(pre_mean, 4) if do_pre else None,
         "prefill_value": round(pre_tops, 1) if do_pre else None, "prefill_unit": "TOP/s",
         "prefill_frac_of_int8_peak": round(pre_tops / INT8_PEAK_TOPS, 4) if do_pre else None,

@@ -63,8 +63,13 @@ int mnnq_version(void);
  * group per row tile is added. */
 size_t mnnq_packed_size(int64_t N, int64_t K, int group, int mode);
 
-/* Bytes of scratch the linear calls need for these shapes (split-K partial
- * sums).  May be 0; then `workspace` may be NULL. */
+/* Bytes of device scratch the linear calls can make use of for these shapes.
+ * No call needs a workspace: NULL / 0 is always accepted.  For M = 1 the value
+ * is what mnnq_linear_decode_fused uses, when given, to hold the int8 row and
+ * its scale (K rounded up to 128, plus 16): for layers above 48 MiB of packed
+ * weights it then runs the quantizer as a kernel of its own in front of the
+ * GEMV, which is faster there than quantizing inside every workgroup.  The
+ * result does not depend on the route.  Other calls return 0. */
 size_t mnnq_workspace_size(int64_t M, int64_t N, int64_t K, int group, int mode);
 
 /* Load-time step (Section 4.2 Eq. 1, Section 5.1 "rearranged at model loading
@@ -98,7 +103,9 @@ int mnnq_linear_decode(const void *packed, int64_t N, int64_t K, int group, int 
  * row x [K] and quantizes it inside the kernel exactly as mnnq_quant_act does
  * (Section 4.2: activations are quantized to int8 during calculation), then
  * computes the same y as mnnq_linear_decode.  Saves one launch and the round
- * trip of xq through memory on the latency-critical decode path. */
+ * trip of xq through memory on the latency-critical decode path.
+ * workspace: optional, see mnnq_workspace_size; 16-byte aligned; its contents
+ * are scratch and calls sharing one workspace must not overlap in time. */
 int mnnq_linear_decode_fused(const void *packed, int64_t N, int64_t K, int group, int mode,
                              const float *x, const float *bias, float *y,
                              void *workspace, size_t workspace_bytes, void *stream);

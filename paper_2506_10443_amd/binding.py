@@ -148,14 +148,18 @@ def mnnq_linear_decode(packed, N: int, K: int, xq, sx, bias=None, out=None):
     return y
 
 
-def mnnq_linear_decode_fused(packed, N: int, K: int, x, bias=None, out=None):
-    """One token, activation quantizer fused in: x f32 [K] (or [1,K]) -> y f32 [N]."""
+def mnnq_linear_decode_fused(packed, N: int, K: int, x, bias=None, out=None, workspace=None):
+    """One token, activation quantizer fused in: x f32 [K] (or [1,K]) -> y f32 [N].
+    workspace: optional uint8 tensor of mnnq_workspace_size(1, N, K) bytes."""
     _dev(packed, torch.uint8, "packed"); _dev(x, torch.float32, "x")
     if x.numel() != K:
         raise ValueError("x must hold K values")
     y = torch.empty((N,), dtype=torch.float32, device=packed.device) if out is None else out
+    if workspace is not None:
+        _dev(workspace, torch.uint8, "workspace")
     _check(lib().mnnq_linear_decode_fused(_ptr(packed), N, K, GROUP, MODE_W4_ZP_INT, _ptr(x), _ptr(bias),
-                                          _ptr(y), None, 0, _stream()), "mnnq_linear_decode_fused")
+                                          _ptr(y), _ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                          _stream()), "mnnq_linear_decode_fused")
     return y
 
 

@@ -33,6 +33,12 @@ int check_shape(int64_t N, int64_t K, int group, int mode)
 
 // The prefill kernel addresses the activations and the packed weights with
 // 32-bit buffer offsets.
+size_t fused_ws_bytes(int64_t K) { return (size_t)((K + 127) / 128 * 128 + 16); }
+
+// Above this many bytes of packed weights the decode GEMV is bandwidth bound and
+// quantizing the row once, in a kernel of its own, beats quantizing it in every workgroup.
+constexpr size_t kFusedTwoKernelBytes = (size_t)48 << 20;
+
 bool prefill_fits(int64_t M, int64_t N, int64_t K)
 {
     const int64_t lim = ((int64_t)1 << 31) - 1;
@@ -74,9 +80,10 @@ size_t mnnq_packed_size(int64_t N, int64_t K, int group, int mode)
 
 size_t mnnq_workspace_size(int64_t M, int64_t N, int64_t K, int group, int mode)
 {
-    (void)M;
     if (check_shape(N, K, group, mode) != MNNQ_OK) return 0;
-    return 0;  // split rows are combined inside a workgroup (decode) or directly in y (prefill)
+    // Split rows are combined inside a workgroup (decode) or directly in y (prefill): nothing
+    // needs scratch.  The fused decode call can use room for the quantized row and its scale.
+    return M == 1 ? fused_ws_bytes(K) : 0;
 }
 
 int mnnq_pack_weights(const float* W, int64_t N, int64_t K, int group, int mode, void* packed,
@@ -132,13 +139,20 @@ int mnnq_linear_decode(const void* packed, int64_t N, int64_t K, int group, int 
 int mnnq_linear_decode_fused(const void* packed, int64_t N, int64_t K, int group, int mode, const float* x,
                              const float* bias, float* y, void* workspace, size_t workspace_bytes, void* stream)
 {
-    (void)workspace; (void)workspace_bytes;
     if (!packed || !x || !y) return MNNQ_ERR_NULL;
     if (int s = check_shape(N, K, group, mode)) return s;
     if (K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
-    if (misaligned(packed) || misaligned(x) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
-    return launch_decode_fused(static_cast<const uint8_t*>(packed), make_layout(N, K), x, bias, y,
-                               static_cast<hipStream_t>(stream));
+    if (misaligned(packed) || misaligned(x) || misaligned(y) || misaligned(bias) || misaligned(workspace))
+        return MNNQ_ERR_ALIGN;
+    const Layout L = make_layout(N, K);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (workspace && workspace_bytes >= fused_ws_bytes(K) && L.total() > kFusedTwoKernelBytes) {
+        int8_t* xq = static_cast<int8_t*>(workspace);
+        float* sx = reinterpret_cast<float*>(xq + (K + 127) / 128 * 128);
+        if (int s = launch_quant_act(x, 1, K, xq, sx, nullptr, st)) return s;
+        return launch_decode(static_cast<const uint8_t*>(packed), L, xq, sx, bias, y, st);
+    }
+    return launch_decode_fused(static_cast<const uint8_t*>(packed), L, x, bias, y, st);
 }
 
 int mnnq_linear_prefill(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,

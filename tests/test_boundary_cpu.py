@@ -48,7 +48,9 @@ def test_packed_size(L):
     assert binding.mnnq_packed_size(16, 128, 32) == 0  # group
     assert binding.mnnq_packed_size(16, 128, 64, 1) == 0  # mode
     assert binding.mnnq_packed_size(0, 128) == 0 and binding.mnnq_packed_size(16, -64) == 0
-    assert binding.mnnq_workspace_size(1, 16, 128) == 0
+    assert binding.mnnq_workspace_size(1, 16, 128) == 128 + 16     # optional scratch of the fused decode call
+    assert binding.mnnq_workspace_size(1, 16, 192) == 256 + 16
+    assert binding.mnnq_workspace_size(4, 16, 128) == 0 and binding.mnnq_workspace_size(1, 8, 128) == 0
 
 
 def test_status_strings(L):
@@ -98,6 +100,7 @@ def test_argument_validation_precedes_hip(L):
     assert lf(FAKE, 16, 128, 64, 0, None, None, FAKE, None, 0, None) == NULL
     assert lf(FAKE, 16, 128, 64, 0, ODD, None, FAKE, None, 0, None) == ALIGN
     assert lf(FAKE, 16, 100, 64, 0, FAKE, None, FAKE, None, 0, None) == SHAPE
+    assert lf(FAKE, 16, 128, 64, 0, FAKE, None, FAKE, ODD, 1024, None) == ALIGN
 
     lp = L.mnnq_linear_prefill
     assert lp(FAKE, 0, 16, 128, 64, 0, FAKE, FAKE, None, FAKE, None, 0, None) == SHAPE

@@ -74,6 +74,13 @@ def check_w4a8_layer(model, name, M, seed, n_samples=4096, acc_rows=8):
     assert np.abs(yd - y0[0]).max() <= tol0
     yf = B.mnnq_linear_decode_fused(packed, N, K, dev(x[0])).cpu().numpy()
     assert np.abs(yf - y0[0]).max() <= tol0
+    # with a workspace the fused call may run the quantizer as its own kernel (large layers):
+    # same codes, same GEMV kernel as the two-call form, hence the same bits; otherwise the same tolerance
+    ws = torch.empty(B.mnnq_workspace_size(1, N, K), dtype=torch.uint8, device="cuda:0")
+    yw = B.mnnq_linear_decode_fused(packed, N, K, dev(x[0]), workspace=ws).cpu().numpy()
+    assert np.abs(yw - y0[0]).max() <= tol0
+    if packed.numel() > (48 << 20):
+        assert np.array_equal(yw, yd)
     # the same row out of the prefill kernel agrees with the decode kernel to the same bound
     assert np.abs(y[0] - y0[0]).max() <= tol0
 

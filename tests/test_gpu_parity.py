@@ -242,6 +242,22 @@ def test_prefill_matches_oracle(M, N, K):
     assert np.abs(y0 - y_o[0]).max() <= tol
 
 
+def test_prefill_many_tiles_ragged_last_column():
+    # More 256-row tiles than the GPU holds at once (several rounds of workgroups), N not a
+    # multiple of the tile width: every output is compared.
+    M, N, K = 1024, 20496, 128
+    note("prefill many tiles", M, N, K)
+    W = synth.weights(N, K, 321)
+    x = synth.activations(M, K, 322, outliers=True)
+    q, s, z = oracle.quant_weights(W)
+    xq, sx, _ = oracle.quant_act(x)
+    bias = synth.weights(1, N, 8)[0] * 10
+    _, y_o = oracle.linear_w4a8(xq, sx, q, s, z, bias=bias, want_acc=False)
+    packed = B.mnnq_pack_weights(dev(W))
+    y = host(B.mnnq_linear_prefill(packed, N, K, dev(xq), dev(sx), bias=dev(bias)))
+    assert np.abs(y - y_o).max() <= TOL_A8 * np.abs(y_o).max()
+
+
 def test_prefill_extreme_codes_accumulator_bound():
     # |I| reaches 64 * 127 * 15: all activations +-127, weights at the ends of the code range.
     N, K, M = 32, 256, 16
