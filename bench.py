@@ -31,7 +31,7 @@ G = 64
 # HBM traffic per launch (bytes, mean over a pass) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this file, scaled by a copy kernel of known size; see profiles/ for the runs.  None = not measured
 # for the current kernels.
-PREFILL_TRAFFIC_BYTES = 170.3e6   # profiles/bench_qwen2-7b_hbm_traffic.txt
+PREFILL_TRAFFIC_BYTES = 169.9e6   # profiles/bench_qwen2-7b_hbm_traffic.txt
 DECODE_TRAFFIC_BYTES = 33.8e6     # same file
 
 
@@ -253,7 +253,7 @@ def main() -> int:
         ach = ops / len(fns) / (t * 1e-3) / 1e12
         roof_pre = {"kernel": "prefill_kernel (W4A8 int8 MFMA GEMM), all %d launches of a pass" % len(fns),
                     "bound": "mfma", "achieved": round(ach, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                    "frac": round(ach / INT8_PEAK_TOPS, 4), "traffic": PREFILL_TRAFFIC_BYTES,
+                    "frac": round(ach / INT8_PEAK_TOPS, 4), "traffic": PREFILL_TRAFFIC_BYTES if args.model == "qwen2-7b" else None,
                     "algorithmic_ops_per_launch": ops // len(fns), "avg_launch_us": round(t * 1e3, 2)}
     if do_dec:
         fns, byt = [], 0
@@ -270,7 +270,7 @@ def main() -> int:
         ach = byt / len(fns) / (t * 1e-3) / 1e9
         roof_dec = {"kernel": "decode_kernel (W4A8 GEMV), all %d block launches of a pass" % len(fns),
                     "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": DECODE_TRAFFIC_BYTES,
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": DECODE_TRAFFIC_BYTES if args.model == "qwen2-7b" else None,
                     "algorithmic_bytes_per_launch": byt // len(fns), "avg_launch_us": round(t * 1e3, 2)}
         if lm is not None:
             x, xq, sx, y = io_dec["lm_head"]
