@@ -65,6 +65,65 @@ __global__ __launch_bounds__(kQThreads) void quant_act_kernel(const float* __res
     }
 }
 
+// Many rows (prefill): the row is held in registers between the maximum and the
+// quantization, so it crosses the memory system once and all of a thread's loads
+// are in flight together.  NV float4 per thread; K <= NV * 4 * kQThreads.
+template <int NV>
+__global__ __launch_bounds__(kQThreads) void quant_act_rows_kernel(const float* __restrict__ x, int64_t K,
+                                                                   int8_t* __restrict__ xq,
+                                                                   float* __restrict__ sx,
+                                                                   int32_t* __restrict__ xsum)
+{
+    __shared__ float s_part[kQThreads / 64];
+    const int64_t m = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int K4 = (int)(K / 4);
+    const float4* xr = reinterpret_cast<const float4*>(x + m * K);
+
+    float4 v[NV];
+    float amax = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int i = tid + j * kQThreads;
+        v[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (i < K4) v[j] = xr[i];
+        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v[j].x), fabsf(v[j].y)), fmaxf(fabsf(v[j].z), fabsf(v[j].w))));
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
+    if ((tid & 63) == 0) s_part[tid >> 6] = amax;
+    __syncthreads();
+    amax = fmaxf(fmaxf(s_part[0], s_part[1]), fmaxf(s_part[2], s_part[3]));
+
+    const bool zero_row = (amax == 0.0f);
+    const float scale = zero_row ? 0.0f : amax / 127.0f;
+    if (tid == 0) sx[m] = scale;
+
+    uint32_t* out = reinterpret_cast<uint32_t*>(xq + m * K);
+    const int64_t G = K / kGroup;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int i = tid + j * kQThreads;
+        int c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+        if (!zero_row) {
+            c0 = (int)fminf(fmaxf(rintf(v[j].x / scale), -127.0f), 127.0f);
+            c1 = (int)fminf(fmaxf(rintf(v[j].y / scale), -127.0f), 127.0f);
+            c2 = (int)fminf(fmaxf(rintf(v[j].z / scale), -127.0f), 127.0f);
+            c3 = (int)fminf(fmaxf(rintf(v[j].w / scale), -127.0f), 127.0f);
+        }
+        if (i < K4)
+            out[i] = (uint32_t)(c0 & 0xff) | ((uint32_t)(c1 & 0xff) << 8) | ((uint32_t)(c2 & 0xff) << 16) |
+                     ((uint32_t)(c3 & 0xff) << 24);
+        if (xsum) {
+            // K4 is a multiple of 16, so a team of 16 lanes is inside the row or outside it as a whole
+            int s = c0 + c1 + c2 + c3;
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) s += __shfl_xor(s, o, 16);
+            if ((tid & 15) == 0 && i < K4) xsum[m * G + i / 16] = s;
+        }
+    }
+}
+
 }  // namespace
 
 int launch_quant_act(const float* x, int64_t M, int64_t K, int8_t* xq, float* sx, int32_t* xsum,
@@ -75,6 +134,18 @@ int launch_quant_act(const float* x, int64_t M, int64_t K, int8_t* xq, float* sx
     if (M <= 16) {
         slices = (unsigned)((K / 4 + kQThreads - 1) / kQThreads);
         if (slices > 32) slices = 32;
+    }
+    if (M > 16 && K <= 20 * 4 * kQThreads) {
+        const int nv = (int)((K / 4 + kQThreads - 1) / kQThreads);
+#define MNNQ_ROWS(NV)                                                                                          \
+    if (nv <= NV) {                                                                                            \
+        hipLaunchKernelGGL(quant_act_rows_kernel<NV>, dim3((unsigned)M), dim3(kQThreads), 0, st, x, K, xq, sx, \
+                           xsum);                                                                              \
+        MNNQ_HIP_TRY(hipGetLastError());                                                                       \
+        return MNNQ_OK;                                                                                        \
+    }
+        MNNQ_ROWS(2) MNNQ_ROWS(4) MNNQ_ROWS(8) MNNQ_ROWS(12) MNNQ_ROWS(20)
+#undef MNNQ_ROWS
     }
     hipLaunchKernelGGL(quant_act_kernel, dim3((unsigned)M, slices), dim3(kQThreads), 0, st, x, K, xq, sx, xsum);
     MNNQ_HIP_TRY(hipGetLastError());

@@ -75,7 +75,8 @@ def test_pack_is_deterministic_and_concatenation_holds():
 
 
 @pytest.mark.parametrize("M,K,outliers", [(1, 1536, False), (1, 64, True), (5, 192, True), (40, 3584, True),
-                                          (3, 18944, True), (257, 1536, True)])
+                                          (3, 18944, True), (257, 1536, True), (33, 64, True), (20, 18944, True),
+                                          (17, 20480, False), (18, 20544, True), (19, 8960, True)])
 def test_quant_act_bit_exact(M, K, outliers):
     note("quant_act", M, K)
     x = synth.activations(M, K, 200 + M + K, outliers=outliers)
