@@ -132,6 +132,17 @@ int mnnq_linear_prefill_f16(const void *packed, int64_t M, int64_t N, int64_t K,
                             const uint16_t *x16, const float *row_scale, const float *bias, float *y,
                             void *workspace, size_t workspace_bytes, void *stream);
 
+/* Import of weights that were quantized elsewhere (Section 4.2: quantized
+ * weights, e.g. from GPTQ, can be imported): canonical arrays in, packed form
+ * out - the inverse of mnnq_unpack_weights.
+ * q: uint8 [N, K], one code per byte (taken modulo 16); scale: fp32 [N, K/group];
+ * zero: uint8 [N, K/group] (values above 15 are stored as 15); all row-major
+ * device pointers, q and packed 16-byte aligned.  The packed buffer then behaves
+ * exactly like one written by mnnq_pack_weights. */
+int mnnq_pack_from_quantized(const uint8_t *q, const float *scale, const uint8_t *zero,
+                             int64_t N, int64_t K, int group, int mode,
+                             void *packed, size_t packed_bytes, void *stream);
+
 /* Integer group accumulators of the W4A8 kernels, for bit-exact checks:
  *   acc[m, n, g] = sum_{k in g} xq[m,k] * (q[n,k] - zero[n,g])      (int32 [M, N, G]).
  * use_prefill_kernel = 0 runs the decode kernel's inner loop row by row (any M),

@@ -23,6 +23,7 @@ EXPORTS = (
     "mnnq_pack_weights", "mnnq_unpack_weights", "mnnq_quant_act", "mnnq_linear_decode",
     "mnnq_linear_decode_fused",
     "mnnq_linear_prefill", "mnnq_linear_decode_f16", "mnnq_linear_prefill_f16", "mnnq_linear_acc_debug",
+    "mnnq_pack_from_quantized",
 )
 
 
@@ -62,6 +63,7 @@ def lib() -> ctypes.CDLL:
         L.mnnq_linear_decode_f16.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
         L.mnnq_linear_prefill_f16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.mnnq_linear_acc_debug.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, i32, vp]
+        L.mnnq_pack_from_quantized.argtypes = [vp, vp, vp, i64, i64, i32, i32, vp, sz, vp]
         for name in EXPORTS[5:]:
             getattr(L, name).restype = i32
         _lib = L
@@ -196,6 +198,21 @@ def mnnq_linear_prefill_f16(packed, N: int, K: int, x16, bias=None, out=None, ro
     _check(lib().mnnq_linear_prefill_f16(_ptr(packed), M, N, K, GROUP, MODE_W4_ZP_INT, _ptr(x16), _ptr(row_scale),
                                          _ptr(bias), _ptr(y), None, 0, _stream()), "mnnq_linear_prefill_f16")
     return y
+
+
+def mnnq_pack_from_quantized(q, scale, zero, out=None):
+    """q u8 [N,K], scale f32 [N,G], zero u8 [N,G] on the GPU -> packed uint8 buffer."""
+    _dev(q, torch.uint8, "q"); _dev(scale, torch.float32, "scale"); _dev(zero, torch.uint8, "zero")
+    N, K = q.shape
+    if tuple(scale.shape) != (N, K // GROUP) or tuple(zero.shape) != (N, K // GROUP):
+        raise ValueError("scale and zero must be [N, K/%d]" % GROUP)
+    nbytes = mnnq_packed_size(N, K)
+    if nbytes == 0:
+        raise ValueError("unsupported shape N=%d K=%d" % (N, K))
+    packed = torch.empty(nbytes, dtype=torch.uint8, device=q.device) if out is None else out
+    _check(lib().mnnq_pack_from_quantized(_ptr(q), _ptr(scale), _ptr(zero), N, K, GROUP, MODE_W4_ZP_INT,
+                                          _ptr(packed), packed.numel(), _stream()), "mnnq_pack_from_quantized")
+    return packed
 
 
 def mnnq_linear_acc_debug(packed, N: int, K: int, xq, use_prefill_kernel: bool):

@@ -97,6 +97,18 @@ int mnnq_pack_weights(const float* W, int64_t N, int64_t K, int group, int mode,
     return launch_pack(W, L, static_cast<uint8_t*>(packed), static_cast<hipStream_t>(stream));
 }
 
+int mnnq_pack_from_quantized(const uint8_t* q, const float* scale, const uint8_t* zero, int64_t N, int64_t K,
+                             int group, int mode, void* packed, size_t packed_bytes, void* stream)
+{
+    if (!q || !scale || !zero || !packed) return MNNQ_ERR_NULL;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    if (misaligned(q) || misaligned(packed)) return MNNQ_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(scale) & 3u) return MNNQ_ERR_ALIGN;
+    const Layout L = make_layout(N, K);
+    if (packed_bytes < L.total()) return MNNQ_ERR_SIZE;
+    return launch_repack(q, scale, zero, L, static_cast<uint8_t*>(packed), static_cast<hipStream_t>(stream));
+}
+
 int mnnq_unpack_weights(const void* packed, int64_t N, int64_t K, int group, int mode, uint8_t* q,
                         float* scale, uint8_t* zero, void* stream)
 {

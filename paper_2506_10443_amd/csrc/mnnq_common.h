@@ -72,6 +72,8 @@ int record_hip_error(hipError_t e);
 
 // Kernel launchers (one translation unit each).  All return a status.
 int launch_pack(const float* W, const Layout& L, uint8_t* packed, hipStream_t st);
+int launch_repack(const uint8_t* q, const float* scale, const uint8_t* zero, const Layout& L, uint8_t* packed,
+                  hipStream_t st);
 int launch_unpack(const uint8_t* packed, const Layout& L, uint8_t* q, float* scale, uint8_t* zero,
                   hipStream_t st);
 int launch_quant_act(const float* x, int64_t M, int64_t K, int8_t* xq, float* sx, int32_t* xsum,

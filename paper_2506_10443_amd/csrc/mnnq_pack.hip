@@ -1,6 +1,7 @@
 // Load-time step: quantize fp32 weights to asymmetric int4 (Section 4.2, Eq. 1,
 // integer zero point, groups of 64 along K) and store them in the chunk layout
-// described in mnnq_common.h; plus the inverse view used by tests and export.
+// described in mnnq_common.h; plus the inverse view used by tests and export,
+// and the import of already quantized weights into the same layout.
 //
 // This file is compiled with -ffp-contract=off: the quantizer is a fixed
 // sequence of IEEE binary32 operations (subtract, divide, round-to-nearest-even,
@@ -111,7 +112,58 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t* __restrict__
     }
 }
 
+// Import of weights that are already quantized (Section 4.2: quantized weights,
+// e.g. from GPTQ, can be imported): canonical arrays -> chunk layout, the exact
+// inverse of unpack_kernel.  One thread per (row, group, k-block).  Codes are
+// taken modulo 16, zero points above 15 are stored as 15.
+__global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__ q, const float* __restrict__ scale,
+                                                     const uint8_t* __restrict__ zero, Layout L,
+                                                     uint8_t* __restrict__ packed)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t total = L.N * L.G * 4;
+    if (idx >= total) return;
+    const int kb = (int)(idx % 4);
+    const int64_t g = (idx / 4) % L.G;
+    const int64_t n = idx / (4 * L.G);
+    const int64_t t = n / kTileN;
+    const int r = (int)(n % kTileN);
+    const int64_t chunk = t * L.C + g / 2;
+    const int half = (int)(g & 1);
+
+    const uint4 o = *reinterpret_cast<const uint4*>(q + n * L.K + g * kGroup + 16 * kb);
+    uint2 w;
+    w.x = (o.x & 0x0f0f0f0fu) | ((o.y & 0x0f0f0f0fu) << 4);
+    w.y = (o.z & 0x0f0f0f0fu) | ((o.w & 0x0f0f0f0fu) << 4);
+    uint2* slot = reinterpret_cast<uint2*>(packed + chunk * kChunkBytes + (16 * kb + r) * 16);
+    slot[half] = w;
+    float* sc = reinterpret_cast<float*>(packed + L.scales_off()) + (chunk * 16 + r) * 2;
+    uint8_t* zp = packed + L.zeros_off() + (chunk * 16 + r) * 2;
+    if (kb == 0) {
+        const uint8_t z = zero[n * L.G + g];
+        sc[half] = scale[n * L.G + g];
+        zp[half] = z > 15 ? (uint8_t)15 : z;
+    }
+    if ((L.G & 1) && g == L.G - 1) {   // padding group of an odd G
+        slot[1] = make_uint2(0u, 0u);
+        if (kb == 0) {
+            sc[1] = 0.0f;
+            zp[1] = 0;
+        }
+    }
+}
+
 }  // namespace
+
+int launch_repack(const uint8_t* q, const float* scale, const uint8_t* zero, const Layout& L, uint8_t* packed,
+                  hipStream_t st)
+{
+    const int64_t total = L.N * L.G * 4;
+    const int64_t blocks = (total + 255) / 256;
+    hipLaunchKernelGGL(repack_kernel, dim3((unsigned)blocks), dim3(256), 0, st, q, scale, zero, L, packed);
+    MNNQ_HIP_TRY(hipGetLastError());
+    return MNNQ_OK;
+}
 
 int launch_pack(const float* W, const Layout& L, uint8_t* packed, hipStream_t st)
 {

@@ -114,6 +114,13 @@ def test_argument_validation_precedes_hip(L):
     assert L.mnnq_linear_prefill_f16(FAKE, -1, 16, 128, 64, 0, FAKE, None, None, FAKE, None, 0, None) == SHAPE
     assert L.mnnq_linear_acc_debug(FAKE, 1, 16, 128, 64, 0, FAKE, None, 0, None) == NULL
     assert L.mnnq_linear_acc_debug(FAKE, 70000, 16, 128, 64, 0, FAKE, FAKE, 0, None) == UNSUP
+    pq = L.mnnq_pack_from_quantized
+    assert pq(None, FAKE, FAKE, 16, 128, 64, 0, FAKE, 10**9, None) == NULL
+    assert pq(FAKE, FAKE, None, 16, 128, 64, 0, FAKE, 10**9, None) == NULL
+    assert pq(FAKE, FAKE, FAKE, 16, 96, 64, 0, FAKE, 10**9, None) == SHAPE
+    assert pq(FAKE, FAKE, FAKE, 16, 128, 64, 1, FAKE, 10**9, None) == UNSUP
+    assert pq(ODD, FAKE, FAKE, 16, 128, 64, 0, FAKE, 10**9, None) == ALIGN
+    assert pq(FAKE, FAKE, FAKE, 16, 128, 64, 0, FAKE, binding.mnnq_packed_size(16, 128) - 1, None) == SIZE
     assert L.mnnq_unpack_weights(None, 16, 128, 64, 0, FAKE, FAKE, FAKE, None) == NULL
     assert L.mnnq_unpack_weights(FAKE, 16, 128, 64, 0, None, None, None, None) == OK  # nothing asked for
     assert L.mnnq_last_hip_error() == 0

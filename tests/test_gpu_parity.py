@@ -74,6 +74,42 @@ def test_pack_is_deterministic_and_concatenation_holds():
     assert torch.equal(zc, torch.cat([za, zb]))
 
 
+@pytest.mark.parametrize("N,K", [(16, 64), (48, 192), (272, 1536), (1024, 4096)])
+def test_pack_from_quantized_is_the_inverse_of_unpack(N, K):
+    # Import of weights quantized elsewhere (here: by the oracle on the CPU): the packed buffer
+    # must be byte-identical to the one the GPU quantizer writes, and unpack must return the inputs.
+    note("pack_from_quantized", N, K)
+    W = synth.weights(N, K, 600 + N + K)
+    q, s, z = oracle.quant_weights(W)
+    packed_ref = B.mnnq_pack_weights(dev(W))
+    packed = B.mnnq_pack_from_quantized(dev(q), dev(s), dev(z))
+    assert torch.equal(packed, packed_ref)
+    q2, s2, z2 = B.mnnq_unpack_weights(packed, N, K)
+    assert np.array_equal(host(q2), q) and np.array_equal(host(z2), z)
+    assert np.array_equal(host(s2).view(np.uint32), s.view(np.uint32))
+    # arbitrary codes / scales / zero points (nothing ties them to a float matrix)
+    rng = np.random.default_rng(N * K)
+    qr = rng.integers(0, 16, (N, K), dtype=np.uint8)
+    sr = rng.uniform(1e-4, 1e-1, (N, K // 64)).astype(np.float32)
+    zr = rng.integers(0, 16, (N, K // 64), dtype=np.uint8)
+    pr = B.mnnq_pack_from_quantized(dev(qr), dev(sr), dev(zr))
+    q3, s3, z3 = B.mnnq_unpack_weights(pr, N, K)
+    assert np.array_equal(host(q3), qr) and np.array_equal(host(z3), zr)
+    assert np.array_equal(host(s3).view(np.uint32), sr.view(np.uint32))
+    # ... and the linear layer on them matches the oracle on the same arrays
+    x = synth.activations(3, K, 601)
+    xq, sx, _ = oracle.quant_act(x)
+    acc_o, y_o = oracle.linear_w4a8(xq, sx, qr, sr, zr)
+    assert np.array_equal(host(B.mnnq_linear_acc_debug(pr, N, K, dev(xq), True)), acc_o)
+    y = host(B.mnnq_linear_prefill(pr, N, K, dev(xq), dev(sx)))
+    assert np.abs(y - y_o).max() <= TOL_A8 * np.abs(y_o).max()
+    y0 = host(B.mnnq_linear_decode(pr, N, K, dev(xq[0]), dev(sx[:1])))
+    assert np.abs(y0 - y_o[0]).max() <= TOL_A8 * np.abs(y_o).max()
+    # out-of-range inputs: codes are taken modulo 16, zero points saturate at 15
+    pm = B.mnnq_pack_from_quantized(dev(qr | 0xa0), dev(sr), dev(np.where(zr == 15, 200, zr).astype(np.uint8)))
+    assert torch.equal(pm, pr)
+
+
 @pytest.mark.parametrize("M,K,outliers", [(1, 1536, False), (1, 64, True), (5, 192, True), (40, 3584, True),
                                           (3, 18944, True), (257, 1536, True), (33, 64, True), (20, 18944, True),
                                           (17, 20480, False), (18, 20544, True), (19, 8960, True)])
