@@ -42,7 +42,9 @@ def _load():
         if _lib is None:
             _lib = ctypes.CDLL(build())
             for name in ("orc_quant_weights", "orc_dequant", "orc_quant_act", "orc_linear_w4a8",
-                         "orc_linear_w4a16", "orc_linear_w4a8_sampled", "orc_linear_w4a16_sampled"):
+                         "orc_linear_w4a16", "orc_linear_w4a8_sampled", "orc_linear_w4a16_sampled",
+                         "orc_quant_weights_minf", "orc_dequant_minf", "orc_linear_w4a8_minf",
+                         "orc_linear_w4a8_minf_sampled"):
                 getattr(_lib, name).restype = None
             _lib.orc_omp_enabled.restype = ctypes.c_int
     return _lib
@@ -169,3 +171,62 @@ def linear_w4a16_sampled(x16, q, s, z, ms, ns, bias=None):
 
 def omp_enabled() -> bool:
     return bool(_load().orc_omp_enabled())
+
+
+# ---- Eq. 1 taken literally: the group minimum stays a float offset (O6..O8)
+
+def quant_weights_minf(W):
+    """O6.  W fp32 [N,K] -> (q u8 [N,K], step f32 [N,G], wmin f32 [N,G])."""
+    W = _c(W, np.float32)
+    N, K = W.shape
+    assert K % GROUP == 0
+    G = K // GROUP
+    q = np.empty((N, K), np.uint8)
+    s = np.empty((N, G), np.float32)
+    mn = np.empty((N, G), np.float32)
+    _load().orc_quant_weights_minf(_p(W), _i64(N), _i64(K), _p(q), _p(s), _p(mn))
+    return q, s, mn
+
+
+def dequant_minf(q, s, wmin):
+    """O7.  fp32 [N,K] of q * step + wmin (binary64, rounded once)."""
+    q = _c(q, np.uint8); s = _c(s, np.float32); wmin = _c(wmin, np.float32)
+    N, K = q.shape
+    out = np.empty((N, K), np.float32)
+    _load().orc_dequant_minf(_p(q), _p(s), _p(wmin), _i64(N), _i64(K), _p(out))
+    return out
+
+
+def linear_w4a8_minf(xq, sx, q, s, wmin, bias=None, want_acc=True):
+    """O8.  Returns (A int32 [M,N,G] or None, y fp32 [M,N])."""
+    xq = _c(xq, np.int8); sx = _c(sx, np.float32)
+    q = _c(q, np.uint8); s = _c(s, np.float32); wmin = _c(wmin, np.float32)
+    if bias is not None:
+        bias = _c(bias, np.float32)
+    M, K = xq.shape
+    N = q.shape[0]
+    assert q.shape[1] == K and K % GROUP == 0
+    G = K // GROUP
+    acc = np.empty((M, N, G), np.int32) if want_acc else None
+    y = np.empty((M, N), np.float32)
+    _load().orc_linear_w4a8_minf(_p(xq), _p(sx), _p(q), _p(s), _p(wmin), _p(bias),
+                                 _i64(M), _i64(N), _i64(K), _p(acc), _p(y))
+    return acc, y
+
+
+def linear_w4a8_minf_sampled(xq, sx, q, s, wmin, ms, ns, bias=None, want_acc=True):
+    """O8 on the listed (m, n) pairs only: (A [count,G] or None, y [count])."""
+    xq = _c(xq, np.int8); sx = _c(sx, np.float32)
+    q = _c(q, np.uint8); s = _c(s, np.float32); wmin = _c(wmin, np.float32)
+    ms = _c(ms, np.int64); ns = _c(ns, np.int64)
+    if bias is not None:
+        bias = _c(bias, np.float32)
+    M, K = xq.shape
+    N = q.shape[0]
+    G = K // GROUP
+    cnt = ms.shape[0]
+    acc = np.empty((cnt, G), np.int32) if want_acc else None
+    y = np.empty((cnt,), np.float32)
+    _load().orc_linear_w4a8_minf_sampled(_p(xq), _p(sx), _p(q), _p(s), _p(wmin), _p(bias),
+                                         _i64(M), _i64(N), _i64(K), _p(ms), _p(ns), _i64(cnt), _p(acc), _p(y))
+    return acc, y

@@ -10,7 +10,9 @@
  *   - Weight codes: the asymmetric quantizer of Section 4.2, Eq. 1 (step =
  *     (w_max - w_min) / (clip_max - clip_min), clip range 0..15 for int4), in
  *     the integer-zero-point form the benchmark configurations name:
- *     group of 64 along K, scale = (max - min)/15, zero = round(-min/scale).
+ *     group of 64 along K, scale = (max - min)/15, zero = round(-min/scale);
+ *     and, second, exactly as Eq. 1 is printed, with the group minimum kept as
+ *     a float offset (O6..O8 below).
  *   - Activation codes: Section 4.2 says activations are quantized to int8 at
  *     run time; the configurations fix per-token symmetric, scale = max|x|/127.
  *   - Linear: Section 5.1 notation, activations [e, l] x weights [h, l] ->
@@ -235,6 +237,124 @@ void orc_linear_w4a16_sampled(const uint16_t *x16,
         }
         if (bias) sum += (double)bias[n];
         y[i] = (float)sum;
+    }
+}
+
+/* ---- Eq. 1 taken literally: the group minimum stays a float offset --------
+ *
+ * Section 4.2, Eq. 1 with clip_min = 0, clip_max = 15:
+ *     q = round((w - w_min) / step),  step = (w_max - w_min) / 15,
+ * and the weight it stands for is w^ = q * step + w_min.  There is no integer
+ * zero point: the stored parameters of a group are (step, w_min). */
+
+/* O6: weight quantizer, float-minimum form.
+ * W [N,K] -> q [N,K] (0..15), s [N,G] (step), wmin [N,G].  A constant group has
+ * step 1 and all codes 0, so that w^ = w_min is exact. */
+void orc_quant_weights_minf(const float *W, int64_t N, int64_t K,
+                            uint8_t *q, float *s, float *wmin)
+{
+    const int64_t G = K / ORC_GROUP;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t g = 0; g < G; ++g) {
+            const float *w = W + n * K + g * ORC_GROUP;
+            uint8_t *qo = q + n * K + g * ORC_GROUP;
+            float mn = w[0], mx = w[0];
+            for (int k = 1; k < ORC_GROUP; ++k) {
+                if (w[k] < mn) mn = w[k];
+                if (w[k] > mx) mx = w[k];
+            }
+            wmin[n * G + g] = mn;
+            if (mx == mn) {
+                s[n * G + g] = 1.0f;
+                for (int k = 0; k < ORC_GROUP; ++k) qo[k] = 0;
+                continue;
+            }
+            const float step = (mx - mn) / 15.0f;
+            s[n * G + g] = step;
+            for (int k = 0; k < ORC_GROUP; ++k) {
+                float c = rintf((w[k] - mn) / step);
+                if (c < 0.0f) c = 0.0f;
+                if (c > 15.0f) c = 15.0f;
+                qo[k] = (uint8_t)c;
+            }
+        }
+    }
+}
+
+/* O7: the weight a code stands for, w^ = q * step + w_min, evaluated in binary64
+ * (the product is exact there) and rounded to binary32 once. */
+void orc_dequant_minf(const uint8_t *q, const float *s, const float *wmin,
+                      int64_t N, int64_t K, float *What)
+{
+    const int64_t G = K / ORC_GROUP;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            const int64_t g = k / ORC_GROUP;
+            What[n * K + k] = (float)((double)q[n * K + k] * (double)s[n * G + g] + (double)wmin[n * G + g]);
+        }
+}
+
+/* O8: W4A8 linear on float-minimum weights.
+ *   A[m,n,g]  = sum_{k in g} xq[m,k] * q[n,k]           (int32, exact)
+ *   xs[m,g]   = sum_{k in g} xq[m,k]                    (int32, exact)
+ *   y[m,n]    = sx[m] * sum_g (s[n,g] * A[m,n,g] + wmin[n,g] * xs[m,g]) (+ bias[n])
+ * which is sum_k (sx xq)[m,k] * w^[n,k] with w^ = q s + wmin.  binary64, rounded once. */
+void orc_linear_w4a8_minf(const int8_t *xq, const float *sx,
+                          const uint8_t *q, const float *s, const float *wmin,
+                          const float *bias, int64_t M, int64_t N, int64_t K,
+                          int32_t *acc, float *y)
+{
+    const int64_t G = K / ORC_GROUP;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t m = 0; m < M; ++m) {
+            double sum = 0.0;
+            for (int64_t g = 0; g < G; ++g) {
+                const int8_t *a = xq + m * K + g * ORC_GROUP;
+                const uint8_t *b = q + n * K + g * ORC_GROUP;
+                int32_t A = 0, xs = 0;
+                for (int k = 0; k < ORC_GROUP; ++k) {
+                    A += (int32_t)a[k] * (int32_t)b[k];
+                    xs += (int32_t)a[k];
+                }
+                if (acc) acc[(m * N + n) * G + g] = A;
+                sum += (double)s[n * G + g] * (double)A + (double)wmin[n * G + g] * (double)xs;
+            }
+            double r = (double)sx[m] * sum;
+            if (bias) r += (double)bias[n];
+            if (y) y[m * N + n] = (float)r;
+        }
+    }
+}
+
+/* Sampled (m,n) pairs of O8. */
+void orc_linear_w4a8_minf_sampled(const int8_t *xq, const float *sx,
+                                  const uint8_t *q, const float *s, const float *wmin,
+                                  const float *bias, int64_t M, int64_t N, int64_t K,
+                                  const int64_t *ms, const int64_t *ns, int64_t count,
+                                  int32_t *acc /* [count,G] or NULL */, float *y /* [count] */)
+{
+    const int64_t G = K / ORC_GROUP;
+    (void)M; (void)N;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < count; ++i) {
+        const int64_t m = ms[i], n = ns[i];
+        double sum = 0.0;
+        for (int64_t g = 0; g < G; ++g) {
+            int32_t A = 0, xs = 0;
+            for (int k = 0; k < ORC_GROUP; ++k) {
+                const int32_t a = xq[m * K + g * ORC_GROUP + k];
+                A += a * (int32_t)q[n * K + g * ORC_GROUP + k];
+                xs += a;
+            }
+            if (acc) acc[i * G + g] = A;
+            sum += (double)s[n * G + g] * (double)A + (double)wmin[n * G + g] * (double)xs;
+        }
+        double r = (double)sx[m] * sum;
+        if (bias) r += (double)bias[n];
+        y[i] = (float)r;
     }
 }
 
