@@ -35,10 +35,13 @@ PREFILL_TRAFFIC_BYTES = 169.9e6   # profiles/bench_qwen2-7b_hbm_traffic.txt
 DECODE_TRAFFIC_BYTES = 33.8e6     # same file
 
 
+GROUP_PARAM_BYTES = 5    # fp32 scale + 1-byte zero point; 8 with an fp32 group minimum (--weight-mode minfloat)
+
+
 def decode_bytes(N, K):
-    """Algorithmic bytes of one decode GEMV: codes + fp32 scale + 1-byte zero
-    per group, the int8 activation row, and the fp32 output."""
-    return N * K // 2 + 5 * N * (K // G) + K + 4 * N
+    """Algorithmic bytes of one decode GEMV: codes + per-group parameters, the int8
+    activation row, and the fp32 output."""
+    return N * K // 2 + GROUP_PARAM_BYTES * N * (K // G) + K + 4 * N
 
 
 def prefill_ops(M, N, K):
@@ -57,6 +60,9 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy, as the known-size reference for rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--weight-mode", default="zp", choices=["zp", "minfloat"],
+                    help="weight quantizer: integer zero point (the benchmark configuration) or Eq. 1 as "
+                         "printed, with the group minimum as a float offset")
     ap.add_argument("--two-call-decode", action="store_true",
                     help="decode pass calls mnnq_quant_act + mnnq_linear_decode per layer instead of "
                          "mnnq_linear_decode_fused (fp32 row in, quantizer inside the call)")
@@ -78,6 +84,9 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     B.lib()  # fail loudly if the HIP library is not built
+    wmode = B.MODE_W4_MIN_FLOAT if args.weight_mode == "minfloat" else B.MODE_W4_ZP_INT
+    global GROUP_PARAM_BYTES
+    GROUP_PARAM_BYTES = 8 if args.weight_mode == "minfloat" else 5
 
     spec = synth.MODELS[args.model]
     n_blocks = spec["blocks"]
@@ -97,7 +106,7 @@ def main() -> int:
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(n_blocks):
-            packed[name].append(B.mnnq_pack_weights(W))
+            packed[name].append(B.mnnq_pack_weights(W, mode=wmode))
         e1.record()
         torch.cuda.synchronize()
         pack_ms += e0.elapsed_time(e1)
@@ -107,7 +116,7 @@ def main() -> int:
     if spec["lm_head"] is not None:
         N, K = spec["lm_head"]
         W = torch.from_numpy(synth.weights(N, K, synth.layer_seed(args.model, 0, "lm_head"))).to(dev)
-        lm = (B.mnnq_pack_weights(W), N, K)
+        lm = (B.mnnq_pack_weights(W, mode=wmode), N, K)
         del W
     torch.cuda.synchronize()
     setup_s = time.time() - t0
@@ -138,10 +147,10 @@ def main() -> int:
     def decode_layer(p, N, K, io, fused=None):
         x, xq, sx, y = io
         if args.fused_decode if fused is None else fused:
-            B.mnnq_linear_decode_fused(p, N, K, x, out=y, workspace=ws_dec)
+            B.mnnq_linear_decode_fused(p, N, K, x, out=y, workspace=ws_dec, mode=wmode)
         else:
             B.mnnq_quant_act(x, want_xsum=False, out=(xq, sx, None))
-            B.mnnq_linear_decode(p, N, K, xq, sx, out=y)
+            B.mnnq_linear_decode(p, N, K, xq, sx, out=y, mode=wmode)
 
     def decode_pass(fused=None):
         for b in range(n_blocks):
@@ -155,7 +164,7 @@ def main() -> int:
             for name, N, K in layers:
                 x, xq, sx, y = io_pre[name]
                 B.mnnq_quant_act(x, want_xsum=False, out=(xq, sx, None))
-                B.mnnq_linear_prefill(packed[name][b], N, K, xq, sx, out=y)
+                B.mnnq_linear_prefill(packed[name][b], N, K, xq, sx, out=y, mode=wmode)
 
     do_dec = args.phase in ("both", "decode")
     do_pre = args.phase in ("both", "prefill")
@@ -243,7 +252,7 @@ def main() -> int:
         for name, N, K in layers:
             x, xq, sx, y = io_pre[name]
             lay = [(lambda p=packed[name][b], N=N, K=K, xq=xq, sx=sx, y=y:
-                    B.mnnq_linear_prefill(p, N, K, xq, sx, out=y)) for b in range(n_blocks)]
+                    B.mnnq_linear_prefill(p, N, K, xq, sx, out=y, mode=wmode)) for b in range(n_blocks)]
             t = time_launches(lay, 2)
             per_layer["prefill_" + name] = {"us": round(t * 1e3, 2),
                                             "tops": round(prefill_ops(M_pre, N, K) / (t * 1e-3) / 1e12, 1)}
@@ -253,14 +262,14 @@ def main() -> int:
         ach = ops / len(fns) / (t * 1e-3) / 1e12
         roof_pre = {"kernel": "prefill_kernel (W4A8 int8 MFMA GEMM), all %d launches of a pass" % len(fns),
                     "bound": "mfma", "achieved": round(ach, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                    "frac": round(ach / INT8_PEAK_TOPS, 4), "traffic": PREFILL_TRAFFIC_BYTES if args.model == "qwen2-7b" else None,
+                    "frac": round(ach / INT8_PEAK_TOPS, 4), "traffic": PREFILL_TRAFFIC_BYTES if (args.model, args.weight_mode) == ("qwen2-7b", "zp") else None,
                     "algorithmic_ops_per_launch": ops // len(fns), "avg_launch_us": round(t * 1e3, 2)}
     if do_dec:
         fns, byt = [], 0
         for name, N, K in layers:
             x, xq, sx, y = io_dec[name]
             lay = [(lambda p=packed[name][b], N=N, K=K, xq=xq, sx=sx, y=y:
-                    B.mnnq_linear_decode(p, N, K, xq, sx, out=y)) for b in range(n_blocks)]
+                    B.mnnq_linear_decode(p, N, K, xq, sx, out=y, mode=wmode)) for b in range(n_blocks)]
             t = time_launches(lay, 4)
             per_layer["decode_" + name] = {"us": round(t * 1e3, 2),
                                            "gbs": round(decode_bytes(N, K) / (t * 1e-3) / 1e9, 1)}
@@ -270,11 +279,11 @@ def main() -> int:
         ach = byt / len(fns) / (t * 1e-3) / 1e9
         roof_dec = {"kernel": "decode_kernel (W4A8 GEMV), all %d block launches of a pass" % len(fns),
                     "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": DECODE_TRAFFIC_BYTES if args.model == "qwen2-7b" else None,
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": DECODE_TRAFFIC_BYTES if (args.model, args.weight_mode) == ("qwen2-7b", "zp") else None,
                     "algorithmic_bytes_per_launch": byt // len(fns), "avg_launch_us": round(t * 1e3, 2)}
         if lm is not None:
             x, xq, sx, y = io_dec["lm_head"]
-            t = time_launches([lambda: B.mnnq_linear_decode(lm[0], lm[1], lm[2], xq, sx, out=y)] * 4, 4)
+            t = time_launches([lambda: B.mnnq_linear_decode(lm[0], lm[1], lm[2], xq, sx, out=y, mode=wmode)] * 4, 4)
             per_layer["decode_lm_head"] = {"us": round(t * 1e3, 2),
                                            "gbs": round(decode_bytes(lm[1], lm[2]) / (t * 1e-3) / 1e9, 1)}
 
@@ -350,7 +359,7 @@ def main() -> int:
                                "q|k|v and gate|up concatenated along N" %
                                (args.model, n_blocks, " + lm_head" if lm else "", M_pre, n_blocks),
                    "group": 64, "graph": not args.no_graph, "phase": args.phase,
-                   "fused_decode_quant": bool(args.fused_decode)},
+                   "fused_decode_quant": bool(args.fused_decode), "weight_mode": args.weight_mode},
         "decode_ms": round(dec_mean, 4) if do_dec else None,
         "decode_gbs": round(dec_gbs, 1) if do_dec else None,
         "decode_frac_of_hbm_peak": round(dec_gbs / HBM_PEAK_GBS, 4) if do_dec else None,

@@ -17,8 +17,9 @@
  *   - Return value: MNNQ_OK (0) or a negative mnnq_status.  All argument
  *     checks run before the first HIP call, so they also work on a machine
  *     without a GPU.  NaN / Inf in W or x: undefined result, no error.
- *   - Only group == 64 and mode == MNNQ_W4_ZP_INT are implemented.  K must be
- *     a multiple of 64 and N a multiple of 16.
+ *   - Only group == 64 is implemented.  K must be a multiple of 64 and N a
+ *     multiple of 16.  `mode` selects the weight quantizer (mnnq_mode); a packed
+ *     buffer must be used with the mode it was written with.
  */
 #ifndef MNNQ_H
 #define MNNQ_H
@@ -45,7 +46,16 @@ typedef enum {
      * scale = (max - min) / 15, zero = round(-min / scale),
      * q = clamp(round(w / scale) + zero, 0, 15), w^ = (q - zero) * scale.
      * This is Eq. 1 of Section 4.2 with the offset rounded to the code grid. */
-    MNNQ_W4_ZP_INT = 0
+    MNNQ_W4_ZP_INT = 0,
+    /* Eq. 1 of Section 4.2 exactly as printed: the group minimum stays a float
+     * offset.  step = (max - min) / 15, q = clamp(round((w - min) / step), 0, 15),
+     * w^ = q * step + min (a constant group: step 1, codes 0).  Stored per
+     * (row, group): fp32 step and fp32 min (3 bytes more than a zero point).
+     *   y[m,n] = sx[m] * sum_g (step[n,g] * A[m,n,g] + min[n,g] * xs[m,g]) (+ bias[n]),
+     *   A = sum_{k in g} xq[m,k] * q[n,k],  xs[m,g] = sum_{k in g} xq[m,k].
+     * Supported by the pack / unpack / import calls and the W4A8 linear calls;
+     * the fp16-activation calls return MNNQ_ERR_UNSUPPORTED for it. */
+    MNNQ_W4_MIN_FLOAT = 1
 } mnnq_mode;
 
 /* Text for a status code (static storage). */
@@ -80,9 +90,11 @@ int mnnq_pack_weights(const float *W, int64_t N, int64_t K, int group, int mode,
                       void *packed, size_t packed_bytes, void *stream);
 
 /* Canonical view of a packed matrix (for tests and export): q [N, K] one code
- * per byte, scale [N, G] fp32, zero [N, G] u8.  Any output may be NULL. */
+ * per byte, scale [N, G] fp32, zero [N, G]: uint8 zero points in mode
+ * MNNQ_W4_ZP_INT, fp32 group minima in mode MNNQ_W4_MIN_FLOAT.  Any output may
+ * be NULL. */
 int mnnq_unpack_weights(const void *packed, int64_t N, int64_t K, int group, int mode,
-                        uint8_t *q, float *scale, uint8_t *zero, void *stream);
+                        uint8_t *q, float *scale, void *zero, void *stream);
 
 /* Run-time activation quantizer (Section 4.2: activations are quantized to
  * int8 during calculation), per token, symmetric: sx[m] = max_k |x[m,k]| / 127,
@@ -136,15 +148,17 @@ int mnnq_linear_prefill_f16(const void *packed, int64_t M, int64_t N, int64_t K,
  * weights, e.g. from GPTQ, can be imported): canonical arrays in, packed form
  * out - the inverse of mnnq_unpack_weights.
  * q: uint8 [N, K], one code per byte (taken modulo 16); scale: fp32 [N, K/group];
- * zero: uint8 [N, K/group] (values above 15 are stored as 15); all row-major
- * device pointers, q and packed 16-byte aligned.  The packed buffer then behaves
+ * zero: [N, K/group], uint8 zero points (values above 15 are stored as 15) in
+ * mode MNNQ_W4_ZP_INT, fp32 group minima in mode MNNQ_W4_MIN_FLOAT; all
+ * row-major device pointers, q and packed 16-byte aligned.  The packed buffer then behaves
  * exactly like one written by mnnq_pack_weights. */
-int mnnq_pack_from_quantized(const uint8_t *q, const float *scale, const uint8_t *zero,
+int mnnq_pack_from_quantized(const uint8_t *q, const float *scale, const void *zero,
                              int64_t N, int64_t K, int group, int mode,
                              void *packed, size_t packed_bytes, void *stream);
 
 /* Integer group accumulators of the W4A8 kernels, for bit-exact checks:
- *   acc[m, n, g] = sum_{k in g} xq[m,k] * (q[n,k] - zero[n,g])      (int32 [M, N, G]).
+ *   acc[m, n, g] = sum_{k in g} xq[m,k] * (q[n,k] - zero[n,g])      (int32 [M, N, G]);
+ * in mode MNNQ_W4_MIN_FLOAT there is no zero point: acc = sum_{k in g} xq[m,k] * q[n,k].
  * use_prefill_kernel = 0 runs the decode kernel's inner loop row by row (any M),
  * 1 runs the prefill kernel's MFMA loop. */
 int mnnq_linear_acc_debug(const void *packed, int64_t M, int64_t N, int64_t K, int group, int mode,

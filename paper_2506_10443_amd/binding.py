@@ -13,7 +13,8 @@ import os
 import torch  # noqa: F401  (must be imported first: the library binds to the HIP runtime torch loaded)
 
 GROUP = 64
-MODE_W4_ZP_INT = 0
+MODE_W4_ZP_INT = 0      # integer zero point per (row, group)
+MODE_W4_MIN_FLOAT = 1   # Eq. 1 as printed: fp32 group minimum per (row, group)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "lib", "libmnnq.so")
@@ -97,29 +98,31 @@ def mnnq_workspace_size(M: int, N: int, K: int, group: int = GROUP, mode: int = 
     return int(lib().mnnq_workspace_size(M, N, K, group, mode))
 
 
-def mnnq_pack_weights(W: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+def mnnq_pack_weights(W: torch.Tensor, out: torch.Tensor | None = None, mode: int = MODE_W4_ZP_INT) -> torch.Tensor:
     """W fp32 [N, K] on the GPU -> packed uint8 buffer."""
     _dev(W, torch.float32, "W")
     N, K = W.shape
-    size = mnnq_packed_size(N, K)
+    size = mnnq_packed_size(N, K, GROUP, mode)
     if size == 0:
-        _check(lib().mnnq_pack_weights(_ptr(W), N, K, GROUP, MODE_W4_ZP_INT, _ptr(W), 0, _stream()),
+        _check(lib().mnnq_pack_weights(_ptr(W), N, K, GROUP, mode, _ptr(W), 0, _stream()),
                "mnnq_pack_weights")
     if out is None:
         out = torch.empty(size, dtype=torch.uint8, device=W.device)
-    _check(lib().mnnq_pack_weights(_ptr(W), N, K, GROUP, MODE_W4_ZP_INT, _ptr(out), out.numel(), _stream()),
+    _check(lib().mnnq_pack_weights(_ptr(W), N, K, GROUP, mode, _ptr(out), out.numel(), _stream()),
            "mnnq_pack_weights")
     return out
 
 
-def mnnq_unpack_weights(packed: torch.Tensor, N: int, K: int):
-    """Canonical view: (q u8 [N,K], scale f32 [N,G], zero u8 [N,G])."""
+def mnnq_unpack_weights(packed: torch.Tensor, N: int, K: int, mode: int = MODE_W4_ZP_INT):
+    """Canonical view: (q u8 [N,K], scale f32 [N,G], zero u8 [N,G]); in mode MODE_W4_MIN_FLOAT the
+    third array holds the fp32 group minima."""
     _dev(packed, torch.uint8, "packed")
     G = K // GROUP
     q = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
     s = torch.empty((N, G), dtype=torch.float32, device=packed.device)
-    z = torch.empty((N, G), dtype=torch.uint8, device=packed.device)
-    _check(lib().mnnq_unpack_weights(_ptr(packed), N, K, GROUP, MODE_W4_ZP_INT, _ptr(q), _ptr(s), _ptr(z),
+    z = torch.empty((N, G), dtype=torch.float32 if mode == MODE_W4_MIN_FLOAT else torch.uint8,
+                    device=packed.device)
+    _check(lib().mnnq_unpack_weights(_ptr(packed), N, K, GROUP, mode, _ptr(q), _ptr(s), _ptr(z),
                                      _stream()), "mnnq_unpack_weights")
     return q, s, z
 
@@ -139,18 +142,19 @@ def mnnq_quant_act(x: torch.Tensor, want_xsum: bool = True, out=None):
     return xq, sx, xsum
 
 
-def mnnq_linear_decode(packed, N: int, K: int, xq, sx, bias=None, out=None):
+def mnnq_linear_decode(packed, N: int, K: int, xq, sx, bias=None, out=None, mode: int = MODE_W4_ZP_INT):
     """One token: xq i8 [K] (or [1,K]), sx f32 [1] -> y f32 [N]."""
     _dev(packed, torch.uint8, "packed"); _dev(xq, torch.int8, "xq"); _dev(sx, torch.float32, "sx")
     if xq.numel() != K:
         raise ValueError("xq must hold K values")
     y = torch.empty((N,), dtype=torch.float32, device=packed.device) if out is None else out
-    _check(lib().mnnq_linear_decode(_ptr(packed), N, K, GROUP, MODE_W4_ZP_INT, _ptr(xq), _ptr(sx), _ptr(bias),
+    _check(lib().mnnq_linear_decode(_ptr(packed), N, K, GROUP, mode, _ptr(xq), _ptr(sx), _ptr(bias),
                                     _ptr(y), None, 0, _stream()), "mnnq_linear_decode")
     return y
 
 
-def mnnq_linear_decode_fused(packed, N: int, K: int, x, bias=None, out=None, workspace=None):
+def mnnq_linear_decode_fused(packed, N: int, K: int, x, bias=None, out=None, workspace=None,
+                             mode: int = MODE_W4_ZP_INT):
     """One token, activation quantizer fused in: x f32 [K] (or [1,K]) -> y f32 [N].
     workspace: optional uint8 tensor of mnnq_workspace_size(1, N, K) bytes."""
     _dev(packed, torch.uint8, "packed"); _dev(x, torch.float32, "x")
@@ -159,20 +163,20 @@ def mnnq_linear_decode_fused(packed, N: int, K: int, x, bias=None, out=None, wor
     y = torch.empty((N,), dtype=torch.float32, device=packed.device) if out is None else out
     if workspace is not None:
         _dev(workspace, torch.uint8, "workspace")
-    _check(lib().mnnq_linear_decode_fused(_ptr(packed), N, K, GROUP, MODE_W4_ZP_INT, _ptr(x), _ptr(bias),
+    _check(lib().mnnq_linear_decode_fused(_ptr(packed), N, K, GROUP, mode, _ptr(x), _ptr(bias),
                                           _ptr(y), _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                           _stream()), "mnnq_linear_decode_fused")
     return y
 
 
-def mnnq_linear_prefill(packed, N: int, K: int, xq, sx, bias=None, out=None):
+def mnnq_linear_prefill(packed, N: int, K: int, xq, sx, bias=None, out=None, mode: int = MODE_W4_ZP_INT):
     """M tokens: xq i8 [M,K], sx f32 [M] -> y f32 [M,N]."""
     _dev(packed, torch.uint8, "packed"); _dev(xq, torch.int8, "xq"); _dev(sx, torch.float32, "sx")
     M = xq.shape[0]
     if xq.shape[1] != K or sx.numel() != M:
         raise ValueError("xq must be [M,K] and sx [M]")
     y = torch.empty((M, N), dtype=torch.float32, device=packed.device) if out is None else out
-    _check(lib().mnnq_linear_prefill(_ptr(packed), M, N, K, GROUP, MODE_W4_ZP_INT, _ptr(xq), _ptr(sx),
+    _check(lib().mnnq_linear_prefill(_ptr(packed), M, N, K, GROUP, mode, _ptr(xq), _ptr(sx),
                                      _ptr(bias), _ptr(y), None, 0, _stream()), "mnnq_linear_prefill")
     return y
 
@@ -200,27 +204,29 @@ def mnnq_linear_prefill_f16(packed, N: int, K: int, x16, bias=None, out=None, ro
     return y
 
 
-def mnnq_pack_from_quantized(q, scale, zero, out=None):
-    """q u8 [N,K], scale f32 [N,G], zero u8 [N,G] on the GPU -> packed uint8 buffer."""
-    _dev(q, torch.uint8, "q"); _dev(scale, torch.float32, "scale"); _dev(zero, torch.uint8, "zero")
+def mnnq_pack_from_quantized(q, scale, zero, out=None, mode: int = MODE_W4_ZP_INT):
+    """q u8 [N,K], scale f32 [N,G], zero u8 [N,G] (fp32 group minima in mode MODE_W4_MIN_FLOAT) on the
+    GPU -> packed uint8 buffer."""
+    _dev(q, torch.uint8, "q"); _dev(scale, torch.float32, "scale")
+    _dev(zero, torch.float32 if mode == MODE_W4_MIN_FLOAT else torch.uint8, "zero")
     N, K = q.shape
     if tuple(scale.shape) != (N, K // GROUP) or tuple(zero.shape) != (N, K // GROUP):
         raise ValueError("scale and zero must be [N, K/%d]" % GROUP)
-    nbytes = mnnq_packed_size(N, K)
+    nbytes = mnnq_packed_size(N, K, GROUP, mode)
     if nbytes == 0:
         raise ValueError("unsupported shape N=%d K=%d" % (N, K))
     packed = torch.empty(nbytes, dtype=torch.uint8, device=q.device) if out is None else out
-    _check(lib().mnnq_pack_from_quantized(_ptr(q), _ptr(scale), _ptr(zero), N, K, GROUP, MODE_W4_ZP_INT,
+    _check(lib().mnnq_pack_from_quantized(_ptr(q), _ptr(scale), _ptr(zero), N, K, GROUP, mode,
                                           _ptr(packed), packed.numel(), _stream()), "mnnq_pack_from_quantized")
     return packed
 
 
-def mnnq_linear_acc_debug(packed, N: int, K: int, xq, use_prefill_kernel: bool):
+def mnnq_linear_acc_debug(packed, N: int, K: int, xq, use_prefill_kernel: bool, mode: int = MODE_W4_ZP_INT):
     """Integer group accumulators I[m,n,g] (int32 [M,N,G]) from the decode or the prefill kernel."""
     _dev(packed, torch.uint8, "packed"); _dev(xq, torch.int8, "xq")
     xq2 = xq.reshape(-1, K)
     M = xq2.shape[0]
     acc = torch.empty((M, N, K // GROUP), dtype=torch.int32, device=packed.device)
-    _check(lib().mnnq_linear_acc_debug(_ptr(packed), M, N, K, GROUP, MODE_W4_ZP_INT, _ptr(xq2), _ptr(acc),
+    _check(lib().mnnq_linear_acc_debug(_ptr(packed), M, N, K, GROUP, mode, _ptr(xq2), _ptr(acc),
                                        1 if use_prefill_kernel else 0, _stream()), "mnnq_linear_acc_debug")
     return acc

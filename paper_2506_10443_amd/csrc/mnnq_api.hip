@@ -24,7 +24,7 @@ inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) &
 int check_shape(int64_t N, int64_t K, int group, int mode)
 {
     if (N <= 0 || K <= 0) return MNNQ_ERR_SHAPE;
-    if (group != kGroup || mode != MNNQ_W4_ZP_INT) return MNNQ_ERR_UNSUPPORTED;
+    if (group != kGroup || (mode != MNNQ_W4_ZP_INT && mode != MNNQ_W4_MIN_FLOAT)) return MNNQ_ERR_UNSUPPORTED;
     if (K % group != 0) return MNNQ_ERR_SHAPE;
     if (N % kTileN != 0) return MNNQ_ERR_UNSUPPORTED;
     if (N > (int64_t)1 << 24 || K > (int64_t)1 << 24) return MNNQ_ERR_UNSUPPORTED;
@@ -39,11 +39,11 @@ size_t fused_ws_bytes(int64_t K) { return (size_t)((K + 127) / 128 * 128 + 16); 
 // quantizing the row once, in a kernel of its own, beats quantizing it in every workgroup.
 constexpr size_t kFusedTwoKernelBytes = (size_t)48 << 20;
 
-bool prefill_fits(int64_t M, int64_t N, int64_t K)
+bool prefill_fits(int64_t M, int64_t N, int64_t K, int mode = MNNQ_W4_ZP_INT)
 {
     const int64_t lim = ((int64_t)1 << 31) - 1;
     // 32-bit byte offsets: activation rows of a whole tile, the packed weights, the output.
-    return M <= ((int64_t)1 << 24) && (M + 256) * K <= lim && (int64_t)make_layout(N, K).total() <= lim &&
+    return M <= ((int64_t)1 << 24) && (M + 256) * K <= lim && (int64_t)make_layout(N, K, mode).total() <= lim &&
            (M + 256) * N * 4 <= lim;
 }
 
@@ -75,7 +75,7 @@ int mnnq_version(void) { return 100; }
 size_t mnnq_packed_size(int64_t N, int64_t K, int group, int mode)
 {
     if (check_shape(N, K, group, mode) != MNNQ_OK) return 0;
-    return make_layout(N, K).total();
+    return make_layout(N, K, mode).total();
 }
 
 size_t mnnq_workspace_size(int64_t M, int64_t N, int64_t K, int group, int mode)
@@ -92,31 +92,32 @@ int mnnq_pack_weights(const float* W, int64_t N, int64_t K, int group, int mode,
     if (!W || !packed) return MNNQ_ERR_NULL;
     if (int s = check_shape(N, K, group, mode)) return s;
     if (misaligned(W) || misaligned(packed)) return MNNQ_ERR_ALIGN;
-    const Layout L = make_layout(N, K);
+    const Layout L = make_layout(N, K, mode);
     if (packed_bytes < L.total()) return MNNQ_ERR_SIZE;
     return launch_pack(W, L, static_cast<uint8_t*>(packed), static_cast<hipStream_t>(stream));
 }
 
-int mnnq_pack_from_quantized(const uint8_t* q, const float* scale, const uint8_t* zero, int64_t N, int64_t K,
+int mnnq_pack_from_quantized(const uint8_t* q, const float* scale, const void* zero, int64_t N, int64_t K,
                              int group, int mode, void* packed, size_t packed_bytes, void* stream)
 {
     if (!q || !scale || !zero || !packed) return MNNQ_ERR_NULL;
     if (int s = check_shape(N, K, group, mode)) return s;
     if (misaligned(q) || misaligned(packed)) return MNNQ_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(scale) & 3u) return MNNQ_ERR_ALIGN;
-    const Layout L = make_layout(N, K);
+    if (mode == MNNQ_W4_MIN_FLOAT && (reinterpret_cast<uintptr_t>(zero) & 3u)) return MNNQ_ERR_ALIGN;
+    const Layout L = make_layout(N, K, mode);
     if (packed_bytes < L.total()) return MNNQ_ERR_SIZE;
     return launch_repack(q, scale, zero, L, static_cast<uint8_t*>(packed), static_cast<hipStream_t>(stream));
 }
 
 int mnnq_unpack_weights(const void* packed, int64_t N, int64_t K, int group, int mode, uint8_t* q,
-                        float* scale, uint8_t* zero, void* stream)
+                        float* scale, void* zero, void* stream)
 {
     if (!packed) return MNNQ_ERR_NULL;
     if (int s = check_shape(N, K, group, mode)) return s;
     if (misaligned(packed) || misaligned(q) || misaligned(scale) || misaligned(zero)) return MNNQ_ERR_ALIGN;
     if (!q && !scale && !zero) return MNNQ_OK;
-    return launch_unpack(static_cast<const uint8_t*>(packed), make_layout(N, K), q, scale, zero,
+    return launch_unpack(static_cast<const uint8_t*>(packed), make_layout(N, K, mode), q, scale, zero,
                          static_cast<hipStream_t>(stream));
 }
 
@@ -144,7 +145,7 @@ int mnnq_linear_decode(const void* packed, int64_t N, int64_t K, int group, int 
     if (K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
     if (misaligned(packed) || misaligned(xq) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(sx) & 3u) return MNNQ_ERR_ALIGN;
-    return launch_decode(static_cast<const uint8_t*>(packed), make_layout(N, K), xq, sx, bias, y,
+    return launch_decode(static_cast<const uint8_t*>(packed), make_layout(N, K, mode), xq, sx, bias, y,
                          static_cast<hipStream_t>(stream));
 }
 
@@ -156,7 +157,7 @@ int mnnq_linear_decode_fused(const void* packed, int64_t N, int64_t K, int group
     if (K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
     if (misaligned(packed) || misaligned(x) || misaligned(y) || misaligned(bias) || misaligned(workspace))
         return MNNQ_ERR_ALIGN;
-    const Layout L = make_layout(N, K);
+    const Layout L = make_layout(N, K, mode);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (workspace && workspace_bytes >= fused_ws_bytes(K) && L.total() > kFusedTwoKernelBytes) {
         int8_t* xq = static_cast<int8_t*>(workspace);
@@ -175,11 +176,11 @@ int mnnq_linear_prefill(const void* packed, int64_t M, int64_t N, int64_t K, int
     if (!packed || !xq || !sx || !y) return MNNQ_ERR_NULL;
     if (M <= 0) return MNNQ_ERR_SHAPE;
     if (int s = check_shape(N, K, group, mode)) return s;
-    if (!prefill_fits(M, N, K)) return MNNQ_ERR_UNSUPPORTED;
+    if (!prefill_fits(M, N, K, mode)) return MNNQ_ERR_UNSUPPORTED;
     if (misaligned(packed) || misaligned(xq) || misaligned(y) || misaligned(bias) || misaligned(workspace))
         return MNNQ_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(sx) & 3u) return MNNQ_ERR_ALIGN;
-    return launch_prefill(static_cast<const uint8_t*>(packed), make_layout(N, K), M, xq, sx, bias, y, nullptr,
+    return launch_prefill(static_cast<const uint8_t*>(packed), make_layout(N, K, mode), M, xq, sx, bias, y, nullptr,
                           static_cast<hipStream_t>(stream));
 }
 
@@ -189,9 +190,10 @@ int mnnq_linear_decode_f16(const void* packed, int64_t N, int64_t K, int group, 
     (void)workspace; (void)workspace_bytes;
     if (!packed || !x16 || !y) return MNNQ_ERR_NULL;
     if (int s = check_shape(N, K, group, mode)) return s;
+    if (mode != MNNQ_W4_ZP_INT) return MNNQ_ERR_UNSUPPORTED;   // fp16 activations: integer zero point only
     if (K > kMaxDecodeKF16) return MNNQ_ERR_UNSUPPORTED;
     if (misaligned(packed) || misaligned(x16) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
-    return launch_decode_f16(static_cast<const uint8_t*>(packed), make_layout(N, K), x16, bias, y,
+    return launch_decode_f16(static_cast<const uint8_t*>(packed), make_layout(N, K, mode), x16, bias, y,
                              static_cast<hipStream_t>(stream));
 }
 
@@ -203,10 +205,11 @@ int mnnq_linear_prefill_f16(const void* packed, int64_t M, int64_t N, int64_t K,
     if (!packed || !x16 || !y) return MNNQ_ERR_NULL;
     if (M <= 0) return MNNQ_ERR_SHAPE;
     if (int s = check_shape(N, K, group, mode)) return s;
+    if (mode != MNNQ_W4_ZP_INT) return MNNQ_ERR_UNSUPPORTED;   // fp16 activations: integer zero point only
     if (!prefill_fits(M, N, 2 * K)) return MNNQ_ERR_UNSUPPORTED;   // byte offsets of fp16 rows
     if (misaligned(packed) || misaligned(x16) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(row_scale) & 3u) return MNNQ_ERR_ALIGN;
-    return launch_prefill_f16(static_cast<const uint8_t*>(packed), make_layout(N, K), M, x16, row_scale, bias, y,
+    return launch_prefill_f16(static_cast<const uint8_t*>(packed), make_layout(N, K, mode), M, x16, row_scale, bias, y,
                               static_cast<hipStream_t>(stream));
 }
 
@@ -218,9 +221,9 @@ int mnnq_linear_acc_debug(const void* packed, int64_t M, int64_t N, int64_t K, i
     if (int s = check_shape(N, K, group, mode)) return s;
     if (M > kMaxM) return MNNQ_ERR_UNSUPPORTED;
     if (!use_prefill_kernel && K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
-    if (use_prefill_kernel && !prefill_fits(M, N, K)) return MNNQ_ERR_UNSUPPORTED;
+    if (use_prefill_kernel && !prefill_fits(M, N, K, mode)) return MNNQ_ERR_UNSUPPORTED;
     if (misaligned(packed) || misaligned(xq) || misaligned(acc)) return MNNQ_ERR_ALIGN;
-    const Layout L = make_layout(N, K);
+    const Layout L = make_layout(N, K, mode);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (use_prefill_kernel)
         return launch_prefill(static_cast<const uint8_t*>(packed), L, M, xq, nullptr, nullptr, nullptr, acc, st);

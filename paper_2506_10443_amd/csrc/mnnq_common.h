@@ -18,7 +18,9 @@
 //            `w & 0x0f0f0f0f` and `(w >> 4) & 0x0f0f0f0f` give codes 8d..8d+3
 //            and 8d+4..8d+7 in byte order.
 //   scales : [T][C][16 rows][2] fp32  at byte T*C*1024
-//   zeros  : [T][C][16 rows][2] u8    at byte T*C*1024 + T*C*128
+//   zeros  : [T][C][16 rows][2] u8    at byte T*C*1024 + T*C*128        (mode MNNQ_W4_ZP_INT)
+//   mins   : [T][C][16 rows][2] fp32  at the same place                 (mode MNNQ_W4_MIN_FLOAT:
+//            the group minimum of Eq. 1 as a float offset instead of an integer zero point)
 //
 // One chunk is exactly one wave-wide 128-bit load (1 KiB) for the decode GEMV,
 // and lane l's 16 bytes are exactly its B operands of two 16x16x64 int8 MFMAs
@@ -39,6 +41,7 @@ constexpr int kChunkBytes = 1024;
 
 struct Layout {
     int64_t N, K;
+    int mode;   // mnnq_mode
     int64_t T;  // row tiles
     int64_t G;  // groups per row
     int64_t C;  // chunks per row tile
@@ -48,16 +51,17 @@ struct Layout {
     __host__ __device__ size_t total() const { return codes_bytes + scales_bytes + zeros_bytes; }
 };
 
-inline __host__ __device__ Layout make_layout(int64_t N, int64_t K)
+inline __host__ __device__ Layout make_layout(int64_t N, int64_t K, int mode = MNNQ_W4_ZP_INT)
 {
     Layout L;
     L.N = N; L.K = K;
+    L.mode = mode;
     L.T = N / kTileN;
     L.G = K / kGroup;
     L.C = (L.G + 1) / 2;
     L.codes_bytes = (size_t)L.T * L.C * kChunkBytes;
     L.scales_bytes = (size_t)L.T * L.C * 32 * sizeof(float);
-    L.zeros_bytes = (size_t)L.T * L.C * 32;
+    L.zeros_bytes = (size_t)L.T * L.C * 32 * (mode == MNNQ_W4_MIN_FLOAT ? sizeof(float) : 1);
     return L;
 }
 
@@ -72,9 +76,10 @@ int record_hip_error(hipError_t e);
 
 // Kernel launchers (one translation unit each).  All return a status.
 int launch_pack(const float* W, const Layout& L, uint8_t* packed, hipStream_t st);
-int launch_repack(const uint8_t* q, const float* scale, const uint8_t* zero, const Layout& L, uint8_t* packed,
+// zero: uint8 zero points (mode MNNQ_W4_ZP_INT) or fp32 group minima (mode MNNQ_W4_MIN_FLOAT), [N, G].
+int launch_repack(const uint8_t* q, const float* scale, const void* zero, const Layout& L, uint8_t* packed,
                   hipStream_t st);
-int launch_unpack(const uint8_t* packed, const Layout& L, uint8_t* q, float* scale, uint8_t* zero,
+int launch_unpack(const uint8_t* packed, const Layout& L, uint8_t* q, float* scale, void* zero,
                   hipStream_t st);
 int launch_quant_act(const float* x, int64_t M, int64_t K, int8_t* xq, float* sx, int32_t* xsum,
                      hipStream_t st);

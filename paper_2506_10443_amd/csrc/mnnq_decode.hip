@@ -38,16 +38,24 @@ enum Mode { kXQ = 0, kFused = 1, kAcc = 2 };
 struct ChunkRegs {
     u32x4 w;      // 32 codes: .x,.y group 2c ; .z,.w group 2c+1
     float2 s;     // scales of the lane's row for both groups
-    uint32_t z;   // zeros, low byte group 2c, next byte group 2c+1
+    uint32_t z;   // zero points, low byte group 2c, next byte group 2c+1      (integer zero point form)
+    float2 mn;    // group minima of the lane's row for both groups          (float minimum form)
 };
 
-__device__ __forceinline__ ChunkRegs load_chunk(const u32x4* wp, const float2* sp, const uint16_t* zp,
-                                                int64_t i)
+// MINF: the packed matrix holds fp32 group minima where the zero points would be.
+template <bool MINF>
+__device__ __forceinline__ ChunkRegs load_chunk(const u32x4* wp, const float2* sp, const void* zp, int64_t i)
 {
     ChunkRegs r;
     r.w = __builtin_nontemporal_load(wp + i * 64);
     r.s = sp[i * 16];
-    r.z = zp[i * 16];
+    if (MINF) {
+        r.mn = static_cast<const float2*>(zp)[i * 16];
+        r.z = 0;
+    } else {
+        r.z = static_cast<const uint16_t*>(zp)[i * 16];
+        r.mn = make_float2(0.0f, 0.0f);
+    }
     return r;
 }
 
@@ -86,7 +94,7 @@ __device__ __forceinline__ int quant4_fast(float4 v, float scale, float inv, flo
 // LDS of a workgroup: the activation row (K int8, zero padded to C * 128 bytes),
 // the sums of its 16-byte blocks stored as [chunk][kb][half], the partial sums
 // of the split rows and the per-wave maxima of the fused quantizer.
-template <int WAVES, int KSPLIT, int UNROLL, int MODE, bool PREFETCH>
+template <int WAVES, int KSPLIT, int UNROLL, int MODE, bool PREFETCH, bool MINF>
 __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __restrict__ packed, Layout L,
                                                             const void* __restrict__ xin,
                                                             const float* __restrict__ sx,
@@ -125,14 +133,18 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
     const int64_t c1 = C * (ks + 1) / KSPLIT;
     const u32x4* wp = reinterpret_cast<const u32x4*>(packed) + (tile * C + c0) * 64 + lane;
     const float2* sp = reinterpret_cast<const float2*>(packed + L.scales_off()) + (tile * C + c0) * 16 + row;
-    const uint16_t* zp = reinterpret_cast<const uint16_t*>(packed + L.zeros_off()) + (tile * C + c0) * 16 + row;
+    // zero points (2 x u8 per row and chunk) or group minima (2 x fp32)
+    const void* zp = MINF ? static_cast<const void*>(reinterpret_cast<const float2*>(packed + L.zeros_off()) +
+                                                     (tile * C + c0) * 16 + row)
+                          : static_cast<const void*>(reinterpret_cast<const uint16_t*>(packed + L.zeros_off()) +
+                                                     (tile * C + c0) * 16 + row);
     const int64_t n_chunks = active ? (c1 - c0) : 0;
 
     // Start the weight stream before the activation row is touched: it does not depend on x.
     ChunkRegs cur[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
-        if (u < n_chunks) cur[u] = load_chunk(wp, sp, zp, u);
+        if (u < n_chunks) cur[u] = load_chunk<MINF>(wp, sp, zp, u);
         else cur[u] = ChunkRegs{};
     }
 
@@ -199,7 +211,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
         if (PREFETCH) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
-                if (i + UNROLL + u < n_chunks) nxt[u] = load_chunk(wp, sp, zp, i + UNROLL + u);
+                if (i + UNROLL + u < n_chunks) nxt[u] = load_chunk<MINF>(wp, sp, zp, i + UNROLL + u);
                 else nxt[u] = ChunkRegs{};
             }
         }
@@ -212,8 +224,10 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
                 const int4 xb = lds_x[cl * 8 + 4 + kb];
                 const int2 xs = *reinterpret_cast<const int2*>(lds_xs + cl * 8 + kb * 2);
                 const ChunkRegs& r = cur[u];
-                int i0 = dot16(r.w.x, r.w.y, xa) - (int)(r.z & 0xffu) * xs.x;
-                int i1 = dot16(r.w.z, r.w.w, xb) - (int)(r.z >> 8) * xs.y;
+                // integer zero point: sum x (q - z) = sum x q - z sum x; float minimum: sum x q, the
+                // minimum enters below with the same block sum
+                int i0 = dot16(r.w.x, r.w.y, xa) - (MINF ? 0 : (int)(r.z & 0xffu) * xs.x);
+                int i1 = dot16(r.w.z, r.w.w, xb) - (MINF ? 0 : (int)(r.z >> 8) * xs.y);
                 if (MODE == kAcc) {
                     i0 += __shfl_xor(i0, 16, 64); i0 += __shfl_xor(i0, 32, 64);
                     i1 += __shfl_xor(i1, 16, 64); i1 += __shfl_xor(i1, 32, 64);
@@ -225,6 +239,10 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
                 } else {
                     accf = fmaf(r.s.x, (float)i0, accf);
                     accf = fmaf(r.s.y, (float)i1, accf);
+                    if (MINF) {
+                        accf = fmaf(r.mn.x, (float)xs.x, accf);
+                        accf = fmaf(r.mn.y, (float)xs.y, accf);
+                    }
                 }
             }
         }
@@ -262,8 +280,14 @@ int launch_cfg(const uint8_t* packed, const Layout& L, int64_t M, const void* xi
     const int PW = (int)((L.C + KSPLIT - 1) / KSPLIT);
     const size_t smem = (MODE == kFused ? (size_t)L.C * 160 : (size_t)WAVES * PW * 160) + WAVES * 17 * sizeof(float);
     if (smem > 64 * 1024) return MNNQ_ERR_UNSUPPORTED;   // only reachable with a forced split
-    hipLaunchKernelGGL((decode_kernel<WAVES, KSPLIT, UNROLL, MODE, PREFETCH>), dim3((unsigned)blocks, (unsigned)M),
-                       dim3(WAVES * 64), smem, st, packed, L, xin, sx, bias, y, acc, PW);
+    if (L.mode == MNNQ_W4_MIN_FLOAT)
+        hipLaunchKernelGGL((decode_kernel<WAVES, KSPLIT, UNROLL, MODE, PREFETCH, true>),
+                           dim3((unsigned)blocks, (unsigned)M), dim3(WAVES * 64), smem, st, packed, L, xin, sx, bias,
+                           y, acc, PW);
+    else
+        hipLaunchKernelGGL((decode_kernel<WAVES, KSPLIT, UNROLL, MODE, PREFETCH, false>),
+                           dim3((unsigned)blocks, (unsigned)M), dim3(WAVES * 64), smem, st, packed, L, xin, sx, bias,
+                           y, acc, PW);
     MNNQ_HIP_TRY(hipGetLastError());
     return MNNQ_OK;
 }

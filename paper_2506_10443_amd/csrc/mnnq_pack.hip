@@ -1,5 +1,6 @@
 // Load-time step: quantize fp32 weights to asymmetric int4 (Section 4.2, Eq. 1,
-// integer zero point, groups of 64 along K) and store them in the chunk layout
+// groups of 64 along K; with an integer zero point or, as the equation is
+// printed, with the group minimum as a float offset) and store them in the chunk layout
 // described in mnnq_common.h; plus the inverse view used by tests and export,
 // and the import of already quantized weights into the same layout.
 //
@@ -34,19 +35,30 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const float* __restr
         mn = fminf(mn, __shfl_xor(mn, o, kTeam));
         mx = fmaxf(mx, __shfl_xor(mx, o, kTeam));
     }
-    // A group that does not straddle zero gets its range widened to contain it.
-    mn = fminf(mn, 0.0f);
-    mx = fmaxf(mx, 0.0f);
+    const bool minf = (L.mode == MNNQ_W4_MIN_FLOAT);
+    if (!minf) {
+        // Integer zero point: a group that does not straddle zero gets its range widened to contain it.
+        mn = fminf(mn, 0.0f);
+        mx = fmaxf(mx, 0.0f);
+    }
 
     float scale = 1.0f, zero = 0.0f;
     uint32_t c0 = 0, c1 = 0, c2 = 0, c3 = 0;
     if (mx != mn) {
         scale = (mx - mn) / 15.0f;
-        zero = rintf((-mn) / scale);
-        c0 = (uint32_t)fminf(fmaxf(rintf(w.x / scale) + zero, 0.0f), 15.0f);
-        c1 = (uint32_t)fminf(fmaxf(rintf(w.y / scale) + zero, 0.0f), 15.0f);
-        c2 = (uint32_t)fminf(fmaxf(rintf(w.z / scale) + zero, 0.0f), 15.0f);
-        c3 = (uint32_t)fminf(fmaxf(rintf(w.w / scale) + zero, 0.0f), 15.0f);
+        if (minf) {
+            // Eq. 1 as printed: the minimum is subtracted before the division.
+            c0 = (uint32_t)fminf(fmaxf(rintf((w.x - mn) / scale), 0.0f), 15.0f);
+            c1 = (uint32_t)fminf(fmaxf(rintf((w.y - mn) / scale), 0.0f), 15.0f);
+            c2 = (uint32_t)fminf(fmaxf(rintf((w.z - mn) / scale), 0.0f), 15.0f);
+            c3 = (uint32_t)fminf(fmaxf(rintf((w.w - mn) / scale), 0.0f), 15.0f);
+        } else {
+            zero = rintf((-mn) / scale);
+            c0 = (uint32_t)fminf(fmaxf(rintf(w.x / scale) + zero, 0.0f), 15.0f);
+            c1 = (uint32_t)fminf(fmaxf(rintf(w.y / scale) + zero, 0.0f), 15.0f);
+            c2 = (uint32_t)fminf(fmaxf(rintf(w.z / scale) + zero, 0.0f), 15.0f);
+            c3 = (uint32_t)fminf(fmaxf(rintf(w.w / scale) + zero, 0.0f), 15.0f);
+        }
     }
     // Lane li holds codes j = 4 (li % 4) .. +3 of k-block kb = li / 4.  Codes
     // j % 8 < 4 go to low nibbles, the others to high nibbles of the same bytes.
@@ -64,25 +76,28 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const float* __restr
     uint32_t* slot = reinterpret_cast<uint32_t*>(packed + chunk * kChunkBytes + (16 * kb + r) * 16);
     float* sc = reinterpret_cast<float*>(packed + L.scales_off()) + (chunk * 16 + r) * 2;
     uint8_t* zp = packed + L.zeros_off() + (chunk * 16 + r) * 2;
+    float* mp = reinterpret_cast<float*>(packed + L.zeros_off()) + (chunk * 16 + r) * 2;
     if ((li & 1) == 0) slot[half * 2 + d] = v;
     if (li == 0) {
         sc[half] = scale;
-        zp[half] = (uint8_t)zero;
+        if (minf) mp[half] = mn;
+        else zp[half] = (uint8_t)zero;
     }
     // Odd number of groups: the second half of the last chunk is padding that
-    // contributes nothing (codes 0, scale 0, zero 0).
+    // contributes nothing (codes 0, scale 0, zero / minimum 0).
     if ((L.G & 1) && g == L.G - 1) {
         if ((li & 1) == 0) slot[2 + d] = 0u;
         if (li == 0) {
             sc[1] = 0.0f;
-            zp[1] = 0;
+            if (minf) mp[1] = 0.0f;
+            else zp[1] = 0;
         }
     }
 }
 
 __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t* __restrict__ packed, Layout L,
                                                      uint8_t* __restrict__ q, float* __restrict__ scale,
-                                                     uint8_t* __restrict__ zero)
+                                                     void* __restrict__ zero)
 {
     // One thread per (row, group, k-block): 8 packed bytes -> 16 codes.
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -108,7 +123,12 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t* __restrict__
     if (kb == 0) {
         const int64_t mi = (chunk * 16 + r) * 2 + half;
         if (scale) scale[n * L.G + g] = reinterpret_cast<const float*>(packed + L.scales_off())[mi];
-        if (zero) zero[n * L.G + g] = (packed + L.zeros_off())[mi];
+        if (zero) {
+            if (L.mode == MNNQ_W4_MIN_FLOAT)
+                static_cast<float*>(zero)[n * L.G + g] = reinterpret_cast<const float*>(packed + L.zeros_off())[mi];
+            else
+                static_cast<uint8_t*>(zero)[n * L.G + g] = (packed + L.zeros_off())[mi];
+        }
     }
 }
 
@@ -117,7 +137,7 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t* __restrict__
 // inverse of unpack_kernel.  One thread per (row, group, k-block).  Codes are
 // taken modulo 16, zero points above 15 are stored as 15.
 __global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__ q, const float* __restrict__ scale,
-                                                     const uint8_t* __restrict__ zero, Layout L,
+                                                     const void* __restrict__ zero, Layout L,
                                                      uint8_t* __restrict__ packed)
 {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -139,23 +159,30 @@ __global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__
     slot[half] = w;
     float* sc = reinterpret_cast<float*>(packed + L.scales_off()) + (chunk * 16 + r) * 2;
     uint8_t* zp = packed + L.zeros_off() + (chunk * 16 + r) * 2;
+    float* mp = reinterpret_cast<float*>(packed + L.zeros_off()) + (chunk * 16 + r) * 2;
+    const bool minf = (L.mode == MNNQ_W4_MIN_FLOAT);
     if (kb == 0) {
-        const uint8_t z = zero[n * L.G + g];
         sc[half] = scale[n * L.G + g];
-        zp[half] = z > 15 ? (uint8_t)15 : z;
+        if (minf) {
+            mp[half] = static_cast<const float*>(zero)[n * L.G + g];
+        } else {
+            const uint8_t z = static_cast<const uint8_t*>(zero)[n * L.G + g];
+            zp[half] = z > 15 ? (uint8_t)15 : z;
+        }
     }
     if ((L.G & 1) && g == L.G - 1) {   // padding group of an odd G
         slot[1] = make_uint2(0u, 0u);
         if (kb == 0) {
             sc[1] = 0.0f;
-            zp[1] = 0;
+            if (minf) mp[1] = 0.0f;
+            else zp[1] = 0;
         }
     }
 }
 
 }  // namespace
 
-int launch_repack(const uint8_t* q, const float* scale, const uint8_t* zero, const Layout& L, uint8_t* packed,
+int launch_repack(const uint8_t* q, const float* scale, const void* zero, const Layout& L, uint8_t* packed,
                   hipStream_t st)
 {
     const int64_t total = L.N * L.G * 4;
@@ -174,7 +201,7 @@ int launch_pack(const float* W, const Layout& L, uint8_t* packed, hipStream_t st
     return MNNQ_OK;
 }
 
-int launch_unpack(const uint8_t* packed, const Layout& L, uint8_t* q, float* scale, uint8_t* zero,
+int launch_unpack(const uint8_t* packed, const Layout& L, uint8_t* q, float* scale, void* zero,
                   hipStream_t st)
 {
     const int64_t total = L.N * L.G * 4;

@@ -63,15 +63,15 @@ __device__ __forceinline__ v4i unpack_b(uint32_t w0, uint32_t w1, uint32_t c4)
 // LDS map of a workgroup: the A tile is double buffered, the B tile (codes, scales,
 // zeros of one chunk) is single buffered - it is copied into registers before
 // the next chunk is loaded over it.
-template <int BM, int BN>
+template <int BM, int BN, bool MINF>
 struct Lds {
     static constexpr int NT16 = BN / 16;                 // row tiles of B per workgroup
     static constexpr int A_BYTES = BM * 128;             // [BM][128] int8, swizzled
     static constexpr int A_OFF = 0;                      // two A buffers
     static constexpr int B_OFF = 2 * A_BYTES;            // [NT16][1024] packed codes
     static constexpr int S_OFF = B_OFF + NT16 * 1024;    // [NT16][16][2] fp32 scales
-    static constexpr int Z_OFF = S_OFF + NT16 * 128;     // [NT16][16][2] u8 zeros
-    static constexpr int BYTES = Z_OFF + NT16 * 32;
+    static constexpr int Z_OFF = S_OFF + NT16 * 128;     // [NT16][16][2] u8 zeros, or fp32 group minima (MINF)
+    static constexpr int BYTES = Z_OFF + NT16 * (MINF ? 128 : 32);
 };
 
 // Work distribution: one workgroup per output tile and K split.  Shapes with few
@@ -79,14 +79,14 @@ struct Lds {
 // CUs with whole tiles, so their K range is cut in two; both halves add their part
 // to a zeroed y with fp32 atomics.  Two addends commute, so the result does not
 // depend on which half arrives first.
-template <int BM, int BN, int KS, bool ACC>
+template <int BM, int BN, int KS, bool ACC, bool MINF>
 __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_kernel(const uint8_t* __restrict__ packed, Layout L, int64_t M,
                                                          const int8_t* __restrict__ xq,
                                                          const float* __restrict__ sx,
                                                          const float* __restrict__ bias, float* __restrict__ y,
                                                          int32_t* __restrict__ acc_out, int MT, int NT, int S)
 {
-    using St = Lds<BM, BN>;
+    using St = Lds<BM, BN, MINF>;
     constexpr int WM = BM / 2, WN = BN / 2;      // 2 x 2 waves
     constexpr int TM = WM / 16, TN = WN / 16;
     constexpr int NT16 = St::NT16;
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
     const int a_sw = col & 7;                                   // swizzle key: row & 7 == col & 7
     const int b_frag_off = St::B_OFF + wn * TN * 1024 + lane * 16;
     const int s_frag_off = St::S_OFF + wn * TN * 128 + col * 8;
-    const int z_frag_off = St::Z_OFF + wn * TN * 32 + col * 2;
+    const int z_frag_off = St::Z_OFF + (MINF ? wn * TN * 128 + col * 8 : wn * TN * 32 + col * 2);
 
     {
         auto issue_stage = [&](int c, int buf) {
@@ -171,7 +171,10 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
             // Scales: one load covers two row tiles (2 x 128 B); zeros: one load covers all eight (8 x 32 B).
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::S_OFF + wave * 256), 4, s_voff,
                                                      scales_off + ((rt0 + wave * 2) * C + c) * 128, 0, 0);
-            if (wave == 0)
+            if (MINF)   // group minima: fp32, laid out like the scales
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::Z_OFF + wave * 256), 4, s_voff,
+                                                         zeros_off + ((rt0 + wave * 2) * C + c) * 128, 0, 0);
+            else if (wave == 0)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::Z_OFF + opaque_zero), 4, z_voff,
                                                          zeros_off + (rt0 * C + c) * 32, 0, 0);
         };
@@ -186,13 +189,15 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
 
         v4i bw[TN];
         v2i bsv[TN];
-        uint32_t bz[TN];
+        uint32_t bz[TN];      // zero points of both groups (integer zero point form)
+        v2i bmn[TN];          // group minima of both groups, fp32 bits (float minimum form)
         auto read_b = [&]() {
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 bw[j] = *reinterpret_cast<const v4i*>(lds + b_frag_off + j * 1024);
                 bsv[j] = *reinterpret_cast<const v2i*>(lds + s_frag_off + j * 128);
-                bz[j] = *reinterpret_cast<const uint16_t*>(lds + z_frag_off + j * 32);
+                if (MINF) bmn[j] = *reinterpret_cast<const v2i*>(lds + z_frag_off + j * 128);
+                else bz[j] = *reinterpret_cast<const uint16_t*>(lds + z_frag_off + j * 32);
             }
         };
 
@@ -215,12 +220,23 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
                 if (KS > 1 && c >= ce) break;   // the shorter share idles through the last round
                 v4i b[TN];
                 float sc[TN];
+                float mnv[TN];
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
-                    // 0x80 - zero point of this group in each of the four bytes
-                    const uint32_t c4 = 0x80808080u - __builtin_amdgcn_perm(bz[j], bz[j], h ? 0x01010101u : 0u);
-                    b[j] = h ? unpack_b((uint32_t)bw[j].z, (uint32_t)bw[j].w, c4)
-                             : unpack_b((uint32_t)bw[j].x, (uint32_t)bw[j].y, c4);
+                    const uint32_t w0 = (uint32_t)(h ? bw[j].z : bw[j].x), w1 = (uint32_t)(h ? bw[j].w : bw[j].y);
+                    if (MINF) {
+                        // the codes themselves (0..15) are the B operand; the minimum enters in the epilogue
+                        b[j].x = (int)(w0 & 0x0f0f0f0fu);
+                        b[j].y = (int)((w0 >> 4) & 0x0f0f0f0fu);
+                        b[j].z = (int)(w1 & 0x0f0f0f0fu);
+                        b[j].w = (int)((w1 >> 4) & 0x0f0f0f0fu);
+                        mnv[j] = __int_as_float(h ? bmn[j].y : bmn[j].x);
+                    } else {
+                        // 0x80 - zero point of this group in each of the four bytes
+                        const uint32_t c4 = 0x80808080u - __builtin_amdgcn_perm(bz[j], bz[j], h ? 0x01010101u : 0u);
+                        b[j] = unpack_b(w0, w1, c4);
+                        mnv[j] = 0.0f;
+                    }
                     sc[j] = __int_as_float(h ? bsv[j].y : bsv[j].x);
                 }
                 const int g = 2 * c + h;
@@ -249,10 +265,17 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
                     // t into the running sums.  The empty asm statements emit nothing; they
                     // only tie values together so that this order survives the compiler's
                     // schedulers: MFMA(t+1) < epilogue(t) < MFMA(t+2).
+                    // Float minimum form: one more MFMA per 16 rows with an all-ones B operand gives
+                    // xs[m] = sum_{k in g} xq[m,k] in the D layout, i.e. for exactly the four rows of
+                    // this lane; the epilogue adds min[n,g] * xs[m,g].
+                    const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
                     v4i a = *reinterpret_cast<const v4i*>(ap);
                     v4i a_nxt = a;
                     if (TM > 1) a_nxt = *reinterpret_cast<const v4i*>(ap + 2048);
                     v4i d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[0], zero, 0, 0, 0);
+                    v4i xs_cur = zero, xs_nxt = zero;
+                    if (MINF) xs_cur = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, ones, zero, 0, 0, 0);
+                    float xsf[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
                     for (int tt = 0; tt < TM * TN; ++tt) {
                         const int i = tt / TN, j = tt % TN;
@@ -264,11 +287,19 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
                                 if (i1 + 1 < TM) a_nxt = *reinterpret_cast<const v4i*>(ap + (i1 + 1) * 2048);
                             }
                             d_nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[j1], zero, 0, 0, 0);
+                            if (MINF && j1 == 0) xs_nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, ones, zero, 0, 0, 0);
                             asm volatile("" : "+v"(d), "+v"(d_nxt));
                         }
+                        if (MINF && j == 0) {
+                            if (i > 0) xs_cur = xs_nxt;      // issued with the first MFMA of this row of tiles
 #pragma unroll
-                        for (int rr = 0; rr < 4; ++rr)
+                            for (int rr = 0; rr < 4; ++rr) xsf[rr] = (float)xs_cur[rr];
+                        }
+#pragma unroll
+                        for (int rr = 0; rr < 4; ++rr) {
                             yacc[i][j][rr] = fmaf(sc[j], (float)d[rr], yacc[i][j][rr]);
+                            if (MINF) yacc[i][j][rr] = fmaf(mnv[j], xsf[rr], yacc[i][j][rr]);
+                        }
                         if (tt + 2 < TM * TN) {
                             const int j2 = (tt + 2) % TN;
                             asm volatile(""
@@ -369,14 +400,14 @@ __global__ void zero_f4_kernel(float4* p, int64_t n4)
     if (i < n4) p[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 }
 
-template <int BM, int BN, int KS, bool ACC>
-int launch_tiles(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
+template <int BM, int BN, int KS, bool ACC, bool MINF>
+int launch_tiles_m(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
                  const float* bias, float* y, int32_t* acc, int S, hipStream_t st)
 {
     const int MT = (int)((M + BM - 1) / BM);
     const int NT = (int)((L.N + BN - 1) / BN);
-    constexpr size_t smem = (size_t)KS * Lds<BM, BN>::BYTES;
-    auto kern = prefill_kernel<BM, BN, KS, ACC>;
+    constexpr size_t smem = (size_t)KS * Lds<BM, BN, MINF>::BYTES;
+    auto kern = prefill_kernel<BM, BN, KS, ACC, MINF>;
     if (smem > 64 * 1024) {
         // More than 64 KiB of dynamic LDS has to be allowed once per kernel and device.
         static thread_local int allowed_dev = -1;
@@ -399,6 +430,15 @@ int launch_tiles(const uint8_t* packed, const Layout& L, int64_t M, const int8_t
                        NT, S);
     MNNQ_HIP_TRY(hipGetLastError());
     return MNNQ_OK;
+}
+
+template <int BM, int BN, int KS, bool ACC>
+int launch_tiles(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
+                 const float* bias, float* y, int32_t* acc, int S, hipStream_t st)
+{
+    if (L.mode == MNNQ_W4_MIN_FLOAT)
+        return launch_tiles_m<BM, BN, KS, ACC, true>(packed, L, M, xq, sx, bias, y, acc, S, st);
+    return launch_tiles_m<BM, BN, KS, ACC, false>(packed, L, M, xq, sx, bias, y, acc, S, st);
 }
 
 // Tile, K-part and split choice.  A compute unit is full with two waves per SIMD:

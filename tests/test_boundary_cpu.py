@@ -46,7 +46,9 @@ def test_packed_size(L):
     assert binding.mnnq_packed_size(8, 128) == 0       # N not a multiple of 16
     assert binding.mnnq_packed_size(16, 100) == 0      # K not a multiple of 64
     assert binding.mnnq_packed_size(16, 128, 32) == 0  # group
-    assert binding.mnnq_packed_size(16, 128, 64, 1) == 0  # mode
+    assert binding.mnnq_packed_size(16, 128, 64, 2) == 0  # mode
+    # float-minimum form: fp32 minimum instead of a one-byte zero point per group
+    assert binding.mnnq_packed_size(3584, 18944, 64, 1) == 3584 * 18944 // 2 + 8 * 3584 * (18944 // 64)
     assert binding.mnnq_packed_size(0, 128) == 0 and binding.mnnq_packed_size(16, -64) == 0
     assert binding.mnnq_workspace_size(1, 16, 128) == 128 + 16     # optional scratch of the fused decode call
     assert binding.mnnq_workspace_size(1, 16, 192) == 256 + 16
@@ -74,6 +76,7 @@ def test_argument_validation_precedes_hip(L):
     assert pw(FAKE, 16, 100, 64, 0, FAKE, 10**9, None) == SHAPE
     assert pw(FAKE, 16, 128, 32, 0, FAKE, 10**9, None) == UNSUP
     assert pw(FAKE, 16, 128, 64, 7, FAKE, 10**9, None) == UNSUP
+    assert pw(FAKE, 16, 128, 64, 1, FAKE, binding.mnnq_packed_size(16, 128, 64, 1) - 1, None) == SIZE
     assert pw(FAKE, 24, 128, 64, 0, FAKE, 10**9, None) == UNSUP
     assert pw(ODD, 16, 128, 64, 0, FAKE, 10**9, None) == ALIGN
     assert pw(FAKE, 16, 128, 64, 0, FAKE, binding.mnnq_packed_size(16, 128) - 1, None) == SIZE
@@ -105,11 +108,13 @@ def test_argument_validation_precedes_hip(L):
     lp = L.mnnq_linear_prefill
     assert lp(FAKE, 0, 16, 128, 64, 0, FAKE, FAKE, None, FAKE, None, 0, None) == SHAPE
     assert lp(FAKE, 4, 16, 128, 64, 0, None, FAKE, None, FAKE, None, 0, None) == NULL
-    assert lp(FAKE, 4, 16, 128, 64, 1, FAKE, FAKE, None, FAKE, None, 0, None) == UNSUP
+    assert lp(FAKE, 4, 16, 128, 64, 2, FAKE, FAKE, None, FAKE, None, 0, None) == UNSUP
     assert lp(FAKE, 4, 16, 128, 64, 0, FAKE, FAKE, None, ODD, None, 0, None) == ALIGN
 
     assert L.mnnq_linear_decode_f16(FAKE, 16, 128, 64, 0, None, None, FAKE, None, 0, None) == NULL
     assert L.mnnq_linear_decode_f16(FAKE, 16, 100, 64, 0, FAKE, None, FAKE, None, 0, None) == SHAPE
+    assert L.mnnq_linear_decode_f16(FAKE, 16, 128, 64, 1, FAKE, None, FAKE, None, 0, None) == UNSUP   # float minimum
+    assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 128, 64, 1, FAKE, None, None, FAKE, None, 0, None) == UNSUP
     assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 128, 64, 0, FAKE, None, None, None, None, 0, None) == NULL
     assert L.mnnq_linear_prefill_f16(FAKE, -1, 16, 128, 64, 0, FAKE, None, None, FAKE, None, 0, None) == SHAPE
     assert L.mnnq_linear_acc_debug(FAKE, 1, 16, 128, 64, 0, FAKE, None, 0, None) == NULL
@@ -118,7 +123,8 @@ def test_argument_validation_precedes_hip(L):
     assert pq(None, FAKE, FAKE, 16, 128, 64, 0, FAKE, 10**9, None) == NULL
     assert pq(FAKE, FAKE, None, 16, 128, 64, 0, FAKE, 10**9, None) == NULL
     assert pq(FAKE, FAKE, FAKE, 16, 96, 64, 0, FAKE, 10**9, None) == SHAPE
-    assert pq(FAKE, FAKE, FAKE, 16, 128, 64, 1, FAKE, 10**9, None) == UNSUP
+    assert pq(FAKE, FAKE, FAKE, 16, 128, 64, 2, FAKE, 10**9, None) == UNSUP
+    assert pq(FAKE, FAKE, ODD + 2, 16, 128, 64, 1, FAKE, 10**9, None) == ALIGN   # fp32 minima
     assert pq(ODD, FAKE, FAKE, 16, 128, 64, 0, FAKE, 10**9, None) == ALIGN
     assert pq(FAKE, FAKE, FAKE, 16, 128, 64, 0, FAKE, binding.mnnq_packed_size(16, 128) - 1, None) == SIZE
     assert L.mnnq_unpack_weights(None, 16, 128, 64, 0, FAKE, FAKE, FAKE, None) == NULL
