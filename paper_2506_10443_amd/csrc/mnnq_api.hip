@@ -2,6 +2,8 @@
 // first HIP call), then the kernel launchers.
 #include "mnnq_common.h"
 
+#include <stdlib.h>
+
 namespace mnnq {
 
 static thread_local int t_last_hip_error = 0;
@@ -180,6 +182,11 @@ int mnnq_linear_prefill(const void* packed, int64_t M, int64_t N, int64_t K, int
     if (misaligned(packed) || misaligned(xq) || misaligned(y) || misaligned(bias) || misaligned(workspace))
         return MNNQ_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(sx) & 3u) return MNNQ_ERR_ALIGN;
+    // A few tokens (batched or speculative decoding) are still memory-bound: one pass over the
+    // weights in the GEMV's streaming order, all tokens at once in the matrix cores.
+    if (M <= 16 && !getenv("MNNQ_NO_SKINNY"))
+        return launch_skinny(static_cast<const uint8_t*>(packed), make_layout(N, K, mode), M, xq, sx, bias, y,
+                             static_cast<hipStream_t>(stream));
     return launch_prefill(static_cast<const uint8_t*>(packed), make_layout(N, K, mode), M, xq, sx, bias, y, nullptr,
                           static_cast<hipStream_t>(stream));
 }

@@ -91,6 +91,9 @@ int launch_decode_acc(const uint8_t* packed, const Layout& L, int64_t M, const i
                       int32_t* acc, hipStream_t st);
 int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq,
                    const float* sx, const float* bias, float* y, int32_t* acc_debug, hipStream_t st);
+// M <= 16 tokens sharing one pass over the weights.
+int launch_skinny(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
+                  const float* bias, float* y, hipStream_t st);
 int launch_decode_f16(const uint8_t* packed, const Layout& L, const uint16_t* x16, const float* bias,
                       float* y, hipStream_t st);
 // rs: optional per-row factor applied to the fp32 sums before the bias (NULL = none).

@@ -51,7 +51,8 @@ def test_pack_unpack_import_bit_exact(N, K):
     assert torch.equal(B.mnnq_pack_from_quantized(dev(q), dev(s), dev(mn), mode=MINF), packed)
 
 
-SHAPES = [(1, 16, 64), (7, 48, 192), (33, 272, 448), (130, 144, 1536), (300, 400, 1024), (64, 1024, 4096)]
+SHAPES = [(1, 16, 64), (7, 48, 192), (16, 144, 18944), (33, 272, 448), (130, 144, 1536), (300, 400, 1024),
+          (64, 1024, 4096)]
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
@@ -72,13 +73,17 @@ def test_linear_matches_oracle(M, N, K):
     # prefill, every tile / split choice
     y = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd, mode=MINF))
     assert np.abs(y - y_o).max() <= tol, (np.abs(y - y_o).max(), tol)
-    for cfg in ("b1", "s1", "b1k", "s1k", "s2", "b2k"):
-        os.environ["MNNQ_PREFILL_TILE"] = cfg
-        try:
-            y2 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd, mode=MINF))
-        finally:
-            os.environ.pop("MNNQ_PREFILL_TILE", None)
-        assert np.abs(y2 - y_o).max() <= tol, cfg
+    os.environ["MNNQ_NO_SKINNY"] = "1"     # M <= 16 would otherwise bypass the tiled kernel
+    try:
+        for cfg in ("b1", "s1", "b1k", "s1k", "s2", "b2k"):
+            os.environ["MNNQ_PREFILL_TILE"] = cfg
+            try:
+                y2 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd, mode=MINF))
+            finally:
+                os.environ.pop("MNNQ_PREFILL_TILE", None)
+            assert np.abs(y2 - y_o).max() <= tol, cfg
+    finally:
+        os.environ.pop("MNNQ_NO_SKINNY", None)
     # decode of a few rows, every K split, and the fused quantizer
     for m in sorted({0, M // 2, M - 1}):
         for ks in ("", "1", "2", "4", "8", "16"):
@@ -87,6 +92,10 @@ def test_linear_matches_oracle(M, N, K):
             try:
                 y0 = host(B.mnnq_linear_decode(packed, N, K, xqd[m].contiguous(), sxd[m:m + 1].contiguous(),
                                                bias=bd, mode=MINF))
+            except B.MnnqError as e:
+                # a forced split that leaves a wave more of the row than its LDS slice holds is refused
+                assert ks and e.status == -3 and K > 8192, (ks, e)
+                continue
             finally:
                 os.environ.pop("MNNQ_DECODE_KSPLIT", None)
             assert np.abs(y0 - y_o[m]).max() <= tol, (m, ks)

@@ -279,6 +279,40 @@ def test_prefill_matches_oracle(M, N, K):
     assert np.abs(y0 - y_o[0]).max() <= tol
 
 
+@pytest.mark.parametrize("M", [1, 2, 5, 16])
+@pytest.mark.parametrize("N,K", [(16, 64), (48, 192), (272, 1536), (144, 18944), (1024, 4096)])
+def test_few_tokens_share_one_pass_over_the_weights(M, N, K):
+    # M <= 16 goes through the streaming kernel (one MFMA per group and row tile for all tokens).
+    note("few tokens", M, N, K)
+    W, x, q, s, z, xq, sx = _layer(N, K, M, 800 + M + N + K)
+    bias = synth.weights(1, N, 10)[0] * 10
+    _, y_o = oracle.linear_w4a8(xq, sx, q, s, z, bias=bias, want_acc=False)
+    tol = TOL_A8 * np.abs(y_o).max()
+    packed = B.mnnq_pack_weights(dev(W))
+    xqd, sxd, bd = dev(xq), dev(sx), dev(bias)
+    for ks in ("", "1", "2", "4", "8"):
+        if ks:
+            os.environ["MNNQ_DECODE_KSPLIT"] = ks
+        try:
+            y = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd))
+            y2 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd))
+        finally:
+            os.environ.pop("MNNQ_DECODE_KSPLIT", None)
+        assert np.abs(y - y_o).max() <= tol, ks
+        assert np.array_equal(y, y2), ks
+    # the tiled GEMM kernel on the same input
+    os.environ["MNNQ_NO_SKINNY"] = "1"
+    try:
+        y3 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd))
+    finally:
+        os.environ.pop("MNNQ_NO_SKINNY", None)
+    assert np.abs(y3 - y_o).max() <= tol
+    # every token agrees with the one-token GEMV to the same bound
+    for m in range(M):
+        y0 = host(B.mnnq_linear_decode(packed, N, K, xqd[m].contiguous(), sxd[m:m + 1].contiguous(), bias=bd))
+        assert np.abs(y0 - y_o[m]).max() <= tol
+
+
 def test_prefill_many_tiles_ragged_last_column():
     # More 256-row tiles than the GPU holds at once (several rounds of workgroups), N not a
     # multiple of the tile width: every output is compared.
