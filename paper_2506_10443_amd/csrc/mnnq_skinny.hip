@@ -12,9 +12,11 @@
 //
 // Work split as in the GEMV: a wave owns one row tile and a contiguous chunk range,
 // KSPLIT waves share a row tile and add their partial sums in a fixed order through
-// LDS.  The activations are small (M * K bytes) and stay in L2; a lane loads its A
-// operand - 16 consecutive k of token lane % 16 - straight from there, so the kernel
-// needs LDS only for the final reduction.
+// LDS.  The activations are small (M * K bytes) and stay in L2.  Where 16 rows of them
+// fit in LDS (K <= 4096) a workgroup of 16 waves copies them there once, in the order
+// the A operand is read (STAGED), and shares them between its row tiles; for longer
+// rows each lane loads its A operand - 16 consecutive k of token lane % 16 - straight
+// from L2.
 //
 // MFMA lane mapping (A: 16 x 64 tokens x k, B: 64 x 16 k x weight rows, D: 16 x 16):
 //   A: lane l holds token l % 16, k block l / 16;  B: lane l holds weight row l % 16,
@@ -64,14 +66,16 @@ __device__ __forceinline__ v4i unpack_group(uint32_t w0, uint32_t w1, uint32_t z
     return b;
 }
 
-template <int WAVES, int KSPLIT, int UNROLL, bool PREFETCH, bool MINF>
+template <int WAVES, int KSPLIT, int UNROLL, bool PREFETCH, bool MINF, bool STAGED>
 __global__ __launch_bounds__(WAVES * 64) void skinny_kernel(const uint8_t* __restrict__ packed, Layout L, int M,
                                                             const int8_t* __restrict__ xq,
                                                             const float* __restrict__ sx,
                                                             const float* __restrict__ bias,
                                                             float* __restrict__ y)
 {
-    __shared__ float lds_part[WAVES * 4 * 64];   // [wave][r][lane]
+    extern __shared__ __align__(16) uint8_t smem[];
+    float* lds_part = reinterpret_cast<float*>(smem);                         // [wave][r][lane]
+    const v4i* lds_a = reinterpret_cast<const v4i*>(smem + WAVES * 4 * 64 * 4);   // STAGED: [C * 8 units][16 tokens]
     const int64_t C = L.C;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -107,8 +111,13 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_kernel(const uint8_t* __res
             r.z = static_cast<const uint16_t*>(zp)[i * 16];
             r.mn = make_float2(0.0f, 0.0f);
         }
-        r.xa = *reinterpret_cast<const v4i*>(xrow + c * 128);
-        r.xb = (odd_tail && c == C - 1) ? v4i{0, 0, 0, 0} : *reinterpret_cast<const v4i*>(xrow + c * 128 + 64);
+        if (!STAGED) {
+            r.xa = *reinterpret_cast<const v4i*>(xrow + c * 128);
+            r.xb = (odd_tail && c == C - 1) ? v4i{0, 0, 0, 0} : *reinterpret_cast<const v4i*>(xrow + c * 128 + 64);
+        } else {
+            r.xa = v4i{0, 0, 0, 0};
+            r.xb = v4i{0, 0, 0, 0};
+        }
         return r;
     };
 
@@ -117,6 +126,23 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_kernel(const uint8_t* __res
     for (int u = 0; u < UNROLL; ++u) {
         if (u < n_chunks) cur[u] = load(u);
         else cur[u] = SkinnyRegs{};
+    }
+
+    if (STAGED) {
+        // The weight loads above are in flight; now the whole workgroup copies the 16 token rows
+        // (tokens past M repeat the last one, k past K is zero) in units of 16 bytes: unit (ku, m)
+        // holds k = 16 ku .. 16 ku + 15 of token m, and lands at index ku * 16 + m.
+        v4i* dst = reinterpret_cast<v4i*>(smem + WAVES * 4 * 64 * 4);
+        const int units = (int)C * 8 * 16;
+        const int valid_ku = (int)(L.K / 16);
+        for (int u = tid; u < units; u += WAVES * 64) {
+            const int m = u & 15, ku = u >> 4;
+            v4i v = {0, 0, 0, 0};
+            if (ku < valid_ku)
+                v = *reinterpret_cast<const v4i*>(xq + (int64_t)(m < M ? m : M - 1) * L.K + ku * 16);
+            dst[u] = v;
+        }
+        __syncthreads();
     }
 
     const v4i zero = {0, 0, 0, 0};
@@ -135,18 +161,24 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_kernel(const uint8_t* __res
         for (int u = 0; u < UNROLL; ++u) {
             if (i + u < n_chunks) {
                 const SkinnyRegs& r = cur[u];
+                v4i xa = r.xa, xb = r.xb;
+                if (STAGED) {
+                    const int64_t c = c0 + i + u;
+                    xa = lds_a[((c * 8 + kb) << 4) + row];
+                    xb = lds_a[((c * 8 + 4 + kb) << 4) + row];
+                }
                 const v4i b0 = unpack_group<MINF>(r.w.x, r.w.y, r.z & 0xffu);
                 const v4i b1 = unpack_group<MINF>(r.w.z, r.w.w, r.z >> 8);
-                const v4i d0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(r.xa, b0, zero, 0, 0, 0);
-                const v4i d1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(r.xb, b1, zero, 0, 0, 0);
+                const v4i d0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, b0, zero, 0, 0, 0);
+                const v4i d1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(xb, b1, zero, 0, 0, 0);
 #pragma unroll
                 for (int rr = 0; rr < 4; ++rr) {
                     acc[rr] = fmaf(r.s.x, (float)d0[rr], acc[rr]);
                     acc[rr] = fmaf(r.s.y, (float)d1[rr], acc[rr]);
                 }
                 if (MINF) {
-                    const v4i x0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(r.xa, ones, zero, 0, 0, 0);
-                    const v4i x1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(r.xb, ones, zero, 0, 0, 0);
+                    const v4i x0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, ones, zero, 0, 0, 0);
+                    const v4i x1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(xb, ones, zero, 0, 0, 0);
 #pragma unroll
                     for (int rr = 0; rr < 4; ++rr) {
                         acc[rr] = fmaf(r.mn.x, (float)x0[rr], acc[rr]);
@@ -181,47 +213,61 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_kernel(const uint8_t* __res
     }
 }
 
-template <int WAVES, int KSPLIT, int UNROLL, bool PREFETCH>
+template <int WAVES, int KSPLIT, int UNROLL, bool PREFETCH, bool STAGED>
 int launch_cfg(const uint8_t* packed, const Layout& L, int M, const int8_t* xq, const float* sx, const float* bias,
                float* y, hipStream_t st)
 {
     constexpr int tiles_per_wg = WAVES / KSPLIT;
     const int64_t blocks = (L.T + tiles_per_wg - 1) / tiles_per_wg;
-    if (L.mode == MNNQ_W4_MIN_FLOAT)
-        hipLaunchKernelGGL((skinny_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, true>), dim3((unsigned)blocks),
-                           dim3(WAVES * 64), 0, st, packed, L, M, xq, sx, bias, y);
-    else
-        hipLaunchKernelGGL((skinny_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, false>), dim3((unsigned)blocks),
-                           dim3(WAVES * 64), 0, st, packed, L, M, xq, sx, bias, y);
-    MNNQ_HIP_TRY(hipGetLastError());
-    return MNNQ_OK;
+    const size_t smem = (size_t)WAVES * 4 * 64 * 4 + (STAGED ? (size_t)L.C * 8 * 16 * 16 : 0);
+    auto launch = [&](auto kern) -> int {
+        if (smem > 64 * 1024) {
+            // More than 64 KiB of dynamic LDS has to be allowed once per kernel and device.
+            static thread_local int allowed_dev = -1;
+            int dev = 0;
+            MNNQ_HIP_TRY(hipGetDevice(&dev));
+            if (allowed_dev != dev) {
+                MNNQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
+                allowed_dev = dev;
+            }
+        }
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(WAVES * 64), smem, st, packed, L, M, xq, sx, bias, y);
+        MNNQ_HIP_TRY(hipGetLastError());
+        return MNNQ_OK;
+    };
+    if (L.mode == MNNQ_W4_MIN_FLOAT) return launch(skinny_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, true, STAGED>);
+    return launch(skinny_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, false, STAGED>);
 }
 
 }  // namespace
 
-// The smallest number of waves per row tile (up to 8) for which a wave's chunk range (weights
-// and activations) fits in its registers, so that all loads are issued at once; longer rows
-// use a prefetching loop.
+// The smallest number of waves per row tile (up to 8) for which a wave's chunk range fits in
+// its registers, so that all loads are issued at once; longer rows use a prefetching loop.
+// Large layers with rows of up to 4096 values take the staged variant: 16 waves, i.e.
+// 16 / KSPLIT row tiles, share one copy of the activations in LDS.
 int launch_skinny(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
                   const float* bias, float* y, hipStream_t st)
 {
-    // At most 8 waves per row tile: a chunk costs 17 registers here (weights and activations),
-    // which a workgroup of 16 waves could not hold for 8 chunks.
+    // At most 8 waves per row tile: without staging a chunk costs 17 registers (weights and
+    // activations), which a workgroup of 16 waves could not hold for 8 chunks.
     int ks = 1;
     while (ks < 8 && (L.C + ks - 1) / ks > 8) ks *= 2;
-    int prefetch = (L.C + ks - 1) / ks > 8;
     if (const char* e = getenv("MNNQ_DECODE_KSPLIT")) {   // tests and tuning: force the split
         const int v = atoi(e);
-        if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16) {
-            ks = v > 8 ? 8 : v;
-            prefetch = (L.C + ks - 1) / ks > 8;
-        }
+        if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16) ks = v > 8 ? 8 : v;
     }
+    const bool prefetch = (L.C + ks - 1) / ks > 8;
+    // Staging pays once the layer is large enough to be bandwidth bound (measured: above ~16 MiB).
+    bool staged = L.C <= 32 && !prefetch && L.T * L.C >= 16384;
+    if (const char* e = getenv("MNNQ_SKINNY_STAGED")) staged = L.C <= 32 && !prefetch && e[0] == '1';   // tests
     const int m = (int)M;
-#define MNNQ_CFG(W, K)                                                                               \
-    if (ks == K)                                                                                     \
-        return prefetch ? launch_cfg<W, K, 4, true>(packed, L, m, xq, sx, bias, y, st)               \
-                        : launch_cfg<W, K, 8, false>(packed, L, m, xq, sx, bias, y, st);
+#define MNNQ_CFG(W, K)                                                                                 \
+    if (ks == K) {                                                                                     \
+        if (staged) return launch_cfg<16, K, 8, false, true>(packed, L, m, xq, sx, bias, y, st);       \
+        return prefetch ? launch_cfg<W, K, 4, true, false>(packed, L, m, xq, sx, bias, y, st)          \
+                        : launch_cfg<W, K, 8, false, false>(packed, L, m, xq, sx, bias, y, st);        \
+    }
     MNNQ_CFG(4, 1) MNNQ_CFG(4, 2) MNNQ_CFG(4, 4) MNNQ_CFG(8, 8)
 #undef MNNQ_CFG
     return MNNQ_ERR_UNSUPPORTED;

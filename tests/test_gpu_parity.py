@@ -290,16 +290,19 @@ def test_few_tokens_share_one_pass_over_the_weights(M, N, K):
     tol = TOL_A8 * np.abs(y_o).max()
     packed = B.mnnq_pack_weights(dev(W))
     xqd, sxd, bd = dev(xq), dev(sx), dev(bias)
-    for ks in ("", "1", "2", "4", "8"):
-        if ks:
-            os.environ["MNNQ_DECODE_KSPLIT"] = ks
-        try:
-            y = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd))
-            y2 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd))
-        finally:
-            os.environ.pop("MNNQ_DECODE_KSPLIT", None)
-        assert np.abs(y - y_o).max() <= tol, ks
-        assert np.array_equal(y, y2), ks
+    for staged in ("0", "1"):        # activations straight from L2, or shared through LDS
+        os.environ["MNNQ_SKINNY_STAGED"] = staged
+        for ks in ("", "1", "2", "4", "8"):
+            if ks:
+                os.environ["MNNQ_DECODE_KSPLIT"] = ks
+            try:
+                y = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd))
+                y2 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd))
+            finally:
+                os.environ.pop("MNNQ_DECODE_KSPLIT", None)
+            assert np.abs(y - y_o).max() <= tol, (staged, ks)
+            assert np.array_equal(y, y2), (staged, ks)
+        os.environ.pop("MNNQ_SKINNY_STAGED", None)
     # the tiled GEMM kernel on the same input
     os.environ["MNNQ_NO_SKINNY"] = "1"
     try:
