@@ -44,7 +44,8 @@ def _load():
             for name in ("orc_quant_weights", "orc_dequant", "orc_quant_act", "orc_linear_w4a8",
                          "orc_linear_w4a16", "orc_linear_w4a8_sampled", "orc_linear_w4a16_sampled",
                          "orc_quant_weights_minf", "orc_dequant_minf", "orc_linear_w4a8_minf",
-                         "orc_linear_w4a8_minf_sampled"):
+                         "orc_linear_w4a8_minf_sampled", "orc_quant_weights8", "orc_linear_w8a8",
+                         "orc_linear_w8a8_sampled"):
                 getattr(_lib, name).restype = None
             _lib.orc_omp_enabled.restype = ctypes.c_int
     return _lib
@@ -229,4 +230,54 @@ def linear_w4a8_minf_sampled(xq, sx, q, s, wmin, ms, ns, bias=None, want_acc=Tru
     y = np.empty((cnt,), np.float32)
     _load().orc_linear_w4a8_minf_sampled(_p(xq), _p(sx), _p(q), _p(s), _p(wmin), _p(bias),
                                          _i64(M), _i64(N), _i64(K), _p(ms), _p(ns), _i64(cnt), _p(acc), _p(y))
+    return acc, y
+
+
+# ---- int8 weights, Eq. 1 with clip range 0..255 and a float group minimum (O9, O10)
+
+def quant_weights8(W):
+    """O9.  W fp32 [N,K] -> (q u8 [N,K] 0..255, step f32 [N,G], wmin f32 [N,G])."""
+    W = _c(W, np.float32)
+    N, K = W.shape
+    assert K % GROUP == 0
+    G = K // GROUP
+    q = np.empty((N, K), np.uint8)
+    s = np.empty((N, G), np.float32)
+    mn = np.empty((N, G), np.float32)
+    _load().orc_quant_weights8(_p(W), _i64(N), _i64(K), _p(q), _p(s), _p(mn))
+    return q, s, mn
+
+
+def linear_w8a8(xq, sx, q, s, wmin, bias=None, want_acc=True):
+    """O10.  Returns (A int32 [M,N,G] or None, y fp32 [M,N]); q holds 8-bit codes."""
+    xq = _c(xq, np.int8); sx = _c(sx, np.float32)
+    q = _c(q, np.uint8); s = _c(s, np.float32); wmin = _c(wmin, np.float32)
+    if bias is not None:
+        bias = _c(bias, np.float32)
+    M, K = xq.shape
+    N = q.shape[0]
+    assert q.shape[1] == K and K % GROUP == 0
+    G = K // GROUP
+    acc = np.empty((M, N, G), np.int32) if want_acc else None
+    y = np.empty((M, N), np.float32)
+    _load().orc_linear_w8a8(_p(xq), _p(sx), _p(q), _p(s), _p(wmin), _p(bias),
+                            _i64(M), _i64(N), _i64(K), _p(acc), _p(y))
+    return acc, y
+
+
+def linear_w8a8_sampled(xq, sx, q, s, wmin, ms, ns, bias=None, want_acc=True):
+    """O10 on the listed (m, n) pairs only."""
+    xq = _c(xq, np.int8); sx = _c(sx, np.float32)
+    q = _c(q, np.uint8); s = _c(s, np.float32); wmin = _c(wmin, np.float32)
+    ms = _c(ms, np.int64); ns = _c(ns, np.int64)
+    if bias is not None:
+        bias = _c(bias, np.float32)
+    M, K = xq.shape
+    N = q.shape[0]
+    G = K // GROUP
+    cnt = ms.shape[0]
+    acc = np.empty((cnt, G), np.int32) if want_acc else None
+    y = np.empty((cnt,), np.float32)
+    _load().orc_linear_w8a8_sampled(_p(xq), _p(sx), _p(q), _p(s), _p(wmin), _p(bias),
+                                    _i64(M), _i64(N), _i64(K), _p(ms), _p(ns), _i64(cnt), _p(acc), _p(y))
     return acc, y

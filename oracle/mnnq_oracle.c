@@ -358,6 +358,64 @@ void orc_linear_w4a8_minf_sampled(const int8_t *xq, const float *sx,
     }
 }
 
+/* ---- int8 weights (Section 4.2: parameters are quantized to int4 or int8; the
+ * LM head is prioritised for int8), Eq. 1 as printed with clip range 0..255:
+ *     q = round((w - w_min) / step),  step = (w_max - w_min) / 255,  w^ = q * step + w_min. */
+
+/* O9: 8-bit weight quantizer.  W [N,K] -> q [N,K] (0..255), s [N,G] (step), wmin [N,G]. */
+void orc_quant_weights8(const float *W, int64_t N, int64_t K,
+                        uint8_t *q, float *s, float *wmin)
+{
+    const int64_t G = K / ORC_GROUP;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t g = 0; g < G; ++g) {
+            const float *w = W + n * K + g * ORC_GROUP;
+            uint8_t *qo = q + n * K + g * ORC_GROUP;
+            float mn = w[0], mx = w[0];
+            for (int k = 1; k < ORC_GROUP; ++k) {
+                if (w[k] < mn) mn = w[k];
+                if (w[k] > mx) mx = w[k];
+            }
+            wmin[n * G + g] = mn;
+            if (mx == mn) {
+                s[n * G + g] = 1.0f;
+                for (int k = 0; k < ORC_GROUP; ++k) qo[k] = 0;
+                continue;
+            }
+            const float step = (mx - mn) / 255.0f;
+            s[n * G + g] = step;
+            for (int k = 0; k < ORC_GROUP; ++k) {
+                float c = rintf((w[k] - mn) / step);
+                if (c < 0.0f) c = 0.0f;
+                if (c > 255.0f) c = 255.0f;
+                qo[k] = (uint8_t)c;
+            }
+        }
+    }
+}
+
+/* O10: W8A8 linear.  The code range only enters through q, so this is O8 on 8-bit codes:
+ *   A[m,n,g] = sum_{k in g} xq[m,k] * q[n,k],  xs[m,g] = sum_{k in g} xq[m,k]   (int32, exact:
+ *   |A| <= 64 * 127 * 255 < 2^21)
+ *   y[m,n] = sx[m] * sum_g (s[n,g] * A[m,n,g] + wmin[n,g] * xs[m,g]) (+ bias[n]). */
+void orc_linear_w8a8(const int8_t *xq, const float *sx,
+                     const uint8_t *q, const float *s, const float *wmin,
+                     const float *bias, int64_t M, int64_t N, int64_t K,
+                     int32_t *acc, float *y)
+{
+    orc_linear_w4a8_minf(xq, sx, q, s, wmin, bias, M, N, K, acc, y);
+}
+
+void orc_linear_w8a8_sampled(const int8_t *xq, const float *sx,
+                             const uint8_t *q, const float *s, const float *wmin,
+                             const float *bias, int64_t M, int64_t N, int64_t K,
+                             const int64_t *ms, const int64_t *ns, int64_t count,
+                             int32_t *acc, float *y)
+{
+    orc_linear_w4a8_minf_sampled(xq, sx, q, s, wmin, bias, M, N, K, ms, ns, count, acc, y);
+}
+
 int orc_omp_enabled(void)
 {
 #ifdef _OPENMP
