@@ -35,13 +35,15 @@ PREFILL_TRAFFIC_BYTES = 169.9e6   # profiles/bench_qwen2-7b_hbm_traffic.txt
 DECODE_TRAFFIC_BYTES = 33.8e6     # same file
 
 
-GROUP_PARAM_BYTES = 5    # fp32 scale + 1-byte zero point; 8 with an fp32 group minimum (--weight-mode minfloat)
+GROUP_PARAM_BYTES = 5    # fp32 scale + 1-byte zero point; 8 with an fp32 group minimum (--weight-mode minfloat);
+                         # 16 for int8 weights (two 4-bit planes, each with step and minimum)
+CODE_BYTES_X2 = 1        # bytes of codes per two weights: 1 for int4, 2 for int8
 
 
 def decode_bytes(N, K):
     """Algorithmic bytes of one decode GEMV: codes + per-group parameters, the int8
     activation row, and the fp32 output."""
-    return N * K // 2 + GROUP_PARAM_BYTES * N * (K // G) + K + 4 * N
+    return CODE_BYTES_X2 * N * K // 2 + GROUP_PARAM_BYTES * N * (K // G) + K + 4 * N
 
 
 def prefill_ops(M, N, K):
@@ -60,9 +62,9 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy, as the known-size reference for rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters")
-    ap.add_argument("--weight-mode", default="zp", choices=["zp", "minfloat"],
-                    help="weight quantizer: integer zero point (the benchmark configuration) or Eq. 1 as "
-                         "printed, with the group minimum as a float offset")
+    ap.add_argument("--weight-mode", default="zp", choices=["zp", "minfloat", "int8"],
+                    help="weight quantizer: int4 with an integer zero point (the benchmark configuration), int4 "
+                         "as Eq. 1 is printed (float group minimum), or int8 weights (float group minimum)")
     ap.add_argument("--two-call-decode", action="store_true",
                     help="decode pass calls mnnq_quant_act + mnnq_linear_decode per layer instead of "
                          "mnnq_linear_decode_fused (fp32 row in, quantizer inside the call)")
@@ -84,9 +86,10 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     B.lib()  # fail loudly if the HIP library is not built
-    wmode = B.MODE_W4_MIN_FLOAT if args.weight_mode == "minfloat" else B.MODE_W4_ZP_INT
-    global GROUP_PARAM_BYTES
-    GROUP_PARAM_BYTES = 8 if args.weight_mode == "minfloat" else 5
+    wmode = {"zp": B.MODE_W4_ZP_INT, "minfloat": B.MODE_W4_MIN_FLOAT, "int8": B.MODE_W8_MIN_FLOAT}[args.weight_mode]
+    global GROUP_PARAM_BYTES, CODE_BYTES_X2
+    GROUP_PARAM_BYTES = {"zp": 5, "minfloat": 8, "int8": 16}[args.weight_mode]
+    CODE_BYTES_X2 = 2 if args.weight_mode == "int8" else 1
 
     spec = synth.MODELS[args.model]
     n_blocks = spec["blocks"]

@@ -55,7 +55,16 @@ typedef enum {
      *   A = sum_{k in g} xq[m,k] * q[n,k],  xs[m,g] = sum_{k in g} xq[m,k].
      * Supported by the pack / unpack / import calls and the W4A8 linear calls;
      * the fp16-activation calls return MNNQ_ERR_UNSUPPORTED for it. */
-    MNNQ_W4_MIN_FLOAT = 1
+    MNNQ_W4_MIN_FLOAT = 1,
+    /* int8 weights (Section 4.2: parameters are quantized to int4 or int8, the LM
+     * head preferably to int8): Eq. 1 with clip range 0..255 and a float minimum,
+     * step = (max - min) / 255, q = clamp(round((w - min) / step), 0, 255),
+     * w^ = q * step + min.  Needs K to be a multiple of 128.  The packed form holds
+     * a code as two 4-bit planes and runs on the int4 kernels (1.25 bytes per
+     * weight).  Supported by the same calls as MNNQ_W4_MIN_FLOAT; q of the
+     * unpack / import calls holds the 8-bit codes; mnnq_linear_acc_debug returns
+     * 2 K/64 sums per (m, n): first the high-nibble planes, then the low ones. */
+    MNNQ_W8_MIN_FLOAT = 2
 } mnnq_mode;
 
 /* Text for a status code (static storage). */

@@ -15,6 +15,7 @@ import torch  # noqa: F401  (must be imported first: the library binds to the HI
 GROUP = 64
 MODE_W4_ZP_INT = 0      # integer zero point per (row, group)
 MODE_W4_MIN_FLOAT = 1   # Eq. 1 as printed: fp32 group minimum per (row, group)
+MODE_W8_MIN_FLOAT = 2   # int8 weights (codes 0..255), fp32 group minimum; K must be a multiple of 128
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "lib", "libmnnq.so")
@@ -120,7 +121,7 @@ def mnnq_unpack_weights(packed: torch.Tensor, N: int, K: int, mode: int = MODE_W
     G = K // GROUP
     q = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
     s = torch.empty((N, G), dtype=torch.float32, device=packed.device)
-    z = torch.empty((N, G), dtype=torch.float32 if mode == MODE_W4_MIN_FLOAT else torch.uint8,
+    z = torch.empty((N, G), dtype=torch.uint8 if mode == MODE_W4_ZP_INT else torch.float32,
                     device=packed.device)
     _check(lib().mnnq_unpack_weights(_ptr(packed), N, K, GROUP, mode, _ptr(q), _ptr(s), _ptr(z),
                                      _stream()), "mnnq_unpack_weights")
@@ -208,7 +209,7 @@ def mnnq_pack_from_quantized(q, scale, zero, out=None, mode: int = MODE_W4_ZP_IN
     """q u8 [N,K], scale f32 [N,G], zero u8 [N,G] (fp32 group minima in mode MODE_W4_MIN_FLOAT) on the
     GPU -> packed uint8 buffer."""
     _dev(q, torch.uint8, "q"); _dev(scale, torch.float32, "scale")
-    _dev(zero, torch.float32 if mode == MODE_W4_MIN_FLOAT else torch.uint8, "zero")
+    _dev(zero, torch.uint8 if mode == MODE_W4_ZP_INT else torch.float32, "zero")
     N, K = q.shape
     if tuple(scale.shape) != (N, K // GROUP) or tuple(zero.shape) != (N, K // GROUP):
         raise ValueError("scale and zero must be [N, K/%d]" % GROUP)
@@ -226,7 +227,9 @@ def mnnq_linear_acc_debug(packed, N: int, K: int, xq, use_prefill_kernel: bool, 
     _dev(packed, torch.uint8, "packed"); _dev(xq, torch.int8, "xq")
     xq2 = xq.reshape(-1, K)
     M = xq2.shape[0]
-    acc = torch.empty((M, N, K // GROUP), dtype=torch.int32, device=packed.device)
+    # int8 weights are two 4-bit planes: 2 K / 64 sums per (m, n), high-nibble planes first
+    Gp = (2 if mode == MODE_W8_MIN_FLOAT else 1) * (K // GROUP)
+    acc = torch.empty((M, N, Gp), dtype=torch.int32, device=packed.device)
     _check(lib().mnnq_linear_acc_debug(_ptr(packed), M, N, K, GROUP, mode, _ptr(xq2), _ptr(acc),
                                        1 if use_prefill_kernel else 0, _stream()), "mnnq_linear_acc_debug")
     return acc

@@ -26,8 +26,9 @@ inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) &
 int check_shape(int64_t N, int64_t K, int group, int mode)
 {
     if (N <= 0 || K <= 0) return MNNQ_ERR_SHAPE;
-    if (group != kGroup || (mode != MNNQ_W4_ZP_INT && mode != MNNQ_W4_MIN_FLOAT)) return MNNQ_ERR_UNSUPPORTED;
+    if (group != kGroup || mode < MNNQ_W4_ZP_INT || mode > MNNQ_W8_MIN_FLOAT) return MNNQ_ERR_UNSUPPORTED;
     if (K % group != 0) return MNNQ_ERR_SHAPE;
+    if (mode == MNNQ_W8_MIN_FLOAT && K % (2 * group) != 0) return MNNQ_ERR_UNSUPPORTED;   // whole chunks per plane
     if (N % kTileN != 0) return MNNQ_ERR_UNSUPPORTED;
     if (N > (int64_t)1 << 24 || K > (int64_t)1 << 24) return MNNQ_ERR_UNSUPPORTED;
     return MNNQ_OK;
@@ -106,7 +107,7 @@ int mnnq_pack_from_quantized(const uint8_t* q, const float* scale, const void* z
     if (int s = check_shape(N, K, group, mode)) return s;
     if (misaligned(q) || misaligned(packed)) return MNNQ_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(scale) & 3u) return MNNQ_ERR_ALIGN;
-    if (mode == MNNQ_W4_MIN_FLOAT && (reinterpret_cast<uintptr_t>(zero) & 3u)) return MNNQ_ERR_ALIGN;
+    if (mode != MNNQ_W4_ZP_INT && (reinterpret_cast<uintptr_t>(zero) & 3u)) return MNNQ_ERR_ALIGN;
     const Layout L = make_layout(N, K, mode);
     if (packed_bytes < L.total()) return MNNQ_ERR_SIZE;
     return launch_repack(q, scale, zero, L, static_cast<uint8_t*>(packed), static_cast<hipStream_t>(stream));
@@ -144,7 +145,7 @@ int mnnq_linear_decode(const void* packed, int64_t N, int64_t K, int group, int 
     (void)workspace; (void)workspace_bytes;
     if (!packed || !xq || !sx || !y) return MNNQ_ERR_NULL;
     if (int s = check_shape(N, K, group, mode)) return s;
-    if (K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
+    if (make_layout(N, K, mode).K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
     if (misaligned(packed) || misaligned(xq) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(sx) & 3u) return MNNQ_ERR_ALIGN;
     return launch_decode(static_cast<const uint8_t*>(packed), make_layout(N, K, mode), xq, sx, bias, y,
@@ -156,7 +157,7 @@ int mnnq_linear_decode_fused(const void* packed, int64_t N, int64_t K, int group
 {
     if (!packed || !x || !y) return MNNQ_ERR_NULL;
     if (int s = check_shape(N, K, group, mode)) return s;
-    if (K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
+    if (make_layout(N, K, mode).K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
     if (misaligned(packed) || misaligned(x) || misaligned(y) || misaligned(bias) || misaligned(workspace))
         return MNNQ_ERR_ALIGN;
     const Layout L = make_layout(N, K, mode);
@@ -227,7 +228,7 @@ int mnnq_linear_acc_debug(const void* packed, int64_t M, int64_t N, int64_t K, i
     if (M <= 0) return MNNQ_ERR_SHAPE;
     if (int s = check_shape(N, K, group, mode)) return s;
     if (M > kMaxM) return MNNQ_ERR_UNSUPPORTED;
-    if (!use_prefill_kernel && K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
+    if (!use_prefill_kernel && make_layout(N, K, mode).K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
     if (use_prefill_kernel && !prefill_fits(M, N, K, mode)) return MNNQ_ERR_UNSUPPORTED;
     if (misaligned(packed) || misaligned(xq) || misaligned(acc)) return MNNQ_ERR_ALIGN;
     const Layout L = make_layout(N, K, mode);

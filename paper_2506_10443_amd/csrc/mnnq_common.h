@@ -39,9 +39,17 @@ constexpr int kGroup = 64;
 constexpr int kTileN = 16;
 constexpr int kChunkBytes = 1024;
 
+// int8 weights (mode MNNQ_W8_MIN_FLOAT) reuse this layout and the int4 kernels: a code
+// q8 = 16 hi + lo is stored as two 4-bit planes along a doubled reduction axis - groups
+// 0..G-1 hold the high nibbles with step 16 s and the group minimum, groups G..2G-1 the low
+// nibbles with step s and minimum 0 - so that q8 s + min = hi (16 s) + min + lo s.  The
+// activation row is not doubled: chunk c of the packed matrix meets chunk c % Cx of the row.
 struct Layout {
-    int64_t N, K;
-    int mode;   // mnnq_mode
+    int64_t N, K;   // K: length of the packed reduction axis (2 x the row length for int8 weights)
+    int64_t Kx;     // length of an activation row
+    int64_t Cx;     // chunks of an activation row
+    int mode;       // mnnq_mode
+    bool minf;      // groups carry an fp32 minimum instead of a one-byte zero point
     int64_t T;  // row tiles
     int64_t G;  // groups per row
     int64_t C;  // chunks per row tile
@@ -54,14 +62,18 @@ struct Layout {
 inline __host__ __device__ Layout make_layout(int64_t N, int64_t K, int mode = MNNQ_W4_ZP_INT)
 {
     Layout L;
-    L.N = N; L.K = K;
+    L.N = N;
+    L.Kx = K;
+    L.K = (mode == MNNQ_W8_MIN_FLOAT) ? 2 * K : K;
     L.mode = mode;
+    L.minf = (mode != MNNQ_W4_ZP_INT);
     L.T = N / kTileN;
-    L.G = K / kGroup;
+    L.G = L.K / kGroup;
     L.C = (L.G + 1) / 2;
+    L.Cx = (K / kGroup + 1) / 2;
     L.codes_bytes = (size_t)L.T * L.C * kChunkBytes;
     L.scales_bytes = (size_t)L.T * L.C * 32 * sizeof(float);
-    L.zeros_bytes = (size_t)L.T * L.C * 32 * (mode == MNNQ_W4_MIN_FLOAT ? sizeof(float) : 1);
+    L.zeros_bytes = (size_t)L.T * L.C * 32 * (L.minf ? sizeof(float) : 1);
     return L;
 }
 

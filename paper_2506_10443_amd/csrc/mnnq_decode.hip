@@ -149,15 +149,17 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
     }
 
     // ---- activation row -> LDS, one dword (four int8) per thread and step
-    const int64_t dwords = C * 32;                       // padded row
+    const int64_t dwords = C * 32;                       // padded row of the packed reduction axis
     const int64_t valid = L.K / 4;
+    const int64_t row_dw = L.Kx / 4;                     // the activation row itself; the packed axis of
+                                                         // int8 weights runs over it twice
     float scale = 0.0f;
     if (MODE == kFused) {
         const float4* x4 = reinterpret_cast<const float4*>(static_cast<const float*>(xin));
         float4 first = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        if (tid < valid) first = x4[tid];
+        if (tid < row_dw) first = x4[tid];
         float amax = fmaxf(fmaxf(fabsf(first.x), fabsf(first.y)), fmaxf(fabsf(first.z), fabsf(first.w)));
-        for (int64_t i = tid + THREADS; i < valid; i += THREADS) {
+        for (int64_t i = tid + THREADS; i < row_dw; i += THREADS) {
             const float4 v = x4[i];
             amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
         }
@@ -173,7 +175,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
         const float thr = (inv < 1.0e37f && scale > 1.0e-30f) ? 6.0e-5f : 2.0f;
         for (int64_t i = tid; i < dwords; i += THREADS) {
             int v = 0;
-            if (i < valid && scale != 0.0f) v = quant4_fast(i == tid ? first : x4[i], scale, inv, thr);
+            if (i < valid && scale != 0.0f) v = quant4_fast(i < row_dw && i == tid ? first : x4[i % row_dw], scale, inv, thr);
             lds_xd[i] = v;
             // sum of the 16-byte block: its four dwords sit in four neighbouring lanes
             int sum = __builtin_amdgcn_sdot4(v, 0x01010101, 0, false);
@@ -187,13 +189,14 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
         __syncthreads();
     } else {
         // This wave's chunks only, in 16-byte units: unit u of the region is unit c0 * 8 + u of the row.
-        const int4* xq16 = reinterpret_cast<const int4*>(static_cast<const int8_t*>(xin) + m * L.K);
+        const int4* xq16 = reinterpret_cast<const int4*>(static_cast<const int8_t*>(xin) + m * L.Kx);
+        const int64_t row_units = L.Kx / 16;
         int4* lds_xw = reinterpret_cast<int4*>(xbase);
         const int64_t own = (c1 - c0) * 8;
         for (int64_t u = lane; u < own; u += 64) {
             const int64_t gu = c0 * 8 + u;
             int4 v = make_int4(0, 0, 0, 0);
-            if (gu * 4 < valid) v = xq16[gu];
+            if (gu * 4 < valid) v = xq16[gu % row_units];
             lds_xw[u] = v;
             int sum = __builtin_amdgcn_sdot4(v.x, 0x01010101, 0, false);
             sum = __builtin_amdgcn_sdot4(v.y, 0x01010101, sum, false);
@@ -280,7 +283,7 @@ int launch_cfg(const uint8_t* packed, const Layout& L, int64_t M, const void* xi
     const int PW = (int)((L.C + KSPLIT - 1) / KSPLIT);
     const size_t smem = (MODE == kFused ? (size_t)L.C * 160 : (size_t)WAVES * PW * 160) + WAVES * 17 * sizeof(float);
     if (smem > 64 * 1024) return MNNQ_ERR_UNSUPPORTED;   // only reachable with a forced split
-    if (L.mode == MNNQ_W4_MIN_FLOAT)
+    if (L.minf)
         hipLaunchKernelGGL((decode_kernel<WAVES, KSPLIT, UNROLL, MODE, PREFETCH, true>),
                            dim3((unsigned)blocks, (unsigned)M), dim3(WAVES * 64), smem, st, packed, L, xin, sx, bias,
                            y, acc, PW);

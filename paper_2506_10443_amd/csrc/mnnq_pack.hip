@@ -16,6 +16,48 @@ namespace {
 constexpr int kTeam = 16;           // lanes per (row, group): 16 x float4 = 64 weights
 constexpr int kPackThreads = 256;   // 16 teams per workgroup
 
+// Stores one quantization group into the chunk layout.  Called by the 16 lanes of a
+// team; lane li holds the codes c0..c3 (each 0..15) of k = 4 li .. 4 li + 3 of group g
+// of the packed reduction axis.
+__device__ __forceinline__ void store_group(uint8_t* __restrict__ packed, const Layout& L, int64_t n, int64_t g,
+                                            int li, uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                            float scale, float mn, float zero)
+{
+    // Lane li holds codes j = 4 (li % 4) .. +3 of k-block kb = li / 4.  Codes
+    // j % 8 < 4 go to low nibbles, the others to high nibbles of the same bytes.
+    uint32_t v = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+    if (li & 1) v <<= 4;
+    v |= __shfl_xor(v, 1, kTeam);
+
+    const int64_t t = n / kTileN;
+    const int r = (int)(n % kTileN);
+    const int64_t c = g / 2;
+    const int half = (int)(g & 1);
+    const int kb = li / 4;
+    const int d = (li % 4) / 2;
+    const int64_t chunk = t * L.C + c;
+    uint32_t* slot = reinterpret_cast<uint32_t*>(packed + chunk * kChunkBytes + (16 * kb + r) * 16);
+    float* sc = reinterpret_cast<float*>(packed + L.scales_off()) + (chunk * 16 + r) * 2;
+    uint8_t* zp = packed + L.zeros_off() + (chunk * 16 + r) * 2;
+    float* mp = reinterpret_cast<float*>(packed + L.zeros_off()) + (chunk * 16 + r) * 2;
+    if ((li & 1) == 0) slot[half * 2 + d] = v;
+    if (li == 0) {
+        sc[half] = scale;
+        if (L.minf) mp[half] = mn;
+        else zp[half] = (uint8_t)zero;
+    }
+    // Odd number of groups: the second half of the last chunk is padding that
+    // contributes nothing (codes 0, scale 0, zero / minimum 0).
+    if ((L.G & 1) && g == L.G - 1) {
+        if ((li & 1) == 0) slot[2 + d] = 0u;
+        if (li == 0) {
+            sc[1] = 0.0f;
+            if (L.minf) mp[1] = 0.0f;
+            else zp[1] = 0;
+        }
+    }
+}
+
 __global__ __launch_bounds__(kPackThreads) void pack_kernel(const float* __restrict__ W, Layout L,
                                                             uint8_t* __restrict__ packed)
 {
@@ -35,7 +77,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const float* __restr
         mn = fminf(mn, __shfl_xor(mn, o, kTeam));
         mx = fmaxf(mx, __shfl_xor(mx, o, kTeam));
     }
-    const bool minf = (L.mode == MNNQ_W4_MIN_FLOAT);
+    const bool minf = L.minf;
     if (!minf) {
         // Integer zero point: a group that does not straddle zero gets its range widened to contain it.
         mn = fminf(mn, 0.0f);
@@ -60,98 +102,106 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const float* __restr
             c3 = (uint32_t)fminf(fmaxf(rintf(w.w / scale) + zero, 0.0f), 15.0f);
         }
     }
-    // Lane li holds codes j = 4 (li % 4) .. +3 of k-block kb = li / 4.  Codes
-    // j % 8 < 4 go to low nibbles, the others to high nibbles of the same bytes.
-    uint32_t v = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
-    if (li & 1) v <<= 4;
-    v |= __shfl_xor(v, 1, kTeam);
+    store_group(packed, L, n, g, li, c0, c1, c2, c3, scale, mn, zero);
+}
 
-    const int64_t t = n / kTileN;
+// int8 weights: Eq. 1 with clip range 0..255 and a float minimum, stored as two 4-bit
+// planes along the doubled reduction axis (see Layout): group g holds the high nibbles
+// with step 16 s and the minimum, group G8 + g the low nibbles with step s and minimum 0.
+__global__ __launch_bounds__(kPackThreads) void pack8_kernel(const float* __restrict__ W, Layout L,
+                                                             uint8_t* __restrict__ packed)
+{
+    const int64_t team = (int64_t)blockIdx.x * (kPackThreads / kTeam) + threadIdx.x / kTeam;
+    const int li = threadIdx.x % kTeam;
+    const int64_t G8 = L.Kx / kGroup;
+    if (team >= L.N * G8) return;
+    const int64_t n = team / G8;
+    const int64_t g = team % G8;
+
+    const float4 w = reinterpret_cast<const float4*>(W + team * kGroup)[li];
+    float mn = fminf(fminf(w.x, w.y), fminf(w.z, w.w));
+    float mx = fmaxf(fmaxf(w.x, w.y), fmaxf(w.z, w.w));
+#pragma unroll
+    for (int o = 1; o < kTeam; o <<= 1) {
+        mn = fminf(mn, __shfl_xor(mn, o, kTeam));
+        mx = fmaxf(mx, __shfl_xor(mx, o, kTeam));
+    }
+    float step = 1.0f;
+    uint32_t c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+    if (mx != mn) {
+        step = (mx - mn) / 255.0f;
+        c0 = (uint32_t)fminf(fmaxf(rintf((w.x - mn) / step), 0.0f), 255.0f);
+        c1 = (uint32_t)fminf(fmaxf(rintf((w.y - mn) / step), 0.0f), 255.0f);
+        c2 = (uint32_t)fminf(fmaxf(rintf((w.z - mn) / step), 0.0f), 255.0f);
+        c3 = (uint32_t)fminf(fmaxf(rintf((w.w - mn) / step), 0.0f), 255.0f);
+    }
+    store_group(packed, L, n, g, li, c0 >> 4, c1 >> 4, c2 >> 4, c3 >> 4, 16.0f * step, mn, 0.0f);
+    store_group(packed, L, n, G8 + g, li, c0 & 15u, c1 & 15u, c2 & 15u, c3 & 15u, step, 0.0f, 0.0f);
+}
+
+// 16 codes (one per byte) of k-block kb of group g of the packed axis, row n.
+__device__ __forceinline__ uint4 read_codes(const uint8_t* __restrict__ packed, const Layout& L, int64_t n, int64_t g,
+                                            int kb)
+{
+    const int64_t chunk = (n / kTileN) * L.C + g / 2;
     const int r = (int)(n % kTileN);
-    const int64_t c = g / 2;
-    const int half = (int)(g & 1);
-    const int kb = li / 4;
-    const int d = (li % 4) / 2;
-    const int64_t chunk = t * L.C + c;
-    uint32_t* slot = reinterpret_cast<uint32_t*>(packed + chunk * kChunkBytes + (16 * kb + r) * 16);
-    float* sc = reinterpret_cast<float*>(packed + L.scales_off()) + (chunk * 16 + r) * 2;
-    uint8_t* zp = packed + L.zeros_off() + (chunk * 16 + r) * 2;
-    float* mp = reinterpret_cast<float*>(packed + L.zeros_off()) + (chunk * 16 + r) * 2;
-    if ((li & 1) == 0) slot[half * 2 + d] = v;
-    if (li == 0) {
-        sc[half] = scale;
-        if (minf) mp[half] = mn;
-        else zp[half] = (uint8_t)zero;
-    }
-    // Odd number of groups: the second half of the last chunk is padding that
-    // contributes nothing (codes 0, scale 0, zero / minimum 0).
-    if ((L.G & 1) && g == L.G - 1) {
-        if ((li & 1) == 0) slot[2 + d] = 0u;
-        if (li == 0) {
-            sc[1] = 0.0f;
-            if (minf) mp[1] = 0.0f;
-            else zp[1] = 0;
-        }
-    }
+    const uint2 w = *reinterpret_cast<const uint2*>(packed + chunk * kChunkBytes + (16 * kb + r) * 16 + (g & 1) * 8);
+    uint4 o;
+    o.x = w.x & 0x0f0f0f0fu;
+    o.y = (w.x >> 4) & 0x0f0f0f0fu;
+    o.z = w.y & 0x0f0f0f0fu;
+    o.w = (w.y >> 4) & 0x0f0f0f0fu;
+    return o;
+}
+
+// Index of the per-group parameters (scale, zero / minimum) of group g, row n.
+__device__ __forceinline__ int64_t param_index(const Layout& L, int64_t n, int64_t g)
+{
+    return (((n / kTileN) * L.C + g / 2) * 16 + n % kTileN) * 2 + (g & 1);
 }
 
 __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t* __restrict__ packed, Layout L,
                                                      uint8_t* __restrict__ q, float* __restrict__ scale,
                                                      void* __restrict__ zero)
 {
-    // One thread per (row, group, k-block): 8 packed bytes -> 16 codes.
+    // One thread per (row, group of the weight matrix, k-block): 16 codes.
+    const int64_t G = L.Kx / kGroup;
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t total = L.N * L.G * 4;
-    if (idx >= total) return;
+    if (idx >= L.N * G * 4) return;
     const int kb = (int)(idx % 4);
-    const int64_t g = (idx / 4) % L.G;
-    const int64_t n = idx / (4 * L.G);
-    const int64_t t = n / kTileN;
-    const int r = (int)(n % kTileN);
-    const int64_t chunk = t * L.C + g / 2;
-    const int half = (int)(g & 1);
+    const int64_t g = (idx / 4) % G;
+    const int64_t n = idx / (4 * G);
+    const bool w8 = (L.mode == MNNQ_W8_MIN_FLOAT);   // high nibbles in group g, low nibbles in group G + g
     if (q) {
-        const uint2 w = *reinterpret_cast<const uint2*>(packed + chunk * kChunkBytes +
-                                                        (16 * kb + r) * 16 + half * 8);
-        uint4 o;
-        o.x = w.x & 0x0f0f0f0fu;
-        o.y = (w.x >> 4) & 0x0f0f0f0fu;
-        o.z = w.y & 0x0f0f0f0fu;
-        o.w = (w.y >> 4) & 0x0f0f0f0fu;
-        *reinterpret_cast<uint4*>(q + n * L.K + g * kGroup + 16 * kb) = o;
+        uint4 o = read_codes(packed, L, n, g, kb);
+        if (w8) {
+            const uint4 lo = read_codes(packed, L, n, G + g, kb);
+            o.x = (o.x << 4) | lo.x; o.y = (o.y << 4) | lo.y; o.z = (o.z << 4) | lo.z; o.w = (o.w << 4) | lo.w;
+        }
+        *reinterpret_cast<uint4*>(q + n * L.Kx + g * kGroup + 16 * kb) = o;
     }
     if (kb == 0) {
-        const int64_t mi = (chunk * 16 + r) * 2 + half;
-        if (scale) scale[n * L.G + g] = reinterpret_cast<const float*>(packed + L.scales_off())[mi];
+        const float* sc = reinterpret_cast<const float*>(packed + L.scales_off());
+        // int8: the low plane carries the step itself, the high plane the minimum
+        if (scale) scale[n * G + g] = sc[param_index(L, n, w8 ? G + g : g)];
         if (zero) {
-            if (L.mode == MNNQ_W4_MIN_FLOAT)
-                static_cast<float*>(zero)[n * L.G + g] = reinterpret_cast<const float*>(packed + L.zeros_off())[mi];
+            if (L.minf)
+                static_cast<float*>(zero)[n * G + g] =
+                    reinterpret_cast<const float*>(packed + L.zeros_off())[param_index(L, n, g)];
             else
-                static_cast<uint8_t*>(zero)[n * L.G + g] = (packed + L.zeros_off())[mi];
+                static_cast<uint8_t*>(zero)[n * G + g] = (packed + L.zeros_off())[param_index(L, n, g)];
         }
     }
 }
 
-// Import of weights that are already quantized (Section 4.2: quantized weights,
-// e.g. from GPTQ, can be imported): canonical arrays -> chunk layout, the exact
-// inverse of unpack_kernel.  One thread per (row, group, k-block).  Codes are
-// taken modulo 16, zero points above 15 are stored as 15.
-__global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__ q, const float* __restrict__ scale,
-                                                     const void* __restrict__ zero, Layout L,
-                                                     uint8_t* __restrict__ packed)
+// Writes 16 codes (one per byte, 0..15) of k-block kb of group g of the packed axis and,
+// from the thread with kb == 0, the group's parameters.
+__device__ __forceinline__ void write_codes(uint8_t* __restrict__ packed, const Layout& L, int64_t n, int64_t g,
+                                            int kb, uint4 o, float scale, float mn, uint8_t z)
 {
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t total = L.N * L.G * 4;
-    if (idx >= total) return;
-    const int kb = (int)(idx % 4);
-    const int64_t g = (idx / 4) % L.G;
-    const int64_t n = idx / (4 * L.G);
-    const int64_t t = n / kTileN;
+    const int64_t chunk = (n / kTileN) * L.C + g / 2;
     const int r = (int)(n % kTileN);
-    const int64_t chunk = t * L.C + g / 2;
     const int half = (int)(g & 1);
-
-    const uint4 o = *reinterpret_cast<const uint4*>(q + n * L.K + g * kGroup + 16 * kb);
     uint2 w;
     w.x = (o.x & 0x0f0f0f0fu) | ((o.y & 0x0f0f0f0fu) << 4);
     w.y = (o.z & 0x0f0f0f0fu) | ((o.w & 0x0f0f0f0fu) << 4);
@@ -160,23 +210,47 @@ __global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__
     float* sc = reinterpret_cast<float*>(packed + L.scales_off()) + (chunk * 16 + r) * 2;
     uint8_t* zp = packed + L.zeros_off() + (chunk * 16 + r) * 2;
     float* mp = reinterpret_cast<float*>(packed + L.zeros_off()) + (chunk * 16 + r) * 2;
-    const bool minf = (L.mode == MNNQ_W4_MIN_FLOAT);
     if (kb == 0) {
-        sc[half] = scale[n * L.G + g];
-        if (minf) {
-            mp[half] = static_cast<const float*>(zero)[n * L.G + g];
-        } else {
-            const uint8_t z = static_cast<const uint8_t*>(zero)[n * L.G + g];
-            zp[half] = z > 15 ? (uint8_t)15 : z;
-        }
+        sc[half] = scale;
+        if (L.minf) mp[half] = mn;
+        else zp[half] = z > 15 ? (uint8_t)15 : z;
     }
     if ((L.G & 1) && g == L.G - 1) {   // padding group of an odd G
         slot[1] = make_uint2(0u, 0u);
         if (kb == 0) {
             sc[1] = 0.0f;
-            if (minf) mp[1] = 0.0f;
+            if (L.minf) mp[1] = 0.0f;
             else zp[1] = 0;
         }
+    }
+}
+
+// Import of weights that are already quantized (Section 4.2: quantized weights,
+// e.g. from GPTQ, can be imported): canonical arrays -> chunk layout, the exact
+// inverse of unpack_kernel.  One thread per (row, group, k-block).  int4 codes are
+// taken modulo 16, zero points above 15 are stored as 15.
+__global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__ q, const float* __restrict__ scale,
+                                                     const void* __restrict__ zero, Layout L,
+                                                     uint8_t* __restrict__ packed)
+{
+    const int64_t G = L.Kx / kGroup;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= L.N * G * 4) return;
+    const int kb = (int)(idx % 4);
+    const int64_t g = (idx / 4) % G;
+    const int64_t n = idx / (4 * G);
+    const uint4 o = *reinterpret_cast<const uint4*>(q + n * L.Kx + g * kGroup + 16 * kb);
+    const float s = scale[n * G + g];
+    if (L.mode == MNNQ_W8_MIN_FLOAT) {
+        const float mn = static_cast<const float*>(zero)[n * G + g];
+        uint4 hi;
+        hi.x = o.x >> 4; hi.y = o.y >> 4; hi.z = o.z >> 4; hi.w = o.w >> 4;
+        write_codes(packed, L, n, g, kb, hi, 16.0f * s, mn, 0);
+        write_codes(packed, L, n, G + g, kb, o, s, 0.0f, 0);
+    } else if (L.minf) {
+        write_codes(packed, L, n, g, kb, o, s, static_cast<const float*>(zero)[n * G + g], 0);
+    } else {
+        write_codes(packed, L, n, g, kb, o, s, 0.0f, static_cast<const uint8_t*>(zero)[n * G + g]);
     }
 }
 
@@ -185,7 +259,7 @@ __global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__
 int launch_repack(const uint8_t* q, const float* scale, const void* zero, const Layout& L, uint8_t* packed,
                   hipStream_t st)
 {
-    const int64_t total = L.N * L.G * 4;
+    const int64_t total = L.N * (L.Kx / kGroup) * 4;
     const int64_t blocks = (total + 255) / 256;
     hipLaunchKernelGGL(repack_kernel, dim3((unsigned)blocks), dim3(256), 0, st, q, scale, zero, L, packed);
     MNNQ_HIP_TRY(hipGetLastError());
@@ -194,9 +268,12 @@ int launch_repack(const uint8_t* q, const float* scale, const void* zero, const 
 
 int launch_pack(const float* W, const Layout& L, uint8_t* packed, hipStream_t st)
 {
-    const int64_t teams = L.N * L.G;
+    const int64_t teams = L.N * (L.Kx / kGroup);
     const int64_t blocks = (teams + (kPackThreads / kTeam) - 1) / (kPackThreads / kTeam);
-    hipLaunchKernelGGL(pack_kernel, dim3((unsigned)blocks), dim3(kPackThreads), 0, st, W, L, packed);
+    if (L.mode == MNNQ_W8_MIN_FLOAT)
+        hipLaunchKernelGGL(pack8_kernel, dim3((unsigned)blocks), dim3(kPackThreads), 0, st, W, L, packed);
+    else
+        hipLaunchKernelGGL(pack_kernel, dim3((unsigned)blocks), dim3(kPackThreads), 0, st, W, L, packed);
     MNNQ_HIP_TRY(hipGetLastError());
     return MNNQ_OK;
 }
@@ -204,7 +281,7 @@ int launch_pack(const float* W, const Layout& L, uint8_t* packed, hipStream_t st
 int launch_unpack(const uint8_t* packed, const Layout& L, uint8_t* q, float* scale, void* zero,
                   hipStream_t st)
 {
-    const int64_t total = L.N * L.G * 4;
+    const int64_t total = L.N * (L.Kx / kGroup) * 4;
     const int64_t blocks = (total + 255) / 256;
     hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)blocks), dim3(256), 0, st, packed, L, q, scale, zero);
     MNNQ_HIP_TRY(hipGetLastError());

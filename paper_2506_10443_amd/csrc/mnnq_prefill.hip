@@ -107,7 +107,8 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
     const int col = lane & 15;
     const int kb = lane >> 4;
     const int C = (int)L.C;
-    const int K = (int)L.K;
+    const int K = (int)L.Kx;    // activation row length
+    const int Cx = (int)L.Cx;   // chunk c of the packed axis meets chunk c % Cx of the activation row
 
     // Workgroups are dealt to the 8 XCDs round-robin by their linear id.  Give each
     // XCD whole columns of output tiles (one weight row block, all token blocks and
@@ -127,7 +128,7 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
 
     // Buffer resources: out-of-range reads (rows past M, row tiles past N) return zero.
     const __amdgpu_buffer_rsrc_t rs_x =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(xq), 0, (int)(M * L.K), kBufFlags);
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(xq), 0, (int)(M * L.Kx), kBufFlags);
     const __amdgpu_buffer_rsrc_t rs_w =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(packed), 0, (int)L.total(), kBufFlags);
 
@@ -159,7 +160,7 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
                 const int q = wave * A_INSTR + i;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(
                     rs_x, MNNQ_LDS(lds + St::A_OFF + buf * St::A_BYTES + q * 1024), 16, a_voff,
-                    ((int)m0 + q * 8) * K + c * 128, 0, 0);
+                    ((int)m0 + q * 8) * K + (c % Cx) * 128, 0, 0);
             }
             // B codes: two row tiles per wave, one chunk block (1 KiB) each.
 #pragma unroll
@@ -436,7 +437,7 @@ template <int BM, int BN, int KS, bool ACC>
 int launch_tiles(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
                  const float* bias, float* y, int32_t* acc, int S, hipStream_t st)
 {
-    if (L.mode == MNNQ_W4_MIN_FLOAT)
+    if (L.minf)
         return launch_tiles_m<BM, BN, KS, ACC, true>(packed, L, M, xq, sx, bias, y, acc, S, st);
     return launch_tiles_m<BM, BN, KS, ACC, false>(packed, L, M, xq, sx, bias, y, acc, S, st);
 }

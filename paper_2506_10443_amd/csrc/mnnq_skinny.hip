@@ -96,7 +96,8 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_kernel(const uint8_t* __res
                                                      (tile * C + c0) * 16 + row);
     const int64_t n_chunks = active ? (c1 - c0) : 0;
     // Tokens past M repeat the last one; their results are not stored.
-    const int8_t* xrow = xq + (int64_t)(row < M ? row : M - 1) * L.K + kb * 16;
+    const int8_t* xrow = xq + (int64_t)(row < M ? row : M - 1) * L.Kx + kb * 16;
+    const int64_t Cx = L.Cx;      // chunk c of the packed axis meets chunk c % Cx of the activation row
     const bool odd_tail = (L.G & 1) != 0;   // the last chunk of a row holds one real group only
 
     auto load = [&](int64_t i) {
@@ -112,8 +113,9 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_kernel(const uint8_t* __res
             r.mn = make_float2(0.0f, 0.0f);
         }
         if (!STAGED) {
-            r.xa = *reinterpret_cast<const v4i*>(xrow + c * 128);
-            r.xb = (odd_tail && c == C - 1) ? v4i{0, 0, 0, 0} : *reinterpret_cast<const v4i*>(xrow + c * 128 + 64);
+            r.xa = *reinterpret_cast<const v4i*>(xrow + (c % Cx) * 128);
+            r.xb = (odd_tail && c == C - 1) ? v4i{0, 0, 0, 0}
+                                            : *reinterpret_cast<const v4i*>(xrow + (c % Cx) * 128 + 64);
         } else {
             r.xa = v4i{0, 0, 0, 0};
             r.xb = v4i{0, 0, 0, 0};
@@ -135,11 +137,12 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_kernel(const uint8_t* __res
         v4i* dst = reinterpret_cast<v4i*>(smem + WAVES * 4 * 64 * 4);
         const int units = (int)C * 8 * 16;
         const int valid_ku = (int)(L.K / 16);
+        const int row_ku = (int)(L.Kx / 16);
         for (int u = tid; u < units; u += WAVES * 64) {
             const int m = u & 15, ku = u >> 4;
             v4i v = {0, 0, 0, 0};
             if (ku < valid_ku)
-                v = *reinterpret_cast<const v4i*>(xq + (int64_t)(m < M ? m : M - 1) * L.K + ku * 16);
+                v = *reinterpret_cast<const v4i*>(xq + (int64_t)(m < M ? m : M - 1) * L.Kx + (ku % row_ku) * 16);
             dst[u] = v;
         }
         __syncthreads();
@@ -236,7 +239,7 @@ int launch_cfg(const uint8_t* packed, const Layout& L, int M, const int8_t* xq, 
         MNNQ_HIP_TRY(hipGetLastError());
         return MNNQ_OK;
     };
-    if (L.mode == MNNQ_W4_MIN_FLOAT) return launch(skinny_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, true, STAGED>);
+    if (L.minf) return launch(skinny_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, true, STAGED>);
     return launch(skinny_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, false, STAGED>);
 }
 

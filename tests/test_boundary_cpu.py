@@ -46,7 +46,10 @@ def test_packed_size(L):
     assert binding.mnnq_packed_size(8, 128) == 0       # N not a multiple of 16
     assert binding.mnnq_packed_size(16, 100) == 0      # K not a multiple of 64
     assert binding.mnnq_packed_size(16, 128, 32) == 0  # group
-    assert binding.mnnq_packed_size(16, 128, 64, 2) == 0  # mode
+    assert binding.mnnq_packed_size(16, 128, 64, 3) == 0  # mode
+    # int8 weights: two nibble planes, each with fp32 step and minimum; K must be a multiple of 128
+    assert binding.mnnq_packed_size(16, 128, 64, 2) == 16 * 128 + 16 * 16 * 2
+    assert binding.mnnq_packed_size(16, 192, 64, 2) == 0
     # float-minimum form: fp32 minimum instead of a one-byte zero point per group
     assert binding.mnnq_packed_size(3584, 18944, 64, 1) == 3584 * 18944 // 2 + 8 * 3584 * (18944 // 64)
     assert binding.mnnq_packed_size(0, 128) == 0 and binding.mnnq_packed_size(16, -64) == 0
@@ -108,12 +111,14 @@ def test_argument_validation_precedes_hip(L):
     lp = L.mnnq_linear_prefill
     assert lp(FAKE, 0, 16, 128, 64, 0, FAKE, FAKE, None, FAKE, None, 0, None) == SHAPE
     assert lp(FAKE, 4, 16, 128, 64, 0, None, FAKE, None, FAKE, None, 0, None) == NULL
-    assert lp(FAKE, 4, 16, 128, 64, 2, FAKE, FAKE, None, FAKE, None, 0, None) == UNSUP
+    assert lp(FAKE, 4, 16, 128, 64, 3, FAKE, FAKE, None, FAKE, None, 0, None) == UNSUP
+    assert lp(FAKE, 4, 16, 192, 64, 2, FAKE, FAKE, None, FAKE, None, 0, None) == UNSUP   # int8 weights: K % 128
     assert lp(FAKE, 4, 16, 128, 64, 0, FAKE, FAKE, None, ODD, None, 0, None) == ALIGN
 
     assert L.mnnq_linear_decode_f16(FAKE, 16, 128, 64, 0, None, None, FAKE, None, 0, None) == NULL
     assert L.mnnq_linear_decode_f16(FAKE, 16, 100, 64, 0, FAKE, None, FAKE, None, 0, None) == SHAPE
     assert L.mnnq_linear_decode_f16(FAKE, 16, 128, 64, 1, FAKE, None, FAKE, None, 0, None) == UNSUP   # float minimum
+    assert L.mnnq_linear_decode_f16(FAKE, 16, 128, 64, 2, FAKE, None, FAKE, None, 0, None) == UNSUP   # int8 weights
     assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 128, 64, 1, FAKE, None, None, FAKE, None, 0, None) == UNSUP
     assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 128, 64, 0, FAKE, None, None, None, None, 0, None) == NULL
     assert L.mnnq_linear_prefill_f16(FAKE, -1, 16, 128, 64, 0, FAKE, None, None, FAKE, None, 0, None) == SHAPE
@@ -123,7 +128,7 @@ def test_argument_validation_precedes_hip(L):
     assert pq(None, FAKE, FAKE, 16, 128, 64, 0, FAKE, 10**9, None) == NULL
     assert pq(FAKE, FAKE, None, 16, 128, 64, 0, FAKE, 10**9, None) == NULL
     assert pq(FAKE, FAKE, FAKE, 16, 96, 64, 0, FAKE, 10**9, None) == SHAPE
-    assert pq(FAKE, FAKE, FAKE, 16, 128, 64, 2, FAKE, 10**9, None) == UNSUP
+    assert pq(FAKE, FAKE, FAKE, 16, 128, 64, 3, FAKE, 10**9, None) == UNSUP
     assert pq(FAKE, FAKE, ODD + 2, 16, 128, 64, 1, FAKE, 10**9, None) == ALIGN   # fp32 minima
     assert pq(ODD, FAKE, FAKE, 16, 128, 64, 0, FAKE, 10**9, None) == ALIGN
     assert pq(FAKE, FAKE, FAKE, 16, 128, 64, 0, FAKE, binding.mnnq_packed_size(16, 128) - 1, None) == SIZE
