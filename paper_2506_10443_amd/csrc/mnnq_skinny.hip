@@ -12,11 +12,11 @@
 //
 // Work split as in the GEMV: a wave owns one row tile and a contiguous chunk range,
 // KSPLIT waves share a row tile and add their partial sums in a fixed order through
-// LDS.  The activations are small (M * K bytes) and stay in L2.  Where 16 rows of them
-// fit in LDS (K <= 4096) a workgroup of 16 waves copies them there once, in the order
-// the A operand is read (STAGED), and shares them between its row tiles; for longer
-// rows each lane loads its A operand - 16 consecutive k of token lane % 16 - straight
-// from L2.
+// LDS.  The activations are small (M * K bytes) and stay in L2: each lane loads its A
+// operand - 16 consecutive k of token lane % 16 - straight from there (skinny_kernel),
+// or, for large layers whose 16 rows fit in LDS (K <= 4096), a persistent workgroup
+// copies them there once and shares them between all its row tiles
+// (skinny_persist_kernel).
 //
 // MFMA lane mapping (A: 16 x 64 tokens x k, B: 64 x 16 k x weight rows, D: 16 x 16):
 //   A: lane l holds token l % 16, k block l / 16;  B: lane l holds weight row l % 16,
@@ -66,16 +66,14 @@ __device__ __forceinline__ v4i unpack_group(uint32_t w0, uint32_t w1, uint32_t z
     return b;
 }
 
-template <int WAVES, int KSPLIT, int UNROLL, bool PREFETCH, bool MINF, bool STAGED>
+template <int WAVES, int KSPLIT, int UNROLL, bool PREFETCH, bool MINF>
 __global__ __launch_bounds__(WAVES * 64) void skinny_kernel(const uint8_t* __restrict__ packed, Layout L, int M,
                                                             const int8_t* __restrict__ xq,
                                                             const float* __restrict__ sx,
                                                             const float* __restrict__ bias,
                                                             float* __restrict__ y)
 {
-    extern __shared__ __align__(16) uint8_t smem[];
-    float* lds_part = reinterpret_cast<float*>(smem);                         // [wave][r][lane]
-    const v4i* lds_a = reinterpret_cast<const v4i*>(smem + WAVES * 4 * 64 * 4);   // STAGED: [C * 8 units][16 tokens]
+    __shared__ float lds_part[WAVES * 4 * 64];   // [wave][r][lane]
     const int64_t C = L.C;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -112,14 +110,8 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_kernel(const uint8_t* __res
             r.z = static_cast<const uint16_t*>(zp)[i * 16];
             r.mn = make_float2(0.0f, 0.0f);
         }
-        if (!STAGED) {
-            r.xa = *reinterpret_cast<const v4i*>(xrow + (c % Cx) * 128);
-            r.xb = (odd_tail && c == C - 1) ? v4i{0, 0, 0, 0}
-                                            : *reinterpret_cast<const v4i*>(xrow + (c % Cx) * 128 + 64);
-        } else {
-            r.xa = v4i{0, 0, 0, 0};
-            r.xb = v4i{0, 0, 0, 0};
-        }
+        r.xa = *reinterpret_cast<const v4i*>(xrow + (c % Cx) * 128);
+        r.xb = (odd_tail && c == C - 1) ? v4i{0, 0, 0, 0} : *reinterpret_cast<const v4i*>(xrow + (c % Cx) * 128 + 64);
         return r;
     };
 
@@ -128,24 +120,6 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_kernel(const uint8_t* __res
     for (int u = 0; u < UNROLL; ++u) {
         if (u < n_chunks) cur[u] = load(u);
         else cur[u] = SkinnyRegs{};
-    }
-
-    if (STAGED) {
-        // The weight loads above are in flight; now the whole workgroup copies the 16 token rows
-        // (tokens past M repeat the last one, k past K is zero) in units of 16 bytes: unit (ku, m)
-        // holds k = 16 ku .. 16 ku + 15 of token m, and lands at index ku * 16 + m.
-        v4i* dst = reinterpret_cast<v4i*>(smem + WAVES * 4 * 64 * 4);
-        const int units = (int)C * 8 * 16;
-        const int valid_ku = (int)(L.K / 16);
-        const int row_ku = (int)(L.Kx / 16);
-        for (int u = tid; u < units; u += WAVES * 64) {
-            const int m = u & 15, ku = u >> 4;
-            v4i v = {0, 0, 0, 0};
-            if (ku < valid_ku)
-                v = *reinterpret_cast<const v4i*>(xq + (int64_t)(m < M ? m : M - 1) * L.Kx + (ku % row_ku) * 16);
-            dst[u] = v;
-        }
-        __syncthreads();
     }
 
     const v4i zero = {0, 0, 0, 0};
@@ -164,12 +138,7 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_kernel(const uint8_t* __res
         for (int u = 0; u < UNROLL; ++u) {
             if (i + u < n_chunks) {
                 const SkinnyRegs& r = cur[u];
-                v4i xa = r.xa, xb = r.xb;
-                if (STAGED) {
-                    const int64_t c = c0 + i + u;
-                    xa = lds_a[((c * 8 + kb) << 4) + row];
-                    xb = lds_a[((c * 8 + 4 + kb) << 4) + row];
-                }
+                const v4i xa = r.xa, xb = r.xb;
                 const v4i b0 = unpack_group<MINF>(r.w.x, r.w.y, r.z & 0xffu);
                 const v4i b1 = unpack_group<MINF>(r.w.z, r.w.w, r.z >> 8);
                 const v4i d0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, b0, zero, 0, 0, 0);
@@ -216,13 +185,147 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_kernel(const uint8_t* __res
     }
 }
 
-template <int WAVES, int KSPLIT, int UNROLL, bool PREFETCH, bool STAGED>
-int launch_cfg(const uint8_t* packed, const Layout& L, int M, const int8_t* xq, const float* sx, const float* bias,
-               float* y, hipStream_t st)
+// Large layers with rows of up to 4096 values: a persistent workgroup of 8 waves copies the
+// 16 token rows into LDS once, in the order the A operand is read, and then walks over its
+// share of the row tiles (8 / KSPLIT at a time).  Every wave's chunk range (<= 8 chunks) is
+// held in registers; as soon as a chunk has been consumed, the same chunk of the next step is
+// fetched into its registers, so a wave keeps its whole range in flight all the time.
+struct WeightRegs {
+    u32x4 w;
+    float2 s;
+    uint32_t z;
+    float2 mn;
+};
+
+template <int KSPLIT, bool MINF>
+__global__ __launch_bounds__(512, 2) void skinny_persist_kernel(const uint8_t* __restrict__ packed, Layout L, int M,
+                                                             const int8_t* __restrict__ xq,
+                                                             const float* __restrict__ sx,
+                                                             const float* __restrict__ bias,
+                                                             float* __restrict__ y)
 {
-    constexpr int tiles_per_wg = WAVES / KSPLIT;
-    const int64_t blocks = (L.T + tiles_per_wg - 1) / tiles_per_wg;
-    const size_t smem = (size_t)WAVES * 4 * 64 * 4 + (STAGED ? (size_t)L.C * 8 * 16 * 16 : 0);
+    constexpr int WAVES = 8, UNROLL = 8;
+    extern __shared__ __align__(16) uint8_t smem[];
+    float* lds_part = reinterpret_cast<float*>(smem);                                 // [wave][r][lane]
+    v4i* lds_a = reinterpret_cast<v4i*>(smem + WAVES * 4 * 64 * 4);                   // [C * 8 units][16 tokens]
+    const int64_t C = L.C;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int row = lane & 15;
+    const int kb = lane >> 4;
+    constexpr int TILES_PER_STEP = WAVES / KSPLIT;
+    const int ks = wave % KSPLIT;
+    const int64_t c0 = C * ks / KSPLIT;
+    const int64_t c1 = C * (ks + 1) / KSPLIT;
+    const int n_own = (int)(c1 - c0);
+    const int64_t n_steps = (L.T + TILES_PER_STEP - 1) / TILES_PER_STEP;
+
+    // One chunk of this wave's range for the given step (nothing past the last step / tile).
+    auto load_chunk = [&](int64_t step, int u) {
+        WeightRegs r{};
+        const int64_t tile = step * TILES_PER_STEP + wave / KSPLIT;
+        if (step < n_steps && tile < L.T && u < n_own) {
+            const int64_t ci = (tile * C + c0 + u);
+            r.w = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(packed) + ci * 64 + lane);
+            r.s = (reinterpret_cast<const float2*>(packed + L.scales_off()) + ci * 16)[row];
+            if (MINF) r.mn = (reinterpret_cast<const float2*>(packed + L.zeros_off()) + ci * 16)[row];
+            else r.z = (reinterpret_cast<const uint16_t*>(packed + L.zeros_off()) + ci * 16)[row];
+        }
+        return r;
+    };
+
+    int64_t step = blockIdx.x;
+    WeightRegs cur[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) cur[u] = load_chunk(step, u);
+
+    // The first weights are in flight; copy the token rows (tokens past M repeat the last one,
+    // k past K is zero) in units of 16 bytes: unit (ku, m) = k 16 ku .. 16 ku + 15 of token m,
+    // stored at index ku * 16 + m.
+    {
+        const int units = (int)C * 8 * 16;
+        const int valid_ku = (int)(L.K / 16);
+        const int row_ku = (int)(L.Kx / 16);
+        for (int u = tid; u < units; u += WAVES * 64) {
+            const int m = u & 15, ku = u >> 4;
+            v4i v = {0, 0, 0, 0};
+            if (ku < valid_ku)
+                v = *reinterpret_cast<const v4i*>(xq + (int64_t)(m < M ? m : M - 1) * L.Kx + (ku % row_ku) * 16);
+            lds_a[u] = v;
+        }
+    }
+    __syncthreads();
+
+    const v4i zero = {0, 0, 0, 0};
+    const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+    // All waves of a workgroup share `step`, so the workgroup-wide barriers below are uniform.
+    for (; step < n_steps; step += gridDim.x) {
+        const int64_t tile = step * TILES_PER_STEP + wave / KSPLIT;
+        const bool active = tile < L.T;
+        float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const WeightRegs r = cur[u];
+            // the registers of this chunk are free: fetch the same chunk of the next step into them
+            cur[u] = load_chunk(step + gridDim.x, u);
+            if (active && u < n_own) {
+                const int64_t c = c0 + u;
+                const v4i xa = lds_a[((c * 8 + kb) << 4) + row];
+                const v4i xb = lds_a[((c * 8 + 4 + kb) << 4) + row];
+                const v4i b0 = unpack_group<MINF>(r.w.x, r.w.y, r.z & 0xffu);
+                const v4i b1 = unpack_group<MINF>(r.w.z, r.w.w, r.z >> 8);
+                const v4i d0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, b0, zero, 0, 0, 0);
+                const v4i d1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(xb, b1, zero, 0, 0, 0);
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    acc[rr] = fmaf(r.s.x, (float)d0[rr], acc[rr]);
+                    acc[rr] = fmaf(r.s.y, (float)d1[rr], acc[rr]);
+                }
+                if (MINF) {
+                    const v4i x0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, ones, zero, 0, 0, 0);
+                    const v4i x1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(xb, ones, zero, 0, 0, 0);
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) {
+                        acc[rr] = fmaf(r.mn.x, (float)x0[rr], acc[rr]);
+                        acc[rr] = fmaf(r.mn.y, (float)x1[rr], acc[rr]);
+                    }
+                }
+            }
+        }
+        if (KSPLIT > 1) {
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) lds_part[(wave * 4 + rr) * 64 + lane] = acc[rr];
+            __syncthreads();
+            if (ks == 0) {
+#pragma unroll
+                for (int j = 1; j < KSPLIT; ++j)
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) acc[rr] += lds_part[((wave + j) * 4 + rr) * 64 + lane];
+            }
+            __syncthreads();   // the partial sums are read before the next round overwrites them
+        }
+        if (active && ks == 0) {
+            const int64_t n = tile * kTileN + row;
+            const float b = bias ? bias[n] : 0.0f;
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int m = kb * 4 + rr;
+                if (m < M) y[(int64_t)m * L.N + n] = fmaf(acc[rr], sx[m], b);
+            }
+        }
+    }
+}
+
+template <int KSPLIT>
+int launch_persist(const uint8_t* packed, const Layout& L, int M, const int8_t* xq, const float* sx, const float* bias,
+                   float* y, hipStream_t st)
+{
+    constexpr int tiles_per_step = 8 / KSPLIT;
+    const int64_t n_steps = (L.T + tiles_per_step - 1) / tiles_per_step;
+    // Two workgroups per CU (LDS: two copies of the activations; registers: 16 waves).
+    const int64_t grid = n_steps < 2 * (int64_t)num_cus() ? n_steps : 2 * (int64_t)num_cus();
+    const size_t smem = (size_t)8 * 4 * 64 * 4 + (size_t)L.C * 8 * 16 * 16;
     auto launch = [&](auto kern) -> int {
         if (smem > 64 * 1024) {
             // More than 64 KiB of dynamic LDS has to be allowed once per kernel and device.
@@ -231,24 +334,40 @@ int launch_cfg(const uint8_t* packed, const Layout& L, int M, const int8_t* xq, 
             MNNQ_HIP_TRY(hipGetDevice(&dev));
             if (allowed_dev != dev) {
                 MNNQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024));
                 allowed_dev = dev;
             }
         }
-        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(WAVES * 64), smem, st, packed, L, M, xq, sx, bias, y);
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), smem, st, packed, L, M, xq, sx, bias, y);
         MNNQ_HIP_TRY(hipGetLastError());
         return MNNQ_OK;
     };
-    if (L.minf) return launch(skinny_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, true, STAGED>);
-    return launch(skinny_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, false, STAGED>);
+    if (L.minf) return launch(skinny_persist_kernel<KSPLIT, true>);
+    return launch(skinny_persist_kernel<KSPLIT, false>);
+}
+
+template <int WAVES, int KSPLIT, int UNROLL, bool PREFETCH>
+int launch_cfg(const uint8_t* packed, const Layout& L, int M, const int8_t* xq, const float* sx, const float* bias,
+               float* y, hipStream_t st)
+{
+    constexpr int tiles_per_wg = WAVES / KSPLIT;
+    const int64_t blocks = (L.T + tiles_per_wg - 1) / tiles_per_wg;
+    if (L.minf)
+        hipLaunchKernelGGL((skinny_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, true>), dim3((unsigned)blocks),
+                           dim3(WAVES * 64), 0, st, packed, L, M, xq, sx, bias, y);
+    else
+        hipLaunchKernelGGL((skinny_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, false>), dim3((unsigned)blocks),
+                           dim3(WAVES * 64), 0, st, packed, L, M, xq, sx, bias, y);
+    MNNQ_HIP_TRY(hipGetLastError());
+    return MNNQ_OK;
 }
 
 }  // namespace
 
 // The smallest number of waves per row tile (up to 8) for which a wave's chunk range fits in
 // its registers, so that all loads are issued at once; longer rows use a prefetching loop.
-// Large layers with rows of up to 4096 values take the staged variant: 16 waves, i.e.
-// 16 / KSPLIT row tiles, share one copy of the activations in LDS.
+// Large layers with rows of up to 4096 values take the persistent variant, which shares one
+// LDS copy of the activations between all the row tiles a workgroup processes.
 int launch_skinny(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
                   const float* bias, float* y, hipStream_t st)
 {
@@ -267,9 +386,9 @@ int launch_skinny(const uint8_t* packed, const Layout& L, int64_t M, const int8_
     const int m = (int)M;
 #define MNNQ_CFG(W, K)                                                                                 \
     if (ks == K) {                                                                                     \
-        if (staged) return launch_cfg<16, K, 8, false, true>(packed, L, m, xq, sx, bias, y, st);       \
-        return prefetch ? launch_cfg<W, K, 4, true, false>(packed, L, m, xq, sx, bias, y, st)          \
-                        : launch_cfg<W, K, 8, false, false>(packed, L, m, xq, sx, bias, y, st);        \
+        if (staged) return launch_persist<K>(packed, L, m, xq, sx, bias, y, st);                       \
+        return prefetch ? launch_cfg<W, K, 4, true>(packed, L, m, xq, sx, bias, y, st)                 \
+                        : launch_cfg<W, K, 8, false>(packed, L, m, xq, sx, bias, y, st);               \
     }
     MNNQ_CFG(4, 1) MNNQ_CFG(4, 2) MNNQ_CFG(4, 4) MNNQ_CFG(8, 8)
 #undef MNNQ_CFG
