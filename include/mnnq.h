@@ -17,6 +17,11 @@
  *   - Return value: MNNQ_OK (0) or a negative mnnq_status.  All argument
  *     checks run before the first HIP call, so they also work on a machine
  *     without a GPU.  NaN / Inf in W or x: undefined result, no error.
+ *   - Limits (MNNQ_ERR_UNSUPPORTED beyond them): N and K up to 2^24.  Decode calls: K up to
+ *     49152 (30720 with fp16 activations; for int8 weights half of that), the row is staged
+ *     in LDS.  Prefill calls address with 32-bit byte offsets: (M + 256) * K, the packed
+ *     matrix and (M + 256) * N * 4 must each stay below 2 GiB (twice K with fp16
+ *     activations); split larger batches along M.  mnnq_linear_acc_debug: M up to 65535.
  *   - Only group == 64 is implemented.  K must be a multiple of 64 and N a
  *     multiple of 16.  `mode` selects the weight quantizer (mnnq_mode); a packed
  *     buffer must be used with the mode it was written with.
@@ -35,7 +40,7 @@ typedef enum {
     MNNQ_OK = 0,
     MNNQ_ERR_NULL = -1,        /* a required pointer is NULL */
     MNNQ_ERR_SHAPE = -2,       /* M, N or K <= 0, or K not a multiple of the group */
-    MNNQ_ERR_UNSUPPORTED = -3, /* group != 64, unknown mode, N not a multiple of 16 */
+    MNNQ_ERR_UNSUPPORTED = -3, /* group != 64, unknown mode, N not a multiple of 16, or a size limit (see Limits) */
     MNNQ_ERR_SIZE = -4,        /* packed / workspace buffer too small */
     MNNQ_ERR_ALIGN = -5,       /* a pointer is not 16-byte aligned */
     MNNQ_ERR_HIP = -6          /* a HIP call failed; see mnnq_last_hip_error() */
