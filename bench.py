@@ -71,7 +71,7 @@ def main() -> int:
     args = ap.parse_args()
     args.fused_decode = not args.two_call_decode
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU; the path shards by output rows (see DESIGN.md) "
+        print("bench.py: this build runs on ONE GPU; the path would shard by output rows "
               "but no multi-GPU figure is produced.  Run with --gpus 1.", file=sys.stderr)
         return 2
 

@@ -114,7 +114,7 @@ def activations_f16(M: int, K: int, seed: int, outliers: bool = False) -> np.nda
 
 
 def config1():
-    """Single decode layer of BASELINE config 1: W [8960, 1536], x [1, 1536],
+    """Single decode layer of the first benchmark configuration: W [8960, 1536], x [1, 1536],
     plain N(0, 1) activations, seed 0."""
     return weights(8960, 1536, 0), activations(1, 1536, 0, outliers=False)
 

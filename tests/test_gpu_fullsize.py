@@ -1,4 +1,4 @@
-"""GPU parity at the benchmark's full layer sizes, in the launch configuration
+"""GPU parity at the full layer sizes of the benchmark configurations, in the launch configuration
 bench.py times (same entry points, same shapes, q|k|v and gate|up concatenated).
 
 Codes, zero points, scales and int8 activations are compared in full (bit-exact).

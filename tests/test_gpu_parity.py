@@ -172,7 +172,7 @@ def test_decode_matches_oracle(N, K):
 
 
 def test_config1_single_layer_seed0():
-    # BASELINE config 1: x [1,1536] ~ N(0,1), W [8960,1536] ~ N(0,0.02), seed 0, whole path on the GPU.
+    # First benchmark configuration: x [1,1536] ~ N(0,1), W [8960,1536] ~ N(0,0.02), seed 0, whole path on the GPU.
     W, x = synth.config1()
     q, s, z = oracle.quant_weights(W)
     xq_o, sx_o, _ = oracle.quant_act(x)
