@@ -173,11 +173,12 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
         scale = (amax == 0.0f) ? 0.0f : amax / 127.0f;
         const float inv = (amax == 0.0f) ? 0.0f : 1.0f / scale;
         const float thr = (inv < 1.0e37f && scale > 1.0e-30f) ? 6.0e-5f : 2.0f;
-        for (int64_t i = tid; i < dwords; i += THREADS) {
+        // One dword of the padded row: quantize, store, and add up its 16-byte block (the four dwords
+        // of a block sit in four neighbouring lanes).
+        auto put = [&](int64_t i, const float4 xv) {
             int v = 0;
-            if (i < valid && scale != 0.0f) v = quant4_fast(i < row_dw && i == tid ? first : x4[i % row_dw], scale, inv, thr);
+            if (i < valid && scale != 0.0f) v = quant4_fast(xv, scale, inv, thr);
             lds_xd[i] = v;
-            // sum of the 16-byte block: its four dwords sit in four neighbouring lanes
             int sum = __builtin_amdgcn_sdot4(v, 0x01010101, 0, false);
             sum += __shfl_xor(sum, 1, 64);
             sum += __shfl_xor(sum, 2, 64);
@@ -185,7 +186,16 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
                 const int64_t u = i / 4, c = u / 8;
                 lds_xs[c * 8 + (int)(u % 4) * 2 + (int)(u % 8) / 4] = sum;
             }
+        };
+        // The first step reuses the values read for the maximum when they are the row's own; it is
+        // kept apart from the loop so that `first` never has to be addressable.
+        // (an if, not a conditional expression: that would select between two addresses)
+        if (tid < dwords) {
+            float4 xv = first;
+            if (tid >= row_dw) xv = x4[tid % row_dw];
+            put(tid, xv);
         }
+        for (int64_t i = tid + THREADS; i < dwords; i += THREADS) put(i, x4[i % row_dw]);
         __syncthreads();
     } else {
         // This wave's chunks only, in 16-byte units: unit u of the region is unit c0 * 8 + u of the row.
