@@ -31,8 +31,8 @@ G = 64
 # HBM traffic per launch (bytes, mean over a pass) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this file, scaled by a copy kernel of known size; see profiles/ for the runs.  None = not measured
 # for the current kernels.
-PREFILL_TRAFFIC_BYTES = 169.9e6   # profiles/bench_qwen2-7b_hbm_traffic.txt
-DECODE_TRAFFIC_BYTES = 33.8e6     # same file
+PREFILL_TRAFFIC_BYTES = 170.8e6   # profiles/bench_qwen2-7b_hbm_traffic.txt
+DECODE_TRAFFIC_BYTES = 33.9e6     # same file
 
 
 GROUP_PARAM_BYTES = 5    # fp32 scale + 1-byte zero point; 8 with an fp32 group minimum (--weight-mode minfloat);
