@@ -349,6 +349,7 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
                             for (int r = 0; r < 4; ++r) yacc[i][j][r] += red[slot + ((i * TN + j) * 4 + r) * 64];
                 }
             }
+            __syncthreads();                     // part 0 has read the sums: LDS is free for the output stage
             if (kh != 0) return;
         }
         if (!ACC) {
@@ -359,8 +360,8 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
                 __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(sx), 0, (int)(M * 4), kBufFlags);
             const __amdgpu_buffer_rsrc_t rs_bias = __builtin_amdgcn_make_buffer_rsrc(
                 const_cast<float*>(bias), 0, (bias && split == 0) ? (int)(L.N * 4) : 0, kBufFlags);
-            const __amdgpu_buffer_rsrc_t rs_y =
-                __builtin_amdgcn_make_buffer_rsrc(y, 0, (int)(uint32_t)(M * L.N * 4), kBufFlags);
+            const int y_bytes = (int)(uint32_t)(M * L.N * 4);
+            const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(y, 0, y_bytes, kBufFlags);
             const int Nb = (int)L.N * 4;                       // bytes per output row
             const int row0 = (int)m0 + wm * WM;                // first row of this wave
             const int nt0 = rt0 + wn * TN;                     // first row tile (16 outputs) of this wave
@@ -368,23 +369,55 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
 #pragma unroll
             for (int j = 0; j < TN; ++j)
                 bj[j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_bias, col * 4, (nt0 + j) * 64, 0));
-            const int y_voff = kb * 4 * Nb + col * 4;
+            if (S == 1) {
+                // The 16 x (16 TN) block of one m-tile goes through a private LDS patch of the wave
+                // (rows padded by 4 floats: conflict-free both ways) and leaves as 128-bit stores of
+                // whole row segments - a quarter of the store instructions and full cache lines.
+                // LDS operations of one wave complete in order, so the patch needs no barrier of its
+                // own; the barrier in front makes sure no wave still reads operands where it lies.
+                static_assert(TN == 4, "a lane stores one 16-byte unit of a 64-column row segment");
+                constexpr int RS = 16 * TN + 4;                // floats per patch row
+                if (KS == 1) __syncthreads();
+                float* patch = reinterpret_cast<float*>(lds_all) + wave * (16 * RS);
+                float* wr = patch + (kb * 4) * RS + col;
+                const float* rd = patch + kb * RS + col * 4;  // + 4 p rows
+                // a lane's 16-byte unit lies in row tile nt0 + col / 4; units past N are sent out of range
+                const int y_voff = (nt0 + (col >> 2) < (int)L.T) ? kb * Nb + col * 16 : y_bytes;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                float sxr[4];
+                for (int i = 0; i < TM; ++i) {
+                    float sxr[4];
 #pragma unroll
-                for (int rr = 0; rr < 4; ++rr)
-                    sxr[rr] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_sx, kb * 16, (row0 + i * 16 + rr) * 4, 0));
+                    for (int rr = 0; rr < 4; ++rr)
+                        sxr[rr] = __uint_as_float(
+                            __builtin_amdgcn_raw_buffer_load_b32(rs_sx, kb * 16, (row0 + i * 16 + rr) * 4, 0));
 #pragma unroll
-                for (int rr = 0; rr < 4; ++rr) {
+                    for (int rr = 0; rr < 4; ++rr)
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        if (nt0 + j >= (int)L.T) continue;     // wave-uniform
-                        const float v = fmaf(yacc[i][j][rr], sxr[rr], bj[j]);
-                        if (S == 1) {
-                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs_y, y_voff,
-                                                                      (row0 + i * 16 + rr) * Nb + (nt0 + j) * 64, 0);
-                        } else {
+                        for (int j = 0; j < TN; ++j) wr[rr * RS + j * 16] = fmaf(yacc[i][j][rr], sxr[rr], bj[j]);
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) {
+                        // (read as a struct of floats: the same scalar type as the writes for alias analysis)
+                        const float4 f = *reinterpret_cast<const float4*>(rd + p * 4 * RS);
+                        const v4i v = {(int)__float_as_uint(f.x), (int)__float_as_uint(f.y), (int)__float_as_uint(f.z),
+                                       (int)__float_as_uint(f.w)};
+                        __builtin_amdgcn_raw_buffer_store_b128(v, rs_y, y_voff,
+                                                               (row0 + i * 16 + p * 4) * Nb + nt0 * 64, 0);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    float sxr[4];
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr)
+                        sxr[rr] = __uint_as_float(
+                            __builtin_amdgcn_raw_buffer_load_b32(rs_sx, kb * 16, (row0 + i * 16 + rr) * 4, 0));
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) {
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) {
+                            if (nt0 + j >= (int)L.T) continue;     // wave-uniform
+                            const float v = fmaf(yacc[i][j][rr], sxr[rr], bj[j]);
                             const int64_t m = (int64_t)row0 + i * 16 + kb * 4 + rr;
                             if (m < M) atomicAdd(&y[m * L.N + (int64_t)(nt0 + j) * 16 + col], v);
                         }

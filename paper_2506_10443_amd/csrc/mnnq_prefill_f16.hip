@@ -290,8 +290,8 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(rs), 0, rs ? (int)(M * 4) : 0, kBufFlags);
     const __amdgpu_buffer_rsrc_t rs_bias =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(bias), 0, bias ? (int)(L.N * 4) : 0, kBufFlags);
-    const __amdgpu_buffer_rsrc_t rs_y =
-        __builtin_amdgcn_make_buffer_rsrc(y, 0, (int)(uint32_t)(M * L.N * 4), kBufFlags);
+    const int y_bytes = (int)(uint32_t)(M * L.N * 4);
+    const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(y, 0, y_bytes, kBufFlags);
     const int Nb = (int)L.N * 4;                       // bytes per output row
     const int row0 = (int)m0 + wm * WM;                // first row of this wave
     const int nt0 = rt0 + wn * TN;                     // first row tile (16 outputs) of this wave
@@ -299,7 +299,18 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
 #pragma unroll
     for (int j = 0; j < TN; ++j)
         bj[j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_bias, col * 4, (nt0 + j) * 64, 0));
-    const int y_voff = kb * 4 * Nb + col * 4;
+    // The 16 x (16 TN) block of one m-tile goes through a private LDS patch of the wave (rows
+    // padded by 4 floats: conflict-free both ways) and leaves as 128-bit stores of whole row
+    // segments.  LDS operations of one wave complete in order, so the patch needs no barrier of
+    // its own; the barrier in front makes sure no wave still reads operands where it lies.
+    static_assert(TN == 4, "a lane stores one 16-byte unit of a 64-column row segment");
+    constexpr int RS = 16 * TN + 4;                    // floats per patch row
+    __syncthreads();
+    float* patch = reinterpret_cast<float*>(lds) + wave * (16 * RS);
+    float* wr = patch + (kb * 4) * RS + col;
+    const float* rd = patch + kb * RS + col * 4;       // + 4 p rows
+    // a lane's 16-byte unit lies in row tile nt0 + col / 4; units past N are sent out of range
+    const int y_voff = (nt0 + (col >> 2) < (int)L.T) ? kb * Nb + col * 16 : y_bytes;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         float rsr[4];
@@ -309,14 +320,16 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
             if (!rs) rsr[rr] = 1.0f;
         }
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
+        for (int rr = 0; rr < 4; ++rr)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                if (nt0 + j >= (int)L.T) continue;     // wave-uniform
-                const float v = fmaf(yacc[i][j][rr], rsr[rr], bj[j]);
-                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs_y, y_voff,
-                                                      (row0 + i * 16 + rr) * Nb + (nt0 + j) * 64, 0);
-            }
+            for (int j = 0; j < TN; ++j) wr[rr * RS + j * 16] = fmaf(yacc[i][j][rr], rsr[rr], bj[j]);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            // (read as a struct of floats: the same scalar type as the writes for alias analysis)
+            const float4 f = *reinterpret_cast<const float4*>(rd + p * 4 * RS);
+            const v4i v = {(int)__float_as_uint(f.x), (int)__float_as_uint(f.y), (int)__float_as_uint(f.z),
+                           (int)__float_as_uint(f.w)};
+            __builtin_amdgcn_raw_buffer_store_b128(v, rs_y, y_voff, (row0 + i * 16 + p * 4) * Nb + nt0 * 64, 0);
         }
     }
 }
