@@ -45,7 +45,7 @@ def _load():
                          "orc_linear_w4a16", "orc_linear_w4a8_sampled", "orc_linear_w4a16_sampled",
                          "orc_quant_weights_minf", "orc_dequant_minf", "orc_linear_w4a8_minf",
                          "orc_linear_w4a8_minf_sampled", "orc_quant_weights8", "orc_linear_w8a8",
-                         "orc_linear_w8a8_sampled"):
+                         "orc_linear_w8a8_sampled", "orc_linear_a16_minf", "orc_linear_a16_minf_sampled"):
                 getattr(_lib, name).restype = None
             _lib.orc_omp_enabled.restype = ctypes.c_int
     return _lib
@@ -281,3 +281,36 @@ def linear_w8a8_sampled(xq, sx, q, s, wmin, ms, ns, bias=None, want_acc=True):
     _load().orc_linear_w8a8_sampled(_p(xq), _p(sx), _p(q), _p(s), _p(wmin), _p(bias),
                                     _i64(M), _i64(N), _i64(K), _p(ms), _p(ns), _i64(cnt), _p(acc), _p(y))
     return acc, y
+
+
+# ---- fp16 activations on float-minimum weights, 4- or 8-bit codes (O11)
+
+def linear_a16_minf(x16, q, s, wmin, bias=None):
+    """O11.  x16 fp16 [M,K]; q codes (0..15 or 0..255); returns y fp32 [M,N]."""
+    x16 = _c(x16, np.float16)
+    q = _c(q, np.uint8); s = _c(s, np.float32); wmin = _c(wmin, np.float32)
+    if bias is not None:
+        bias = _c(bias, np.float32)
+    M, K = x16.shape
+    N = q.shape[0]
+    assert q.shape[1] == K and K % GROUP == 0
+    y = np.empty((M, N), np.float32)
+    _load().orc_linear_a16_minf(_p(x16.view(np.uint16)), _p(q), _p(s), _p(wmin), _p(bias),
+                                _i64(M), _i64(N), _i64(K), _p(y))
+    return y
+
+
+def linear_a16_minf_sampled(x16, q, s, wmin, ms, ns, bias=None):
+    """O11 on the listed (m, n) pairs only: y [count]."""
+    x16 = _c(x16, np.float16)
+    q = _c(q, np.uint8); s = _c(s, np.float32); wmin = _c(wmin, np.float32)
+    ms = _c(ms, np.int64); ns = _c(ns, np.int64)
+    if bias is not None:
+        bias = _c(bias, np.float32)
+    M, K = x16.shape
+    N = q.shape[0]
+    cnt = ms.shape[0]
+    y = np.empty((cnt,), np.float32)
+    _load().orc_linear_a16_minf_sampled(_p(x16.view(np.uint16)), _p(q), _p(s), _p(wmin), _p(bias),
+                                        _i64(M), _i64(N), _i64(K), _p(ms), _p(ns), _i64(cnt), _p(y))
+    return y

@@ -12,7 +12,8 @@
  *     the integer-zero-point form the benchmark configurations name:
  *     group of 64 along K, scale = (max - min)/15, zero = round(-min/scale);
  *     and, second, exactly as Eq. 1 is printed, with the group minimum kept as
- *     a float offset (O6..O8 below).
+ *     a float offset (O6..O8 below; O9, O10 the same with 8-bit codes; O11 these
+ *     weights against fp16 activations).
  *   - Activation codes: Section 4.2 says activations are quantized to int8 at
  *     run time; the configurations fix per-token symmetric, scale = max|x|/127.
  *   - Linear: Section 5.1 notation, activations [e, l] x weights [h, l] ->
@@ -414,6 +415,53 @@ void orc_linear_w8a8_sampled(const int8_t *xq, const float *sx,
                              int32_t *acc, float *y)
 {
     orc_linear_w4a8_minf_sampled(xq, sx, q, s, wmin, bias, M, N, K, ms, ns, count, acc, y);
+}
+
+/* O11: fp16 activations on float-minimum weights (Section 4.2: the GPU path combines the
+ * quantized weights with fp16 activations; Eq. 1 gives the weight a code stands for).
+ *   y[m,n] = sum_k float(x16[m,k]) * (q[n,k] * s[n,g] + wmin[n,g]) (+ bias[n])
+ * for 4-bit (0..15) and 8-bit (0..255) codes alike; every product and the sum in binary64,
+ * rounded once. */
+void orc_linear_a16_minf(const uint16_t *x16,
+                         const uint8_t *q, const float *s, const float *wmin,
+                         const float *bias, int64_t M, int64_t N, int64_t K, float *y)
+{
+    const int64_t G = K / ORC_GROUP;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t m = 0; m < M; ++m) {
+            double sum = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                const int64_t g = k / ORC_GROUP;
+                const double what = (double)q[n * K + k] * (double)s[n * G + g] + (double)wmin[n * G + g];
+                sum += (double)orc_half_to_float(x16[m * K + k]) * what;
+            }
+            if (bias) sum += (double)bias[n];
+            y[m * N + n] = (float)sum;
+        }
+    }
+}
+
+/* Sampled (m,n) pairs of O11. */
+void orc_linear_a16_minf_sampled(const uint16_t *x16,
+                                 const uint8_t *q, const float *s, const float *wmin,
+                                 const float *bias, int64_t M, int64_t N, int64_t K,
+                                 const int64_t *ms, const int64_t *ns, int64_t count, float *y)
+{
+    const int64_t G = K / ORC_GROUP;
+    (void)M; (void)N;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < count; ++i) {
+        const int64_t m = ms[i], n = ns[i];
+        double sum = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            const int64_t g = k / ORC_GROUP;
+            const double what = (double)q[n * K + k] * (double)s[n * G + g] + (double)wmin[n * G + g];
+            sum += (double)orc_half_to_float(x16[m * K + k]) * what;
+        }
+        if (bias) sum += (double)bias[n];
+        y[i] = (float)sum;
+    }
 }
 
 int orc_omp_enabled(void)
