@@ -65,6 +65,9 @@ def main() -> int:
     ap.add_argument("--weight-mode", default="zp", choices=["zp", "minfloat", "int8"],
                     help="weight quantizer: int4 with an integer zero point (the benchmark configuration), int4 "
                          "as Eq. 1 is printed (float group minimum), or int8 weights (float group minimum)")
+    ap.add_argument("--act16", action="store_true",
+                    help="also time the fp16-activation entry points (W4A16 / W8A16) per layer: per_layer "
+                         "gains decode16_* (GB/s of their algorithmic bytes) and prefill16_* (TFLOP/s)")
     ap.add_argument("--two-call-decode", action="store_true",
                     help="decode pass calls mnnq_quant_act + mnnq_linear_decode per layer instead of "
                          "mnnq_linear_decode_fused (fp32 row in, quantizer inside the call)")
@@ -289,6 +292,30 @@ def main() -> int:
             t = time_launches([lambda: B.mnnq_linear_decode(lm[0], lm[1], lm[2], xq, sx, out=y, mode=wmode)] * 4, 4)
             per_layer["decode_lm_head"] = {"us": round(t * 1e3, 2),
                                            "gbs": round(decode_bytes(lm[1], lm[2]) / (t * 1e-3) / 1e9, 1)}
+
+    # ---- fp16 activations on the same packed weights (reported beside the target path, not part of `value`)
+    if args.act16:
+        for name, N, K in layers:
+            if do_pre:
+                x16 = io_pre[name][0].to(torch.float16)
+                y = io_pre[name][3]
+                lay = [(lambda p=packed[name][b], N=N, K=K, x16=x16, y=y:
+                        B.mnnq_linear_prefill_f16(p, N, K, x16, out=y, mode=wmode)) for b in range(n_blocks)]
+                t = time_launches(lay, 2)
+                per_layer["prefill16_" + name] = {"us": round(t * 1e3, 2),
+                                                  "tflops": round(prefill_ops(M_pre, N, K) / (t * 1e-3) / 1e12, 1)}
+            if do_dec:
+                x16 = io_dec[name][0].to(torch.float16)
+                y = io_dec[name][3]
+                lay = [(lambda p=packed[name][b], N=N, K=K, x16=x16, y=y:
+                        B.mnnq_linear_decode_f16(p, N, K, x16[0], out=y[0], mode=wmode)) for b in range(n_blocks)]
+                try:
+                    t = time_launches(lay, 4)
+                except B.MnnqError:      # the fp16 row of this layer does not fit the GEMV's LDS staging
+                    per_layer["decode16_" + name] = None
+                    continue
+                per_layer["decode16_" + name] = {"us": round(t * 1e3, 2),
+                                                 "gbs": round((decode_bytes(N, K) + K) / (t * 1e-3) / 1e9, 1)}
 
     # ---- the same decode pass through the fused entry point (quantizer inside the GEMV), for comparison
     dec_other = None

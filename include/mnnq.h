@@ -18,8 +18,8 @@
  *     checks run before the first HIP call, so they also work on a machine
  *     without a GPU.  NaN / Inf in W or x: undefined result, no error.
  *   - Limits (MNNQ_ERR_UNSUPPORTED beyond them): N and K up to 2^24.  Decode calls: K up to
- *     49152 (30720 with fp16 activations; for int8 weights half of that), the row is staged
- *     in LDS.  Prefill calls address with 32-bit byte offsets: (M + 256) * K, the packed
+ *     49152 (with fp16 activations 30720, or 27648 in the float-minimum modes; for int8
+ *     weights half of these), the row is staged in LDS.  Prefill calls address with 32-bit byte offsets: (M + 256) * K, the packed
  *     matrix and (M + 256) * N * 4 must each stay below 2 GiB (twice K with fp16
  *     activations); split larger batches along M.  mnnq_linear_acc_debug: M up to 65535.
  *   - Only group == 64 is implemented.  K must be a multiple of 64 and N a
@@ -143,8 +143,10 @@ int mnnq_linear_prefill(const void *packed, int64_t M, int64_t N, int64_t K, int
                         const int8_t *xq, const float *sx, const float *bias, float *y,
                         void *workspace, size_t workspace_bytes, void *stream);
 
-/* W4A16 variants (Section 4.2: int4 weights with fp16 activations on GPUs):
- *   y[m,n] = sum_k float(x16[m,k]) * (q[n,k] - zero[n,g]) * scale[n,g] (+ bias[n]),
+/* fp16-activation variants (Section 4.2: quantized weights with fp16 activations on GPUs;
+ * W4A16, and W8A16 with mode MNNQ_W8_MIN_FLOAT):
+ *   y[m,n] = sum_k float(x16[m,k]) * w^[n,k] (+ bias[n]),  w^ the weight the stored code
+ * stands for in the packed buffer's mode ((q - zero) * scale, or q * step + min),
  * fp32 accumulation.  x16: IEEE binary16 bits, [K] resp. [M, K]. */
 int mnnq_linear_decode_f16(const void *packed, int64_t N, int64_t K, int group, int mode,
                            const uint16_t *x16, const float *bias, float *y,

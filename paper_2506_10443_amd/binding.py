@@ -182,25 +182,27 @@ def mnnq_linear_prefill(packed, N: int, K: int, xq, sx, bias=None, out=None, mod
     return y
 
 
-def mnnq_linear_decode_f16(packed, N: int, K: int, x16, bias=None, out=None):
-    """One token, W4A16: x16 fp16 [K] -> y f32 [N]."""
+def mnnq_linear_decode_f16(packed, N: int, K: int, x16, bias=None, out=None, mode: int = MODE_W4_ZP_INT):
+    """One token, fp16 activations (W4A16; W8A16 with MODE_W8_MIN_FLOAT): x16 fp16 [K] -> y f32 [N]."""
     _dev(packed, torch.uint8, "packed"); _dev(x16, torch.float16, "x16")
     if x16.numel() != K:
         raise ValueError("x16 must hold K values")
     y = torch.empty((N,), dtype=torch.float32, device=packed.device) if out is None else out
-    _check(lib().mnnq_linear_decode_f16(_ptr(packed), N, K, GROUP, MODE_W4_ZP_INT, _ptr(x16), _ptr(bias),
+    _check(lib().mnnq_linear_decode_f16(_ptr(packed), N, K, GROUP, mode, _ptr(x16), _ptr(bias),
                                         _ptr(y), None, 0, _stream()), "mnnq_linear_decode_f16")
     return y
 
 
-def mnnq_linear_prefill_f16(packed, N: int, K: int, x16, bias=None, out=None, row_scale=None):
-    """M tokens, W4A16: x16 fp16 [M,K] -> y f32 [M,N]; row_scale f32 [M] optional."""
+def mnnq_linear_prefill_f16(packed, N: int, K: int, x16, bias=None, out=None, row_scale=None,
+                            mode: int = MODE_W4_ZP_INT):
+    """M tokens, fp16 activations (W4A16; W8A16 with MODE_W8_MIN_FLOAT): x16 fp16 [M,K] -> y f32 [M,N];
+    row_scale f32 [M] optional."""
     _dev(packed, torch.uint8, "packed"); _dev(x16, torch.float16, "x16")
     M = x16.shape[0]
     if x16.shape[1] != K:
         raise ValueError("x16 must be [M,K]")
     y = torch.empty((M, N), dtype=torch.float32, device=packed.device) if out is None else out
-    _check(lib().mnnq_linear_prefill_f16(_ptr(packed), M, N, K, GROUP, MODE_W4_ZP_INT, _ptr(x16), _ptr(row_scale),
+    _check(lib().mnnq_linear_prefill_f16(_ptr(packed), M, N, K, GROUP, mode, _ptr(x16), _ptr(row_scale),
                                          _ptr(bias), _ptr(y), None, 0, _stream()), "mnnq_linear_prefill_f16")
     return y
 

@@ -18,6 +18,7 @@ namespace {
 
 constexpr int64_t kMaxDecodeK = 49152;     // int8 row + block sums in LDS: 160 B per 128 k, under 64 KiB
 constexpr int64_t kMaxDecodeKF16 = 30720;  // fp16 row in LDS: 256 B per 128 k, under 64 KiB
+constexpr int64_t kMaxDecodeKF16Min = 27648;  // float minimum form: 32 B of block sums more per 128 k
 constexpr int64_t kMaxM = 65535;
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -42,12 +43,12 @@ size_t fused_ws_bytes(int64_t K) { return (size_t)((K + 127) / 128 * 128 + 16); 
 // quantizing the row once, in a kernel of its own, beats quantizing it in every workgroup.
 constexpr size_t kFusedTwoKernelBytes = (size_t)48 << 20;
 
-bool prefill_fits(int64_t M, int64_t N, int64_t K, int mode = MNNQ_W4_ZP_INT)
+bool prefill_fits(int64_t M, int64_t N, int64_t K, int mode = MNNQ_W4_ZP_INT, int act_bytes = 1)
 {
     const int64_t lim = ((int64_t)1 << 31) - 1;
     // 32-bit byte offsets: activation rows of a whole tile, the packed weights, the output.
-    return M <= ((int64_t)1 << 24) && (M + 256) * K <= lim && (int64_t)make_layout(N, K, mode).total() <= lim &&
-           (M + 256) * N * 4 <= lim;
+    return M <= ((int64_t)1 << 24) && (M + 256) * K * act_bytes <= lim &&
+           (int64_t)make_layout(N, K, mode).total() <= lim && (M + 256) * N * 4 <= lim;
 }
 
 }  // namespace
@@ -198,8 +199,10 @@ int mnnq_linear_decode_f16(const void* packed, int64_t N, int64_t K, int group, 
     (void)workspace; (void)workspace_bytes;
     if (!packed || !x16 || !y) return MNNQ_ERR_NULL;
     if (int s = check_shape(N, K, group, mode)) return s;
-    if (mode != MNNQ_W4_ZP_INT) return MNNQ_ERR_UNSUPPORTED;   // fp16 activations: integer zero point only
-    if (K > kMaxDecodeKF16) return MNNQ_ERR_UNSUPPORTED;
+    {
+        const Layout L = make_layout(N, K, mode);   // the packed reduction axis is what is staged
+        if (L.K > (L.minf ? kMaxDecodeKF16Min : kMaxDecodeKF16)) return MNNQ_ERR_UNSUPPORTED;
+    }
     if (misaligned(packed) || misaligned(x16) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
     return launch_decode_f16(static_cast<const uint8_t*>(packed), make_layout(N, K, mode), x16, bias, y,
                              static_cast<hipStream_t>(stream));
@@ -213,8 +216,7 @@ int mnnq_linear_prefill_f16(const void* packed, int64_t M, int64_t N, int64_t K,
     if (!packed || !x16 || !y) return MNNQ_ERR_NULL;
     if (M <= 0) return MNNQ_ERR_SHAPE;
     if (int s = check_shape(N, K, group, mode)) return s;
-    if (mode != MNNQ_W4_ZP_INT) return MNNQ_ERR_UNSUPPORTED;   // fp16 activations: integer zero point only
-    if (!prefill_fits(M, N, 2 * K)) return MNNQ_ERR_UNSUPPORTED;   // byte offsets of fp16 rows
+    if (!prefill_fits(M, N, K, mode, 2)) return MNNQ_ERR_UNSUPPORTED;   // byte offsets of fp16 rows
     if (misaligned(packed) || misaligned(x16) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(row_scale) & 3u) return MNNQ_ERR_ALIGN;
     return launch_prefill_f16(static_cast<const uint8_t*>(packed), make_layout(N, K, mode), M, x16, row_scale, bias, y,

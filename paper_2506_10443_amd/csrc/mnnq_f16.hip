@@ -9,6 +9,11 @@
 // in fp32.  Codes become fp16 two at a time: (0x6400 | q) is the half 1024 + q,
 // and subtracting the half 1024 + z leaves q - z exactly.
 //
+// Float-minimum weights (Eq. 1 as printed; also the two 4-bit planes of 8-bit codes):
+//   y[n] = sum_g (step[n,g] * sum_{k in g} x[k] q[n,k] + min[n,g] * sum_{k in g} x[k]);
+// the codes enter as the halves q (subtract 1024 only) and the fp32 sums of the
+// 16-element blocks of x are computed once, when x is staged.
+//
 // A pair built from one dword with `(w >> 4 s) & 0x000f000f` holds the codes
 // j = s/2 + 4 (s%2) and j + 2 of that dword's eight codes, i.e. the eight
 // codes come out in the order 0 2 4 6 1 3 5 7.  The activations are put into
@@ -68,16 +73,23 @@ __device__ __forceinline__ uint4 permute8(uint4 v)
 struct ChunkRegs {
     u32x4 w;
     float2 s;
-    uint32_t z;
+    uint32_t z;    // zero points of both groups (integer zero point form)
+    float2 mn;     // group minima of both groups (float minimum form)
 };
 
-__device__ __forceinline__ ChunkRegs load_chunk(const u32x4* wp, const float2* sp, const uint16_t* zp,
-                                                int64_t i)
+template <bool MINF>
+__device__ __forceinline__ ChunkRegs load_chunk(const u32x4* wp, const float2* sp, const void* zp, int64_t i)
 {
     ChunkRegs r;
     r.w = __builtin_nontemporal_load(wp + i * 64);
     r.s = sp[i * 16];
-    r.z = zp[i * 16];
+    if (MINF) {
+        r.mn = static_cast<const float2*>(zp)[i * 16];
+        r.z = 0;
+    } else {
+        r.z = static_cast<const uint16_t*>(zp)[i * 16];
+        r.mn = make_float2(0.0f, 0.0f);
+    }
     return r;
 }
 
@@ -104,7 +116,7 @@ __device__ __forceinline__ float dot16_f16(uint32_t w0, uint32_t w1, uint32_t z,
 // registers: all weight loads are issued before the activations are touched, and
 // each wave stages only the slice of x it consumes into a private LDS region (no
 // barrier).
-template <int WAVES, int KSPLIT, int UNROLL, bool PREFETCH>
+template <int WAVES, int KSPLIT, int UNROLL, bool PREFETCH, bool MINF>
 __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* __restrict__ packed, Layout L,
                                                                 const uint16_t* __restrict__ x16,
                                                                 const float* __restrict__ bias,
@@ -117,8 +129,12 @@ __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* _
     const int wave = tid >> 6;
     const int row = lane & 15;
     const int kb = lane >> 4;
-    uint4* lds_x = reinterpret_cast<uint4*>(smem + (size_t)wave * PW * 256);   // PW * 128 halves, permuted by 8
-    float* lds_part = reinterpret_cast<float*>(smem + (size_t)WAVES * PW * 256);  // [WAVES][16]
+    // per wave: PW * 128 halves (permuted by 8), then the fp32 sums of their 16-element blocks
+    // stored as [chunk][half][kb] (used by the float minimum form only)
+    constexpr int kPerChunk = MINF ? 256 + 32 : 256;
+    uint4* lds_x = reinterpret_cast<uint4*>(smem + (size_t)wave * PW * kPerChunk);
+    float* lds_xs = reinterpret_cast<float*>(smem + (size_t)wave * PW * kPerChunk + (size_t)PW * 256);
+    float* lds_part = reinterpret_cast<float*>(smem + (size_t)WAVES * PW * kPerChunk);  // [WAVES][16]
 
     constexpr int TILES_PER_WG = WAVES / KSPLIT;
     const int64_t tile = (int64_t)blockIdx.x * TILES_PER_WG + wave / KSPLIT;
@@ -128,26 +144,42 @@ __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* _
     const int64_t c1 = C * (ks + 1) / KSPLIT;
     const u32x4* wp = reinterpret_cast<const u32x4*>(packed) + (tile * C + c0) * 64 + lane;
     const float2* sp = reinterpret_cast<const float2*>(packed + L.scales_off()) + (tile * C + c0) * 16 + row;
-    const uint16_t* zp = reinterpret_cast<const uint16_t*>(packed + L.zeros_off()) + (tile * C + c0) * 16 + row;
+    const void* zp = MINF ? static_cast<const void*>(reinterpret_cast<const float2*>(packed + L.zeros_off()) +
+                                                     (tile * C + c0) * 16 + row)
+                          : static_cast<const void*>(reinterpret_cast<const uint16_t*>(packed + L.zeros_off()) +
+                                                     (tile * C + c0) * 16 + row);
     const int64_t n_chunks = active ? (c1 - c0) : 0;
 
     ChunkRegs cur[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
-        if (u < n_chunks) cur[u] = load_chunk(wp, sp, zp, u);
+        if (u < n_chunks) cur[u] = load_chunk<MINF>(wp, sp, zp, u);
         else cur[u] = ChunkRegs{};
     }
 
     // This wave's slice of x in units of 8 halves (16 B): unit u of the region is unit
-    // c0 * 16 + u of the row; units past K are zero.
+    // c0 * 16 + u of the packed reduction axis, which runs over the activation row once
+    // (twice for 8-bit codes: one 4-bit plane after the other); units past K are zero.
     {
         const int64_t own = (c1 - c0) * 16;
         const int64_t valid = L.K / 8;
+        const int64_t row_units = L.Kx / 8;
         for (int64_t u = lane; u < own; u += 64) {
             const int64_t gu = c0 * 16 + u;
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (gu < valid) v = reinterpret_cast<const uint4*>(x16)[gu];
+            if (gu < valid) v = reinterpret_cast<const uint4*>(x16)[gu % row_units];
             lds_x[u] = permute8(v);
+            if (MINF) {
+                // sum of the 16-element block: its two units sit in neighbouring lanes
+                const h2 one = {(_Float16)1.0f, (_Float16)1.0f};
+                float sum = __builtin_amdgcn_fdot2(as_h2(v.x), one, 0.0f, false);
+                sum = __builtin_amdgcn_fdot2(as_h2(v.y), one, sum, false);
+                sum = __builtin_amdgcn_fdot2(as_h2(v.z), one, sum, false);
+                sum = __builtin_amdgcn_fdot2(as_h2(v.w), one, sum, false);
+                sum += __shfl_xor(sum, 1, 64);
+                // unit 8 h + 2 kb + e of the chunk -> block [h][kb]
+                if ((u & 1) == 0) lds_xs[(u / 16) * 8 + ((u % 16) / 8) * 4 + ((u % 8) / 2)] = sum;
+            }
         }
         // The region is private to the wave; LDS operations of one wave complete in order.
     }
@@ -158,7 +190,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* _
         if (PREFETCH) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
-                if (i + UNROLL + u < n_chunks) nxt[u] = load_chunk(wp, sp, zp, i + UNROLL + u);
+                if (i + UNROLL + u < n_chunks) nxt[u] = load_chunk<MINF>(wp, sp, zp, i + UNROLL + u);
                 else nxt[u] = ChunkRegs{};
             }
         }
@@ -172,6 +204,10 @@ __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* _
                 const float p1 = dot16_f16(r.w.z, r.w.w, r.z >> 8, xp[8], xp[9]);
                 accf = fmaf(r.s.x, p0, accf);
                 accf = fmaf(r.s.y, p1, accf);
+                if (MINF) {
+                    accf = fmaf(r.mn.x, lds_xs[(i + u) * 8 + kb], accf);
+                    accf = fmaf(r.mn.y, lds_xs[(i + u) * 8 + 4 + kb], accf);
+                }
             }
         }
         if (!PREFETCH) break;   // the host guarantees n_chunks <= UNROLL
@@ -204,10 +240,14 @@ int launch_decode_cfg(const uint8_t* packed, const Layout& L, const uint16_t* x1
     constexpr int tiles_per_wg = WAVES / KSPLIT;
     const int64_t blocks = (L.T + tiles_per_wg - 1) / tiles_per_wg;
     const int PW = (int)((L.C + KSPLIT - 1) / KSPLIT);
-    const size_t smem = (size_t)WAVES * PW * 256 + WAVES * 16 * sizeof(float);
+    const size_t smem = (size_t)WAVES * PW * (L.minf ? 256 + 32 : 256) + WAVES * 16 * sizeof(float);
     if (smem > 64 * 1024) return MNNQ_ERR_UNSUPPORTED;   // only reachable with a forced split
-    hipLaunchKernelGGL((decode_f16_kernel<WAVES, KSPLIT, UNROLL, PREFETCH>), dim3((unsigned)blocks),
-                       dim3(WAVES * 64), smem, st, packed, L, x16, bias, y, PW);
+    if (L.minf)
+        hipLaunchKernelGGL((decode_f16_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, true>), dim3((unsigned)blocks),
+                           dim3(WAVES * 64), smem, st, packed, L, x16, bias, y, PW);
+    else
+        hipLaunchKernelGGL((decode_f16_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, false>), dim3((unsigned)blocks),
+                           dim3(WAVES * 64), smem, st, packed, L, x16, bias, y, PW);
     MNNQ_HIP_TRY(hipGetLastError());
     return MNNQ_OK;
 }

@@ -15,6 +15,13 @@
 // the int32 accumulators of the int8 kernel, and no int -> float conversion is
 // needed in the epilogue.
 //
+// Float-minimum weights (Eq. 1 as printed; also the two 4-bit planes of 8-bit codes, whose
+// reduction axis runs over the activation row twice):
+//   y[m,n] = rs[m] * sum_g (step[n,g] * sum_{k in g} x[m,k] q[n,k] + min[n,g] * sum_{k in g} x[m,k]);
+// the B operand is the code itself, and one more MFMA pair per 16 rows and group with an
+// all-ones B operand yields the group sums of x in the D layout, i.e. for exactly the four
+// rows a lane holds.
+//
 // The structure is that of the int8 prefill kernel: operands reach LDS with
 // direct buffer loads, an A stage is one group (BM rows x 64 halves = 128 B per
 // row, 16-byte units XOR-swizzled by the row), a B chunk (two groups) is copied
@@ -82,25 +89,25 @@ __device__ __forceinline__ h8 unpack8(uint32_t w, h2 zb)
     return r.h;
 }
 
-template <int BM, int BN>
+template <int BM, int BN, bool MINF>
 struct Lds {
     static constexpr int NT16 = BN / 16;                 // row tiles of B per workgroup
     static constexpr int A_BYTES = BM * 128;             // [BM][64] halves, swizzled
     static constexpr int A_OFF = 0;                      // two A buffers (even / odd group)
     static constexpr int B_OFF = 2 * A_BYTES;            // [NT16][1024] packed codes
     static constexpr int S_OFF = B_OFF + NT16 * 1024;    // [NT16][16][2] fp32 scales
-    static constexpr int Z_OFF = S_OFF + NT16 * 128;     // [NT16][16][2] u8 zeros
-    static constexpr int BYTES = Z_OFF + NT16 * 32;
+    static constexpr int Z_OFF = S_OFF + NT16 * 128;     // [NT16][16][2] u8 zeros, or fp32 group minima (MINF)
+    static constexpr int BYTES = Z_OFF + NT16 * (MINF ? 128 : 32);
 };
 
-template <int BM, int BN>
+template <int BM, int BN, bool MINF>
 __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __restrict__ packed, Layout L, int64_t M,
                                                              const uint16_t* __restrict__ x16,
                                                              const float* __restrict__ rs,
                                                              const float* __restrict__ bias, float* __restrict__ y,
                                                              int MT, int NT)
 {
-    using St = Lds<BM, BN>;
+    using St = Lds<BM, BN, MINF>;
     constexpr int WM = BM / 2, WN = BN / 2;      // 2 x 2 waves
     constexpr int TM = WM / 16, TN = WN / 16;
     constexpr int NT16 = St::NT16;
@@ -116,7 +123,8 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
     const int col = lane & 15;
     const int kb = lane >> 4;
     const int C = (int)L.C;
-    const int K2 = (int)L.K * 2;                 // bytes per activation row
+    const int K2 = (int)L.Kx * 2;                // bytes per activation row
+    const int Gx = (int)L.Kx / 64;               // group g of the packed axis meets group g % Gx of the row
 
     // Each XCD gets whole columns of output tiles, so that a weight block is fetched
     // into one L2 only.
@@ -130,7 +138,7 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
 
     // Out-of-range reads (rows past M, row tiles past N) return zero.
     const __amdgpu_buffer_rsrc_t rs_x =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(x16), 0, (int)(M * L.K * 2), kBufFlags);
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(x16), 0, (int)(M * L.Kx * 2), kBufFlags);
     const __amdgpu_buffer_rsrc_t rs_w =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(packed), 0, (int)L.total(), kBufFlags);
 
@@ -152,7 +160,7 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
     const int a_u1 = ((2 * kb + 1) ^ a_sw) << 4;                // unit of halves 16 kb + 8 .. 16 kb + 15
     const int b_frag_off = St::B_OFF + wn * TN * 1024 + lane * 16;
     const int s_frag_off = St::S_OFF + wn * TN * 128 + col * 8;
-    const int z_frag_off = St::Z_OFF + wn * TN * 32 + col * 2;
+    const int z_frag_off = St::Z_OFF + (MINF ? wn * TN * 128 + col * 8 : wn * TN * 32 + col * 2);
 
     // A stage: group g of this workgroup's BM rows.
     auto issue_a = [&](int g, int buf) {
@@ -160,7 +168,7 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
         for (int i = 0; i < A_INSTR; ++i) {
             const int q = wave * A_INSTR + i;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, MNNQ_LDS(lds + St::A_OFF + buf * St::A_BYTES + q * 1024),
-                                                     16, a_voff, ((int)m0 + q * 8) * K2 + g * 128, 0, 0);
+                                                     16, a_voff, ((int)m0 + q * 8) * K2 + (g % Gx) * 128, 0, 0);
         }
     };
     auto issue_b = [&](int c) {
@@ -172,7 +180,10 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
         }
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::S_OFF + wave * 256), 4, s_voff,
                                                  scales_off + ((rt0 + wave * 2) * C + c) * 128, 0, 0);
-        if (wave == 0)
+        if (MINF)   // group minima: fp32, laid out like the scales
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::Z_OFF + wave * 256), 4, s_voff,
+                                                     zeros_off + ((rt0 + wave * 2) * C + c) * 128, 0, 0);
+        else if (wave == 0)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::Z_OFF + opaque_zero), 4, z_voff,
                                                      zeros_off + (rt0 * C + c) * 32, 0, 0);
     };
@@ -187,13 +198,15 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
 
     v4i bw[TN];
     v2i bsv[TN];
-    uint32_t bz[TN];
+    uint32_t bz[TN];      // zero points of both groups (integer zero point form)
+    v2i bmn[TN];          // group minima of both groups, fp32 bits (float minimum form)
     auto read_b = [&]() {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             bw[j] = *reinterpret_cast<const v4i*>(lds + b_frag_off + j * 1024);
             bsv[j] = *reinterpret_cast<const v2i*>(lds + s_frag_off + j * 128);
-            bz[j] = *reinterpret_cast<const uint16_t*>(lds + z_frag_off + j * 32);
+            if (MINF) bmn[j] = *reinterpret_cast<const v2i*>(lds + z_frag_off + j * 128);
+            else bz[j] = *reinterpret_cast<const uint16_t*>(lds + z_frag_off + j * 32);
         }
     };
 
@@ -203,13 +216,16 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
     auto compute = [&](int h, int buf) {
         h8 b0[TN], b1[TN];
         float sc[TN];
+        float mnv[TN];
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            H2Bits zb;   // the half 1024 + zero point, twice
-            zb.u = __builtin_amdgcn_perm(0x64646464u, bz[j], h ? 0x04010401u : 0x04000400u);
+            H2Bits zb;   // the half 1024 + zero point, twice (float minimum form: 1024, the codes stay as they are)
+            if (MINF) zb.u = 0x64006400u;
+            else zb.u = __builtin_amdgcn_perm(0x64646464u, bz[j], h ? 0x04010401u : 0x04000400u);
             b0[j] = unpack8((uint32_t)(h ? bw[j].z : bw[j].x), zb.h);
             b1[j] = unpack8((uint32_t)(h ? bw[j].w : bw[j].y), zb.h);
             sc[j] = __int_as_float(h ? bsv[j].y : bsv[j].x);
+            mnv[j] = MINF ? __int_as_float(h ? bmn[j].y : bmn[j].x) : 0.0f;
         }
         const uint8_t* ap = lds + buf * St::A_BYTES + a_row_off;
         const v4f zero = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -222,6 +238,14 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
         }
         v4f d = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, b0[0], zero, 0, 0, 0);
         d = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, b1[0], d, 0, 0, 0);
+        // float minimum form: group sums of x for the lane's four rows of this and the next m-tile
+        H8Bits ones;
+        ones.u[0] = ones.u[1] = ones.u[2] = ones.u[3] = 0x3c003c00u;
+        v4f xs_cur = zero, xs_nxt = zero;
+        if (MINF) {
+            xs_cur = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, ones.h, zero, 0, 0, 0);
+            xs_cur = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, ones.h, xs_cur, 0, 0, 0);
+        }
 #pragma unroll
         for (int tt = 0; tt < TM * TN; ++tt) {
             const int i = tt / TN, j = tt % TN;
@@ -238,10 +262,18 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
                 }
                 d_nxt = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, b0[j1], zero, 0, 0, 0);
                 d_nxt = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, b1[j1], d_nxt, 0, 0, 0);
+                if (MINF && j1 == 0) {
+                    xs_nxt = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, ones.h, zero, 0, 0, 0);
+                    xs_nxt = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, ones.h, xs_nxt, 0, 0, 0);
+                }
                 asm volatile("" : "+v"(d), "+v"(d_nxt));
             }
+            if (MINF && j == 0 && i > 0) xs_cur = xs_nxt;   // issued with the first MFMA pair of this row of tiles
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) yacc[i][j][rr] = fmaf(sc[j], d[rr], yacc[i][j][rr]);
+            for (int rr = 0; rr < 4; ++rr) {
+                yacc[i][j][rr] = fmaf(sc[j], d[rr], yacc[i][j][rr]);
+                if (MINF) yacc[i][j][rr] = fmaf(mnv[j], xs_cur[rr], yacc[i][j][rr]);
+            }
             if (tt + 2 < TM * TN) {
                 const int j2 = (tt + 2) % TN;
                 asm volatile(""
@@ -334,14 +366,14 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
     }
 }
 
-template <int BM, int BN>
-int launch_tiles(const uint8_t* packed, const Layout& L, int64_t M, const uint16_t* x16, const float* rs,
-                 const float* bias, float* y, hipStream_t st)
+template <int BM, int BN, bool MINF>
+int launch_tiles_m(const uint8_t* packed, const Layout& L, int64_t M, const uint16_t* x16, const float* rs,
+                   const float* bias, float* y, hipStream_t st)
 {
     const int MT = (int)((M + BM - 1) / BM);
     const int NT = (int)((L.N + BN - 1) / BN);
-    constexpr size_t smem = (size_t)Lds<BM, BN>::BYTES;
-    auto kern = prefill_f16_kernel<BM, BN>;
+    constexpr size_t smem = (size_t)Lds<BM, BN, MINF>::BYTES;
+    auto kern = prefill_f16_kernel<BM, BN, MINF>;
     if (smem > 64 * 1024) {
         // More than 64 KiB of dynamic LDS has to be allowed once per kernel and device.
         static thread_local int allowed_dev = -1;
@@ -357,6 +389,14 @@ int launch_tiles(const uint8_t* packed, const Layout& L, int64_t M, const uint16
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), smem, st, packed, L, M, x16, rs, bias, y, MT, NT);
     MNNQ_HIP_TRY(hipGetLastError());
     return MNNQ_OK;
+}
+
+template <int BM, int BN>
+int launch_tiles(const uint8_t* packed, const Layout& L, int64_t M, const uint16_t* x16, const float* rs,
+                 const float* bias, float* y, hipStream_t st)
+{
+    if (L.minf) return launch_tiles_m<BM, BN, true>(packed, L, M, x16, rs, bias, y, st);
+    return launch_tiles_m<BM, BN, false>(packed, L, M, x16, rs, bias, y, st);
 }
 
 }  // namespace

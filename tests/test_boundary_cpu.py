@@ -117,9 +117,13 @@ def test_argument_validation_precedes_hip(L):
 
     assert L.mnnq_linear_decode_f16(FAKE, 16, 128, 64, 0, None, None, FAKE, None, 0, None) == NULL
     assert L.mnnq_linear_decode_f16(FAKE, 16, 100, 64, 0, FAKE, None, FAKE, None, 0, None) == SHAPE
-    assert L.mnnq_linear_decode_f16(FAKE, 16, 128, 64, 1, FAKE, None, FAKE, None, 0, None) == UNSUP   # float minimum
-    assert L.mnnq_linear_decode_f16(FAKE, 16, 128, 64, 2, FAKE, None, FAKE, None, 0, None) == UNSUP   # int8 weights
-    assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 128, 64, 1, FAKE, None, None, FAKE, None, 0, None) == UNSUP
+    assert L.mnnq_linear_decode_f16(FAKE, 16, 128, 64, 3, FAKE, None, FAKE, None, 0, None) == UNSUP   # no such mode
+    assert L.mnnq_linear_decode_f16(FAKE, 16, 192, 64, 2, FAKE, None, FAKE, None, 0, None) == UNSUP   # int8 weights: K % 128
+    assert L.mnnq_linear_decode_f16(FAKE, 16, 30720 + 64, 64, 0, FAKE, None, FAKE, None, 0, None) == UNSUP  # row too long for LDS
+    assert L.mnnq_linear_decode_f16(FAKE, 16, 27648 + 64, 64, 1, FAKE, None, FAKE, None, 0, None) == UNSUP  # same, float minimum
+    assert L.mnnq_linear_decode_f16(FAKE, 16, 13824 + 128, 64, 2, FAKE, None, FAKE, None, 0, None) == UNSUP  # same, two planes
+    assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 128, 64, 3, FAKE, None, None, FAKE, None, 0, None) == UNSUP
+    assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 192, 64, 2, FAKE, None, None, FAKE, None, 0, None) == UNSUP
     assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 128, 64, 0, FAKE, None, None, None, None, 0, None) == NULL
     assert L.mnnq_linear_prefill_f16(FAKE, -1, 16, 128, 64, 0, FAKE, None, None, FAKE, None, 0, None) == SHAPE
     assert L.mnnq_linear_acc_debug(FAKE, 1, 16, 128, 64, 0, FAKE, None, 0, None) == NULL
