@@ -68,6 +68,8 @@ def main() -> int:
     ap.add_argument("--act16", action="store_true",
                     help="also time the fp16-activation entry points (W4A16 / W8A16) per layer: per_layer "
                          "gains decode16_* (GB/s of their algorithmic bytes) and prefill16_* (TFLOP/s)")
+    ap.add_argument("--out16", action="store_true",
+                    help="also time the prefill call with binary16 output per layer (per_layer prefill_o16_*)")
     ap.add_argument("--two-call-decode", action="store_true",
                     help="decode pass calls mnnq_quant_act + mnnq_linear_decode per layer instead of "
                          "mnnq_linear_decode_fused (fp32 row in, quantizer inside the call)")
@@ -316,6 +318,16 @@ def main() -> int:
                     continue
                 per_layer["decode16_" + name] = {"us": round(t * 1e3, 2),
                                                  "gbs": round((decode_bytes(N, K) + K) / (t * 1e-3) / 1e9, 1)}
+
+    if args.out16 and do_pre:
+        for name, N, K in layers:
+            x, xq, sx, y = io_pre[name]
+            y16 = torch.empty((M_pre, N), dtype=torch.float16, device=dev)
+            lay = [(lambda p=packed[name][b], N=N, K=K, xq=xq, sx=sx, y16=y16:
+                    B.mnnq_linear_prefill_o16(p, N, K, xq, sx, out=y16, mode=wmode)) for b in range(n_blocks)]
+            t = time_launches(lay, 2)
+            per_layer["prefill_o16_" + name] = {"us": round(t * 1e3, 2),
+                                                "tops": round(prefill_ops(M_pre, N, K) / (t * 1e-3) / 1e12, 1)}
 
     # ---- the same decode pass through the fused entry point (quantizer inside the GEMV), for comparison
     dec_other = None

@@ -160,6 +160,20 @@ int mnnq_linear_prefill_f16(const void *packed, int64_t M, int64_t N, int64_t K,
                             const uint16_t *x16, const float *row_scale, const float *bias, float *y,
                             void *workspace, size_t workspace_bytes, void *stream);
 
+/* Output in IEEE binary16 (Section 4.2 runs the GPU path in fp16): the same sums as the calls
+ * above, accumulated in fp32 and rounded once, to nearest even, when stored.  y16: binary16 bits,
+ * [N] resp. [M, N] row-major, 16-byte aligned; every other argument as in the call of the same
+ * name without the suffix.  Results beyond the binary16 range become infinities. */
+int mnnq_linear_decode_o16(const void *packed, int64_t N, int64_t K, int group, int mode,
+                           const int8_t *xq, const float *sx, const float *bias, uint16_t *y16, void *stream);
+int mnnq_linear_prefill_o16(const void *packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                            const int8_t *xq, const float *sx, const float *bias, uint16_t *y16, void *stream);
+int mnnq_linear_decode_f16_o16(const void *packed, int64_t N, int64_t K, int group, int mode,
+                               const uint16_t *x16, const float *bias, uint16_t *y16, void *stream);
+int mnnq_linear_prefill_f16_o16(const void *packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                                const uint16_t *x16, const float *row_scale, const float *bias, uint16_t *y16,
+                                void *stream);
+
 /* Import of weights that were quantized elsewhere (Section 4.2: quantized
  * weights, e.g. from GPTQ, can be imported): canonical arrays in, packed form
  * out - the inverse of mnnq_unpack_weights.

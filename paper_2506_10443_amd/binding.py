@@ -26,6 +26,7 @@ EXPORTS = (
     "mnnq_linear_decode_fused",
     "mnnq_linear_prefill", "mnnq_linear_decode_f16", "mnnq_linear_prefill_f16", "mnnq_linear_acc_debug",
     "mnnq_pack_from_quantized",
+    "mnnq_linear_decode_o16", "mnnq_linear_prefill_o16", "mnnq_linear_decode_f16_o16", "mnnq_linear_prefill_f16_o16",
 )
 
 
@@ -66,6 +67,10 @@ def lib() -> ctypes.CDLL:
         L.mnnq_linear_prefill_f16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.mnnq_linear_acc_debug.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, i32, vp]
         L.mnnq_pack_from_quantized.argtypes = [vp, vp, vp, i64, i64, i32, i32, vp, sz, vp]
+        L.mnnq_linear_decode_o16.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, vp]
+        L.mnnq_linear_prefill_o16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp]
+        L.mnnq_linear_decode_f16_o16.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
+        L.mnnq_linear_prefill_f16_o16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp]
         for name in EXPORTS[5:]:
             getattr(L, name).restype = i32
         _lib = L
@@ -235,3 +240,56 @@ def mnnq_linear_acc_debug(packed, N: int, K: int, xq, use_prefill_kernel: bool, 
     _check(lib().mnnq_linear_acc_debug(_ptr(packed), M, N, K, GROUP, mode, _ptr(xq2), _ptr(acc),
                                        1 if use_prefill_kernel else 0, _stream()), "mnnq_linear_acc_debug")
     return acc
+
+
+# ---- the same linear calls with IEEE binary16 output
+
+def mnnq_linear_decode_o16(packed, N: int, K: int, xq, sx, bias=None, out=None, mode: int = MODE_W4_ZP_INT):
+    """One token: xq i8 [K], sx f32 [1] -> y fp16 [N]."""
+    _dev(packed, torch.uint8, "packed"); _dev(xq, torch.int8, "xq"); _dev(sx, torch.float32, "sx")
+    if xq.numel() != K:
+        raise ValueError("xq must hold K values")
+    y = torch.empty((N,), dtype=torch.float16, device=packed.device) if out is None else out
+    _dev(y, torch.float16, "out")
+    _check(lib().mnnq_linear_decode_o16(_ptr(packed), N, K, GROUP, mode, _ptr(xq), _ptr(sx), _ptr(bias),
+                                        _ptr(y), _stream()), "mnnq_linear_decode_o16")
+    return y
+
+
+def mnnq_linear_prefill_o16(packed, N: int, K: int, xq, sx, bias=None, out=None, mode: int = MODE_W4_ZP_INT):
+    """M tokens: xq i8 [M,K], sx f32 [M] -> y fp16 [M,N]."""
+    _dev(packed, torch.uint8, "packed"); _dev(xq, torch.int8, "xq"); _dev(sx, torch.float32, "sx")
+    M = xq.shape[0]
+    if xq.shape[1] != K or sx.numel() != M:
+        raise ValueError("xq must be [M,K] and sx [M]")
+    y = torch.empty((M, N), dtype=torch.float16, device=packed.device) if out is None else out
+    _dev(y, torch.float16, "out")
+    _check(lib().mnnq_linear_prefill_o16(_ptr(packed), M, N, K, GROUP, mode, _ptr(xq), _ptr(sx),
+                                         _ptr(bias), _ptr(y), _stream()), "mnnq_linear_prefill_o16")
+    return y
+
+
+def mnnq_linear_decode_f16_o16(packed, N: int, K: int, x16, bias=None, out=None, mode: int = MODE_W4_ZP_INT):
+    """One token, fp16 activations: x16 fp16 [K] -> y fp16 [N]."""
+    _dev(packed, torch.uint8, "packed"); _dev(x16, torch.float16, "x16")
+    if x16.numel() != K:
+        raise ValueError("x16 must hold K values")
+    y = torch.empty((N,), dtype=torch.float16, device=packed.device) if out is None else out
+    _dev(y, torch.float16, "out")
+    _check(lib().mnnq_linear_decode_f16_o16(_ptr(packed), N, K, GROUP, mode, _ptr(x16), _ptr(bias),
+                                            _ptr(y), _stream()), "mnnq_linear_decode_f16_o16")
+    return y
+
+
+def mnnq_linear_prefill_f16_o16(packed, N: int, K: int, x16, bias=None, out=None, row_scale=None,
+                                mode: int = MODE_W4_ZP_INT):
+    """M tokens, fp16 activations: x16 fp16 [M,K] -> y fp16 [M,N]; row_scale f32 [M] optional."""
+    _dev(packed, torch.uint8, "packed"); _dev(x16, torch.float16, "x16")
+    M = x16.shape[0]
+    if x16.shape[1] != K:
+        raise ValueError("x16 must be [M,K]")
+    y = torch.empty((M, N), dtype=torch.float16, device=packed.device) if out is None else out
+    _dev(y, torch.float16, "out")
+    _check(lib().mnnq_linear_prefill_f16_o16(_ptr(packed), M, N, K, GROUP, mode, _ptr(x16), _ptr(row_scale),
+                                             _ptr(bias), _ptr(y), _stream()), "mnnq_linear_prefill_f16_o16")
+    return y

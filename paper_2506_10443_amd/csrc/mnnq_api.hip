@@ -51,6 +51,72 @@ bool prefill_fits(int64_t M, int64_t N, int64_t K, int mode = MNNQ_W4_ZP_INT, in
            (int64_t)make_layout(N, K, mode).total() <= lim && (M + 256) * N * 4 <= lim;
 }
 
+Layout layout_for(int64_t N, int64_t K, int mode, bool out16)
+{
+    Layout L = make_layout(N, K, mode);
+    L.out16 = out16;
+    return L;
+}
+
+// The four linear calls that exist with fp32 and with binary16 output; y points to the output array
+// of the requested kind (the kernels store through it according to Layout::out16).
+int decode_impl(const void* packed, int64_t N, int64_t K, int group, int mode, const int8_t* xq, const float* sx,
+                const float* bias, void* y, bool out16, void* stream)
+{
+    if (!packed || !xq || !sx || !y) return MNNQ_ERR_NULL;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    if (make_layout(N, K, mode).K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
+    if (misaligned(packed) || misaligned(xq) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(sx) & 3u) return MNNQ_ERR_ALIGN;
+    return launch_decode(static_cast<const uint8_t*>(packed), layout_for(N, K, mode, out16), xq, sx, bias,
+                         static_cast<float*>(y), static_cast<hipStream_t>(stream));
+}
+
+int prefill_impl(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode, const int8_t* xq,
+                 const float* sx, const float* bias, void* y, bool out16, void* workspace, void* stream)
+{
+    if (!packed || !xq || !sx || !y) return MNNQ_ERR_NULL;
+    if (M <= 0) return MNNQ_ERR_SHAPE;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    if (!prefill_fits(M, N, K, mode)) return MNNQ_ERR_UNSUPPORTED;
+    if (misaligned(packed) || misaligned(xq) || misaligned(y) || misaligned(bias) || misaligned(workspace))
+        return MNNQ_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(sx) & 3u) return MNNQ_ERR_ALIGN;
+    const Layout L = layout_for(N, K, mode, out16);
+    // A few tokens (batched or speculative decoding) are still memory-bound: one pass over the
+    // weights in the GEMV's streaming order, all tokens at once in the matrix cores.
+    if (M <= 16 && !getenv("MNNQ_NO_SKINNY"))
+        return launch_skinny(static_cast<const uint8_t*>(packed), L, M, xq, sx, bias, static_cast<float*>(y),
+                             static_cast<hipStream_t>(stream));
+    return launch_prefill(static_cast<const uint8_t*>(packed), L, M, xq, sx, bias, static_cast<float*>(y), nullptr,
+                          static_cast<hipStream_t>(stream));
+}
+
+int decode_f16_impl(const void* packed, int64_t N, int64_t K, int group, int mode, const uint16_t* x16,
+                    const float* bias, void* y, bool out16, void* stream)
+{
+    if (!packed || !x16 || !y) return MNNQ_ERR_NULL;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    const Layout L = layout_for(N, K, mode, out16);   // the packed reduction axis is what is staged
+    if (L.K > (L.minf ? kMaxDecodeKF16Min : kMaxDecodeKF16)) return MNNQ_ERR_UNSUPPORTED;
+    if (misaligned(packed) || misaligned(x16) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
+    return launch_decode_f16(static_cast<const uint8_t*>(packed), L, x16, bias, static_cast<float*>(y),
+                             static_cast<hipStream_t>(stream));
+}
+
+int prefill_f16_impl(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode, const uint16_t* x16,
+                     const float* row_scale, const float* bias, void* y, bool out16, void* stream)
+{
+    if (!packed || !x16 || !y) return MNNQ_ERR_NULL;
+    if (M <= 0) return MNNQ_ERR_SHAPE;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    if (!prefill_fits(M, N, K, mode, 2)) return MNNQ_ERR_UNSUPPORTED;   // byte offsets of fp16 rows
+    if (misaligned(packed) || misaligned(x16) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(row_scale) & 3u) return MNNQ_ERR_ALIGN;
+    return launch_prefill_f16(static_cast<const uint8_t*>(packed), layout_for(N, K, mode, out16), M, x16, row_scale,
+                              bias, static_cast<float*>(y), static_cast<hipStream_t>(stream));
+}
+
 }  // namespace
 }  // namespace mnnq
 
@@ -144,13 +210,7 @@ int mnnq_linear_decode(const void* packed, int64_t N, int64_t K, int group, int 
                        void* stream)
 {
     (void)workspace; (void)workspace_bytes;
-    if (!packed || !xq || !sx || !y) return MNNQ_ERR_NULL;
-    if (int s = check_shape(N, K, group, mode)) return s;
-    if (make_layout(N, K, mode).K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
-    if (misaligned(packed) || misaligned(xq) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
-    if (reinterpret_cast<uintptr_t>(sx) & 3u) return MNNQ_ERR_ALIGN;
-    return launch_decode(static_cast<const uint8_t*>(packed), make_layout(N, K, mode), xq, sx, bias, y,
-                         static_cast<hipStream_t>(stream));
+    return decode_impl(packed, N, K, group, mode, xq, sx, bias, y, false, stream);
 }
 
 int mnnq_linear_decode_fused(const void* packed, int64_t N, int64_t K, int group, int mode, const float* x,
@@ -177,35 +237,14 @@ int mnnq_linear_prefill(const void* packed, int64_t M, int64_t N, int64_t K, int
                         size_t workspace_bytes, void* stream)
 {
     (void)workspace_bytes;
-    if (!packed || !xq || !sx || !y) return MNNQ_ERR_NULL;
-    if (M <= 0) return MNNQ_ERR_SHAPE;
-    if (int s = check_shape(N, K, group, mode)) return s;
-    if (!prefill_fits(M, N, K, mode)) return MNNQ_ERR_UNSUPPORTED;
-    if (misaligned(packed) || misaligned(xq) || misaligned(y) || misaligned(bias) || misaligned(workspace))
-        return MNNQ_ERR_ALIGN;
-    if (reinterpret_cast<uintptr_t>(sx) & 3u) return MNNQ_ERR_ALIGN;
-    // A few tokens (batched or speculative decoding) are still memory-bound: one pass over the
-    // weights in the GEMV's streaming order, all tokens at once in the matrix cores.
-    if (M <= 16 && !getenv("MNNQ_NO_SKINNY"))
-        return launch_skinny(static_cast<const uint8_t*>(packed), make_layout(N, K, mode), M, xq, sx, bias, y,
-                             static_cast<hipStream_t>(stream));
-    return launch_prefill(static_cast<const uint8_t*>(packed), make_layout(N, K, mode), M, xq, sx, bias, y, nullptr,
-                          static_cast<hipStream_t>(stream));
+    return prefill_impl(packed, M, N, K, group, mode, xq, sx, bias, y, false, workspace, stream);
 }
 
 int mnnq_linear_decode_f16(const void* packed, int64_t N, int64_t K, int group, int mode, const uint16_t* x16,
                            const float* bias, float* y, void* workspace, size_t workspace_bytes, void* stream)
 {
     (void)workspace; (void)workspace_bytes;
-    if (!packed || !x16 || !y) return MNNQ_ERR_NULL;
-    if (int s = check_shape(N, K, group, mode)) return s;
-    {
-        const Layout L = make_layout(N, K, mode);   // the packed reduction axis is what is staged
-        if (L.K > (L.minf ? kMaxDecodeKF16Min : kMaxDecodeKF16)) return MNNQ_ERR_UNSUPPORTED;
-    }
-    if (misaligned(packed) || misaligned(x16) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
-    return launch_decode_f16(static_cast<const uint8_t*>(packed), make_layout(N, K, mode), x16, bias, y,
-                             static_cast<hipStream_t>(stream));
+    return decode_f16_impl(packed, N, K, group, mode, x16, bias, y, false, stream);
 }
 
 int mnnq_linear_prefill_f16(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
@@ -213,14 +252,32 @@ int mnnq_linear_prefill_f16(const void* packed, int64_t M, int64_t N, int64_t K,
                             void* workspace, size_t workspace_bytes, void* stream)
 {
     (void)workspace; (void)workspace_bytes;
-    if (!packed || !x16 || !y) return MNNQ_ERR_NULL;
-    if (M <= 0) return MNNQ_ERR_SHAPE;
-    if (int s = check_shape(N, K, group, mode)) return s;
-    if (!prefill_fits(M, N, K, mode, 2)) return MNNQ_ERR_UNSUPPORTED;   // byte offsets of fp16 rows
-    if (misaligned(packed) || misaligned(x16) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
-    if (reinterpret_cast<uintptr_t>(row_scale) & 3u) return MNNQ_ERR_ALIGN;
-    return launch_prefill_f16(static_cast<const uint8_t*>(packed), make_layout(N, K, mode), M, x16, row_scale, bias, y,
-                              static_cast<hipStream_t>(stream));
+    return prefill_f16_impl(packed, M, N, K, group, mode, x16, row_scale, bias, y, false, stream);
+}
+
+int mnnq_linear_decode_o16(const void* packed, int64_t N, int64_t K, int group, int mode, const int8_t* xq,
+                           const float* sx, const float* bias, uint16_t* y16, void* stream)
+{
+    return decode_impl(packed, N, K, group, mode, xq, sx, bias, y16, true, stream);
+}
+
+int mnnq_linear_prefill_o16(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                            const int8_t* xq, const float* sx, const float* bias, uint16_t* y16, void* stream)
+{
+    return prefill_impl(packed, M, N, K, group, mode, xq, sx, bias, y16, true, nullptr, stream);
+}
+
+int mnnq_linear_decode_f16_o16(const void* packed, int64_t N, int64_t K, int group, int mode, const uint16_t* x16,
+                               const float* bias, uint16_t* y16, void* stream)
+{
+    return decode_f16_impl(packed, N, K, group, mode, x16, bias, y16, true, stream);
+}
+
+int mnnq_linear_prefill_f16_o16(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                                const uint16_t* x16, const float* row_scale, const float* bias, uint16_t* y16,
+                                void* stream)
+{
+    return prefill_f16_impl(packed, M, N, K, group, mode, x16, row_scale, bias, y16, true, stream);
 }
 
 int mnnq_linear_acc_debug(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,

@@ -50,6 +50,7 @@ struct Layout {
     int64_t Cx;     // chunks of an activation row
     int mode;       // mnnq_mode
     bool minf;      // groups carry an fp32 minimum instead of a one-byte zero point
+    bool out16;     // the output array holds IEEE binary16 values (set per call, not a property of the packing)
     int64_t T;  // row tiles
     int64_t G;  // groups per row
     int64_t C;  // chunks per row tile
@@ -67,6 +68,7 @@ inline __host__ __device__ Layout make_layout(int64_t N, int64_t K, int mode = M
     L.K = (mode == MNNQ_W8_MIN_FLOAT) ? 2 * K : K;
     L.mode = mode;
     L.minf = (mode != MNNQ_W4_ZP_INT);
+    L.out16 = false;
     L.T = N / kTileN;
     L.G = L.K / kGroup;
     L.C = (L.G + 1) / 2;
@@ -76,6 +78,15 @@ inline __host__ __device__ Layout make_layout(int64_t N, int64_t K, int mode = M
     L.zeros_bytes = (size_t)L.T * L.C * 32 * (L.minf ? sizeof(float) : 1);
     return L;
 }
+
+#if defined(__HIPCC__)
+// One output value: fp32, or rounded once (nearest even) to binary16 when the call asked for it.
+__device__ __forceinline__ void store_out(float* y, int64_t i, float v, bool out16)
+{
+    if (out16) reinterpret_cast<_Float16*>(y)[i] = (_Float16)v;
+    else y[i] = v;
+}
+#endif
 
 // Records a failing HIP call for mnnq_last_hip_error() and maps it to a status.
 int record_hip_error(hipError_t e);

@@ -280,7 +280,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
         const int64_t n = tile * kTileN + row;
         float r = accf * ((MODE == kFused) ? scale : sx[0]);
         if (bias) r += bias[n];
-        y[n] = r;
+        store_out(y, n, r, L.out16);
     }
 }
 

@@ -229,7 +229,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* _
         const int64_t n = tile * kTileN + row;
         float r = accf;
         if (bias) r += bias[n];
-        y[n] = r;
+        store_out(y, n, r, L.out16);
     }
 }
 

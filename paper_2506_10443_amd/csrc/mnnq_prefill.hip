@@ -37,6 +37,17 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
+typedef _Float16 h2v __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t h2_bits(h2v h)
+{
+    union {
+        h2v h;
+        uint32_t u;
+    } b;
+    b.h = h;
+    return b.u;
+}
 
 #define MNNQ_LDS(p) ((__attribute__((address_space(3))) void*)(p))
 
@@ -382,7 +393,11 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
                 float* wr = patch + (kb * 4) * RS + col;
                 const float* rd = patch + kb * RS + col * 4;  // + 4 p rows
                 // a lane's 16-byte unit lies in row tile nt0 + col / 4; units past N are sent out of range
-                const int y_voff = (nt0 + (col >> 2) < (int)L.T) ? kb * Nb + col * 16 : y_bytes;
+                const bool unit_ok = nt0 + (col >> 2) < (int)L.T;
+                const int y_voff = unit_ok ? kb * Nb + col * 16 : y_bytes;
+                // binary16 output: the same unit is four halves, rows are half as long
+                const __amdgpu_buffer_rsrc_t rs_y16 = __builtin_amdgcn_make_buffer_rsrc(y, 0, y_bytes / 2, kBufFlags);
+                const int y_voff16 = unit_ok ? kb * (Nb / 2) + col * 8 : y_bytes / 2;
 #pragma unroll
                 for (int i = 0; i < TM; ++i) {
                     float sxr[4];
@@ -398,6 +413,13 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
                     for (int p = 0; p < 4; ++p) {
                         // (read as a struct of floats: the same scalar type as the writes for alias analysis)
                         const float4 f = *reinterpret_cast<const float4*>(rd + p * 4 * RS);
+                        if (L.out16) {
+                            const h2v lo = {(_Float16)f.x, (_Float16)f.y}, hi = {(_Float16)f.z, (_Float16)f.w};
+                            const v2i v = {(int)h2_bits(lo), (int)h2_bits(hi)};
+                            __builtin_amdgcn_raw_buffer_store_b64(v, rs_y16, y_voff16,
+                                                                  (row0 + i * 16 + p * 4) * (Nb / 2) + nt0 * 32, 0);
+                            continue;
+                        }
                         const v4i v = {(int)__float_as_uint(f.x), (int)__float_as_uint(f.y), (int)__float_as_uint(f.z),
                                        (int)__float_as_uint(f.w)};
                         __builtin_amdgcn_raw_buffer_store_b128(v, rs_y, y_voff,
@@ -544,7 +566,8 @@ int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8
         if (M > 128) return launch_tiles<256, 128, 1, true>(packed, L, M, xq, sx, bias, y, acc_debug, 1, st);
         return launch_tiles<128, 128, 1, true>(packed, L, M, xq, sx, bias, y, acc_debug, 1, st);
     }
-    const TilePlan p = plan_tiles(L, M);
+    TilePlan p = plan_tiles(L, M);
+    if (L.out16) p.S = 1;   // the split over two workgroups adds fp32 partial sums in the output array
     if (p.big && p.KS == 2) return launch_tiles<256, 128, 2, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
     if (p.big) return launch_tiles<256, 128, 1, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
     if (p.KS == 2) return launch_tiles<128, 128, 2, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);

@@ -342,7 +342,11 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
     float* wr = patch + (kb * 4) * RS + col;
     const float* rd = patch + kb * RS + col * 4;       // + 4 p rows
     // a lane's 16-byte unit lies in row tile nt0 + col / 4; units past N are sent out of range
-    const int y_voff = (nt0 + (col >> 2) < (int)L.T) ? kb * Nb + col * 16 : y_bytes;
+    const bool unit_ok = nt0 + (col >> 2) < (int)L.T;
+    const int y_voff = unit_ok ? kb * Nb + col * 16 : y_bytes;
+    // binary16 output: the same unit is four halves, rows are half as long
+    const __amdgpu_buffer_rsrc_t rs_y16 = __builtin_amdgcn_make_buffer_rsrc(y, 0, y_bytes / 2, kBufFlags);
+    const int y_voff16 = unit_ok ? kb * (Nb / 2) + col * 8 : y_bytes / 2;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         float rsr[4];
@@ -359,6 +363,14 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
         for (int p = 0; p < 4; ++p) {
             // (read as a struct of floats: the same scalar type as the writes for alias analysis)
             const float4 f = *reinterpret_cast<const float4*>(rd + p * 4 * RS);
+            if (L.out16) {
+                H2Bits lo, hi;
+                lo.h = h2{(_Float16)f.x, (_Float16)f.y};
+                hi.h = h2{(_Float16)f.z, (_Float16)f.w};
+                const v2i v = {(int)lo.u, (int)hi.u};
+                __builtin_amdgcn_raw_buffer_store_b64(v, rs_y16, y_voff16, (row0 + i * 16 + p * 4) * (Nb / 2) + nt0 * 32, 0);
+                continue;
+            }
             const v4i v = {(int)__float_as_uint(f.x), (int)__float_as_uint(f.y), (int)__float_as_uint(f.z),
                            (int)__float_as_uint(f.w)};
             __builtin_amdgcn_raw_buffer_store_b128(v, rs_y, y_voff, (row0 + i * 16 + p * 4) * Nb + nt0 * 64, 0);

@@ -181,7 +181,7 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_kernel(const uint8_t* __res
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) {
         const int m = kb * 4 + rr;
-        if (m < M) y[(int64_t)m * L.N + n] = fmaf(acc[rr], sx[m], b);
+        if (m < M) store_out(y, (int64_t)m * L.N + n, fmaf(acc[rr], sx[m], b), L.out16);
     }
 }
 
@@ -311,7 +311,7 @@ __global__ __launch_bounds__(512, 2) void skinny_persist_kernel(const uint8_t* _
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
                 const int m = kb * 4 + rr;
-                if (m < M) y[(int64_t)m * L.N + n] = fmaf(acc[rr], sx[m], b);
+                if (m < M) store_out(y, (int64_t)m * L.N + n, fmaf(acc[rr], sx[m], b), L.out16);
             }
         }
     }

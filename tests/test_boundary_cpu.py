@@ -126,6 +126,13 @@ def test_argument_validation_precedes_hip(L):
     assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 192, 64, 2, FAKE, None, None, FAKE, None, 0, None) == UNSUP
     assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 128, 64, 0, FAKE, None, None, None, None, 0, None) == NULL
     assert L.mnnq_linear_prefill_f16(FAKE, -1, 16, 128, 64, 0, FAKE, None, None, FAKE, None, 0, None) == SHAPE
+    # binary16 output: the same checks as the calls they mirror
+    assert L.mnnq_linear_decode_o16(FAKE, 16, 128, 64, 0, FAKE, FAKE, None, None, None) == NULL
+    assert L.mnnq_linear_decode_o16(FAKE, 16, 100, 64, 0, FAKE, FAKE, None, FAKE, None) == SHAPE
+    assert L.mnnq_linear_prefill_o16(FAKE, 0, 16, 128, 64, 0, FAKE, FAKE, None, FAKE, None) == SHAPE
+    assert L.mnnq_linear_prefill_o16(FAKE, 4, 16, 128, 64, 0, FAKE, FAKE, None, ODD, None) == ALIGN
+    assert L.mnnq_linear_decode_f16_o16(FAKE, 16, 128, 64, 3, FAKE, None, FAKE, None) == UNSUP
+    assert L.mnnq_linear_prefill_f16_o16(FAKE, 4, 16, 128, 64, 0, None, None, None, FAKE, None) == NULL
     assert L.mnnq_linear_acc_debug(FAKE, 1, 16, 128, 64, 0, FAKE, None, 0, None) == NULL
     assert L.mnnq_linear_acc_debug(FAKE, 70000, 16, 128, 64, 0, FAKE, FAKE, 0, None) == UNSUP
     pq = L.mnnq_pack_from_quantized
