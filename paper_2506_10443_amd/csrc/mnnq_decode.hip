@@ -91,6 +91,70 @@ __device__ __forceinline__ int quant4_fast(float4 v, float scale, float inv, flo
     return (c0 & 0xff) | ((c1 & 0xff) << 8) | ((c2 & 0xff) << 16) | ((c3 & 0xff) << 24);
 }
 
+// Fused activation quantizer: per-token symmetric int8 (Section 4.2) of the fp32 row x into the
+// workgroup's LDS image - the row as dwords of four codes over the padded packed reduction axis
+// (which runs over the row twice for int8 weights) and the sums of its 16-byte blocks as
+// [chunk][kb][half].  Returns the scale max|x| / 127; the same IEEE operations as mnnq_quant_act.
+// All WAVES * 64 threads of the workgroup call it; it ends with a barrier.
+template <int WAVES>
+__device__ __forceinline__ float quantize_row_to_lds(const float* __restrict__ x, const Layout& L, int* lds_xd,
+                                                     int* lds_xs, float* lds_amax)
+{
+    constexpr int THREADS = WAVES * 64;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int64_t dwords = L.C * 32;                     // padded row of the packed reduction axis
+    const int64_t valid = L.K / 4;
+    const int64_t row_dw = L.Kx / 4;                     // the activation row itself
+    float scale;
+    {
+        const float4* x4 = reinterpret_cast<const float4*>(x);
+        float4 first = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (tid < row_dw) first = x4[tid];
+        float amax = fmaxf(fmaxf(fabsf(first.x), fabsf(first.y)), fmaxf(fabsf(first.z), fabsf(first.w)));
+        for (int64_t i = tid + THREADS; i < row_dw; i += THREADS) {
+            const float4 v = x4[i];
+            amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+        }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
+        if (lane == 0) lds_amax[wave] = amax;
+        __syncthreads();
+        amax = lds_amax[0];
+#pragma unroll
+        for (int w = 1; w < WAVES; ++w) amax = fmaxf(amax, lds_amax[w]);
+        scale = (amax == 0.0f) ? 0.0f : amax / 127.0f;
+        const float inv = (amax == 0.0f) ? 0.0f : 1.0f / scale;
+        const float thr = (inv < 1.0e37f && scale > 1.0e-30f) ? 6.0e-5f : 2.0f;
+        // One dword of the padded row: quantize, store, and add up its 16-byte block (the four dwords
+        // of a block sit in four neighbouring lanes).
+        auto put = [&](int64_t i, const float4 xv) {
+            int v = 0;
+            if (i < valid && scale != 0.0f) v = quant4_fast(xv, scale, inv, thr);
+            lds_xd[i] = v;
+            int sum = __builtin_amdgcn_sdot4(v, 0x01010101, 0, false);
+            sum += __shfl_xor(sum, 1, 64);
+            sum += __shfl_xor(sum, 2, 64);
+            if ((tid & 3) == 0) {
+                const int64_t u = i / 4, c = u / 8;
+                lds_xs[c * 8 + (int)(u % 4) * 2 + (int)(u % 8) / 4] = sum;
+            }
+        };
+        // The first step reuses the values read for the maximum when they are the row's own; it is
+        // kept apart from the loop so that `first` never has to be addressable.
+        // (an if, not a conditional expression: that would select between two addresses)
+        if (tid < dwords) {
+            float4 xv = first;
+            if (tid >= row_dw) xv = x4[tid % row_dw];
+            put(tid, xv);
+        }
+        for (int64_t i = tid + THREADS; i < dwords; i += THREADS) put(i, x4[i % row_dw]);
+        __syncthreads();
+    }
+    return scale;
+}
+
 // LDS of a workgroup: the activation row (K int8, zero padded to C * 128 bytes),
 // the sums of its 16-byte blocks stored as [chunk][kb][half], the partial sums
 // of the split rows and the per-wave maxima of the fused quantizer.
@@ -103,7 +167,6 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
                                                             int32_t* __restrict__ acc, int PW)
 {
     extern __shared__ __align__(16) uint8_t smem[];
-    constexpr int THREADS = WAVES * 64;
     const int64_t C = L.C;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -148,55 +211,11 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
         else cur[u] = ChunkRegs{};
     }
 
-    // ---- activation row -> LDS, one dword (four int8) per thread and step
-    const int64_t dwords = C * 32;                       // padded row of the packed reduction axis
-    const int64_t valid = L.K / 4;
-    const int64_t row_dw = L.Kx / 4;                     // the activation row itself; the packed axis of
-                                                         // int8 weights runs over it twice
+    // ---- activation row -> LDS
+    const int64_t valid = L.K / 4;                       // dwords of the packed reduction axis that carry data
     float scale = 0.0f;
     if (MODE == kFused) {
-        const float4* x4 = reinterpret_cast<const float4*>(static_cast<const float*>(xin));
-        float4 first = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        if (tid < row_dw) first = x4[tid];
-        float amax = fmaxf(fmaxf(fabsf(first.x), fabsf(first.y)), fmaxf(fabsf(first.z), fabsf(first.w)));
-        for (int64_t i = tid + THREADS; i < row_dw; i += THREADS) {
-            const float4 v = x4[i];
-            amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
-        }
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
-        if (lane == 0) lds_amax[wave] = amax;
-        __syncthreads();
-        amax = lds_amax[0];
-#pragma unroll
-        for (int w = 1; w < WAVES; ++w) amax = fmaxf(amax, lds_amax[w]);
-        scale = (amax == 0.0f) ? 0.0f : amax / 127.0f;
-        const float inv = (amax == 0.0f) ? 0.0f : 1.0f / scale;
-        const float thr = (inv < 1.0e37f && scale > 1.0e-30f) ? 6.0e-5f : 2.0f;
-        // One dword of the padded row: quantize, store, and add up its 16-byte block (the four dwords
-        // of a block sit in four neighbouring lanes).
-        auto put = [&](int64_t i, const float4 xv) {
-            int v = 0;
-            if (i < valid && scale != 0.0f) v = quant4_fast(xv, scale, inv, thr);
-            lds_xd[i] = v;
-            int sum = __builtin_amdgcn_sdot4(v, 0x01010101, 0, false);
-            sum += __shfl_xor(sum, 1, 64);
-            sum += __shfl_xor(sum, 2, 64);
-            if ((tid & 3) == 0) {
-                const int64_t u = i / 4, c = u / 8;
-                lds_xs[c * 8 + (int)(u % 4) * 2 + (int)(u % 8) / 4] = sum;
-            }
-        };
-        // The first step reuses the values read for the maximum when they are the row's own; it is
-        // kept apart from the loop so that `first` never has to be addressable.
-        // (an if, not a conditional expression: that would select between two addresses)
-        if (tid < dwords) {
-            float4 xv = first;
-            if (tid >= row_dw) xv = x4[tid % row_dw];
-            put(tid, xv);
-        }
-        for (int64_t i = tid + THREADS; i < dwords; i += THREADS) put(i, x4[i % row_dw]);
-        __syncthreads();
+        scale = quantize_row_to_lds<WAVES>(static_cast<const float*>(xin), L, lds_xd, lds_xs, lds_amax);
     } else {
         // This wave's chunks only, in 16-byte units: unit u of the region is unit c0 * 8 + u of the row.
         const int4* xq16 = reinterpret_cast<const int4*>(static_cast<const int8_t*>(xin) + m * L.Kx);
