@@ -93,7 +93,8 @@ size_t mnnq_packed_size(int64_t N, int64_t K, int group, int mode);
  * its scale (K rounded up to 128, plus 16): for layers above 48 MiB of packed
  * weights it then runs the quantizer as a kernel of its own in front of the
  * GEMV, which is faster there than quantizing inside every workgroup.  The
- * result does not depend on the route.  Other calls return 0. */
+ * result does not depend on the route.  For M > 1 the value is what
+ * mnnq_linear_prefill_fused requires: room for the int8 codes [M, K] and the scales [M]. */
 size_t mnnq_workspace_size(int64_t M, int64_t N, int64_t K, int group, int mode);
 
 /* Load-time step (Section 4.2 Eq. 1, Section 5.1 "rearranged at model loading
@@ -142,6 +143,17 @@ int mnnq_linear_decode_fused(const void *packed, int64_t N, int64_t K, int group
 int mnnq_linear_prefill(const void *packed, int64_t M, int64_t N, int64_t K, int group, int mode,
                         const int8_t *xq, const float *sx, const float *bias, float *y,
                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* Same as mnnq_quant_act followed by mnnq_linear_prefill (Section 4.2: the activations are
+ * quantized to int8 during calculation): x fp32 [M, K] in, y fp32 [M, N] out, bit for bit the
+ * result of the two calls.  The codes and scales pass through `workspace`, which this call
+ * requires: at least mnnq_workspace_size(M, N, K, group, mode) bytes, 16-byte aligned, scratch
+ * (MNNQ_ERR_NULL without it, MNNQ_ERR_SIZE if too small); calls sharing one workspace must not
+ * overlap in time.  M = 1 is accepted too (the value mnnq_workspace_size gives for M = 1 is
+ * large enough), though mnnq_linear_decode_fused is the call made for single tokens. */
+int mnnq_linear_prefill_fused(const void *packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                              const float *x, const float *bias, float *y,
+                              void *workspace, size_t workspace_bytes, void *stream);
 
 /* fp16-activation variants (Section 4.2: quantized weights with fp16 activations on GPUs;
  * W4A16, and W8A16 with mode MNNQ_W8_MIN_FLOAT):

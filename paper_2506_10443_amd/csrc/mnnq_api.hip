@@ -39,6 +39,14 @@ int check_shape(int64_t N, int64_t K, int group, int mode)
 // 32-bit buffer offsets.
 size_t fused_ws_bytes(int64_t K) { return (size_t)((K + 127) / 128 * 128 + 16); }
 
+// Scratch of the fused prefill call: the int8 codes [M, K], then the fp32 scales [M], each part
+// rounded up to 16 bytes.
+size_t fused_prefill_codes_bytes(int64_t M, int64_t K) { return (size_t)((M * K + 15) / 16 * 16); }
+size_t fused_prefill_ws_bytes(int64_t M, int64_t K)
+{
+    return fused_prefill_codes_bytes(M, K) + (size_t)((4 * M + 15) / 16 * 16);
+}
+
 // Above this many bytes of packed weights the decode GEMV is bandwidth bound and
 // quantizing the row once, in a kernel of its own, beats quantizing it in every workgroup.
 constexpr size_t kFusedTwoKernelBytes = (size_t)48 << 20;
@@ -153,7 +161,8 @@ size_t mnnq_workspace_size(int64_t M, int64_t N, int64_t K, int group, int mode)
     if (check_shape(N, K, group, mode) != MNNQ_OK) return 0;
     // Split rows are combined inside a workgroup (decode) or directly in y (prefill): nothing
     // needs scratch.  The fused decode call can use room for the quantized row and its scale.
-    return M == 1 ? fused_ws_bytes(K) : 0;
+    if (M == 1) return fused_ws_bytes(K);
+    return M > 1 ? fused_prefill_ws_bytes(M, K) : 0;
 }
 
 int mnnq_pack_weights(const float* W, int64_t N, int64_t K, int group, int mode, void* packed,
@@ -238,6 +247,22 @@ int mnnq_linear_prefill(const void* packed, int64_t M, int64_t N, int64_t K, int
 {
     (void)workspace_bytes;
     return prefill_impl(packed, M, N, K, group, mode, xq, sx, bias, y, false, workspace, stream);
+}
+
+int mnnq_linear_prefill_fused(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                              const float* x, const float* bias, float* y, void* workspace, size_t workspace_bytes,
+                              void* stream)
+{
+    if (!packed || !x || !y || !workspace) return MNNQ_ERR_NULL;
+    if (M <= 0) return MNNQ_ERR_SHAPE;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    if (!prefill_fits(M, N, K, mode)) return MNNQ_ERR_UNSUPPORTED;
+    if (workspace_bytes < fused_prefill_ws_bytes(M, K)) return MNNQ_ERR_SIZE;
+    if (misaligned(x) || misaligned(workspace)) return MNNQ_ERR_ALIGN;
+    int8_t* xq = static_cast<int8_t*>(workspace);
+    float* sx = reinterpret_cast<float*>(xq + fused_prefill_codes_bytes(M, K));
+    if (int s = launch_quant_act(x, M, K, xq, sx, nullptr, static_cast<hipStream_t>(stream))) return s;
+    return prefill_impl(packed, M, N, K, group, mode, xq, sx, bias, y, false, nullptr, stream);
 }
 
 int mnnq_linear_decode_f16(const void* packed, int64_t N, int64_t K, int group, int mode, const uint16_t* x16,

@@ -55,7 +55,9 @@ def test_packed_size(L):
     assert binding.mnnq_packed_size(0, 128) == 0 and binding.mnnq_packed_size(16, -64) == 0
     assert binding.mnnq_workspace_size(1, 16, 128) == 128 + 16     # optional scratch of the fused decode call
     assert binding.mnnq_workspace_size(1, 16, 192) == 256 + 16
-    assert binding.mnnq_workspace_size(4, 16, 128) == 0 and binding.mnnq_workspace_size(1, 8, 128) == 0
+    assert binding.mnnq_workspace_size(4, 16, 128) == 4 * 128 + 16   # fused prefill call: codes [M,K] + scales [M]
+    assert binding.mnnq_workspace_size(3, 16, 192) == 576 + 16
+    assert binding.mnnq_workspace_size(1, 8, 128) == 0 and binding.mnnq_workspace_size(0, 16, 128) == 0
 
 
 def test_status_strings(L):
@@ -126,6 +128,12 @@ def test_argument_validation_precedes_hip(L):
     assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 192, 64, 2, FAKE, None, None, FAKE, None, 0, None) == UNSUP
     assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 128, 64, 0, FAKE, None, None, None, None, 0, None) == NULL
     assert L.mnnq_linear_prefill_f16(FAKE, -1, 16, 128, 64, 0, FAKE, None, None, FAKE, None, 0, None) == SHAPE
+    pf = L.mnnq_linear_prefill_fused
+    assert pf(FAKE, 4, 16, 128, 64, 0, FAKE, None, FAKE, None, 0, None) == NULL        # the workspace is required
+    assert pf(FAKE, 4, 16, 128, 64, 0, FAKE, None, FAKE, FAKE, 100, None) == SIZE
+    assert pf(FAKE, 4, 16, 128, 64, 0, FAKE, None, FAKE, ODD, 4096, None) == ALIGN
+    assert pf(FAKE, 0, 16, 128, 64, 0, FAKE, None, FAKE, FAKE, 4096, None) == SHAPE
+    assert pf(FAKE, 4, 16, 128, 64, 3, FAKE, None, FAKE, FAKE, 4096, None) == UNSUP
     # binary16 output: the same checks as the calls they mirror
     assert L.mnnq_linear_decode_o16(FAKE, 16, 128, 64, 0, FAKE, FAKE, None, None, None) == NULL
     assert L.mnnq_linear_decode_o16(FAKE, 16, 100, 64, 0, FAKE, FAKE, None, FAKE, None) == SHAPE

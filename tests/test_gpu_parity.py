@@ -316,6 +316,26 @@ def test_few_tokens_share_one_pass_over_the_weights(M, N, K):
         assert np.abs(y0 - y_o[m]).max() <= tol
 
 
+@pytest.mark.parametrize("M,N,K", [(1, 48, 192), (5, 272, 1536), (16, 144, 640), (130, 272, 1536), (300, 400, 1024)])
+def test_prefill_fused_equals_the_two_calls(M, N, K):
+    # activation quantizer inside the call: the codes pass through the caller's workspace and the
+    # same kernels run, so the result is that of mnnq_quant_act + mnnq_linear_prefill bit for bit
+    note("prefill fused", M, N, K)
+    W, x, q, s, z, xq, sx = _layer(N, K, M, 650 + M + N + K, outliers=True)
+    _, y_o = oracle.linear_w4a8(xq, sx, q, s, z, want_acc=False)
+    packed = B.mnnq_pack_weights(dev(W))
+    xd = dev(x)
+    xq_g, sx_g, _ = B.mnnq_quant_act(xd, want_xsum=False)
+    y2 = B.mnnq_linear_prefill(packed, N, K, xq_g, sx_g)
+    ws = torch.full((B.mnnq_workspace_size(M, N, K) + 32,), 0x5a, dtype=torch.uint8, device="cuda:0")
+    yf = B.mnnq_linear_prefill_fused(packed, N, K, xd, workspace=ws[:B.mnnq_workspace_size(M, N, K)])
+    assert torch.equal(yf, y2)
+    assert np.abs(host(yf) - y_o).max() <= TOL_A8 * np.abs(y_o).max()
+    assert (host(ws[-32:]) == 0x5a).all()                      # nothing past the stated size is touched
+    with pytest.raises(B.MnnqError):
+        B.mnnq_linear_prefill_fused(packed, N, K, xd, workspace=ws[:16])
+
+
 def test_prefill_many_tiles_ragged_last_column():
     # More 256-row tiles than the GPU holds at once (several rounds of workgroups), N not a
     # multiple of the tile width: every output is compared.
