@@ -68,6 +68,9 @@ def main() -> int:
     ap.add_argument("--act16", action="store_true",
                     help="also time the fp16-activation entry points (W4A16 / W8A16) per layer: per_layer "
                          "gains decode16_* (GB/s of their algorithmic bytes) and prefill16_* (TFLOP/s)")
+    ap.add_argument("--peaks", action="store_true",
+                    help="also measure what this GPU sustains (streaming read, matrix instructions with and "
+                         "without the epilogue's vector work) and report it as `achievable`")
     ap.add_argument("--out16", action="store_true",
                     help="also time the prefill call with binary16 output per layer (per_layer prefill_o16_*)")
     ap.add_argument("--two-call-decode", action="store_true",
@@ -360,6 +363,35 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    # ---- what the GPU sustains, measured with the library's register-only / streaming helper kernels
+    achievable = None
+    if args.peaks:
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) * 1e-3 / reps
+        sink = torch.zeros(4, dtype=torch.float32, device=dev)
+        big = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)       # 1 GiB: 4x the Infinity Cache
+        t = timed(lambda: B.mnnq_peak_read(big, sink), 10)
+        achievable = {"hbm_read_gbs": round(big.numel() / t / 1e9, 1)}
+        del big
+        cus = torch.cuda.get_device_properties(dev).multi_processor_count
+        ops = {0: 2 * 16 * 16 * 64, 1: 2 * 16 * 16 * 32, 2: 2 * 16 * 16 * 128}
+        for key, kind, epi in (("mfma_int8_tops", 0, 0), ("mfma_fp16_tflops", 1, 0), ("mfma_fp8_tflops", 2, 0),
+                               ("mfma_int8_with_cvt_fma_tops", 0, 1), ("mfma_int8_with_cvt_fma_8int_tops", 0, 2)):
+            best = 0.0
+            for w in (2, 4):
+                n = [0]
+                t = timed(lambda: n.__setitem__(0, B.mnnq_peak_mfma(kind, epi, w, 2000, sink)), 3)
+                best = max(best, cus * 4 * w * n[0] * ops[kind] / t / 1e12)
+            achievable[key] = round(best, 1)
+
     # ---- CPU baseline: the oracle, as it stands, on the host cores, on a bounded sample
     cpu = None
     if not args.no_cpu_baseline:
@@ -413,6 +445,7 @@ def main() -> int:
         "roofline_decode": roof_dec,
         "per_layer": per_layer,
         "cpu_baseline": cpu,
+        "achievable": achievable,
         "pack_gbs_fp32_in": round(pack_bytes_in / (pack_ms * 1e-3) / 1e9, 1),
         "setup_s": round(setup_s, 1),
     }

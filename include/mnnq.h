@@ -198,6 +198,20 @@ int mnnq_pack_from_quantized(const uint8_t *q, const float *scale, const void *z
                              int64_t N, int64_t K, int group, int mode,
                              void *packed, size_t packed_bytes, void *stream);
 
+/* Measurement helpers (used by the benchmark to state what this GPU sustains next to its
+ * published peaks; not part of the linear path).  Both only enqueue kernels; the caller times them.
+ * mnnq_peak_read: reads `bytes` bytes of `buf` (device, 16-byte aligned) once with 128-bit loads,
+ *   consecutive lanes on consecutive addresses; sink: 4 bytes of device memory, practically never
+ *   written.
+ * mnnq_peak_mfma: one workgroup per compute unit with `waves_per_simd` (1..4) waves per SIMD, each
+ *   wave issuing iters * mnnq_peak_mfma_count() matrix instructions on register operands.
+ *   kind 0: int8 16x16x64 (32768 operations each), 1: fp16 16x16x32 (16384), 2: fp8 16x16x128
+ *   (65536).  epilogue (kind 0 only): 0 none, 1: the dependent 4 converts + 4 fused multiply-adds of
+ *   the prefill epilogue after every MFMA, 2: those plus 8 integer operations. */
+int mnnq_peak_read(const void *buf, size_t bytes, void *sink, void *stream);
+int mnnq_peak_mfma(int kind, int epilogue, int waves_per_simd, int iters, void *sink, void *stream);
+int mnnq_peak_mfma_count(void);
+
 /* Integer group accumulators of the W4A8 kernels, for bit-exact checks:
  *   acc[m, n, g] = sum_{k in g} xq[m,k] * (q[n,k] - zero[n,g])      (int32 [M, N, G]);
  * in mode MNNQ_W4_MIN_FLOAT there is no zero point: acc = sum_{k in g} xq[m,k] * q[n,k].

@@ -27,7 +27,7 @@ EXPORTS = (
     "mnnq_linear_prefill", "mnnq_linear_decode_f16", "mnnq_linear_prefill_f16", "mnnq_linear_acc_debug",
     "mnnq_pack_from_quantized",
     "mnnq_linear_decode_o16", "mnnq_linear_prefill_o16", "mnnq_linear_decode_f16_o16", "mnnq_linear_prefill_f16_o16",
-    "mnnq_linear_prefill_fused",
+    "mnnq_linear_prefill_fused", "mnnq_peak_read", "mnnq_peak_mfma", "mnnq_peak_mfma_count",
 )
 
 
@@ -69,6 +69,9 @@ def lib() -> ctypes.CDLL:
         L.mnnq_linear_acc_debug.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, i32, vp]
         L.mnnq_pack_from_quantized.argtypes = [vp, vp, vp, i64, i64, i32, i32, vp, sz, vp]
         L.mnnq_linear_prefill_fused.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.mnnq_peak_read.argtypes = [vp, sz, vp, vp]
+        L.mnnq_peak_mfma.argtypes = [i32, i32, i32, i32, vp, vp]
+        L.mnnq_peak_mfma_count.argtypes = []
         L.mnnq_linear_decode_o16.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, vp]
         L.mnnq_linear_prefill_o16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp]
         L.mnnq_linear_decode_f16_o16.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
@@ -315,3 +318,16 @@ def mnnq_linear_prefill_fused(packed, N: int, K: int, x, bias=None, out=None, wo
                                            _ptr(workspace), workspace.numel(), _stream()),
            "mnnq_linear_prefill_fused")
     return y
+
+
+# ---- measurement helpers
+
+def mnnq_peak_read(buf, sink):
+    """Enqueue one streaming read of the whole tensor `buf`; sink: 4-byte device tensor."""
+    _check(lib().mnnq_peak_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream()), "mnnq_peak_read")
+
+
+def mnnq_peak_mfma(kind: int, epilogue: int, waves_per_simd: int, iters: int, sink) -> int:
+    """Enqueue the matrix-instruction loop; returns the number of matrix instructions per wave."""
+    _check(lib().mnnq_peak_mfma(kind, epilogue, waves_per_simd, iters, _ptr(sink), _stream()), "mnnq_peak_mfma")
+    return iters * int(lib().mnnq_peak_mfma_count())

@@ -1,0 +1,129 @@
+// Measurement helpers, not part of the linear path: what this GPU sustains for the two resources
+// the decode GEMV and the prefill GEMM are priced against (Section 2.1: decode is bound by memory
+// bandwidth, prefill by compute), measured with the simplest kernels that use them.
+//   * mnnq_peak_read: every byte of a buffer is read once with 128-bit loads, consecutive lanes on
+//     consecutive addresses (the access rule of Section 5.1 for GPUs) - the streaming-read rate.
+//   * mnnq_peak_mfma: back-to-back matrix instructions on register operands, optionally followed
+//     by the vector work the prefill epilogue needs per MFMA (4 converts + 4 fused multiply-adds,
+//     or those plus 8 integer operations) in the order the GEMM issues them (MFMA of tile t + 1,
+//     then the dependent epilogue of tile t) - the matrix rate and what each VALU instruction costs.
+// The caller times the launches; nothing is returned but a status.
+#include "mnnq_common.h"
+
+namespace mnnq {
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void peak_read_kernel(const u32x4* __restrict__ p, int64_t n16, uint32_t* sink)
+{
+    uint32_t acc = 0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
+        const u32x4 v = __builtin_nontemporal_load(p + i);
+        acc += v.x ^ v.y ^ v.z ^ v.w;
+    }
+    if (acc == 0x9e3779b9u) *sink = acc;   // keeps the loads alive; practically never taken
+}
+
+// KIND 0: v_mfma_i32_16x16x64_i8, 1: v_mfma_f32_16x16x32_f16, 2: v_mfma_f32_16x16x128_f8f6f4 (fp8).
+// EPI (KIND 0 only) 0: none, 1: 4 cvt + 4 fma per MFMA, 2: the same plus 8 integer operations.
+template <int KIND, int EPI>
+__global__ __launch_bounds__(1024) void peak_mfma_kernel(int iters, int seed, float* sink)
+{
+    constexpr int NT = 16;
+    v4i ai = {seed, seed + 1, seed + 2, seed + 3}, bi[4];
+    for (int j = 0; j < 4; ++j) bi[j] = v4i{seed * 3 + j, seed * 5, seed * 7, seed * 9};
+    h8 ah, bh;
+    for (int i = 0; i < 8; ++i) {
+        ah[i] = (_Float16)(float)(seed + i);
+        bh[i] = (_Float16)(float)(seed - i);
+    }
+    const v8i a8 = {seed, 1, 2, 3, 4, 5, 6, 7}, b8 = {seed, 7, 6, 5, 4, 3, 2, 1};
+    float yacc[NT][4];
+    v4f facc[NT];
+    for (int t = 0; t < NT; ++t) {
+        facc[t] = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int r = 0; r < 4; ++r) yacc[t][r] = 0.f;
+    }
+    const v4i zero = {0, 0, 0, 0};
+    const float sc = 1.0f + seed * 1e-6f;
+    for (int it = 0; it < iters; ++it) {
+        if (KIND == 0) {
+            v4i d = __builtin_amdgcn_mfma_i32_16x16x64_i8(ai, bi[0], zero, 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                v4i d_nxt = d;
+                if (t + 1 < NT) {
+                    d_nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(ai, bi[(t + 1) & 3], zero, 0, 0, 0);
+                    asm volatile("" : "+v"(d), "+v"(d_nxt));
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    if (EPI >= 1) yacc[t][r] = fmaf(sc, (float)d[r], yacc[t][r]);
+                    if (EPI == 2) bi[(t + 2) & 3][r] = (bi[(t + 2) & 3][r] & 0x0f0f0f0f) + seed;
+                }
+                if (EPI == 0) asm volatile("" : "+v"(d));
+                asm volatile("" : "+v"(yacc[t][0]), "+v"(yacc[t][1]), "+v"(yacc[t][2]), "+v"(yacc[t][3]),
+                             "+v"(bi[(t + 2) & 3]));
+                d = d_nxt;
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                if (KIND == 1) facc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, bh, facc[t], 0, 0, 0);
+                if (KIND == 2)
+                    facc[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, facc[t], 0, 0, 0, 0, 0, 0);
+            }
+        }
+    }
+    float s = (float)bi[0][0];
+    for (int t = 0; t < NT; ++t) s += yacc[t][0] + yacc[t][1] + yacc[t][2] + yacc[t][3] + facc[t][0];
+    if (s == 12345.678f) *sink = s;        // keeps the arithmetic alive; practically never taken
+}
+
+}  // namespace
+}  // namespace mnnq
+
+using namespace mnnq;
+
+extern "C" {
+
+int mnnq_peak_read(const void* buf, size_t bytes, void* sink, void* stream)
+{
+    if (!buf || !sink) return MNNQ_ERR_NULL;
+    if (bytes < 16) return MNNQ_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(buf) & 15u) return MNNQ_ERR_ALIGN;
+    const int64_t n16 = (int64_t)(bytes / 16);
+    const int blocks = num_cus() * 16;
+    hipLaunchKernelGGL(peak_read_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const u32x4*>(buf), n16, static_cast<uint32_t*>(sink));
+    MNNQ_HIP_TRY(hipGetLastError());
+    return MNNQ_OK;
+}
+
+int mnnq_peak_mfma(int kind, int epilogue, int waves_per_simd, int iters, void* sink, void* stream)
+{
+    if (!sink) return MNNQ_ERR_NULL;
+    if (iters <= 0 || waves_per_simd < 1 || waves_per_simd > 4) return MNNQ_ERR_SHAPE;
+    if (kind < 0 || kind > 2 || epilogue < 0 || epilogue > 2 || (kind != 0 && epilogue != 0)) return MNNQ_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)num_cus()), block(256u * (unsigned)waves_per_simd);   // one workgroup per CU
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float* out = static_cast<float*>(sink);
+    if (kind == 0 && epilogue == 0) hipLaunchKernelGGL((peak_mfma_kernel<0, 0>), grid, block, 0, st, iters, 1, out);
+    if (kind == 0 && epilogue == 1) hipLaunchKernelGGL((peak_mfma_kernel<0, 1>), grid, block, 0, st, iters, 1, out);
+    if (kind == 0 && epilogue == 2) hipLaunchKernelGGL((peak_mfma_kernel<0, 2>), grid, block, 0, st, iters, 1, out);
+    if (kind == 1) hipLaunchKernelGGL((peak_mfma_kernel<1, 0>), grid, block, 0, st, iters, 1, out);
+    if (kind == 2) hipLaunchKernelGGL((peak_mfma_kernel<2, 0>), grid, block, 0, st, iters, 1, out);
+    MNNQ_HIP_TRY(hipGetLastError());
+    return MNNQ_OK;
+}
+
+int mnnq_peak_mfma_count(void) { return 16; }   // matrix instructions per iteration and wave
+
+}  // extern "C"

@@ -128,6 +128,9 @@ def test_argument_validation_precedes_hip(L):
     assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 192, 64, 2, FAKE, None, None, FAKE, None, 0, None) == UNSUP
     assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 128, 64, 0, FAKE, None, None, None, None, 0, None) == NULL
     assert L.mnnq_linear_prefill_f16(FAKE, -1, 16, 128, 64, 0, FAKE, None, None, FAKE, None, 0, None) == SHAPE
+    assert L.mnnq_peak_read(None, 1024, FAKE, None) == NULL and L.mnnq_peak_read(FAKE, 8, FAKE, None) == SHAPE
+    assert L.mnnq_peak_mfma(3, 0, 2, 10, FAKE, None) == UNSUP and L.mnnq_peak_mfma(1, 1, 2, 10, FAKE, None) == UNSUP
+    assert L.mnnq_peak_mfma(0, 0, 5, 10, FAKE, None) == SHAPE and L.mnnq_peak_mfma_count() == 16
     pf = L.mnnq_linear_prefill_fused
     assert pf(FAKE, 4, 16, 128, 64, 0, FAKE, None, FAKE, None, 0, None) == NULL        # the workspace is required
     assert pf(FAKE, 4, 16, 128, 64, 0, FAKE, None, FAKE, FAKE, 100, None) == SIZE
