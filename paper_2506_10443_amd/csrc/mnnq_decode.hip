@@ -96,9 +96,31 @@ __device__ __forceinline__ int quant4_fast(float4 v, float scale, float inv, flo
 // (which runs over the row twice for int8 weights) and the sums of its 16-byte blocks as
 // [chunk][kb][half].  Returns the scale max|x| / 127; the same IEEE operations as mnnq_quant_act.
 // All WAVES * 64 threads of the workgroup call it; it ends with a barrier.
+//
+// Loads return in the order they were issued, so a row that is read after the weight stream has
+// been started cannot be touched before all those weights have arrived.  The caller therefore
+// reads the first XR float4 per thread (elements tid + j * THREADS) before it starts the weights
+// and passes them in; rows that fit (K <= 4 * XR * THREADS) are then quantized without another
+// load, longer ones read the rest from memory.
+constexpr int kRowRegs = 2;
+
 template <int WAVES>
-__device__ __forceinline__ float quantize_row_to_lds(const float* __restrict__ x, const Layout& L, int* lds_xd,
-                                                     int* lds_xs, float* lds_amax)
+__device__ __forceinline__ void preload_row(const float* __restrict__ x, const Layout& L, float4 (&xr)[kRowRegs])
+{
+    constexpr int THREADS = WAVES * 64;
+    const int64_t row_dw = L.Kx / 4;
+    const float4* x4 = reinterpret_cast<const float4*>(x);
+#pragma unroll
+    for (int j = 0; j < kRowRegs; ++j) {
+        const int64_t i = (int64_t)threadIdx.x + j * THREADS;
+        xr[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (i < row_dw) xr[j] = x4[i];
+    }
+}
+
+template <int WAVES>
+__device__ __forceinline__ float quantize_row_to_lds(const float* __restrict__ x, const float4 (&xr)[kRowRegs],
+                                                     const Layout& L, int* lds_xd, int* lds_xs, float* lds_amax)
 {
     constexpr int THREADS = WAVES * 64;
     const int tid = threadIdx.x;
@@ -107,51 +129,57 @@ __device__ __forceinline__ float quantize_row_to_lds(const float* __restrict__ x
     const int64_t dwords = L.C * 32;                     // padded row of the packed reduction axis
     const int64_t valid = L.K / 4;
     const int64_t row_dw = L.Kx / 4;                     // the activation row itself
-    float scale;
-    {
-        const float4* x4 = reinterpret_cast<const float4*>(x);
-        float4 first = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        if (tid < row_dw) first = x4[tid];
-        float amax = fmaxf(fmaxf(fabsf(first.x), fabsf(first.y)), fmaxf(fabsf(first.z), fabsf(first.w)));
-        for (int64_t i = tid + THREADS; i < row_dw; i += THREADS) {
-            const float4 v = x4[i];
-            amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
-        }
+    const float4* x4 = reinterpret_cast<const float4*>(x);
+
+    float amax = 0.0f;
 #pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
-        if (lane == 0) lds_amax[wave] = amax;
-        __syncthreads();
-        amax = lds_amax[0];
-#pragma unroll
-        for (int w = 1; w < WAVES; ++w) amax = fmaxf(amax, lds_amax[w]);
-        scale = (amax == 0.0f) ? 0.0f : amax / 127.0f;
-        const float inv = (amax == 0.0f) ? 0.0f : 1.0f / scale;
-        const float thr = (inv < 1.0e37f && scale > 1.0e-30f) ? 6.0e-5f : 2.0f;
-        // One dword of the padded row: quantize, store, and add up its 16-byte block (the four dwords
-        // of a block sit in four neighbouring lanes).
-        auto put = [&](int64_t i, const float4 xv) {
-            int v = 0;
-            if (i < valid && scale != 0.0f) v = quant4_fast(xv, scale, inv, thr);
-            lds_xd[i] = v;
-            int sum = __builtin_amdgcn_sdot4(v, 0x01010101, 0, false);
-            sum += __shfl_xor(sum, 1, 64);
-            sum += __shfl_xor(sum, 2, 64);
-            if ((tid & 3) == 0) {
-                const int64_t u = i / 4, c = u / 8;
-                lds_xs[c * 8 + (int)(u % 4) * 2 + (int)(u % 8) / 4] = sum;
-            }
-        };
-        // The first step reuses the values read for the maximum when they are the row's own; it is
-        // kept apart from the loop so that `first` never has to be addressable.
-        // (an if, not a conditional expression: that would select between two addresses)
-        if (tid < dwords) {
-            float4 xv = first;
-            if (tid >= row_dw) xv = x4[tid % row_dw];
-            put(tid, xv);
-        }
-        for (int64_t i = tid + THREADS; i < dwords; i += THREADS) put(i, x4[i % row_dw]);
-        __syncthreads();
+    for (int j = 0; j < kRowRegs; ++j)                   // zeros past the row do not change the maximum
+        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(xr[j].x), fabsf(xr[j].y)), fmaxf(fabsf(xr[j].z), fabsf(xr[j].w))));
+    for (int64_t i = tid + kRowRegs * THREADS; i < row_dw; i += THREADS) {
+        const float4 v = x4[i];
+        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
     }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
+    if (lane == 0) lds_amax[wave] = amax;
+    __syncthreads();
+    amax = lds_amax[0];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) amax = fmaxf(amax, lds_amax[w]);
+    const float scale = (amax == 0.0f) ? 0.0f : amax / 127.0f;
+    const float inv = (amax == 0.0f) ? 0.0f : 1.0f / scale;
+    const float thr = (inv < 1.0e37f && scale > 1.0e-30f) ? 6.0e-5f : 2.0f;
+    // One dword of the padded row: quantize, store, and add up its 16-byte block (the four dwords
+    // of a block sit in four neighbouring lanes).
+    auto put = [&](int64_t i, const float4 xv) {
+        int v = 0;
+        if (i < valid && scale != 0.0f) v = quant4_fast(xv, scale, inv, thr);
+        lds_xd[i] = v;
+        int sum = __builtin_amdgcn_sdot4(v, 0x01010101, 0, false);
+        sum += __shfl_xor(sum, 1, 64);
+        sum += __shfl_xor(sum, 2, 64);
+        if ((tid & 3) == 0) {
+            const int64_t u = i / 4, c = u / 8;
+            lds_xs[c * 8 + (int)(u % 4) * 2 + (int)(u % 8) / 4] = sum;
+        }
+    };
+    // The row itself: first the elements already in registers, then the rest from memory.  (No
+    // conditional between a register value and a load: it would select between two addresses and
+    // force the registers into scratch memory.)  The row length is a multiple of 16 dwords, so the
+    // four lanes of a block always take the same branch.
+#pragma unroll
+    for (int j = 0; j < kRowRegs; ++j) {
+        const int64_t i = (int64_t)tid + j * THREADS;
+        if (i < row_dw) put(i, xr[j]);
+    }
+    for (int64_t i = tid + kRowRegs * THREADS; i < row_dw; i += THREADS) put(i, x4[i]);
+    // Past the row: its second pass (int8 weights) and the zero padding of the last chunk.
+    for (int64_t i = row_dw + tid; i < dwords; i += THREADS) {
+        float4 xv = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (i < valid) xv = x4[i % row_dw];
+        put(i, xv);
+    }
+    __syncthreads();
     return scale;
 }
 
@@ -203,6 +231,10 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
                                                      (tile * C + c0) * 16 + row);
     const int64_t n_chunks = active ? (c1 - c0) : 0;
 
+    // Fused quantizer: the first elements of the row are requested ahead of the weights, so that
+    // they arrive first (see quantize_row_to_lds).
+    float4 xr[kRowRegs];
+    if (MODE == kFused) preload_row<WAVES>(static_cast<const float*>(xin), L, xr);
     // Start the weight stream before the activation row is touched: it does not depend on x.
     ChunkRegs cur[UNROLL];
 #pragma unroll
@@ -215,7 +247,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
     const int64_t valid = L.K / 4;                       // dwords of the packed reduction axis that carry data
     float scale = 0.0f;
     if (MODE == kFused) {
-        scale = quantize_row_to_lds<WAVES>(static_cast<const float*>(xin), L, lds_xd, lds_xs, lds_amax);
+        scale = quantize_row_to_lds<WAVES>(static_cast<const float*>(xin), xr, L, lds_xd, lds_xs, lds_amax);
     } else {
         // This wave's chunks only, in 16-byte units: unit u of the region is unit c0 * 8 + u of the row.
         const int4* xq16 = reinterpret_cast<const int4*>(static_cast<const int8_t*>(xin) + m * L.Kx);
