@@ -155,15 +155,3 @@ def test_full_size_gateup_sampled():
     ws = torch.empty(B.mnnq_workspace_size(1, N, K), dtype=torch.uint8, device="cuda:0")
     yf = host(B.mnnq_linear_decode_fused(packed, N, K, dev(x[0]), workspace=ws, mode=MINF))
     assert np.array_equal(yf, yd)
-
-
-def test_fp16_activation_calls_refuse_the_form():
-    W = synth.weights(16, 128, 1)
-    packed = B.mnnq_pack_weights(dev(W), mode=MINF)
-    x16 = dev(synth.activations_f16(1, 128, 2))
-    with pytest.raises(B.MnnqError):
-        B.lib()  # make sure the library is loaded before poking at the raw entry point
-        st = B.lib().mnnq_linear_decode_f16(packed.data_ptr(), 16, 128, 64, MINF, x16.data_ptr(), None,
-                                            torch.empty(16, device="cuda:0").data_ptr(), None, 0, None)
-        if st != 0:
-            raise B.MnnqError(st, "mnnq_linear_decode_f16")
