@@ -35,7 +35,8 @@ def close_to_oracle(y16, y_o, tol):
 
 
 SHAPES = [(1, 16, 64), (4, 48, 192), (16, 272, 1536), (33, 272, 640), (130, 144, 1536), (300, 400, 1024),
-          (513, 1040, 448)]
+          (513, 1040, 448),
+          (100, 144, 8192)]   # few tiles, long rows: the fp32 call splits K over two workgroups, this one must not
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
@@ -59,7 +60,11 @@ def test_w4a8_out16(M, N, K):
         finally:
             os.environ.pop("MNNQ_PREFILL_TILE", None)
             os.environ.pop("MNNQ_NO_SKINNY", None)
-        assert y16.dtype == torch.float16 and torch.equal(y16, y32.to(torch.float16)), cfg
+        assert y16.dtype == torch.float16
+        if K < 8192 or cfg:       # same tile plan and summation order as the fp32 call
+            assert torch.equal(y16, y32.to(torch.float16)), cfg
+        else:                     # the fp32 call adds two K halves in the output array
+            assert (y16.float() - y32).abs().max().item() <= 2.0 ** -10 * y32.abs().max().item()
         close_to_oracle(host(y16), y_o, TOL_A8)
     y32 = B.mnnq_linear_decode(packed, N, K, xqd[0].contiguous(), sxd[:1].contiguous(), bias=bd)
     y16 = B.mnnq_linear_decode_o16(packed, N, K, xqd[0].contiguous(), sxd[:1].contiguous(), bias=bd)
