@@ -118,27 +118,12 @@ __device__ __forceinline__ void preload_row(const float* __restrict__ x, const L
     }
 }
 
+// Maximum over the workgroup (one barrier) -> quantization scale max|x| / 127.
 template <int WAVES>
-__device__ __forceinline__ float quantize_row_to_lds(const float* __restrict__ x, const float4 (&xr)[kRowRegs],
-                                                     const Layout& L, int* lds_xd, int* lds_xs, float* lds_amax)
+__device__ __forceinline__ float workgroup_scale(float amax, float* lds_amax)
 {
-    constexpr int THREADS = WAVES * 64;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int64_t dwords = L.C * 32;                     // padded row of the packed reduction axis
-    const int64_t valid = L.K / 4;
-    const int64_t row_dw = L.Kx / 4;                     // the activation row itself
-    const float4* x4 = reinterpret_cast<const float4*>(x);
-
-    float amax = 0.0f;
-#pragma unroll
-    for (int j = 0; j < kRowRegs; ++j)                   // zeros past the row do not change the maximum
-        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(xr[j].x), fabsf(xr[j].y)), fmaxf(fabsf(xr[j].z), fabsf(xr[j].w))));
-    for (int64_t i = tid + kRowRegs * THREADS; i < row_dw; i += THREADS) {
-        const float4 v = x4[i];
-        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
-    }
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
     if (lane == 0) lds_amax[wave] = amax;
@@ -146,23 +131,57 @@ __device__ __forceinline__ float quantize_row_to_lds(const float* __restrict__ x
     amax = lds_amax[0];
 #pragma unroll
     for (int w = 1; w < WAVES; ++w) amax = fmaxf(amax, lds_amax[w]);
-    const float scale = (amax == 0.0f) ? 0.0f : amax / 127.0f;
-    const float inv = (amax == 0.0f) ? 0.0f : 1.0f / scale;
-    const float thr = (inv < 1.0e37f && scale > 1.0e-30f) ? 6.0e-5f : 2.0f;
-    // One dword of the padded row: quantize, store, and add up its 16-byte block (the four dwords
-    // of a block sit in four neighbouring lanes).
-    auto put = [&](int64_t i, const float4 xv) {
+    return (amax == 0.0f) ? 0.0f : amax / 127.0f;
+}
+
+__device__ __forceinline__ float max_abs4(float amax, const float4 v)
+{
+    return fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+}
+
+// One dword i of the padded row: quantize, store, and add up its 16-byte block (the four dwords
+// of a block sit in four neighbouring lanes, which all call this together).
+struct RowQuantizer {
+    float scale, inv, thr;
+    int64_t valid;
+    int* lds_xd;
+    int* lds_xs;
+    __device__ __forceinline__ explicit RowQuantizer(float s, int64_t valid_, int* xd, int* xs)
+        : scale(s), inv(s == 0.0f ? 0.0f : 1.0f / s), valid(valid_), lds_xd(xd), lds_xs(xs)
+    {
+        thr = (inv < 1.0e37f && scale > 1.0e-30f) ? 6.0e-5f : 2.0f;
+    }
+    __device__ __forceinline__ void put(int64_t i, const float4 xv) const
+    {
         int v = 0;
         if (i < valid && scale != 0.0f) v = quant4_fast(xv, scale, inv, thr);
         lds_xd[i] = v;
         int sum = __builtin_amdgcn_sdot4(v, 0x01010101, 0, false);
         sum += __shfl_xor(sum, 1, 64);
         sum += __shfl_xor(sum, 2, 64);
-        if ((tid & 3) == 0) {
+        if ((threadIdx.x & 3) == 0) {
             const int64_t u = i / 4, c = u / 8;
             lds_xs[c * 8 + (int)(u % 4) * 2 + (int)(u % 8) / 4] = sum;
         }
-    };
+    }
+};
+
+template <int WAVES>
+__device__ __forceinline__ float quantize_row_to_lds(const float* __restrict__ x, const float4 (&xr)[kRowRegs],
+                                                     const Layout& L, int* lds_xd, int* lds_xs, float* lds_amax)
+{
+    constexpr int THREADS = WAVES * 64;
+    const int tid = threadIdx.x;
+    const int64_t dwords = L.C * 32;                     // padded row of the packed reduction axis
+    const int64_t valid = L.K / 4;
+    const int64_t row_dw = L.Kx / 4;                     // the activation row itself
+    const float4* x4 = reinterpret_cast<const float4*>(x);
+
+    float amax = 0.0f;
+#pragma unroll
+    for (int j = 0; j < kRowRegs; ++j) amax = max_abs4(amax, xr[j]);   // zeros past the row do not change the maximum
+    for (int64_t i = tid + kRowRegs * THREADS; i < row_dw; i += THREADS) amax = max_abs4(amax, x4[i]);
+    const RowQuantizer q(workgroup_scale<WAVES>(amax, lds_amax), valid, lds_xd, lds_xs);
     // The row itself: first the elements already in registers, then the rest from memory.  (No
     // conditional between a register value and a load: it would select between two addresses and
     // force the registers into scratch memory.)  The row length is a multiple of 16 dwords, so the
@@ -170,17 +189,17 @@ __device__ __forceinline__ float quantize_row_to_lds(const float* __restrict__ x
 #pragma unroll
     for (int j = 0; j < kRowRegs; ++j) {
         const int64_t i = (int64_t)tid + j * THREADS;
-        if (i < row_dw) put(i, xr[j]);
+        if (i < row_dw) q.put(i, xr[j]);
     }
-    for (int64_t i = tid + kRowRegs * THREADS; i < row_dw; i += THREADS) put(i, x4[i]);
+    for (int64_t i = tid + kRowRegs * THREADS; i < row_dw; i += THREADS) q.put(i, x4[i]);
     // Past the row: its second pass (int8 weights) and the zero padding of the last chunk.
     for (int64_t i = row_dw + tid; i < dwords; i += THREADS) {
         float4 xv = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         if (i < valid) xv = x4[i % row_dw];
-        put(i, xv);
+        q.put(i, xv);
     }
     __syncthreads();
-    return scale;
+    return q.scale;
 }
 
 // LDS of a workgroup: the activation row (K int8, zero padded to C * 128 bytes),
