@@ -54,7 +54,7 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--model", default="qwen2-7b", choices=["qwen2-1.5b", "qwen2-7b", "llama3-8b"])
     ap.add_argument("--phase", default="both", choices=["both", "decode", "prefill"])
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
@@ -68,6 +68,11 @@ def main() -> int:
     ap.add_argument("--act16", action="store_true",
                     help="also time the fp16-activation entry points (W4A16 / W8A16) per layer: per_layer "
                          "gains decode16_* (GB/s of their algorithmic bytes) and prefill16_* (TFLOP/s)")
+    ap.add_argument("--separate-projections", action="store_true",
+                    help="run q, k, v and gate, up as launches of their own instead of concatenated along N")
+    ap.add_argument("--warm", action="store_true",
+                    help="also time the decode GEMV of each layer on ONE packed buffer over and over (weights stay "
+                         "in the Infinity Cache): per_layer decode_*_warm, a cache-resident figure, not HBM")
     ap.add_argument("--peaks", action="store_true",
                     help="also measure what this GPU sustains (streaming read, matrix instructions with and "
                          "without the epilogue's vector work) and report it as `achievable`")
@@ -102,7 +107,7 @@ def main() -> int:
     spec = synth.MODELS[args.model]
     n_blocks = spec["blocks"]
     M_pre = spec["prefill_m"]
-    layers = synth.block_layers(args.model, fused=True)   # q|k|v and gate|up share their input
+    layers = synth.block_layers(args.model, fused=not args.separate_projections)   # q|k|v and gate|up share their input
 
     # ---- weights: one block drawn on the host (seeded), packed into n_blocks distinct buffers
     t0 = time.time()
@@ -286,6 +291,10 @@ def main() -> int:
                                            "gbs": round(decode_bytes(N, K) / (t * 1e-3) / 1e9, 1)}
             fns += lay
             byt += n_blocks * decode_bytes(N, K)
+            if args.warm:
+                t = time_launches(lay[:1] * n_blocks, 4)
+                per_layer["decode_" + name + "_warm"] = {"us": round(t * 1e3, 2), "cache_resident": True,
+                                                         "gbs": round(decode_bytes(N, K) / (t * 1e-3) / 1e9, 1)}
         t = time_launches(fns, 4)
         ach = byt / len(fns) / (t * 1e-3) / 1e9
         roof_dec = {"kernel": "decode_kernel (W4A8 GEMV), all %d block launches of a pass" % len(fns),
@@ -433,7 +442,8 @@ def main() -> int:
                                "q|k|v and gate|up concatenated along N" %
                                (args.model, n_blocks, " + lm_head" if lm else "", M_pre, n_blocks),
                    "group": 64, "graph": not args.no_graph, "phase": args.phase,
-                   "fused_decode_quant": bool(args.fused_decode), "weight_mode": args.weight_mode},
+                   "fused_decode_quant": bool(args.fused_decode), "weight_mode": args.weight_mode,
+                   "concatenated_projections": not args.separate_projections},
         "decode_ms": round(dec_mean, 4) if do_dec else None,
         "decode_gbs": round(dec_gbs, 1) if do_dec else None,
         "decode_frac_of_hbm_peak": round(dec_gbs / HBM_PEAK_GBS, 4) if do_dec else None,
