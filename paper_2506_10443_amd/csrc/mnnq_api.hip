@@ -232,7 +232,9 @@ int mnnq_linear_decode_fused(const void* packed, int64_t N, int64_t K, int group
         return MNNQ_ERR_ALIGN;
     const Layout L = make_layout(N, K, mode);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (workspace && workspace_bytes >= fused_ws_bytes(K) && L.total() > kFusedTwoKernelBytes) {
+    size_t two_kernel_bytes = kFusedTwoKernelBytes;
+    if (const char* e = getenv("MNNQ_FUSED_TWO_KERNEL_MIB")) two_kernel_bytes = (size_t)atoll(e) << 20;   // tuning only
+    if (workspace && workspace_bytes >= fused_ws_bytes(K) && L.total() > two_kernel_bytes) {
         int8_t* xq = static_cast<int8_t*>(workspace);
         float* sx = reinterpret_cast<float*>(xq + (K + 127) / 128 * 128);
         if (int s = launch_quant_act(x, 1, K, xq, sx, nullptr, st)) return s;

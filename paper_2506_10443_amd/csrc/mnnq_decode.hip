@@ -20,7 +20,7 @@
 //           scale = max|x| / 127, the same IEEE operations as mnnq_quant_act.
 //           Every workgroup repeats this for the whole row; the rounding is done
 //           with a multiply and falls back to the division only next to a tie
-//           (see quant1_fast), which gives the same codes at a third of the cost.
+//           (see quant4_fast), which gives the same codes at a fraction of the cost.
 // This file is compiled with -ffp-contract=off for that reason.
 #include "mnnq_common.h"
 
@@ -72,23 +72,27 @@ __device__ __forceinline__ int dot16(uint32_t wa, uint32_t wb, const int4& x)
 // a correctly rounded division per element is what makes the repeated row
 // quantization expensive.  r = x * fl(1 / scale) differs from fl(x / scale) by
 // less than 3 * 2^-24 * 127.5 < 2.3e-5, so both round to the same integer unless
-// r is within that distance of a half-integer; only then (about one element in
-// ten thousand) the division is done.
-// (thr is 6e-5 normally; 2 - "always divide" - when 1 / scale is not a normal number.)
-__device__ __forceinline__ int quant1_fast(float v, float scale, float inv, float thr)
+// r is within that distance of a half-integer, i.e. unless |r - rint(r)| (exact:
+// the two are within 0.5 of each other) exceeds 0.5 - 6e-5; only then (about one
+// element in ten thousand) the division is done, for the four elements of a dword
+// together.  |r| <= 127 (1 + 2^-22) in this path, so rint(r) needs no clamp.
+// (lim is 0.5 - 6e-5 normally; negative - "always divide" - when 1 / scale is not
+// a normal number; the division path clamps like mnnq_quant_act does.)
+__device__ __forceinline__ int quant4_fast(float4 v, float scale, float inv, float lim)
 {
-    const float r = v * inv;
-    float t = rintf(r);
-    const float frac = r - floorf(r);                    // exact
-    if (!(fabsf(frac - 0.5f) >= thr)) t = rintf(v / scale);
-    return (int)fminf(fmaxf(t, -127.0f), 127.0f);
-}
-
-__device__ __forceinline__ int quant4_fast(float4 v, float scale, float inv, float thr)
-{
-    const int c0 = quant1_fast(v.x, scale, inv, thr), c1 = quant1_fast(v.y, scale, inv, thr);
-    const int c2 = quant1_fast(v.z, scale, inv, thr), c3 = quant1_fast(v.w, scale, inv, thr);
-    return (c0 & 0xff) | ((c1 & 0xff) << 8) | ((c2 & 0xff) << 16) | ((c3 & 0xff) << 24);
+    float t0 = rintf(v.x * inv), t1 = rintf(v.y * inv), t2 = rintf(v.z * inv), t3 = rintf(v.w * inv);
+    const float d0 = fabsf(v.x * inv - t0), d1 = fabsf(v.y * inv - t1);
+    const float d2 = fabsf(v.z * inv - t2), d3 = fabsf(v.w * inv - t3);
+    if (!(fmaxf(fmaxf(d0, d1), fmaxf(d2, d3)) <= lim)) {
+        t0 = fminf(fmaxf(rintf(v.x / scale), -127.0f), 127.0f);
+        t1 = fminf(fmaxf(rintf(v.y / scale), -127.0f), 127.0f);
+        t2 = fminf(fmaxf(rintf(v.z / scale), -127.0f), 127.0f);
+        t3 = fminf(fmaxf(rintf(v.w / scale), -127.0f), 127.0f);
+    }
+    // low bytes of the four integers into one dword
+    const uint32_t lo = __builtin_amdgcn_perm((uint32_t)(int)t1, (uint32_t)(int)t0, 0x0c0c0400u);
+    const uint32_t hi = __builtin_amdgcn_perm((uint32_t)(int)t3, (uint32_t)(int)t2, 0x04000c0cu);
+    return (int)(lo | hi);
 }
 
 // Fused activation quantizer: per-token symmetric int8 (Section 4.2) of the fp32 row x into the
@@ -142,19 +146,19 @@ __device__ __forceinline__ float max_abs4(float amax, const float4 v)
 // One dword i of the padded row: quantize, store, and add up its 16-byte block (the four dwords
 // of a block sit in four neighbouring lanes, which all call this together).
 struct RowQuantizer {
-    float scale, inv, thr;
+    float scale, inv, lim;
     int64_t valid;
     int* lds_xd;
     int* lds_xs;
     __device__ __forceinline__ explicit RowQuantizer(float s, int64_t valid_, int* xd, int* xs)
         : scale(s), inv(s == 0.0f ? 0.0f : 1.0f / s), valid(valid_), lds_xd(xd), lds_xs(xs)
     {
-        thr = (inv < 1.0e37f && scale > 1.0e-30f) ? 6.0e-5f : 2.0f;
+        lim = (inv < 1.0e37f && scale > 1.0e-30f) ? 0.5f - 6.0e-5f : -1.0f;   // largest |r - rint(r)| of the fast path
     }
     __device__ __forceinline__ void put(int64_t i, const float4 xv) const
     {
         int v = 0;
-        if (i < valid && scale != 0.0f) v = quant4_fast(xv, scale, inv, thr);
+        if (i < valid && scale != 0.0f) v = quant4_fast(xv, scale, inv, lim);
         lds_xd[i] = v;
         int sum = __builtin_amdgcn_sdot4(v, 0x01010101, 0, false);
         sum += __shfl_xor(sum, 1, 64);
