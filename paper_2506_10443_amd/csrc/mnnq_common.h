@@ -86,6 +86,42 @@ __device__ __forceinline__ void store_out(float* y, int64_t i, float v, bool out
     if (out16) reinterpret_cast<_Float16*>(y)[i] = (_Float16)v;
     else y[i] = v;
 }
+
+// Activation codes (Section 4.2, per-token symmetric int8): the definition is
+// clamp(rint(fl(x / scale)), -127, 127) with IEEE binary32 operations, but
+// a correctly rounded division per element is expensive (about ten vector
+// instructions).  r = x * fl(1 / scale) differs from fl(x / scale) by
+// less than 3 * 2^-24 * 127.5 < 2.3e-5, so both round to the same integer unless
+// r is within that distance of a half-integer, i.e. unless |r - rint(r)| (exact:
+// the two are within 0.5 of each other) exceeds 0.5 - 6e-5; only then (about one
+// element in ten thousand) the division is done, for the four elements of a dword
+// together.  |r| <= 127 (1 + 2^-22) in this path, so rint(r) needs no clamp.
+// (lim is 0.5 - 6e-5 normally; negative - "always divide" - when 1 / scale is not
+// a normal number; the division path clamps as the definition does.)
+// Callers are compiled with -ffp-contract=off: x * inv - rint(x * inv) must be a
+// product rounded to binary32 and an exact subtraction.
+__device__ __forceinline__ int quant4_fast(float4 v, float scale, float inv, float lim)
+{
+    float t0 = rintf(v.x * inv), t1 = rintf(v.y * inv), t2 = rintf(v.z * inv), t3 = rintf(v.w * inv);
+    const float d0 = fabsf(v.x * inv - t0), d1 = fabsf(v.y * inv - t1);
+    const float d2 = fabsf(v.z * inv - t2), d3 = fabsf(v.w * inv - t3);
+    if (!(fmaxf(fmaxf(d0, d1), fmaxf(d2, d3)) <= lim)) {
+        t0 = fminf(fmaxf(rintf(v.x / scale), -127.0f), 127.0f);
+        t1 = fminf(fmaxf(rintf(v.y / scale), -127.0f), 127.0f);
+        t2 = fminf(fmaxf(rintf(v.z / scale), -127.0f), 127.0f);
+        t3 = fminf(fmaxf(rintf(v.w / scale), -127.0f), 127.0f);
+    }
+    // low bytes of the four integers into one dword
+    const uint32_t lo = __builtin_amdgcn_perm((uint32_t)(int)t1, (uint32_t)(int)t0, 0x0c0c0400u);
+    const uint32_t hi = __builtin_amdgcn_perm((uint32_t)(int)t3, (uint32_t)(int)t2, 0x04000c0cu);
+    return (int)(lo | hi);
+}
+
+__device__ __forceinline__ float quant_fast_limit(float scale, float inv)
+{
+    return (inv < 1.0e37f && scale > 1.0e-30f) ? 0.5f - 6.0e-5f : -1.0f;   // largest |r - rint(r)| of the fast path
+}
+
 #endif
 
 // Records a failing HIP call for mnnq_last_hip_error() and maps it to a status.

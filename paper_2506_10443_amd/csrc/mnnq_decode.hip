@@ -68,33 +68,6 @@ __device__ __forceinline__ int dot16(uint32_t wa, uint32_t wb, const int4& x)
     return d;
 }
 
-// Quantization must give exactly rint(fl(x / scale)) as mnnq_quant_act does, but
-// a correctly rounded division per element is what makes the repeated row
-// quantization expensive.  r = x * fl(1 / scale) differs from fl(x / scale) by
-// less than 3 * 2^-24 * 127.5 < 2.3e-5, so both round to the same integer unless
-// r is within that distance of a half-integer, i.e. unless |r - rint(r)| (exact:
-// the two are within 0.5 of each other) exceeds 0.5 - 6e-5; only then (about one
-// element in ten thousand) the division is done, for the four elements of a dword
-// together.  |r| <= 127 (1 + 2^-22) in this path, so rint(r) needs no clamp.
-// (lim is 0.5 - 6e-5 normally; negative - "always divide" - when 1 / scale is not
-// a normal number; the division path clamps like mnnq_quant_act does.)
-__device__ __forceinline__ int quant4_fast(float4 v, float scale, float inv, float lim)
-{
-    float t0 = rintf(v.x * inv), t1 = rintf(v.y * inv), t2 = rintf(v.z * inv), t3 = rintf(v.w * inv);
-    const float d0 = fabsf(v.x * inv - t0), d1 = fabsf(v.y * inv - t1);
-    const float d2 = fabsf(v.z * inv - t2), d3 = fabsf(v.w * inv - t3);
-    if (!(fmaxf(fmaxf(d0, d1), fmaxf(d2, d3)) <= lim)) {
-        t0 = fminf(fmaxf(rintf(v.x / scale), -127.0f), 127.0f);
-        t1 = fminf(fmaxf(rintf(v.y / scale), -127.0f), 127.0f);
-        t2 = fminf(fmaxf(rintf(v.z / scale), -127.0f), 127.0f);
-        t3 = fminf(fmaxf(rintf(v.w / scale), -127.0f), 127.0f);
-    }
-    // low bytes of the four integers into one dword
-    const uint32_t lo = __builtin_amdgcn_perm((uint32_t)(int)t1, (uint32_t)(int)t0, 0x0c0c0400u);
-    const uint32_t hi = __builtin_amdgcn_perm((uint32_t)(int)t3, (uint32_t)(int)t2, 0x04000c0cu);
-    return (int)(lo | hi);
-}
-
 // Fused activation quantizer: per-token symmetric int8 (Section 4.2) of the fp32 row x into the
 // workgroup's LDS image - the row as dwords of four codes over the padded packed reduction axis
 // (which runs over the row twice for int8 weights) and the sums of its 16-byte blocks as
@@ -153,7 +126,7 @@ struct RowQuantizer {
     __device__ __forceinline__ explicit RowQuantizer(float s, int64_t valid_, int* xd, int* xs)
         : scale(s), inv(s == 0.0f ? 0.0f : 1.0f / s), valid(valid_), lds_xd(xd), lds_xs(xs)
     {
-        lim = (inv < 1.0e37f && scale > 1.0e-30f) ? 0.5f - 6.0e-5f : -1.0f;   // largest |r - rint(r)| of the fast path
+        lim = quant_fast_limit(scale, inv);
     }
     __device__ __forceinline__ void put(int64_t i, const float4 xv) const
     {

@@ -129,6 +129,33 @@ def test_quant_act_bit_exact(M, K, outliers):
     assert none is None and torch.equal(xq2, xq) and torch.equal(sx2, sx)
 
 
+@pytest.mark.parametrize("M", [1, 24])
+def test_quant_act_is_exact_at_rounding_boundaries(M):
+    # The kernels round x * fl(1/scale) and do the division of the definition only next to a
+    # half-integer.  Rows of values on and within a few ulps of every tie, for scales of many
+    # magnitudes (also where 1/scale is not a normal number): the codes must be the oracle's.
+    K = 1536
+    rng = np.random.default_rng(11)
+    rows = []
+    for amax in (127.0, 3.3, 1e-3, 517.25, 1e-30, 3e-38, 1e-40, 2.5e38, 0.9999999, 64.0):
+        scale = np.float32(amax) / np.float32(127.0)
+        for ulps in (0, 1, -1, 2, -2, 7, -7):
+            n = rng.integers(-126, 126, K).astype(np.float32)
+            xv = ((n + np.float32(0.5)) * scale).astype(np.float32)
+            if ulps:
+                xv = (xv.view(np.int32) + np.where(xv >= 0, ulps, -ulps)).astype(np.int32).view(np.float32)
+            xv[0] = amax
+            rows.append(xv)
+    x = np.stack(rows)
+    for lo in range(0, len(rows), M):
+        xb = x[lo:lo + M]
+        xq_o, sx_o, xs_o = oracle.quant_act(xb)
+        xq, sx, xs = B.mnnq_quant_act(dev(xb))
+        assert np.array_equal(host(sx).view(np.uint32), sx_o.view(np.uint32))
+        assert np.array_equal(host(xq), xq_o), lo
+        assert np.array_equal(host(xs), xs_o)
+
+
 def _layer(N, K, M, seed, outliers=True):
     W = synth.weights(N, K, seed)
     x = synth.activations(M, K, seed + 1, outliers=outliers)
