@@ -70,6 +70,17 @@ def test_w4a8_out16(M, N, K):
     y16 = B.mnnq_linear_decode_o16(packed, N, K, xqd[0].contiguous(), sxd[:1].contiguous(), bias=bd)
     assert torch.equal(y16, y32.to(torch.float16))
     close_to_oracle(host(y16), y_o[0], TOL_A8)
+    if M <= 16 and K <= 4096:
+        # both few-token kernels (the persistent one is normally reserved for large layers)
+        for staged in ("0", "1"):
+            os.environ["MNNQ_SKINNY_STAGED"] = staged
+            try:
+                y32 = B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd)
+                y16 = B.mnnq_linear_prefill_o16(packed, N, K, xqd, sxd, bias=bd)
+            finally:
+                os.environ.pop("MNNQ_SKINNY_STAGED", None)
+            assert torch.equal(y16, y32.to(torch.float16)), staged
+            close_to_oracle(host(y16), y_o, TOL_A8)
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 16, 64), (9, 48, 192), (130, 272, 1536), (300, 272, 448)])
