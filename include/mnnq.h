@@ -185,6 +185,13 @@ int mnnq_linear_decode_f16_o16(const void *packed, int64_t N, int64_t K, int gro
 int mnnq_linear_prefill_f16_o16(const void *packed, int64_t M, int64_t N, int64_t K, int group, int mode,
                                 const uint16_t *x16, const float *row_scale, const float *bias, uint16_t *y16,
                                 void *stream);
+/* The two fused calls keep their workspace arguments (optional for decode, required for prefill). */
+int mnnq_linear_decode_fused_o16(const void *packed, int64_t N, int64_t K, int group, int mode,
+                                 const float *x, const float *bias, uint16_t *y16,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+int mnnq_linear_prefill_fused_o16(const void *packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                                  const float *x, const float *bias, uint16_t *y16,
+                                  void *workspace, size_t workspace_bytes, void *stream);
 
 /* Import of weights that were quantized elsewhere (Section 4.2: quantized
  * weights, e.g. from GPTQ, can be imported): canonical arrays in, packed form

@@ -27,7 +27,7 @@ EXPORTS = (
     "mnnq_linear_prefill", "mnnq_linear_decode_f16", "mnnq_linear_prefill_f16", "mnnq_linear_acc_debug",
     "mnnq_pack_from_quantized",
     "mnnq_linear_decode_o16", "mnnq_linear_prefill_o16", "mnnq_linear_decode_f16_o16", "mnnq_linear_prefill_f16_o16",
-    "mnnq_linear_prefill_fused", "mnnq_peak_read", "mnnq_peak_mfma", "mnnq_peak_mfma_count",
+    "mnnq_linear_prefill_fused", "mnnq_linear_decode_fused_o16", "mnnq_linear_prefill_fused_o16", "mnnq_peak_read", "mnnq_peak_mfma", "mnnq_peak_mfma_count",
 )
 
 
@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.mnnq_linear_acc_debug.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, i32, vp]
         L.mnnq_pack_from_quantized.argtypes = [vp, vp, vp, i64, i64, i32, i32, vp, sz, vp]
         L.mnnq_linear_prefill_fused.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.mnnq_linear_decode_fused_o16.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.mnnq_linear_prefill_fused_o16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
         L.mnnq_peak_read.argtypes = [vp, sz, vp, vp]
         L.mnnq_peak_mfma.argtypes = [i32, i32, i32, i32, vp, vp]
         L.mnnq_peak_mfma_count.argtypes = []
@@ -317,6 +319,41 @@ def mnnq_linear_prefill_fused(packed, N: int, K: int, x, bias=None, out=None, wo
     _check(lib().mnnq_linear_prefill_fused(_ptr(packed), M, N, K, GROUP, mode, _ptr(x), _ptr(bias), _ptr(y),
                                            _ptr(workspace), workspace.numel(), _stream()),
            "mnnq_linear_prefill_fused")
+    return y
+
+
+def mnnq_linear_decode_fused_o16(packed, N: int, K: int, x, bias=None, out=None, workspace=None,
+                                 mode: int = MODE_W4_ZP_INT):
+    """One token, activation quantizer fused in: x f32 [K] -> y fp16 [N]."""
+    _dev(packed, torch.uint8, "packed"); _dev(x, torch.float32, "x")
+    if x.numel() != K:
+        raise ValueError("x must hold K values")
+    y = torch.empty((N,), dtype=torch.float16, device=packed.device) if out is None else out
+    _dev(y, torch.float16, "out")
+    if workspace is not None:
+        _dev(workspace, torch.uint8, "workspace")
+    _check(lib().mnnq_linear_decode_fused_o16(_ptr(packed), N, K, GROUP, mode, _ptr(x), _ptr(bias), _ptr(y),
+                                              _ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                              _stream()), "mnnq_linear_decode_fused_o16")
+    return y
+
+
+def mnnq_linear_prefill_fused_o16(packed, N: int, K: int, x, bias=None, out=None, workspace=None,
+                                  mode: int = MODE_W4_ZP_INT):
+    """M tokens, activation quantizer inside the call: x f32 [M,K] -> y fp16 [M,N]."""
+    _dev(packed, torch.uint8, "packed"); _dev(x, torch.float32, "x")
+    M = x.shape[0]
+    if x.shape[1] != K:
+        raise ValueError("x must be [M,K]")
+    if workspace is None:
+        workspace = torch.empty(max(16, mnnq_workspace_size(M, N, K, GROUP, mode)), dtype=torch.uint8,
+                                device=packed.device)
+    _dev(workspace, torch.uint8, "workspace")
+    y = torch.empty((M, N), dtype=torch.float16, device=packed.device) if out is None else out
+    _dev(y, torch.float16, "out")
+    _check(lib().mnnq_linear_prefill_fused_o16(_ptr(packed), M, N, K, GROUP, mode, _ptr(x), _ptr(bias), _ptr(y),
+                                               _ptr(workspace), workspace.numel(), _stream()),
+           "mnnq_linear_prefill_fused_o16")
     return y
 
 

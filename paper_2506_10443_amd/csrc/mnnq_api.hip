@@ -125,6 +125,44 @@ int prefill_f16_impl(const void* packed, int64_t M, int64_t N, int64_t K, int gr
                               bias, static_cast<float*>(y), static_cast<hipStream_t>(stream));
 }
 
+// The fused calls: activation quantizer and linear layer in one call.
+int decode_fused_impl(const void* packed, int64_t N, int64_t K, int group, int mode, const float* x,
+                      const float* bias, void* y, bool out16, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!packed || !x || !y) return MNNQ_ERR_NULL;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    if (make_layout(N, K, mode).K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
+    if (misaligned(packed) || misaligned(x) || misaligned(y) || misaligned(bias) || misaligned(workspace))
+        return MNNQ_ERR_ALIGN;
+    const Layout L = layout_for(N, K, mode, out16);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    size_t two_kernel_bytes = kFusedTwoKernelBytes;
+    if (const char* e = getenv("MNNQ_FUSED_TWO_KERNEL_MIB")) two_kernel_bytes = (size_t)atoll(e) << 20;   // tuning only
+    if (workspace && workspace_bytes >= fused_ws_bytes(K) && L.total() > two_kernel_bytes) {
+        int8_t* xq = static_cast<int8_t*>(workspace);
+        float* sx = reinterpret_cast<float*>(xq + (K + 127) / 128 * 128);
+        if (int s = launch_quant_act(x, 1, K, xq, sx, nullptr, st)) return s;
+        return launch_decode(static_cast<const uint8_t*>(packed), L, xq, sx, bias, static_cast<float*>(y), st);
+    }
+    return launch_decode_fused(static_cast<const uint8_t*>(packed), L, x, bias, static_cast<float*>(y), st);
+}
+
+int prefill_fused_impl(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode, const float* x,
+                       const float* bias, void* y, bool out16, void* workspace, size_t workspace_bytes,
+                       void* stream)
+{
+    if (!packed || !x || !y || !workspace) return MNNQ_ERR_NULL;
+    if (M <= 0) return MNNQ_ERR_SHAPE;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    if (!prefill_fits(M, N, K, mode)) return MNNQ_ERR_UNSUPPORTED;
+    if (workspace_bytes < fused_prefill_ws_bytes(M, K)) return MNNQ_ERR_SIZE;
+    if (misaligned(x) || misaligned(workspace)) return MNNQ_ERR_ALIGN;
+    int8_t* xq = static_cast<int8_t*>(workspace);
+    float* sx = reinterpret_cast<float*>(xq + fused_prefill_codes_bytes(M, K));
+    if (int s = launch_quant_act(x, M, K, xq, sx, nullptr, static_cast<hipStream_t>(stream))) return s;
+    return prefill_impl(packed, M, N, K, group, mode, xq, sx, bias, y, out16, nullptr, stream);
+}
+
 }  // namespace
 }  // namespace mnnq
 
@@ -225,22 +263,14 @@ int mnnq_linear_decode(const void* packed, int64_t N, int64_t K, int group, int 
 int mnnq_linear_decode_fused(const void* packed, int64_t N, int64_t K, int group, int mode, const float* x,
                              const float* bias, float* y, void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (!packed || !x || !y) return MNNQ_ERR_NULL;
-    if (int s = check_shape(N, K, group, mode)) return s;
-    if (make_layout(N, K, mode).K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
-    if (misaligned(packed) || misaligned(x) || misaligned(y) || misaligned(bias) || misaligned(workspace))
-        return MNNQ_ERR_ALIGN;
-    const Layout L = make_layout(N, K, mode);
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    size_t two_kernel_bytes = kFusedTwoKernelBytes;
-    if (const char* e = getenv("MNNQ_FUSED_TWO_KERNEL_MIB")) two_kernel_bytes = (size_t)atoll(e) << 20;   // tuning only
-    if (workspace && workspace_bytes >= fused_ws_bytes(K) && L.total() > two_kernel_bytes) {
-        int8_t* xq = static_cast<int8_t*>(workspace);
-        float* sx = reinterpret_cast<float*>(xq + (K + 127) / 128 * 128);
-        if (int s = launch_quant_act(x, 1, K, xq, sx, nullptr, st)) return s;
-        return launch_decode(static_cast<const uint8_t*>(packed), L, xq, sx, bias, y, st);
-    }
-    return launch_decode_fused(static_cast<const uint8_t*>(packed), L, x, bias, y, st);
+    return decode_fused_impl(packed, N, K, group, mode, x, bias, y, false, workspace, workspace_bytes, stream);
+}
+
+int mnnq_linear_decode_fused_o16(const void* packed, int64_t N, int64_t K, int group, int mode, const float* x,
+                                 const float* bias, uint16_t* y16, void* workspace, size_t workspace_bytes,
+                                 void* stream)
+{
+    return decode_fused_impl(packed, N, K, group, mode, x, bias, y16, true, workspace, workspace_bytes, stream);
 }
 
 int mnnq_linear_prefill(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
@@ -255,16 +285,14 @@ int mnnq_linear_prefill_fused(const void* packed, int64_t M, int64_t N, int64_t 
                               const float* x, const float* bias, float* y, void* workspace, size_t workspace_bytes,
                               void* stream)
 {
-    if (!packed || !x || !y || !workspace) return MNNQ_ERR_NULL;
-    if (M <= 0) return MNNQ_ERR_SHAPE;
-    if (int s = check_shape(N, K, group, mode)) return s;
-    if (!prefill_fits(M, N, K, mode)) return MNNQ_ERR_UNSUPPORTED;
-    if (workspace_bytes < fused_prefill_ws_bytes(M, K)) return MNNQ_ERR_SIZE;
-    if (misaligned(x) || misaligned(workspace)) return MNNQ_ERR_ALIGN;
-    int8_t* xq = static_cast<int8_t*>(workspace);
-    float* sx = reinterpret_cast<float*>(xq + fused_prefill_codes_bytes(M, K));
-    if (int s = launch_quant_act(x, M, K, xq, sx, nullptr, static_cast<hipStream_t>(stream))) return s;
-    return prefill_impl(packed, M, N, K, group, mode, xq, sx, bias, y, false, nullptr, stream);
+    return prefill_fused_impl(packed, M, N, K, group, mode, x, bias, y, false, workspace, workspace_bytes, stream);
+}
+
+int mnnq_linear_prefill_fused_o16(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                                  const float* x, const float* bias, uint16_t* y16, void* workspace,
+                                  size_t workspace_bytes, void* stream)
+{
+    return prefill_fused_impl(packed, M, N, K, group, mode, x, bias, y16, true, workspace, workspace_bytes, stream);
 }
 
 int mnnq_linear_decode_f16(const void* packed, int64_t N, int64_t K, int group, int mode, const uint16_t* x16,

@@ -74,13 +74,16 @@ __device__ __forceinline__ v4i unpack_b(uint32_t w0, uint32_t w1, uint32_t c4)
 // LDS map of a workgroup: the A tile is double buffered, the B tile (codes, scales,
 // zeros of one chunk) is single buffered - it is copied into registers before
 // the next chunk is loaded over it.
-template <int BM, int BN, bool MINF>
+// W8: the packed matrix holds 8-bit codes as two nibble planes; the low plane's chunk gets a B
+// tile of its own behind the high plane's.
+template <int BM, int BN, bool MINF, bool W8 = false>
 struct Lds {
     static constexpr int NT16 = BN / 16;                 // row tiles of B per workgroup
     static constexpr int A_BYTES = BM * 128;             // [BM][128] int8, swizzled
     static constexpr int A_OFF = 0;                      // two A buffers
     static constexpr int B_OFF = 2 * A_BYTES;            // [NT16][1024] packed codes
-    static constexpr int S_OFF = B_OFF + NT16 * 1024;    // [NT16][16][2] fp32 scales
+    static constexpr int B2_OFF = B_OFF + NT16 * 1024;   // W8: [NT16][1024] codes of the low nibble plane
+    static constexpr int S_OFF = B2_OFF + (W8 ? NT16 * 1024 : 0);   // [NT16][16][2] fp32 scales
     static constexpr int Z_OFF = S_OFF + NT16 * 128;     // [NT16][16][2] u8 zeros, or fp32 group minima (MINF)
     static constexpr int BYTES = Z_OFF + NT16 * (MINF ? 128 : 32);
 };
@@ -90,14 +93,21 @@ struct Lds {
 // CUs with whole tiles, so their K range is cut in two; both halves add their part
 // to a zeroed y with fp32 atomics.  Two addends commute, so the result does not
 // depend on which half arrives first.
-template <int BM, int BN, int KS, bool ACC, bool MINF>
+//
+// W8 (8-bit weights, float minimum form): a code q8 = 16 hi + lo lies in two nibble planes, chunk c
+// of the high plane and chunk c + Cx of the low one.  Both are fetched, merged in registers into
+// the signed byte q8 - 128 and contracted with one MFMA per group; with D = sum xq (q8 - 128) and
+// xs = sum xq the group's term  s (D + 128 xs) + min xs  is  s D + (min + 128 s) xs, so only the
+// minimum that enters the epilogue changes.  The stored scale of the high plane is 16 s.
+template <int BM, int BN, int KS, bool ACC, bool MINF, bool W8 = false>
 __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_kernel(const uint8_t* __restrict__ packed, Layout L, int64_t M,
                                                          const int8_t* __restrict__ xq,
                                                          const float* __restrict__ sx,
                                                          const float* __restrict__ bias, float* __restrict__ y,
                                                          int32_t* __restrict__ acc_out, int MT, int NT, int S)
 {
-    using St = Lds<BM, BN, MINF>;
+    using St = Lds<BM, BN, MINF, W8>;
+    static_assert(!W8 || (MINF && !ACC), "8-bit weights come in the float minimum form; the accumulator dump stays per plane");
     constexpr int WM = BM / 2, WN = BN / 2;      // 2 x 2 waves
     constexpr int TM = WM / 16, TN = WN / 16;
     constexpr int NT16 = St::NT16;
@@ -117,9 +127,10 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
     const int wm = wave >> 1, wn = wave & 1;
     const int col = lane & 15;
     const int kb = lane >> 4;
-    const int C = (int)L.C;
+    const int C = (int)L.C;     // chunks per row tile in the packed matrix
     const int K = (int)L.Kx;    // activation row length
     const int Cx = (int)L.Cx;   // chunk c of the packed axis meets chunk c % Cx of the activation row
+    const int CL = W8 ? Cx : C; // chunks this kernel walks over (merged planes: those of the activation row)
 
     // Workgroups are dealt to the 8 XCDs round-robin by their linear id.  Give each
     // XCD whole columns of output tiles (one weight row block, all token blocks and
@@ -130,7 +141,7 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
     const int tile_m = (seq / S) % MT;
     const int tile_n = (seq / (S * MT)) * 8 + xcd;
     if (tile_n >= NT) return;
-    const int wcb = C * split / S, wce = C * (split + 1) / S;   // this workgroup's chunks
+    const int wcb = CL * split / S, wce = CL * (split + 1) / S;   // this workgroup's chunks
     // ... of which each K part of the workgroup takes a contiguous share
     const int cb = wcb + (wce - wcb) * kh / KS, ce = wcb + (wce - wcb) * (kh + 1) / KS;
     const int n_iter = (wce - wcb + KS - 1) / KS;                // the longest share: all waves run the same barriers
@@ -179,6 +190,9 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
                 const int j = wave * 2 + i;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::B_OFF + j * 1024), 16, b_voff,
                                                          ((rt0 + j) * C + c) * 1024, 0, 0);
+                if (W8)   // the low nibble plane of the same weights
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::B2_OFF + j * 1024), 16, b_voff,
+                                                             ((rt0 + j) * C + c + Cx) * 1024, 0, 0);
             }
             // Scales: one load covers two row tiles (2 x 128 B); zeros: one load covers all eight (8 x 32 B).
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::S_OFF + wave * 256), 4, s_voff,
@@ -200,6 +214,7 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
                 for (int r = 0; r < 4; ++r) yacc[i][j][r] = 0.0f;
 
         v4i bw[TN];
+        v4i bw2[W8 ? TN : 1];   // low nibble plane (W8)
         v2i bsv[TN];
         uint32_t bz[TN];      // zero points of both groups (integer zero point form)
         v2i bmn[TN];          // group minima of both groups, fp32 bits (float minimum form)
@@ -207,6 +222,7 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 bw[j] = *reinterpret_cast<const v4i*>(lds + b_frag_off + j * 1024);
+                if (W8) bw2[j] = *reinterpret_cast<const v4i*>(lds + b_frag_off + (St::B2_OFF - St::B_OFF) + j * 1024);
                 bsv[j] = *reinterpret_cast<const v2i*>(lds + s_frag_off + j * 128);
                 if (MINF) bmn[j] = *reinterpret_cast<const v2i*>(lds + z_frag_off + j * 128);
                 else bz[j] = *reinterpret_cast<const uint16_t*>(lds + z_frag_off + j * 32);
@@ -236,7 +252,15 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const uint32_t w0 = (uint32_t)(h ? bw[j].z : bw[j].x), w1 = (uint32_t)(h ? bw[j].w : bw[j].y);
-                    if (MINF) {
+                    if (W8) {
+                        // q8 - 128 per byte: high plane nibble above low plane nibble, top bit flipped
+                        const uint32_t l0 = (uint32_t)(h ? bw2[j].z : bw2[j].x), l1 = (uint32_t)(h ? bw2[j].w : bw2[j].y);
+                        b[j].x = (int)((((w0 << 4) & 0xf0f0f0f0u) | (l0 & 0x0f0f0f0fu)) ^ 0x80808080u);
+                        b[j].y = (int)(((w0 & 0xf0f0f0f0u) | ((l0 >> 4) & 0x0f0f0f0fu)) ^ 0x80808080u);
+                        b[j].z = (int)((((w1 << 4) & 0xf0f0f0f0u) | (l1 & 0x0f0f0f0fu)) ^ 0x80808080u);
+                        b[j].w = (int)(((w1 & 0xf0f0f0f0u) | ((l1 >> 4) & 0x0f0f0f0fu)) ^ 0x80808080u);
+                        mnv[j] = __int_as_float(h ? bmn[j].y : bmn[j].x);
+                    } else if (MINF) {
                         // the codes themselves (0..15) are the B operand; the minimum enters in the epilogue
                         b[j].x = (int)(w0 & 0x0f0f0f0fu);
                         b[j].y = (int)((w0 >> 4) & 0x0f0f0f0fu);
@@ -250,6 +274,10 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
                         mnv[j] = 0.0f;
                     }
                     sc[j] = __int_as_float(h ? bsv[j].y : bsv[j].x);
+                    if (W8) {
+                        sc[j] *= 0.0625f;                         // the high plane stores 16 s (exact)
+                        mnv[j] = fmaf(sc[j], 128.0f, mnv[j]);     // min + 128 s
+                    }
                 }
                 const int g = 2 * c + h;
                 const uint8_t* ap = st + a_row_off + (((h * 4 + kb) ^ a_sw) << 4);
@@ -456,14 +484,14 @@ __global__ void zero_f4_kernel(float4* p, int64_t n4)
     if (i < n4) p[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 }
 
-template <int BM, int BN, int KS, bool ACC, bool MINF>
+template <int BM, int BN, int KS, bool ACC, bool MINF, bool W8 = false>
 int launch_tiles_m(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
                  const float* bias, float* y, int32_t* acc, int S, hipStream_t st)
 {
     const int MT = (int)((M + BM - 1) / BM);
     const int NT = (int)((L.N + BN - 1) / BN);
-    constexpr size_t smem = (size_t)KS * Lds<BM, BN, MINF>::BYTES;
-    auto kern = prefill_kernel<BM, BN, KS, ACC, MINF>;
+    constexpr size_t smem = (size_t)KS * Lds<BM, BN, MINF, W8>::BYTES;
+    auto kern = prefill_kernel<BM, BN, KS, ACC, MINF, W8>;
     if (smem > 64 * 1024) {
         // More than 64 KiB of dynamic LDS has to be allowed once per kernel and device.
         static thread_local int allowed_dev = -1;
@@ -568,6 +596,20 @@ int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8
     }
     TilePlan p = plan_tiles(L, M);
     if (L.out16) p.S = 1;   // the split over two workgroups adds fp32 partial sums in the output array
+    // 8-bit weights: both nibble planes of a chunk in one MFMA (128-row tiles: two B tiles need the LDS
+    // of the larger A tile).  MNNQ_W8_PLANES=1 (tests, comparisons) keeps one MFMA per plane instead.
+    const char* planes = getenv("MNNQ_W8_PLANES");
+    const bool forced_plan = getenv("MNNQ_PREFILL_TILE") != nullptr;
+    if (L.mode == MNNQ_W8_MIN_FLOAT && !(planes && planes[0] == '1')) {
+        if (!forced_plan) {   // the plan above counted 256-row tiles too
+            p.big = false;
+            p.KS = ((M + 127) / 128) * ((L.N + 127) / 128) <= num_cus() ? 2 : 1;
+        }
+        if (p.S > 1 && L.Cx < 64) p.S = 1;
+        if (p.KS == 2)
+            return launch_tiles_m<128, 128, 2, false, true, true>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
+        return launch_tiles_m<128, 128, 1, false, true, true>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
+    }
     if (p.big && p.KS == 2) return launch_tiles<256, 128, 2, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
     if (p.big) return launch_tiles<256, 128, 1, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
     if (p.KS == 2) return launch_tiles<128, 128, 2, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);

@@ -144,6 +144,10 @@ def test_argument_validation_precedes_hip(L):
     assert L.mnnq_linear_prefill_o16(FAKE, 4, 16, 128, 64, 0, FAKE, FAKE, None, ODD, None) == ALIGN
     assert L.mnnq_linear_decode_f16_o16(FAKE, 16, 128, 64, 3, FAKE, None, FAKE, None) == UNSUP
     assert L.mnnq_linear_prefill_f16_o16(FAKE, 4, 16, 128, 64, 0, None, None, None, FAKE, None) == NULL
+    assert L.mnnq_linear_decode_fused_o16(FAKE, 16, 128, 64, 0, FAKE, None, None, None, 0, None) == NULL
+    assert L.mnnq_linear_decode_fused_o16(FAKE, 16, 128, 64, 0, FAKE, None, ODD, None, 0, None) == ALIGN
+    assert L.mnnq_linear_prefill_fused_o16(FAKE, 4, 16, 128, 64, 0, FAKE, None, FAKE, None, 0, None) == NULL
+    assert L.mnnq_linear_prefill_fused_o16(FAKE, 4, 16, 128, 64, 0, FAKE, None, FAKE, FAKE, 16, None) == SIZE
     assert L.mnnq_linear_acc_debug(FAKE, 1, 16, 128, 64, 0, FAKE, None, 0, None) == NULL
     assert L.mnnq_linear_acc_debug(FAKE, 70000, 16, 128, 64, 0, FAKE, FAKE, 0, None) == UNSUP
     pq = L.mnnq_pack_from_quantized

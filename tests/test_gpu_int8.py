@@ -53,7 +53,7 @@ def test_pack_unpack_import_bit_exact(N, K):
 
 
 SHAPES = [(1, 16, 128), (7, 48, 384), (16, 144, 9472), (33, 272, 640), (130, 144, 1536), (300, 400, 1024),
-          (64, 1024, 4096)]
+          (64, 1024, 4096), (129, 144, 8192), (513, 1040, 896)]
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
@@ -74,15 +74,20 @@ def test_linear_matches_oracle(M, N, K):
         assert np.array_equal(16 * planes[:, :, :G] + planes[:, :, G:], acc_o)
     y = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd, mode=W8))
     assert np.abs(y - y_o).max() <= tol, (np.abs(y - y_o).max(), tol)
+    # every tile plan, with both nibble planes merged into one matrix instruction per group (the
+    # default) and with one per plane; "2" splits K over two workgroups (long rows only)
     os.environ["MNNQ_NO_SKINNY"] = "1"
     try:
-        for cfg in ("b1", "s1", "b1k", "s1k"):
-            os.environ["MNNQ_PREFILL_TILE"] = cfg
-            try:
-                y2 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd, mode=W8))
-            finally:
-                os.environ.pop("MNNQ_PREFILL_TILE", None)
-            assert np.abs(y2 - y_o).max() <= tol, cfg
+        for planes in ("0", "1"):
+            for cfg in ("b1", "s1", "b1k", "s1k", "s2", "s2k"):
+                os.environ["MNNQ_PREFILL_TILE"] = cfg
+                os.environ["MNNQ_W8_PLANES"] = planes
+                try:
+                    y2 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd, mode=W8))
+                finally:
+                    os.environ.pop("MNNQ_PREFILL_TILE", None)
+                    os.environ.pop("MNNQ_W8_PLANES", None)
+                assert np.abs(y2 - y_o).max() <= tol, (planes, cfg)
     finally:
         os.environ.pop("MNNQ_NO_SKINNY", None)
     if M <= 16:

@@ -132,3 +132,33 @@ def test_values_beyond_half_range_become_infinite():
     y32 = host(B.mnnq_linear_decode(packed, N, K, xq[0], sx))
     y16 = host(B.mnnq_linear_decode_o16(packed, N, K, xq[0], sx))
     assert (y32 > 65504 * 1.01).all() and np.isinf(y16).all()
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 48, 192), (1, 272, 1536), (7, 144, 640), (130, 144, 1536), (300, 400, 1024)])
+def test_fused_calls_out16(M, N, K):
+    """fp32 activations in, binary16 out: the fused calls with the suffix give the fp32 fused call's
+    result converted to half, with and without a workspace for the single-token call."""
+    note("out16 fused", M, N, K)
+    W = synth.weights(N, K, 340 + M + N + K)
+    x = synth.activations(M, K, 341 + M + N + K, outliers=True)
+    q, s, z = oracle.quant_weights(W)
+    xq, sx, _ = oracle.quant_act(x)
+    bias = synth.weights(1, N, 6)[0] * 10
+    y_o = oracle.linear_w4a8(xq, sx, q, s, z, bias=bias, want_acc=False)[1]
+    packed = B.mnnq_pack_weights(dev(W))
+    xd, bd = dev(x), dev(bias)
+    y32 = B.mnnq_linear_prefill_fused(packed, N, K, xd, bias=bd)
+    y16 = B.mnnq_linear_prefill_fused_o16(packed, N, K, xd, bias=bd)
+    assert y16.dtype == torch.float16 and torch.equal(y16, y32.to(torch.float16))
+    close_to_oracle(host(y16), y_o, TOL_A8)
+    ws = torch.empty(B.mnnq_workspace_size(1, N, K), dtype=torch.uint8, device="cuda:0")
+    for workspace, two_kernel in ((None, None), (ws, "0")):
+        if two_kernel is not None:
+            os.environ["MNNQ_FUSED_TWO_KERNEL_MIB"] = two_kernel   # quantizer as a kernel of its own
+        try:
+            r32 = B.mnnq_linear_decode_fused(packed, N, K, xd[0].contiguous(), bias=bd, workspace=workspace)
+            r16 = B.mnnq_linear_decode_fused_o16(packed, N, K, xd[0].contiguous(), bias=bd, workspace=workspace)
+        finally:
+            os.environ.pop("MNNQ_FUSED_TWO_KERNEL_MIB", None)
+        assert r16.dtype == torch.float16 and torch.equal(r16, r32.to(torch.float16))
+        close_to_oracle(host(r16), y_o[0], TOL_A8)
