@@ -51,6 +51,10 @@ __device__ __forceinline__ uint32_t h2_bits(h2v h)
 
 #define MNNQ_LDS(p) ((__attribute__((address_space(3))) void*)(p))
 
+// A value that is the same in every lane, said so to the compiler: as the scalar offset of a
+// buffer load it then needs no loop over the distinct values of a vector register.
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
 constexpr int kBufFlags = 0x00020000;  // raw buffer, 32-bit data format (gfx9 family)
 
 // q - z per byte for four codes (0..15) in the bytes of v.  c4 holds 0x80 - z in
@@ -99,8 +103,12 @@ struct Lds {
 // the signed byte q8 - 128 and contracted with one MFMA per group; with D = sum xq (q8 - 128) and
 // xs = sum xq the group's term  s (D + 128 xs) + min xs  is  s D + (min + 128 s) xs, so only the
 // minimum that enters the epilogue changes.  The stored scale of the high plane is 16 s.
-template <int BM, int BN, int KS, bool ACC, bool MINF, bool W8 = false>
-__global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_kernel(const uint8_t* __restrict__ packed, Layout L, int64_t M,
+//
+// WNW: waves along N per K part (2 x WNW waves work on a tile).  With WNW = 4 a wave owns 128 x 32
+// outputs of a 256 x 128 tile: half the accumulators, so that four waves fit on a SIMD (two
+// workgroups of eight waves per CU) while a B unpack is still shared by eight MFMAs.
+template <int BM, int BN, int KS, bool ACC, bool MINF, bool W8 = false, int WNW = 2>
+__global__ __launch_bounds__(128 * WNW * KS, (ACC || KS > 1) ? 1 : 2) void prefill_kernel(const uint8_t* __restrict__ packed, Layout L, int64_t M,
                                                          const int8_t* __restrict__ xq,
                                                          const float* __restrict__ sx,
                                                          const float* __restrict__ bias, float* __restrict__ y,
@@ -108,12 +116,15 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
 {
     using St = Lds<BM, BN, MINF, W8>;
     static_assert(!W8 || (MINF && !ACC), "8-bit weights come in the float minimum form; the accumulator dump stays per plane");
-    constexpr int WM = BM / 2, WN = BN / 2;      // 2 x 2 waves
+    constexpr int WPK = 2 * WNW;                 // waves per K part: 2 x WNW
+    constexpr int WM = BM / 2, WN = BN / WNW;
     constexpr int TM = WM / 16, TN = WN / 16;
     constexpr int NT16 = St::NT16;
-    constexpr int A_INSTR = BM / 8 / 4;          // 1 KiB direct loads of A per wave and stage
+    constexpr int A_INSTR = BM / 8 / WPK;        // 1 KiB direct loads of A per wave and stage
+    constexpr int B_INSTR = NT16 / WPK;          // row tiles of B codes per wave and stage
     static_assert(NT16 == 8, "B side is written for 8 row tiles per workgroup");
-    static_assert(KS == 1 || 4 * TM * TN * 4 * 64 * 4 <= KS * St::BYTES, "the K parts' sums must fit in LDS");
+    static_assert(WNW == 2 || WNW == 4, "four or eight waves per K part");
+    static_assert(KS == 1 || WPK * TM * TN * 4 * 64 * 4 <= KS * St::BYTES, "the K parts' sums must fit in LDS");
     static_assert(KS == 1 || !ACC, "the accumulator dump runs unsplit");
 
     extern __shared__ __align__(16) uint8_t lds_all[];   // KS * St::BYTES
@@ -121,10 +132,10 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wave = wave_id & 3;                // position in the 2 x 2 wave grid of its K part
-    const int kh = wave_id >> 2;                 // K part of this wave (0 .. KS-1)
+    const int wave = wave_id % WPK;              // position in the 2 x WNW wave grid of its K part
+    const int kh = wave_id / WPK;                // K part of this wave (0 .. KS-1)
     uint8_t* const lds = lds_all + kh * St::BYTES;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WNW, wn = wave % WNW;
     const int col = lane & 15;
     const int kb = lane >> 4;
     const int C = (int)L.C;     // chunks per row tile in the packed matrix
@@ -184,25 +195,28 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
                     rs_x, MNNQ_LDS(lds + St::A_OFF + buf * St::A_BYTES + q * 1024), 16, a_voff,
                     ((int)m0 + q * 8) * K + (c % Cx) * 128, 0, 0);
             }
-            // B codes: two row tiles per wave, one chunk block (1 KiB) each.
+            // B codes: B_INSTR row tiles per wave, one chunk block (1 KiB) each.
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int j = wave * 2 + i;
+            for (int i = 0; i < B_INSTR; ++i) {
+                const int j = wave * B_INSTR + i;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::B_OFF + j * 1024), 16, b_voff,
-                                                         ((rt0 + j) * C + c) * 1024, 0, 0);
+                                                         uniform(((rt0 + j) * C + c) * 1024), 0, 0);
                 if (W8)   // the low nibble plane of the same weights
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::B2_OFF + j * 1024), 16, b_voff,
-                                                             ((rt0 + j) * C + c + Cx) * 1024, 0, 0);
+                                                             uniform(((rt0 + j) * C + c + Cx) * 1024), 0, 0);
             }
-            // Scales: one load covers two row tiles (2 x 128 B); zeros: one load covers all eight (8 x 32 B).
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::S_OFF + wave * 256), 4, s_voff,
-                                                     scales_off + ((rt0 + wave * 2) * C + c) * 128, 0, 0);
-            if (MINF)   // group minima: fp32, laid out like the scales
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::Z_OFF + wave * 256), 4, s_voff,
-                                                         zeros_off + ((rt0 + wave * 2) * C + c) * 128, 0, 0);
-            else if (wave == 0)
+            // Scales: one load covers two row tiles (2 x 128 B), four loads in all; zeros: one load covers
+            // all eight row tiles (8 x 32 B).  (wave is uniform: these are scalar branches.)
+            if (WPK == 4 || wave < 4)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::S_OFF + wave * 256), 4, s_voff,
+                                                         uniform(scales_off + ((rt0 + wave * 2) * C + c) * 128), 0, 0);
+            if (MINF) {   // group minima: fp32, laid out like the scales
+                if (WPK == 4 || wave < 4)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::Z_OFF + wave * 256), 4, s_voff,
+                                                             uniform(zeros_off + ((rt0 + wave * 2) * C + c) * 128), 0, 0);
+            } else if (wave == 0)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::Z_OFF + opaque_zero), 4, z_voff,
-                                                         zeros_off + (rt0 * C + c) * 32, 0, 0);
+                                                         uniform(zeros_off + (rt0 * C + c) * 32), 0, 0);
         };
 
         float yacc[TM][TN][4];
@@ -414,18 +428,21 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
                 // whole row segments - a quarter of the store instructions and full cache lines.
                 // LDS operations of one wave complete in order, so the patch needs no barrier of its
                 // own; the barrier in front makes sure no wave still reads operands where it lies.
-                static_assert(TN == 4, "a lane stores one 16-byte unit of a 64-column row segment");
+                static_assert(TN == 4 || TN == 2, "a lane stores one 16-byte unit of a row segment of 64 or 32 columns");
                 constexpr int RS = 16 * TN + 4;                // floats per patch row
+                constexpr int LPR = 4 * TN;                    // lanes (16-byte units) per row segment
+                constexpr int RPP = 64 / LPR;                  // rows a wave stores per instruction
                 if (KS == 1) __syncthreads();
                 float* patch = reinterpret_cast<float*>(lds_all) + wave * (16 * RS);
                 float* wr = patch + (kb * 4) * RS + col;
-                const float* rd = patch + kb * RS + col * 4;  // + 4 p rows
-                // a lane's 16-byte unit lies in row tile nt0 + col / 4; units past N are sent out of range
-                const bool unit_ok = nt0 + (col >> 2) < (int)L.T;
-                const int y_voff = unit_ok ? kb * Nb + col * 16 : y_bytes;
+                const int lr = lane / LPR, lu = lane % LPR;    // this lane's row within a pass and unit within the row
+                const float* rd = patch + lr * RS + lu * 4;    // + RPP p rows
+                // a lane's 16-byte unit lies in row tile nt0 + lu / 4; units past N are sent out of range
+                const bool unit_ok = nt0 + (lu >> 2) < (int)L.T;
+                const int y_voff = unit_ok ? lr * Nb + lu * 16 : y_bytes;
                 // binary16 output: the same unit is four halves, rows are half as long
                 const __amdgpu_buffer_rsrc_t rs_y16 = __builtin_amdgcn_make_buffer_rsrc(y, 0, y_bytes / 2, kBufFlags);
-                const int y_voff16 = unit_ok ? kb * (Nb / 2) + col * 8 : y_bytes / 2;
+                const int y_voff16 = unit_ok ? lr * (Nb / 2) + lu * 8 : y_bytes / 2;
 #pragma unroll
                 for (int i = 0; i < TM; ++i) {
                     float sxr[4];
@@ -438,20 +455,20 @@ __global__ __launch_bounds__(256 * KS, (ACC || KS > 1) ? 1 : 2) void prefill_ker
 #pragma unroll
                         for (int j = 0; j < TN; ++j) wr[rr * RS + j * 16] = fmaf(yacc[i][j][rr], sxr[rr], bj[j]);
 #pragma unroll
-                    for (int p = 0; p < 4; ++p) {
+                    for (int p = 0; p < 16 / RPP; ++p) {
                         // (read as a struct of floats: the same scalar type as the writes for alias analysis)
-                        const float4 f = *reinterpret_cast<const float4*>(rd + p * 4 * RS);
+                        const float4 f = *reinterpret_cast<const float4*>(rd + p * RPP * RS);
                         if (L.out16) {
                             const h2v lo = {(_Float16)f.x, (_Float16)f.y}, hi = {(_Float16)f.z, (_Float16)f.w};
                             const v2i v = {(int)h2_bits(lo), (int)h2_bits(hi)};
                             __builtin_amdgcn_raw_buffer_store_b64(v, rs_y16, y_voff16,
-                                                                  (row0 + i * 16 + p * 4) * (Nb / 2) + nt0 * 32, 0);
+                                                                  (row0 + i * 16 + p * RPP) * (Nb / 2) + nt0 * 32, 0);
                             continue;
                         }
                         const v4i v = {(int)__float_as_uint(f.x), (int)__float_as_uint(f.y), (int)__float_as_uint(f.z),
                                        (int)__float_as_uint(f.w)};
                         __builtin_amdgcn_raw_buffer_store_b128(v, rs_y, y_voff,
-                                                               (row0 + i * 16 + p * 4) * Nb + nt0 * 64, 0);
+                                                               (row0 + i * 16 + p * RPP) * Nb + nt0 * 64, 0);
                     }
                 }
             } else {
@@ -484,14 +501,14 @@ __global__ void zero_f4_kernel(float4* p, int64_t n4)
     if (i < n4) p[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 }
 
-template <int BM, int BN, int KS, bool ACC, bool MINF, bool W8 = false>
+template <int BM, int BN, int KS, bool ACC, bool MINF, bool W8 = false, int WNW = 2>
 int launch_tiles_m(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
                  const float* bias, float* y, int32_t* acc, int S, hipStream_t st)
 {
     const int MT = (int)((M + BM - 1) / BM);
     const int NT = (int)((L.N + BN - 1) / BN);
     constexpr size_t smem = (size_t)KS * Lds<BM, BN, MINF, W8>::BYTES;
-    auto kern = prefill_kernel<BM, BN, KS, ACC, MINF, W8>;
+    auto kern = prefill_kernel<BM, BN, KS, ACC, MINF, W8, WNW>;
     if (smem > 64 * 1024) {
         // More than 64 KiB of dynamic LDS has to be allowed once per kernel and device.
         static thread_local int allowed_dev = -1;
@@ -510,7 +527,7 @@ int launch_tiles_m(const uint8_t* packed, const Layout& L, int64_t M, const int8
         MNNQ_HIP_TRY(hipGetLastError());
     }
     const int64_t blocks = (int64_t)MT * S * ((NT + 7) / 8) * 8;
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256 * KS), smem, st, packed, L, M, xq, sx, bias, y, acc, MT,
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(128 * WNW * KS), smem, st, packed, L, M, xq, sx, bias, y, acc, MT,
                        NT, S);
     MNNQ_HIP_TRY(hipGetLastError());
     return MNNQ_OK;
@@ -541,15 +558,17 @@ struct TilePlan {
     bool big;
     int KS;
     int S;
+    bool wide;   // 256-row tile worked on by eight waves (128 x 32 outputs each), two workgroups per CU
 };
 
 TilePlan plan_tiles(const Layout& L, int64_t M)
 {
-    TilePlan p{true, 1, 1};
+    TilePlan p{true, 1, 1, false};
     const int64_t cus = num_cus();
     auto tiles = [&](int bm) { return ((M + bm - 1) / bm) * ((L.N + 127) / 128); };
     if (M > 128 && tiles(256) >= 2 * cus) {
         p.big = true;
+        p.wide = !L.minf;   // the float minimum form needs more registers than four waves per SIMD leave
     } else if (tiles(128) <= cus) {
         p.big = false;
         p.KS = 2;
@@ -561,8 +580,9 @@ TilePlan plan_tiles(const Layout& L, int64_t M)
         p.big = false;
     }
     if (const char* e = getenv("MNNQ_PREFILL_TILE")) {   // tuning and tests: "b"/"s", split digit, "k" = K parts
-        if (e[0] == 'b') p.big = true;
+        if (e[0] == 'b' || e[0] == 'w') p.big = true;
         if (e[0] == 's') p.big = false;
+        p.wide = (e[0] == 'w');
         if (e[0] && (e[1] == '1' || e[1] == '2' || e[1] == '4')) {
             p.S = e[1] - '0';
             p.KS = (e[2] == 'k') ? 2 : 1;
@@ -609,6 +629,10 @@ int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8
         if (p.KS == 2)
             return launch_tiles_m<128, 128, 2, false, true, true>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
         return launch_tiles_m<128, 128, 1, false, true, true>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
+    }
+    if (p.big && p.wide && p.KS == 1) {
+        if (L.minf) return launch_tiles_m<256, 128, 1, false, true, false, 4>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
+        return launch_tiles_m<256, 128, 1, false, false, false, 4>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
     }
     if (p.big && p.KS == 2) return launch_tiles<256, 128, 2, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
     if (p.big) return launch_tiles<256, 128, 1, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
