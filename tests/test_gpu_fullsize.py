@@ -145,3 +145,41 @@ def test_llama3_8b_w4a16_and_w4a8_side_by_side(name):
     assert np.abs(y8[ms, ns] - y8_s).max() <= 1e-5 * np.abs(y8).max()
     # the two variants see the same weights: they differ only by the activation rounding
     assert np.abs(y8[ms, ns] - y16[ms, ns]).max() < 0.05 * np.abs(y16).max()
+
+
+@pytest.mark.parametrize("name", ["gateup", "down"])
+@pytest.mark.parametrize("form", ["minfloat", "int8"])
+def test_qwen2_7b_other_weight_forms(form, name):
+    """Float-minimum int4 and int8 weights at the sizes and launch plans `bench.py --weight-mode` times:
+    sampled prefill outputs (M = 1024) and the first row through both single-token calls."""
+    model, M, seed = "qwen2-7b", 1024, 77
+    W = fused_weights(model, name)
+    N, K = W.shape
+    note("full-size", form, model, name, "M", M, "N", N, "K", K)
+    x = synth.activations(M, K, seed, outliers=True)
+    if form == "minfloat":
+        mode, quant, sampled = B.MODE_W4_MIN_FLOAT, oracle.quant_weights_minf, oracle.linear_w4a8_minf_sampled
+    else:
+        mode, quant, sampled = B.MODE_W8_MIN_FLOAT, oracle.quant_weights8, oracle.linear_w8a8_sampled
+    q, s, mn = quant(W)
+    xq_o, sx_o, _ = oracle.quant_act(x)
+    packed = B.mnnq_pack_weights(dev(W), mode=mode)
+    del W
+    xq, sx = dev(xq_o), dev(sx_o)
+    y = B.mnnq_linear_prefill(packed, N, K, xq, sx, mode=mode).cpu().numpy()
+    rng = np.random.default_rng(seed)
+    ms = np.concatenate([rng.integers(0, M, 4096), [0, 0, M - 1, M - 1]])
+    ns = np.concatenate([rng.integers(0, N, 4096), [0, N - 1, 0, N - 1]])
+    _, y_s = sampled(xq_o, sx_o, q, s, mn, ms, ns, want_acc=False)
+    ymax = np.abs(y).max()
+    assert np.isfinite(y).all()
+    assert np.abs(y[ms, ns] - y_s).max() <= 1e-5 * ymax
+    # the first token in full through the GEMV and the fused GEMV
+    n_all = np.arange(N)
+    _, y0 = sampled(xq_o, sx_o, q, s, mn, np.zeros(N, dtype=np.int64), n_all, want_acc=False)
+    tol0 = 1e-5 * np.abs(y0).max()
+    yd = B.mnnq_linear_decode(packed, N, K, xq[0].contiguous(), sx[:1].contiguous(), mode=mode).cpu().numpy()
+    assert np.abs(yd - y0).max() <= tol0
+    yf = B.mnnq_linear_decode_fused(packed, N, K, dev(x[0]), mode=mode).cpu().numpy()
+    assert np.abs(yf - y0).max() <= tol0
+    assert np.abs(y[0] - y0).max() <= tol0
