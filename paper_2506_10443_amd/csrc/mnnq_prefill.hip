@@ -6,9 +6,9 @@
 //
 //   y[m,n] = sx[m] * sum_g scale[n,g] * I[m,n,g] (+ bias[n])
 //
-// The epilogue needs two VALU operations (convert, fused multiply-add) per
-// output and group - 8 per MFMA and lane, 32 cycles of the vector pipe against
-// 16 cycles of the matrix pipe - so the kernel is bound by the vector ALU, not
+// The epilogue needs two VALU operations (int32 -> fp32, fused multiply-add) per
+// output and group - 8 per MFMA and lane, which take longer to issue than the
+// MFMA occupies the matrix pipe - so the kernel is bound by the vector ALU, not
 // by the MFMA rate.  Everything else is arranged to add as little VALU work as
 // possible and to let it overlap the MFMAs:
 //   * all operands reach LDS with direct buffer loads (buffer_load ... lds): no
@@ -227,6 +227,12 @@ __global__ __launch_bounds__(128 * WNW * KS, (ACC || KS > 1) ? 1 : 2) void prefi
 #pragma unroll
                 for (int r = 0; r < 4; ++r) yacc[i][j][r] = 0.0f;
 
+        // C operand of the MFMAs whose results go to the fp32 epilogue (see there)
+        constexpr int kFloatBiasBits = 0x4B400000;
+        constexpr float kFloatBias = 12582912.0f;
+        v4i fbias = {kFloatBiasBits, kFloatBiasBits, kFloatBiasBits, kFloatBiasBits};
+        asm volatile("" : "+v"(fbias));
+
         v4i bw[TN];
         v4i bw2[W8 ? TN : 1];   // low nibble plane (W8)
         v2i bsv[TN];
@@ -322,13 +328,17 @@ __global__ __launch_bounds__(128 * WNW * KS, (ACC || KS > 1) ? 1 : 2) void prefi
                     // Float minimum form: one more MFMA per 16 rows with an all-ones B operand gives
                     // xs[m] = sum_{k in g} xq[m,k] in the D layout, i.e. for exactly the four rows of
                     // this lane; the epilogue adds min[n,g] * xs[m,g].
+                    // int32 -> fp32 without a convert instruction (it runs at a fraction of the rate of the
+                    // other vector instructions): the C operand carries the bit pattern of 1.5 * 2^23, so the
+                    // MFMA's integer result I + 0x4B400000 is, read as a float, exactly 12582912 + I for
+                    // |I| < 2^22 (here |I| <= 64 * 127 * 15), and one exact subtraction gives float(I).
                     const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
                     v4i a = *reinterpret_cast<const v4i*>(ap);
                     v4i a_nxt = a;
                     if (TM > 1) a_nxt = *reinterpret_cast<const v4i*>(ap + 2048);
-                    v4i d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[0], zero, 0, 0, 0);
+                    v4i d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[0], fbias, 0, 0, 0);
                     v4i xs_cur = zero, xs_nxt = zero;
-                    if (MINF) xs_cur = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, ones, zero, 0, 0, 0);
+                    if (MINF) xs_cur = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, ones, fbias, 0, 0, 0);
                     float xsf[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
                     for (int tt = 0; tt < TM * TN; ++tt) {
@@ -340,18 +350,18 @@ __global__ __launch_bounds__(128 * WNW * KS, (ACC || KS > 1) ? 1 : 2) void prefi
                                 a = a_nxt;
                                 if (i1 + 1 < TM) a_nxt = *reinterpret_cast<const v4i*>(ap + (i1 + 1) * 2048);
                             }
-                            d_nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[j1], zero, 0, 0, 0);
-                            if (MINF && j1 == 0) xs_nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, ones, zero, 0, 0, 0);
+                            d_nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[j1], fbias, 0, 0, 0);
+                            if (MINF && j1 == 0) xs_nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, ones, fbias, 0, 0, 0);
                             asm volatile("" : "+v"(d), "+v"(d_nxt));
                         }
                         if (MINF && j == 0) {
                             if (i > 0) xs_cur = xs_nxt;      // issued with the first MFMA of this row of tiles
 #pragma unroll
-                            for (int rr = 0; rr < 4; ++rr) xsf[rr] = (float)xs_cur[rr];
+                            for (int rr = 0; rr < 4; ++rr) xsf[rr] = __int_as_float(xs_cur[rr]) - kFloatBias;
                         }
 #pragma unroll
                         for (int rr = 0; rr < 4; ++rr) {
-                            yacc[i][j][rr] = fmaf(sc[j], (float)d[rr], yacc[i][j][rr]);
+                            yacc[i][j][rr] = fmaf(sc[j], __int_as_float(d[rr]) - kFloatBias, yacc[i][j][rr]);
                             if (MINF) yacc[i][j][rr] = fmaf(mnv[j], xsf[rr], yacc[i][j][rr]);
                         }
                         if (tt + 2 < TM * TN) {
