@@ -552,6 +552,18 @@ int launch_tiles(const uint8_t* packed, const Layout& L, int64_t M, const int8_t
     return launch_tiles_m<BM, BN, KS, ACC, false>(packed, L, M, xq, sx, bias, y, acc, S, st);
 }
 
+// Eight waves per K part (128 x 32 or 64 x 32 outputs per wave).
+template <int BM, int KS>
+int launch_wide(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
+                const float* bias, float* y, int S, hipStream_t st)
+{
+    if (L.minf) {
+        if constexpr (BM == 256 && KS == 2) return MNNQ_ERR_UNSUPPORTED;   // not built: see launch_prefill
+        else return launch_tiles_m<BM, 128, KS, false, true, false, 4>(packed, L, M, xq, sx, bias, y, nullptr, S, st);
+    }
+    return launch_tiles_m<BM, 128, KS, false, false, false, 4>(packed, L, M, xq, sx, bias, y, nullptr, S, st);
+}
+
 // Tile, K-part and split choice.  A compute unit is full with two waves per SIMD:
 // two workgroups of four waves, or one workgroup of eight whose halves take one half
 // of K each (KS = 2) and add their sums through LDS.
@@ -582,17 +594,19 @@ TilePlan plan_tiles(const Layout& L, int64_t M)
     } else if (tiles(128) <= cus) {
         p.big = false;
         p.KS = 2;
+        p.wide = true;      // sixteen waves: two K parts of eight
         if (tiles(128) * 2 <= cus && L.C >= 64) p.S = 2;
     } else if (tiles(128) < 2 * cus) {
         p.big = M > 128;
         p.KS = p.big ? 2 : 1;
+        p.wide = p.big && !L.minf;
     } else {
         p.big = false;
     }
     if (const char* e = getenv("MNNQ_PREFILL_TILE")) {   // tuning and tests: "b"/"s", split digit, "k" = K parts
         if (e[0] == 'b' || e[0] == 'w') p.big = true;
-        if (e[0] == 's') p.big = false;
-        p.wide = (e[0] == 'w');
+        if (e[0] == 's' || e[0] == 'v') p.big = false;
+        p.wide = (e[0] == 'w' || e[0] == 'v');     // "w"/"v" = "b"/"s" worked on by twice the waves
         if (e[0] && (e[1] == '1' || e[1] == '2' || e[1] == '4')) {
             p.S = e[1] - '0';
             p.KS = (e[2] == 'k') ? 2 : 1;
@@ -636,13 +650,17 @@ int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8
             p.KS = ((M + 127) / 128) * ((L.N + 127) / 128) <= num_cus() ? 2 : 1;
         }
         if (p.S > 1 && L.Cx < 64) p.S = 1;
+        if (p.KS == 2 && (p.wide || !forced_plan))
+            return launch_tiles_m<128, 128, 2, false, true, true, 4>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
         if (p.KS == 2)
             return launch_tiles_m<128, 128, 2, false, true, true>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
         return launch_tiles_m<128, 128, 1, false, true, true>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
     }
-    if (p.big && p.wide && p.KS == 1) {
-        if (L.minf) return launch_tiles_m<256, 128, 1, false, true, false, 4>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
-        return launch_tiles_m<256, 128, 1, false, false, false, 4>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
+    if (p.wide) {   // twice the waves per tile; the combinations not listed run in the four-wave form
+        if (p.big && p.KS == 1) return launch_wide<256, 1>(packed, L, M, xq, sx, bias, y, p.S, st);
+        if (p.big && p.KS == 2 && !L.minf)   // (the float minimum form would spill registers here)
+            return launch_wide<256, 2>(packed, L, M, xq, sx, bias, y, p.S, st);
+        if (!p.big && p.KS == 2) return launch_wide<128, 2>(packed, L, M, xq, sx, bias, y, p.S, st);
     }
     if (p.big && p.KS == 2) return launch_tiles<256, 128, 2, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
     if (p.big) return launch_tiles<256, 128, 1, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);

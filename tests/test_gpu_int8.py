@@ -79,7 +79,7 @@ def test_linear_matches_oracle(M, N, K):
     os.environ["MNNQ_NO_SKINNY"] = "1"
     try:
         for planes in ("0", "1"):
-            for cfg in ("b1", "s1", "b1k", "s1k", "s2", "s2k"):
+            for cfg in ("b1", "s1", "b1k", "s1k", "s2", "s2k", "v1k", "v2k"):
                 os.environ["MNNQ_PREFILL_TILE"] = cfg
                 os.environ["MNNQ_W8_PLANES"] = planes
                 try:
