@@ -564,15 +564,15 @@ int launch_wide(const uint8_t* packed, const Layout& L, int64_t M, const int8_t*
     return launch_tiles_m<BM, 128, KS, false, false, false, 4>(packed, L, M, xq, sx, bias, y, nullptr, S, st);
 }
 
-// Tile, K-part and split choice.  A compute unit is full with two waves per SIMD:
-// two workgroups of four waves, or one workgroup of eight whose halves take one half
-// of K each (KS = 2) and add their sums through LDS.
+// Tile, K-part and split choice.  A SIMD is full with four waves of the forms that need at most
+// 128 registers (eight waves per K part: 128 x 32 or 64 x 32 outputs per wave), with two otherwise.
 //   * 256-row tiles share one B unpack between 8 MFMAs and are preferred when they
-//     alone give every CU two workgroups;
+//     alone give every CU two workgroups (of eight waves each);
 //   * with at most one 128-row tile per CU, the tile's K range is split inside the
-//     workgroup, which fills the SIMDs without any traffic through memory;
+//     workgroup (two K parts of eight waves), which fills the SIMDs without any traffic
+//     through memory;
 //   * in between (more 128-row tiles than CUs, fewer than two each) a second round of
-//     workgroups would run on a few CUs only; 256-row tiles with a K split inside the
+//     workgroups would run on a few CUs only; 256-row tiles with the same K split inside the
 //     workgroup use fewer CUs but use them fully;
 //   * a split of K over two workgroups (S = 2, fp32 atomics onto a zeroed y) is left
 //     for long rows with so few tiles that most CUs would idle.
