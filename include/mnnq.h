@@ -227,6 +227,17 @@ int mnnq_peak_mfma_count(void);
 int mnnq_linear_acc_debug(const void *packed, int64_t M, int64_t N, int64_t K, int group, int mode,
                           const int8_t *xq, int32_t *acc, int use_prefill_kernel, void *stream);
 
+/* Test view of the host logic (Section 5.1 chooses loop tiling from the problem's dimensions; here:
+ * which kernel configuration a call would launch).  Nothing is launched and no device is needed.
+ * what = 0: mnnq_linear_prefill with M > 16 tokens (the tiled GEMM); out8 = {tile rows, tile columns,
+ *           K parts inside a workgroup, K split over workgroups, waves per workgroup, LDS bytes per
+ *           workgroup, workgroups, 1 if the two nibble planes of int8 weights are merged in registers};
+ * what = 1: mnnq_linear_decode; what = 2: mnnq_linear_decode_fused without workspace; out8 = {waves per
+ *           workgroup, waves per row tile, weight chunks a wave holds in registers, 1 if it loops with a
+ *           prefetch, LDS bytes per workgroup, workgroups, row tiles per workgroup, 0}.
+ * out8: HOST pointer to 8 int32.  Same shape / mode errors as the calls themselves. */
+int mnnq_plan_debug(int what, int64_t M, int64_t N, int64_t K, int group, int mode, int32_t *out8);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,7 +27,7 @@ EXPORTS = (
     "mnnq_linear_prefill", "mnnq_linear_decode_f16", "mnnq_linear_prefill_f16", "mnnq_linear_acc_debug",
     "mnnq_pack_from_quantized",
     "mnnq_linear_decode_o16", "mnnq_linear_prefill_o16", "mnnq_linear_decode_f16_o16", "mnnq_linear_prefill_f16_o16",
-    "mnnq_linear_prefill_fused", "mnnq_linear_decode_fused_o16", "mnnq_linear_prefill_fused_o16", "mnnq_peak_read", "mnnq_peak_mfma", "mnnq_peak_mfma_count",
+    "mnnq_plan_debug", "mnnq_linear_prefill_fused", "mnnq_linear_decode_fused_o16", "mnnq_linear_prefill_fused_o16", "mnnq_peak_read", "mnnq_peak_mfma", "mnnq_peak_mfma_count",
 )
 
 
@@ -71,6 +71,7 @@ def lib() -> ctypes.CDLL:
         L.mnnq_linear_prefill_fused.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
         L.mnnq_linear_decode_fused_o16.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
         L.mnnq_linear_prefill_fused_o16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.mnnq_plan_debug.argtypes = [i32, i64, i64, i64, i32, i32, vp]
         L.mnnq_peak_read.argtypes = [vp, sz, vp, vp]
         L.mnnq_peak_mfma.argtypes = [i32, i32, i32, i32, vp, vp]
         L.mnnq_peak_mfma_count.argtypes = []
@@ -355,6 +356,13 @@ def mnnq_linear_prefill_fused_o16(packed, N: int, K: int, x, bias=None, out=None
                                                _ptr(workspace), workspace.numel(), _stream()),
            "mnnq_linear_prefill_fused_o16")
     return y
+
+
+def mnnq_plan_debug(what: int, M: int, N: int, K: int, mode: int = MODE_W4_ZP_INT):
+    """Launch configuration a call would choose (host logic, no GPU needed): a list of 8 ints, see mnnq.h."""
+    out = (ctypes.c_int32 * 8)()
+    _check(lib().mnnq_plan_debug(what, M, N, K, GROUP, mode, ctypes.cast(out, ctypes.c_void_p)), "mnnq_plan_debug")
+    return list(out)
 
 
 # ---- measurement helpers

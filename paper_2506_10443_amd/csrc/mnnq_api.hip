@@ -335,6 +335,23 @@ int mnnq_linear_prefill_f16_o16(const void* packed, int64_t M, int64_t N, int64_
     return prefill_f16_impl(packed, M, N, K, group, mode, x16, row_scale, bias, y16, true, stream);
 }
 
+int mnnq_plan_debug(int what, int64_t M, int64_t N, int64_t K, int group, int mode, int32_t* out8)
+{
+    if (!out8) return MNNQ_ERR_NULL;
+    if (what < 0 || what > 2) return MNNQ_ERR_UNSUPPORTED;
+    if (what == 0 && M <= 0) return MNNQ_ERR_SHAPE;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    const Layout L = make_layout(N, K, mode);
+    if (what == 0) {
+        if (!prefill_fits(M, N, K, mode)) return MNNQ_ERR_UNSUPPORTED;
+        describe_prefill(L, M, out8);
+    } else {
+        if (L.K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
+        describe_decode(L, what == 2, out8);
+    }
+    return MNNQ_OK;
+}
+
 int mnnq_linear_acc_debug(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
                           const int8_t* xq, int32_t* acc, int use_prefill_kernel, void* stream)
 {

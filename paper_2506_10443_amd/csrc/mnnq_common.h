@@ -162,4 +162,12 @@ int launch_prefill_f16(const uint8_t* packed, const Layout& L, int64_t M, const 
 // Compute units of the current device (cached per thread and device).
 int num_cus();
 
+// Launch configuration the launchers above would choose (host logic only, nothing is launched).
+// prefill: {tile rows, tile columns, K parts in the workgroup, K split over workgroups, waves per
+// workgroup, LDS bytes, workgroups, 1 if the nibble planes of int8 weights are merged};
+// decode: {waves per workgroup, waves per row tile, chunks held in registers, 1 if the wave loops with
+// a prefetch, LDS bytes, workgroups, row tiles per workgroup, 0}.
+void describe_prefill(const Layout& L, int64_t M, int32_t out[8]);
+void describe_decode(const Layout& L, bool fused, int32_t out[8]);
+
 }  // namespace mnnq

@@ -357,9 +357,11 @@ int launch_cfg(const uint8_t* packed, const Layout& L, int64_t M, const void* xi
 // the layer are issued at once; very long rows fall back to a prefetching loop.
 // WAVES is the workgroup size: larger workgroups repeat the staging of the
 // activation row less often.
-template <int MODE>
-int dispatch(const uint8_t* packed, const Layout& L, int64_t M, const void* xin, const float* sx,
-             const float* bias, float* y, int32_t* acc, hipStream_t st)
+struct DecodeCfg {
+    int waves, ks, unroll, prefetch;
+};
+
+DecodeCfg decode_config(const Layout& L, bool fused)
 {
     int ks = 1;
     while (ks < 16 && (L.C + ks - 1) / ks > 8) ks *= 2;
@@ -377,12 +379,27 @@ int dispatch(const uint8_t* packed, const Layout& L, int64_t M, const void* xin,
             prefetch = pw > unroll;
         }
     }
-    int waves = (MODE == kFused) ? (ks > 8 ? 16 : 8) : (ks > 4 ? ks : 4);
+    int waves = fused ? (ks > 8 ? 16 : 8) : (ks > 4 ? ks : 4);
     if (const char* e = getenv("MNNQ_DECODE_WAVES")) {    // tuning only
         const int v = atoi(e);
         if ((v == 4 || v == 8 || v == 16) && v >= ks) waves = v;
     }
     if (waves < ks) waves = ks;
+    return DecodeCfg{waves, ks, unroll, prefetch};
+}
+
+size_t decode_lds_bytes(const Layout& L, const DecodeCfg& c, bool fused)
+{
+    const int64_t pw = (L.C + c.ks - 1) / c.ks;
+    return (fused ? (size_t)L.C * 160 : (size_t)c.waves * pw * 160) + c.waves * 17 * sizeof(float);
+}
+
+template <int MODE>
+int dispatch(const uint8_t* packed, const Layout& L, int64_t M, const void* xin, const float* sx,
+             const float* bias, float* y, int32_t* acc, hipStream_t st)
+{
+    const DecodeCfg c = decode_config(L, MODE == kFused);
+    const int waves = c.waves, ks = c.ks, unroll = c.unroll, prefetch = c.prefetch;
 #define MNNQ_CFG(W, K, U, P)                                                    \
     if (waves == W && ks == K && unroll == U && prefetch == P)                  \
         return launch_cfg<W, K, U, MODE, (P != 0)>(packed, L, M, xin, sx, bias, y, acc, st);
@@ -397,6 +414,20 @@ int dispatch(const uint8_t* packed, const Layout& L, int64_t M, const void* xin,
 }
 
 }  // namespace
+
+void describe_decode(const Layout& L, bool fused, int32_t out[8])
+{
+    const DecodeCfg c = decode_config(L, fused);
+    const int tiles_per_wg = c.waves / c.ks;
+    out[0] = c.waves;
+    out[1] = c.ks;
+    out[2] = c.unroll;
+    out[3] = c.prefetch;
+    out[4] = (int32_t)decode_lds_bytes(L, c, fused);
+    out[5] = (int32_t)((L.T + tiles_per_wg - 1) / tiles_per_wg);   // workgroups
+    out[6] = tiles_per_wg;
+    out[7] = 0;
+}
 
 int launch_decode(const uint8_t* packed, const Layout& L, const int8_t* xq, const float* sx,
                   const float* bias, float* y, hipStream_t st)

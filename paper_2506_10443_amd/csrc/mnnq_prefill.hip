@@ -631,6 +631,63 @@ int num_cus()
     return cached;
 }
 
+namespace {
+
+// What launch_prefill starts for a shape: tile rows, K parts inside the workgroup, K split over
+// workgroups, waves along N per K part (2 x WNW waves each), merged nibble planes of int8 weights.
+struct PrefillLaunch {
+    int BM, KS, S, WNW;
+    bool w8;
+};
+
+PrefillLaunch resolve_prefill(const Layout& L, int64_t M)
+{
+    TilePlan p = plan_tiles(L, M);
+    if (L.out16) p.S = 1;   // the split over two workgroups adds fp32 partial sums in the output array
+    const bool forced_plan = getenv("MNNQ_PREFILL_TILE") != nullptr;
+    PrefillLaunch r{p.big ? 256 : 128, p.KS, p.S, 2, false};
+    // 8-bit weights: both nibble planes of a chunk in one MFMA (128-row tiles: two B tiles need the LDS
+    // of the larger A tile).  MNNQ_W8_PLANES=1 (tests, comparisons) keeps one MFMA per plane instead.
+    const char* planes = getenv("MNNQ_W8_PLANES");
+    if (L.mode == MNNQ_W8_MIN_FLOAT && !(planes && planes[0] == '1')) {
+        r.w8 = true;
+        r.BM = 128;
+        if (!forced_plan)   // the plan above counted 256-row tiles too
+            r.KS = ((M + 127) / 128) * ((L.N + 127) / 128) <= num_cus() ? 2 : 1;
+        if (r.S > 1 && L.Cx < 64) r.S = 1;
+        r.WNW = (r.KS == 2 && (p.wide || !forced_plan)) ? 4 : 2;
+        return r;
+    }
+    // twice the waves per tile; the combinations not listed run in the four-wave form
+    if (p.wide && ((r.BM == 256 && r.KS == 1) || (r.BM == 256 && r.KS == 2 && !L.minf) || (r.BM == 128 && r.KS == 2)))
+        r.WNW = 4;   // (256 rows, two K parts, float minimum form: would spill registers)
+    return r;
+}
+
+static_assert(Lds<256, 128, false>::BYTES == 2 * 256 * 128 + 8 * 1024 + 8 * 128 + 8 * 32, "prefill_lds_bytes");
+static_assert(Lds<128, 128, true, true>::BYTES == 2 * 128 * 128 + 16 * 1024 + 8 * 128 + 8 * 128, "prefill_lds_bytes");
+
+size_t prefill_lds_bytes(const PrefillLaunch& r, bool minf)
+{
+    return (size_t)r.KS * (2 * r.BM * 128 + 8 * 1024 * (r.w8 ? 2 : 1) + 8 * 128 + 8 * (minf ? 128 : 32));
+}
+
+}  // namespace
+
+void describe_prefill(const Layout& L, int64_t M, int32_t out[8])
+{
+    const PrefillLaunch r = resolve_prefill(L, M);
+    const int64_t MT = (M + r.BM - 1) / r.BM, NT = (L.N + 127) / 128;
+    out[0] = r.BM;
+    out[1] = 128;
+    out[2] = r.KS;
+    out[3] = r.S;
+    out[4] = 2 * r.WNW * r.KS;                                   // waves per workgroup
+    out[5] = (int32_t)prefill_lds_bytes(r, L.minf);
+    out[6] = (int32_t)(MT * r.S * ((NT + 7) / 8) * 8);           // workgroups
+    out[7] = r.w8 ? 1 : 0;
+}
+
 int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
                    const float* bias, float* y, int32_t* acc_debug, hipStream_t st)
 {
@@ -638,34 +695,23 @@ int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8
         if (M > 128) return launch_tiles<256, 128, 1, true>(packed, L, M, xq, sx, bias, y, acc_debug, 1, st);
         return launch_tiles<128, 128, 1, true>(packed, L, M, xq, sx, bias, y, acc_debug, 1, st);
     }
-    TilePlan p = plan_tiles(L, M);
-    if (L.out16) p.S = 1;   // the split over two workgroups adds fp32 partial sums in the output array
-    // 8-bit weights: both nibble planes of a chunk in one MFMA (128-row tiles: two B tiles need the LDS
-    // of the larger A tile).  MNNQ_W8_PLANES=1 (tests, comparisons) keeps one MFMA per plane instead.
-    const char* planes = getenv("MNNQ_W8_PLANES");
-    const bool forced_plan = getenv("MNNQ_PREFILL_TILE") != nullptr;
-    if (L.mode == MNNQ_W8_MIN_FLOAT && !(planes && planes[0] == '1')) {
-        if (!forced_plan) {   // the plan above counted 256-row tiles too
-            p.big = false;
-            p.KS = ((M + 127) / 128) * ((L.N + 127) / 128) <= num_cus() ? 2 : 1;
-        }
-        if (p.S > 1 && L.Cx < 64) p.S = 1;
-        if (p.KS == 2 && (p.wide || !forced_plan))
-            return launch_tiles_m<128, 128, 2, false, true, true, 4>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
-        if (p.KS == 2)
-            return launch_tiles_m<128, 128, 2, false, true, true>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
-        return launch_tiles_m<128, 128, 1, false, true, true>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
+    const PrefillLaunch r = resolve_prefill(L, M);
+#define MNNQ_ARGS packed, L, M, xq, sx, bias, y, nullptr, r.S, st
+    if (r.w8) {
+        if (r.KS == 2 && r.WNW == 4) return launch_tiles_m<128, 128, 2, false, true, true, 4>(MNNQ_ARGS);
+        if (r.KS == 2) return launch_tiles_m<128, 128, 2, false, true, true>(MNNQ_ARGS);
+        return launch_tiles_m<128, 128, 1, false, true, true>(MNNQ_ARGS);
     }
-    if (p.wide) {   // twice the waves per tile; the combinations not listed run in the four-wave form
-        if (p.big && p.KS == 1) return launch_wide<256, 1>(packed, L, M, xq, sx, bias, y, p.S, st);
-        if (p.big && p.KS == 2 && !L.minf)   // (the float minimum form would spill registers here)
-            return launch_wide<256, 2>(packed, L, M, xq, sx, bias, y, p.S, st);
-        if (!p.big && p.KS == 2) return launch_wide<128, 2>(packed, L, M, xq, sx, bias, y, p.S, st);
+    if (r.WNW == 4) {
+        if (r.BM == 256 && r.KS == 1) return launch_wide<256, 1>(packed, L, M, xq, sx, bias, y, r.S, st);
+        if (r.BM == 256) return launch_wide<256, 2>(packed, L, M, xq, sx, bias, y, r.S, st);
+        return launch_wide<128, 2>(packed, L, M, xq, sx, bias, y, r.S, st);
     }
-    if (p.big && p.KS == 2) return launch_tiles<256, 128, 2, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
-    if (p.big) return launch_tiles<256, 128, 1, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
-    if (p.KS == 2) return launch_tiles<128, 128, 2, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
-    return launch_tiles<128, 128, 1, false>(packed, L, M, xq, sx, bias, y, nullptr, p.S, st);
+    if (r.BM == 256 && r.KS == 2) return launch_tiles<256, 128, 2, false>(MNNQ_ARGS);
+    if (r.BM == 256) return launch_tiles<256, 128, 1, false>(MNNQ_ARGS);
+    if (r.KS == 2) return launch_tiles<128, 128, 2, false>(MNNQ_ARGS);
+    return launch_tiles<128, 128, 1, false>(MNNQ_ARGS);
+#undef MNNQ_ARGS
 }
 
 }  // namespace mnnq

@@ -1,0 +1,98 @@
+"""Host logic of the launchers, checked without a GPU through mnnq_plan_debug: for every layer shape of
+the benchmark models the chosen kernel configuration fits the hardware limits the kernels assume
+(1024 threads, 160 KiB of LDS per workgroup for the GEMM, 64 KiB for the GEMV), covers the whole
+problem, and is the one the design documents for the Qwen2-7B shapes.  Nothing is launched."""
+import os
+
+import pytest
+
+from paper_2506_10443_amd import binding as B, synth
+
+LDS_GEMM, LDS_GEMV = 160 * 1024, 64 * 1024
+
+
+@pytest.fixture(scope="module", autouse=True)
+def built():
+    if not os.path.exists(B.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    for v in ("MNNQ_PREFILL_TILE", "MNNQ_DECODE_KSPLIT", "MNNQ_DECODE_WAVES", "MNNQ_W8_PLANES"):
+        os.environ.pop(v, None)
+
+
+def shapes():
+    out = []
+    for model, spec in synth.MODELS.items():
+        for fused in (True, False):
+            for name, N, K in synth.block_layers(model, fused=fused):
+                out.append((model, name, spec["prefill_m"], N, K))
+        if spec["lm_head"]:
+            out.append((model, "lm_head", spec["prefill_m"], *spec["lm_head"]))
+    return out
+
+
+@pytest.mark.parametrize("mode", [B.MODE_W4_ZP_INT, B.MODE_W4_MIN_FLOAT, B.MODE_W8_MIN_FLOAT])
+@pytest.mark.parametrize("model,name,M,N,K", shapes())
+def test_prefill_plan_fits_and_covers(model, name, M, N, K, mode):
+    for m in sorted({M, 17, 129, 300}):
+        bm, bn, ks, s, waves, lds, wgs, merged = B.mnnq_plan_debug(0, m, N, K, mode)
+        assert (bm, bn) in ((128, 128), (256, 128)) and ks in (1, 2) and s in (1, 2)
+        assert waves in (4, 8, 16) and waves * 64 <= 1024 and waves % ks == 0
+        assert lds <= LDS_GEMM
+        if waves // ks == 4:
+            assert 2 * lds <= LDS_GEMM or ks == 2      # the four-wave forms count on two workgroups per CU
+        assert wgs >= -(-m // bm) * s * -(-N // bn)     # every output tile (and K part) has a workgroup
+        assert merged == (1 if mode == B.MODE_W8_MIN_FLOAT else 0)
+        if merged:
+            assert bm == 128
+
+
+@pytest.mark.parametrize("mode", [B.MODE_W4_ZP_INT, B.MODE_W4_MIN_FLOAT, B.MODE_W8_MIN_FLOAT])
+@pytest.mark.parametrize("model,name,M,N,K", shapes())
+def test_decode_plan_fits_and_covers(model, name, M, N, K, mode):
+    chunks = -(-(K * (2 if mode == B.MODE_W8_MIN_FLOAT else 1)) // 128)
+    tiles = N // 16
+    for what in (1, 2):
+        if chunks * 128 > 49152:
+            with pytest.raises(B.MnnqError):
+                B.mnnq_plan_debug(what, 1, N, K, mode)
+            continue
+        waves, ks, unroll, prefetch, lds, wgs, tiles_per_wg, _ = B.mnnq_plan_debug(what, 1, N, K, mode)
+        assert waves in (4, 8, 16) and ks in (1, 2, 4, 8, 16) and waves % ks == 0 and tiles_per_wg == waves // ks
+        assert lds <= LDS_GEMV
+        assert wgs * tiles_per_wg >= tiles
+        per_wave = -(-chunks // ks)
+        assert prefetch == (1 if per_wave > unroll else 0)      # else the whole range sits in registers
+
+
+def test_documented_plans_of_the_qwen2_7b_block():
+    plan = lambda n, k: B.mnnq_plan_debug(0, 1024, n, k)[:5]
+    assert plan(37888, 3584) == [256, 128, 1, 1, 8]      # gate|up: two workgroups of eight waves per CU
+    assert plan(4608, 3584) == [256, 128, 2, 1, 16]      # q|k|v: two K parts of eight waves
+    assert plan(3584, 3584) == [128, 128, 2, 1, 16]      # o
+    assert plan(3584, 18944) == [128, 128, 2, 1, 16]     # down
+    assert B.mnnq_plan_debug(1, 1, 37888, 3584)[:4] == [4, 4, 8, 0]      # GEMV: four waves per row tile, 7 chunks each
+    assert B.mnnq_plan_debug(1, 1, 3584, 18944)[:4] == [16, 16, 12, 0]   # 148 chunks over sixteen waves
+    assert B.mnnq_plan_debug(2, 1, 4608, 3584)[0] == 8                    # fused quantizer: larger workgroups
+
+
+def test_switches_and_errors():
+    os.environ["MNNQ_PREFILL_TILE"] = "s1"
+    try:
+        assert B.mnnq_plan_debug(0, 1024, 37888, 3584)[:5] == [128, 128, 1, 1, 4]
+    finally:
+        os.environ.pop("MNNQ_PREFILL_TILE")
+    os.environ["MNNQ_W8_PLANES"] = "1"
+    try:
+        assert B.mnnq_plan_debug(0, 1024, 37888, 3584, B.MODE_W8_MIN_FLOAT)[7] == 0
+    finally:
+        os.environ.pop("MNNQ_W8_PLANES")
+    L = B.lib()
+    assert L.mnnq_plan_debug(0, 4, 16, 128, 64, 0, None) == -1
+    import ctypes
+    out = (ctypes.c_int32 * 8)()
+    p = ctypes.cast(out, ctypes.c_void_p)
+    assert L.mnnq_plan_debug(3, 4, 16, 128, 64, 0, p) == -3
+    assert L.mnnq_plan_debug(0, 0, 16, 128, 64, 0, p) == -2
+    assert L.mnnq_plan_debug(1, 1, 16, 100, 64, 0, p) == -2
+    assert L.mnnq_plan_debug(1, 1, 16, 65536, 64, 0, p) == -3     # longer than the GEMV stages in LDS
