@@ -597,9 +597,11 @@ TilePlan plan_tiles(const Layout& L, int64_t M)
         p.wide = true;      // sixteen waves: two K parts of eight
         if (tiles(128) * 2 <= cus && L.C >= 64) p.S = 2;
     } else if (tiles(128) < 2 * cus) {
-        p.big = M > 128;
+        // (float minimum form: the sixteen-wave 256-row form would spill; eight waves on 128-row tiles
+        // measured 5 - 9 % faster than two K parts of four waves on 256-row tiles)
+        p.big = M > 128 && !L.minf;
         p.KS = p.big ? 2 : 1;
-        p.wide = p.big && !L.minf;
+        p.wide = p.big || L.minf;
     } else {
         p.big = false;
     }
@@ -652,14 +654,18 @@ PrefillLaunch resolve_prefill(const Layout& L, int64_t M)
     if (L.mode == MNNQ_W8_MIN_FLOAT && !(planes && planes[0] == '1')) {
         r.w8 = true;
         r.BM = 128;
-        if (!forced_plan)   // the plan above counted 256-row tiles too
-            r.KS = ((M + 127) / 128) * ((L.N + 127) / 128) <= num_cus() ? 2 : 1;
+        const int64_t tiles128 = ((M + 127) / 128) * ((L.N + 127) / 128), cus = num_cus();
+        if (!forced_plan) {   // the plan above counted 256-row tiles too
+            r.KS = tiles128 <= cus ? 2 : 1;
+            r.WNW = tiles128 < 2 * cus ? 4 : 2;     // few tiles: twice the waves on each
+        } else {
+            r.WNW = p.wide ? 4 : 2;
+        }
         if (r.S > 1 && L.Cx < 64) r.S = 1;
-        r.WNW = (r.KS == 2 && (p.wide || !forced_plan)) ? 4 : 2;
         return r;
     }
     // twice the waves per tile; the combinations not listed run in the four-wave form
-    if (p.wide && ((r.BM == 256 && r.KS == 1) || (r.BM == 256 && r.KS == 2 && !L.minf) || (r.BM == 128 && r.KS == 2)))
+    if (p.wide && ((r.BM == 256 && r.KS == 1) || (r.BM == 256 && r.KS == 2 && !L.minf) || r.BM == 128))
         r.WNW = 4;   // (256 rows, two K parts, float minimum form: would spill registers)
     return r;
 }
@@ -699,13 +705,15 @@ int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8
 #define MNNQ_ARGS packed, L, M, xq, sx, bias, y, nullptr, r.S, st
     if (r.w8) {
         if (r.KS == 2 && r.WNW == 4) return launch_tiles_m<128, 128, 2, false, true, true, 4>(MNNQ_ARGS);
+        if (r.WNW == 4) return launch_tiles_m<128, 128, 1, false, true, true, 4>(MNNQ_ARGS);
         if (r.KS == 2) return launch_tiles_m<128, 128, 2, false, true, true>(MNNQ_ARGS);
         return launch_tiles_m<128, 128, 1, false, true, true>(MNNQ_ARGS);
     }
     if (r.WNW == 4) {
         if (r.BM == 256 && r.KS == 1) return launch_wide<256, 1>(packed, L, M, xq, sx, bias, y, r.S, st);
         if (r.BM == 256) return launch_wide<256, 2>(packed, L, M, xq, sx, bias, y, r.S, st);
-        return launch_wide<128, 2>(packed, L, M, xq, sx, bias, y, r.S, st);
+        if (r.KS == 2) return launch_wide<128, 2>(packed, L, M, xq, sx, bias, y, r.S, st);
+        return launch_wide<128, 1>(packed, L, M, xq, sx, bias, y, r.S, st);
     }
     if (r.BM == 256 && r.KS == 2) return launch_tiles<256, 128, 2, false>(MNNQ_ARGS);
     if (r.BM == 256) return launch_tiles<256, 128, 1, false>(MNNQ_ARGS);
