@@ -1,8 +1,8 @@
 // Prefill (M tokens): W4A8 GEMM on the gfx950 int8 matrix cores, compute-bound
 // (Section 2.1).  One v_mfma_i32_16x16x64_i8 contracts exactly one quantization
-// group (K = 64) of a 16 x 16 output tile, so with a zero C operand its result
-// is the int32 group accumulator I[m, n, g]; the fused epilogue converts it and
-// adds scale[n, g] * I to the fp32 running sum:
+// group (K = 64) of a 16 x 16 output tile, so its result (above the constant in
+// its C operand) is the int32 group accumulator I[m, n, g]; the fused epilogue
+// turns it into fp32 and adds scale[n, g] * I to the running sum:
 //
 //   y[m,n] = sx[m] * sum_g scale[n,g] * I[m,n,g] (+ bias[n])
 //
@@ -21,7 +21,10 @@
 //     free 128-bit read per lane;
 //   * A rows are 128 B in LDS with their 16-byte units XOR-swizzled by the row,
 //     which makes the 128-bit fragment reads conflict free without padding;
-//   * the epilogue of one tile is issued behind the MFMA of the next.
+//   * the epilogue of one tile is issued behind the MFMA of the next;
+//   * a tile is worked on by four or eight waves per K part (template parameter
+//     WNW); the eight-wave forms need at most 128 registers, which puts four waves
+//     on every SIMD.
 //
 // Lane mapping of the 16x16x64 int8 MFMA (A: 16 x 64, B: 64 x 16, D: 16 x 16):
 //   A operand: lane l holds row l % 16, 16 consecutive k of block l / 16;
