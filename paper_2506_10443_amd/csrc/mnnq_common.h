@@ -98,22 +98,29 @@ __device__ __forceinline__ void store_out(float* y, int64_t i, float v, bool out
 // together.  |r| <= 127 (1 + 2^-22) in this path, so rint(r) needs no clamp.
 // (lim is 0.5 - 6e-5 normally; negative - "always divide" - when 1 / scale is not
 // a normal number; the division path clamps as the definition does.)
+// rint(r) itself is taken from the sum r + 1.5 * 2^23 (round to nearest even happens in the
+// addition), which costs an add and a subtract instead of a rounding and a convert instruction
+// per element - converts run at a fraction of the rate of the other vector instructions.
 // Callers are compiled with -ffp-contract=off: x * inv - rint(x * inv) must be a
 // product rounded to binary32 and an exact subtraction.
 __device__ __forceinline__ int quant4_fast(float4 v, float scale, float inv, float lim)
 {
-    float t0 = rintf(v.x * inv), t1 = rintf(v.y * inv), t2 = rintf(v.z * inv), t3 = rintf(v.w * inv);
-    const float d0 = fabsf(v.x * inv - t0), d1 = fabsf(v.y * inv - t1);
-    const float d2 = fabsf(v.z * inv - t2), d3 = fabsf(v.w * inv - t3);
+    // Round to nearest even by adding 1.5 * 2^23: for |r| < 2^22 the sum is exactly 12582912 + rint(r),
+    // and its bit pattern is 0x4B400000 + rint(r), i.e. the low byte already is the int8 code.
+    constexpr float kMagic = 12582912.0f;
+    const float r0 = v.x * inv, r1 = v.y * inv, r2 = v.z * inv, r3 = v.w * inv;
+    float m0 = r0 + kMagic, m1 = r1 + kMagic, m2 = r2 + kMagic, m3 = r3 + kMagic;
+    const float d0 = fabsf(r0 - (m0 - kMagic)), d1 = fabsf(r1 - (m1 - kMagic));
+    const float d2 = fabsf(r2 - (m2 - kMagic)), d3 = fabsf(r3 - (m3 - kMagic));
     if (!(fmaxf(fmaxf(d0, d1), fmaxf(d2, d3)) <= lim)) {
-        t0 = fminf(fmaxf(rintf(v.x / scale), -127.0f), 127.0f);
-        t1 = fminf(fmaxf(rintf(v.y / scale), -127.0f), 127.0f);
-        t2 = fminf(fmaxf(rintf(v.z / scale), -127.0f), 127.0f);
-        t3 = fminf(fmaxf(rintf(v.w / scale), -127.0f), 127.0f);
+        m0 = fminf(fmaxf(rintf(v.x / scale), -127.0f), 127.0f) + kMagic;
+        m1 = fminf(fmaxf(rintf(v.y / scale), -127.0f), 127.0f) + kMagic;
+        m2 = fminf(fmaxf(rintf(v.z / scale), -127.0f), 127.0f) + kMagic;
+        m3 = fminf(fmaxf(rintf(v.w / scale), -127.0f), 127.0f) + kMagic;
     }
-    // low bytes of the four integers into one dword
-    const uint32_t lo = __builtin_amdgcn_perm((uint32_t)(int)t1, (uint32_t)(int)t0, 0x0c0c0400u);
-    const uint32_t hi = __builtin_amdgcn_perm((uint32_t)(int)t3, (uint32_t)(int)t2, 0x04000c0cu);
+    // low bytes of the four patterns into one dword
+    const uint32_t lo = __builtin_amdgcn_perm(__float_as_uint(m1), __float_as_uint(m0), 0x0c0c0400u);
+    const uint32_t hi = __builtin_amdgcn_perm(__float_as_uint(m3), __float_as_uint(m2), 0x04000c0cu);
     return (int)(lo | hi);
 }
 
