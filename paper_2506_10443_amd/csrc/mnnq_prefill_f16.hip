@@ -100,8 +100,11 @@ struct Lds {
     static constexpr int BYTES = Z_OFF + NT16 * (MINF ? 128 : 32);
 };
 
-template <int BM, int BN, bool MINF>
-__global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __restrict__ packed, Layout L, int64_t M,
+// KS: K parts inside the workgroup (as in the int8 kernel): with KS = 2 the workgroup has eight waves,
+// each half takes one half of the chunks with staging buffers of its own, and the halves' sums are
+// added through LDS in a fixed order - for shapes with at most one tile per CU.
+template <int BM, int BN, bool MINF, int KS = 1>
+__global__ __launch_bounds__(256 * KS, KS > 1 ? 1 : 2) void prefill_f16_kernel(const uint8_t* __restrict__ packed, Layout L, int64_t M,
                                                              const uint16_t* __restrict__ x16,
                                                              const float* __restrict__ rs,
                                                              const float* __restrict__ bias, float* __restrict__ y,
@@ -113,12 +116,16 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
     constexpr int NT16 = St::NT16;
     constexpr int A_INSTR = BM / 8 / 4;          // 1 KiB direct loads of A per wave and stage
     static_assert(NT16 == 8, "B side is written for 8 row tiles per workgroup");
+    static_assert(KS == 1 || 4 * TM * TN * 4 * 64 * 4 <= KS * St::BYTES, "the K parts' sums must fit in LDS");
 
-    extern __shared__ __align__(16) uint8_t lds[];   // St::BYTES
+    extern __shared__ __align__(16) uint8_t lds_all[];   // KS * St::BYTES
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = wave_id & 3;                // position in the 2 x 2 wave grid of its K part
+    const int kh = wave_id >> 2;                 // K part of this wave (0 .. KS-1)
+    uint8_t* const lds = lds_all + kh * St::BYTES;
     const int wm = wave >> 1, wn = wave & 1;
     const int col = lane & 15;
     const int kb = lane >> 4;
@@ -286,23 +293,31 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
         }
     };
 
-    issue_a(0, 0);
-    issue_b(0);
+    // This K part's chunks; all waves run the longest share's barriers, the shorter share idles
+    // through the last round.
+    const int cb = C * kh / KS, ce = C * (kh + 1) / KS;
+    const int n_iter = (C + KS - 1) / KS;
+    if (cb < ce) {
+        issue_a(2 * cb, 0);
+        issue_b(cb);
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     __syncthreads();
-    read_b();
+    if (cb < ce) read_b();
 
-    for (int c = 0; c < C; ++c) {
-        const bool more = c + 1 < C;
+    for (int it = 0; it < n_iter; ++it) {
+        const int c = cb + it;
+        const bool live = c < ce;
+        const bool more = c + 1 < ce;
         // Every wave has finished group 2c - 1 and holds chunk c's B fragments in
         // registers: the odd A buffer and the B tile may be overwritten.
         __syncthreads();
         // The padding group of an odd G is skipped: its activations would be the next
         // row's, and 0 * x is not 0 for every x.
-        const bool odd_group = 2 * c + 1 < (int)L.G;
+        const bool odd_group = live && 2 * c + 1 < (int)L.G;
         if (odd_group) issue_a(2 * c + 1, 1);
         if (more) issue_b(c + 1);
-        compute(0, 0);
+        if (live) compute(0, 0);
         // Group 2c + 1 (and chunk c + 1's B tile) has landed for every wave, and every
         // wave has finished reading the even A buffer.
         __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -313,6 +328,36 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
             read_b();
             __builtin_amdgcn_s_waitcnt(0x0F70);
         }
+    }
+
+    if (KS > 1) {
+        // Add the K parts in a fixed order: part kh > 0 leaves its sums in LDS (one conflict-free
+        // float per lane and accumulator), part 0 adds them.
+        float* red = reinterpret_cast<float*>(lds_all);
+        const int slot = wave * (TM * TN * 4 * 64) + lane;
+#pragma unroll
+        for (int p = 1; p < KS; ++p) {
+            __syncthreads();                 // staging buffers (or the previous part's sums) are dead
+            if (kh == p) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) red[slot + ((i * TN + j) * 4 + r) * 64] = yacc[i][j][r];
+            }
+            __syncthreads();
+            if (kh == 0) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) yacc[i][j][r] += red[slot + ((i * TN + j) * 4 + r) * 64];
+            }
+        }
+        __syncthreads();                     // part 0 has read the sums: LDS is free for the output stage
+        if (kh != 0) return;
     }
 
     // Output: y = yacc * rs[m] + bias[n].  Buffer accesses keep this free of branches
@@ -337,8 +382,8 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
     // its own; the barrier in front makes sure no wave still reads operands where it lies.
     static_assert(TN == 4, "a lane stores one 16-byte unit of a 64-column row segment");
     constexpr int RS = 16 * TN + 4;                    // floats per patch row
-    __syncthreads();
-    float* patch = reinterpret_cast<float*>(lds) + wave * (16 * RS);
+    if (KS == 1) __syncthreads();
+    float* patch = reinterpret_cast<float*>(lds_all) + wave * (16 * RS);
     float* wr = patch + (kb * 4) * RS + col;
     const float* rd = patch + kb * RS + col * 4;       // + 4 p rows
     // a lane's 16-byte unit lies in row tile nt0 + col / 4; units past N are sent out of range
@@ -378,14 +423,14 @@ __global__ __launch_bounds__(256, 2) void prefill_f16_kernel(const uint8_t* __re
     }
 }
 
-template <int BM, int BN, bool MINF>
+template <int BM, int BN, bool MINF, int KS = 1>
 int launch_tiles_m(const uint8_t* packed, const Layout& L, int64_t M, const uint16_t* x16, const float* rs,
                    const float* bias, float* y, hipStream_t st)
 {
     const int MT = (int)((M + BM - 1) / BM);
     const int NT = (int)((L.N + BN - 1) / BN);
-    constexpr size_t smem = (size_t)Lds<BM, BN, MINF>::BYTES;
-    auto kern = prefill_f16_kernel<BM, BN, MINF>;
+    constexpr size_t smem = (size_t)KS * Lds<BM, BN, MINF>::BYTES;
+    auto kern = prefill_f16_kernel<BM, BN, MINF, KS>;
     if (smem > 64 * 1024) {
         // More than 64 KiB of dynamic LDS has to be allowed once per kernel and device.
         static thread_local int allowed_dev = -1;
@@ -398,17 +443,17 @@ int launch_tiles_m(const uint8_t* packed, const Layout& L, int64_t M, const uint
         }
     }
     const int64_t blocks = (int64_t)MT * ((NT + 7) / 8) * 8;
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), smem, st, packed, L, M, x16, rs, bias, y, MT, NT);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256 * KS), smem, st, packed, L, M, x16, rs, bias, y, MT, NT);
     MNNQ_HIP_TRY(hipGetLastError());
     return MNNQ_OK;
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int KS = 1>
 int launch_tiles(const uint8_t* packed, const Layout& L, int64_t M, const uint16_t* x16, const float* rs,
                  const float* bias, float* y, hipStream_t st)
 {
-    if (L.minf) return launch_tiles_m<BM, BN, true>(packed, L, M, x16, rs, bias, y, st);
-    return launch_tiles_m<BM, BN, false>(packed, L, M, x16, rs, bias, y, st);
+    if (L.minf) return launch_tiles_m<BM, BN, true, KS>(packed, L, M, x16, rs, bias, y, st);
+    return launch_tiles_m<BM, BN, false, KS>(packed, L, M, x16, rs, bias, y, st);
 }
 
 }  // namespace
@@ -418,12 +463,18 @@ int launch_prefill_f16(const uint8_t* packed, const Layout& L, int64_t M, const 
 {
     const int cus = num_cus();
     const int64_t tiles_big = ((M + 255) / 256) * ((L.N + 127) / 128);
+    const int64_t tiles_small = ((M + 127) / 128) * ((L.N + 127) / 128);
     bool big = M > 128 && tiles_big >= 2 * (int64_t)cus;
-    if (const char* e = getenv("MNNQ_PREFILL_TILE")) {   // tuning only
+    // at most one 128-row tile per CU: split the chunks over the two halves of an eight-wave workgroup
+    int ks = (!big && tiles_small <= (int64_t)cus && L.C >= 4) ? 2 : 1;
+    if (const char* e = getenv("MNNQ_PREFILL_TILE")) {   // tuning and tests: "b"/"s" tile, third letter "k" = K parts
         if (e[0] == 'b') big = true;
         if (e[0] == 's') big = false;
+        if (e[0]) ks = (e[1] && e[2] == 'k') ? 2 : 1;
     }
+    if (big && ks == 2) return launch_tiles<256, 128, 2>(packed, L, M, x16, rs, bias, y, st);
     if (big) return launch_tiles<256, 128>(packed, L, M, x16, rs, bias, y, st);
+    if (ks == 2) return launch_tiles<128, 128, 2>(packed, L, M, x16, rs, bias, y, st);
     return launch_tiles<128, 128>(packed, L, M, x16, rs, bias, y, st);
 }
 

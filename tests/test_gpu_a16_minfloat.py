@@ -49,7 +49,7 @@ def test_a16_matches_oracle(M, N, K, which):
     packed = B.mnnq_pack_weights(dev(W), mode=mode)
     xd = dev(x16)
     tol = TOL_A16 * np.abs(y_o).max()
-    for tile in ("", "b", "s"):
+    for tile in ("", "b", "s", "b1k", "s1k"):
         if tile:
             os.environ["MNNQ_PREFILL_TILE"] = tile
         try:

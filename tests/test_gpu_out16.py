@@ -93,10 +93,16 @@ def test_w4a16_out16(M, N, K):
     y_o = oracle.linear_w4a16(x16, q, s, z, bias=bias)
     packed = B.mnnq_pack_weights(dev(W))
     xd, bd = dev(x16), dev(bias)
-    y32 = B.mnnq_linear_prefill_f16(packed, N, K, xd, bias=bd)
-    y16 = B.mnnq_linear_prefill_f16_o16(packed, N, K, xd, bias=bd)
-    assert torch.equal(y16, y32.to(torch.float16))
-    close_to_oracle(host(y16), y_o, TOL_A16)
+    for cfg in ("", "s1", "b1", "s1k", "b1k"):       # tile and K parts of the fp16 GEMM
+        if cfg:
+            os.environ["MNNQ_PREFILL_TILE"] = cfg
+        try:
+            y32 = B.mnnq_linear_prefill_f16(packed, N, K, xd, bias=bd)
+            y16 = B.mnnq_linear_prefill_f16_o16(packed, N, K, xd, bias=bd)
+        finally:
+            os.environ.pop("MNNQ_PREFILL_TILE", None)
+        assert torch.equal(y16, y32.to(torch.float16)), cfg
+        close_to_oracle(host(y16), y_o, TOL_A16)
     y32 = B.mnnq_linear_decode_f16(packed, N, K, xd[0].contiguous(), bias=bd)
     y16 = B.mnnq_linear_decode_f16_o16(packed, N, K, xd[0].contiguous(), bias=bd)
     assert torch.equal(y16, y32.to(torch.float16))

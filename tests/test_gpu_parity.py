@@ -425,28 +425,36 @@ def test_w4a16_matches_oracle(M, N, K):
 
 
 @pytest.mark.parametrize("M,N,K", [(17, 16, 64), (300, 272, 448), (513, 400, 1536), (1024, 512, 3584)])
-@pytest.mark.parametrize("tile", ["", "b", "s"])
+@pytest.mark.parametrize("tile", ["", "b", "s", "b1k", "s1k"])
 def test_prefill_f16_with_integer_codes_equals_int8_prefill(M, N, K, tile):
     # int8 codes are exact in fp16 and every group sum is an integer below 2^24: the fp16
-    # matrix cores give the int32 accumulators exactly, hence bit-identical y.
+    # matrix cores give the int32 accumulators exactly, hence bit-identical y - as long as the
+    # fp32 sums over the groups are added in the same order: by one wave in sequence ("s1"), or in
+    # two halves of the chunks that are added at the end ("s1k"; the fp16 kernel's own choice for
+    # shapes with few tiles).
     note("f16 == int8", M, N, K, tile)
     W = synth.weights(N, K, 900 + M)
     x = synth.activations(M, K, 901 + M, outliers=True)
     packed = B.mnnq_pack_weights(dev(W))
     xq, sx, _ = B.mnnq_quant_act(dev(x), want_xsum=False)
     bias = dev(synth.weights(1, N, 7)[0] * 10)
-    os.environ["MNNQ_PREFILL_TILE"] = "s1"       # groups summed in order by one wave, as the fp16 kernel does
-    try:
-        y8 = B.mnnq_linear_prefill(packed, N, K, xq, sx, bias=bias)
-    finally:
-        os.environ.pop("MNNQ_PREFILL_TILE", None)
+    y8 = {}
+    for plan in ("s1", "s1k"):
+        os.environ["MNNQ_PREFILL_TILE"] = plan
+        try:
+            y8[plan] = B.mnnq_linear_prefill(packed, N, K, xq, sx, bias=bias)
+        finally:
+            os.environ.pop("MNNQ_PREFILL_TILE", None)
     if tile:
         os.environ["MNNQ_PREFILL_TILE"] = tile
     try:
         y16 = B.mnnq_linear_prefill_f16(packed, N, K, xq.to(torch.float16), bias=bias, row_scale=sx)
     finally:
         os.environ.pop("MNNQ_PREFILL_TILE", None)
-    assert torch.equal(y8, y16)
+    if tile == "":
+        assert torch.equal(y8["s1"], y16) or torch.equal(y8["s1k"], y16)
+    else:
+        assert torch.equal(y8["s1k" if tile.endswith("k") else "s1"], y16)
 
 
 def test_prefill_f16_rows_do_not_leak_into_each_other():
