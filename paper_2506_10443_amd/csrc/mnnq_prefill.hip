@@ -584,14 +584,24 @@ struct TilePlan {
     int KS;
     int S;
     bool wide;   // 256-row tile worked on by eight waves (128 x 32 outputs each), two workgroups per CU
+    bool tiny;   // 64-row tile (at most 64 tokens): the call is bound by the weight stream, not by the MFMAs
 };
 
 TilePlan plan_tiles(const Layout& L, int64_t M)
 {
-    TilePlan p{true, 1, 1, false};
+    TilePlan p{true, 1, 1, false, false};
     const int64_t cus = num_cus();
     auto tiles = [&](int bm) { return ((M + bm - 1) / bm) * ((L.N + 127) / 128); };
-    if (M > 128 && tiles(256) >= 2 * cus) {
+    if (M <= 64 && L.mode != MNNQ_W8_MIN_FLOAT) {
+        // A few dozen tokens (batched decoding): one 64-row tile per 128 columns, a quarter of the MFMAs
+        // of a 128-row tile per chunk; the K range goes to 1, 2 or 4 parts of four waves so that the
+        // few workgroups there are keep many loads in flight, and long rows are also cut in two.
+        p.big = false;
+        p.tiny = true;
+        const int64_t t = tiles(64);
+        p.KS = t >= cus ? 1 : (2 * t >= cus ? 2 : 4);
+        if (4 * t <= cus && L.C >= 64) p.S = 2;
+    } else if (M > 128 && tiles(256) >= 2 * cus) {
         p.big = true;
         p.wide = !L.minf;   // the float minimum form needs more registers than four waves per SIMD leave
     } else if (tiles(128) <= cus) {
@@ -610,11 +620,12 @@ TilePlan plan_tiles(const Layout& L, int64_t M)
     }
     if (const char* e = getenv("MNNQ_PREFILL_TILE")) {   // tuning and tests: "b"/"s", split digit, "k" = K parts
         if (e[0] == 'b' || e[0] == 'w') p.big = true;
-        if (e[0] == 's' || e[0] == 'v') p.big = false;
+        if (e[0] == 's' || e[0] == 'v' || e[0] == 't') p.big = false;
         p.wide = (e[0] == 'w' || e[0] == 'v');     // "w"/"v" = "b"/"s" worked on by twice the waves
+        p.tiny = (e[0] == 't') && L.mode != MNNQ_W8_MIN_FLOAT;   // "t" = 64-row tile; "k" / "q" = 2 / 4 K parts
         if (e[0] && (e[1] == '1' || e[1] == '2' || e[1] == '4')) {
             p.S = e[1] - '0';
-            p.KS = (e[2] == 'k') ? 2 : 1;
+            p.KS = (e[2] == 'k') ? 2 : ((e[2] == 'q' && p.tiny) ? 4 : 1);
         }
     }
     return p;
@@ -650,7 +661,7 @@ PrefillLaunch resolve_prefill(const Layout& L, int64_t M)
     TilePlan p = plan_tiles(L, M);
     if (L.out16) p.S = 1;   // the split over two workgroups adds fp32 partial sums in the output array
     const bool forced_plan = getenv("MNNQ_PREFILL_TILE") != nullptr;
-    PrefillLaunch r{p.big ? 256 : 128, p.KS, p.S, 2, false};
+    PrefillLaunch r{p.big ? 256 : (p.tiny ? 64 : 128), p.KS, p.S, 2, false};
     // 8-bit weights: both nibble planes of a chunk in one MFMA (128-row tiles: two B tiles need the LDS
     // of the larger A tile).  MNNQ_W8_PLANES=1 (tests, comparisons) keeps one MFMA per plane instead.
     const char* planes = getenv("MNNQ_W8_PLANES");
@@ -717,6 +728,11 @@ int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8
         if (r.BM == 256) return launch_wide<256, 2>(packed, L, M, xq, sx, bias, y, r.S, st);
         if (r.KS == 2) return launch_wide<128, 2>(packed, L, M, xq, sx, bias, y, r.S, st);
         return launch_wide<128, 1>(packed, L, M, xq, sx, bias, y, r.S, st);
+    }
+    if (r.BM == 64) {
+        if (r.KS == 4) return launch_tiles<64, 128, 4, false>(MNNQ_ARGS);
+        if (r.KS == 2) return launch_tiles<64, 128, 2, false>(MNNQ_ARGS);
+        return launch_tiles<64, 128, 1, false>(MNNQ_ARGS);
     }
     if (r.BM == 256 && r.KS == 2) return launch_tiles<256, 128, 2, false>(MNNQ_ARGS);
     if (r.BM == 256) return launch_tiles<256, 128, 1, false>(MNNQ_ARGS);

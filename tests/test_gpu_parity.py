@@ -271,7 +271,7 @@ def test_decode_bias_and_one_hot():
 
 
 PREFILL_SHAPES = [(1, 16, 64), (17, 144, 192), (128, 128, 128), (200, 512, 1536), (130, 272, 3584),
-                  (512, 1536, 1536), (64, 256, 8960)]
+                  (512, 1536, 1536), (64, 256, 8960), (33, 400, 1536), (48, 144, 18944), (20, 4608, 1024)]
 
 
 @pytest.mark.parametrize("M,N,K", PREFILL_SHAPES)
@@ -292,7 +292,7 @@ def test_prefill_matches_oracle(M, N, K):
     y2 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=dev(bias)))
     assert np.array_equal(y, y2)
     # every tile / split choice gives the same result to the same tolerance
-    for cfg in ("b1", "b2", "s1", "s2", "b1k", "s1k", "b2k", "s2k", "w1", "w2", "v1k", "v2k", "w1k", "w2k"):
+    for cfg in ("b1", "b2", "s1", "s2", "b1k", "s1k", "b2k", "s2k", "w1", "w2", "v1k", "v2k", "w1k", "w2k", "t1", "t2", "t1k", "t1q", "t2q"):
         os.environ["MNNQ_PREFILL_TILE"] = cfg
         try:
             y3 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=dev(bias)))
