@@ -592,10 +592,10 @@ TilePlan plan_tiles(const Layout& L, int64_t M)
     TilePlan p{true, 1, 1, false, false};
     const int64_t cus = num_cus();
     auto tiles = [&](int bm) { return ((M + bm - 1) / bm) * ((L.N + 127) / 128); };
-    if (M <= 64 && L.mode != MNNQ_W8_MIN_FLOAT) {
-        // A few dozen tokens (batched decoding): one 64-row tile per 128 columns, a quarter of the MFMAs
-        // of a 128-row tile per chunk; the K range goes to 1, 2 or 4 parts of four waves so that the
-        // few workgroups there are keep many loads in flight, and long rows are also cut in two.
+    if (M <= 128 && L.mode != MNNQ_W8_MIN_FLOAT) {
+        // Up to 128 tokens (batched decoding): 64-row tiles, a quarter of the MFMAs of a 128-row tile
+        // per chunk; the K range goes to 1, 2 or 4 parts of four waves so that the few workgroups
+        // there are keep many loads in flight, and long rows are also cut in two.
         p.big = false;
         p.tiny = true;
         const int64_t t = tiles(64);
