@@ -31,7 +31,7 @@ G = 64
 # HBM traffic per launch (bytes, mean over a pass) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this file, scaled by a copy kernel of known size; see profiles/ for the runs.  None = not measured
 # for the current kernels.
-PREFILL_TRAFFIC_BYTES = 171.0e6   # profiles/bench_qwen2-7b_hbm_traffic.txt
+PREFILL_TRAFFIC_BYTES = 171.1e6   # profiles/bench_qwen2-7b_hbm_traffic.txt
 DECODE_TRAFFIC_BYTES = 33.9e6     # same file
 
 
