@@ -435,12 +435,13 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8 x int4 -> int32, fp32 epilogue",
+        "dtype": "int8",   # int8 x int4 -> int32 group sums, fp32 epilogue
         "data": "synthetic: N(0,0.02) weights of one block drawn on the host (seeded) and packed into "
                 "%d distinct buffers, N(0,1) activations with 0.1%% outlier channels x20" % n_blocks,
         "config": {"workload": "%s-shaped W4A8 linears: decode batch 1 (%d blocks%s) + prefill M=%d (%d blocks), "
                                "q|k|v and gate|up concatenated along N" %
                                (args.model, n_blocks, " + lm_head" if lm else "", M_pre, n_blocks),
+                   "arithmetic": "int8 x int4 -> int32, fp32 epilogue",
                    "group": 64, "graph": not args.no_graph, "phase": args.phase,
                    "fused_decode_quant": bool(args.fused_decode), "weight_mode": args.weight_mode,
                    "concatenated_projections": not args.separate_projections},
