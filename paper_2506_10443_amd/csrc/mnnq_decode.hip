@@ -370,6 +370,9 @@ DecodeCfg decode_config(const Layout& L, bool fused)
         if ((L.C + 15) / 16 <= 12) unroll = 12;
         else prefetch = 1;
     }
+    // Fused quantizer (eight-wave workgroups) on a layer with at most one row tile per CU: all eight
+    // waves on one row tile, so that every tile has a workgroup of its own (o of Qwen2-7B: 6.1 -> 5.3 us).
+    if (fused && ks < 8 && L.T <= num_cus() && L.C >= 8) ks = 8;
     if (const char* e = getenv("MNNQ_DECODE_KSPLIT")) {   // tests and tuning: force the split
         const int v = atoi(e);
         if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16) {
