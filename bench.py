@@ -57,6 +57,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--model", default="qwen2-7b", choices=["qwen2-1.5b", "qwen2-7b", "llama3-8b"])
     ap.add_argument("--phase", default="both", choices=["both", "decode", "prefill"])
+    ap.add_argument("--lm-head-prefill", action="store_true",
+                    help="also time the LM head through the prefill GEMM at the prefill batch (per_layer.prefill_lm_head)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -306,6 +308,17 @@ def main() -> int:
             t = time_launches([lambda: B.mnnq_linear_decode(lm[0], lm[1], lm[2], xq, sx, out=y, mode=wmode)] * 4, 4)
             per_layer["decode_lm_head"] = {"us": round(t * 1e3, 2),
                                            "gbs": round(decode_bytes(lm[1], lm[2]) / (t * 1e-3) / 1e9, 1)}
+
+    # ---- the LM head through the prefill GEMM (a shape stress: a real prefill needs only the last token's row;
+    #      reported separately, not part of any pass)
+    if args.lm_head_prefill and lm is not None and do_pre:
+        xf = torch.from_numpy(synth.activations(M_pre, lm[2], 4242, outliers=True)).to(dev)
+        xq_l, sx_l, _ = B.mnnq_quant_act(xf, want_xsum=False)
+        y_l = torch.empty((M_pre, lm[1]), dtype=torch.float32, device=dev)
+        t = time_launches([lambda: B.mnnq_linear_prefill(lm[0], lm[1], lm[2], xq_l, sx_l, out=y_l, mode=wmode)] * 2, 3)
+        per_layer["prefill_lm_head"] = {"us": round(t * 1e3, 2),
+                                        "tops": round(prefill_ops(M_pre, lm[1], lm[2]) / (t * 1e-3) / 1e12, 1)}
+        del xf, xq_l, sx_l, y_l
 
     # ---- fp16 activations on the same packed weights (reported beside the target path, not part of `value`)
     if args.act16:
