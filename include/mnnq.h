@@ -19,9 +19,10 @@
  *     without a GPU.  NaN / Inf in W or x: undefined result, no error.
  *   - Limits (MNNQ_ERR_UNSUPPORTED beyond them): N and K up to 2^24.  Decode calls: K up to
  *     49152 (with fp16 activations 30720, or 27648 in the float-minimum modes; for int8
- *     weights half of these), the row is staged in LDS.  Prefill calls address with 32-bit byte offsets: (M + 256) * K, the packed
- *     matrix and (M + 256) * N * 4 must each stay below 2 GiB (twice K with fp16
- *     activations); split larger batches along M.  mnnq_linear_acc_debug: M up to 65535.
+ *     weights half of these), the row is staged in LDS.  Prefill calls address with 32-bit byte offsets: the packed matrix
+ *     must stay below 2 GiB; batches for which (M + 256) * K (twice that with fp16 activations) or
+ *     (M + 256) * N * 4 reaches 2 GiB are processed in slabs of rows, one launch per slab.
+ *     mnnq_linear_acc_debug: M up to 65535 and within one such slab.
  *   - Only group == 64 is implemented.  K must be a multiple of 64 and N a
  *     multiple of 16.  `mode` selects the weight quantizer (mnnq_mode); a packed
  *     buffer must be used with the mode it was written with.

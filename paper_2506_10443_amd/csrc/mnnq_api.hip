@@ -59,6 +59,19 @@ bool prefill_fits(int64_t M, int64_t N, int64_t K, int mode = MNNQ_W4_ZP_INT, in
            (int64_t)make_layout(N, K, mode).total() <= lim && (M + 256) * N * 4 <= lim;
 }
 
+// Batches beyond what prefill_fits allows are processed in slabs of this many rows (a multiple of
+// 256, so every slab starts on a 16-byte boundary of x and y), one launch each; 0 if even the packed
+// matrix or a single slab is out of reach of the 32-bit offsets.
+int64_t prefill_slab_rows(int64_t N, int64_t K, int mode, int act_bytes = 1)
+{
+    const int64_t lim = ((int64_t)1 << 31) - 1;
+    if ((int64_t)make_layout(N, K, mode).total() > lim) return 0;
+    int64_t rows = lim / (K * act_bytes) < lim / (N * 4) ? lim / (K * act_bytes) : lim / (N * 4);
+    rows = (rows - 256) / 256 * 256;
+    if (rows > ((int64_t)1 << 24)) rows = (int64_t)1 << 24;
+    return rows >= 256 ? rows : 0;
+}
+
 Layout layout_for(int64_t N, int64_t K, int mode, bool out16)
 {
     Layout L = make_layout(N, K, mode);
@@ -86,11 +99,22 @@ int prefill_impl(const void* packed, int64_t M, int64_t N, int64_t K, int group,
     if (!packed || !xq || !sx || !y) return MNNQ_ERR_NULL;
     if (M <= 0) return MNNQ_ERR_SHAPE;
     if (int s = check_shape(N, K, group, mode)) return s;
-    if (!prefill_fits(M, N, K, mode)) return MNNQ_ERR_UNSUPPORTED;
+    const int64_t slab = prefill_fits(M, N, K, mode) ? M : prefill_slab_rows(N, K, mode);
+    if (slab <= 0) return MNNQ_ERR_UNSUPPORTED;
     if (misaligned(packed) || misaligned(xq) || misaligned(y) || misaligned(bias) || misaligned(workspace))
         return MNNQ_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(sx) & 3u) return MNNQ_ERR_ALIGN;
     const Layout L = layout_for(N, K, mode, out16);
+    if (slab < M) {   // a batch too large for one launch: slab by slab
+        for (int64_t m0 = 0; m0 < M; m0 += slab) {
+            const int64_t rows = M - m0 < slab ? M - m0 : slab;
+            void* ys = static_cast<uint8_t*>(y) + (size_t)m0 * N * (out16 ? 2 : 4);
+            if (int s = prefill_impl(packed, rows, N, K, group, mode, xq + m0 * K, sx + m0, bias, ys, out16, workspace,
+                                     stream))
+                return s;
+        }
+        return MNNQ_OK;
+    }
     // A few tokens (batched or speculative decoding) are still memory-bound: one pass over the
     // weights in the GEMV's streaming order, all tokens at once in the matrix cores.
     if (M <= 16 && !getenv("MNNQ_NO_SKINNY"))
@@ -118,9 +142,20 @@ int prefill_f16_impl(const void* packed, int64_t M, int64_t N, int64_t K, int gr
     if (!packed || !x16 || !y) return MNNQ_ERR_NULL;
     if (M <= 0) return MNNQ_ERR_SHAPE;
     if (int s = check_shape(N, K, group, mode)) return s;
-    if (!prefill_fits(M, N, K, mode, 2)) return MNNQ_ERR_UNSUPPORTED;   // byte offsets of fp16 rows
+    const int64_t slab = prefill_fits(M, N, K, mode, 2) ? M : prefill_slab_rows(N, K, mode, 2);   // byte offsets of fp16 rows
+    if (slab <= 0) return MNNQ_ERR_UNSUPPORTED;
     if (misaligned(packed) || misaligned(x16) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(row_scale) & 3u) return MNNQ_ERR_ALIGN;
+    if (slab < M) {
+        for (int64_t m0 = 0; m0 < M; m0 += slab) {
+            const int64_t rows = M - m0 < slab ? M - m0 : slab;
+            void* ys = static_cast<uint8_t*>(y) + (size_t)m0 * N * (out16 ? 2 : 4);
+            if (int s = prefill_f16_impl(packed, rows, N, K, group, mode, x16 + m0 * K, row_scale ? row_scale + m0 : nullptr,
+                                         bias, ys, out16, stream))
+                return s;
+        }
+        return MNNQ_OK;
+    }
     return launch_prefill_f16(static_cast<const uint8_t*>(packed), layout_for(N, K, mode, out16), M, x16, row_scale,
                               bias, static_cast<float*>(y), static_cast<hipStream_t>(stream));
 }
@@ -154,7 +189,7 @@ int prefill_fused_impl(const void* packed, int64_t M, int64_t N, int64_t K, int 
     if (!packed || !x || !y || !workspace) return MNNQ_ERR_NULL;
     if (M <= 0) return MNNQ_ERR_SHAPE;
     if (int s = check_shape(N, K, group, mode)) return s;
-    if (!prefill_fits(M, N, K, mode)) return MNNQ_ERR_UNSUPPORTED;
+    if (!prefill_fits(M, N, K, mode) && prefill_slab_rows(N, K, mode) <= 0) return MNNQ_ERR_UNSUPPORTED;
     if (workspace_bytes < fused_prefill_ws_bytes(M, K)) return MNNQ_ERR_SIZE;
     if (misaligned(x) || misaligned(workspace)) return MNNQ_ERR_ALIGN;
     int8_t* xq = static_cast<int8_t*>(workspace);
@@ -343,8 +378,9 @@ int mnnq_plan_debug(int what, int64_t M, int64_t N, int64_t K, int group, int mo
     if (int s = check_shape(N, K, group, mode)) return s;
     const Layout L = make_layout(N, K, mode);
     if (what == 0) {
-        if (!prefill_fits(M, N, K, mode)) return MNNQ_ERR_UNSUPPORTED;
-        describe_prefill(L, M, out8);
+        const int64_t slab = prefill_fits(M, N, K, mode) ? M : prefill_slab_rows(N, K, mode);
+        if (slab <= 0) return MNNQ_ERR_UNSUPPORTED;
+        describe_prefill(L, slab < M ? slab : M, out8);   // (of the first slab, for batches beyond one launch)
     } else {
         if (L.K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
         describe_decode(L, what == 2, out8);

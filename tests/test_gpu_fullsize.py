@@ -183,3 +183,35 @@ def test_qwen2_7b_other_weight_forms(form, name):
     yf = B.mnnq_linear_decode_fused(packed, N, K, dev(x[0]), mode=mode).cpu().numpy()
     assert np.abs(yf - y0).max() <= tol0
     assert np.abs(y[0] - y0).max() <= tol0
+
+
+def test_batch_beyond_one_launch_is_processed_in_slabs():
+    """(M + 256) * N * 4 bytes of output beyond 2 GiB: the call runs slab by slab (32512 rows here);
+    sampled outputs, with rows on both sides of the slab boundary and the last row."""
+    M, N, K = 40000, 16384, 64
+    note("slabs", M, N, K)
+    W = synth.weights(N, K, 91)
+    x = synth.activations(M, K, 92, outliers=False)
+    q, s, z = oracle.quant_weights(W)
+    xq_o, sx_o, _ = oracle.quant_act(x)
+    packed = B.mnnq_pack_weights(dev(W))
+    bias = synth.weights(1, N, 93)[0] * 10
+    y = B.mnnq_linear_prefill(packed, N, K, dev(xq_o), dev(sx_o), bias=dev(bias))
+    rng = np.random.default_rng(94)
+    ms = np.concatenate([rng.integers(0, M, 4096), [0, 32511, 32511, 32512, 32512, M - 1, M - 1]])
+    ns = np.concatenate([rng.integers(0, N, 4096), [0, 0, N - 1, 0, N - 1, 0, N - 1]])
+    got = y[torch.from_numpy(ms).to("cuda:0"), torch.from_numpy(ns).to("cuda:0")].cpu().numpy()
+    _, y_s = oracle.linear_w4a8_sampled(xq_o, sx_o, q, s, z, ms, ns, bias=bias, want_acc=False)
+    assert np.abs(got - y_s).max() <= 1e-5 * np.abs(y_s).max()
+    del y
+    # the fused call and the fp16-activation call take the same route
+    ws = torch.empty(B.mnnq_workspace_size(M, N, K), dtype=torch.uint8, device="cuda:0")
+    yf = B.mnnq_linear_prefill_fused(packed, N, K, dev(x), bias=dev(bias), workspace=ws)
+    got = yf[torch.from_numpy(ms).to("cuda:0"), torch.from_numpy(ns).to("cuda:0")].cpu().numpy()
+    assert np.abs(got - y_s).max() <= 1e-5 * np.abs(y_s).max()
+    del yf, ws
+    x16 = x.astype(np.float16)
+    y16 = B.mnnq_linear_prefill_f16(packed, N, K, dev(x16), bias=dev(bias))
+    got = y16[torch.from_numpy(ms).to("cuda:0"), torch.from_numpy(ns).to("cuda:0")].cpu().numpy()
+    y_s16 = oracle.linear_w4a16_sampled(x16, q, s, z, ms, ns, bias=bias)
+    assert np.abs(got - y_s16).max() <= 1e-3 * np.abs(y_s16).max()
