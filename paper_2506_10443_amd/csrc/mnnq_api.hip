@@ -16,9 +16,9 @@ int record_hip_error(hipError_t e)
 
 namespace {
 
-constexpr int64_t kMaxDecodeK = 49152;     // int8 row + block sums in LDS: 160 B per 128 k, under 64 KiB
-constexpr int64_t kMaxDecodeKF16 = 30720;  // fp16 row in LDS: 256 B per 128 k, under 64 KiB
-constexpr int64_t kMaxDecodeKF16Min = 27648;  // float minimum form: 32 B of block sums more per 128 k
+constexpr int64_t kMaxDecodeK = 126976;    // int8 row + block sums in LDS: 160 B per 128 k, under 160 KiB
+constexpr int64_t kMaxDecodeKF16 = 80640;  // fp16 row in LDS: 256 B per 128 k, under 160 KiB
+constexpr int64_t kMaxDecodeKF16Min = 71680;  // float minimum form: 32 B of block sums more per 128 k
 constexpr int64_t kMaxM = 65535;
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }

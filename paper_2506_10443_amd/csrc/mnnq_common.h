@@ -169,6 +169,27 @@ int launch_prefill_f16(const uint8_t* packed, const Layout& L, int64_t M, const 
 // Compute units of the current device (cached per thread and device).
 int num_cus();
 
+// LDS of a workgroup on gfx950, and the amount a kernel may use without asking.
+constexpr size_t kLdsPerWorkgroup = 160 * 1024;
+constexpr size_t kLdsDefault = 64 * 1024;
+
+// Allows `kern` more than 64 KiB of dynamic LDS (needed once per kernel and device; remembered per
+// thread in `allowed_dev`, which starts at -1).  Returns a status.
+template <typename Kernel>
+int allow_large_lds(Kernel kern, size_t bytes, int& allowed_dev)
+{
+    if (bytes <= kLdsDefault) return MNNQ_OK;
+    if (bytes > kLdsPerWorkgroup) return MNNQ_ERR_UNSUPPORTED;
+    int dev = 0;
+    MNNQ_HIP_TRY(hipGetDevice(&dev));
+    if (allowed_dev != dev) {
+        MNNQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)kLdsPerWorkgroup));
+        allowed_dev = dev;
+    }
+    return MNNQ_OK;
+}
+
 // Launch configuration the launchers above would choose (host logic only, nothing is launched).
 // prefill: {tile rows, tile columns, K parts in the workgroup, K split over workgroups, waves per
 // workgroup, LDS bytes, workgroups, 1 if the nibble planes of int8 weights are merged};

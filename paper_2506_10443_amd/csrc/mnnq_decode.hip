@@ -339,15 +339,19 @@ int launch_cfg(const uint8_t* packed, const Layout& L, int64_t M, const void* xi
     const int64_t blocks = (L.T + tiles_per_wg - 1) / tiles_per_wg;
     const int PW = (int)((L.C + KSPLIT - 1) / KSPLIT);
     const size_t smem = (MODE == kFused ? (size_t)L.C * 160 : (size_t)WAVES * PW * 160) + WAVES * 17 * sizeof(float);
-    if (smem > 64 * 1024) return MNNQ_ERR_UNSUPPORTED;   // only reachable with a forced split
-    if (L.minf)
-        hipLaunchKernelGGL((decode_kernel<WAVES, KSPLIT, UNROLL, MODE, PREFETCH, true>),
-                           dim3((unsigned)blocks, (unsigned)M), dim3(WAVES * 64), smem, st, packed, L, xin, sx, bias,
-                           y, acc, PW);
-    else
-        hipLaunchKernelGGL((decode_kernel<WAVES, KSPLIT, UNROLL, MODE, PREFETCH, false>),
-                           dim3((unsigned)blocks, (unsigned)M), dim3(WAVES * 64), smem, st, packed, L, xin, sx, bias,
-                           y, acc, PW);
+    // Rows beyond about 50000 values need more than the 64 KiB of LDS a kernel gets by default.
+    static thread_local int allowed_minf = -1, allowed_zp = -1;
+    if (L.minf) {
+        auto kern = decode_kernel<WAVES, KSPLIT, UNROLL, MODE, PREFETCH, true>;
+        if (int s = allow_large_lds(kern, smem, allowed_minf)) return s;
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks, (unsigned)M), dim3(WAVES * 64), smem, st, packed, L, xin, sx,
+                           bias, y, acc, PW);
+    } else {
+        auto kern = decode_kernel<WAVES, KSPLIT, UNROLL, MODE, PREFETCH, false>;
+        if (int s = allow_large_lds(kern, smem, allowed_zp)) return s;
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks, (unsigned)M), dim3(WAVES * 64), smem, st, packed, L, xin, sx,
+                           bias, y, acc, PW);
+    }
     MNNQ_HIP_TRY(hipGetLastError());
     return MNNQ_OK;
 }

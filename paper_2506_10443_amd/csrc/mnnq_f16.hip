@@ -241,13 +241,17 @@ int launch_decode_cfg(const uint8_t* packed, const Layout& L, const uint16_t* x1
     const int64_t blocks = (L.T + tiles_per_wg - 1) / tiles_per_wg;
     const int PW = (int)((L.C + KSPLIT - 1) / KSPLIT);
     const size_t smem = (size_t)WAVES * PW * (L.minf ? 256 + 32 : 256) + WAVES * 16 * sizeof(float);
-    if (smem > 64 * 1024) return MNNQ_ERR_UNSUPPORTED;   // only reachable with a forced split
-    if (L.minf)
-        hipLaunchKernelGGL((decode_f16_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, true>), dim3((unsigned)blocks),
-                           dim3(WAVES * 64), smem, st, packed, L, x16, bias, y, PW);
-    else
-        hipLaunchKernelGGL((decode_f16_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, false>), dim3((unsigned)blocks),
-                           dim3(WAVES * 64), smem, st, packed, L, x16, bias, y, PW);
+    // Rows beyond about 30000 values need more than the 64 KiB of LDS a kernel gets by default.
+    static thread_local int allowed_minf = -1, allowed_zp = -1;
+    if (L.minf) {
+        auto kern = decode_f16_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, true>;
+        if (int s = allow_large_lds(kern, smem, allowed_minf)) return s;
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(WAVES * 64), smem, st, packed, L, x16, bias, y, PW);
+    } else {
+        auto kern = decode_f16_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, false>;
+        if (int s = allow_large_lds(kern, smem, allowed_zp)) return s;
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(WAVES * 64), smem, st, packed, L, x16, bias, y, PW);
+    }
     MNNQ_HIP_TRY(hipGetLastError());
     return MNNQ_OK;
 }

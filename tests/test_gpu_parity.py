@@ -486,3 +486,34 @@ def test_w4a16_one_hot_exact_weights():
         np.testing.assert_allclose(y, what[:, j], rtol=1e-6, atol=0)
         y = host(B.mnnq_linear_prefill_f16(packed, N, K, dev(x16)))
         np.testing.assert_allclose(y[0], what[:, j], rtol=1e-6, atol=0)
+
+
+@pytest.mark.parametrize("K", [53248, 126976])
+def test_decode_rows_beyond_64k_of_lds(K):
+    """Rows whose int8 image needs more than the default 64 KiB of LDS (e.g. K = 53248, the down projection
+    of a 405B-class model): plain and fused GEMV, a few tokens, the accumulators and the fp16-activation GEMV."""
+    N, M = 144, 3
+    note("long rows", N, K)
+    W, x, q, s, z, xq, sx = _layer(N, K, M, 1300 + K)
+    acc_o, y_o = oracle.linear_w4a8(xq, sx, q, s, z)
+    tol = TOL_A8 * np.abs(y_o).max()
+    packed = B.mnnq_pack_weights(dev(W))
+    xqd, sxd = dev(xq), dev(sx)
+    y0 = host(B.mnnq_linear_decode(packed, N, K, xqd[0].contiguous(), sxd[:1].contiguous()))
+    assert np.abs(y0 - y_o[0]).max() <= tol
+    yf = host(B.mnnq_linear_decode_fused(packed, N, K, dev(x[0])))
+    assert np.abs(yf - y_o[0]).max() <= tol
+    ws = torch.empty(B.mnnq_workspace_size(1, N, K), dtype=torch.uint8, device="cuda:0")
+    yw = host(B.mnnq_linear_decode_fused(packed, N, K, dev(x[0]), workspace=ws))
+    assert np.abs(yw - y_o[0]).max() <= tol
+    assert np.array_equal(host(B.mnnq_linear_acc_debug(packed, N, K, xqd, False)), acc_o)
+    ys = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd))          # few tokens: the streaming kernel
+    assert np.abs(ys - y_o).max() <= tol
+    if K <= 80640:
+        x16 = x.astype(np.float16)
+        y16_o = oracle.linear_w4a16(x16, q, s, z)
+        y16 = host(B.mnnq_linear_decode_f16(packed, N, K, dev(x16[0])))
+        assert np.abs(y16 - y16_o[0]).max() <= TOL_A16 * np.abs(y16_o).max()
+    else:
+        with pytest.raises(B.MnnqError):
+            B.mnnq_linear_decode_f16(packed, N, K, dev(x.astype(np.float16)[0]))

@@ -1,6 +1,6 @@
 """Host logic of the launchers, checked without a GPU through mnnq_plan_debug: for every layer shape of
 the benchmark models the chosen kernel configuration fits the hardware limits the kernels assume
-(1024 threads, 160 KiB of LDS per workgroup for the GEMM, 64 KiB for the GEMV), covers the whole
+(1024 threads, 160 KiB of LDS per workgroup), covers the whole
 problem, and is the one the design documents for the Qwen2-7B shapes.  Nothing is launched."""
 import os
 
@@ -8,7 +8,7 @@ import pytest
 
 from paper_2506_10443_amd import binding as B, synth
 
-LDS_GEMM, LDS_GEMV = 160 * 1024, 64 * 1024
+LDS_GEMM, LDS_GEMV = 160 * 1024, 160 * 1024
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -54,7 +54,7 @@ def test_decode_plan_fits_and_covers(model, name, M, N, K, mode):
     chunks = -(-(K * (2 if mode == B.MODE_W8_MIN_FLOAT else 1)) // 128)
     tiles = N // 16
     for what in (1, 2):
-        if chunks * 128 > 49152:
+        if chunks * 128 > 126976:
             with pytest.raises(B.MnnqError):
                 B.mnnq_plan_debug(what, 1, N, K, mode)
             continue
@@ -96,4 +96,5 @@ def test_switches_and_errors():
     assert L.mnnq_plan_debug(3, 4, 16, 128, 64, 0, p) == -3
     assert L.mnnq_plan_debug(0, 0, 16, 128, 64, 0, p) == -2
     assert L.mnnq_plan_debug(1, 1, 16, 100, 64, 0, p) == -2
-    assert L.mnnq_plan_debug(1, 1, 16, 65536, 64, 0, p) == -3     # longer than the GEMV stages in LDS
+    assert L.mnnq_plan_debug(1, 1, 16, 131072, 64, 0, p) == -3    # longer than the GEMV stages in LDS
+    assert L.mnnq_plan_debug(1, 1, 16, 53248, 64, 0, p) == 0 and out[4] > 64 * 1024 and out[4] <= 160 * 1024
