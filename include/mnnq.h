@@ -14,6 +14,9 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work; buffers must stay valid until the stream has
  *     passed that work.
+ *   - Stream capture: the calls enqueue kernels only (no memset or copy nodes) and can be recorded
+ *     into a HIP graph.  The first call of a kernel variant on a device may also set a function
+ *     attribute (more than 64 KiB of LDS), so run a call once outside the capture before recording it.
  *   - Return value: MNNQ_OK (0) or a negative mnnq_status.  All argument
  *     checks run before the first HIP call, so they also work on a machine
  *     without a GPU.  NaN / Inf in W or x: undefined result, no error.
