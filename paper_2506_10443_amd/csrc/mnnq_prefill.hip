@@ -92,7 +92,8 @@ struct Lds {
     static constexpr int B2_OFF = B_OFF + NT16 * 1024;   // W8: [NT16][1024] codes of the low nibble plane
     static constexpr int S_OFF = B2_OFF + (W8 ? NT16 * 1024 : 0);   // [NT16][16][2] fp32 scales
     static constexpr int Z_OFF = S_OFF + NT16 * 128;     // [NT16][16][2] u8 zeros, or fp32 group minima (MINF)
-    static constexpr int BYTES = Z_OFF + NT16 * (MINF ? 128 : 32);
+    // (the zero points arrive with one load of 8 x 32 B whatever NT16 is: lanes past the tile bring zeros)
+    static constexpr int BYTES = Z_OFF + (MINF ? NT16 * 128 : 8 * 32);
 };
 
 // Work distribution: one workgroup per output tile and K split.  Shapes with few
@@ -125,7 +126,8 @@ __global__ __launch_bounds__(128 * WNW * KS, (ACC || KS > 1) ? 1 : 2) void prefi
     constexpr int NT16 = St::NT16;
     constexpr int A_INSTR = BM / 8 / WPK;        // 1 KiB direct loads of A per wave and stage
     constexpr int B_INSTR = NT16 / WPK;          // row tiles of B codes per wave and stage
-    static_assert(NT16 == 8, "B side is written for 8 row tiles per workgroup");
+    static_assert(NT16 == 8 || NT16 == 4, "B side: 8 row tiles per workgroup, or 4 (64-column tiles for few tokens)");
+    static_assert(NT16 % WPK == 0 && (NT16 == 8 || (!ACC && !W8)), "64-column tiles: plain GEMM, four waves per K part");
     static_assert(WNW == 2 || WNW == 4, "four or eight waves per K part");
     static_assert(KS == 1 || WPK * TM * TN * 4 * 64 * 4 <= KS * St::BYTES, "the K parts' sums must fit in LDS");
     static_assert(KS == 1 || !ACC, "the accumulator dump runs unsplit");
@@ -177,7 +179,8 @@ __global__ __launch_bounds__(128 * WNW * KS, (ACC || KS > 1) ? 1 : 2) void prefi
     const int a_voff = (lane >> 3) * K + (((lane & 7) ^ (lane >> 3)) << 4);
     const int b_voff = lane * 16;
     const int s_voff = (lane >> 5) * C * 128 + (lane & 31) * 4;
-    const int z_voff = (lane >> 3) * C * 32 + (lane & 7) * 4;
+    // (lanes past the tile's row tiles are sent out of the buffer's range and bring zeros)
+    const int z_voff = (lane >> 3) < NT16 ? (lane >> 3) * C * 32 + (lane & 7) * 4 : 0x7ffffff0;
     const int scales_off = (int)L.scales_off();
     const int zeros_off = (int)L.zeros_off();
 
@@ -210,11 +213,11 @@ __global__ __launch_bounds__(128 * WNW * KS, (ACC || KS > 1) ? 1 : 2) void prefi
             }
             // Scales: one load covers two row tiles (2 x 128 B), four loads in all; zeros: one load covers
             // all eight row tiles (8 x 32 B).  (wave is uniform: these are scalar branches.)
-            if (WPK == 4 || wave < 4)
+            if ((WPK == 4 && NT16 == 8) || wave < NT16 / 2)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::S_OFF + wave * 256), 4, s_voff,
                                                          uniform(scales_off + ((rt0 + wave * 2) * C + c) * 128), 0, 0);
             if (MINF) {   // group minima: fp32, laid out like the scales
-                if (WPK == 4 || wave < 4)
+                if ((WPK == 4 && NT16 == 8) || wave < NT16 / 2)
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::Z_OFF + wave * 256), 4, s_voff,
                                                              uniform(zeros_off + ((rt0 + wave * 2) * C + c) * 128), 0, 0);
             } else if (wave == 0)
@@ -584,12 +587,13 @@ struct TilePlan {
     int KS;
     int S;
     bool wide;   // 256-row tile worked on by eight waves (128 x 32 outputs each), two workgroups per CU
-    bool tiny;   // 64-row tile (at most 64 tokens): the call is bound by the weight stream, not by the MFMAs
+    bool tiny;   // 64-row tile (few tokens): the call is bound by the weight stream, not by the MFMAs
+    bool narrow; // ... of 64 columns: twice the workgroups for layers with few output columns
 };
 
 TilePlan plan_tiles(const Layout& L, int64_t M)
 {
-    TilePlan p{true, 1, 1, false, false};
+    TilePlan p{true, 1, 1, false, false, false};
     const int64_t cus = num_cus();
     auto tiles = [&](int bm) { return ((M + bm - 1) / bm) * ((L.N + 127) / 128); };
     if (M <= 128 && L.mode != MNNQ_W8_MIN_FLOAT) {
@@ -598,7 +602,11 @@ TilePlan plan_tiles(const Layout& L, int64_t M)
         // there are keep many loads in flight, and long rows are also cut in two.
         p.big = false;
         p.tiny = true;
-        const int64_t t = tiles(64);
+        int64_t t = tiles(64);
+        if (2 * t <= cus) {      // few output columns: 64-column tiles double the workgroups
+            p.narrow = true;
+            t *= 2;
+        }
         p.KS = t >= cus ? 1 : (2 * t >= cus ? 2 : 4);
         if (4 * t <= cus && L.C >= 64) p.S = 2;
     } else if (M > 128 && tiles(256) >= 2 * cus) {
@@ -620,9 +628,10 @@ TilePlan plan_tiles(const Layout& L, int64_t M)
     }
     if (const char* e = getenv("MNNQ_PREFILL_TILE")) {   // tuning and tests: "b"/"s", split digit, "k" = K parts
         if (e[0] == 'b' || e[0] == 'w') p.big = true;
-        if (e[0] == 's' || e[0] == 'v' || e[0] == 't') p.big = false;
+        if (e[0] == 's' || e[0] == 'v' || e[0] == 't' || e[0] == 'n') p.big = false;
         p.wide = (e[0] == 'w' || e[0] == 'v');     // "w"/"v" = "b"/"s" worked on by twice the waves
-        p.tiny = (e[0] == 't') && L.mode != MNNQ_W8_MIN_FLOAT;   // "t" = 64-row tile; "k" / "q" = 2 / 4 K parts
+        p.tiny = (e[0] == 't' || e[0] == 'n') && L.mode != MNNQ_W8_MIN_FLOAT;   // "t" = 64-row tile; "k" / "q" = 2 / 4 K parts
+        p.narrow = p.tiny && e[0] == 'n';                                        // "n" = 64 x 64 tile
         if (e[0] && (e[1] == '1' || e[1] == '2' || e[1] == '4')) {
             p.S = e[1] - '0';
             p.KS = (e[2] == 'k') ? 2 : ((e[2] == 'q' && p.tiny) ? 4 : 1);
@@ -654,6 +663,7 @@ namespace {
 struct PrefillLaunch {
     int BM, KS, S, WNW;
     bool w8;
+    int BN;
 };
 
 PrefillLaunch resolve_prefill(const Layout& L, int64_t M)
@@ -661,7 +671,7 @@ PrefillLaunch resolve_prefill(const Layout& L, int64_t M)
     TilePlan p = plan_tiles(L, M);
     if (L.out16) p.S = 1;   // the split over two workgroups adds fp32 partial sums in the output array
     const bool forced_plan = getenv("MNNQ_PREFILL_TILE") != nullptr;
-    PrefillLaunch r{p.big ? 256 : (p.tiny ? 64 : 128), p.KS, p.S, 2, false};
+    PrefillLaunch r{p.big ? 256 : (p.tiny ? 64 : 128), p.KS, p.S, 2, false, p.narrow ? 64 : 128};
     // 8-bit weights: both nibble planes of a chunk in one MFMA (128-row tiles: two B tiles need the LDS
     // of the larger A tile).  MNNQ_W8_PLANES=1 (tests, comparisons) keeps one MFMA per plane instead.
     const char* planes = getenv("MNNQ_W8_PLANES");
@@ -686,10 +696,12 @@ PrefillLaunch resolve_prefill(const Layout& L, int64_t M)
 
 static_assert(Lds<256, 128, false>::BYTES == 2 * 256 * 128 + 8 * 1024 + 8 * 128 + 8 * 32, "prefill_lds_bytes");
 static_assert(Lds<128, 128, true, true>::BYTES == 2 * 128 * 128 + 16 * 1024 + 8 * 128 + 8 * 128, "prefill_lds_bytes");
+static_assert(Lds<64, 64, false>::BYTES == 2 * 64 * 128 + 4 * 1024 + 4 * 128 + 8 * 32, "prefill_lds_bytes");
 
 size_t prefill_lds_bytes(const PrefillLaunch& r, bool minf)
 {
-    return (size_t)r.KS * (2 * r.BM * 128 + 8 * 1024 * (r.w8 ? 2 : 1) + 8 * 128 + 8 * (minf ? 128 : 32));
+    const int nt16 = r.BN / 16;
+    return (size_t)r.KS * (2 * r.BM * 128 + nt16 * 1024 * (r.w8 ? 2 : 1) + nt16 * 128 + (minf ? nt16 * 128 : 8 * 32));
 }
 
 }  // namespace
@@ -697,9 +709,9 @@ size_t prefill_lds_bytes(const PrefillLaunch& r, bool minf)
 void describe_prefill(const Layout& L, int64_t M, int32_t out[8])
 {
     const PrefillLaunch r = resolve_prefill(L, M);
-    const int64_t MT = (M + r.BM - 1) / r.BM, NT = (L.N + 127) / 128;
+    const int64_t MT = (M + r.BM - 1) / r.BM, NT = (L.N + r.BN - 1) / r.BN;
     out[0] = r.BM;
-    out[1] = 128;
+    out[1] = r.BN;
     out[2] = r.KS;
     out[3] = r.S;
     out[4] = 2 * r.WNW * r.KS;                                   // waves per workgroup
@@ -728,6 +740,11 @@ int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8
         if (r.BM == 256) return launch_wide<256, 2>(packed, L, M, xq, sx, bias, y, r.S, st);
         if (r.KS == 2) return launch_wide<128, 2>(packed, L, M, xq, sx, bias, y, r.S, st);
         return launch_wide<128, 1>(packed, L, M, xq, sx, bias, y, r.S, st);
+    }
+    if (r.BM == 64 && r.BN == 64) {
+        if (r.KS == 4) return launch_tiles<64, 64, 4, false>(MNNQ_ARGS);
+        if (r.KS == 2) return launch_tiles<64, 64, 2, false>(MNNQ_ARGS);
+        return launch_tiles<64, 64, 1, false>(MNNQ_ARGS);
     }
     if (r.BM == 64) {
         if (r.KS == 4) return launch_tiles<64, 128, 4, false>(MNNQ_ARGS);

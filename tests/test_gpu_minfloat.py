@@ -75,7 +75,7 @@ def test_linear_matches_oracle(M, N, K):
     assert np.abs(y - y_o).max() <= tol, (np.abs(y - y_o).max(), tol)
     os.environ["MNNQ_NO_SKINNY"] = "1"     # M <= 16 would otherwise bypass the tiled kernel
     try:
-        for cfg in ("b1", "s1", "b1k", "s1k", "s2", "b2k", "w1", "w2", "v1k", "v2k", "w1k", "t1", "t1k", "t2q"):
+        for cfg in ("b1", "s1", "b1k", "s1k", "s2", "b2k", "w1", "w2", "v1k", "v2k", "w1k", "t1", "t1k", "t2q", "n1", "n2q"):
             os.environ["MNNQ_PREFILL_TILE"] = cfg
             try:
                 y2 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd, mode=MINF))

@@ -50,7 +50,7 @@ def test_w4a8_out16(M, N, K):
     y_o = oracle.linear_w4a8(xq, sx, q, s, z, bias=bias, want_acc=False)[1]
     packed = B.mnnq_pack_weights(dev(W))
     xqd, sxd, bd = dev(xq), dev(sx), dev(bias)
-    for cfg in ("", "b1", "s1", "b1k", "s1k", "w1", "v1k", "w1k", "t1", "t1q"):
+    for cfg in ("", "b1", "s1", "b1k", "s1k", "w1", "v1k", "w1k", "t1", "t1q", "n1", "n1q"):
         if cfg:
             os.environ["MNNQ_PREFILL_TILE"] = cfg
             os.environ["MNNQ_NO_SKINNY"] = "1"

@@ -292,7 +292,7 @@ def test_prefill_matches_oracle(M, N, K):
     y2 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=dev(bias)))
     assert np.array_equal(y, y2)
     # every tile / split choice gives the same result to the same tolerance
-    for cfg in ("b1", "b2", "s1", "s2", "b1k", "s1k", "b2k", "s2k", "w1", "w2", "v1k", "v2k", "w1k", "w2k", "t1", "t2", "t1k", "t1q", "t2q"):
+    for cfg in ("b1", "b2", "s1", "s2", "b1k", "s1k", "b2k", "s2k", "w1", "w2", "v1k", "v2k", "w1k", "w2k", "t1", "t2", "t1k", "t1q", "t2q", "n1", "n2", "n1k", "n1q", "n2q"):
         os.environ["MNNQ_PREFILL_TILE"] = cfg
         try:
             y3 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=dev(bias)))

@@ -36,7 +36,7 @@ def shapes():
 def test_prefill_plan_fits_and_covers(model, name, M, N, K, mode):
     for m in sorted({M, 17, 129, 300}):
         bm, bn, ks, s, waves, lds, wgs, merged = B.mnnq_plan_debug(0, m, N, K, mode)
-        assert (bm, bn) in ((64, 128), (128, 128), (256, 128)) and ks in (1, 2, 4) and s in (1, 2)
+        assert (bm, bn) in ((64, 64), (64, 128), (128, 128), (256, 128)) and ks in (1, 2, 4) and s in (1, 2)
         assert (bm == 64) == (m <= 128 and not merged) and (ks < 4 or bm == 64)
         assert waves in (4, 8, 16) and waves * 64 <= 1024 and waves % ks == 0
         assert lds <= LDS_GEMM
