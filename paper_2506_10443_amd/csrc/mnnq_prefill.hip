@@ -596,18 +596,20 @@ TilePlan plan_tiles(const Layout& L, int64_t M)
     TilePlan p{true, 1, 1, false, false, false};
     const int64_t cus = num_cus();
     auto tiles = [&](int bm) { return ((M + bm - 1) / bm) * ((L.N + 127) / 128); };
-    if (M <= 128 && L.mode != MNNQ_W8_MIN_FLOAT) {
+    if (M <= 128 && L.mode != MNNQ_W8_MIN_FLOAT && !(M > 64 && tiles(128) >= 4 * cus)) {
         // Up to 128 tokens (batched decoding): 64-row tiles, a quarter of the MFMAs of a 128-row tile
-        // per chunk; the K range goes to 1, 2 or 4 parts of four waves so that the few workgroups
-        // there are keep many loads in flight, and long rows are also cut in two.
+        // per chunk.  Such a call is bound by stalls, not by the MFMAs, and runs the faster the more
+        // waves a CU holds: 64-column tiles (twice the workgroups, of 21 KiB of LDS each) unless there
+        // are very many tiles, the K range in 1, 2 or 4 parts of four waves, and long rows also cut in
+        // two.  (Beyond 64 tokens and with that many tiles, 128-row tiles are faster: the plans below.)
         p.big = false;
         p.tiny = true;
         int64_t t = tiles(64);
-        if (2 * t <= cus) {      // few output columns: 64-column tiles double the workgroups
+        if (t < 4 * cus) {
             p.narrow = true;
             t *= 2;
         }
-        p.KS = t >= cus ? 1 : (2 * t >= cus ? 2 : 4);
+        p.KS = t >= 4 * cus ? 1 : (2 * t >= cus ? 2 : 4);
         if (4 * t <= cus && L.C >= 64) p.S = 2;
     } else if (M > 128 && tiles(256) >= 2 * cus) {
         p.big = true;

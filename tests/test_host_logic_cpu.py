@@ -34,10 +34,11 @@ def shapes():
 @pytest.mark.parametrize("mode", [B.MODE_W4_ZP_INT, B.MODE_W4_MIN_FLOAT, B.MODE_W8_MIN_FLOAT])
 @pytest.mark.parametrize("model,name,M,N,K", shapes())
 def test_prefill_plan_fits_and_covers(model, name, M, N, K, mode):
-    for m in sorted({M, 17, 129, 300}):
+    for m in sorted({M, 17, 100, 129, 300}):
         bm, bn, ks, s, waves, lds, wgs, merged = B.mnnq_plan_debug(0, m, N, K, mode)
         assert (bm, bn) in ((64, 64), (64, 128), (128, 128), (256, 128)) and ks in (1, 2, 4) and s in (1, 2)
-        assert (bm == 64) == (m <= 128 and not merged) and (ks < 4 or bm == 64)
+        assert (bm == 64) == (m <= 128 and not merged and not (m > 64 and -(-N // 128) >= 1024))
+        assert ks < 4 or bm == 64
         assert waves in (4, 8, 16) and waves * 64 <= 1024 and waves % ks == 0
         assert lds <= LDS_GEMM
         if waves // ks == 4:
@@ -75,6 +76,19 @@ def test_documented_plans_of_the_qwen2_7b_block():
     assert B.mnnq_plan_debug(1, 1, 37888, 3584)[:4] == [4, 4, 8, 0]      # GEMV: four waves per row tile, 7 chunks each
     assert B.mnnq_plan_debug(1, 1, 3584, 18944)[:4] == [16, 16, 12, 0]   # 148 chunks over sixteen waves
     assert B.mnnq_plan_debug(2, 1, 4608, 3584)[0] == 8                    # fused quantizer: larger workgroups
+
+
+def test_documented_plans_for_few_tokens():
+    """Batched decoding (17 .. 128 tokens): 64-row tiles, 64 columns wide unless there are very many,
+    the K range in more parts the fewer workgroups there are; very many tiles beyond 64 tokens take
+    128-row tiles."""
+    plan = lambda m, n, k: B.mnnq_plan_debug(0, m, n, k)[:5]
+    assert plan(64, 4608, 3584) == [64, 64, 4, 1, 16]        # q|k|v: 72 workgroups
+    assert plan(64, 3584, 18944) == [64, 64, 4, 2, 16]       # down: long rows cut in two as well
+    assert plan(64, 37888, 3584) == [64, 64, 2, 1, 8]        # gate|up: 592 workgroups, two to three per CU
+    assert plan(128, 37888, 3584) == [64, 64, 1, 1, 4]       # 1184 workgroups of four waves
+    assert plan(64, 152064, 3584) == [64, 128, 1, 1, 4]      # lm_head: 1188 tiles of 64 x 128
+    assert plan(128, 152064, 3584) == [128, 128, 1, 1, 4]    # ... and 128-row tiles beyond 64 tokens
 
 
 def test_switches_and_errors():
