@@ -116,7 +116,14 @@ __device__ __forceinline__ float dot16_f16(uint32_t w0, uint32_t w1, uint32_t z,
 // registers: all weight loads are issued before the activations are touched, and
 // each wave stages only the slice of x it consumes into a private LDS region (no
 // barrier).
-template <int WAVES, int KSPLIT, int UNROLL, bool PREFETCH, bool MINF>
+//
+// EARLY (whole chunk range in registers): the wave's slice of x is requested ahead of the weights
+// and every wave issues all UNROLL chunk loads without a branch, a wave with fewer chunks repeating
+// its first one.  Loads return in order, and only for straight-line code does the compiler count
+// how many younger loads may still be in flight when x is first used (behind conditional loads it
+// waits for the whole weight stream before x is staged).  Used where it pays: small layers, and
+// layers whose waves all have exactly UNROLL chunks.
+template <int WAVES, int KSPLIT, int UNROLL, bool PREFETCH, bool MINF, bool EARLY = false>
 __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* __restrict__ packed, Layout L,
                                                                 const uint16_t* __restrict__ x16,
                                                                 const float* __restrict__ bias,
@@ -140,34 +147,48 @@ __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* _
     const int64_t tile = (int64_t)blockIdx.x * TILES_PER_WG + wave / KSPLIT;
     const int ks = wave % KSPLIT;
     const bool active = tile < L.T;
+    static_assert(!EARLY || !PREFETCH, "EARLY: no prefetch loop");
     const int64_t c0 = C * ks / KSPLIT;
     const int64_t c1 = C * (ks + 1) / KSPLIT;
-    const u32x4* wp = reinterpret_cast<const u32x4*>(packed) + (tile * C + c0) * 64 + lane;
-    const float2* sp = reinterpret_cast<const float2*>(packed + L.scales_off()) + (tile * C + c0) * 16 + row;
-    const void* zp = MINF ? static_cast<const void*>(reinterpret_cast<const float2*>(packed + L.zeros_off()) +
-                                                     (tile * C + c0) * 16 + row)
-                          : static_cast<const void*>(reinterpret_cast<const uint16_t*>(packed + L.zeros_off()) +
-                                                     (tile * C + c0) * 16 + row);
     const int64_t n_chunks = active ? (c1 - c0) : 0;
-
-    ChunkRegs cur[UNROLL];
-#pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
-        if (u < n_chunks) cur[u] = load_chunk<MINF>(wp, sp, zp, u);
-        else cur[u] = ChunkRegs{};
-    }
+    // (EARLY: a wave without chunks - a row tile past the matrix, an empty share of a short row -
+    // points at chunk 0 of the last row tile; what it loads is discarded)
+    const int64_t first = (!EARLY || n_chunks > 0) ? tile * C + c0 : (L.T - 1) * C;
+    const u32x4* wp = reinterpret_cast<const u32x4*>(packed) + first * 64 + lane;
+    const float2* sp = reinterpret_cast<const float2*>(packed + L.scales_off()) + first * 16 + row;
+    const void* zp = MINF ? static_cast<const void*>(reinterpret_cast<const float2*>(packed + L.zeros_off()) +
+                                                     first * 16 + row)
+                          : static_cast<const void*>(reinterpret_cast<const uint16_t*>(packed + L.zeros_off()) +
+                                                     first * 16 + row);
 
     // This wave's slice of x in units of 8 halves (16 B): unit u of the region is unit
     // c0 * 16 + u of the packed reduction axis, which runs over the activation row once
     // (twice for 8-bit codes: one 4-bit plane after the other); units past K are zero.
+    constexpr int XP = (UNROLL * 16 + 63) / 64;
+    const int64_t own = n_chunks * 16;
+    const int64_t valid = L.K / 8;
+    const int64_t row_units = L.Kx / 8;
+    uint4 xv[XP];
+    if (EARLY) {
+#pragma unroll
+        for (int j = 0; j < XP; ++j) {
+            const int64_t u = lane + 64 * j, gu = c0 * 16 + u;
+            const bool ok = u < own && gu < valid;
+            xv[j] = reinterpret_cast<const uint4*>(x16)[ok ? (gu >= row_units ? gu - row_units : gu) : 0];
+            if (!ok) xv[j] = make_uint4(0, 0, 0, 0);
+        }
+    }
+
+    ChunkRegs cur[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        if (EARLY) cur[u] = load_chunk<MINF>(wp, sp, zp, u < n_chunks ? u : 0);
+        else if (u < n_chunks) cur[u] = load_chunk<MINF>(wp, sp, zp, u);
+        else cur[u] = ChunkRegs{};
+    }
+
     {
-        const int64_t own = (c1 - c0) * 16;
-        const int64_t valid = L.K / 8;
-        const int64_t row_units = L.Kx / 8;
-        for (int64_t u = lane; u < own; u += 64) {
-            const int64_t gu = c0 * 16 + u;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (gu < valid) v = reinterpret_cast<const uint4*>(x16)[gu % row_units];
+        auto put = [&](int64_t u, const uint4 v) {
             lds_x[u] = permute8(v);
             if (MINF) {
                 // sum of the 16-element block: its two units sit in neighbouring lanes
@@ -179,6 +200,18 @@ __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* _
                 sum += __shfl_xor(sum, 1, 64);
                 // unit 8 h + 2 kb + e of the chunk -> block [h][kb]
                 if ((u & 1) == 0) lds_xs[(u / 16) * 8 + ((u % 16) / 8) * 4 + ((u % 8) / 2)] = sum;
+            }
+        };
+        if (EARLY) {   // at most UNROLL chunks: all of them were requested above
+#pragma unroll
+            for (int j = 0; j < XP; ++j)
+                if (lane + 64 * j < own) put(lane + 64 * j, xv[j]);
+        } else {
+            for (int64_t u = lane; u < own; u += 64) {
+                const int64_t gu = c0 * 16 + u;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (gu < valid) v = reinterpret_cast<const uint4*>(x16)[gu >= row_units ? gu - row_units : gu];
+                put(u, v);
             }
         }
         // The region is private to the wave; LDS operations of one wave complete in order.
@@ -233,7 +266,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* _
     }
 }
 
-template <int WAVES, int KSPLIT, int UNROLL, bool PREFETCH>
+template <int WAVES, int KSPLIT, int UNROLL, bool PREFETCH, bool EARLY = false>
 int launch_decode_cfg(const uint8_t* packed, const Layout& L, const uint16_t* x16, const float* bias,
                       float* y, hipStream_t st)
 {
@@ -244,11 +277,11 @@ int launch_decode_cfg(const uint8_t* packed, const Layout& L, const uint16_t* x1
     // Rows beyond about 30000 values need more than the 64 KiB of LDS a kernel gets by default.
     static thread_local int allowed_minf = -1, allowed_zp = -1;
     if (L.minf) {
-        auto kern = decode_f16_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, true>;
+        auto kern = decode_f16_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, true, EARLY>;
         if (int s = allow_large_lds(kern, smem, allowed_minf)) return s;
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(WAVES * 64), smem, st, packed, L, x16, bias, y, PW);
     } else {
-        auto kern = decode_f16_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, false>;
+        auto kern = decode_f16_kernel<WAVES, KSPLIT, UNROLL, PREFETCH, false, EARLY>;
         if (int s = allow_large_lds(kern, smem, allowed_zp)) return s;
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(WAVES * 64), smem, st, packed, L, x16, bias, y, PW);
     }
@@ -279,10 +312,20 @@ int launch_decode_f16(const uint8_t* packed, const Layout& L, const uint16_t* x1
             prefetch = pw > unroll;
         }
     }
-#define MNNQ_CFG(W, K, U, P)                      \
-    if (ks == K && unroll == U && prefetch == P)  \
-        return launch_decode_cfg<W, K, U, (P != 0)>(packed, L, x16, bias, y, st);
-    MNNQ_CFG(4, 1, 8, 0) MNNQ_CFG(4, 2, 8, 0) MNNQ_CFG(4, 4, 8, 0) MNNQ_CFG(8, 8, 8, 0)
+    // Rows of 28 chunks (K = 3584) on four waves: seven chunks each, with no register left unused
+    if (ks == 4 && L.C == 28 && !prefetch && !getenv("MNNQ_DECODE_KSPLIT")) unroll = 7;
+    // x staged under the weight stream: small layers, and those whose waves all have exactly `unroll` chunks
+    const bool exact = L.C % ks == 0 && L.C / ks == unroll;
+    bool early = !prefetch && ((int64_t)L.total() <= (16 << 20) || exact);
+    if (const char* e = getenv("MNNQ_DECODE_EARLY")) early = !prefetch && e[0] == '1';   // tests and tuning
+#define MNNQ_CFG(W, K, U, P)                                                              \
+    if (ks == K && unroll == U && prefetch == P) {                                        \
+        if constexpr (P == 0) {                                                           \
+            if (early) return launch_decode_cfg<W, K, U, false, true>(packed, L, x16, bias, y, st); \
+        }                                                                                 \
+        return launch_decode_cfg<W, K, U, (P != 0)>(packed, L, x16, bias, y, st);         \
+    }
+    MNNQ_CFG(4, 1, 8, 0) MNNQ_CFG(4, 2, 8, 0) MNNQ_CFG(4, 4, 8, 0) MNNQ_CFG(4, 4, 7, 0) MNNQ_CFG(8, 8, 8, 0)
     MNNQ_CFG(16, 16, 8, 0) MNNQ_CFG(16, 16, 12, 0)
     MNNQ_CFG(4, 1, 8, 1) MNNQ_CFG(4, 2, 8, 1) MNNQ_CFG(4, 4, 8, 1) MNNQ_CFG(8, 8, 8, 1) MNNQ_CFG(16, 16, 8, 1)
 #undef MNNQ_CFG

@@ -192,10 +192,39 @@ def test_decode_matches_oracle(N, K):
         results.append(y)
     y2 = host(B.mnnq_linear_decode(packed, N, K, xqd, sxd))
     assert np.array_equal(results[0], y2)          # run-to-run identical
+    # the row staged under the weight stream (small layers) or after it: the same sums
+    for ks in ("", "1", "4", "16"):
+        pair = []
+        for early in ("0", "1"):
+            os.environ["MNNQ_DECODE_EARLY"] = early
+            if ks:
+                os.environ["MNNQ_DECODE_KSPLIT"] = ks
+            try:
+                pair.append(host(B.mnnq_linear_decode(packed, N, K, xqd, sxd)))
+            finally:
+                os.environ.pop("MNNQ_DECODE_EARLY", None)
+                os.environ.pop("MNNQ_DECODE_KSPLIT", None)
+        assert np.array_equal(pair[0], pair[1]), ks
+        assert np.abs(pair[1] - y_o[0]).max() <= tol, ks
     # fused activation quantizer: same codes -> same result up to the summation order
     yf = host(B.mnnq_linear_decode_fused(packed, N, K, dev(x)))
     assert np.abs(yf - y_o[0]).max() <= tol, (np.abs(yf - y_o[0]).max(), tol)
     assert np.abs(yf - results[0]).max() <= 2e-6 * np.abs(y_o).max()
+    # ... with the quantizer run under the weight stream (small layers) or after it: the same sums
+    xd = dev(x)
+    for ks in ("", "1", "4", "8", "16"):
+        pair = []
+        for early in ("0", "1"):
+            os.environ["MNNQ_DECODE_EARLY"] = early
+            if ks:
+                os.environ["MNNQ_DECODE_KSPLIT"] = ks
+            try:
+                pair.append(host(B.mnnq_linear_decode_fused(packed, N, K, xd)))
+            finally:
+                os.environ.pop("MNNQ_DECODE_EARLY", None)
+                os.environ.pop("MNNQ_DECODE_KSPLIT", None)
+        assert np.array_equal(pair[0], pair[1]), ks
+        assert np.abs(pair[1] - y_o[0]).max() <= tol, ks
 
 
 def test_config1_single_layer_seed0():
@@ -415,13 +444,20 @@ def test_w4a16_matches_oracle(M, N, K):
     tol = TOL_A16 * np.abs(y_o).max()
     assert np.abs(y - y_o).max() <= tol, (np.abs(y - y_o).max(), tol)
     for ks in ("", "1", "2", "4", "8", "16"):
-        if ks:
-            os.environ["MNNQ_DECODE_KSPLIT"] = ks
-        try:
-            y0 = host(B.mnnq_linear_decode_f16(packed, N, K, xd[0].contiguous(), bias=dev(bias)))
-        finally:
-            os.environ.pop("MNNQ_DECODE_KSPLIT", None)
-        assert np.abs(y0 - y_o[0]).max() <= TOL_A16 * np.abs(y_o[0]).max(), ks
+        pair = []
+        for early in ("0", "1"):     # x staged after or under the weight stream: the same sums
+            os.environ["MNNQ_DECODE_EARLY"] = early
+            if ks:
+                os.environ["MNNQ_DECODE_KSPLIT"] = ks
+            try:
+                pair.append(host(B.mnnq_linear_decode_f16(packed, N, K, xd[0].contiguous(), bias=dev(bias))))
+            finally:
+                os.environ.pop("MNNQ_DECODE_KSPLIT", None)
+                os.environ.pop("MNNQ_DECODE_EARLY", None)
+        assert np.array_equal(pair[0], pair[1]), ks
+        assert np.abs(pair[1] - y_o[0]).max() <= TOL_A16 * np.abs(y_o[0]).max(), ks
+    y0 = host(B.mnnq_linear_decode_f16(packed, N, K, xd[0].contiguous(), bias=dev(bias)))
+    assert np.abs(y0 - y_o[0]).max() <= TOL_A16 * np.abs(y_o[0]).max()
 
 
 @pytest.mark.parametrize("M,N,K", [(17, 16, 64), (300, 272, 448), (513, 400, 1536), (1024, 512, 3584)])

@@ -16,7 +16,7 @@ def built():
     if not os.path.exists(B.LIB_PATH):
         import __graft_entry__
         __graft_entry__.build()
-    for v in ("MNNQ_PREFILL_TILE", "MNNQ_DECODE_KSPLIT", "MNNQ_DECODE_WAVES", "MNNQ_W8_PLANES"):
+    for v in ("MNNQ_PREFILL_TILE", "MNNQ_DECODE_KSPLIT", "MNNQ_DECODE_WAVES", "MNNQ_DECODE_EARLY", "MNNQ_W8_PLANES"):
         os.environ.pop(v, None)
 
 
@@ -73,9 +73,14 @@ def test_documented_plans_of_the_qwen2_7b_block():
     assert plan(4608, 3584) == [256, 128, 2, 1, 16]      # q|k|v: two K parts of eight waves
     assert plan(3584, 3584) == [128, 128, 2, 1, 16]      # o
     assert plan(3584, 18944) == [128, 128, 2, 1, 16]     # down
-    assert B.mnnq_plan_debug(1, 1, 37888, 3584)[:4] == [4, 4, 8, 0]      # GEMV: four waves per row tile, 7 chunks each
+    assert B.mnnq_plan_debug(1, 1, 37888, 3584)[:4] == [4, 4, 7, 0]      # GEMV: four waves per row tile, 7 chunks each
     assert B.mnnq_plan_debug(1, 1, 3584, 18944)[:4] == [16, 16, 12, 0]   # 148 chunks over sixteen waves
     assert B.mnnq_plan_debug(2, 1, 4608, 3584)[0] == 8                    # fused quantizer: larger workgroups
+    # the activation row is handled under the weight stream for layers of at most 16 MiB (q|k|v, o) and where
+    # every wave has exactly as many chunks as registers for them (gate|up), after it otherwise (down)
+    for what in (1, 2):
+        assert [B.mnnq_plan_debug(what, 1, n, k)[7] for n, k in
+                ((4608, 3584), (3584, 3584), (3584, 18944), (37888, 3584))] == [1, 1, 0, 1]
 
 
 def test_documented_plans_for_few_tokens():
