@@ -94,7 +94,7 @@ size_t mnnq_packed_size(int64_t N, int64_t K, int group, int mode);
 /* Bytes of device scratch the linear calls can make use of for these shapes.
  * No call needs a workspace: NULL / 0 is always accepted.  For M = 1 the value
  * is what mnnq_linear_decode_fused uses, when given, to hold the int8 row and
- * its scale (K rounded up to 128, plus 16): for layers above 48 MiB of packed
+ * its scale (K rounded up to 128, plus 16): for layers above 96 MiB of packed
  * weights it then runs the quantizer as a kernel of its own in front of the
  * GEMV, which is faster there than quantizing inside every workgroup.  The
  * result does not depend on the route.  For M > 1 the value is what
