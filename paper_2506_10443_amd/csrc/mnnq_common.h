@@ -124,6 +124,39 @@ __device__ __forceinline__ int quant4_fast(float4 v, float scale, float inv, flo
     return (int)(lo | hi);
 }
 
+// Lane exchange inside a row of 16 lanes as an operand modifier of the vector ALU (a general shuffle
+// goes through the LDS pipe and costs a round trip each).  CTRL: 0xB1 / 0x4E = lanes xor 1 / xor 2
+// of a quad, 0x141 / 0x140 = mirror of 8 / of 16 lanes.
+template <int CTRL>
+__device__ __forceinline__ int row_exchange(int v)
+{
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
+}
+
+// Maximum of a non-negative, non-NaN value over the wave (as integers: the order of such floats),
+// the same in all lanes.
+__device__ __forceinline__ float wave_max_nonneg(float a)
+{
+    int v = __float_as_int(a);
+    v = max(v, row_exchange<0xB1>(v));
+    v = max(v, row_exchange<0x4E>(v));
+    v = max(v, row_exchange<0x141>(v));
+    v = max(v, row_exchange<0x140>(v));     // every lane: maximum of its row of 16
+    const int m = max(max(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+                      max(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
+    return __int_as_float(m);
+}
+
+// Sum over each row of 16 lanes, the same in all of its lanes.
+__device__ __forceinline__ int row_sum16(int v)
+{
+    v += row_exchange<0xB1>(v);
+    v += row_exchange<0x4E>(v);
+    v += row_exchange<0x141>(v);     // the quads hold equal values: the mirrored lane is in the other quad
+    v += row_exchange<0x140>(v);
+    return v;
+}
+
 __device__ __forceinline__ float quant_fast_limit(float scale, float inv)
 {
     return (inv < 1.0e37f && scale > 1.0e-30f) ? 0.5f - 6.0e-5f : -1.0f;   // largest |r - rint(r)| of the fast path

@@ -109,8 +109,7 @@ __device__ __forceinline__ float workgroup_scale(float amax, float* lds_amax)
 {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
+    amax = wave_max_nonneg(amax);            // (max_abs4 drops NaNs and signs)
     if (lane == 0) lds_amax[wave] = amax;
     lds_barrier();
     amax = lds_amax[0];
@@ -142,8 +141,8 @@ struct RowQuantizer {
         if (i < valid && scale != 0.0f) v = quant4_fast(xv, scale, inv, lim);
         lds_xd[i] = v;
         int sum = __builtin_amdgcn_sdot4(v, 0x01010101, 0, false);
-        sum += __shfl_xor(sum, 1, 64);
-        sum += __shfl_xor(sum, 2, 64);
+        sum += row_exchange<0xB1>(sum);      // the four dwords of a block: one quad of lanes
+        sum += row_exchange<0x4E>(sum);
         if ((threadIdx.x & 3) == 0) {
             const int64_t u = i / 4, c = u / 8;
             lds_xs[c * 8 + (int)(u % 4) * 2 + (int)(u % 8) / 4] = sum;

@@ -35,8 +35,7 @@ __global__ __launch_bounds__(kQThreads) void quant_act_kernel(const float* __res
         const float4 v = xr[i];
         amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
     }
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
+    amax = wave_max_nonneg(amax);
     if ((tid & 63) == 0) s_part[tid >> 6] = amax;
     __syncthreads();
     amax = fmaxf(fmaxf(s_part[0], s_part[1]), fmaxf(s_part[2], s_part[3]));
@@ -54,9 +53,7 @@ __global__ __launch_bounds__(kQThreads) void quant_act_kernel(const float* __res
         if (!zero_row) codes = quant4_fast(xr[i], scale, inv, lim);
         out[i] = (uint32_t)codes;
         if (xsum) {
-            int s = __builtin_amdgcn_sdot4(codes, 0x01010101, 0, false);
-#pragma unroll
-            for (int o = 1; o < 16; o <<= 1) s += __shfl_xor(s, o, 16);
+            const int s = row_sum16(__builtin_amdgcn_sdot4(codes, 0x01010101, 0, false));
             if ((tid & 15) == 0) xsum[m * G + i / 16] = s;
         }
     }
@@ -86,8 +83,7 @@ __global__ __launch_bounds__(kQThreads) void quant_act_rows_kernel(const float* 
         if (i < K4) v[j] = xr[i];
         amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v[j].x), fabsf(v[j].y)), fmaxf(fabsf(v[j].z), fabsf(v[j].w))));
     }
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
+    amax = wave_max_nonneg(amax);
     if ((tid & 63) == 0) s_part[tid >> 6] = amax;
     __syncthreads();
     amax = fmaxf(fmaxf(s_part[0], s_part[1]), fmaxf(s_part[2], s_part[3]));
@@ -108,9 +104,7 @@ __global__ __launch_bounds__(kQThreads) void quant_act_rows_kernel(const float* 
         if (i < K4) out[i] = (uint32_t)codes;
         if (xsum) {
             // K4 is a multiple of 16, so a team of 16 lanes is inside the row or outside it as a whole
-            int s = __builtin_amdgcn_sdot4(codes, 0x01010101, 0, false);
-#pragma unroll
-            for (int o = 1; o < 16; o <<= 1) s += __shfl_xor(s, o, 16);
+            const int s = row_sum16(__builtin_amdgcn_sdot4(codes, 0x01010101, 0, false));
             if ((tid & 15) == 0 && i < K4) xsum[m * G + i / 16] = s;
         }
     }
