@@ -85,11 +85,11 @@ template <int WAVES>
 __device__ __forceinline__ void preload_row(const float* __restrict__ x, const Layout& L, float4 (&xr)[kRowRegs])
 {
     constexpr int THREADS = WAVES * 64;
-    const int64_t row_dw = L.Kx / 4;
+    const int row_dw = (int)(L.Kx / 4);     // (a row the GEMV can stage has fewer than 2^17 values: 32-bit indices)
     const float4* x4 = reinterpret_cast<const float4*>(x);
 #pragma unroll
     for (int j = 0; j < kRowRegs; ++j) {
-        const int64_t i = (int64_t)threadIdx.x + j * THREADS;
+        const int i = (int)threadIdx.x + j * THREADS;
         xr[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         if (i < row_dw) xr[j] = x4[i];
     }
@@ -127,15 +127,15 @@ __device__ __forceinline__ float max_abs4(float amax, const float4 v)
 // of a block sit in four neighbouring lanes, which all call this together).
 struct RowQuantizer {
     float scale, inv, lim;
-    int64_t valid;
+    int valid;
     int* lds_xd;
     int* lds_xs;
-    __device__ __forceinline__ explicit RowQuantizer(float s, int64_t valid_, int* xd, int* xs)
+    __device__ __forceinline__ explicit RowQuantizer(float s, int valid_, int* xd, int* xs)
         : scale(s), inv(s == 0.0f ? 0.0f : 1.0f / s), valid(valid_), lds_xd(xd), lds_xs(xs)
     {
         lim = quant_fast_limit(scale, inv);
     }
-    __device__ __forceinline__ void put(int64_t i, const float4 xv) const
+    __device__ __forceinline__ void put(int i, const float4 xv) const
     {
         int v = 0;
         if (i < valid && scale != 0.0f) v = quant4_fast(xv, scale, inv, lim);
@@ -144,8 +144,8 @@ struct RowQuantizer {
         sum += row_exchange<0xB1>(sum);      // the four dwords of a block: one quad of lanes
         sum += row_exchange<0x4E>(sum);
         if ((threadIdx.x & 3) == 0) {
-            const int64_t u = i / 4, c = u / 8;
-            lds_xs[c * 8 + (int)(u % 4) * 2 + (int)(u % 8) / 4] = sum;
+            const int u = i >> 2;                       // 16-byte block; chunk u / 8
+            lds_xs[(u & ~7) + (u & 3) * 2 + ((u >> 2) & 1)] = sum;
         }
     }
 };
@@ -156,15 +156,15 @@ __device__ __forceinline__ float quantize_row_to_lds(const float* __restrict__ x
 {
     constexpr int THREADS = WAVES * 64;
     const int tid = threadIdx.x;
-    const int64_t dwords = L.C * 32;                     // padded row of the packed reduction axis
-    const int64_t valid = L.K / 4;
-    const int64_t row_dw = L.Kx / 4;                     // the activation row itself
+    const int dwords = (int)(L.C * 32);                  // padded row of the packed reduction axis
+    const int valid = (int)(L.K / 4);
+    const int row_dw = (int)(L.Kx / 4);                  // the activation row itself
     const float4* x4 = reinterpret_cast<const float4*>(x);
 
     float amax = 0.0f;
 #pragma unroll
     for (int j = 0; j < kRowRegs; ++j) amax = max_abs4(amax, xr[j]);   // zeros past the row do not change the maximum
-    for (int64_t i = tid + kRowRegs * THREADS; i < row_dw; i += THREADS) amax = max_abs4(amax, x4[i]);
+    for (int i = tid + kRowRegs * THREADS; i < row_dw; i += THREADS) amax = max_abs4(amax, x4[i]);
     const RowQuantizer q(workgroup_scale<WAVES>(amax, lds_amax), valid, lds_xd, lds_xs);
     // The row itself: first the elements already in registers, then the rest from memory.  (No
     // conditional between a register value and a load: it would select between two addresses and
@@ -172,14 +172,14 @@ __device__ __forceinline__ float quantize_row_to_lds(const float* __restrict__ x
     // four lanes of a block always take the same branch.
 #pragma unroll
     for (int j = 0; j < kRowRegs; ++j) {
-        const int64_t i = (int64_t)tid + j * THREADS;
+        const int i = tid + j * THREADS;
         if (i < row_dw) q.put(i, xr[j]);
     }
-    for (int64_t i = tid + kRowRegs * THREADS; i < row_dw; i += THREADS) q.put(i, x4[i]);
+    for (int i = tid + kRowRegs * THREADS; i < row_dw; i += THREADS) q.put(i, x4[i]);
     // Past the row: its second pass (int8 weights) and the zero padding of the last chunk.
-    for (int64_t i = row_dw + tid; i < dwords; i += THREADS) {
+    for (int i = row_dw + tid; i < dwords; i += THREADS) {
         float4 xv = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        if (i < valid) xv = x4[i % row_dw];
+        if (i < valid) xv = x4[i - row_dw];              // (the packed axis runs over the row at most twice)
         q.put(i, xv);
     }
     lds_barrier();
