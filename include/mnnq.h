@@ -238,7 +238,8 @@ int mnnq_linear_acc_debug(const void *packed, int64_t M, int64_t N, int64_t K, i
  *           workgroup, workgroups, 1 if the two nibble planes of int8 weights are merged in registers};
  * what = 1: mnnq_linear_decode; what = 2: mnnq_linear_decode_fused without workspace; out8 = {waves per
  *           workgroup, waves per row tile, weight chunks a wave holds in registers, 1 if it loops with a
- *           prefetch, LDS bytes per workgroup, workgroups, row tiles per workgroup, 0}.
+ *           prefetch, LDS bytes per workgroup, workgroups, row tiles per workgroup, 1 if the activation
+ *           row is requested ahead of the weights and handled while they arrive}.
  * out8: HOST pointer to 8 int32.  Same shape / mode errors as the calls themselves. */
 int mnnq_plan_debug(int what, int64_t M, int64_t N, int64_t K, int group, int mode, int32_t *out8);
 
