@@ -182,7 +182,10 @@ __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* _
     ChunkRegs cur[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
-        if (EARLY) cur[u] = load_chunk<MINF>(wp, sp, zp, u < n_chunks ? u : 0);
+        if (EARLY) {
+            // (a repeated chunk: all lanes on its first 16 bytes, one cache line instead of sixteen)
+            cur[u] = load_chunk<MINF>(u < n_chunks ? wp : wp - lane, sp, zp, u < n_chunks ? u : 0);
+        }
         else if (u < n_chunks) cur[u] = load_chunk<MINF>(wp, sp, zp, u);
         else cur[u] = ChunkRegs{};
     }
@@ -314,9 +317,10 @@ int launch_decode_f16(const uint8_t* packed, const Layout& L, const uint16_t* x1
     }
     // Rows of 28 chunks (K = 3584) on four waves: seven chunks each, with no register left unused
     if (ks == 4 && L.C == 28 && !prefetch && !getenv("MNNQ_DECODE_KSPLIT")) unroll = 7;
-    // x staged under the weight stream: small layers, and those whose waves all have exactly `unroll` chunks
+    // x staged under the weight stream: small layers whose waves have at most two chunks fewer than `unroll`,
+    // and those whose waves all have exactly `unroll` chunks
     const bool exact = L.C % ks == 0 && L.C / ks == unroll;
-    bool early = !prefetch && ((int64_t)L.total() <= (16 << 20) || exact);
+    bool early = !prefetch && (((int64_t)L.total() <= (16 << 20) && L.C / ks >= unroll - 2) || exact);
     if (const char* e = getenv("MNNQ_DECODE_EARLY")) early = !prefetch && e[0] == '1';   // tests and tuning
 #define MNNQ_CFG(W, K, U, P)                                                              \
     if (ks == K && unroll == U && prefetch == P) {                                        \

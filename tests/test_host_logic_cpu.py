@@ -76,11 +76,13 @@ def test_documented_plans_of_the_qwen2_7b_block():
     assert B.mnnq_plan_debug(1, 1, 37888, 3584)[:4] == [4, 4, 7, 0]      # GEMV: four waves per row tile, 7 chunks each
     assert B.mnnq_plan_debug(1, 1, 3584, 18944)[:4] == [16, 16, 12, 0]   # 148 chunks over sixteen waves
     assert B.mnnq_plan_debug(2, 1, 4608, 3584)[0] == 8                    # fused quantizer: larger workgroups
-    # the activation row is handled under the weight stream for layers of at most 16 MiB (q|k|v, o) and where
-    # every wave has exactly as many chunks as registers for them (gate|up), after it otherwise (down)
-    for what in (1, 2):
-        assert [B.mnnq_plan_debug(what, 1, n, k)[7] for n, k in
-                ((4608, 3584), (3584, 3584), (3584, 18944), (37888, 3584))] == [1, 1, 0, 1]
+    # the activation row is handled under the weight stream where (nearly) every wave's registers are filled:
+    # small layers with at most two chunks fewer per wave than registers for them, and exactly fitting ones
+    early = lambda what, n, k: B.mnnq_plan_debug(what, 1, n, k)[7]
+    shapes = ((4608, 3584), (3584, 3584), (3584, 18944), (37888, 3584))
+    assert [early(1, n, k) for n, k in shapes] == [1, 1, 0, 1]
+    assert [early(2, n, k) for n, k in shapes] == [1, 0, 0, 1]     # fused o: eight waves per row tile, 3 - 4 chunks each
+    assert early(1, 1536, 8960) == 0 and early(1, 2048, 1536) == 1  # Qwen2-1.5B down (4 - 5 of 8 chunks) and q|k|v
 
 
 def test_documented_plans_for_few_tokens():
