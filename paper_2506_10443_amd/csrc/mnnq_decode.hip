@@ -196,8 +196,8 @@ __device__ __forceinline__ float quantize_row_to_lds(const float* __restrict__ x
 // compiler count how many younger loads may still be in flight when the row elements are first
 // used; behind conditional loads it waits for all of them, so that the row is quantized and staged
 // only when the whole weight stream has arrived.  The launches of small layers, which are bound by
-// latency, gain 7 - 9 % from the overlap; large layers lose 3 - 7 % to the repeated loads and keep
-// the conditional form.
+// latency, gain 7 - 9 % from the overlap; layers whose waves hold clearly fewer chunks than UNROLL
+// lose (3 - 13 % measured) and keep the conditional form: the host decides (decode_config).
 template <int WAVES, int KSPLIT, int UNROLL, int MODE, bool PREFETCH, bool MINF, bool EARLY = false>
 __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __restrict__ packed, Layout L,
                                                             const void* __restrict__ xin,
@@ -275,9 +275,11 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
         if (EARLY) {
             // (a repeated chunk: all lanes on its first 16 bytes, one cache line instead of sixteen)
             cur[u] = load_chunk<MINF>(u < n_chunks ? wp : wp - lane, sp, zp, u < n_chunks ? u : 0);
+        } else if (u < n_chunks) {
+            cur[u] = load_chunk<MINF>(wp, sp, zp, u);
+        } else {
+            cur[u] = ChunkRegs{};
         }
-        else if (u < n_chunks) cur[u] = load_chunk<MINF>(wp, sp, zp, u);
-        else cur[u] = ChunkRegs{};
     }
 
     // ---- activation row -> LDS

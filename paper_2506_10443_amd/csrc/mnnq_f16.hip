@@ -185,9 +185,11 @@ __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* _
         if (EARLY) {
             // (a repeated chunk: all lanes on its first 16 bytes, one cache line instead of sixteen)
             cur[u] = load_chunk<MINF>(u < n_chunks ? wp : wp - lane, sp, zp, u < n_chunks ? u : 0);
+        } else if (u < n_chunks) {
+            cur[u] = load_chunk<MINF>(wp, sp, zp, u);
+        } else {
+            cur[u] = ChunkRegs{};
         }
-        else if (u < n_chunks) cur[u] = load_chunk<MINF>(wp, sp, zp, u);
-        else cur[u] = ChunkRegs{};
     }
 
     {
