@@ -315,23 +315,25 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
 
     float accf = 0.0f;
     for (int64_t i = 0; i < n_chunks; i += UNROLL) {
-        ChunkRegs nxt[PREFETCH ? UNROLL : 1];
-        if (PREFETCH) {
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                if (i + UNROLL + u < n_chunks) nxt[u] = load_chunk<MINF>(wp, sp, zp, i + UNROLL + u);
-                else nxt[u] = ChunkRegs{};
-            }
-        }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
+            const ChunkRegs r = cur[u];
+            if (PREFETCH) {
+                // Rows longer than the registers hold: a rolling window.  The registers of the chunk about
+                // to be consumed are refilled with the chunk UNROLL further on, so that a wave keeps
+                // UNROLL chunks in flight all the time.  No branch around the load (past the wave's
+                // range all lanes read the first 16 bytes of its first chunk, and the copy is never
+                // used): only then does the compiler wait by count for the chunk it consumes next, with
+                // the refills issued since still in flight.
+                const bool have = i + UNROLL + u < n_chunks;
+                cur[u] = load_chunk<MINF>(have ? wp : wp - lane, sp, zp, have ? i + UNROLL + u : 0);
+            }
             if (i + u < n_chunks) {
                 const int64_t c = c0 + i + u;
                 const int64_t cl = cbase + i + u;
                 const int4 xa = lds_x[cl * 8 + kb];
                 const int4 xb = lds_x[cl * 8 + 4 + kb];
                 const int2 xs = *reinterpret_cast<const int2*>(lds_xs + cl * 8 + kb * 2);
-                const ChunkRegs& r = cur[u];
                 // integer zero point: sum x (q - z) = sum x q - z sum x; float minimum: sum x q, the
                 // minimum enters below with the same block sum
                 int i0 = dot16(r.w.x, r.w.y, xa) - (MINF ? 0 : (int)(r.z & 0xffu) * xs.x);
@@ -355,8 +357,6 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
             }
         }
         if (!PREFETCH) break;   // the host guarantees n_chunks <= UNROLL
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) cur[u] = nxt[u];
     }
     if (MODE == kAcc) return;
 

@@ -224,20 +224,20 @@ __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* _
 
     float accf = 0.0f;
     for (int64_t i = 0; i < n_chunks; i += UNROLL) {
-        ChunkRegs nxt[PREFETCH ? UNROLL : 1];
-        if (PREFETCH) {
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                if (i + UNROLL + u < n_chunks) nxt[u] = load_chunk<MINF>(wp, sp, zp, i + UNROLL + u);
-                else nxt[u] = ChunkRegs{};
-            }
-        }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
+            const ChunkRegs r = cur[u];
+            if (PREFETCH) {
+                // Rolling window: the registers of the chunk about to be consumed are refilled with the
+                // chunk UNROLL further on, without a branch around the load (past the wave's range all
+                // lanes read the first 16 bytes of its first chunk; the copy is never used), so that the
+                // compiler waits by count and the refills stay in flight.
+                const bool have = i + UNROLL + u < n_chunks;
+                cur[u] = load_chunk<MINF>(have ? wp : wp - lane, sp, zp, have ? i + UNROLL + u : 0);
+            }
             if (i + u < n_chunks) {
                 // 16-byte unit of x[128 c + 64 h + 16 kb] inside the region: 16 (i + u) + 8 h + 2 kb
                 const uint4* xp = lds_x + (i + u) * 16 + kb * 2;
-                const ChunkRegs& r = cur[u];
                 const float p0 = dot16_f16(r.w.x, r.w.y, r.z & 0xffu, xp[0], xp[1]);
                 const float p1 = dot16_f16(r.w.z, r.w.w, r.z >> 8, xp[8], xp[9]);
                 accf = fmaf(r.s.x, p0, accf);
@@ -249,8 +249,6 @@ __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* _
             }
         }
         if (!PREFETCH) break;   // the host guarantees n_chunks <= UNROLL
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) cur[u] = nxt[u];
     }
 
     accf += __shfl_xor(accf, 16, 64);
