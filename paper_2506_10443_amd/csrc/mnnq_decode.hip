@@ -317,17 +317,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
     for (int64_t i = 0; i < n_chunks; i += UNROLL) {
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const ChunkRegs r = cur[u];
-            if (PREFETCH) {
-                // Rows longer than the registers hold: a rolling window.  The registers of the chunk about
-                // to be consumed are refilled with the chunk UNROLL further on, so that a wave keeps
-                // UNROLL chunks in flight all the time.  No branch around the load (past the wave's
-                // range all lanes read the first 16 bytes of its first chunk, and the copy is never
-                // used): only then does the compiler wait by count for the chunk it consumes next, with
-                // the refills issued since still in flight.
-                const bool have = i + UNROLL + u < n_chunks;
-                cur[u] = load_chunk<MINF>(have ? wp : wp - lane, sp, zp, have ? i + UNROLL + u : 0);
-            }
+            const ChunkRegs& r = cur[u];
             if (i + u < n_chunks) {
                 const int64_t c = c0 + i + u;
                 const int64_t cl = cbase + i + u;
@@ -354,6 +344,16 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
                         accf = fmaf(r.mn.y, (float)xs.y, accf);
                     }
                 }
+            }
+            if (PREFETCH) {
+                // Rows longer than the registers hold: a rolling window.  The registers of the chunk just
+                // consumed are refilled with the chunk UNROLL further on, so that a wave keeps UNROLL
+                // chunks in flight all the time.  No branch around the load (past the wave's range all
+                // lanes read the first 16 bytes of its first chunk, and the copy is never used): only
+                // then does the compiler wait by count for the chunk it consumes next, with the refills
+                // issued since still in flight.
+                const bool have = i + UNROLL + u < n_chunks;
+                cur[u] = load_chunk<MINF>(have ? wp : wp - lane, sp, zp, have ? i + UNROLL + u : 0);
             }
         }
         if (!PREFETCH) break;   // the host guarantees n_chunks <= UNROLL

@@ -226,15 +226,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* _
     for (int64_t i = 0; i < n_chunks; i += UNROLL) {
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const ChunkRegs r = cur[u];
-            if (PREFETCH) {
-                // Rolling window: the registers of the chunk about to be consumed are refilled with the
-                // chunk UNROLL further on, without a branch around the load (past the wave's range all
-                // lanes read the first 16 bytes of its first chunk; the copy is never used), so that the
-                // compiler waits by count and the refills stay in flight.
-                const bool have = i + UNROLL + u < n_chunks;
-                cur[u] = load_chunk<MINF>(have ? wp : wp - lane, sp, zp, have ? i + UNROLL + u : 0);
-            }
+            const ChunkRegs& r = cur[u];
             if (i + u < n_chunks) {
                 // 16-byte unit of x[128 c + 64 h + 16 kb] inside the region: 16 (i + u) + 8 h + 2 kb
                 const uint4* xp = lds_x + (i + u) * 16 + kb * 2;
@@ -246,6 +238,14 @@ __global__ __launch_bounds__(WAVES * 64) void decode_f16_kernel(const uint8_t* _
                     accf = fmaf(r.mn.x, lds_xs[(i + u) * 8 + kb], accf);
                     accf = fmaf(r.mn.y, lds_xs[(i + u) * 8 + 4 + kb], accf);
                 }
+            }
+            if (PREFETCH) {
+                // Rolling window: the registers of the chunk just consumed are refilled with the chunk
+                // UNROLL further on, without a branch around the load (past the wave's range all lanes
+                // read the first 16 bytes of its first chunk; the copy is never used), so that the
+                // compiler waits by count and the refills stay in flight.
+                const bool have = i + UNROLL + u < n_chunks;
+                cur[u] = load_chunk<MINF>(have ? wp : wp - lane, sp, zp, have ? i + UNROLL + u : 0);
             }
         }
         if (!PREFETCH) break;   // the host guarantees n_chunks <= UNROLL
