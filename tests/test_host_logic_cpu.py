@@ -81,7 +81,8 @@ def test_documented_plans_of_the_qwen2_7b_block():
     early = lambda what, n, k: B.mnnq_plan_debug(what, 1, n, k)[7]
     shapes = ((4608, 3584), (3584, 3584), (3584, 18944), (37888, 3584))
     assert [early(1, n, k) for n, k in shapes] == [1, 1, 0, 1]
-    assert [early(2, n, k) for n, k in shapes] == [1, 0, 0, 1]     # fused o: eight waves per row tile, 3 - 4 chunks each
+    assert [early(2, n, k) for n, k in shapes] == [1, 1, 0, 1]
+    assert B.mnnq_plan_debug(2, 1, 3584, 3584)[:3] == [8, 8, 4]    # fused o: eight waves per row tile, 3 - 4 chunks each
     assert early(1, 1536, 8960) == 0 and early(1, 2048, 1536) == 1  # Qwen2-1.5B down (4 - 5 of 8 chunks) and q|k|v
 
 
