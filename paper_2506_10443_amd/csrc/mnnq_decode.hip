@@ -437,8 +437,9 @@ DecodeCfg decode_config(const Layout& L, bool fused)
             prefetch = pw > unroll;
         }
     }
-    // Rows of 28 chunks (K = 3584) on four waves: seven chunks each, with no register left unused
-    if (ks == 4 && L.C == 28 && !prefetch && !getenv("MNNQ_DECODE_KSPLIT")) unroll = 7;
+    // Rows of 28 chunks (K = 3584) on four waves or of 112 (K = 14336) on sixteen: seven chunks each, with no
+    // register left unused
+    if ((ks == 4 || ks == 16) && L.C == 7 * ks && !prefetch && !getenv("MNNQ_DECODE_KSPLIT")) unroll = 7;
     // ... and eight waves on a row tile with at most four chunks each (the fused form of small layers)
     if (fused && ks == 8 && (L.C + 7) / 8 <= 4 && !getenv("MNNQ_DECODE_KSPLIT")) unroll = 4;
     int waves = fused ? (ks > 8 ? 16 : 8) : (ks > 4 ? ks : 4);
@@ -477,7 +478,7 @@ int dispatch(const uint8_t* packed, const Layout& L, int64_t M, const void* xin,
     }
 #define MNNQ_CFG_W(K, U, P) MNNQ_CFG(4, K, U, P) MNNQ_CFG(8, K, U, P) MNNQ_CFG(16, K, U, P)
     MNNQ_CFG_W(1, 8, 0) MNNQ_CFG_W(2, 8, 0) MNNQ_CFG_W(4, 8, 0) MNNQ_CFG_W(4, 7, 0)
-    MNNQ_CFG(8, 8, 8, 0) MNNQ_CFG(8, 8, 4, 0) MNNQ_CFG(16, 8, 8, 0) MNNQ_CFG(16, 16, 8, 0) MNNQ_CFG(16, 16, 12, 0)
+    MNNQ_CFG(8, 8, 8, 0) MNNQ_CFG(8, 8, 4, 0) MNNQ_CFG(16, 8, 8, 0) MNNQ_CFG(16, 16, 8, 0) MNNQ_CFG(16, 16, 7, 0) MNNQ_CFG(16, 16, 12, 0)
     MNNQ_CFG_W(1, 8, 1) MNNQ_CFG_W(2, 8, 1) MNNQ_CFG_W(4, 8, 1)
     MNNQ_CFG(8, 8, 8, 1) MNNQ_CFG(16, 8, 8, 1) MNNQ_CFG(16, 16, 8, 1)
 #undef MNNQ_CFG_W

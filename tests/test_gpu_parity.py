@@ -164,7 +164,8 @@ def _layer(N, K, M, seed, outliers=True):
     return W, x, q, s, z, xq, sx
 
 
-DECODE_SHAPES = [(16, 64), (32, 192), (48, 1536), (8960, 1536), (1536, 8960), (528, 3584), (4096, 4096)]
+DECODE_SHAPES = [(16, 64), (32, 192), (48, 1536), (8960, 1536), (1536, 8960), (528, 3584), (4096, 4096),
+                 (80, 14336)]     # (seven chunks on each of sixteen waves)
 
 
 @pytest.mark.parametrize("N,K", DECODE_SHAPES)

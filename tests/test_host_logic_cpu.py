@@ -75,6 +75,7 @@ def test_documented_plans_of_the_qwen2_7b_block():
     assert plan(3584, 18944) == [128, 128, 2, 1, 16]     # down
     assert B.mnnq_plan_debug(1, 1, 37888, 3584)[:4] == [4, 4, 7, 0]      # GEMV: four waves per row tile, 7 chunks each
     assert B.mnnq_plan_debug(1, 1, 3584, 18944)[:4] == [16, 16, 12, 0]   # 148 chunks over sixteen waves
+    assert B.mnnq_plan_debug(1, 1, 4096, 14336)[:4] == [16, 16, 7, 0]    # (Llama-3-8B down) 112 chunks: seven each
     assert B.mnnq_plan_debug(2, 1, 4608, 3584)[0] == 8                    # fused quantizer: larger workgroups
     # the activation row is handled under the weight stream where (nearly) every wave's registers are filled:
     # small layers with at most two chunks fewer per wave than registers for them, and exactly fitting ones
