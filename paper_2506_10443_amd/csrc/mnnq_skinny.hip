@@ -77,7 +77,7 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_kernel(const uint8_t* __res
     const int64_t C = L.C;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: addresses start in scalar registers
     const int row = lane & 15;     // weight row of the B operand and of the results; token of the A operand
     const int kb = lane >> 4;
     constexpr int TILES_PER_WG = WAVES / KSPLIT;
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(512, 2) void skinny_persist_kernel(const uint8_t* _
     const int64_t C = L.C;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: addresses start in scalar registers
     const int row = lane & 15;
     const int kb = lane >> 4;
     constexpr int TILES_PER_STEP = WAVES / KSPLIT;
