@@ -159,6 +159,20 @@ int mnnq_linear_prefill_fused(const void *packed, int64_t M, int64_t N, int64_t 
                               const float *x, const float *bias, float *y,
                               void *workspace, size_t workspace_bytes, void *stream);
 
+/* mnnq_linear_prefill_fused for callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the int8
+ * codes and scales pass through an array inside the library instead, of
+ * mnnq_static_scratch_bytes() = 32 MiB per device, which every device the library runs on holds
+ * until the process ends.  The call allocates and frees nothing.  Same arguments, checks and result
+ * (bit for bit) as mnnq_linear_prefill_fused without the workspace; additionally MNNQ_ERR_SIZE when
+ * M * K rounded up to 16, plus 4 * M rounded up to 16, exceeds mnnq_static_scratch_bytes().
+ * All calls on one device share that device's array: calls that overlap in time on one device
+ * (different streams or threads) race and give undefined results; calls ordered on one stream are
+ * safe.  Nothing in the array has to survive between calls. */
+int mnnq_linear_prefill_fused_static(const void *packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                                     const float *x, const float *bias, float *y, void *stream);
+size_t mnnq_static_scratch_bytes(void);
+
 /* fp16-activation variants (Section 4.2: quantized weights with fp16 activations on GPUs;
  * W4A16, and W8A16 with mode MNNQ_W8_MIN_FLOAT):
  *   y[m,n] = sum_k float(x16[m,k]) * w^[n,k] (+ bias[n]),  w^ the weight the stored code

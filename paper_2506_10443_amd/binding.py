@@ -28,6 +28,7 @@ EXPORTS = (
     "mnnq_pack_from_quantized",
     "mnnq_linear_decode_o16", "mnnq_linear_prefill_o16", "mnnq_linear_decode_f16_o16", "mnnq_linear_prefill_f16_o16",
     "mnnq_plan_debug", "mnnq_linear_prefill_fused", "mnnq_linear_decode_fused_o16", "mnnq_linear_prefill_fused_o16", "mnnq_peak_read", "mnnq_peak_mfma", "mnnq_peak_mfma_count",
+    "mnnq_linear_prefill_fused_static", "mnnq_static_scratch_bytes",
 )
 
 
@@ -79,8 +80,11 @@ def lib() -> ctypes.CDLL:
         L.mnnq_linear_prefill_o16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp]
         L.mnnq_linear_decode_f16_o16.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
         L.mnnq_linear_prefill_f16_o16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp]
+        L.mnnq_linear_prefill_fused_static.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp]
         for name in EXPORTS[5:]:
             getattr(L, name).restype = i32
+        L.mnnq_static_scratch_bytes.restype = sz
+        L.mnnq_static_scratch_bytes.argtypes = []
         _lib = L
     return _lib
 
@@ -321,6 +325,23 @@ def mnnq_linear_prefill_fused(packed, N: int, K: int, x, bias=None, out=None, wo
                                            _ptr(workspace), workspace.numel(), _stream()),
            "mnnq_linear_prefill_fused")
     return y
+
+
+def mnnq_linear_prefill_fused_static(packed, N: int, K: int, x, bias=None, out=None, mode: int = MODE_W4_ZP_INT):
+    """mnnq_linear_prefill_fused through the library's own scratch array: x f32 [M,K] -> y f32 [M,N];
+    `out` must be given by callers that may not allocate (this wrapper allocates it otherwise)."""
+    _dev(packed, torch.uint8, "packed"); _dev(x, torch.float32, "x")
+    M = x.shape[0]
+    if x.shape[1] != K:
+        raise ValueError("x must be [M,K]")
+    y = torch.empty((M, N), dtype=torch.float32, device=packed.device) if out is None else out
+    _check(lib().mnnq_linear_prefill_fused_static(_ptr(packed), M, N, K, GROUP, mode, _ptr(x), _ptr(bias), _ptr(y),
+                                                  _stream()), "mnnq_linear_prefill_fused_static")
+    return y
+
+
+def mnnq_static_scratch_bytes() -> int:
+    return int(lib().mnnq_static_scratch_bytes())
 
 
 def mnnq_linear_decode_fused_o16(packed, N: int, K: int, x, bias=None, out=None, workspace=None,

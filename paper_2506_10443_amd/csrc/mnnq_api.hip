@@ -4,6 +4,8 @@
 
 #include <stdlib.h>
 
+#include <mutex>
+
 namespace mnnq {
 
 static thread_local int t_last_hip_error = 0;
@@ -192,11 +194,39 @@ int prefill_fused_impl(const void* packed, int64_t M, int64_t N, int64_t K, int 
     if (int s = check_shape(N, K, group, mode)) return s;
     if (!prefill_fits(M, N, K, mode) && prefill_slab_rows(N, K, mode) <= 0) return MNNQ_ERR_UNSUPPORTED;
     if (workspace_bytes < fused_prefill_ws_bytes(M, K)) return MNNQ_ERR_SIZE;
-    if (misaligned(x) || misaligned(workspace)) return MNNQ_ERR_ALIGN;
+    if (misaligned(packed) || misaligned(x) || misaligned(workspace) || misaligned(y) || misaligned(bias))
+        return MNNQ_ERR_ALIGN;
     int8_t* xq = static_cast<int8_t*>(workspace);
     float* sx = reinterpret_cast<float*>(xq + fused_prefill_codes_bytes(M, K));
     if (int s = launch_quant_act(x, M, K, xq, sx, nullptr, static_cast<hipStream_t>(stream))) return s;
     return prefill_impl(packed, M, N, K, group, mode, xq, sx, bias, y, out16, nullptr, stream);
+}
+
+// Scratch of mnnq_linear_prefill_fused_static: the int8 codes [M, K] and the scales [M] pass through
+// this array instead of a caller's workspace.  Every device the library runs on holds its own copy
+// at its own address; in host code the array's name is only a handle for hipGetSymbolAddress.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) uint8_t scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];   // device address of `scratch`, per device; NULL until first asked for
+std::mutex g_scratch_mutex;
+
+// Device address of the current device's copy of `scratch` (looked up once per device).
+int static_scratch(uint8_t** out)
+{
+    int dev = 0;
+    MNNQ_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return MNNQ_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        MNNQ_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return MNNQ_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = static_cast<uint8_t*>(g_scratch_ptr[dev]);
+    return MNNQ_OK;
 }
 
 }  // namespace
@@ -323,6 +353,23 @@ int mnnq_linear_prefill_fused(const void* packed, int64_t M, int64_t N, int64_t 
 {
     return prefill_fused_impl(packed, M, N, K, group, mode, x, bias, y, false, workspace, workspace_bytes, stream);
 }
+
+int mnnq_linear_prefill_fused_static(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                                     const float* x, const float* bias, float* y, void* stream)
+{
+    if (!packed || !x || !y) return MNNQ_ERR_NULL;
+    if (M <= 0) return MNNQ_ERR_SHAPE;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    if (fused_prefill_ws_bytes(M, K) > kStaticScratchBytes) return MNNQ_ERR_SIZE;
+    uint8_t* ws = nullptr;
+    // (every other check is made by the call this one forwards to, before anything is launched)
+    if (misaligned(packed) || misaligned(x) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
+    if (!prefill_fits(M, N, K, mode) && prefill_slab_rows(N, K, mode) <= 0) return MNNQ_ERR_UNSUPPORTED;
+    if (int s = static_scratch(&ws)) return s;
+    return prefill_fused_impl(packed, M, N, K, group, mode, x, bias, y, false, ws, kStaticScratchBytes, stream);
+}
+
+size_t mnnq_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 int mnnq_linear_prefill_fused_o16(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
                                   const float* x, const float* bias, uint16_t* y16, void* workspace,
