@@ -73,7 +73,14 @@ typedef enum {
      * weight).  Supported by the same calls as MNNQ_W4_MIN_FLOAT; q of the
      * unpack / import calls holds the 8-bit codes; mnnq_linear_acc_debug returns
      * 2 K/64 sums per (m, n): first the high-nibble planes, then the low ones. */
-    MNNQ_W8_MIN_FLOAT = 2
+    MNNQ_W8_MIN_FLOAT = 2,
+    /* Flag, to be OR-ed to MNNQ_W4_ZP_INT in every call that takes a mode: the packed buffer also
+     * holds the weights a second time, rearranged at load (Section 5.1) for the fp6 matrix
+     * instructions of gfx950 (the "matrix-core plane": 0.81 bytes per weight more).  The prefill calls
+     * then run on those instructions when they are also given a workspace for the activations'
+     * counterpart (mnnq_workspace_size); every other call reads the chunk layout in front as before.
+     * Results are those of the unflagged mode: the plane holds the same integers q - zero. */
+    MNNQ_WITH_MATRIX_PLANE = 16
 } mnnq_mode;
 
 /* Text for a status code (static storage). */
@@ -244,6 +251,16 @@ int mnnq_peak_mfma_count(void);
  * 1 runs the prefill kernel's MFMA loop. */
 int mnnq_linear_acc_debug(const void *packed, int64_t M, int64_t N, int64_t K, int group, int mode,
                           const int8_t *xq, int32_t *acc, int use_prefill_kernel, void *stream);
+
+/* The same integers from the GEMM on the fp6 matrix instructions (mode with MNNQ_WITH_MATRIX_PLANE,
+ * M > 32): acc[m, n, g] as above.  workspace: at least mnnq_workspace_size(M, N, K, group, mode) bytes. */
+int mnnq_linear_acc_debug_planes(const void *packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                                 const int8_t *xq, int32_t *acc, void *workspace, size_t workspace_bytes,
+                                 void *stream);
+
+/* Tests and tuning: fix the tile plan of a kernel family for all later calls of this process
+ * (kernel 6 = the fp6 GEMM: plan 0..4; -1 = choose from the shape again).  Not thread safe. */
+int mnnq_debug_force_plan(int kernel, int plan);
 
 /* Test view of the host logic (Section 5.1 chooses loop tiling from the problem's dimensions; here:
  * which kernel configuration a call would launch).  Nothing is launched and no device is needed.

@@ -16,6 +16,7 @@ GROUP = 64
 MODE_W4_ZP_INT = 0      # integer zero point per (row, group)
 MODE_W4_MIN_FLOAT = 1   # Eq. 1 as printed: fp32 group minimum per (row, group)
 MODE_W8_MIN_FLOAT = 2   # int8 weights (codes 0..255), fp32 group minimum; K must be a multiple of 128
+WITH_MATRIX_PLANE = 16  # flag for MODE_W4_ZP_INT: the packed buffer also holds the fp6 matrix-core plane
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "lib", "libmnnq.so")
@@ -29,6 +30,7 @@ EXPORTS = (
     "mnnq_linear_decode_o16", "mnnq_linear_prefill_o16", "mnnq_linear_decode_f16_o16", "mnnq_linear_prefill_f16_o16",
     "mnnq_plan_debug", "mnnq_linear_prefill_fused", "mnnq_linear_decode_fused_o16", "mnnq_linear_prefill_fused_o16", "mnnq_peak_read", "mnnq_peak_mfma", "mnnq_peak_mfma_count",
     "mnnq_linear_prefill_fused_static", "mnnq_static_scratch_bytes",
+    "mnnq_linear_acc_debug_planes", "mnnq_debug_force_plan",
 )
 
 
@@ -80,6 +82,8 @@ def lib() -> ctypes.CDLL:
         L.mnnq_linear_prefill_o16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp]
         L.mnnq_linear_decode_f16_o16.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
         L.mnnq_linear_prefill_f16_o16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp]
+        L.mnnq_linear_acc_debug_planes.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, sz, vp]
+        L.mnnq_debug_force_plan.argtypes = [i32, i32]
         L.mnnq_linear_prefill_fused_static.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp]
         for name in EXPORTS[5:]:
             getattr(L, name).restype = i32
@@ -138,7 +142,7 @@ def mnnq_unpack_weights(packed: torch.Tensor, N: int, K: int, mode: int = MODE_W
     G = K // GROUP
     q = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
     s = torch.empty((N, G), dtype=torch.float32, device=packed.device)
-    z = torch.empty((N, G), dtype=torch.uint8 if mode == MODE_W4_ZP_INT else torch.float32,
+    z = torch.empty((N, G), dtype=torch.uint8 if (mode & 15) == MODE_W4_ZP_INT else torch.float32,
                     device=packed.device)
     _check(lib().mnnq_unpack_weights(_ptr(packed), N, K, GROUP, mode, _ptr(q), _ptr(s), _ptr(z),
                                      _stream()), "mnnq_unpack_weights")
@@ -187,16 +191,39 @@ def mnnq_linear_decode_fused(packed, N: int, K: int, x, bias=None, out=None, wor
     return y
 
 
-def mnnq_linear_prefill(packed, N: int, K: int, xq, sx, bias=None, out=None, mode: int = MODE_W4_ZP_INT):
-    """M tokens: xq i8 [M,K], sx f32 [M] -> y f32 [M,N]."""
+def mnnq_linear_prefill(packed, N: int, K: int, xq, sx, bias=None, out=None, mode: int = MODE_W4_ZP_INT,
+                        workspace=None):
+    """M tokens: xq i8 [M,K], sx f32 [M] -> y f32 [M,N].  workspace: optional uint8 tensor
+    (mnnq_workspace_size bytes); with the matrix-core plane in `packed` it selects the fp6 GEMM."""
     _dev(packed, torch.uint8, "packed"); _dev(xq, torch.int8, "xq"); _dev(sx, torch.float32, "sx")
     M = xq.shape[0]
     if xq.shape[1] != K or sx.numel() != M:
         raise ValueError("xq must be [M,K] and sx [M]")
+    if workspace is not None:
+        _dev(workspace, torch.uint8, "workspace")
     y = torch.empty((M, N), dtype=torch.float32, device=packed.device) if out is None else out
     _check(lib().mnnq_linear_prefill(_ptr(packed), M, N, K, GROUP, mode, _ptr(xq), _ptr(sx),
-                                     _ptr(bias), _ptr(y), None, 0, _stream()), "mnnq_linear_prefill")
+                                     _ptr(bias), _ptr(y), _ptr(workspace),
+                                     0 if workspace is None else workspace.numel(), _stream()), "mnnq_linear_prefill")
     return y
+
+
+def mnnq_linear_acc_debug_planes(packed, N: int, K: int, xq, mode: int, workspace=None):
+    """int32 group accumulators [M,N,G] from the fp6 GEMM (mode must carry WITH_MATRIX_PLANE)."""
+    _dev(packed, torch.uint8, "packed"); _dev(xq, torch.int8, "xq")
+    M = xq.shape[0]
+    if workspace is None:
+        workspace = torch.empty(max(16, mnnq_workspace_size(M, N, K, GROUP, mode)), dtype=torch.uint8,
+                                device=packed.device)
+    acc = torch.empty((M, N, K // GROUP), dtype=torch.int32, device=packed.device)
+    _check(lib().mnnq_linear_acc_debug_planes(_ptr(packed), M, N, K, GROUP, mode, _ptr(xq), _ptr(acc),
+                                              _ptr(workspace), workspace.numel(), _stream()),
+           "mnnq_linear_acc_debug_planes")
+    return acc
+
+
+def mnnq_debug_force_plan(kernel: int, plan: int) -> None:
+    _check(lib().mnnq_debug_force_plan(kernel, plan), "mnnq_debug_force_plan")
 
 
 def mnnq_linear_decode_f16(packed, N: int, K: int, x16, bias=None, out=None, mode: int = MODE_W4_ZP_INT):
@@ -228,7 +255,7 @@ def mnnq_pack_from_quantized(q, scale, zero, out=None, mode: int = MODE_W4_ZP_IN
     """q u8 [N,K], scale f32 [N,G], zero u8 [N,G] (fp32 group minima in mode MODE_W4_MIN_FLOAT) on the
     GPU -> packed uint8 buffer."""
     _dev(q, torch.uint8, "q"); _dev(scale, torch.float32, "scale")
-    _dev(zero, torch.uint8 if mode == MODE_W4_ZP_INT else torch.float32, "zero")
+    _dev(zero, torch.uint8 if (mode & 15) == MODE_W4_ZP_INT else torch.float32, "zero")
     N, K = q.shape
     if tuple(scale.shape) != (N, K // GROUP) or tuple(zero.shape) != (N, K // GROUP):
         raise ValueError("scale and zero must be [N, K/%d]" % GROUP)

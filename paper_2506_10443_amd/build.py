@@ -13,11 +13,11 @@ LIB_DIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIB_DIR, "libmnnq.so")
 
 SOURCES = ["mnnq_api.hip", "mnnq_pack.hip", "mnnq_quant_act.hip", "mnnq_decode.hip",
-           "mnnq_prefill.hip", "mnnq_prefill_f16.hip", "mnnq_f16.hip", "mnnq_skinny.hip", "mnnq_peaks.hip"]
+           "mnnq_prefill.hip", "mnnq_prefill6.hip", "mnnq_prefill_f16.hip", "mnnq_f16.hip", "mnnq_skinny.hip", "mnnq_peaks.hip"]
 # The quantizers are fixed sequences of IEEE binary32 operations: no contraction.
 STRICT_FP = {"mnnq_pack.hip", "mnnq_quant_act.hip", "mnnq_decode.hip"}
 # MFMA results stay in architectural VGPRs so that the VALU epilogue reads them directly.
-MFMA_VGPR = {"mnnq_prefill.hip", "mnnq_prefill_f16.hip", "mnnq_skinny.hip", "mnnq_peaks.hip"}
+MFMA_VGPR = {"mnnq_prefill.hip", "mnnq_prefill6.hip", "mnnq_prefill6.hip", "mnnq_prefill_f16.hip", "mnnq_skinny.hip", "mnnq_peaks.hip"}
 
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
           "-fhip-fp32-correctly-rounded-divide-sqrt",

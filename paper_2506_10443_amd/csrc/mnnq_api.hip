@@ -26,9 +26,13 @@ constexpr int64_t kMaxM = 65535;
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 // Shape / mode checks shared by every call.  Returns MNNQ_OK or the error.
-int check_shape(int64_t N, int64_t K, int group, int mode)
+int check_shape(int64_t N, int64_t K, int group, int mode_and_flags)
 {
     if (N <= 0 || K <= 0) return MNNQ_ERR_SHAPE;
+    const int mode = mode_and_flags & kModeMask;
+    if (mode_and_flags < 0 || (mode_and_flags & ~(kModeMask | MNNQ_WITH_MATRIX_PLANE))) return MNNQ_ERR_UNSUPPORTED;
+    // the matrix-core plane holds q - zero: integer zero point form only
+    if ((mode_and_flags & MNNQ_WITH_MATRIX_PLANE) && mode != MNNQ_W4_ZP_INT) return MNNQ_ERR_UNSUPPORTED;
     if (group != kGroup || mode < MNNQ_W4_ZP_INT || mode > MNNQ_W8_MIN_FLOAT) return MNNQ_ERR_UNSUPPORTED;
     if (K % group != 0) return MNNQ_ERR_SHAPE;
     if (mode == MNNQ_W8_MIN_FLOAT && K % (2 * group) != 0) return MNNQ_ERR_UNSUPPORTED;   // whole chunks per plane
@@ -48,6 +52,10 @@ size_t fused_prefill_ws_bytes(int64_t M, int64_t K)
 {
     return fused_prefill_codes_bytes(M, K) + (size_t)((4 * M + 15) / 16 * 16);
 }
+
+// With the matrix-core plane in the packed buffer, a prefill call's workspace starts with the
+// activation planes (a multiple of 256 bytes); the fused call's codes and scales follow.
+size_t planes_ws_bytes(const Layout& L, int64_t M) { return prefill6_wanted(L, M) ? prefill6_ws_bytes(M, L.Kx) : 0; }
 
 // Above this many bytes of packed weights quantizing the row once, in a kernel of its own (about
 // 4 us), beats quantizing it in every workgroup (measured: 75 MiB 16.4 us fused against 4.2 + 14.6 us,
@@ -97,7 +105,8 @@ int decode_impl(const void* packed, int64_t N, int64_t K, int group, int mode, c
 }
 
 int prefill_impl(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode, const int8_t* xq,
-                 const float* sx, const float* bias, void* y, bool out16, void* workspace, void* stream)
+                 const float* sx, const float* bias, void* y, bool out16, void* workspace, size_t workspace_bytes,
+                 void* stream)
 {
     if (!packed || !xq || !sx || !y) return MNNQ_ERR_NULL;
     if (M <= 0) return MNNQ_ERR_SHAPE;
@@ -113,13 +122,17 @@ int prefill_impl(const void* packed, int64_t M, int64_t N, int64_t K, int group,
             const int64_t rows = M - m0 < slab ? M - m0 : slab;
             void* ys = static_cast<uint8_t*>(y) + (size_t)m0 * N * (out16 ? 2 : 4);
             if (int s = prefill_impl(packed, rows, N, K, group, mode, xq + m0 * K, sx + m0, bias, ys, out16, workspace,
-                                     stream))
+                                     workspace_bytes, stream))
                 return s;
         }
         return MNNQ_OK;
     }
     // A few tokens (batched or speculative decoding) are still memory-bound: one pass over the
     // weights in the GEMV's streaming order, all tokens at once in the matrix cores.
+    // With the matrix-core plane and room for the activations' planes: the GEMM on the fp6 matrix instructions.
+    if (prefill6_wanted(L, M) && workspace && workspace_bytes >= prefill6_ws_bytes(M, K))
+        return launch_prefill6(static_cast<const uint8_t*>(packed), L, M, xq, sx, bias, static_cast<float*>(y), nullptr,
+                               workspace, static_cast<hipStream_t>(stream));
     if (M <= 16 && !getenv("MNNQ_NO_SKINNY"))
         return launch_skinny(static_cast<const uint8_t*>(packed), L, M, xq, sx, bias, static_cast<float*>(y),
                              static_cast<hipStream_t>(stream));
@@ -196,10 +209,13 @@ int prefill_fused_impl(const void* packed, int64_t M, int64_t N, int64_t K, int 
     if (workspace_bytes < fused_prefill_ws_bytes(M, K)) return MNNQ_ERR_SIZE;
     if (misaligned(packed) || misaligned(x) || misaligned(workspace) || misaligned(y) || misaligned(bias))
         return MNNQ_ERR_ALIGN;
-    int8_t* xq = static_cast<int8_t*>(workspace);
+    // The activation planes of the fp6 GEMM lie in front when they fit as well (else: the int8 GEMM).
+    size_t planes = planes_ws_bytes(make_layout(N, K, mode), M);
+    if (workspace_bytes < planes + fused_prefill_ws_bytes(M, K)) planes = 0;
+    int8_t* xq = static_cast<int8_t*>(workspace) + planes;
     float* sx = reinterpret_cast<float*>(xq + fused_prefill_codes_bytes(M, K));
     if (int s = launch_quant_act(x, M, K, xq, sx, nullptr, static_cast<hipStream_t>(stream))) return s;
-    return prefill_impl(packed, M, N, K, group, mode, xq, sx, bias, y, out16, nullptr, stream);
+    return prefill_impl(packed, M, N, K, group, mode, xq, sx, bias, y, out16, planes ? workspace : nullptr, planes, stream);
 }
 
 // Scratch of mnnq_linear_prefill_fused_static: the int8 codes [M, K] and the scales [M] pass through
@@ -257,7 +273,7 @@ int mnnq_version(void) { return 100; }
 size_t mnnq_packed_size(int64_t N, int64_t K, int group, int mode)
 {
     if (check_shape(N, K, group, mode) != MNNQ_OK) return 0;
-    return make_layout(N, K, mode).total();
+    return make_layout(N, K, mode).full_total();
 }
 
 size_t mnnq_workspace_size(int64_t M, int64_t N, int64_t K, int group, int mode)
@@ -266,7 +282,7 @@ size_t mnnq_workspace_size(int64_t M, int64_t N, int64_t K, int group, int mode)
     // Split rows are combined inside a workgroup (decode) or directly in y (prefill): nothing
     // needs scratch.  The fused decode call can use room for the quantized row and its scale.
     if (M == 1) return fused_ws_bytes(K);
-    return M > 1 ? fused_prefill_ws_bytes(M, K) : 0;
+    return M > 1 ? planes_ws_bytes(make_layout(N, K, mode), M) + fused_prefill_ws_bytes(M, K) : 0;
 }
 
 int mnnq_pack_weights(const float* W, int64_t N, int64_t K, int group, int mode, void* packed,
@@ -276,8 +292,9 @@ int mnnq_pack_weights(const float* W, int64_t N, int64_t K, int group, int mode,
     if (int s = check_shape(N, K, group, mode)) return s;
     if (misaligned(W) || misaligned(packed)) return MNNQ_ERR_ALIGN;
     const Layout L = make_layout(N, K, mode);
-    if (packed_bytes < L.total()) return MNNQ_ERR_SIZE;
-    return launch_pack(W, L, static_cast<uint8_t*>(packed), static_cast<hipStream_t>(stream));
+    if (packed_bytes < L.full_total()) return MNNQ_ERR_SIZE;
+    if (int s = launch_pack(W, L, static_cast<uint8_t*>(packed), static_cast<hipStream_t>(stream))) return s;
+    return L.plane ? launch_plane_build(static_cast<uint8_t*>(packed), L, static_cast<hipStream_t>(stream)) : MNNQ_OK;
 }
 
 int mnnq_pack_from_quantized(const uint8_t* q, const float* scale, const void* zero, int64_t N, int64_t K,
@@ -287,10 +304,11 @@ int mnnq_pack_from_quantized(const uint8_t* q, const float* scale, const void* z
     if (int s = check_shape(N, K, group, mode)) return s;
     if (misaligned(q) || misaligned(packed)) return MNNQ_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(scale) & 3u) return MNNQ_ERR_ALIGN;
-    if (mode != MNNQ_W4_ZP_INT && (reinterpret_cast<uintptr_t>(zero) & 3u)) return MNNQ_ERR_ALIGN;
+    if ((mode & kModeMask) != MNNQ_W4_ZP_INT && (reinterpret_cast<uintptr_t>(zero) & 3u)) return MNNQ_ERR_ALIGN;
     const Layout L = make_layout(N, K, mode);
-    if (packed_bytes < L.total()) return MNNQ_ERR_SIZE;
-    return launch_repack(q, scale, zero, L, static_cast<uint8_t*>(packed), static_cast<hipStream_t>(stream));
+    if (packed_bytes < L.full_total()) return MNNQ_ERR_SIZE;
+    if (int s = launch_repack(q, scale, zero, L, static_cast<uint8_t*>(packed), static_cast<hipStream_t>(stream))) return s;
+    return L.plane ? launch_plane_build(static_cast<uint8_t*>(packed), L, static_cast<hipStream_t>(stream)) : MNNQ_OK;
 }
 
 int mnnq_unpack_weights(const void* packed, int64_t N, int64_t K, int group, int mode, uint8_t* q,
@@ -343,8 +361,7 @@ int mnnq_linear_prefill(const void* packed, int64_t M, int64_t N, int64_t K, int
                         const int8_t* xq, const float* sx, const float* bias, float* y, void* workspace,
                         size_t workspace_bytes, void* stream)
 {
-    (void)workspace_bytes;
-    return prefill_impl(packed, M, N, K, group, mode, xq, sx, bias, y, false, workspace, stream);
+    return prefill_impl(packed, M, N, K, group, mode, xq, sx, bias, y, false, workspace, workspace_bytes, stream);
 }
 
 int mnnq_linear_prefill_fused(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
@@ -366,6 +383,7 @@ int mnnq_linear_prefill_fused_static(const void* packed, int64_t M, int64_t N, i
     if (misaligned(packed) || misaligned(x) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
     if (!prefill_fits(M, N, K, mode) && prefill_slab_rows(N, K, mode) <= 0) return MNNQ_ERR_UNSUPPORTED;
     if (int s = static_scratch(&ws)) return s;
+    // (with the matrix-core plane, the fp6 GEMM runs when the activations' planes fit in the array too)
     return prefill_fused_impl(packed, M, N, K, group, mode, x, bias, y, false, ws, kStaticScratchBytes, stream);
 }
 
@@ -402,7 +420,7 @@ int mnnq_linear_decode_o16(const void* packed, int64_t N, int64_t K, int group, 
 int mnnq_linear_prefill_o16(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
                             const int8_t* xq, const float* sx, const float* bias, uint16_t* y16, void* stream)
 {
-    return prefill_impl(packed, M, N, K, group, mode, xq, sx, bias, y16, true, nullptr, stream);
+    return prefill_impl(packed, M, N, K, group, mode, xq, sx, bias, y16, true, nullptr, 0, stream);
 }
 
 int mnnq_linear_decode_f16_o16(const void* packed, int64_t N, int64_t K, int group, int mode, const uint16_t* x16,
@@ -428,11 +446,34 @@ int mnnq_plan_debug(int what, int64_t M, int64_t N, int64_t K, int group, int mo
     if (what == 0) {
         const int64_t slab = prefill_fits(M, N, K, mode) ? M : prefill_slab_rows(N, K, mode);
         if (slab <= 0) return MNNQ_ERR_UNSUPPORTED;
-        describe_prefill(L, slab < M ? slab : M, out8);   // (of the first slab, for batches beyond one launch)
+        const int64_t rows = slab < M ? slab : M;         // (of the first slab, for batches beyond one launch)
+        if (prefill6_wanted(L, rows)) describe_prefill6(L, rows, out8);   // (when the call is given its workspace)
+        else describe_prefill(L, rows, out8);
     } else {
         if (L.K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
         describe_decode(L, what == 2, out8);
     }
+    return MNNQ_OK;
+}
+
+int mnnq_linear_acc_debug_planes(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                                 const int8_t* xq, int32_t* acc, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!packed || !xq || !acc || !workspace) return MNNQ_ERR_NULL;
+    if (M <= 0) return MNNQ_ERR_SHAPE;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    const Layout L = make_layout(N, K, mode);
+    if (M > kMaxM || !prefill_fits(M, N, K, mode) || !prefill6_wanted(L, M)) return MNNQ_ERR_UNSUPPORTED;
+    if (workspace_bytes < prefill6_ws_bytes(M, K)) return MNNQ_ERR_SIZE;
+    if (misaligned(packed) || misaligned(xq) || misaligned(acc) || misaligned(workspace)) return MNNQ_ERR_ALIGN;
+    return launch_prefill6(static_cast<const uint8_t*>(packed), L, M, xq, nullptr, nullptr, nullptr, acc, workspace,
+                           static_cast<hipStream_t>(stream));
+}
+
+int mnnq_debug_force_plan(int kernel, int plan)
+{
+    if (kernel != 6 || plan < -1 || plan > 4) return MNNQ_ERR_UNSUPPORTED;
+    set_prefill6_plan(plan);
     return MNNQ_OK;
 }
 

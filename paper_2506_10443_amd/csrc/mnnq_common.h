@@ -44,6 +44,19 @@ constexpr int kChunkBytes = 1024;
 // 0..G-1 hold the high nibbles with step 16 s and the group minimum, groups G..2G-1 the low
 // nibbles with step s and minimum 0 - so that q8 s + min = hi (16 s) + min + lo s.  The
 // activation row is not doubled: chunk c of the packed matrix meets chunk c % Cx of the row.
+// Matrix-core plane (mode flag MNNQ_WITH_MATRIX_PLANE): a second copy of the int4 weights behind the
+// chunk layout, as the B operand of the fp6 matrix instruction v_mfma_scale_f32_32x32x64_f8f6f4 -
+// every q - zero (|q - zero| <= 15) is the e2m3 value (q - zero) / 8 exactly, and its code is the
+// sign-magnitude form of q - zero.  Unit: column tile tn = n / 32 and group g (64 values of K):
+//   codes  [G][T32p][1536 B]: lane l (0..63) holds column 32 tn + l % 32 and the 32 values
+//          k = 64 g + 32 (l / 32) + j, j = 0..31, code j at bits [6 j, 6 j + 6) of its 192 bits;
+//          dwords 0..3 of lane l at byte 16 l, dwords 4..5 at byte 1024 + 8 l of the block;
+//   scales [G][T32p][32] fp32 behind the codes.
+// T32p = column tiles rounded up to a multiple of 8 (zero codes and scales in the padding), so that a
+// workgroup's tile of up to 256 columns is one contiguous, in-range piece per group.
+constexpr int kPlaneBlockBytes = 1536;
+constexpr int kPlaneTilePad = 8;
+
 struct Layout {
     int64_t N, K;   // K: length of the packed reduction axis (2 x the row length for int8 weights)
     int64_t Kx;     // length of an activation row
@@ -55,14 +68,30 @@ struct Layout {
     int64_t G;  // groups per row
     int64_t C;  // chunks per row tile
     size_t codes_bytes, scales_bytes, zeros_bytes;
+    bool plane;       // the packed buffer carries the matrix-core plane behind the chunk layout
+    int64_t T32p;     // column tiles of 32 in the plane (padded to a multiple of 8)
+    int64_t Gx;       // quantization groups of an activation row (= groups of the plane)
     __host__ __device__ size_t scales_off() const { return codes_bytes; }
     __host__ __device__ size_t zeros_off() const { return codes_bytes + scales_bytes; }
+    // bytes of the chunk layout (what the decode kernels and the int8 GEMM read)
     __host__ __device__ size_t total() const { return codes_bytes + scales_bytes + zeros_bytes; }
+    __host__ __device__ size_t plane_off() const { return (total() + 255) / 256 * 256; }
+    __host__ __device__ size_t plane_codes_bytes() const { return (size_t)Gx * T32p * kPlaneBlockBytes; }
+    __host__ __device__ size_t plane_scales_bytes() const { return (size_t)Gx * T32p * 32 * sizeof(float); }
+    __host__ __device__ size_t plane_bytes() const { return plane_codes_bytes() + plane_scales_bytes(); }
+    // bytes of the whole packed buffer
+    __host__ __device__ size_t full_total() const { return plane ? plane_off() + plane_bytes() : total(); }
 };
 
-inline __host__ __device__ Layout make_layout(int64_t N, int64_t K, int mode = MNNQ_W4_ZP_INT)
+constexpr int kModeMask = 15;
+
+inline __host__ __device__ Layout make_layout(int64_t N, int64_t K, int mode_and_flags = MNNQ_W4_ZP_INT)
 {
     Layout L;
+    const int mode = mode_and_flags & kModeMask;
+    L.plane = (mode_and_flags & MNNQ_WITH_MATRIX_PLANE) != 0;
+    L.T32p = ((N + 31) / 32 + kPlaneTilePad - 1) / kPlaneTilePad * kPlaneTilePad;
+    L.Gx = K / kGroup;
     L.N = N;
     L.Kx = K;
     L.K = (mode == MNNQ_W8_MIN_FLOAT) ? 2 * K : K;
@@ -190,6 +219,15 @@ int launch_decode_acc(const uint8_t* packed, const Layout& L, int64_t M, const i
                       int32_t* acc, hipStream_t st);
 int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq,
                    const float* sx, const float* bias, float* y, int32_t* acc_debug, hipStream_t st);
+// GEMM on the fp6 matrix instructions (mnnq_prefill6.hip): needs the matrix-core plane in the packed
+// buffer and `planes_ws`, prefill6_ws_bytes(M, K) bytes of scratch for the activation planes.
+int launch_plane_build(uint8_t* packed, const Layout& L, hipStream_t st);
+int launch_prefill6(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
+                    const float* bias, float* y, int32_t* acc_debug, void* planes_ws, hipStream_t st);
+size_t prefill6_ws_bytes(int64_t M, int64_t K);
+bool prefill6_wanted(const Layout& L, int64_t M);
+void describe_prefill6(const Layout& L, int64_t M, int32_t out[8]);
+void set_prefill6_plan(int plan);   // tests: -1 = chosen from the shape, 0..4 = that tile plan
 // M <= 16 tokens sharing one pass over the weights.
 int launch_skinny(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
                   const float* bias, float* y, hipStream_t st);

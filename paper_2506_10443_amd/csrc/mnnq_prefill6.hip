@@ -1,0 +1,529 @@
+// Prefill (M tokens) on the fp6 matrix instructions of gfx950 (Section 2.1: the compute-bound phase;
+// Section 5.1: operands rearranged once so that the inner loop reads what one instruction consumes).
+//
+//   y[m,n] = sx[m] * sum_g scale[n,g] * I[m,n,g] (+ bias[n]),   I = sum_{k in g} xq[m,k] (q[n,k] - zero[n,g])
+//
+// Why not the int8 instruction: its int32 result needs two vector operations per output and group
+// (to fp32, multiply-add with the group's scale), and on this chip a SIMD issues vector and matrix
+// instructions one after the other, not side by side - the epilogue, not the matrix pipe, sets the
+// pace.  v_mfma_scale_f32_32x32x64_f8f6f4 with fp6 (e2m3) operands runs at the same rate per group as the
+// int8 form and delivers the group sum in fp32, which leaves one multiply-add per output and group:
+//   * an e2m3 number is (-1)^s * m / 8 for m = 0..15 (and coarser above), so every integer of
+//     magnitude <= 15 is exact: the weight operand is (q - zero) / 8, its code the sign-magnitude
+//     form of q - zero;
+//   * an int8 activation is split as xq = 16 hi + lo with lo = xq & 15 (0..15) and hi = xq >> 4
+//     (-8..7), both exact as well; one instruction contracts the 64 high parts of a group with the
+//     weights, a second one the low parts, accumulating on the first; the instruction's power-of-two
+//     operand scale (2^10 resp. 2^6 on the activation side) puts back the 16 and the two divisions by 8;
+//   * all products and the sums (|I| <= 64 * 127 * 15 < 2^17) are integers, exact in fp32, so the
+//     result is the int32 group accumulator, bit for bit (the accumulator dump of this kernel is
+//     compared with the oracle's integers).
+// Both operands are prepared ahead: the weights at load time (the matrix-core plane of the packed
+// buffer, see mnnq_common.h), the activations by a small kernel per call (planes_kernel below), so
+// the GEMM's loop holds nothing but LDS reads, matrix instructions and the multiply-adds.
+//
+// Lane mapping of the 32x32x64 instruction as used here (A: 32 x 64, B: 64 x 32, D: 32 x 32):
+//   A / B operand: lane l holds row / column l % 32 and the 32 values of k-block l / 32, value j at
+//                  bits [6 j, 6 j + 6) of six registers; one scale byte per lane covers its 32 values;
+//   D: lane l holds column l % 32, rows 8 (r / 4) + 4 (l / 32) + r % 4 for r = 0..15.
+#include "mnnq_common.h"
+
+namespace mnnq {
+
+namespace {
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+#define MNNQ_LDS(p) ((__attribute__((address_space(3))) void*)(p))
+
+constexpr int kBufFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family)
+constexpr int kOutOfRange = 0x7ffffff0; // a byte offset beyond every buffer: loads give 0, stores are dropped
+
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// ---------------------------------------------------------------------------------------------
+// fp6 packing.  c[0..7]: 32 six-bit codes, one per byte, code j in byte j % 4 of c[j / 4].
+// out[0..5]: the same codes at bits [6 j, 6 j + 6).
+__device__ __forceinline__ uint32_t pack24(uint32_t c)
+{
+    return (c & 0x3fu) | ((c >> 2) & 0xfc0u) | ((c >> 4) & 0x3f000u) | ((c >> 6) & 0xfc0000u);
+}
+
+__device__ __forceinline__ void pack_fp6(const uint32_t (&c)[8], uint32_t (&out)[6])
+{
+    const uint32_t p0 = pack24(c[0]), p1 = pack24(c[1]), p2 = pack24(c[2]), p3 = pack24(c[3]);
+    const uint32_t p4 = pack24(c[4]), p5 = pack24(c[5]), p6 = pack24(c[6]), p7 = pack24(c[7]);
+    out[0] = p0 | (p1 << 24);
+    out[1] = (p1 >> 8) | (p2 << 16);
+    out[2] = (p2 >> 16) | (p3 << 8);
+    out[3] = p4 | (p5 << 24);
+    out[4] = (p5 >> 8) | (p6 << 16);
+    out[5] = (p6 >> 16) | (p7 << 8);
+}
+
+// Sign-magnitude six-bit codes of four small integers held as bytes 0x80 + v (|v| <= 15).
+__device__ __forceinline__ uint32_t signmag_from_biased(uint32_t b)
+{
+    uint32_t r = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int v = (int)((b >> (8 * i)) & 0xffu) - 0x80;
+        const uint32_t code = v < 0 ? (32u | (uint32_t)(-v)) : (uint32_t)v;
+        r |= code << (8 * i);
+    }
+    return r;
+}
+
+// One block (1536 B) of a plane: dwords 0..3 of lane l at 16 l, dwords 4..5 at 1024 + 8 l.
+__device__ __forceinline__ void store_block(uint8_t* block, int lane, const uint32_t (&d)[6])
+{
+    *reinterpret_cast<uint4*>(block + lane * 16) = make_uint4(d[0], d[1], d[2], d[3]);
+    *reinterpret_cast<uint2*>(block + 1024 + lane * 8) = make_uint2(d[4], d[5]);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Load time: the matrix-core plane from the chunk layout in front of it (one wave per group and
+// column tile of 32).
+__global__ __launch_bounds__(256) void plane_build_kernel(uint8_t* __restrict__ packed, Layout L)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t blk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (blk >= L.Gx * L.T32p) return;
+    // (the few bytes between the chunk layout and the plane's 256-byte boundary: zero, so that equal
+    // weights give equal buffers)
+    if (blk == 0)
+        for (size_t i = L.total() + lane; i < L.plane_off(); i += 64) packed[i] = 0;
+    const int64_t g = blk / L.T32p, tn = blk % L.T32p;
+    const int col = lane & 31, kb = lane >> 5;
+    const int64_t n = tn * 32 + col;
+    uint32_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    float scale = 0.0f;
+    if (n < L.N) {
+        const int64_t t16 = n / 16, chunk = g / 2;
+        const int r16 = (int)(n % 16), h = (int)(g & 1);
+        const int64_t cell = t16 * L.C + chunk;
+        const uint32_t z = packed[L.zeros_off() + (cell * 16 + r16) * 2 + h];
+        scale = *reinterpret_cast<const float*>(packed + L.scales_off() + (cell * 16 + r16) * 8 + h * 4);
+        const uint32_t bias4 = 0x80808080u - z * 0x01010101u;     // 0x80 - zero in every byte
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int lane16 = r16 + 16 * (2 * kb + half);
+            const uint2 w = *reinterpret_cast<const uint2*>(packed + (cell * 64 + lane16) * 16 + 8 * h);
+            c[half * 4 + 0] = signmag_from_biased((w.x & 0x0f0f0f0fu) + bias4);
+            c[half * 4 + 1] = signmag_from_biased(((w.x >> 4) & 0x0f0f0f0fu) + bias4);
+            c[half * 4 + 2] = signmag_from_biased((w.y & 0x0f0f0f0fu) + bias4);
+            c[half * 4 + 3] = signmag_from_biased(((w.y >> 4) & 0x0f0f0f0fu) + bias4);
+        }
+    }
+    uint32_t d[6];
+    pack_fp6(c, d);
+    uint8_t* plane = packed + L.plane_off();
+    store_block(plane + blk * kPlaneBlockBytes, lane, d);
+    if (lane < 32) *reinterpret_cast<float*>(plane + L.plane_codes_bytes() + blk * 128 + lane * 4) = scale;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Per call: the activation planes [Gx][TMp][2][1536 B] from the int8 codes [M, K] - block (g, tm, 0)
+// the high parts hi = xq >> 4, block (g, tm, 1) the low parts lo = xq & 15 of rows 32 tm .. 32 tm + 31
+// and group g, lane l holding row l % 32 and k = 64 g + 32 (l / 32) + j.  Rows past M are zero.
+// One wave per (tm, g); consecutive waves take consecutive groups of the same rows, so that the
+// 128-byte lines of xq (two groups each) are fetched once.
+__global__ __launch_bounds__(256) void planes_kernel(const int8_t* __restrict__ xq, int64_t M, int64_t K, int Gx,
+                                                     int TMp, uint8_t* __restrict__ out)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wid = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (wid >= (int64_t)Gx * TMp) return;
+    const int64_t tm = wid / Gx, g = wid % Gx;
+    const int64_t m = tm * 32 + (lane & 31);
+    uint32_t x[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (m < M) {
+        const uint4* p = reinterpret_cast<const uint4*>(xq + m * K + g * 64 + (lane >> 5) * 32);
+        const uint4 a = p[0], b = p[1];
+        x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+        x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+    }
+    uint32_t hi[8], lo[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        lo[i] = x[i] & 0x0f0f0f0fu;                       // 0..15: its own code
+        const uint32_t h = (x[i] >> 4) & 0x0f0f0f0fu;     // hi as a 4-bit two's complement number
+        const uint32_t neg = (h >> 3) & 0x01010101u;      // 1 in the bytes with hi < 0
+        const uint32_t m15 = (neg << 4) - neg;            // 15 there
+        hi[i] = ((h ^ m15) + neg) | (neg << 5);           // magnitude 16 - h resp. h, sign in bit 5
+    }
+    uint32_t dh[6], dl[6];
+    pack_fp6(hi, dh);
+    pack_fp6(lo, dl);
+    uint8_t* block = out + ((g * TMp + tm) * 2) * (int64_t)kPlaneBlockBytes;
+    store_block(block, lane, dh);
+    store_block(block + kPlaneBlockBytes, lane, dl);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The GEMM.  Workgroup tile BM x BN, K range in KS parts of WM x WN waves each; a wave owns
+// TMW x TNW tiles of 32 x 32.  Per group (stage): BM * 96 bytes of activation planes, BN * 48 bytes
+// of weight plane and BN scales travel verbatim from memory to LDS with direct 128-bit loads.
+template <int BM, int BN>
+struct Stage {
+    static constexpr int A_BYTES = BM * 96;
+    static constexpr int B_BYTES = BN * 48;
+    static constexpr int S_BYTES = 1024;             // BN <= 256 scales, one wave-wide load
+    static constexpr int B_OFF = A_BYTES;
+    static constexpr int S_OFF = A_BYTES + B_BYTES;
+    static constexpr int BYTES = A_BYTES + B_BYTES + S_BYTES;
+    static constexpr int NA = A_BYTES / 1024, NB = B_BYTES / 1024;
+    static_assert(A_BYTES % 1024 == 0 && B_BYTES % 1024 == 0 && BN <= 256, "whole wave-wide loads");
+};
+
+// LDS of a workgroup: the stages of every K part and the junk kilobyte, or the K parts' sums when
+// those need more (they are exchanged after the last stage is dead).
+template <int BM, int BN, int WM, int WN, int KS, int NS>
+constexpr size_t lds_bytes6()
+{
+    const size_t stages = (size_t)KS * NS * Stage<BM, BN>::BYTES + 1024;
+    const size_t sums = KS > 1 ? (size_t)(BM / 32) * (BN / 32) * 16 * 64 * 4 : 0;
+    return stages > sums ? stages : sums;
+}
+
+__device__ __forceinline__ v8i frag6(const uint8_t* block, int lane)
+{
+    const v4i p0 = *reinterpret_cast<const v4i*>(block + lane * 16);
+    const v2i p1 = *reinterpret_cast<const v2i*>(block + 1024 + lane * 8);
+    return v8i{p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, 0, 0};
+}
+
+// D = A x B + C on fp6 (e2m3) operands with per-lane power-of-two operand scales.
+__device__ __forceinline__ v16f mfma6(v8i a, v8i b, v16f c, int scale_a, int scale_b)
+{
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 2, 2, 0, scale_a, 0, scale_b);
+}
+
+template <int BM, int BN, int WM, int WN, int KS, int NS, bool ACC>
+__global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
+    const uint8_t* __restrict__ plane, const uint8_t* __restrict__ a6, Layout L, int64_t M, int TMp,
+    const float* __restrict__ sx, const float* __restrict__ bias, float* __restrict__ y,
+    int32_t* __restrict__ acc_out, int MT, int NT)
+{
+    using St = Stage<BM, BN>;
+    constexpr int W = WM * WN;                        // waves per K part
+    constexpr int TMW = BM / WM / 32, TNW = BN / WN / 32;
+    constexpr int NL = (St::NA + St::NB + 1 + W - 1) / W;   // direct loads per wave and stage
+    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "whole 32 x 32 tiles per wave");
+    static_assert(KS == 1 || (size_t)W * TMW * TNW * 16 * 64 * 4 <= lds_bytes6<BM, BN, WM, WN, KS, NS>(),
+                  "the K parts' sums must fit in LDS");
+    static_assert(NS == 2 || NS == 3, "two or three stages");
+
+    extern __shared__ __align__(16) uint8_t lds_all[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave_id = uniform(tid >> 6);
+    const int part = wave_id / W;                    // K part of this wave
+    const int w = wave_id % W;
+    const int wm = w / WN, wn = w % WN;
+    uint8_t* const lds = lds_all + part * (NS * St::BYTES);
+    uint8_t* const junk = lds_all + KS * NS * St::BYTES;
+
+    // Workgroups are dealt to the 8 XCDs round-robin by their linear id: each XCD gets whole columns
+    // of output tiles, so that a block of weights is fetched into one L2 only.
+    const int xcd = blockIdx.x % 8;
+    const int seq = blockIdx.x / 8;
+    const int tile_m = seq % MT;
+    const int tile_n = (seq / MT) * 8 + xcd;
+    if (tile_n >= NT) return;
+    const int G = (int)L.Gx;
+    const int gb = G * part / KS, ge = G * (part + 1) / KS;      // this part's groups
+    const int n_iter = (G + KS - 1) / KS;                        // the longest share: every wave runs the same barriers
+
+    const __amdgpu_buffer_rsrc_t rs_a = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(a6), 0, (int)((int64_t)G * TMp * 2 * kPlaneBlockBytes), kBufFlags);
+    const __amdgpu_buffer_rsrc_t rs_w =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(plane), 0, (int)L.plane_bytes(), kBufFlags);
+
+    const int a_base = tile_m * (BM / 32) * 2 * kPlaneBlockBytes, a_step = TMp * 2 * kPlaneBlockBytes;
+    const int w_base = tile_n * (BN / 32) * kPlaneBlockBytes, w_step = (int)L.T32p * kPlaneBlockBytes;
+    const int s_base = (int)L.plane_codes_bytes() + tile_n * (BN / 32) * 128, s_step = (int)L.T32p * 128;
+    const int voff = lane * 16;
+
+    // Stage `buf` <- group g: this wave's NL pieces of 1 KiB (slots past the stage's pieces go to a
+    // junk kilobyte with an out-of-range source, so that every wave has the same number of loads in
+    // flight and can wait by count).
+    auto issue_stage = [&](int g, int buf) {
+        uint8_t* st = lds + buf * St::BYTES;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int s = w + W * i;   // wave-uniform
+            // (the offsets are named before the calls: with the expressions written into a 128-bit direct
+            // load's argument list this toolchain's host pass drops the kernel without a message)
+            const int so_a = uniform(a_base + g * a_step + s * 1024);
+            const int so_w = uniform(w_base + g * w_step + (s - St::NA) * 1024);
+            const int so_s = uniform(s_base + g * s_step);
+            if (s < St::NA)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, MNNQ_LDS(st + s * 1024), 16, voff,
+                                                         so_a, 0, 0);
+            else if (s < St::NA + St::NB)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(st + St::B_OFF + (s - St::NA) * 1024), 16, voff,
+                                                         so_w, 0, 0);
+            else if (s == St::NA + St::NB)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(st + St::S_OFF), 16, voff,
+                                                         so_s, 0, 0);
+            else
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(junk), 16, voff, kOutOfRange, 0, 0);
+        }
+    };
+
+    float yacc[TMW * TNW][16];
+#pragma unroll
+    for (int t = 0; t < TMW * TNW; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) yacc[t][r] = 0.0f;
+
+    // operand scales (one byte per lane, 2^(b - 127)): operands are value / 8 each, the high parts weigh 16
+    int scale_hi = 127 + 10, scale_lo = 127 + 6, scale_b = 127;
+    asm volatile("" : "+v"(scale_hi), "+v"(scale_lo), "+v"(scale_b));
+    const v16f zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) issue_stage(gb + s, s);
+
+    for (int it = 0; it < n_iter; ++it) {
+        const int g = gb + it;
+        const int buf = it % NS;
+        // This wave's pieces of stage `it` have landed (later stages may still be in flight); after the
+        // barrier everybody's have, and everybody is done with the stage that is loaded over next.
+        if (NS == 3) __builtin_amdgcn_s_waitcnt(0x0F70 | (NL & 15) | ((NL >> 4) << 14));   // vmcnt(NL)
+        else __builtin_amdgcn_s_waitcnt(0x0F70);                                             // vmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        const uint8_t* st = lds + buf * St::BYTES;
+
+        v8i ahi[TMW], alo[TMW], b[TNW];
+        float sc[TNW];
+        if (KS == 1 || g < ge) {
+#pragma unroll
+            for (int j = 0; j < TNW; ++j) {
+                b[j] = frag6(st + St::B_OFF + (wn * TNW + j) * kPlaneBlockBytes, lane);
+                sc[j] = *reinterpret_cast<const float*>(st + St::S_OFF + (wn * TNW + j) * 128 + (lane & 31) * 4);
+            }
+#pragma unroll
+            for (int i = 0; i < TMW; ++i) {
+                ahi[i] = frag6(st + (wm * TMW + i) * 2 * kPlaneBlockBytes, lane);
+                alo[i] = frag6(st + (wm * TMW + i) * 2 * kPlaneBlockBytes + kPlaneBlockBytes, lane);
+            }
+        }
+        issue_stage(g + NS - 1, (it + NS - 1) % NS);
+        if (KS > 1 && g >= ge) continue;   // the shorter share idles through the last round
+
+        // Tile t + 1's two matrix instructions are issued ahead of tile t's sixteen multiply-adds.
+        v16f d[2];
+        d[0] = mfma6(ahi[0], b[0], zero16, scale_hi, scale_b);
+        d[0] = mfma6(alo[0], b[0], d[0], scale_lo, scale_b);
+#pragma unroll
+        for (int t = 0; t < TMW * TNW; ++t) {
+            const int i = t / TNW, j = t % TNW;
+            if (t + 1 < TMW * TNW) {
+                const int i1 = (t + 1) / TNW, j1 = (t + 1) % TNW;
+                d[(t + 1) & 1] = mfma6(ahi[i1], b[j1], zero16, scale_hi, scale_b);
+                d[(t + 1) & 1] = mfma6(alo[i1], b[j1], d[(t + 1) & 1], scale_lo, scale_b);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (ACC) {
+                const int64_t n = (int64_t)tile_n * BN + (wn * TNW + j) * 32 + (lane & 31);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t m = (int64_t)tile_m * BM + (wm * TMW + i) * 32 + 8 * (r / 4) + 4 * (lane >> 5) + r % 4;
+                    if (m < M && n < L.N) acc_out[(m * L.N + n) * G + g] = (int32_t)d[t & 1][r];
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) yacc[t][r] = fmaf(sc[j], d[t & 1][r], yacc[t][r]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    if (ACC) return;
+
+    if (KS > 1) {
+        // Add the K parts in a fixed order: part p > 0 leaves its sums in LDS, part 0 adds them.
+        float* red = reinterpret_cast<float*>(lds_all);
+        const int slot = w * (TMW * TNW * 16 * 64) + lane;
+#pragma unroll
+        for (int p = 1; p < KS; ++p) {
+            __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0): no direct load may still land in LDS
+            __builtin_amdgcn_s_barrier();
+            if (part == p) {
+#pragma unroll
+                for (int t = 0; t < TMW * TNW; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) red[slot + (t * 16 + r) * 64] = yacc[t][r];
+            }
+            __builtin_amdgcn_s_waitcnt(0x0070);
+            __builtin_amdgcn_s_barrier();
+            if (part == 0) {
+#pragma unroll
+                for (int t = 0; t < TMW * TNW; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) yacc[t][r] += red[slot + (t * 16 + r) * 64];
+            }
+        }
+        if (part != 0) return;
+    }
+
+    // Output: y = yacc * sx[m] + bias[n].  Buffer accesses: rows past M fall outside the buffers (loads
+    // give 0, stores are dropped), columns past N are sent out of range, a NULL bias is an empty buffer.
+    const __amdgpu_buffer_rsrc_t rs_sx =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(sx), 0, (int)(M * 4), kBufFlags);
+    const __amdgpu_buffer_rsrc_t rs_bias =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(bias), 0, bias ? (int)(L.N * 4) : 0, kBufFlags);
+    const int y_bytes = (int)(uint32_t)(M * L.N * (L.out16 ? 2 : 4));
+    const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(y, 0, y_bytes, kBufFlags);
+    const int N = (int)L.N;
+    const int row0 = tile_m * BM + wm * TMW * 32;
+    const int col0 = tile_n * BN + wn * TNW * 32;
+    const int esz = L.out16 ? 2 : 4;
+#pragma unroll
+    for (int j = 0; j < TNW; ++j) {
+        const int n = col0 + j * 32 + (lane & 31);
+        const float bj = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_bias, (lane & 31) * 4, (col0 + j * 32) * 4, 0));
+        const int y_voff = n < N ? ((lane >> 5) * 4 * N + (lane & 31)) * esz : kOutOfRange;
+#pragma unroll
+        for (int i = 0; i < TMW; ++i) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int mrow = row0 + i * 32 + 8 * q;     // + 4 (lane / 32) + r % 4
+                const v4i s4 = __builtin_amdgcn_raw_buffer_load_b128(rs_sx, (lane >> 5) * 16, mrow * 4, 0);
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const float v = fmaf(yacc[i * TNW + j][q * 4 + rr], __int_as_float(s4[rr]), bj);
+                    const int soff = ((mrow + rr) * N + col0 + j * 32) * esz;
+                    if (L.out16) {
+                        const _Float16 hv = (_Float16)v;
+                        __builtin_amdgcn_raw_buffer_store_b16(*reinterpret_cast<const short*>(&hv), rs_y, y_voff, soff, 0);
+                    } else {
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs_y, y_voff, soff, 0);
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WM, int WN, int KS, int NS, bool ACC>
+int launch6(const uint8_t* packed, const Layout& L, int64_t M, const uint8_t* a6, int TMp, const float* sx,
+            const float* bias, float* y, int32_t* acc, hipStream_t st)
+{
+    const int MT = (int)((M + BM - 1) / BM);
+    const int NT = (int)((L.N + BN - 1) / BN);
+    constexpr size_t smem = lds_bytes6<BM, BN, WM, WN, KS, NS>();
+    static_assert(smem <= kLdsPerWorkgroup, "LDS of a workgroup");
+    auto kern = prefill6_kernel<BM, BN, WM, WN, KS, NS, ACC>;
+    static thread_local int allowed_dev = -1;
+    if (int s = allow_large_lds(kern, smem, allowed_dev)) return s;
+    const int64_t blocks = (int64_t)MT * ((NT + 7) / 8) * 8;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * WM * WN * KS), smem, st, packed + L.plane_off(), a6, L, M,
+                       TMp, sx, bias, y, acc, MT, NT);
+    MNNQ_HIP_TRY(hipGetLastError());
+    return MNNQ_OK;
+}
+
+int tmp_tiles(int64_t M) { return (int)(((M + 31) / 32 + kPlaneTilePad - 1) / kPlaneTilePad * kPlaneTilePad); }
+
+// Tile plan: 0 = 128 x 128 tiles of four waves (two workgroups per CU), 1 = 128 x 128 with the K range
+// in two parts (eight waves), 2 = 128 x 192 with two K parts, 3 = 128 x 256 of eight waves,
+// 4 = 256 x 256 of eight waves.
+int g_force_plan6 = -1;
+
+int choose_plan6(const Layout& L, int64_t M)
+{
+    if (g_force_plan6 >= 0) return g_force_plan6;
+    const int64_t cus = num_cus();
+    auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((L.N + bn - 1) / bn); };
+    auto eff = [&](int64_t t, int64_t slots) { return (double)t / (double)((t + slots - 1) / slots * slots); };
+    // how well each form fills the chip, times what its wave tile is worth
+    const double e0 = eff(tiles(128, 128), 2 * cus) * 1.00;
+    const double e1 = eff(tiles(128, 128), cus) * 0.97;
+    const double e2 = eff(tiles(128, 192), cus) * 1.00;
+    const double e3 = eff(tiles(128, 256), cus) * 1.00;
+    int best = 0;
+    double eb = e0;
+    if (e1 > eb) { best = 1; eb = e1; }
+    if (e2 > eb) { best = 2; eb = e2; }
+    if (e3 > eb) { best = 3; eb = e3; }
+    return best;
+}
+
+struct Plan6Info {
+    int BM, BN, KS, waves;
+    size_t lds;
+};
+
+Plan6Info plan6_info(int plan)
+{
+    switch (plan) {
+        case 1: return {128, 128, 2, 8, lds_bytes6<128, 128, 2, 2, 2, 2>()};
+        case 2: return {128, 192, 2, 8, lds_bytes6<128, 192, 2, 2, 2, 2>()};
+        case 3: return {128, 256, 1, 8, lds_bytes6<128, 256, 2, 4, 1, 2>()};
+        case 4: return {256, 256, 1, 8, lds_bytes6<256, 256, 4, 2, 1, 2>()};
+        default: return {128, 128, 1, 4, lds_bytes6<128, 128, 2, 2, 1, 2>()};
+    }
+}
+
+}  // namespace
+
+void set_prefill6_plan(int plan) { g_force_plan6 = plan; }
+
+size_t prefill6_ws_bytes(int64_t M, int64_t K) { return (size_t)(K / kGroup) * tmp_tiles(M) * 2 * kPlaneBlockBytes; }
+
+bool prefill6_wanted(const Layout& L, int64_t M)
+{
+    const int64_t lim = ((int64_t)1 << 31) - 1;
+    return L.plane && L.mode == MNNQ_W4_ZP_INT && M > 32 && (int64_t)L.plane_bytes() <= lim &&
+           (int64_t)prefill6_ws_bytes(M, L.Kx) <= lim;
+}
+
+void describe_prefill6(const Layout& L, int64_t M, int32_t out[8])
+{
+    const Plan6Info p = plan6_info(choose_plan6(L, M));
+    const int64_t MT = (M + p.BM - 1) / p.BM, NT = (L.N + p.BN - 1) / p.BN;
+    out[0] = p.BM;
+    out[1] = p.BN;
+    out[2] = p.KS;
+    out[3] = 1;
+    out[4] = p.waves;
+    out[5] = (int32_t)p.lds;
+    out[6] = (int32_t)(MT * ((NT + 7) / 8) * 8);
+    out[7] = 6;   // operands in fp6
+}
+
+int launch_plane_build(uint8_t* packed, const Layout& L, hipStream_t st)
+{
+    const int64_t blocks = (L.Gx * L.T32p + 3) / 4;
+    hipLaunchKernelGGL(plane_build_kernel, dim3((unsigned)blocks), dim3(256), 0, st, packed, L);
+    MNNQ_HIP_TRY(hipGetLastError());
+    return MNNQ_OK;
+}
+
+int launch_prefill6(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
+                    const float* bias, float* y, int32_t* acc_debug, void* planes_ws, hipStream_t st)
+{
+    const int TMp = tmp_tiles(M);
+    const int Gx = (int)L.Gx;
+    uint8_t* a6 = static_cast<uint8_t*>(planes_ws);
+    const int64_t waves = (int64_t)Gx * TMp;
+    hipLaunchKernelGGL(planes_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, xq, M, L.Kx, Gx, TMp, a6);
+    MNNQ_HIP_TRY(hipGetLastError());
+    if (acc_debug) return launch6<128, 128, 2, 2, 1, 2, true>(packed, L, M, a6, TMp, sx, bias, y, acc_debug, st);
+    switch (choose_plan6(L, M)) {
+        case 1: return launch6<128, 128, 2, 2, 2, 2, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
+        case 2: return launch6<128, 192, 2, 2, 2, 2, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
+        case 3: return launch6<128, 256, 2, 4, 1, 2, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
+        case 4: return launch6<256, 256, 4, 2, 1, 2, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
+        default: return launch6<128, 128, 2, 2, 1, 2, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
+    }
+}
+
+}  // namespace mnnq

@@ -1,0 +1,111 @@
+"""GPU parity of the GEMM on the fp6 matrix instructions (packed buffers with the matrix-core plane,
+mode MNNQ_W4_ZP_INT | MNNQ_WITH_MATRIX_PLANE) against the CPU oracle: the int32 group accumulators
+bit-exact for every tile plan, y within 1e-5 * max|y|, and bit-identical codes in front of the plane."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2506_10443_amd import binding as B, synth
+
+pytestmark = pytest.mark.gpu
+
+MODE = B.MODE_W4_ZP_INT | B.WITH_MATRIX_PLANE
+TOL_A8 = 1e-5
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def note(*a):
+    print(*a, flush=True)
+
+
+@pytest.fixture(autouse=True)
+def _auto_plan():
+    yield
+    B.mnnq_debug_force_plan(6, -1)
+
+
+def make(N, K, M, seed, special=False):
+    W = synth.weights(N, K, seed)
+    if special:
+        W[0, :64] = 0.0
+        W[1, :64] = np.abs(W[1, :64]) + 0.01
+        W[2, :64] = -np.abs(W[2, :64]) - 0.01
+        t = np.zeros(64, np.float32); t[:9] = [-3.5, 11.5, 0.5, 1.5, 2.5, -0.5, -2.5, -1.5, 0.0]
+        W[4, :64] = t
+    x = synth.activations(M, K, seed + 1, outliers=True)
+    if special:
+        x[0, :] = 0.0                       # zero row
+        x[1, :] = 127.0                     # every code at the top of the range
+        x[2, ::2] = -127.0; x[2, 1::2] = 127.0
+        x[3, :] = -1.0
+    q, s, z = oracle.quant_weights(W)
+    xq, sx, _ = oracle.quant_act(x)
+    return W, x, q, s, z, xq, sx
+
+
+def test_plane_leaves_the_chunk_layout_alone():
+    N, K = 272, 1536
+    W = synth.weights(N, K, 4101)
+    p0 = B.mnnq_pack_weights(dev(W))
+    p1 = B.mnnq_pack_weights(dev(W), mode=MODE)
+    assert p1.numel() == B.mnnq_packed_size(N, K, 64, MODE) > p0.numel()
+    assert torch.equal(p1[:p0.numel()], p0)
+    q, s, z = oracle.quant_weights(W)
+    qg, sg, zg = B.mnnq_unpack_weights(p1, N, K, mode=MODE)
+    assert np.array_equal(qg.cpu().numpy(), q) and np.array_equal(sg.cpu().numpy(), s) and np.array_equal(zg.cpu().numpy(), z)
+    # the import call builds the same plane
+    p2 = B.mnnq_pack_from_quantized(dev(q), dev(s), dev(z), mode=MODE)
+    assert torch.equal(p2, p1)
+
+
+@pytest.mark.parametrize("plan", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("M,N,K", [(200, 400 - 400 % 16, 1536), (129, 592, 448), (40, 48, 64), (333, 1024, 192)])
+def test_prefill6_every_plan(plan, M, N, K):
+    note("prefill6 plan", plan, "M", M, "N", N, "K", K)
+    W, x, q, s, z, xq, sx = make(N, K, M, 4200 + plan, special=True)
+    acc_o, y_o = oracle.linear_w4a8(xq, sx, q, s, z)
+    packed = B.mnnq_pack_weights(dev(W), mode=MODE)
+    ws = torch.empty(B.mnnq_workspace_size(M, N, K, 64, MODE), dtype=torch.uint8, device="cuda:0")
+    B.mnnq_debug_force_plan(6, plan)
+    assert B.mnnq_plan_debug(0, M, N, K, mode=MODE)[7] == 6
+    y = B.mnnq_linear_prefill(packed, N, K, dev(xq), dev(sx), mode=MODE, workspace=ws).cpu().numpy()
+    err = np.abs(y - y_o).max()
+    assert err <= TOL_A8 * np.abs(y_o).max(), (err, np.abs(y_o).max())
+    # the same call again gives the same bits
+    y2 = B.mnnq_linear_prefill(packed, N, K, dev(xq), dev(sx), mode=MODE, workspace=ws).cpu().numpy()
+    assert np.array_equal(y, y2)
+
+
+@pytest.mark.parametrize("M,N,K", [(200, 400 - 400 % 16, 1536), (129, 592, 448), (40, 48, 64)])
+def test_prefill6_accumulators_bit_exact(M, N, K):
+    note("prefill6 acc", "M", M, "N", N, "K", K)
+    W, x, q, s, z, xq, sx = make(N, K, M, 4300, special=True)
+    acc_o, _ = oracle.linear_w4a8(xq, sx, q, s, z)
+    packed = B.mnnq_pack_weights(dev(W), mode=MODE)
+    acc = B.mnnq_linear_acc_debug_planes(packed, N, K, dev(xq), MODE).cpu().numpy()
+    assert np.array_equal(acc, acc_o)
+
+
+def test_prefill6_bias_fused_and_fallbacks():
+    M, N, K = 150, 512, 1536
+    W, x, q, s, z, xq, sx = make(N, K, M, 4400)
+    bias = (0.5 * np.random.default_rng(4401).standard_normal(N)).astype(np.float32)
+    _, y_o = oracle.linear_w4a8(xq, sx, q, s, z, bias=bias)
+    packed = B.mnnq_pack_weights(dev(W), mode=MODE)
+    tol = TOL_A8 * np.abs(y_o).max()
+    # fused call (quantizer inside), workspace brought by the wrapper
+    yf = B.mnnq_linear_prefill_fused(packed, N, K, dev(x), bias=dev(bias), mode=MODE).cpu().numpy()
+    assert np.abs(yf - y_o).max() <= tol
+    # no workspace: the int8 GEMM on the chunk layout in front of the plane
+    y8 = B.mnnq_linear_prefill(packed, N, K, dev(xq), dev(sx), bias=dev(bias), mode=MODE).cpu().numpy()
+    assert np.abs(y8 - y_o).max() <= tol
+    # decode and the few-token path read the chunk layout too
+    y1 = B.mnnq_linear_decode(packed, N, K, dev(xq[0]), dev(sx[:1]), bias=dev(bias), mode=MODE).cpu().numpy()
+    assert np.abs(y1 - y_o[0]).max() <= TOL_A8 * np.abs(y_o[0]).max()
+    # the entry point without allocations takes the plane too
+    ys = B.mnnq_linear_prefill_fused_static(packed, N, K, dev(x), bias=dev(bias), mode=MODE).cpu().numpy()
+    assert np.array_equal(ys, yf)
