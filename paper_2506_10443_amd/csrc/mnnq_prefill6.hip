@@ -78,7 +78,9 @@ __device__ __forceinline__ uint32_t signmag_from_biased(uint32_t b)
     return r;
 }
 
-// One block (1536 B) of a plane: dwords 0..3 of lane l at 16 l, dwords 4..5 at 1024 + 8 l.
+// One block (1536 B) of a plane: six dwords per lane, dwords 0..3 of lane l at 16 l, dwords 4..5 at
+// 1024 + 8 l - a kilobyte of 16-byte units and half a kilobyte of 8-byte units, both read without
+// bank conflicts.
 __device__ __forceinline__ void store_block(uint8_t* block, int lane, const uint32_t (&d)[6])
 {
     *reinterpret_cast<uint4*>(block + lane * 16) = make_uint4(d[0], d[1], d[2], d[3]);
@@ -167,7 +169,12 @@ __global__ __launch_bounds__(256) void planes_kernel(const int8_t* __restrict__ 
 // ---------------------------------------------------------------------------------------------
 // The GEMM.  Workgroup tile BM x BN, K range in KS parts of WM x WN waves each; a wave owns
 // TMW x TNW tiles of 32 x 32.  Per group (stage): BM * 96 bytes of activation planes, BN * 48 bytes
-// of weight plane and BN scales travel verbatim from memory to LDS with direct 128-bit loads.
+// of weight plane and BN scales travel verbatim from memory to LDS with direct 128-bit loads, two
+// stages per K part.  The loop is software pipelined over the groups: while group g is contracted,
+// every fragment (six registers per lane) is refilled from the stage of group g + 1 right after the
+// matrix instruction that used it last, so the LDS reads run between the matrix instructions; at the
+// top of a group one barrier makes the stage of g + 1 visible and frees the stage of g for the direct
+// loads of g + 2.
 template <int BM, int BN>
 struct Stage {
     static constexpr int A_BYTES = BM * 96;
@@ -180,20 +187,24 @@ struct Stage {
     static_assert(A_BYTES % 1024 == 0 && B_BYTES % 1024 == 0 && BN <= 256, "whole wave-wide loads");
 };
 
-// LDS of a workgroup: the stages of every K part and the junk kilobyte, or the K parts' sums when
-// those need more (they are exchanged after the last stage is dead).
-template <int BM, int BN, int WM, int WN, int KS, int NS>
+// LDS of a workgroup: two stages per K part and the junk kilobyte, or the K parts' sums when those
+// need more (they are exchanged after the last stage is dead).
+template <int BM, int BN, int KS>
 constexpr size_t lds_bytes6()
 {
-    const size_t stages = (size_t)KS * NS * Stage<BM, BN>::BYTES + 1024;
+    const size_t stages = (size_t)KS * 2 * Stage<BM, BN>::BYTES + 1024;
     const size_t sums = KS > 1 ? (size_t)(BM / 32) * (BN / 32) * 16 * 64 * 4 : 0;
     return stages > sums ? stages : sums;
 }
 
-__device__ __forceinline__ v8i frag6(const uint8_t* block, int lane)
+// A fragment (six registers) from a block in LDS; off16 = 16 lane, off8 = 8 lane.  Neighbouring blocks
+// are read with two copies of off8 that the compiler cannot tell to be equal: it would otherwise merge
+// their 8-byte reads into one instruction whose four result registers belong to two fragments, and
+// pay for that with register copies in the loop.
+__device__ __forceinline__ v8i frag6(const uint8_t* block, int off16, int off8)
 {
-    const v4i p0 = *reinterpret_cast<const v4i*>(block + lane * 16);
-    const v2i p1 = *reinterpret_cast<const v2i*>(block + 1024 + lane * 8);
+    const v4i p0 = *reinterpret_cast<const v4i*>(block + off16);
+    const v2i p1 = *reinterpret_cast<const v2i*>(block + 1024 + off8);
     return v8i{p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, 0, 0};
 }
 
@@ -203,7 +214,7 @@ __device__ __forceinline__ v16f mfma6(v8i a, v8i b, v16f c, int scale_a, int sca
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 2, 2, 0, scale_a, 0, scale_b);
 }
 
-template <int BM, int BN, int WM, int WN, int KS, int NS, bool ACC>
+template <int BM, int BN, int WM, int WN, int KS, bool ACC>
 __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
     const uint8_t* __restrict__ plane, const uint8_t* __restrict__ a6, Layout L, int64_t M, int TMp,
     const float* __restrict__ sx, const float* __restrict__ bias, float* __restrict__ y,
@@ -214,9 +225,6 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
     constexpr int TMW = BM / WM / 32, TNW = BN / WN / 32;
     constexpr int NL = (St::NA + St::NB + 1 + W - 1) / W;   // direct loads per wave and stage
     static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "whole 32 x 32 tiles per wave");
-    static_assert(KS == 1 || (size_t)W * TMW * TNW * 16 * 64 * 4 <= lds_bytes6<BM, BN, WM, WN, KS, NS>(),
-                  "the K parts' sums must fit in LDS");
-    static_assert(NS == 2 || NS == 3, "two or three stages");
 
     extern __shared__ __align__(16) uint8_t lds_all[];
 
@@ -226,8 +234,8 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
     const int part = wave_id / W;                    // K part of this wave
     const int w = wave_id % W;
     const int wm = w / WN, wn = w % WN;
-    uint8_t* const lds = lds_all + part * (NS * St::BYTES);
-    uint8_t* const junk = lds_all + KS * NS * St::BYTES;
+    uint8_t* const lds = lds_all + part * (2 * St::BYTES);
+    uint8_t* const junk = lds_all + KS * 2 * St::BYTES;
 
     // Workgroups are dealt to the 8 XCDs round-robin by their linear id: each XCD gets whole columns
     // of output tiles, so that a block of weights is fetched into one L2 only.
@@ -251,8 +259,8 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
     const int voff = lane * 16;
 
     // Stage `buf` <- group g: this wave's NL pieces of 1 KiB (slots past the stage's pieces go to a
-    // junk kilobyte with an out-of-range source, so that every wave has the same number of loads in
-    // flight and can wait by count).
+    // junk kilobyte with an out-of-range source, so that every wave issues the same number of loads).
+    // Groups past the end of the matrix lie outside the buffers and arrive as zeros.
     auto issue_stage = [&](int g, int buf) {
         uint8_t* st = lds + buf * St::BYTES;
 #pragma unroll
@@ -264,14 +272,12 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
             const int so_w = uniform(w_base + g * w_step + (s - St::NA) * 1024);
             const int so_s = uniform(s_base + g * s_step);
             if (s < St::NA)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, MNNQ_LDS(st + s * 1024), 16, voff,
-                                                         so_a, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, MNNQ_LDS(st + s * 1024), 16, voff, so_a, 0, 0);
             else if (s < St::NA + St::NB)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(st + St::B_OFF + (s - St::NA) * 1024), 16, voff,
                                                          so_w, 0, 0);
             else if (s == St::NA + St::NB)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(st + St::S_OFF), 16, voff,
-                                                         so_s, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(st + St::S_OFF), 16, voff, so_s, 0, 0);
             else
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(junk), 16, voff, kOutOfRange, 0, 0);
         }
@@ -288,62 +294,95 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
     asm volatile("" : "+v"(scale_hi), "+v"(scale_lo), "+v"(scale_b));
     const v16f zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
+    // this wave's fragments inside a stage
+    const int a_frag = (wm * TMW) * 2 * kPlaneBlockBytes;
+    const int b_frag = St::B_OFF + (wn * TNW) * kPlaneBlockBytes;
+    const int s_frag = St::S_OFF + (wn * TNW) * 128 + (lane & 31) * 4;
+
+    const int off16 = lane * 16, off8 = lane * 8;
+    int off8x = off8;
+    asm volatile("" : "+v"(off8x));   // the same value, unknown to the compiler (see frag6)
+
+    v8i ahi[TMW], alo[TMW], b[TNW];
+    float sc[TNW], scn[TNW];
+    auto read_a = [&](const uint8_t* st, int i) {
+        ahi[i] = frag6(st + a_frag + i * 2 * kPlaneBlockBytes, off16, off8);
+        alo[i] = frag6(st + a_frag + i * 2 * kPlaneBlockBytes + kPlaneBlockBytes, off16, off8x);
+    };
+    auto read_b = [&](const uint8_t* st, int j) {
+        b[j] = frag6(st + b_frag + j * kPlaneBlockBytes, off16, (j & 1) ? off8x : off8);
+    };
+
+    issue_stage(gb, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    issue_stage(gb + 1, 1);
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s) issue_stage(gb + s, s);
+    for (int j = 0; j < TNW; ++j) {
+        read_b(lds, j);
+        sc[j] = *reinterpret_cast<const float*>(lds + s_frag + j * 128);
+    }
+#pragma unroll
+    for (int i = 0; i < TMW; ++i) read_a(lds, i);
 
     for (int it = 0; it < n_iter; ++it) {
         const int g = gb + it;
-        const int buf = it % NS;
-        // This wave's pieces of stage `it` have landed (later stages may still be in flight); after the
-        // barrier everybody's have, and everybody is done with the stage that is loaded over next.
-        if (NS == 3) __builtin_amdgcn_s_waitcnt(0x0F70 | (NL & 15) | ((NL >> 4) << 14));   // vmcnt(NL)
-        else __builtin_amdgcn_s_waitcnt(0x0F70);                                             // vmcnt(0)
+        // Top of group g: its fragments are in registers (or on their way).  Once this wave's reads of
+        // the stage they came from and its pieces of the next stage are complete, and every other
+        // wave's too, the old stage can be loaded over and the next one read.
+        __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
-        const uint8_t* st = lds + buf * St::BYTES;
+        issue_stage(g + 2, it & 1);
+        if (KS > 1 && g >= ge) continue;      // the shorter share idles through the last round
+        const uint8_t* nx = lds + ((it + 1) & 1) * St::BYTES;   // stage of group g + 1
 
-        v8i ahi[TMW], alo[TMW], b[TNW];
-        float sc[TNW];
-        if (KS == 1 || g < ge) {
-#pragma unroll
-            for (int j = 0; j < TNW; ++j) {
-                b[j] = frag6(st + St::B_OFF + (wn * TNW + j) * kPlaneBlockBytes, lane);
-                sc[j] = *reinterpret_cast<const float*>(st + St::S_OFF + (wn * TNW + j) * 128 + (lane & 31) * 4);
-            }
-#pragma unroll
-            for (int i = 0; i < TMW; ++i) {
-                ahi[i] = frag6(st + (wm * TMW + i) * 2 * kPlaneBlockBytes, lane);
-                alo[i] = frag6(st + (wm * TMW + i) * 2 * kPlaneBlockBytes + kPlaneBlockBytes, lane);
-            }
-        }
-        issue_stage(g + NS - 1, (it + NS - 1) % NS);
-        if (KS > 1 && g >= ge) continue;   // the shorter share idles through the last round
-
-        // Tile t + 1's two matrix instructions are issued ahead of tile t's sixteen multiply-adds.
         v16f d[2];
-        d[0] = mfma6(ahi[0], b[0], zero16, scale_hi, scale_b);
-        d[0] = mfma6(alo[0], b[0], d[0], scale_lo, scale_b);
 #pragma unroll
         for (int t = 0; t < TMW * TNW; ++t) {
             const int i = t / TNW, j = t % TNW;
-            if (t + 1 < TMW * TNW) {
-                const int i1 = (t + 1) / TNW, j1 = (t + 1) % TNW;
-                d[(t + 1) & 1] = mfma6(ahi[i1], b[j1], zero16, scale_hi, scale_b);
-                d[(t + 1) & 1] = mfma6(alo[i1], b[j1], d[(t + 1) & 1], scale_lo, scale_b);
+            d[t & 1] = mfma6(ahi[i], b[j], zero16, scale_hi, scale_b);
+            d[t & 1] = mfma6(alo[i], b[j], d[t & 1], scale_lo, scale_b);
+            // fragments used for the last time in this group: fetch their successors
+            if (j == TNW - 1) read_a(nx, i);
+            if (i == TMW - 1) {
+                read_b(nx, j);
+                scn[j] = *reinterpret_cast<const float*>(nx + s_frag + j * 128);
             }
             __builtin_amdgcn_sched_barrier(0);
-            if (ACC) {
-                const int64_t n = (int64_t)tile_n * BN + (wn * TNW + j) * 32 + (lane & 31);
+            // the multiply-adds of the tile before, behind this tile's matrix instructions
+            if (t > 0) {
+                const int tp = t - 1, jp = (t - 1) % TNW;
+                if (ACC) {
+                    const int ip = tp / TNW;
+                    const int64_t n = (int64_t)tile_n * BN + (wn * TNW + jp) * 32 + (lane & 31);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t m = (int64_t)tile_m * BM + (wm * TMW + i) * 32 + 8 * (r / 4) + 4 * (lane >> 5) + r % 4;
-                    if (m < M && n < L.N) acc_out[(m * L.N + n) * G + g] = (int32_t)d[t & 1][r];
+                    for (int r = 0; r < 16; ++r) {
+                        const int64_t m = (int64_t)tile_m * BM + (wm * TMW + ip) * 32 + 8 * (r / 4) + 4 * (lane >> 5) + r % 4;
+                        if (m < M && n < L.N) acc_out[(m * L.N + n) * G + g] = (int32_t)d[tp & 1][r];
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) yacc[tp][r] = fmaf(sc[jp], d[tp & 1][r], yacc[tp][r]);
                 }
-            } else {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) yacc[t][r] = fmaf(sc[j], d[t & 1][r], yacc[t][r]);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+        {
+            constexpr int tp = TMW * TNW - 1, jp = tp % TNW, ip = tp / TNW;
+            if (ACC) {
+                const int64_t n = (int64_t)tile_n * BN + (wn * TNW + jp) * 32 + (lane & 31);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t m = (int64_t)tile_m * BM + (wm * TMW + ip) * 32 + 8 * (r / 4) + 4 * (lane >> 5) + r % 4;
+                    if (m < M && n < L.N) acc_out[(m * L.N + n) * G + g] = (int32_t)d[tp & 1][r];
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) yacc[tp][r] = fmaf(sc[jp], d[tp & 1][r], yacc[tp][r]);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < TNW; ++j) sc[j] = scn[j];
     }
     if (ACC) return;
 
@@ -412,15 +451,15 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
     }
 }
 
-template <int BM, int BN, int WM, int WN, int KS, int NS, bool ACC>
+template <int BM, int BN, int WM, int WN, int KS, bool ACC>
 int launch6(const uint8_t* packed, const Layout& L, int64_t M, const uint8_t* a6, int TMp, const float* sx,
             const float* bias, float* y, int32_t* acc, hipStream_t st)
 {
     const int MT = (int)((M + BM - 1) / BM);
     const int NT = (int)((L.N + BN - 1) / BN);
-    constexpr size_t smem = lds_bytes6<BM, BN, WM, WN, KS, NS>();
+    constexpr size_t smem = lds_bytes6<BM, BN, KS>();
     static_assert(smem <= kLdsPerWorkgroup, "LDS of a workgroup");
-    auto kern = prefill6_kernel<BM, BN, WM, WN, KS, NS, ACC>;
+    auto kern = prefill6_kernel<BM, BN, WM, WN, KS, ACC>;
     static thread_local int allowed_dev = -1;
     if (int s = allow_large_lds(kern, smem, allowed_dev)) return s;
     const int64_t blocks = (int64_t)MT * ((NT + 7) / 8) * 8;
@@ -432,9 +471,9 @@ int launch6(const uint8_t* packed, const Layout& L, int64_t M, const uint8_t* a6
 
 int tmp_tiles(int64_t M) { return (int)(((M + 31) / 32 + kPlaneTilePad - 1) / kPlaneTilePad * kPlaneTilePad); }
 
-// Tile plan: 0 = 128 x 128 tiles of four waves (two workgroups per CU), 1 = 128 x 128 with the K range
-// in two parts (eight waves), 2 = 128 x 192 with two K parts, 3 = 128 x 256 of eight waves,
-// 4 = 256 x 256 of eight waves.
+// Tile plans (all waves own 64 rows): 0 = 128 x 128 tiles of four waves (two workgroups per CU),
+// 1 = 128 x 128 with the K range in two parts (eight waves), 2 = 128 x 256 of four waves (64 x 128
+// outputs per wave, two workgroups per CU), 3 = 128 x 256 with two K parts, 4 = 256 x 256 of eight waves.
 int g_force_plan6 = -1;
 
 int choose_plan6(const Layout& L, int64_t M)
@@ -444,10 +483,10 @@ int choose_plan6(const Layout& L, int64_t M)
     auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((L.N + bn - 1) / bn); };
     auto eff = [&](int64_t t, int64_t slots) { return (double)t / (double)((t + slots - 1) / slots * slots); };
     // how well each form fills the chip, times what its wave tile is worth
-    const double e0 = eff(tiles(128, 128), 2 * cus) * 1.00;
-    const double e1 = eff(tiles(128, 128), cus) * 0.97;
-    const double e2 = eff(tiles(128, 192), cus) * 1.00;
-    const double e3 = eff(tiles(128, 256), cus) * 1.00;
+    const double e0 = eff(tiles(128, 128), 2 * cus) * 0.90;
+    const double e1 = eff(tiles(128, 128), cus) * 0.85;
+    const double e2 = eff(tiles(128, 256), 2 * cus) * 1.00;
+    const double e3 = eff(tiles(128, 256), cus) * 0.95;
     int best = 0;
     double eb = e0;
     if (e1 > eb) { best = 1; eb = e1; }
@@ -464,11 +503,11 @@ struct Plan6Info {
 Plan6Info plan6_info(int plan)
 {
     switch (plan) {
-        case 1: return {128, 128, 2, 8, lds_bytes6<128, 128, 2, 2, 2, 2>()};
-        case 2: return {128, 192, 2, 8, lds_bytes6<128, 192, 2, 2, 2, 2>()};
-        case 3: return {128, 256, 1, 8, lds_bytes6<128, 256, 2, 4, 1, 2>()};
-        case 4: return {256, 256, 1, 8, lds_bytes6<256, 256, 4, 2, 1, 2>()};
-        default: return {128, 128, 1, 4, lds_bytes6<128, 128, 2, 2, 1, 2>()};
+        case 1: return {128, 128, 2, 8, lds_bytes6<128, 128, 2>()};
+        case 2: return {128, 256, 1, 4, lds_bytes6<128, 256, 1>()};
+        case 3: return {128, 256, 2, 8, lds_bytes6<128, 256, 2>()};
+        case 4: return {256, 256, 1, 8, lds_bytes6<256, 256, 1>()};
+        default: return {128, 128, 1, 4, lds_bytes6<128, 128, 1>()};
     }
 }
 
@@ -516,13 +555,13 @@ int launch_prefill6(const uint8_t* packed, const Layout& L, int64_t M, const int
     const int64_t waves = (int64_t)Gx * TMp;
     hipLaunchKernelGGL(planes_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, xq, M, L.Kx, Gx, TMp, a6);
     MNNQ_HIP_TRY(hipGetLastError());
-    if (acc_debug) return launch6<128, 128, 2, 2, 1, 2, true>(packed, L, M, a6, TMp, sx, bias, y, acc_debug, st);
+    if (acc_debug) return launch6<128, 128, 2, 2, 1, true>(packed, L, M, a6, TMp, sx, bias, y, acc_debug, st);
     switch (choose_plan6(L, M)) {
-        case 1: return launch6<128, 128, 2, 2, 2, 2, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
-        case 2: return launch6<128, 192, 2, 2, 2, 2, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
-        case 3: return launch6<128, 256, 2, 4, 1, 2, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
-        case 4: return launch6<256, 256, 4, 2, 1, 2, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
-        default: return launch6<128, 128, 2, 2, 1, 2, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
+        case 1: return launch6<128, 128, 2, 2, 2, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
+        case 2: return launch6<128, 256, 2, 2, 1, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
+        case 3: return launch6<128, 256, 2, 2, 2, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
+        case 4: return launch6<256, 256, 4, 2, 1, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
+        default: return launch6<128, 128, 2, 2, 1, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
     }
 }
 
