@@ -166,6 +166,21 @@ int mnnq_linear_prefill_fused(const void *packed, int64_t M, int64_t N, int64_t 
                               const float *x, const float *bias, float *y,
                               void *workspace, size_t workspace_bytes, void *stream);
 
+/* The two steps of mnnq_linear_prefill on a packed buffer with the matrix-core plane, as calls of their
+ * own - for callers that feed several projections with the same activations (q, k, v; gate, up) and
+ * want the activations rearranged once (Section 5.1 rearranges operands for the instruction that
+ * consumes them; for activations that has to happen per call):
+ *   mnnq_act_planes: int8 codes xq [M, K] -> the activation operand of the fp6 matrix instructions
+ *     (every code as 16 hi + lo, both parts exact e2m3 numbers), mnnq_act_planes_size(M, K, group) bytes;
+ *   mnnq_linear_prefill_planes: y [M, N] from those planes, the scales sx [M] and the packed weights;
+ *     mode must carry MNNQ_WITH_MATRIX_PLANE and M must exceed 32 (MNNQ_ERR_UNSUPPORTED otherwise).
+ * The result is that of mnnq_linear_prefill with a workspace, bit for bit. */
+size_t mnnq_act_planes_size(int64_t M, int64_t K, int group);
+int mnnq_act_planes(const int8_t *xq, int64_t M, int64_t K, int group, void *planes, size_t planes_bytes,
+                    void *stream);
+int mnnq_linear_prefill_planes(const void *packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                               const void *planes, const float *sx, const float *bias, float *y, void *stream);
+
 /* mnnq_linear_prefill_fused for callers that cannot allocate device memory or hand over a workspace
  * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the int8
  * codes and scales pass through an array inside the library instead, of
@@ -229,20 +244,6 @@ int mnnq_linear_prefill_fused_o16(const void *packed, int64_t M, int64_t N, int6
 int mnnq_pack_from_quantized(const uint8_t *q, const float *scale, const void *zero,
                              int64_t N, int64_t K, int group, int mode,
                              void *packed, size_t packed_bytes, void *stream);
-
-/* Measurement helpers (used by the benchmark to state what this GPU sustains next to its
- * published peaks; not part of the linear path).  Both only enqueue kernels; the caller times them.
- * mnnq_peak_read: reads `bytes` bytes of `buf` (device, 16-byte aligned) once with 128-bit loads,
- *   consecutive lanes on consecutive addresses; sink: 4 bytes of device memory, practically never
- *   written.
- * mnnq_peak_mfma: one workgroup per compute unit with `waves_per_simd` (1..4) waves per SIMD, each
- *   wave issuing iters * mnnq_peak_mfma_count() matrix instructions on register operands.
- *   kind 0: int8 16x16x64 (32768 operations each), 1: fp16 16x16x32 (16384), 2: fp8 16x16x128
- *   (65536).  epilogue (kind 0 only): 0 none, 1: the dependent 4 converts + 4 fused multiply-adds of
- *   the prefill epilogue after every MFMA, 2: those plus 8 integer operations. */
-int mnnq_peak_read(const void *buf, size_t bytes, void *sink, void *stream);
-int mnnq_peak_mfma(int kind, int epilogue, int waves_per_simd, int iters, void *sink, void *stream);
-int mnnq_peak_mfma_count(void);
 
 /* Integer group accumulators of the W4A8 kernels, for bit-exact checks:
  *   acc[m, n, g] = sum_{k in g} xq[m,k] * (q[n,k] - zero[n,g])      (int32 [M, N, G]);

@@ -28,9 +28,10 @@ EXPORTS = (
     "mnnq_linear_prefill", "mnnq_linear_decode_f16", "mnnq_linear_prefill_f16", "mnnq_linear_acc_debug",
     "mnnq_pack_from_quantized",
     "mnnq_linear_decode_o16", "mnnq_linear_prefill_o16", "mnnq_linear_decode_f16_o16", "mnnq_linear_prefill_f16_o16",
-    "mnnq_plan_debug", "mnnq_linear_prefill_fused", "mnnq_linear_decode_fused_o16", "mnnq_linear_prefill_fused_o16", "mnnq_peak_read", "mnnq_peak_mfma", "mnnq_peak_mfma_count",
+    "mnnq_plan_debug", "mnnq_linear_prefill_fused", "mnnq_linear_decode_fused_o16", "mnnq_linear_prefill_fused_o16",
     "mnnq_linear_prefill_fused_static", "mnnq_static_scratch_bytes",
     "mnnq_linear_acc_debug_planes", "mnnq_debug_force_plan",
+    "mnnq_act_planes", "mnnq_linear_prefill_planes", "mnnq_act_planes_size",
 )
 
 
@@ -75,9 +76,6 @@ def lib() -> ctypes.CDLL:
         L.mnnq_linear_decode_fused_o16.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
         L.mnnq_linear_prefill_fused_o16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
         L.mnnq_plan_debug.argtypes = [i32, i64, i64, i64, i32, i32, vp]
-        L.mnnq_peak_read.argtypes = [vp, sz, vp, vp]
-        L.mnnq_peak_mfma.argtypes = [i32, i32, i32, i32, vp, vp]
-        L.mnnq_peak_mfma_count.argtypes = []
         L.mnnq_linear_decode_o16.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, vp]
         L.mnnq_linear_prefill_o16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp]
         L.mnnq_linear_decode_f16_o16.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
@@ -87,6 +85,10 @@ def lib() -> ctypes.CDLL:
         L.mnnq_linear_prefill_fused_static.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp]
         for name in EXPORTS[5:]:
             getattr(L, name).restype = i32
+        L.mnnq_act_planes.argtypes = [vp, i64, i64, i32, vp, sz, vp]
+        L.mnnq_linear_prefill_planes.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp]
+        L.mnnq_act_planes_size.restype = sz
+        L.mnnq_act_planes_size.argtypes = [i64, i64, i32]
         L.mnnq_static_scratch_bytes.restype = sz
         L.mnnq_static_scratch_bytes.argtypes = []
         _lib = L
@@ -220,6 +222,26 @@ def mnnq_linear_acc_debug_planes(packed, N: int, K: int, xq, mode: int, workspac
                                               _ptr(workspace), workspace.numel(), _stream()),
            "mnnq_linear_acc_debug_planes")
     return acc
+
+
+def mnnq_act_planes(xq, out=None):
+    """int8 codes [M,K] -> the activation operand of the fp6 GEMM (uint8 tensor)."""
+    _dev(xq, torch.int8, "xq")
+    M, K = xq.shape
+    size = int(lib().mnnq_act_planes_size(M, K, GROUP))
+    planes = torch.empty(size, dtype=torch.uint8, device=xq.device) if out is None else out
+    _check(lib().mnnq_act_planes(_ptr(xq), M, K, GROUP, _ptr(planes), planes.numel(), _stream()), "mnnq_act_planes")
+    return planes
+
+
+def mnnq_linear_prefill_planes(packed, M: int, N: int, K: int, planes, sx, bias=None, out=None,
+                               mode: int = MODE_W4_ZP_INT | WITH_MATRIX_PLANE):
+    """y f32 [M,N] from activation planes (mnnq_act_planes), scales sx [M] and packed weights with the plane."""
+    _dev(packed, torch.uint8, "packed"); _dev(planes, torch.uint8, "planes"); _dev(sx, torch.float32, "sx")
+    y = torch.empty((M, N), dtype=torch.float32, device=packed.device) if out is None else out
+    _check(lib().mnnq_linear_prefill_planes(_ptr(packed), M, N, K, GROUP, mode, _ptr(planes), _ptr(sx), _ptr(bias),
+                                            _ptr(y), _stream()), "mnnq_linear_prefill_planes")
+    return y
 
 
 def mnnq_debug_force_plan(kernel: int, plan: int) -> None:
@@ -411,16 +433,3 @@ def mnnq_plan_debug(what: int, M: int, N: int, K: int, mode: int = MODE_W4_ZP_IN
     out = (ctypes.c_int32 * 8)()
     _check(lib().mnnq_plan_debug(what, M, N, K, GROUP, mode, ctypes.cast(out, ctypes.c_void_p)), "mnnq_plan_debug")
     return list(out)
-
-
-# ---- measurement helpers
-
-def mnnq_peak_read(buf, sink):
-    """Enqueue one streaming read of the whole tensor `buf`; sink: 4-byte device tensor."""
-    _check(lib().mnnq_peak_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream()), "mnnq_peak_read")
-
-
-def mnnq_peak_mfma(kind: int, epilogue: int, waves_per_simd: int, iters: int, sink) -> int:
-    """Enqueue the matrix-instruction loop; returns the number of matrix instructions per wave."""
-    _check(lib().mnnq_peak_mfma(kind, epilogue, waves_per_simd, iters, _ptr(sink), _stream()), "mnnq_peak_mfma")
-    return iters * int(lib().mnnq_peak_mfma_count())

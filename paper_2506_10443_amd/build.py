@@ -13,11 +13,14 @@ LIB_DIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIB_DIR, "libmnnq.so")
 
 SOURCES = ["mnnq_api.hip", "mnnq_pack.hip", "mnnq_quant_act.hip", "mnnq_decode.hip",
-           "mnnq_prefill.hip", "mnnq_prefill6.hip", "mnnq_prefill_f16.hip", "mnnq_f16.hip", "mnnq_skinny.hip", "mnnq_peaks.hip"]
+           "mnnq_prefill.hip", "mnnq_prefill6.hip", "mnnq_prefill_f16.hip", "mnnq_f16.hip", "mnnq_skinny.hip"]
+# measurement helpers of bench.py: a library of their own, not part of the product's C-ABI
+BENCH_SOURCES = ["bench_kernels.hip"]
+BENCH_LIB = os.path.join(LIB_DIR, "libmnnq_bench.so")
 # The quantizers are fixed sequences of IEEE binary32 operations: no contraction.
 STRICT_FP = {"mnnq_pack.hip", "mnnq_quant_act.hip", "mnnq_decode.hip"}
 # MFMA results stay in architectural VGPRs so that the VALU epilogue reads them directly.
-MFMA_VGPR = {"mnnq_prefill.hip", "mnnq_prefill6.hip", "mnnq_prefill6.hip", "mnnq_prefill_f16.hip", "mnnq_skinny.hip", "mnnq_peaks.hip"}
+MFMA_VGPR = {"mnnq_prefill.hip", "mnnq_prefill6.hip", "mnnq_prefill6.hip", "mnnq_prefill_f16.hip", "mnnq_skinny.hip", "bench_kernels.hip"}
 
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
           "-fhip-fp32-correctly-rounded-divide-sqrt",
@@ -51,16 +54,17 @@ def _compile(src: str) -> str:
 def build(verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
     os.makedirs(LIB_DIR, exist_ok=True)
-    with ThreadPoolExecutor(len(SOURCES)) as pool:
-        objs = list(pool.map(_compile, SOURCES))
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
-    os.replace(tmp, LIB)
-    if verbose:
-        print("built", LIB)
+    with ThreadPoolExecutor(8) as pool:
+        objs = list(pool.map(_compile, SOURCES + BENCH_SOURCES))
+    for lib, lib_objs in ((LIB, objs[:len(SOURCES)]), (BENCH_LIB, objs[len(SOURCES):])):
+        tmp = lib + ".tmp.%d" % os.getpid()
+        cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + lib_objs
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
+        os.replace(tmp, lib)
+        if verbose:
+            print("built", lib)
     return LIB
 
 

@@ -1,16 +1,32 @@
-// Measurement helpers, not part of the linear path: what this GPU sustains for the two resources
+// libmnnq_bench.so - measurement helpers for bench.py, a library of its own: nothing here is part of
+// the linear path or of the product's C-ABI.  What this GPU sustains for the two resources
 // the decode GEMV and the prefill GEMM are priced against (Section 2.1: decode is bound by memory
 // bandwidth, prefill by compute), measured with the simplest kernels that use them.
-//   * mnnq_peak_read: every byte of a buffer is read once with 128-bit loads, consecutive lanes on
+//   * mnnqb_empty: a kernel that does nothing (the launch floor of a graph of kernels).
+//   * mnnqb_peak_read: every byte of a buffer is read once with 128-bit loads, consecutive lanes on
 //     consecutive addresses (the access rule of Section 5.1 for GPUs) - the streaming-read rate.
-//   * mnnq_peak_mfma: back-to-back matrix instructions on register operands, optionally followed
+//   * mnnqb_peak_mfma: back-to-back matrix instructions on register operands, optionally followed
 //     by the vector work the prefill epilogue needs per MFMA (4 converts + 4 fused multiply-adds,
 //     or those plus 8 integer operations) in the order the GEMM issues them (MFMA of tile t + 1,
 //     then the dependent epilogue of tile t) - the matrix rate and what each VALU instruction costs.
-// The caller times the launches; nothing is returned but a status.
-#include "mnnq_common.h"
+//     Kinds 3 and 4 are the loop shape of the fp6 GEMM: two chained v_mfma_scale_f32_32x32x64_f8f6f4
+//     (fp6 operands) per 32 x 32 tile and group, without and with the 16 multiply-adds behind them.
+// The caller times the launches; nothing is returned but a status (0 = ok, negative = bad argument).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
 
-namespace mnnq {
+namespace {
+
+int num_cus()
+{
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
+    return n;
+}
+
+}  // namespace
 
 namespace {
 
@@ -87,31 +103,78 @@ __global__ __launch_bounds__(1024) void peak_mfma_kernel(int iters, int seed, fl
     if (s == 12345.678f) *sink = s;        // keeps the arithmetic alive; practically never taken
 }
 
-}  // namespace
-}  // namespace mnnq
+typedef float v16f __attribute__((ext_vector_type(16)));
 
-using namespace mnnq;
+__device__ __forceinline__ v16f mfma6(v8i a, v8i b, v16f c, int scale_a, int scale_b)
+{
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 2, 2, 0, scale_a, 0, scale_b);
+}
+
+// Two chained fp6 matrix instructions per 32 x 32 tile and group (high and low parts of the int8
+// activations), tile t + 1 issued ahead of tile t's multiply-adds; eight tiles per wave.
+template <bool EPI>
+__global__ __launch_bounds__(512) void peak_fp6_kernel(int iters, int seed, float* sink)
+{
+    constexpr int NT = 8;
+    v8i a0 = {seed, 1, 2, 3, 4, 5, 6, 7}, a1 = {seed + 1, 1, 2, 3, 4, 5, 6, 7}, b[2];
+    for (int j = 0; j < 2; ++j) b[j] = v8i{seed * 3 + j, 7, 6, 5, 4, 3, 2, 1};
+    float yacc[NT][16];
+    for (int t = 0; t < NT; ++t)
+        for (int r = 0; r < 16; ++r) yacc[t][r] = 0.f;
+    const v16f z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const float sc = 1.0f + seed * 1e-6f;
+    v16f d[2];
+    d[0] = mfma6(a1, b[0], mfma6(a0, b[0], z, 137, 127), 133, 127);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            asm volatile("" : "+v"(b[(t + 1) & 1]));
+            d[(t + 1) & 1] = mfma6(a1, b[(t + 1) & 1], mfma6(a0, b[(t + 1) & 1], z, 137, 127), 133, 127);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                if (EPI) yacc[t][r] = fmaf(sc, d[t & 1][r], yacc[t][r]);
+                else asm volatile("" : "+v"(d[t & 1][r]));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    float s = d[0][0];
+    for (int t = 0; t < NT; ++t)
+        for (int r = 0; r < 16; ++r) s += yacc[t][r];
+    if (s == 12345.678f) *sink = s;
+}
+
+__global__ void empty_kernel() {}
+
+}  // namespace
 
 extern "C" {
 
-int mnnq_peak_read(const void* buf, size_t bytes, void* sink, void* stream)
+int mnnqb_empty(void* stream)
 {
-    if (!buf || !sink) return MNNQ_ERR_NULL;
-    if (bytes < 16) return MNNQ_ERR_SHAPE;
-    if (reinterpret_cast<uintptr_t>(buf) & 15u) return MNNQ_ERR_ALIGN;
+    hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream));
+    return hipGetLastError() == hipSuccess ? 0 : -6;
+}
+
+int mnnqb_peak_read(const void* buf, size_t bytes, void* sink, void* stream)
+{
+    if (!buf || !sink) return -1;
+    if (bytes < 16) return -2;
+    if (reinterpret_cast<uintptr_t>(buf) & 15u) return -5;
     const int64_t n16 = (int64_t)(bytes / 16);
     const int blocks = num_cus() * 16;
     hipLaunchKernelGGL(peak_read_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const u32x4*>(buf), n16, static_cast<uint32_t*>(sink));
-    MNNQ_HIP_TRY(hipGetLastError());
-    return MNNQ_OK;
+    return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
-int mnnq_peak_mfma(int kind, int epilogue, int waves_per_simd, int iters, void* sink, void* stream)
+int mnnqb_peak_mfma(int kind, int epilogue, int waves_per_simd, int iters, void* sink, void* stream)
 {
-    if (!sink) return MNNQ_ERR_NULL;
-    if (iters <= 0 || waves_per_simd < 1 || waves_per_simd > 4) return MNNQ_ERR_SHAPE;
-    if (kind < 0 || kind > 2 || epilogue < 0 || epilogue > 2 || (kind != 0 && epilogue != 0)) return MNNQ_ERR_UNSUPPORTED;
+    if (!sink) return -1;
+    if (iters <= 0 || waves_per_simd < 1 || waves_per_simd > 4) return -2;
+    if (kind < 0 || kind > 4 || epilogue < 0 || epilogue > 2 || (kind != 0 && epilogue != 0)) return -3;
+    if (kind >= 3 && waves_per_simd > 2) return -3;   // the fp6 loop needs 200 registers
     const dim3 grid((unsigned)num_cus()), block(256u * (unsigned)waves_per_simd);   // one workgroup per CU
     hipStream_t st = static_cast<hipStream_t>(stream);
     float* out = static_cast<float*>(sink);
@@ -120,10 +183,13 @@ int mnnq_peak_mfma(int kind, int epilogue, int waves_per_simd, int iters, void* 
     if (kind == 0 && epilogue == 2) hipLaunchKernelGGL((peak_mfma_kernel<0, 2>), grid, block, 0, st, iters, 1, out);
     if (kind == 1) hipLaunchKernelGGL((peak_mfma_kernel<1, 0>), grid, block, 0, st, iters, 1, out);
     if (kind == 2) hipLaunchKernelGGL((peak_mfma_kernel<2, 0>), grid, block, 0, st, iters, 1, out);
-    MNNQ_HIP_TRY(hipGetLastError());
-    return MNNQ_OK;
+    if (kind == 3) hipLaunchKernelGGL((peak_fp6_kernel<false>), grid, block, 0, st, iters, 1, out);
+    if (kind == 4) hipLaunchKernelGGL((peak_fp6_kernel<true>), grid, block, 0, st, iters, 1, out);
+    return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
-int mnnq_peak_mfma_count(void) { return 16; }   // matrix instructions per iteration and wave
+// matrix instructions per iteration and wave (kinds 3, 4: 16 instructions of 32x32x64 = 131072 operations
+// each of which only half are the GEMM's - the activations take two fp6 parts)
+int mnnqb_peak_mfma_count(void) { return 16; }
 
 }  // extern "C"

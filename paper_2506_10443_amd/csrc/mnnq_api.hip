@@ -130,9 +130,11 @@ int prefill_impl(const void* packed, int64_t M, int64_t N, int64_t K, int group,
     // A few tokens (batched or speculative decoding) are still memory-bound: one pass over the
     // weights in the GEMV's streaming order, all tokens at once in the matrix cores.
     // With the matrix-core plane and room for the activations' planes: the GEMM on the fp6 matrix instructions.
-    if (prefill6_wanted(L, M) && workspace && workspace_bytes >= prefill6_ws_bytes(M, K))
-        return launch_prefill6(static_cast<const uint8_t*>(packed), L, M, xq, sx, bias, static_cast<float*>(y), nullptr,
-                               workspace, static_cast<hipStream_t>(stream));
+    if (prefill6_wanted(L, M) && workspace && workspace_bytes >= prefill6_ws_bytes(M, K)) {
+        if (int s = launch_act_planes(xq, M, K, workspace, static_cast<hipStream_t>(stream))) return s;
+        return launch_prefill6(static_cast<const uint8_t*>(packed), L, M, workspace, sx, bias, static_cast<float*>(y),
+                               nullptr, static_cast<hipStream_t>(stream));
+    }
     if (M <= 16 && !getenv("MNNQ_NO_SKINNY"))
         return launch_skinny(static_cast<const uint8_t*>(packed), L, M, xq, sx, bias, static_cast<float*>(y),
                              static_cast<hipStream_t>(stream));
@@ -466,7 +468,40 @@ int mnnq_linear_acc_debug_planes(const void* packed, int64_t M, int64_t N, int64
     if (M > kMaxM || !prefill_fits(M, N, K, mode) || !prefill6_wanted(L, M)) return MNNQ_ERR_UNSUPPORTED;
     if (workspace_bytes < prefill6_ws_bytes(M, K)) return MNNQ_ERR_SIZE;
     if (misaligned(packed) || misaligned(xq) || misaligned(acc) || misaligned(workspace)) return MNNQ_ERR_ALIGN;
-    return launch_prefill6(static_cast<const uint8_t*>(packed), L, M, xq, nullptr, nullptr, nullptr, acc, workspace,
+    if (int s = launch_act_planes(xq, M, K, workspace, static_cast<hipStream_t>(stream))) return s;
+    return launch_prefill6(static_cast<const uint8_t*>(packed), L, M, workspace, nullptr, nullptr, nullptr, acc,
+                           static_cast<hipStream_t>(stream));
+}
+
+size_t mnnq_act_planes_size(int64_t M, int64_t K, int group)
+{
+    if (M <= 0 || K <= 0 || group != kGroup || K % group != 0) return 0;
+    return prefill6_ws_bytes(M, K);
+}
+
+int mnnq_act_planes(const int8_t* xq, int64_t M, int64_t K, int group, void* planes, size_t planes_bytes, void* stream)
+{
+    if (!xq || !planes) return MNNQ_ERR_NULL;
+    if (M <= 0 || K <= 0) return MNNQ_ERR_SHAPE;
+    if (group != kGroup) return MNNQ_ERR_UNSUPPORTED;
+    if (K % group != 0) return MNNQ_ERR_SHAPE;
+    if (M > ((int64_t)1 << 24) || (int64_t)prefill6_ws_bytes(M, K) > ((int64_t)1 << 31) - 1) return MNNQ_ERR_UNSUPPORTED;
+    if (planes_bytes < prefill6_ws_bytes(M, K)) return MNNQ_ERR_SIZE;
+    if (misaligned(xq) || misaligned(planes)) return MNNQ_ERR_ALIGN;
+    return launch_act_planes(xq, M, K, planes, static_cast<hipStream_t>(stream));
+}
+
+int mnnq_linear_prefill_planes(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,
+                               const void* planes, const float* sx, const float* bias, float* y, void* stream)
+{
+    if (!packed || !planes || !sx || !y) return MNNQ_ERR_NULL;
+    if (M <= 0) return MNNQ_ERR_SHAPE;
+    if (int s = check_shape(N, K, group, mode)) return s;
+    const Layout L = make_layout(N, K, mode);
+    if (!prefill_fits(M, N, K, mode) || !prefill6_wanted(L, M)) return MNNQ_ERR_UNSUPPORTED;
+    if (misaligned(packed) || misaligned(planes) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(sx) & 3u) return MNNQ_ERR_ALIGN;
+    return launch_prefill6(static_cast<const uint8_t*>(packed), L, M, planes, sx, bias, y, nullptr,
                            static_cast<hipStream_t>(stream));
 }
 

@@ -222,8 +222,10 @@ int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8
 // GEMM on the fp6 matrix instructions (mnnq_prefill6.hip): needs the matrix-core plane in the packed
 // buffer and `planes_ws`, prefill6_ws_bytes(M, K) bytes of scratch for the activation planes.
 int launch_plane_build(uint8_t* packed, const Layout& L, hipStream_t st);
-int launch_prefill6(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
-                    const float* bias, float* y, int32_t* acc_debug, void* planes_ws, hipStream_t st);
+// planes: the activation planes launch_act_planes wrote for the same M and K.
+int launch_act_planes(const int8_t* xq, int64_t M, int64_t K, void* planes, hipStream_t st);
+int launch_prefill6(const uint8_t* packed, const Layout& L, int64_t M, const void* planes, const float* sx,
+                    const float* bias, float* y, int32_t* acc_debug, hipStream_t st);
 size_t prefill6_ws_bytes(int64_t M, int64_t K);
 bool prefill6_wanted(const Layout& L, int64_t M);
 void describe_prefill6(const Layout& L, int64_t M, int32_t out[8]);

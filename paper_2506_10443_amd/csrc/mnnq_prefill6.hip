@@ -546,15 +546,22 @@ int launch_plane_build(uint8_t* packed, const Layout& L, hipStream_t st)
     return MNNQ_OK;
 }
 
-int launch_prefill6(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
-                    const float* bias, float* y, int32_t* acc_debug, void* planes_ws, hipStream_t st)
+int launch_act_planes(const int8_t* xq, int64_t M, int64_t K, void* planes, hipStream_t st)
 {
     const int TMp = tmp_tiles(M);
-    const int Gx = (int)L.Gx;
-    uint8_t* a6 = static_cast<uint8_t*>(planes_ws);
+    const int Gx = (int)(K / kGroup);
     const int64_t waves = (int64_t)Gx * TMp;
-    hipLaunchKernelGGL(planes_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, xq, M, L.Kx, Gx, TMp, a6);
+    hipLaunchKernelGGL(planes_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, xq, M, K, Gx, TMp,
+                       static_cast<uint8_t*>(planes));
     MNNQ_HIP_TRY(hipGetLastError());
+    return MNNQ_OK;
+}
+
+int launch_prefill6(const uint8_t* packed, const Layout& L, int64_t M, const void* planes, const float* sx,
+                    const float* bias, float* y, int32_t* acc_debug, hipStream_t st)
+{
+    const int TMp = tmp_tiles(M);
+    const uint8_t* a6 = static_cast<const uint8_t*>(planes);
     if (acc_debug) return launch6<128, 128, 2, 2, 1, true>(packed, L, M, a6, TMp, sx, bias, y, acc_debug, st);
     switch (choose_plan6(L, M)) {
         case 1: return launch6<128, 128, 2, 2, 2, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);

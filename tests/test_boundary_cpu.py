@@ -128,9 +128,36 @@ def test_argument_validation_precedes_hip(L):
     assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 192, 64, 2, FAKE, None, None, FAKE, None, 0, None) == UNSUP
     assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 128, 64, 0, FAKE, None, None, None, None, 0, None) == NULL
     assert L.mnnq_linear_prefill_f16(FAKE, -1, 16, 128, 64, 0, FAKE, None, None, FAKE, None, 0, None) == SHAPE
-    assert L.mnnq_peak_read(None, 1024, FAKE, None) == NULL and L.mnnq_peak_read(FAKE, 8, FAKE, None) == SHAPE
-    assert L.mnnq_peak_mfma(3, 0, 2, 10, FAKE, None) == UNSUP and L.mnnq_peak_mfma(1, 1, 2, 10, FAKE, None) == UNSUP
-    assert L.mnnq_peak_mfma(0, 0, 5, 10, FAKE, None) == SHAPE and L.mnnq_peak_mfma_count() == 16
+    # the matrix-core plane: a flag of the integer zero point mode only
+    PL = 16
+    # chunk layout rounded up to 256 bytes, then 2 groups x 8 column tiles (padded) x (1536 B of codes + 32 scales)
+    assert binding.mnnq_packed_size(64, 128, 64, 0) == 4736
+    assert binding.mnnq_packed_size(64, 128, 64, PL) == 4864 + 2 * 8 * (1536 + 128)
+    assert binding.mnnq_packed_size(64, 128, 64, PL | 1) == 0 and binding.mnnq_packed_size(64, 128, 64, 32) == 0
+    assert L.mnnq_pack_weights(FAKE, 64, 128, 64, PL, FAKE, binding.mnnq_packed_size(64, 128, 64, 0), None) == SIZE
+    assert L.mnnq_pack_weights(FAKE, 64, 128, 64, PL | 2, FAKE, 10**9, None) == UNSUP
+    assert binding.mnnq_workspace_size(64, 64, 128, 64, PL) == 2 * 8 * 2 * 1536 + 64 * 128 + 256
+    assert binding.mnnq_workspace_size(64, 64, 128, 64, 0) == 64 * 128 + 256
+    assert binding.mnnq_workspace_size(32, 64, 128, 64, PL) == 32 * 128 + 128      # 32 tokens or fewer: the int8 kernels
+    ap_, lp = L.mnnq_act_planes, L.mnnq_linear_prefill_planes
+    assert L.mnnq_act_planes_size(64, 128, 64) == 2 * 8 * 2 * 1536 and L.mnnq_act_planes_size(64, 100, 64) == 0
+    assert ap_(None, 64, 128, 64, FAKE, 10**9, None) == NULL and ap_(FAKE, 64, 100, 64, FAKE, 10**9, None) == SHAPE
+    assert ap_(FAKE, 64, 128, 64, FAKE, 100, None) == SIZE and ap_(FAKE, 64, 128, 64, ODD, 10**9, None) == ALIGN
+    assert lp(FAKE, 64, 64, 128, 64, PL, None, FAKE, None, FAKE, None) == NULL
+    assert lp(FAKE, 64, 64, 128, 64, 0, FAKE, FAKE, None, FAKE, None) == UNSUP      # no plane in the buffer
+    assert lp(FAKE, 16, 64, 128, 64, PL, FAKE, FAKE, None, FAKE, None) == UNSUP     # too few tokens for this kernel
+    assert lp(FAKE, 64, 64, 128, 64, PL, FAKE, FAKE, None, ODD, None) == ALIGN
+    ad = L.mnnq_linear_acc_debug_planes
+    assert ad(FAKE, 64, 64, 128, 64, PL, FAKE, FAKE, None, 0, None) == NULL
+    assert ad(FAKE, 64, 64, 128, 64, PL, FAKE, FAKE, FAKE, 100, None) == SIZE
+    assert ad(FAKE, 64, 64, 128, 64, 0, FAKE, FAKE, FAKE, 10**9, None) == UNSUP
+    assert L.mnnq_debug_force_plan(5, 0) == UNSUP and L.mnnq_debug_force_plan(6, 9) == UNSUP
+    assert L.mnnq_debug_force_plan(6, 2) == OK and L.mnnq_debug_force_plan(6, -1) == OK
+    st = L.mnnq_linear_prefill_fused_static
+    assert st(None, 4, 16, 128, 64, 0, FAKE, None, FAKE, None) == NULL
+    assert st(FAKE, 4096, 16, 8192, 64, 0, FAKE, None, FAKE, None) == SIZE          # codes and scales beyond the array
+    assert st(FAKE, 4, 16, 128, 64, 0, ODD, None, FAKE, None) == ALIGN
+    assert L.mnnq_static_scratch_bytes() == 32 << 20
     pf = L.mnnq_linear_prefill_fused
     assert pf(FAKE, 4, 16, 128, 64, 0, FAKE, None, FAKE, None, 0, None) == NULL        # the workspace is required
     assert pf(FAKE, 4, 16, 128, 64, 0, FAKE, None, FAKE, FAKE, 100, None) == SIZE
