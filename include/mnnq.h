@@ -259,9 +259,14 @@ int mnnq_linear_acc_debug_planes(const void *packed, int64_t M, int64_t N, int64
                                  const int8_t *xq, int32_t *acc, void *workspace, size_t workspace_bytes,
                                  void *stream);
 
-/* Tests and tuning: fix the tile plan of a kernel family for all later calls of this process
- * (kernel 6 = the fp6 GEMM: plan 0..4; -1 = choose from the shape again).  Not thread safe. */
-int mnnq_debug_force_plan(int kernel, int plan);
+/* Tests and tuning: overrides of the launch plans, which otherwise follow from the shapes alone (the
+ * library never reads the environment).  key: one of MNNQ_DECODE_KSPLIT (waves per row tile of the GEMV:
+ * 1, 2, 4, 8, 16), MNNQ_DECODE_WAVES (4, 8, 16), MNNQ_DECODE_EARLY (0/1), MNNQ_PREFILL_TILE (tile letter,
+ * K split digit, k/q), MNNQ_NO_SKINNY, MNNQ_SKINNY_STAGED (0/1), MNNQ_W8_PLANES (1), MNNQ_FUSED_TWO_KERNEL_MIB,
+ * MNNQ_PREFILL6_PLAN (0..4: tile plan of the fp6 GEMM); value: a string of at most 15 characters, or NULL to
+ * clear the override.  Applies to all later calls of the process; not thread safe.  MNNQ_ERR_UNSUPPORTED
+ * for an unknown key. */
+int mnnq_debug_set(const char *key, const char *value);
 
 /* Test view of the host logic (Section 5.1 chooses loop tiling from the problem's dimensions; here:
  * which kernel configuration a call would launch).  Nothing is launched and no device is needed.

@@ -30,7 +30,7 @@ EXPORTS = (
     "mnnq_linear_decode_o16", "mnnq_linear_prefill_o16", "mnnq_linear_decode_f16_o16", "mnnq_linear_prefill_f16_o16",
     "mnnq_plan_debug", "mnnq_linear_prefill_fused", "mnnq_linear_decode_fused_o16", "mnnq_linear_prefill_fused_o16",
     "mnnq_linear_prefill_fused_static", "mnnq_static_scratch_bytes",
-    "mnnq_linear_acc_debug_planes", "mnnq_debug_force_plan",
+    "mnnq_linear_acc_debug_planes", "mnnq_debug_set",
     "mnnq_act_planes", "mnnq_linear_prefill_planes", "mnnq_act_planes_size",
 )
 
@@ -81,7 +81,7 @@ def lib() -> ctypes.CDLL:
         L.mnnq_linear_decode_f16_o16.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
         L.mnnq_linear_prefill_f16_o16.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp]
         L.mnnq_linear_acc_debug_planes.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, sz, vp]
-        L.mnnq_debug_force_plan.argtypes = [i32, i32]
+        L.mnnq_debug_set.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
         L.mnnq_linear_prefill_fused_static.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp]
         for name in EXPORTS[5:]:
             getattr(L, name).restype = i32
@@ -244,8 +244,9 @@ def mnnq_linear_prefill_planes(packed, M: int, N: int, K: int, planes, sx, bias=
     return y
 
 
-def mnnq_debug_force_plan(kernel: int, plan: int) -> None:
-    _check(lib().mnnq_debug_force_plan(kernel, plan), "mnnq_debug_force_plan")
+def mnnq_debug_set(key: str, value) -> None:
+    """Test / tuning override of a launch plan (see mnnq.h); value None clears it."""
+    _check(lib().mnnq_debug_set(key.encode(), None if value is None else str(value).encode()), "mnnq_debug_set")
 
 
 def mnnq_linear_decode_f16(packed, N: int, K: int, x16, bias=None, out=None, mode: int = MODE_W4_ZP_INT):

@@ -3,6 +3,7 @@
 #include "mnnq_common.h"
 
 #include <stdlib.h>
+#include <string.h>
 
 #include <mutex>
 
@@ -15,6 +16,20 @@ int record_hip_error(hipError_t e)
     t_last_hip_error = (int)e;
     return MNNQ_ERR_HIP;
 }
+
+namespace {
+struct DebugSlot {
+    const char* name;
+    char value[16];
+    bool set;
+};
+DebugSlot g_debug[kDbgCount] = {
+    {"MNNQ_DECODE_KSPLIT", "", false},  {"MNNQ_DECODE_WAVES", "", false},   {"MNNQ_DECODE_EARLY", "", false},
+    {"MNNQ_PREFILL_TILE", "", false},   {"MNNQ_NO_SKINNY", "", false},      {"MNNQ_SKINNY_STAGED", "", false},
+    {"MNNQ_W8_PLANES", "", false},      {"MNNQ_FUSED_TWO_KERNEL_MIB", "", false}, {"MNNQ_PREFILL6_PLAN", "", false}};
+}  // namespace
+
+const char* debug_option(DebugKey key) { return g_debug[key].set ? g_debug[key].value : nullptr; }
 
 namespace {
 
@@ -135,7 +150,7 @@ int prefill_impl(const void* packed, int64_t M, int64_t N, int64_t K, int group,
         return launch_prefill6(static_cast<const uint8_t*>(packed), L, M, workspace, sx, bias, static_cast<float*>(y),
                                nullptr, static_cast<hipStream_t>(stream));
     }
-    if (M <= 16 && !getenv("MNNQ_NO_SKINNY"))
+    if (M <= 16 && !debug_option(kDbgNoSkinny))
         return launch_skinny(static_cast<const uint8_t*>(packed), L, M, xq, sx, bias, static_cast<float*>(y),
                              static_cast<hipStream_t>(stream));
     return launch_prefill(static_cast<const uint8_t*>(packed), L, M, xq, sx, bias, static_cast<float*>(y), nullptr,
@@ -190,7 +205,7 @@ int decode_fused_impl(const void* packed, int64_t N, int64_t K, int group, int m
     const Layout L = layout_for(N, K, mode, out16);
     hipStream_t st = static_cast<hipStream_t>(stream);
     size_t two_kernel_bytes = kFusedTwoKernelBytes;
-    if (const char* e = getenv("MNNQ_FUSED_TWO_KERNEL_MIB")) two_kernel_bytes = (size_t)atoll(e) << 20;   // tuning only
+    if (const char* e = debug_option(kDbgFusedTwoKernelMib)) two_kernel_bytes = (size_t)atoll(e) << 20;   // tuning only
     if (workspace && workspace_bytes >= fused_ws_bytes(K) && L.total() > two_kernel_bytes) {
         int8_t* xq = static_cast<int8_t*>(workspace);
         float* sx = reinterpret_cast<float*>(xq + (K + 127) / 128 * 128);
@@ -505,11 +520,17 @@ int mnnq_linear_prefill_planes(const void* packed, int64_t M, int64_t N, int64_t
                            static_cast<hipStream_t>(stream));
 }
 
-int mnnq_debug_force_plan(int kernel, int plan)
+int mnnq_debug_set(const char* key, const char* value)
 {
-    if (kernel != 6 || plan < -1 || plan > 4) return MNNQ_ERR_UNSUPPORTED;
-    set_prefill6_plan(plan);
-    return MNNQ_OK;
+    if (!key) return MNNQ_ERR_NULL;
+    for (int i = 0; i < kDbgCount; ++i) {
+        if (strcmp(key, g_debug[i].name) != 0) continue;
+        if (value && strlen(value) >= sizeof(g_debug[i].value)) return MNNQ_ERR_SIZE;
+        g_debug[i].set = value != nullptr;
+        if (value) strcpy(g_debug[i].value, value);
+        return MNNQ_OK;
+    }
+    return MNNQ_ERR_UNSUPPORTED;
 }
 
 int mnnq_linear_acc_debug(const void* packed, int64_t M, int64_t N, int64_t K, int group, int mode,

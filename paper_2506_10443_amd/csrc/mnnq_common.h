@@ -193,6 +193,14 @@ __device__ __forceinline__ float quant_fast_limit(float scale, float inv)
 
 #endif
 
+// Test and tuning switches (mnnq_debug_set): nullptr unless set by that call.  The launch plans depend
+// on the shapes alone otherwise; the environment is never read.
+enum DebugKey {
+    kDbgDecodeKsplit, kDbgDecodeWaves, kDbgDecodeEarly, kDbgPrefillTile, kDbgNoSkinny, kDbgSkinnyStaged,
+    kDbgW8Planes, kDbgFusedTwoKernelMib, kDbgPrefill6Plan, kDbgCount
+};
+const char* debug_option(DebugKey key);
+
 // Records a failing HIP call for mnnq_last_hip_error() and maps it to a status.
 int record_hip_error(hipError_t e);
 
@@ -229,7 +237,6 @@ int launch_prefill6(const uint8_t* packed, const Layout& L, int64_t M, const voi
 size_t prefill6_ws_bytes(int64_t M, int64_t K);
 bool prefill6_wanted(const Layout& L, int64_t M);
 void describe_prefill6(const Layout& L, int64_t M, int32_t out[8]);
-void set_prefill6_plan(int plan);   // tests: -1 = chosen from the shape, 0..4 = that tile plan
 // M <= 16 tokens sharing one pass over the weights.
 int launch_skinny(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
                   const float* bias, float* y, hipStream_t st);

@@ -431,7 +431,7 @@ DecodeCfg decode_config(const Layout& L, bool fused)
     // Fused quantizer (eight-wave workgroups) on a layer with at most one row tile per CU: all eight
     // waves on one row tile, so that every tile has a workgroup of its own (o of Qwen2-7B: 6.1 -> 5.3 us).
     if (fused && ks < 8 && L.T <= num_cus() && L.C >= 8) ks = 8;
-    if (const char* e = getenv("MNNQ_DECODE_KSPLIT")) {   // tests and tuning: force the split
+    if (const char* e = debug_option(kDbgDecodeKsplit)) {   // tests and tuning: force the split
         const int v = atoi(e);
         if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16) {
             ks = v;
@@ -442,11 +442,11 @@ DecodeCfg decode_config(const Layout& L, bool fused)
     }
     // Rows of 28 chunks (K = 3584) on four waves or of 112 (K = 14336) on sixteen: seven chunks each, with no
     // register left unused
-    if ((ks == 4 || ks == 16) && L.C == 7 * ks && !prefetch && !getenv("MNNQ_DECODE_KSPLIT")) unroll = 7;
+    if ((ks == 4 || ks == 16) && L.C == 7 * ks && !prefetch && !debug_option(kDbgDecodeKsplit)) unroll = 7;
     // ... and eight waves on a row tile with at most four chunks each (the fused form of small layers)
-    if (fused && ks == 8 && (L.C + 7) / 8 <= 4 && !getenv("MNNQ_DECODE_KSPLIT")) unroll = 4;
+    if (fused && ks == 8 && (L.C + 7) / 8 <= 4 && !debug_option(kDbgDecodeKsplit)) unroll = 4;
     int waves = fused ? (ks > 8 ? 16 : 8) : (ks > 4 ? ks : 4);
-    if (const char* e = getenv("MNNQ_DECODE_WAVES")) {    // tuning only
+    if (const char* e = debug_option(kDbgDecodeWaves)) {    // tuning only
         const int v = atoi(e);
         if ((v == 4 || v == 8 || v == 16) && v >= ks) waves = v;
     }
@@ -456,7 +456,7 @@ DecodeCfg decode_config(const Layout& L, bool fused)
     // waves all have exactly `unroll` chunks (nothing is loaded twice)
     const bool exact = L.C % ks == 0 && L.C / ks == unroll;
     int early = !prefetch && (((int64_t)L.total() <= kEarlyMaxBytes && L.C / ks >= unroll - 2) || exact);
-    if (const char* e = getenv("MNNQ_DECODE_EARLY")) early = !prefetch && e[0] == '1';   // tests and tuning
+    if (const char* e = debug_option(kDbgDecodeEarly)) early = !prefetch && e[0] == '1';   // tests and tuning
     return DecodeCfg{waves, ks, unroll, prefetch, early};
 }
 

@@ -306,7 +306,7 @@ int launch_decode_f16(const uint8_t* packed, const Layout& L, const uint16_t* x1
         if ((L.C + 15) / 16 <= 12) unroll = 12;
         else prefetch = 1;
     }
-    if (const char* e = getenv("MNNQ_DECODE_KSPLIT")) {   // tests and tuning: force the split
+    if (const char* e = debug_option(kDbgDecodeKsplit)) {   // tests and tuning: force the split
         const int v = atoi(e);
         if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16) {
             ks = v;
@@ -316,12 +316,12 @@ int launch_decode_f16(const uint8_t* packed, const Layout& L, const uint16_t* x1
         }
     }
     // Rows of 28 chunks (K = 3584) on four waves: seven chunks each, with no register left unused
-    if (ks == 4 && L.C == 28 && !prefetch && !getenv("MNNQ_DECODE_KSPLIT")) unroll = 7;
+    if (ks == 4 && L.C == 28 && !prefetch && !debug_option(kDbgDecodeKsplit)) unroll = 7;
     // x staged under the weight stream: small layers whose waves have at most two chunks fewer than `unroll`,
     // and those whose waves all have exactly `unroll` chunks
     const bool exact = L.C % ks == 0 && L.C / ks == unroll;
     bool early = !prefetch && (((int64_t)L.total() <= (16 << 20) && L.C / ks >= unroll - 2) || exact);
-    if (const char* e = getenv("MNNQ_DECODE_EARLY")) early = !prefetch && e[0] == '1';   // tests and tuning
+    if (const char* e = debug_option(kDbgDecodeEarly)) early = !prefetch && e[0] == '1';   // tests and tuning
 #define MNNQ_CFG(W, K, U, P)                                                              \
     if (ks == K && unroll == U && prefetch == P) {                                        \
         if constexpr (P == 0) {                                                           \

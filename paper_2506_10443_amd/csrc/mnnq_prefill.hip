@@ -628,7 +628,7 @@ TilePlan plan_tiles(const Layout& L, int64_t M)
     } else {
         p.big = false;
     }
-    if (const char* e = getenv("MNNQ_PREFILL_TILE")) {   // tuning and tests: "b"/"s", split digit, "k" = K parts
+    if (const char* e = debug_option(kDbgPrefillTile)) {   // tuning and tests: "b"/"s", split digit, "k" = K parts
         if (e[0] == 'b' || e[0] == 'w') p.big = true;
         if (e[0] == 's' || e[0] == 'v' || e[0] == 't' || e[0] == 'n') p.big = false;
         p.wide = (e[0] == 'w' || e[0] == 'v');     // "w"/"v" = "b"/"s" worked on by twice the waves
@@ -672,11 +672,11 @@ PrefillLaunch resolve_prefill(const Layout& L, int64_t M)
 {
     TilePlan p = plan_tiles(L, M);
     if (L.out16) p.S = 1;   // the split over two workgroups adds fp32 partial sums in the output array
-    const bool forced_plan = getenv("MNNQ_PREFILL_TILE") != nullptr;
+    const bool forced_plan = debug_option(kDbgPrefillTile) != nullptr;
     PrefillLaunch r{p.big ? 256 : (p.tiny ? 64 : 128), p.KS, p.S, 2, false, p.narrow ? 64 : 128};
     // 8-bit weights: both nibble planes of a chunk in one MFMA (128-row tiles: two B tiles need the LDS
     // of the larger A tile).  MNNQ_W8_PLANES=1 (tests, comparisons) keeps one MFMA per plane instead.
-    const char* planes = getenv("MNNQ_W8_PLANES");
+    const char* planes = debug_option(kDbgW8Planes);
     if (L.mode == MNNQ_W8_MIN_FLOAT && !(planes && planes[0] == '1')) {
         r.w8 = true;
         r.BM = 128;

@@ -474,11 +474,10 @@ int tmp_tiles(int64_t M) { return (int)(((M + 31) / 32 + kPlaneTilePad - 1) / kP
 // Tile plans (all waves own 64 rows): 0 = 128 x 128 tiles of four waves (two workgroups per CU),
 // 1 = 128 x 128 with the K range in two parts (eight waves), 2 = 128 x 256 of four waves (64 x 128
 // outputs per wave, two workgroups per CU), 3 = 128 x 256 with two K parts, 4 = 256 x 256 of eight waves.
-int g_force_plan6 = -1;
-
 int choose_plan6(const Layout& L, int64_t M)
 {
-    if (g_force_plan6 >= 0) return g_force_plan6;
+    if (const char* e = debug_option(kDbgPrefill6Plan))   // tests and tuning
+        if (e[0] >= '0' && e[0] <= '4') return e[0] - '0';
     const int64_t cus = num_cus();
     auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((L.N + bn - 1) / bn); };
     auto eff = [&](int64_t t, int64_t slots) { return (double)t / (double)((t + slots - 1) / slots * slots); };
@@ -512,8 +511,6 @@ Plan6Info plan6_info(int plan)
 }
 
 }  // namespace
-
-void set_prefill6_plan(int plan) { g_force_plan6 = plan; }
 
 size_t prefill6_ws_bytes(int64_t M, int64_t K) { return (size_t)(K / kGroup) * tmp_tiles(M) * 2 * kPlaneBlockBytes; }
 

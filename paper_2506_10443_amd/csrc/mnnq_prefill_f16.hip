@@ -467,7 +467,7 @@ int launch_prefill_f16(const uint8_t* packed, const Layout& L, int64_t M, const 
     bool big = M > 128 && tiles_big >= 2 * (int64_t)cus;
     // at most one 128-row tile per CU: split the chunks over the two halves of an eight-wave workgroup
     int ks = (!big && tiles_small <= (int64_t)cus && L.C >= 4) ? 2 : 1;
-    if (const char* e = getenv("MNNQ_PREFILL_TILE")) {   // tuning and tests: "b"/"s" tile, third letter "k" = K parts
+    if (const char* e = debug_option(kDbgPrefillTile)) {   // tuning and tests: "b"/"s" tile, third letter "k" = K parts
         if (e[0] == 'b') big = true;
         if (e[0] == 's') big = false;
         if (e[0]) ks = (e[1] && e[2] == 'k') ? 2 : 1;

@@ -375,14 +375,14 @@ int launch_skinny(const uint8_t* packed, const Layout& L, int64_t M, const int8_
     // activations), which a workgroup of 16 waves could not hold for 8 chunks.
     int ks = 1;
     while (ks < 8 && (L.C + ks - 1) / ks > 8) ks *= 2;
-    if (const char* e = getenv("MNNQ_DECODE_KSPLIT")) {   // tests and tuning: force the split
+    if (const char* e = debug_option(kDbgDecodeKsplit)) {   // tests and tuning: force the split
         const int v = atoi(e);
         if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16) ks = v > 8 ? 8 : v;
     }
     const bool prefetch = (L.C + ks - 1) / ks > 8;
     // Staging pays once the layer is large enough to be bandwidth bound (measured: above ~16 MiB).
     bool staged = L.C <= 32 && !prefetch && L.T * L.C >= 16384;
-    if (const char* e = getenv("MNNQ_SKINNY_STAGED")) staged = L.C <= 32 && !prefetch && e[0] == '1';   // tests
+    if (const char* e = debug_option(kDbgSkinnyStaged)) staged = L.C <= 32 && !prefetch && e[0] == '1';   // tests
     const int m = (int)M;
 #define MNNQ_CFG(W, K)                                                                                 \
     if (ks == K) {                                                                                     \

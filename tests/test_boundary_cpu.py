@@ -151,8 +151,7 @@ def test_argument_validation_precedes_hip(L):
     assert ad(FAKE, 64, 64, 128, 64, PL, FAKE, FAKE, None, 0, None) == NULL
     assert ad(FAKE, 64, 64, 128, 64, PL, FAKE, FAKE, FAKE, 100, None) == SIZE
     assert ad(FAKE, 64, 64, 128, 64, 0, FAKE, FAKE, FAKE, 10**9, None) == UNSUP
-    assert L.mnnq_debug_force_plan(5, 0) == UNSUP and L.mnnq_debug_force_plan(6, 9) == UNSUP
-    assert L.mnnq_debug_force_plan(6, 2) == OK and L.mnnq_debug_force_plan(6, -1) == OK
+    assert L.mnnq_debug_set(b"MNNQ_PREFILL6_PLAN", b"2") == OK and L.mnnq_debug_set(b"MNNQ_PREFILL6_PLAN", None) == OK
     st = L.mnnq_linear_prefill_fused_static
     assert st(None, 4, 16, 128, 64, 0, FAKE, None, FAKE, None) == NULL
     assert st(FAKE, 4096, 16, 8192, 64, 0, FAKE, None, FAKE, None) == SIZE          # codes and scales beyond the array

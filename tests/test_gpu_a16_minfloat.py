@@ -51,15 +51,15 @@ def test_a16_matches_oracle(M, N, K, which):
     tol = TOL_A16 * np.abs(y_o).max()
     for tile in ("", "b", "s", "b1k", "s1k"):
         if tile:
-            os.environ["MNNQ_PREFILL_TILE"] = tile
+            B.mnnq_debug_set("MNNQ_PREFILL_TILE", tile)
         try:
             y = host(B.mnnq_linear_prefill_f16(packed, N, K, xd, bias=dev(bias), mode=mode))
         finally:
-            os.environ.pop("MNNQ_PREFILL_TILE", None)
+            B.mnnq_debug_set("MNNQ_PREFILL_TILE", None)
         assert np.abs(y - y_o).max() <= tol, (tile, np.abs(y - y_o).max(), tol)
     for ks in ("", "1", "2", "4", "8", "16"):
         if ks:
-            os.environ["MNNQ_DECODE_KSPLIT"] = ks
+            B.mnnq_debug_set("MNNQ_DECODE_KSPLIT", ks)
         try:
             y0 = host(B.mnnq_linear_decode_f16(packed, N, K, xd[0].contiguous(), bias=dev(bias), mode=mode))
         except B.MnnqError as e:
@@ -67,7 +67,7 @@ def test_a16_matches_oracle(M, N, K, which):
             assert ks and e.status == -3, (ks, e)
             continue
         finally:
-            os.environ.pop("MNNQ_DECODE_KSPLIT", None)
+            B.mnnq_debug_set("MNNQ_DECODE_KSPLIT", None)
         assert np.abs(y0 - y_o[0]).max() <= TOL_A16 * np.abs(y_o[0]).max(), ks
 
 

@@ -83,11 +83,11 @@ def check_w4a8_layer(model, name, M, seed, n_samples=4096, acc_rows=8):
     assert np.abs(yw - y0[0]).max() <= tol0
     if packed.numel() > (96 << 20):
         assert np.array_equal(yw, yd)
-    os.environ["MNNQ_FUSED_TWO_KERNEL_MIB"] = "0"       # ... forced for any size
+    B.mnnq_debug_set("MNNQ_FUSED_TWO_KERNEL_MIB", "0")       # ... forced for any size
     try:
         yw = B.mnnq_linear_decode_fused(packed, N, K, dev(x[0]), workspace=ws).cpu().numpy()
     finally:
-        os.environ.pop("MNNQ_FUSED_TWO_KERNEL_MIB", None)
+        B.mnnq_debug_set("MNNQ_FUSED_TWO_KERNEL_MIB", None)
     assert np.array_equal(yw, yd)
     # the same row out of the prefill kernel agrees with the decode kernel to the same bound
     assert np.abs(y[0] - y0[0]).max() <= tol0

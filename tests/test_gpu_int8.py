@@ -76,27 +76,27 @@ def test_linear_matches_oracle(M, N, K):
     assert np.abs(y - y_o).max() <= tol, (np.abs(y - y_o).max(), tol)
     # every tile plan, with both nibble planes merged into one matrix instruction per group (the
     # default) and with one per plane; "2" splits K over two workgroups (long rows only)
-    os.environ["MNNQ_NO_SKINNY"] = "1"
+    B.mnnq_debug_set("MNNQ_NO_SKINNY", "1")
     try:
         for planes in ("0", "1"):
             for cfg in ("b1", "s1", "b1k", "s1k", "s2", "s2k", "v1k", "v2k"):
-                os.environ["MNNQ_PREFILL_TILE"] = cfg
-                os.environ["MNNQ_W8_PLANES"] = planes
+                B.mnnq_debug_set("MNNQ_PREFILL_TILE", cfg)
+                B.mnnq_debug_set("MNNQ_W8_PLANES", planes)
                 try:
                     y2 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd, mode=W8))
                 finally:
-                    os.environ.pop("MNNQ_PREFILL_TILE", None)
-                    os.environ.pop("MNNQ_W8_PLANES", None)
+                    B.mnnq_debug_set("MNNQ_PREFILL_TILE", None)
+                    B.mnnq_debug_set("MNNQ_W8_PLANES", None)
                 assert np.abs(y2 - y_o).max() <= tol, (planes, cfg)
     finally:
-        os.environ.pop("MNNQ_NO_SKINNY", None)
+        B.mnnq_debug_set("MNNQ_NO_SKINNY", None)
     if M <= 16:
         for staged in ("0", "1"):
-            os.environ["MNNQ_SKINNY_STAGED"] = staged
+            B.mnnq_debug_set("MNNQ_SKINNY_STAGED", staged)
             try:
                 y3 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd, mode=W8))
             finally:
-                os.environ.pop("MNNQ_SKINNY_STAGED", None)
+                B.mnnq_debug_set("MNNQ_SKINNY_STAGED", None)
             assert np.abs(y3 - y_o).max() <= tol, staged
     for m in sorted({0, M - 1}):
         y0 = host(B.mnnq_linear_decode(packed, N, K, xqd[m].contiguous(), sxd[m:m + 1].contiguous(), bias=bd, mode=W8))

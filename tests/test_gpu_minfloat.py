@@ -73,22 +73,22 @@ def test_linear_matches_oracle(M, N, K):
     # prefill, every tile / split choice
     y = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd, mode=MINF))
     assert np.abs(y - y_o).max() <= tol, (np.abs(y - y_o).max(), tol)
-    os.environ["MNNQ_NO_SKINNY"] = "1"     # M <= 16 would otherwise bypass the tiled kernel
+    B.mnnq_debug_set("MNNQ_NO_SKINNY", "1")     # M <= 16 would otherwise bypass the tiled kernel
     try:
         for cfg in ("b1", "s1", "b1k", "s1k", "s2", "b2k", "w1", "w2", "v1k", "v2k", "w1k", "t1", "t1k", "t2q", "n1", "n2q"):
-            os.environ["MNNQ_PREFILL_TILE"] = cfg
+            B.mnnq_debug_set("MNNQ_PREFILL_TILE", cfg)
             try:
                 y2 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd, mode=MINF))
             finally:
-                os.environ.pop("MNNQ_PREFILL_TILE", None)
+                B.mnnq_debug_set("MNNQ_PREFILL_TILE", None)
             assert np.abs(y2 - y_o).max() <= tol, cfg
     finally:
-        os.environ.pop("MNNQ_NO_SKINNY", None)
+        B.mnnq_debug_set("MNNQ_NO_SKINNY", None)
     # decode of a few rows, every K split, and the fused quantizer
     for m in sorted({0, M // 2, M - 1}):
         for ks in ("", "1", "2", "4", "8", "16"):
             if ks:
-                os.environ["MNNQ_DECODE_KSPLIT"] = ks
+                B.mnnq_debug_set("MNNQ_DECODE_KSPLIT", ks)
             try:
                 y0 = host(B.mnnq_linear_decode(packed, N, K, xqd[m].contiguous(), sxd[m:m + 1].contiguous(),
                                                bias=bd, mode=MINF))
@@ -97,7 +97,7 @@ def test_linear_matches_oracle(M, N, K):
                 assert ks and e.status == -3 and K > 8192, (ks, e)
                 continue
             finally:
-                os.environ.pop("MNNQ_DECODE_KSPLIT", None)
+                B.mnnq_debug_set("MNNQ_DECODE_KSPLIT", None)
             assert np.abs(y0 - y_o[m]).max() <= tol, (m, ks)
         yf = host(B.mnnq_linear_decode_fused(packed, N, K, dev(x[m]), bias=bd, mode=MINF))
         assert np.abs(yf - y_o[m]).max() <= tol, m

@@ -52,14 +52,14 @@ def test_w4a8_out16(M, N, K):
     xqd, sxd, bd = dev(xq), dev(sx), dev(bias)
     for cfg in ("", "b1", "s1", "b1k", "s1k", "w1", "v1k", "w1k", "t1", "t1q", "n1", "n1q"):
         if cfg:
-            os.environ["MNNQ_PREFILL_TILE"] = cfg
-            os.environ["MNNQ_NO_SKINNY"] = "1"
+            B.mnnq_debug_set("MNNQ_PREFILL_TILE", cfg)
+            B.mnnq_debug_set("MNNQ_NO_SKINNY", "1")
         try:
             y32 = B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd)
             y16 = B.mnnq_linear_prefill_o16(packed, N, K, xqd, sxd, bias=bd)
         finally:
-            os.environ.pop("MNNQ_PREFILL_TILE", None)
-            os.environ.pop("MNNQ_NO_SKINNY", None)
+            B.mnnq_debug_set("MNNQ_PREFILL_TILE", None)
+            B.mnnq_debug_set("MNNQ_NO_SKINNY", None)
         assert y16.dtype == torch.float16
         if K < 8192 or cfg:       # same tile plan and summation order as the fp32 call
             assert torch.equal(y16, y32.to(torch.float16)), cfg
@@ -73,12 +73,12 @@ def test_w4a8_out16(M, N, K):
     if M <= 16 and K <= 4096:
         # both few-token kernels (the persistent one is normally reserved for large layers)
         for staged in ("0", "1"):
-            os.environ["MNNQ_SKINNY_STAGED"] = staged
+            B.mnnq_debug_set("MNNQ_SKINNY_STAGED", staged)
             try:
                 y32 = B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd)
                 y16 = B.mnnq_linear_prefill_o16(packed, N, K, xqd, sxd, bias=bd)
             finally:
-                os.environ.pop("MNNQ_SKINNY_STAGED", None)
+                B.mnnq_debug_set("MNNQ_SKINNY_STAGED", None)
             assert torch.equal(y16, y32.to(torch.float16)), staged
             close_to_oracle(host(y16), y_o, TOL_A8)
 
@@ -95,12 +95,12 @@ def test_w4a16_out16(M, N, K):
     xd, bd = dev(x16), dev(bias)
     for cfg in ("", "s1", "b1", "s1k", "b1k"):       # tile and K parts of the fp16 GEMM
         if cfg:
-            os.environ["MNNQ_PREFILL_TILE"] = cfg
+            B.mnnq_debug_set("MNNQ_PREFILL_TILE", cfg)
         try:
             y32 = B.mnnq_linear_prefill_f16(packed, N, K, xd, bias=bd)
             y16 = B.mnnq_linear_prefill_f16_o16(packed, N, K, xd, bias=bd)
         finally:
-            os.environ.pop("MNNQ_PREFILL_TILE", None)
+            B.mnnq_debug_set("MNNQ_PREFILL_TILE", None)
         assert torch.equal(y16, y32.to(torch.float16)), cfg
         close_to_oracle(host(y16), y_o, TOL_A16)
     y32 = B.mnnq_linear_decode_f16(packed, N, K, xd[0].contiguous(), bias=bd)
@@ -160,11 +160,11 @@ def test_fused_calls_out16(M, N, K):
     ws = torch.empty(B.mnnq_workspace_size(1, N, K), dtype=torch.uint8, device="cuda:0")
     for workspace, two_kernel in ((None, None), (ws, "0")):
         if two_kernel is not None:
-            os.environ["MNNQ_FUSED_TWO_KERNEL_MIB"] = two_kernel   # quantizer as a kernel of its own
+            B.mnnq_debug_set("MNNQ_FUSED_TWO_KERNEL_MIB", two_kernel)   # quantizer as a kernel of its own
         try:
             r32 = B.mnnq_linear_decode_fused(packed, N, K, xd[0].contiguous(), bias=bd, workspace=workspace)
             r16 = B.mnnq_linear_decode_fused_o16(packed, N, K, xd[0].contiguous(), bias=bd, workspace=workspace)
         finally:
-            os.environ.pop("MNNQ_FUSED_TWO_KERNEL_MIB", None)
+            B.mnnq_debug_set("MNNQ_FUSED_TWO_KERNEL_MIB", None)
         assert r16.dtype == torch.float16 and torch.equal(r16, r32.to(torch.float16))
         close_to_oracle(host(r16), y_o[0], TOL_A8)

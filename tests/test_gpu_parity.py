@@ -181,13 +181,13 @@ def test_decode_matches_oracle(N, K):
     results = []
     for ks in ("", "1", "2", "4", "8", "16"):
         if ks:
-            os.environ["MNNQ_DECODE_KSPLIT"] = ks
+            B.mnnq_debug_set("MNNQ_DECODE_KSPLIT", ks)
         else:
-            os.environ.pop("MNNQ_DECODE_KSPLIT", None)
+            B.mnnq_debug_set("MNNQ_DECODE_KSPLIT", None)
         try:
             y = host(B.mnnq_linear_decode(packed, N, K, xqd, sxd))
         finally:
-            os.environ.pop("MNNQ_DECODE_KSPLIT", None)
+            B.mnnq_debug_set("MNNQ_DECODE_KSPLIT", None)
         err = np.abs(y - y_o[0]).max()
         assert err <= tol, (ks, err, tol)
         results.append(y)
@@ -197,14 +197,14 @@ def test_decode_matches_oracle(N, K):
     for ks in ("", "1", "4", "16"):
         pair = []
         for early in ("0", "1"):
-            os.environ["MNNQ_DECODE_EARLY"] = early
+            B.mnnq_debug_set("MNNQ_DECODE_EARLY", early)
             if ks:
-                os.environ["MNNQ_DECODE_KSPLIT"] = ks
+                B.mnnq_debug_set("MNNQ_DECODE_KSPLIT", ks)
             try:
                 pair.append(host(B.mnnq_linear_decode(packed, N, K, xqd, sxd)))
             finally:
-                os.environ.pop("MNNQ_DECODE_EARLY", None)
-                os.environ.pop("MNNQ_DECODE_KSPLIT", None)
+                B.mnnq_debug_set("MNNQ_DECODE_EARLY", None)
+                B.mnnq_debug_set("MNNQ_DECODE_KSPLIT", None)
         assert np.array_equal(pair[0], pair[1]), ks
         assert np.abs(pair[1] - y_o[0]).max() <= tol, ks
     # fused activation quantizer: same codes -> same result up to the summation order
@@ -216,14 +216,14 @@ def test_decode_matches_oracle(N, K):
     for ks in ("", "1", "4", "8", "16"):
         pair = []
         for early in ("0", "1"):
-            os.environ["MNNQ_DECODE_EARLY"] = early
+            B.mnnq_debug_set("MNNQ_DECODE_EARLY", early)
             if ks:
-                os.environ["MNNQ_DECODE_KSPLIT"] = ks
+                B.mnnq_debug_set("MNNQ_DECODE_KSPLIT", ks)
             try:
                 pair.append(host(B.mnnq_linear_decode_fused(packed, N, K, xd)))
             finally:
-                os.environ.pop("MNNQ_DECODE_EARLY", None)
-                os.environ.pop("MNNQ_DECODE_KSPLIT", None)
+                B.mnnq_debug_set("MNNQ_DECODE_EARLY", None)
+                B.mnnq_debug_set("MNNQ_DECODE_KSPLIT", None)
         assert np.array_equal(pair[0], pair[1]), ks
         assert np.abs(pair[1] - y_o[0]).max() <= tol, ks
 
@@ -323,12 +323,12 @@ def test_prefill_matches_oracle(M, N, K):
     assert np.array_equal(y, y2)
     # every tile / split choice gives the same result to the same tolerance
     for cfg in ("b1", "b2", "s1", "s2", "b1k", "s1k", "b2k", "s2k", "w1", "w2", "v1k", "v2k", "w1k", "w2k", "t1", "t2", "t1k", "t1q", "t2q", "n1", "n2", "n1k", "n1q", "n2q"):
-        os.environ["MNNQ_PREFILL_TILE"] = cfg
+        B.mnnq_debug_set("MNNQ_PREFILL_TILE", cfg)
         try:
             y3 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=dev(bias)))
             y4 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=dev(bias)))
         finally:
-            os.environ.pop("MNNQ_PREFILL_TILE", None)
+            B.mnnq_debug_set("MNNQ_PREFILL_TILE", None)
         assert np.abs(y3 - y_o).max() <= tol, cfg
         assert np.array_equal(y3, y4), cfg           # two commuting addends: still reproducible
     # decode of row 0 agrees with prefill row 0 to the same tolerance
@@ -348,24 +348,24 @@ def test_few_tokens_share_one_pass_over_the_weights(M, N, K):
     packed = B.mnnq_pack_weights(dev(W))
     xqd, sxd, bd = dev(xq), dev(sx), dev(bias)
     for staged in ("0", "1"):        # activations straight from L2, or shared through LDS
-        os.environ["MNNQ_SKINNY_STAGED"] = staged
+        B.mnnq_debug_set("MNNQ_SKINNY_STAGED", staged)
         for ks in ("", "1", "2", "4", "8"):
             if ks:
-                os.environ["MNNQ_DECODE_KSPLIT"] = ks
+                B.mnnq_debug_set("MNNQ_DECODE_KSPLIT", ks)
             try:
                 y = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd))
                 y2 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd))
             finally:
-                os.environ.pop("MNNQ_DECODE_KSPLIT", None)
+                B.mnnq_debug_set("MNNQ_DECODE_KSPLIT", None)
             assert np.abs(y - y_o).max() <= tol, (staged, ks)
             assert np.array_equal(y, y2), (staged, ks)
-        os.environ.pop("MNNQ_SKINNY_STAGED", None)
+        B.mnnq_debug_set("MNNQ_SKINNY_STAGED", None)
     # the tiled GEMM kernel on the same input
-    os.environ["MNNQ_NO_SKINNY"] = "1"
+    B.mnnq_debug_set("MNNQ_NO_SKINNY", "1")
     try:
         y3 = host(B.mnnq_linear_prefill(packed, N, K, xqd, sxd, bias=bd))
     finally:
-        os.environ.pop("MNNQ_NO_SKINNY", None)
+        B.mnnq_debug_set("MNNQ_NO_SKINNY", None)
     assert np.abs(y3 - y_o).max() <= tol
     # every token agrees with the one-token GEMV to the same bound
     for m in range(M):
@@ -447,14 +447,14 @@ def test_w4a16_matches_oracle(M, N, K):
     for ks in ("", "1", "2", "4", "8", "16"):
         pair = []
         for early in ("0", "1"):     # x staged after or under the weight stream: the same sums
-            os.environ["MNNQ_DECODE_EARLY"] = early
+            B.mnnq_debug_set("MNNQ_DECODE_EARLY", early)
             if ks:
-                os.environ["MNNQ_DECODE_KSPLIT"] = ks
+                B.mnnq_debug_set("MNNQ_DECODE_KSPLIT", ks)
             try:
                 pair.append(host(B.mnnq_linear_decode_f16(packed, N, K, xd[0].contiguous(), bias=dev(bias))))
             finally:
-                os.environ.pop("MNNQ_DECODE_KSPLIT", None)
-                os.environ.pop("MNNQ_DECODE_EARLY", None)
+                B.mnnq_debug_set("MNNQ_DECODE_KSPLIT", None)
+                B.mnnq_debug_set("MNNQ_DECODE_EARLY", None)
         assert np.array_equal(pair[0], pair[1]), ks
         assert np.abs(pair[1] - y_o[0]).max() <= TOL_A16 * np.abs(y_o[0]).max(), ks
     y0 = host(B.mnnq_linear_decode_f16(packed, N, K, xd[0].contiguous(), bias=dev(bias)))
@@ -477,17 +477,17 @@ def test_prefill_f16_with_integer_codes_equals_int8_prefill(M, N, K, tile):
     bias = dev(synth.weights(1, N, 7)[0] * 10)
     y8 = {}
     for plan in ("s1", "s1k"):
-        os.environ["MNNQ_PREFILL_TILE"] = plan
+        B.mnnq_debug_set("MNNQ_PREFILL_TILE", plan)
         try:
             y8[plan] = B.mnnq_linear_prefill(packed, N, K, xq, sx, bias=bias)
         finally:
-            os.environ.pop("MNNQ_PREFILL_TILE", None)
+            B.mnnq_debug_set("MNNQ_PREFILL_TILE", None)
     if tile:
-        os.environ["MNNQ_PREFILL_TILE"] = tile
+        B.mnnq_debug_set("MNNQ_PREFILL_TILE", tile)
     try:
         y16 = B.mnnq_linear_prefill_f16(packed, N, K, xq.to(torch.float16), bias=bias, row_scale=sx)
     finally:
-        os.environ.pop("MNNQ_PREFILL_TILE", None)
+        B.mnnq_debug_set("MNNQ_PREFILL_TILE", None)
     if tile == "":
         assert torch.equal(y8["s1"], y16) or torch.equal(y8["s1k"], y16)
     else:

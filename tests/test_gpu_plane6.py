@@ -25,7 +25,7 @@ def note(*a):
 @pytest.fixture(autouse=True)
 def _auto_plan():
     yield
-    B.mnnq_debug_force_plan(6, -1)
+    B.mnnq_debug_set("MNNQ_PREFILL6_PLAN", None)
 
 
 def make(N, K, M, seed, special=False):
@@ -70,7 +70,7 @@ def test_prefill6_every_plan(plan, M, N, K):
     acc_o, y_o = oracle.linear_w4a8(xq, sx, q, s, z)
     packed = B.mnnq_pack_weights(dev(W), mode=MODE)
     ws = torch.empty(B.mnnq_workspace_size(M, N, K, 64, MODE), dtype=torch.uint8, device="cuda:0")
-    B.mnnq_debug_force_plan(6, plan)
+    B.mnnq_debug_set("MNNQ_PREFILL6_PLAN", plan)
     assert B.mnnq_plan_debug(0, M, N, K, mode=MODE)[7] == 6
     y = B.mnnq_linear_prefill(packed, N, K, dev(xq), dev(sx), mode=MODE, workspace=ws).cpu().numpy()
     err = np.abs(y - y_o).max()

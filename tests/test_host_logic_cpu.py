@@ -17,7 +17,7 @@ def built():
         import __graft_entry__
         __graft_entry__.build()
     for v in ("MNNQ_PREFILL_TILE", "MNNQ_DECODE_KSPLIT", "MNNQ_DECODE_WAVES", "MNNQ_DECODE_EARLY", "MNNQ_W8_PLANES"):
-        os.environ.pop(v, None)
+        B.mnnq_debug_set(v, None)
 
 
 def shapes():
@@ -101,17 +101,25 @@ def test_documented_plans_for_few_tokens():
 
 
 def test_switches_and_errors():
-    os.environ["MNNQ_PREFILL_TILE"] = "s1"
+    B.mnnq_debug_set("MNNQ_PREFILL_TILE", "s1")
     try:
         assert B.mnnq_plan_debug(0, 1024, 37888, 3584)[:5] == [128, 128, 1, 1, 4]
     finally:
-        os.environ.pop("MNNQ_PREFILL_TILE")
-    os.environ["MNNQ_W8_PLANES"] = "1"
+        B.mnnq_debug_set("MNNQ_PREFILL_TILE", None)
+    B.mnnq_debug_set("MNNQ_W8_PLANES", "1")
     try:
         assert B.mnnq_plan_debug(0, 1024, 37888, 3584, B.MODE_W8_MIN_FLOAT)[7] == 0
     finally:
-        os.environ.pop("MNNQ_W8_PLANES")
+        B.mnnq_debug_set("MNNQ_W8_PLANES", None)
+    # the library does not read the environment: a stray variable changes nothing
+    os.environ["MNNQ_PREFILL_TILE"] = "s1"
+    try:
+        assert B.mnnq_plan_debug(0, 1024, 37888, 3584)[:5] != [128, 128, 1, 1, 4]
+    finally:
+        os.environ.pop("MNNQ_PREFILL_TILE")
     L = B.lib()
+    assert L.mnnq_debug_set(b"MNNQ_NO_SUCH_SWITCH", b"1") == -3 and L.mnnq_debug_set(None, b"1") == -1
+    assert L.mnnq_debug_set(b"MNNQ_PREFILL_TILE", b"0123456789abcdef") == -4
     assert L.mnnq_plan_debug(0, 4, 16, 128, 64, 0, None) == -1
     import ctypes
     out = (ctypes.c_int32 * 8)()
