@@ -21,7 +21,7 @@
  *     checks run before the first HIP call, so they also work on a machine
  *     without a GPU.  NaN / Inf in W or x: undefined result, no error.
  *   - Limits (MNNQ_ERR_UNSUPPORTED beyond them): N and K up to 2^24.  Decode calls: K up to
- *     126976 (with fp16 activations 80640, or 71680 in the float-minimum modes; for int8
+ *     126976 (with fp16 activations 79872, or 71680 in the float-minimum modes; for int8
  *     weights half of these), the row is staged in LDS.  Prefill calls address with 32-bit byte offsets: the packed matrix
  *     must stay below 2 GiB; batches for which (M + 256) * K (twice that with fp16 activations) or
  *     (M + 256) * N * 4 reaches 2 GiB are processed in slabs of rows, one launch per slab.

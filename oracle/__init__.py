@@ -19,7 +19,10 @@ import numpy as np
 GROUP = 64
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "mnnq_oracle.c")
-_LIB = os.path.join(_HERE, "libmnnq_oracle.so")
+# MNNQ_ORACLE_SANITIZE=1 (tests only): a second build with AddressSanitizer and UndefinedBehaviorSanitizer;
+# the process must then have been started with libasan preloaded.
+_SANITIZE = os.environ.get("MNNQ_ORACLE_SANITIZE") == "1"
+_LIB = os.path.join(_HERE, "libmnnq_oracle_san.so" if _SANITIZE else "libmnnq_oracle.so")
 _lock = threading.Lock()
 _lib = None
 
@@ -31,6 +34,9 @@ def build(force: bool = False) -> str:
         tmp = _LIB + ".tmp.%d" % os.getpid()
         cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
                "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"]
+        if _SANITIZE:
+            cmd[1:2] = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                        "-fno-sanitize-recover=all"]
         subprocess.run(cmd, check=True)
         os.replace(tmp, _LIB)
     return _LIB

@@ -34,8 +34,10 @@ const char* debug_option(DebugKey key) { return g_debug[key].set ? g_debug[key].
 namespace {
 
 constexpr int64_t kMaxDecodeK = 126976;    // int8 row + block sums in LDS: 160 B per 128 k, under 160 KiB
-constexpr int64_t kMaxDecodeKF16 = 80640;  // fp16 row in LDS: 256 B per 128 k, under 160 KiB
-constexpr int64_t kMaxDecodeKF16Min = 71680;  // float minimum form: 32 B of block sums more per 128 k
+// fp16 row in LDS: sixteen waves stage ceil(C / 16) chunks of 128 values each, 256 B per chunk, plus 1 KiB
+// of partial sums, under 160 KiB: at most 39 chunks per wave, C <= 624
+constexpr int64_t kMaxDecodeKF16 = 79872;
+constexpr int64_t kMaxDecodeKF16Min = 71680;  // float minimum form: 32 B of block sums more per chunk (35 chunks per wave)
 constexpr int64_t kMaxM = 65535;
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }

@@ -121,7 +121,7 @@ def test_argument_validation_precedes_hip(L):
     assert L.mnnq_linear_decode_f16(FAKE, 16, 100, 64, 0, FAKE, None, FAKE, None, 0, None) == SHAPE
     assert L.mnnq_linear_decode_f16(FAKE, 16, 128, 64, 3, FAKE, None, FAKE, None, 0, None) == UNSUP   # no such mode
     assert L.mnnq_linear_decode_f16(FAKE, 16, 192, 64, 2, FAKE, None, FAKE, None, 0, None) == UNSUP   # int8 weights: K % 128
-    assert L.mnnq_linear_decode_f16(FAKE, 16, 80640 + 64, 64, 0, FAKE, None, FAKE, None, 0, None) == UNSUP  # row too long for LDS
+    assert L.mnnq_linear_decode_f16(FAKE, 16, 79872 + 64, 64, 0, FAKE, None, FAKE, None, 0, None) == UNSUP  # row too long for LDS
     assert L.mnnq_linear_decode_f16(FAKE, 16, 71680 + 64, 64, 1, FAKE, None, FAKE, None, 0, None) == UNSUP  # same, float minimum
     assert L.mnnq_linear_decode_f16(FAKE, 16, 35840 + 128, 64, 2, FAKE, None, FAKE, None, 0, None) == UNSUP  # same, two planes
     assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 128, 64, 3, FAKE, None, None, FAKE, None, 0, None) == UNSUP

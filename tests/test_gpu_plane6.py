@@ -109,3 +109,17 @@ def test_prefill6_bias_fused_and_fallbacks():
     # the entry point without allocations takes the plane too
     ys = B.mnnq_linear_prefill_fused_static(packed, N, K, dev(x), bias=dev(bias), mode=MODE).cpu().numpy()
     assert np.array_equal(ys, yf)
+
+
+def test_act_planes_and_gemm_as_separate_calls():
+    M, N, K = 300, 768, 1536
+    W, x, q, s, z, xq, sx = make(N, K, M, 4500)
+    _, y_o = oracle.linear_w4a8(xq, sx, q, s, z)
+    packed = B.mnnq_pack_weights(dev(W), mode=MODE)
+    ws = torch.empty(B.mnnq_workspace_size(M, N, K, 64, MODE), dtype=torch.uint8, device="cuda:0")
+    y_ws = B.mnnq_linear_prefill(packed, N, K, dev(xq), dev(sx), mode=MODE, workspace=ws)
+    planes = B.mnnq_act_planes(dev(xq))
+    assert planes.numel() == B.lib().mnnq_act_planes_size(M, K, 64)
+    y_pl = B.mnnq_linear_prefill_planes(packed, M, N, K, planes, dev(sx), mode=MODE)
+    assert torch.equal(y_pl, y_ws)
+    assert np.abs(y_pl.cpu().numpy() - y_o).max() <= TOL_A8 * np.abs(y_o).max()
