@@ -299,16 +299,21 @@ def main() -> int:
             for name, N, K in self.layers:
                 xs, xq, sx, y, ws = self.io_pre[name]
                 nb = self.n_blocks
-                tq = time_graph([(lambda x=xs[b]: B.mnnq_quant_act(x, want_xsum=False, out=(xq, sx, None))) for b in range(nb)], 2)
+                # (every loop variable a launch uses is bound as a default argument: the launches are replayed again
+                # after the loop, when the names point at the last layer)
+                tq = time_graph([(lambda x=xs[b], xq=xq, sx=sx: B.mnnq_quant_act(x, want_xsum=False, out=(xq, sx, None)))
+                                 for b in range(nb)], 2)
                 entry = {"quant_us": round(tq * 1e3, 2)}
                 if self.plane and self.M > 32:
                     planes = ws[:B.lib().mnnq_act_planes_size(self.M, K, 64)]
-                    tp = time_graph([lambda: B.mnnq_act_planes(xq, out=planes)] * nb, 2)
-                    lay = [(lambda p=self.packed[name][b]: B.mnnq_linear_prefill_planes(p, self.M, N, K, planes, sx, out=y, mode=self.mode))
+                    tp = time_graph([lambda xq=xq, planes=planes: B.mnnq_act_planes(xq, out=planes)] * nb, 2)
+                    lay = [(lambda p=self.packed[name][b], N=N, K=K, planes=planes, sx=sx, y=y:
+                            B.mnnq_linear_prefill_planes(p, self.M, N, K, planes, sx, out=y, mode=self.mode))
                            for b in range(nb)]
                     entry["planes_us"] = round(tp * 1e3, 2)
                 else:
-                    lay = [(lambda p=self.packed[name][b]: B.mnnq_linear_prefill(p, N, K, xq, sx, out=y, mode=self.mode))
+                    lay = [(lambda p=self.packed[name][b], N=N, K=K, xq=xq, sx=sx, y=y:
+                            B.mnnq_linear_prefill(p, N, K, xq, sx, out=y, mode=self.mode))
                            for b in range(nb)]
                 tg = time_graph(lay, 2)
                 entry["gemm_us"] = round(tg * 1e3, 2)
@@ -323,13 +328,15 @@ def main() -> int:
             per, fns = {}, []
             for name, N, K in self.layers:
                 io = self.io_dec[name]
-                lay = [(lambda p=self.packed[name][b]: self.decode_layer(p, N, K, io, fused)) for b in range(self.n_blocks)]
+                lay = [(lambda p=self.packed[name][b], N=N, K=K, io=io: self.decode_layer(p, N, K, io, fused))
+                       for b in range(self.n_blocks)]
                 t = time_graph(lay, 4)
                 per["decode_" + name] = {"us": round(t * 1e3, 2), "gbs": round(decode_bytes(N, K, self.wm) / (t * 1e-3) / 1e9, 1)}
                 if fused:   # the GEMV alone, on a row quantized beforehand
                     x, xq, sx, y = io
                     B.mnnq_quant_act(x, want_xsum=False, out=(xq, sx, None))
-                    t2 = time_graph([(lambda p=self.packed[name][b]: B.mnnq_linear_decode(p, N, K, xq, sx, out=y, mode=self.mode))
+                    t2 = time_graph([(lambda p=self.packed[name][b], N=N, K=K, xq=xq, sx=sx, y=y:
+                                      B.mnnq_linear_decode(p, N, K, xq, sx, out=y, mode=self.mode))
                                      for b in range(self.n_blocks)], 4)
                     per["decode_" + name]["gemv_alone_us"] = round(t2 * 1e3, 2)
                 fns += lay
@@ -462,7 +469,8 @@ def main() -> int:
             if do_pre:
                 x16 = mdl.io_pre[name][0][0].to(torch.float16)
                 y = mdl.io_pre[name][3]
-                t = time_graph([(lambda p=mdl.packed[name][b]: B.mnnq_linear_prefill_f16(p, N, K, x16, out=y, mode=mdl.mode))
+                t = time_graph([(lambda p=mdl.packed[name][b], N=N, K=K, x16=x16, y=y:
+                                 B.mnnq_linear_prefill_f16(p, N, K, x16, out=y, mode=mdl.mode))
                                 for b in range(mdl.n_blocks)], 2)
                 per_layer["prefill16_" + name] = {"us": round(t * 1e3, 2),
                                                   "tflops": round(prefill_ops(mdl.M, N, K) / (t * 1e-3) / 1e12, 1)}
@@ -470,7 +478,8 @@ def main() -> int:
                 x16 = mdl.io_dec[name][0].to(torch.float16)
                 y = mdl.io_dec[name][3]
                 try:
-                    t = time_graph([(lambda p=mdl.packed[name][b]: B.mnnq_linear_decode_f16(p, N, K, x16[0], out=y[0], mode=mdl.mode))
+                    t = time_graph([(lambda p=mdl.packed[name][b], N=N, K=K, x16=x16, y=y:
+                                     B.mnnq_linear_decode_f16(p, N, K, x16[0], out=y[0], mode=mdl.mode))
                                     for b in range(mdl.n_blocks)], 4)
                 except B.MnnqError:      # the fp16 row of this layer does not fit the GEMV's LDS staging
                     per_layer["decode16_" + name] = None

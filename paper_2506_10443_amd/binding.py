@@ -114,6 +114,21 @@ def _dev(t, dtype, what):
     return t
 
 
+def _need(t, n: int, what: str):
+    """The C-ABI takes plain pointers and trusts the sizes it is told: a buffer smaller than the shape
+    implies is an out-of-bounds access on the GPU.  Refuse it here, on the host."""
+    if t is not None and t.numel() < n:
+        raise ValueError("%s holds %d elements, the shape needs %d" % (what, t.numel(), n))
+    return t
+
+
+def _need_packed(packed, N: int, K: int, mode: int):
+    size = mnnq_packed_size(N, K, GROUP, mode)
+    if size == 0:
+        raise ValueError("unsupported shape N=%d K=%d mode=%d" % (N, K, mode))
+    return _need(packed, size, "packed")
+
+
 def mnnq_packed_size(N: int, K: int, group: int = GROUP, mode: int = MODE_W4_ZP_INT) -> int:
     return int(lib().mnnq_packed_size(N, K, group, mode))
 
@@ -141,6 +156,7 @@ def mnnq_unpack_weights(packed: torch.Tensor, N: int, K: int, mode: int = MODE_W
     """Canonical view: (q u8 [N,K], scale f32 [N,G], zero u8 [N,G]); in mode MODE_W4_MIN_FLOAT the
     third array holds the fp32 group minima."""
     _dev(packed, torch.uint8, "packed")
+    _need_packed(packed, N, K, mode)
     G = K // GROUP
     q = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
     s = torch.empty((N, G), dtype=torch.float32, device=packed.device)
@@ -169,9 +185,11 @@ def mnnq_quant_act(x: torch.Tensor, want_xsum: bool = True, out=None):
 def mnnq_linear_decode(packed, N: int, K: int, xq, sx, bias=None, out=None, mode: int = MODE_W4_ZP_INT):
     """One token: xq i8 [K] (or [1,K]), sx f32 [1] -> y f32 [N]."""
     _dev(packed, torch.uint8, "packed"); _dev(xq, torch.int8, "xq"); _dev(sx, torch.float32, "sx")
+    _need_packed(packed, N, K, mode)
     if xq.numel() != K:
         raise ValueError("xq must hold K values")
     y = torch.empty((N,), dtype=torch.float32, device=packed.device) if out is None else out
+    _need(y, N, "out"); _need(bias, N, "bias")
     _check(lib().mnnq_linear_decode(_ptr(packed), N, K, GROUP, mode, _ptr(xq), _ptr(sx), _ptr(bias),
                                     _ptr(y), None, 0, _stream()), "mnnq_linear_decode")
     return y
@@ -182,9 +200,11 @@ def mnnq_linear_decode_fused(packed, N: int, K: int, x, bias=None, out=None, wor
     """One token, activation quantizer fused in: x f32 [K] (or [1,K]) -> y f32 [N].
     workspace: optional uint8 tensor of mnnq_workspace_size(1, N, K) bytes."""
     _dev(packed, torch.uint8, "packed"); _dev(x, torch.float32, "x")
+    _need_packed(packed, N, K, mode)
     if x.numel() != K:
         raise ValueError("x must hold K values")
     y = torch.empty((N,), dtype=torch.float32, device=packed.device) if out is None else out
+    _need(y, N, "out"); _need(bias, N, "bias")
     if workspace is not None:
         _dev(workspace, torch.uint8, "workspace")
     _check(lib().mnnq_linear_decode_fused(_ptr(packed), N, K, GROUP, mode, _ptr(x), _ptr(bias),
@@ -198,12 +218,14 @@ def mnnq_linear_prefill(packed, N: int, K: int, xq, sx, bias=None, out=None, mod
     """M tokens: xq i8 [M,K], sx f32 [M] -> y f32 [M,N].  workspace: optional uint8 tensor
     (mnnq_workspace_size bytes); with the matrix-core plane in `packed` it selects the fp6 GEMM."""
     _dev(packed, torch.uint8, "packed"); _dev(xq, torch.int8, "xq"); _dev(sx, torch.float32, "sx")
+    _need_packed(packed, N, K, mode)
     M = xq.shape[0]
     if xq.shape[1] != K or sx.numel() != M:
         raise ValueError("xq must be [M,K] and sx [M]")
     if workspace is not None:
         _dev(workspace, torch.uint8, "workspace")
     y = torch.empty((M, N), dtype=torch.float32, device=packed.device) if out is None else out
+    _need(y, M * N, "out"); _need(bias, N, "bias")
     _check(lib().mnnq_linear_prefill(_ptr(packed), M, N, K, GROUP, mode, _ptr(xq), _ptr(sx),
                                      _ptr(bias), _ptr(y), _ptr(workspace),
                                      0 if workspace is None else workspace.numel(), _stream()), "mnnq_linear_prefill")
@@ -213,6 +235,7 @@ def mnnq_linear_prefill(packed, N: int, K: int, xq, sx, bias=None, out=None, mod
 def mnnq_linear_acc_debug_planes(packed, N: int, K: int, xq, mode: int, workspace=None):
     """int32 group accumulators [M,N,G] from the fp6 GEMM (mode must carry WITH_MATRIX_PLANE)."""
     _dev(packed, torch.uint8, "packed"); _dev(xq, torch.int8, "xq")
+    _need_packed(packed, N, K, mode)
     M = xq.shape[0]
     if workspace is None:
         workspace = torch.empty(max(16, mnnq_workspace_size(M, N, K, GROUP, mode)), dtype=torch.uint8,
@@ -238,7 +261,10 @@ def mnnq_linear_prefill_planes(packed, M: int, N: int, K: int, planes, sx, bias=
                                mode: int = MODE_W4_ZP_INT | WITH_MATRIX_PLANE):
     """y f32 [M,N] from activation planes (mnnq_act_planes), scales sx [M] and packed weights with the plane."""
     _dev(packed, torch.uint8, "packed"); _dev(planes, torch.uint8, "planes"); _dev(sx, torch.float32, "sx")
+    _need_packed(packed, N, K, mode)
+    _need(planes, int(lib().mnnq_act_planes_size(M, K, GROUP)), "planes"); _need(sx, M, "sx")
     y = torch.empty((M, N), dtype=torch.float32, device=packed.device) if out is None else out
+    _need(y, M * N, "out"); _need(bias, N, "bias")
     _check(lib().mnnq_linear_prefill_planes(_ptr(packed), M, N, K, GROUP, mode, _ptr(planes), _ptr(sx), _ptr(bias),
                                             _ptr(y), _stream()), "mnnq_linear_prefill_planes")
     return y
@@ -252,9 +278,11 @@ def mnnq_debug_set(key: str, value) -> None:
 def mnnq_linear_decode_f16(packed, N: int, K: int, x16, bias=None, out=None, mode: int = MODE_W4_ZP_INT):
     """One token, fp16 activations (W4A16; W8A16 with MODE_W8_MIN_FLOAT): x16 fp16 [K] -> y f32 [N]."""
     _dev(packed, torch.uint8, "packed"); _dev(x16, torch.float16, "x16")
+    _need_packed(packed, N, K, mode)
     if x16.numel() != K:
         raise ValueError("x16 must hold K values")
     y = torch.empty((N,), dtype=torch.float32, device=packed.device) if out is None else out
+    _need(y, N, "out"); _need(bias, N, "bias")
     _check(lib().mnnq_linear_decode_f16(_ptr(packed), N, K, GROUP, mode, _ptr(x16), _ptr(bias),
                                         _ptr(y), None, 0, _stream()), "mnnq_linear_decode_f16")
     return y
@@ -265,10 +293,12 @@ def mnnq_linear_prefill_f16(packed, N: int, K: int, x16, bias=None, out=None, ro
     """M tokens, fp16 activations (W4A16; W8A16 with MODE_W8_MIN_FLOAT): x16 fp16 [M,K] -> y f32 [M,N];
     row_scale f32 [M] optional."""
     _dev(packed, torch.uint8, "packed"); _dev(x16, torch.float16, "x16")
+    _need_packed(packed, N, K, mode)
     M = x16.shape[0]
     if x16.shape[1] != K:
         raise ValueError("x16 must be [M,K]")
     y = torch.empty((M, N), dtype=torch.float32, device=packed.device) if out is None else out
+    _need(y, M * N, "out"); _need(bias, N, "bias")
     _check(lib().mnnq_linear_prefill_f16(_ptr(packed), M, N, K, GROUP, mode, _ptr(x16), _ptr(row_scale),
                                          _ptr(bias), _ptr(y), None, 0, _stream()), "mnnq_linear_prefill_f16")
     return y
@@ -294,6 +324,7 @@ def mnnq_pack_from_quantized(q, scale, zero, out=None, mode: int = MODE_W4_ZP_IN
 def mnnq_linear_acc_debug(packed, N: int, K: int, xq, use_prefill_kernel: bool, mode: int = MODE_W4_ZP_INT):
     """Integer group accumulators I[m,n,g] (int32 [M,N,G]) from the decode or the prefill kernel."""
     _dev(packed, torch.uint8, "packed"); _dev(xq, torch.int8, "xq")
+    _need_packed(packed, N, K, mode)
     xq2 = xq.reshape(-1, K)
     M = xq2.shape[0]
     # int8 weights are two 4-bit planes: 2 K / 64 sums per (m, n), high-nibble planes first
@@ -309,9 +340,11 @@ def mnnq_linear_acc_debug(packed, N: int, K: int, xq, use_prefill_kernel: bool, 
 def mnnq_linear_decode_o16(packed, N: int, K: int, xq, sx, bias=None, out=None, mode: int = MODE_W4_ZP_INT):
     """One token: xq i8 [K], sx f32 [1] -> y fp16 [N]."""
     _dev(packed, torch.uint8, "packed"); _dev(xq, torch.int8, "xq"); _dev(sx, torch.float32, "sx")
+    _need_packed(packed, N, K, mode)
     if xq.numel() != K:
         raise ValueError("xq must hold K values")
     y = torch.empty((N,), dtype=torch.float16, device=packed.device) if out is None else out
+    _need(y, N, "out"); _need(bias, N, "bias")
     _dev(y, torch.float16, "out")
     _check(lib().mnnq_linear_decode_o16(_ptr(packed), N, K, GROUP, mode, _ptr(xq), _ptr(sx), _ptr(bias),
                                         _ptr(y), _stream()), "mnnq_linear_decode_o16")
@@ -321,10 +354,12 @@ def mnnq_linear_decode_o16(packed, N: int, K: int, xq, sx, bias=None, out=None, 
 def mnnq_linear_prefill_o16(packed, N: int, K: int, xq, sx, bias=None, out=None, mode: int = MODE_W4_ZP_INT):
     """M tokens: xq i8 [M,K], sx f32 [M] -> y fp16 [M,N]."""
     _dev(packed, torch.uint8, "packed"); _dev(xq, torch.int8, "xq"); _dev(sx, torch.float32, "sx")
+    _need_packed(packed, N, K, mode)
     M = xq.shape[0]
     if xq.shape[1] != K or sx.numel() != M:
         raise ValueError("xq must be [M,K] and sx [M]")
     y = torch.empty((M, N), dtype=torch.float16, device=packed.device) if out is None else out
+    _need(y, M * N, "out"); _need(bias, N, "bias")
     _dev(y, torch.float16, "out")
     _check(lib().mnnq_linear_prefill_o16(_ptr(packed), M, N, K, GROUP, mode, _ptr(xq), _ptr(sx),
                                          _ptr(bias), _ptr(y), _stream()), "mnnq_linear_prefill_o16")
@@ -334,9 +369,11 @@ def mnnq_linear_prefill_o16(packed, N: int, K: int, xq, sx, bias=None, out=None,
 def mnnq_linear_decode_f16_o16(packed, N: int, K: int, x16, bias=None, out=None, mode: int = MODE_W4_ZP_INT):
     """One token, fp16 activations: x16 fp16 [K] -> y fp16 [N]."""
     _dev(packed, torch.uint8, "packed"); _dev(x16, torch.float16, "x16")
+    _need_packed(packed, N, K, mode)
     if x16.numel() != K:
         raise ValueError("x16 must hold K values")
     y = torch.empty((N,), dtype=torch.float16, device=packed.device) if out is None else out
+    _need(y, N, "out"); _need(bias, N, "bias")
     _dev(y, torch.float16, "out")
     _check(lib().mnnq_linear_decode_f16_o16(_ptr(packed), N, K, GROUP, mode, _ptr(x16), _ptr(bias),
                                             _ptr(y), _stream()), "mnnq_linear_decode_f16_o16")
@@ -347,10 +384,12 @@ def mnnq_linear_prefill_f16_o16(packed, N: int, K: int, x16, bias=None, out=None
                                 mode: int = MODE_W4_ZP_INT):
     """M tokens, fp16 activations: x16 fp16 [M,K] -> y fp16 [M,N]; row_scale f32 [M] optional."""
     _dev(packed, torch.uint8, "packed"); _dev(x16, torch.float16, "x16")
+    _need_packed(packed, N, K, mode)
     M = x16.shape[0]
     if x16.shape[1] != K:
         raise ValueError("x16 must be [M,K]")
     y = torch.empty((M, N), dtype=torch.float16, device=packed.device) if out is None else out
+    _need(y, M * N, "out"); _need(bias, N, "bias")
     _dev(y, torch.float16, "out")
     _check(lib().mnnq_linear_prefill_f16_o16(_ptr(packed), M, N, K, GROUP, mode, _ptr(x16), _ptr(row_scale),
                                              _ptr(bias), _ptr(y), _stream()), "mnnq_linear_prefill_f16_o16")
@@ -363,6 +402,7 @@ def mnnq_linear_prefill_fused(packed, N: int, K: int, x, bias=None, out=None, wo
     workspace: uint8 tensor of at least mnnq_workspace_size(M, N, K) bytes (required by the library;
     this wrapper brings one along when none is given)."""
     _dev(packed, torch.uint8, "packed"); _dev(x, torch.float32, "x")
+    _need_packed(packed, N, K, mode)
     M = x.shape[0]
     if x.shape[1] != K:
         raise ValueError("x must be [M,K]")
@@ -371,6 +411,7 @@ def mnnq_linear_prefill_fused(packed, N: int, K: int, x, bias=None, out=None, wo
                                 device=packed.device)
     _dev(workspace, torch.uint8, "workspace")
     y = torch.empty((M, N), dtype=torch.float32, device=packed.device) if out is None else out
+    _need(y, M * N, "out"); _need(bias, N, "bias")
     _check(lib().mnnq_linear_prefill_fused(_ptr(packed), M, N, K, GROUP, mode, _ptr(x), _ptr(bias), _ptr(y),
                                            _ptr(workspace), workspace.numel(), _stream()),
            "mnnq_linear_prefill_fused")
@@ -381,10 +422,12 @@ def mnnq_linear_prefill_fused_static(packed, N: int, K: int, x, bias=None, out=N
     """mnnq_linear_prefill_fused through the library's own scratch array: x f32 [M,K] -> y f32 [M,N];
     `out` must be given by callers that may not allocate (this wrapper allocates it otherwise)."""
     _dev(packed, torch.uint8, "packed"); _dev(x, torch.float32, "x")
+    _need_packed(packed, N, K, mode)
     M = x.shape[0]
     if x.shape[1] != K:
         raise ValueError("x must be [M,K]")
     y = torch.empty((M, N), dtype=torch.float32, device=packed.device) if out is None else out
+    _need(y, M * N, "out"); _need(bias, N, "bias")
     _check(lib().mnnq_linear_prefill_fused_static(_ptr(packed), M, N, K, GROUP, mode, _ptr(x), _ptr(bias), _ptr(y),
                                                   _stream()), "mnnq_linear_prefill_fused_static")
     return y
@@ -398,9 +441,11 @@ def mnnq_linear_decode_fused_o16(packed, N: int, K: int, x, bias=None, out=None,
                                  mode: int = MODE_W4_ZP_INT):
     """One token, activation quantizer fused in: x f32 [K] -> y fp16 [N]."""
     _dev(packed, torch.uint8, "packed"); _dev(x, torch.float32, "x")
+    _need_packed(packed, N, K, mode)
     if x.numel() != K:
         raise ValueError("x must hold K values")
     y = torch.empty((N,), dtype=torch.float16, device=packed.device) if out is None else out
+    _need(y, N, "out"); _need(bias, N, "bias")
     _dev(y, torch.float16, "out")
     if workspace is not None:
         _dev(workspace, torch.uint8, "workspace")
@@ -414,6 +459,7 @@ def mnnq_linear_prefill_fused_o16(packed, N: int, K: int, x, bias=None, out=None
                                   mode: int = MODE_W4_ZP_INT):
     """M tokens, activation quantizer inside the call: x f32 [M,K] -> y fp16 [M,N]."""
     _dev(packed, torch.uint8, "packed"); _dev(x, torch.float32, "x")
+    _need_packed(packed, N, K, mode)
     M = x.shape[0]
     if x.shape[1] != K:
         raise ValueError("x must be [M,K]")
@@ -422,6 +468,7 @@ def mnnq_linear_prefill_fused_o16(packed, N: int, K: int, x, bias=None, out=None
                                 device=packed.device)
     _dev(workspace, torch.uint8, "workspace")
     y = torch.empty((M, N), dtype=torch.float16, device=packed.device) if out is None else out
+    _need(y, M * N, "out"); _need(bias, N, "bias")
     _dev(y, torch.float16, "out")
     _check(lib().mnnq_linear_prefill_fused_o16(_ptr(packed), M, N, K, GROUP, mode, _ptr(x), _ptr(bias), _ptr(y),
                                                _ptr(workspace), workspace.numel(), _stream()),
