@@ -105,6 +105,8 @@ def main() -> int:
     ap.add_argument("--two-call-decode", action="store_true",
                     help="decode pass calls mnnq_quant_act + mnnq_linear_decode per layer instead of the fused call")
     ap.add_argument("--lm-head-prefill", action="store_true", help="also time the LM head through the prefill GEMM")
+    ap.add_argument("--prefill-plan", type=int, default=None, choices=[0, 1, 2, 3, 4],
+                    help="force one tile plan of the fp6 GEMM for every layer (tuning; default: the library's choice)")
     ap.add_argument("--peaks", action="store_true", help="also measure what this GPU sustains (`achievable`)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -133,6 +135,8 @@ def main() -> int:
         raise RuntimeError("libmnnq.so is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
     torch.zeros(16, device=dev).sum().item()     # first allocation and kernel before the library is loaded
     B.lib()
+    if args.prefill_plan is not None:
+        B.mnnq_debug_set("MNNQ_PREFILL6_PLAN", args.prefill_plan)
     bench_lib = []
 
     def BL():

@@ -171,10 +171,12 @@ int mnnq_linear_prefill_fused(const void *packed, int64_t M, int64_t N, int64_t 
  * want the activations rearranged once (Section 5.1 rearranges operands for the instruction that
  * consumes them; for activations that has to happen per call):
  *   mnnq_act_planes: int8 codes xq [M, K] -> the activation operand of the fp6 matrix instructions
- *     (every code as 16 hi + lo, both parts exact e2m3 numbers), mnnq_act_planes_size(M, K, group) bytes;
+ *     (every code as sign * (16 hi + lo), both parts exact e2m3 numbers), mnnq_act_planes_size(M, K, group) bytes;
  *   mnnq_linear_prefill_planes: y [M, N] from those planes, the scales sx [M] and the packed weights;
  *     mode must carry MNNQ_WITH_MATRIX_PLANE and M must exceed 32 (MNNQ_ERR_UNSUPPORTED otherwise).
- * The result is that of mnnq_linear_prefill with a workspace, bit for bit. */
+ * The result is that of mnnq_linear_prefill with a workspace, bit for bit, whenever that call takes
+ * the fp6 GEMM as well (it leaves shapes with very few output tiles and a long K to the int8 GEMM;
+ * mnnq_plan_debug tells). */
 size_t mnnq_act_planes_size(int64_t M, int64_t K, int group);
 int mnnq_act_planes(const int8_t *xq, int64_t M, int64_t K, int group, void *planes, size_t planes_bytes,
                     void *stream);

@@ -72,7 +72,7 @@ size_t fused_prefill_ws_bytes(int64_t M, int64_t K)
 
 // With the matrix-core plane in the packed buffer, a prefill call's workspace starts with the
 // activation planes (a multiple of 256 bytes); the fused call's codes and scales follow.
-size_t planes_ws_bytes(const Layout& L, int64_t M) { return prefill6_wanted(L, M) ? prefill6_ws_bytes(M, L.Kx) : 0; }
+size_t planes_ws_bytes(const Layout& L, int64_t M) { return prefill6_possible(L, M) ? prefill6_ws_bytes(M, L.Kx) : 0; }
 
 // Above this many bytes of packed weights quantizing the row once, in a kernel of its own (about
 // 4 us), beats quantizing it in every workgroup (measured: 75 MiB 16.4 us fused against 4.2 + 14.6 us,
@@ -482,7 +482,7 @@ int mnnq_linear_acc_debug_planes(const void* packed, int64_t M, int64_t N, int64
     if (M <= 0) return MNNQ_ERR_SHAPE;
     if (int s = check_shape(N, K, group, mode)) return s;
     const Layout L = make_layout(N, K, mode);
-    if (M > kMaxM || !prefill_fits(M, N, K, mode) || !prefill6_wanted(L, M)) return MNNQ_ERR_UNSUPPORTED;
+    if (M > kMaxM || !prefill_fits(M, N, K, mode) || !prefill6_possible(L, M)) return MNNQ_ERR_UNSUPPORTED;
     if (workspace_bytes < prefill6_ws_bytes(M, K)) return MNNQ_ERR_SIZE;
     if (misaligned(packed) || misaligned(xq) || misaligned(acc) || misaligned(workspace)) return MNNQ_ERR_ALIGN;
     if (int s = launch_act_planes(xq, M, K, workspace, static_cast<hipStream_t>(stream))) return s;
@@ -515,7 +515,7 @@ int mnnq_linear_prefill_planes(const void* packed, int64_t M, int64_t N, int64_t
     if (M <= 0) return MNNQ_ERR_SHAPE;
     if (int s = check_shape(N, K, group, mode)) return s;
     const Layout L = make_layout(N, K, mode);
-    if (!prefill_fits(M, N, K, mode) || !prefill6_wanted(L, M)) return MNNQ_ERR_UNSUPPORTED;
+    if (!prefill_fits(M, N, K, mode) || !prefill6_possible(L, M)) return MNNQ_ERR_UNSUPPORTED;
     if (misaligned(packed) || misaligned(planes) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(sx) & 3u) return MNNQ_ERR_ALIGN;
     return launch_prefill6(static_cast<const uint8_t*>(packed), L, M, planes, sx, bias, y, nullptr,

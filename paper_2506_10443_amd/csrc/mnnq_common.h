@@ -235,6 +235,9 @@ int launch_act_planes(const int8_t* xq, int64_t M, int64_t K, void* planes, hipS
 int launch_prefill6(const uint8_t* packed, const Layout& L, int64_t M, const void* planes, const float* sx,
                     const float* bias, float* y, int32_t* acc_debug, hipStream_t st);
 size_t prefill6_ws_bytes(int64_t M, int64_t K);
+// possible: the plane is there, more than 32 tokens, sizes within the kernels' 32-bit offsets;
+// wanted: possible, and the shape has enough output tiles for this GEMM to beat the int8 one (or a plan is forced).
+bool prefill6_possible(const Layout& L, int64_t M);
 bool prefill6_wanted(const Layout& L, int64_t M);
 void describe_prefill6(const Layout& L, int64_t M, int32_t out[8]);
 // M <= 16 tokens sharing one pass over the weights.

@@ -11,8 +11,11 @@
 //   * an e2m3 number is (-1)^s * m / 8 for m = 0..15 (and coarser above), so every integer of
 //     magnitude <= 15 is exact: the weight operand is (q - zero) / 8, its code the sign-magnitude
 //     form of q - zero;
-//   * an int8 activation is split as xq = 16 hi + lo with lo = xq & 15 (0..15) and hi = xq >> 4
-//     (-8..7), both exact as well; one instruction contracts the 64 high parts of a group with the
+//   * an int8 activation is split as xq = sign(xq) (16 hi + lo) with hi = |xq| >> 4 (0..8) and
+//     lo = |xq| & 15, both parts signed like xq and exact as well (the split by magnitude rather than
+//     by two's-complement bits leaves the high part of every small value - nearly all of them, once a
+//     token has an outlier - an all-zero code: fewer bits toggle in the matrix pipe, and the chip,
+//     which runs this kernel against its power limit, clocks higher); one instruction contracts the 64 high parts of a group with the
 //     weights, a second one the low parts, accumulating on the first; the instruction's power-of-two
 //     operand scale (2^10 resp. 2^6 on the activation side) puts back the 16 and the two divisions by 8;
 //   * all products and the sums (|I| <= 64 * 127 * 15 < 2^17) are integers, exact in fp32, so the
@@ -130,7 +133,8 @@ __global__ __launch_bounds__(256) void plane_build_kernel(uint8_t* __restrict__ 
 
 // ---------------------------------------------------------------------------------------------
 // Per call: the activation planes [Gx][TMp][2][1536 B] from the int8 codes [M, K] - block (g, tm, 0)
-// the high parts hi = xq >> 4, block (g, tm, 1) the low parts lo = xq & 15 of rows 32 tm .. 32 tm + 31
+// the high parts, block (g, tm, 1) the low parts of xq = sign(xq) (16 hi + lo), hi = |xq| >> 4,
+// lo = |xq| & 15, both carrying the sign of xq (so that small values have an all-zero high part), of rows 32 tm .. 32 tm + 31
 // and group g, lane l holding row l % 32 and k = 64 g + 32 (l / 32) + j.  Rows past M are zero.
 // One wave per (tm, g); consecutive waves take consecutive groups of the same rows, so that the
 // 128-byte lines of xq (two groups each) are fetched once.
@@ -152,11 +156,14 @@ __global__ __launch_bounds__(256) void planes_kernel(const int8_t* __restrict__ 
     uint32_t hi[8], lo[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        lo[i] = x[i] & 0x0f0f0f0fu;                       // 0..15: its own code
-        const uint32_t h = (x[i] >> 4) & 0x0f0f0f0fu;     // hi as a 4-bit two's complement number
-        const uint32_t neg = (h >> 3) & 0x01010101u;      // 1 in the bytes with hi < 0
-        const uint32_t m15 = (neg << 4) - neg;            // 15 there
-        hi[i] = ((h ^ m15) + neg) | (neg << 5);           // magnitude 16 - h resp. h, sign in bit 5
+        // byte-wise: xq = s (16 hi + lo) with s = +-1, hi = |xq| >> 4 (0..8), lo = |xq| & 15; the code of a
+        // part is its magnitude with the sign in bit 5, zero parts stay all-zero codes
+        const uint32_t neg = (x[i] >> 7) & 0x01010101u;           // 1 in the bytes with xq < 0
+        const uint32_t mag = (x[i] ^ (neg * 255u)) + neg;         // |xq| (at most 128: no carry between bytes)
+        const uint32_t ml = mag & 0x0f0f0f0fu, mh = (mag >> 4) & 0x0f0f0f0fu;
+        const uint32_t nzl = ((ml + 0x0f0f0f0fu) >> 4) & 0x01010101u, nzh = ((mh + 0x0f0f0f0fu) >> 4) & 0x01010101u;
+        lo[i] = ml | ((neg & nzl) << 5);
+        hi[i] = mh | ((neg & nzh) << 5);
     }
     uint32_t dh[6], dl[6];
     pack_fp6(hi, dh);
@@ -480,18 +487,21 @@ int choose_plan6(const Layout& L, int64_t M)
         if (e[0] >= '0' && e[0] <= '4') return e[0] - '0';
     const int64_t cus = num_cus();
     auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((L.N + bn - 1) / bn); };
-    auto eff = [&](int64_t t, int64_t slots) { return (double)t / (double)((t + slots - 1) / slots * slots); };
-    // how well each form fills the chip, times what its wave tile is worth
-    const double e0 = eff(tiles(128, 128), 2 * cus) * 0.90;
-    const double e1 = eff(tiles(128, 128), cus) * 0.85;
-    const double e2 = eff(tiles(128, 256), 2 * cus) * 1.00;
-    const double e3 = eff(tiles(128, 256), cus) * 0.95;
-    int best = 0;
-    double eb = e0;
-    if (e1 > eb) { best = 1; eb = e1; }
-    if (e2 > eb) { best = 2; eb = e2; }
-    if (e3 > eb) { best = 3; eb = e3; }
-    return best;
+    auto rounds = [&](int64_t t, int64_t slots) { return (double)((t + slots - 1) / slots); };
+    // Fewer 128 x 128 tiles than CUs: one tile per CU with its K range in two parts keeps every SIMD busy
+    // (measured on Qwen2-7B's o and down at 1024 tokens: 1.3 and 1.5 times faster than one part).
+    const int64_t t0 = tiles(128, 128);
+    if (t0 <= cus) return 1;
+    // Else two workgroups of four waves per CU.  A 128 x 256 tile takes 1.54 times as long as a 128 x 128
+    // one (measured at K = 3584) for twice the outputs; what decides is how many rounds of workgroups
+    // each form needs.  With a single round the larger tile loses (its writes of 128 KiB per workgroup
+    // all come at the end, with nothing left to overlap them).
+    // (The K-split forms of these sizes lost everywhere they were measured: their loops are short and the
+    // exchange of the sums is a fixed cost per tile.)
+    const double r2 = rounds(tiles(128, 256), 2 * cus);
+    const double c0 = rounds(t0, 2 * cus) * 1.0;
+    const double c2 = r2 * 1.54;
+    return (r2 >= 2 && c2 < c0) ? 2 : 0;
 }
 
 struct Plan6Info {
@@ -514,11 +524,21 @@ Plan6Info plan6_info(int plan)
 
 size_t prefill6_ws_bytes(int64_t M, int64_t K) { return (size_t)(K / kGroup) * tmp_tiles(M) * 2 * kPlaneBlockBytes; }
 
-bool prefill6_wanted(const Layout& L, int64_t M)
+bool prefill6_possible(const Layout& L, int64_t M)
 {
     const int64_t lim = ((int64_t)1 << 31) - 1;
     return L.plane && L.mode == MNNQ_W4_ZP_INT && M > 32 && (int64_t)L.plane_bytes() <= lim &&
            (int64_t)prefill6_ws_bytes(M, L.Kx) <= lim;
+}
+
+bool prefill6_wanted(const Layout& L, int64_t M)
+{
+    if (!prefill6_possible(L, M)) return false;
+    if (debug_option(kDbgPrefill6Plan)) return true;   // a forced plan: tests and tuning
+    // fewer 128 x 128 tiles than a quarter of the CUs and a long K: the int8 GEMM, which splits K four
+    // ways, fills the chip better than this one's two parts
+    const int64_t t0 = ((M + 127) / 128) * ((L.N + 127) / 128);
+    return 4 * t0 >= num_cus() || L.Kx < 4096;
 }
 
 void describe_prefill6(const Layout& L, int64_t M, int32_t out[8])

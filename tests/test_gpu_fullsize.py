@@ -70,7 +70,9 @@ def check_w4a8_layer(model, name, M, seed, acc_rows=8):
     ms, ns = stratified_pairs(M, N, rng)
     _, y_s = oracle.linear_w4a8_sampled(xq_o, sx_o, q, s, z, ms, ns, want_acc=False)
     ws = torch.empty(B.mnnq_workspace_size(M, N, K, 64, MODE_PLANE), dtype=torch.uint8, device="cuda:0")
-    assert B.mnnq_plan_debug(0, M, N, K, mode=MODE_PLANE)[7] == 6         # the plan of the fp6 GEMM
+    # the fp6 GEMM, except where the shape has too few output tiles for it (Qwen2-1.5B's down: 48 tiles)
+    fp6 = B.mnnq_plan_debug(0, M, N, K, mode=MODE_PLANE)[7] == 6
+    assert fp6 == ((model, name) != ("qwen2-1.5b", "down"))
     y6 = B.mnnq_linear_prefill(packed, N, K, xq, sx, mode=MODE_PLANE, workspace=ws).cpu().numpy()
     ymax = np.abs(y6).max()
     err = np.abs(y6[ms, ns] - y_s).max()

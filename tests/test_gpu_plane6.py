@@ -90,8 +90,32 @@ def test_prefill6_accumulators_bit_exact(M, N, K):
     assert np.array_equal(acc, acc_o)
 
 
+def test_prefill6_every_int8_code_bit_exact():
+    """Caller-supplied codes over the whole int8 range, -128 included (the activation quantizer never
+    produces it): every value in every position of a group, accumulators against the oracle."""
+    M, N, K = 64, 96, 256
+    rng = np.random.default_rng(4350)
+    W = synth.weights(N, K, 4351)
+    q, s, z = oracle.quant_weights(W)
+    xq = rng.integers(-128, 128, (M, K)).astype(np.int8)
+    xq[0, :] = -128
+    xq[1, :256] = np.arange(-128, 128).astype(np.int8)
+    xq[2, :] = np.where(np.arange(K) % 2 == 0, -16, 16).astype(np.int8)
+    xq[3, :] = np.where(np.arange(K) % 2 == 0, -15, 15).astype(np.int8)
+    sx = np.ones(M, np.float32)
+    acc_o, y_o = oracle.linear_w4a8(xq, sx, q, s, z)
+    packed = B.mnnq_pack_weights(dev(W), mode=MODE)
+    acc = B.mnnq_linear_acc_debug_planes(packed, N, K, dev(xq), MODE).cpu().numpy()
+    assert np.array_equal(acc, acc_o)
+    B.mnnq_debug_set("MNNQ_PREFILL6_PLAN", 0)
+    ws = torch.empty(B.mnnq_workspace_size(M, N, K, 64, MODE), dtype=torch.uint8, device="cuda:0")
+    y = B.mnnq_linear_prefill(packed, N, K, dev(xq), dev(sx), mode=MODE, workspace=ws).cpu().numpy()
+    assert np.abs(y - y_o).max() <= TOL_A8 * np.abs(y_o).max()
+
+
 def test_prefill6_bias_fused_and_fallbacks():
     M, N, K = 150, 512, 1536
+    B.mnnq_debug_set("MNNQ_PREFILL6_PLAN", 0)       # (so few tiles would go to the int8 GEMM otherwise)
     W, x, q, s, z, xq, sx = make(N, K, M, 4400)
     bias = (0.5 * np.random.default_rng(4401).standard_normal(N)).astype(np.float32)
     _, y_o = oracle.linear_w4a8(xq, sx, q, s, z, bias=bias)
@@ -111,8 +135,21 @@ def test_prefill6_bias_fused_and_fallbacks():
     assert np.array_equal(ys, yf)
 
 
+def test_few_output_tiles_take_the_int8_gemm_unless_a_plan_is_forced():
+    M, N, K = 150, 512, 4096
+    assert B.mnnq_plan_debug(0, M, N, K, mode=MODE)[7] != 6
+    assert B.mnnq_plan_debug(0, M, N, 1536, mode=MODE)[7] == 6      # short K: nothing to split
+    assert B.mnnq_plan_debug(0, 1024, 4608, 3584, mode=MODE)[7] == 6
+    B.mnnq_debug_set("MNNQ_PREFILL6_PLAN", 2)
+    assert B.mnnq_plan_debug(0, M, N, K, mode=MODE)[:2] == [128, 256] and B.mnnq_plan_debug(0, M, N, K, mode=MODE)[7] == 6
+    # the workspace size does not depend on the choice
+    B.mnnq_debug_set("MNNQ_PREFILL6_PLAN", None)
+    assert B.mnnq_workspace_size(M, N, K, 64, MODE) >= B.lib().mnnq_act_planes_size(M, K, 64) + M * K + 4 * M
+
+
 def test_act_planes_and_gemm_as_separate_calls():
     M, N, K = 300, 768, 1536
+    B.mnnq_debug_set("MNNQ_PREFILL6_PLAN", 0)       # (so few tiles would go to the int8 GEMM otherwise)
     W, x, q, s, z, xq, sx = make(N, K, M, 4500)
     _, y_o = oracle.linear_w4a8(xq, sx, q, s, z)
     packed = B.mnnq_pack_weights(dev(W), mode=MODE)
