@@ -11,7 +11,11 @@
 //     then the dependent epilogue of tile t) - the matrix rate and what each VALU instruction costs.
 //     Kinds 3 and 4 are the loop shape of the fp6 GEMM: two chained v_mfma_scale_f32_32x32x64_f8f6f4
 //     (fp6 operands) per 32 x 32 tile and group, without and with the 16 multiply-adds behind them.
-// The caller times the launches; nothing is returned but a status (0 = ok, negative = bad argument).
+//     seed 1 gives operands of small constants, any other seed operands whose bits differ from lane to
+//     lane like real data: the chip runs these loops against its power limit, and the clock it grants
+//     depends on how many bits toggle.  sink[1] receives the shader clock in MHz that wave 0 of
+//     workgroup 0 saw over the kernel's life.
+// The caller times the launches; nothing else is returned but a status (0 = ok, negative = bad argument).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
@@ -47,20 +51,49 @@ __global__ __launch_bounds__(256) void peak_read_kernel(const u32x4* __restrict_
     if (acc == 0x9e3779b9u) *sink = acc;   // keeps the loads alive; practically never taken
 }
 
+// Operand words of the matrix loops: small constants (seed 1: hardly a bit toggles in the matrix pipe), or
+// for any other seed bits that differ from lane to lane and word to word like those of real operands.
+__device__ __forceinline__ int operand_word(int seed, int i)
+{
+    if (seed == 1) return i == 0 ? seed : i;
+    uint32_t h = (uint32_t)(threadIdx.x * 8 + i) * 2654435761u ^ (uint32_t)seed * 0x9e3779b9u;
+    h ^= h >> 15; h *= 0x85ebca6bu; h ^= h >> 13;
+    return (int)h;
+}
+
+// Shader clock in MHz over the kernel's life, seen by wave 0 of workgroup 0: cycles of the clock the SIMDs
+// run on against the constant 100 MHz reference counter.
+struct ClockProbe {
+    uint64_t c0, r0;
+    __device__ void start() { c0 = __builtin_amdgcn_s_memtime(); r0 = __builtin_amdgcn_s_memrealtime(); }
+    __device__ void stop(float* sink) const
+    {
+        const uint64_t c1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
+        if (blockIdx.x == 0 && threadIdx.x == 0 && r1 > r0) sink[1] = (float)(c1 - c0) / (float)(r1 - r0) * 100.0f;
+    }
+};
+
 // KIND 0: v_mfma_i32_16x16x64_i8, 1: v_mfma_f32_16x16x32_f16, 2: v_mfma_f32_16x16x128_f8f6f4 (fp8).
 // EPI (KIND 0 only) 0: none, 1: 4 cvt + 4 fma per MFMA, 2: the same plus 8 integer operations.
 template <int KIND, int EPI>
 __global__ __launch_bounds__(1024) void peak_mfma_kernel(int iters, int seed, float* sink)
 {
     constexpr int NT = 16;
-    v4i ai = {seed, seed + 1, seed + 2, seed + 3}, bi[4];
-    for (int j = 0; j < 4; ++j) bi[j] = v4i{seed * 3 + j, seed * 5, seed * 7, seed * 9};
+    ClockProbe clock;
+    clock.start();
+    v4i ai = {operand_word(seed, 0), operand_word(seed, 1), operand_word(seed, 2), operand_word(seed, 3)}, bi[4];
+    for (int j = 0; j < 4; ++j)
+        bi[j] = v4i{operand_word(seed, 4 + j), operand_word(seed, 8 + j), operand_word(seed, 12 + j), operand_word(seed, 16 + j)};
     h8 ah, bh;
-    for (int i = 0; i < 8; ++i) {
-        ah[i] = (_Float16)(float)(seed + i);
-        bh[i] = (_Float16)(float)(seed - i);
+    for (int i = 0; i < 8; ++i) {   // halves: small integers, so that the sums stay finite
+        ah[i] = (_Float16)(float)(operand_word(seed, 20 + i) % 64);
+        bh[i] = (_Float16)(float)(operand_word(seed, 28 + i) % 64);
     }
-    const v8i a8 = {seed, 1, 2, 3, 4, 5, 6, 7}, b8 = {seed, 7, 6, 5, 4, 3, 2, 1};
+    v8i a8, b8;
+    for (int i = 0; i < 8; ++i) {   // fp8 (e4m3): the all-ones exponent-and-mantissa pattern (NaN) masked out
+        a8[i] = operand_word(seed, 36 + i) & 0x77777777;
+        b8[i] = operand_word(seed, 44 + i) & 0x77777777;
+    }
     float yacc[NT][4];
     v4f facc[NT];
     for (int t = 0; t < NT; ++t) {
@@ -101,6 +134,7 @@ __global__ __launch_bounds__(1024) void peak_mfma_kernel(int iters, int seed, fl
     float s = (float)bi[0][0];
     for (int t = 0; t < NT; ++t) s += yacc[t][0] + yacc[t][1] + yacc[t][2] + yacc[t][3] + facc[t][0];
     if (s == 12345.678f) *sink = s;        // keeps the arithmetic alive; practically never taken
+    clock.stop(sink);
 }
 
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -116,8 +150,15 @@ template <bool EPI>
 __global__ __launch_bounds__(512) void peak_fp6_kernel(int iters, int seed, float* sink)
 {
     constexpr int NT = 8;
-    v8i a0 = {seed, 1, 2, 3, 4, 5, 6, 7}, a1 = {seed + 1, 1, 2, 3, 4, 5, 6, 7}, b[2];
-    for (int j = 0; j < 2; ++j) b[j] = v8i{seed * 3 + j, 7, 6, 5, 4, 3, 2, 1};
+    ClockProbe clock;
+    clock.start();
+    v8i a0, a1, b[2];
+    for (int i = 0; i < 8; ++i) {   // (every 6-bit pattern is a number in e2m3; registers 6 and 7 are not read)
+        a0[i] = operand_word(seed, i);
+        a1[i] = operand_word(seed, 8 + i);
+        b[0][i] = operand_word(seed, 16 + i);
+        b[1][i] = operand_word(seed, 24 + i);
+    }
     float yacc[NT][16];
     for (int t = 0; t < NT; ++t)
         for (int r = 0; r < 16; ++r) yacc[t][r] = 0.f;
@@ -143,6 +184,7 @@ __global__ __launch_bounds__(512) void peak_fp6_kernel(int iters, int seed, floa
     for (int t = 0; t < NT; ++t)
         for (int r = 0; r < 16; ++r) s += yacc[t][r];
     if (s == 12345.678f) *sink = s;
+    clock.stop(sink);
 }
 
 __global__ void empty_kernel() {}
@@ -169,7 +211,7 @@ int mnnqb_peak_read(const void* buf, size_t bytes, void* sink, void* stream)
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
-int mnnqb_peak_mfma(int kind, int epilogue, int waves_per_simd, int iters, void* sink, void* stream)
+int mnnqb_peak_mfma(int kind, int epilogue, int waves_per_simd, int iters, int seed, void* sink, void* stream)
 {
     if (!sink) return -1;
     if (iters <= 0 || waves_per_simd < 1 || waves_per_simd > 4) return -2;
@@ -178,13 +220,13 @@ int mnnqb_peak_mfma(int kind, int epilogue, int waves_per_simd, int iters, void*
     const dim3 grid((unsigned)num_cus()), block(256u * (unsigned)waves_per_simd);   // one workgroup per CU
     hipStream_t st = static_cast<hipStream_t>(stream);
     float* out = static_cast<float*>(sink);
-    if (kind == 0 && epilogue == 0) hipLaunchKernelGGL((peak_mfma_kernel<0, 0>), grid, block, 0, st, iters, 1, out);
-    if (kind == 0 && epilogue == 1) hipLaunchKernelGGL((peak_mfma_kernel<0, 1>), grid, block, 0, st, iters, 1, out);
-    if (kind == 0 && epilogue == 2) hipLaunchKernelGGL((peak_mfma_kernel<0, 2>), grid, block, 0, st, iters, 1, out);
-    if (kind == 1) hipLaunchKernelGGL((peak_mfma_kernel<1, 0>), grid, block, 0, st, iters, 1, out);
-    if (kind == 2) hipLaunchKernelGGL((peak_mfma_kernel<2, 0>), grid, block, 0, st, iters, 1, out);
-    if (kind == 3) hipLaunchKernelGGL((peak_fp6_kernel<false>), grid, block, 0, st, iters, 1, out);
-    if (kind == 4) hipLaunchKernelGGL((peak_fp6_kernel<true>), grid, block, 0, st, iters, 1, out);
+    if (kind == 0 && epilogue == 0) hipLaunchKernelGGL((peak_mfma_kernel<0, 0>), grid, block, 0, st, iters, seed, out);
+    if (kind == 0 && epilogue == 1) hipLaunchKernelGGL((peak_mfma_kernel<0, 1>), grid, block, 0, st, iters, seed, out);
+    if (kind == 0 && epilogue == 2) hipLaunchKernelGGL((peak_mfma_kernel<0, 2>), grid, block, 0, st, iters, seed, out);
+    if (kind == 1) hipLaunchKernelGGL((peak_mfma_kernel<1, 0>), grid, block, 0, st, iters, seed, out);
+    if (kind == 2) hipLaunchKernelGGL((peak_mfma_kernel<2, 0>), grid, block, 0, st, iters, seed, out);
+    if (kind == 3) hipLaunchKernelGGL((peak_fp6_kernel<false>), grid, block, 0, st, iters, seed, out);
+    if (kind == 4) hipLaunchKernelGGL((peak_fp6_kernel<true>), grid, block, 0, st, iters, seed, out);
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
