@@ -531,6 +531,25 @@ def main() -> int:
                 achievable[key + suffix + "_shader_mhz"] = round(mhz)
 
     pack_gbs = round(mdl.pack_bytes_in / (mdl.pack_ms * 1e-3) / 1e9, 1)
+    # The load-time kernels in steady state: the largest layer of the block quantized and stored into buffers
+    # allocated before (the set-up figure above includes the allocations and, with the plane, both kernels).
+    note("load-time kernels")
+    name_p, N_p, K_p = max(mdl.layers, key=lambda l: l[1] * l[2])
+    srcs = [torch.randn((N_p, K_p), dtype=torch.float32, device=dev) * 0.02 for _ in range(2)]
+    mode_c = mdl.mode & 15
+    dsts = [torch.empty(B.mnnq_packed_size(N_p, K_p, 64, mode_c), dtype=torch.uint8, device=dev) for _ in range(2)]
+    t_pack = time_run(lambda: [B.mnnq_pack_weights(s, out=d, mode=mode_c) for s, d in zip(srcs, dsts)], 5) / 2
+    pack = {"layer": name_p, "quantize_and_store_us": round(t_pack * 1e3, 1),
+            "bytes": 4 * N_p * K_p + dsts[0].numel(),
+            "gbs": round((4 * N_p * K_p + dsts[0].numel()) / (t_pack * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round((4 * N_p * K_p + dsts[0].numel()) / (t_pack * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "set_up_gbs_fp32_in": pack_gbs}
+    if mdl.plane:
+        dsts6 = [torch.empty(B.mnnq_packed_size(N_p, K_p, 64, mdl.mode), dtype=torch.uint8, device=dev) for _ in range(2)]
+        t6 = time_run(lambda: [B.mnnq_pack_weights(s, out=d, mode=mdl.mode) for s, d in zip(srcs, dsts6)], 5) / 2
+        pack["with_matrix_plane_us"] = round(t6 * 1e3, 1)
+        del dsts6
+    del srcs, dsts
     setup_s = mdl.setup_s
     n_blocks, M_pre, has_lm, plane = mdl.n_blocks, mdl.M, mdl.lm is not None, mdl.plane
     packed_bytes_per_weight = round(sum(mdl.packed[name][0].numel() for name, _, _ in mdl.layers) /
@@ -700,7 +719,7 @@ def main() -> int:
         "configs": configs,
         "cpu_baseline": cpu,
         "achievable": achievable,
-        "pack_gbs_fp32_in": pack_gbs,
+        "pack": pack,
         "setup_s": round(setup_s, 1),
     }
     print(json.dumps(out))

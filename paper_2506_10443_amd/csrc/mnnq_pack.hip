@@ -58,51 +58,104 @@ __device__ __forceinline__ void store_group(uint8_t* __restrict__ packed, const 
     }
 }
 
+// int4 forms.  A workgroup takes kPackChunks consecutive chunks of the layout (16 rows x 128 weights each):
+// team r (16 lanes, one float4 each) quantizes the two groups of row 16 t + r, the chunk images are put
+// together in LDS in the layout's lane order, and the workgroup stores them - codes, scales, zero points or
+// minima - as whole consecutive kilobytes (Section 5.1: consecutive lanes on consecutive addresses; the
+// one-group-per-team form before this one wrote 8 bytes here and 8 bytes a kilobyte further on, and the
+// memory system wrote 2.4 times the bytes).  All loads are issued before the first is used.
+constexpr int kPackChunks = 4;
+
 __global__ __launch_bounds__(kPackThreads) void pack_kernel(const float* __restrict__ W, Layout L,
                                                             uint8_t* __restrict__ packed)
 {
-    const int64_t team = (int64_t)blockIdx.x * (kPackThreads / kTeam) + threadIdx.x / kTeam;
-    const int li = threadIdx.x % kTeam;
-    const int64_t total = L.N * L.G;
-    // Whole teams leave together, so the 16-lane shuffles below stay convergent.
-    if (team >= total) return;
-    const int64_t n = team / L.G;
-    const int64_t g = team % L.G;
-
-    const float4 w = reinterpret_cast<const float4*>(W + team * kGroup)[li];
-    float mn = fminf(fminf(w.x, w.y), fminf(w.z, w.w));
-    float mx = fmaxf(fmaxf(w.x, w.y), fmaxf(w.z, w.w));
-#pragma unroll
-    for (int o = 1; o < kTeam; o <<= 1) {
-        mn = fminf(mn, __shfl_xor(mn, o, kTeam));
-        mx = fmaxf(mx, __shfl_xor(mx, o, kTeam));
-    }
+    __shared__ __align__(16) uint32_t img[kPackChunks * 256];   // codes: 64 lanes x 16 bytes per chunk
+    __shared__ float sc_s[kPackChunks * 32], mn_s[kPackChunks * 32];
+    __shared__ uint8_t z_s[kPackChunks * 32];
+    const int tid = threadIdx.x;
+    const int r = tid / kTeam, li = tid % kTeam;
+    const int64_t chunk0 = (int64_t)blockIdx.x * kPackChunks;
+    const int64_t n_chunks = L.T * L.C;
     const bool minf = L.minf;
-    if (!minf) {
-        // Integer zero point: a group that does not straddle zero gets its range widened to contain it.
-        mn = fminf(mn, 0.0f);
-        mx = fmaxf(mx, 0.0f);
-    }
 
-    float scale = 1.0f, zero = 0.0f;
-    uint32_t c0 = 0, c1 = 0, c2 = 0, c3 = 0;
-    if (mx != mn) {
-        scale = (mx - mn) / 15.0f;
-        if (minf) {
-            // Eq. 1 as printed: the minimum is subtracted before the division.
-            c0 = (uint32_t)fminf(fmaxf(rintf((w.x - mn) / scale), 0.0f), 15.0f);
-            c1 = (uint32_t)fminf(fmaxf(rintf((w.y - mn) / scale), 0.0f), 15.0f);
-            c2 = (uint32_t)fminf(fmaxf(rintf((w.z - mn) / scale), 0.0f), 15.0f);
-            c3 = (uint32_t)fminf(fmaxf(rintf((w.w - mn) / scale), 0.0f), 15.0f);
-        } else {
-            zero = rintf((-mn) / scale);
-            c0 = (uint32_t)fminf(fmaxf(rintf(w.x / scale) + zero, 0.0f), 15.0f);
-            c1 = (uint32_t)fminf(fmaxf(rintf(w.y / scale) + zero, 0.0f), 15.0f);
-            c2 = (uint32_t)fminf(fmaxf(rintf(w.z / scale) + zero, 0.0f), 15.0f);
-            c3 = (uint32_t)fminf(fmaxf(rintf(w.w / scale) + zero, 0.0f), 15.0f);
+    float4 w[kPackChunks][2];
+#pragma unroll
+    for (int i = 0; i < kPackChunks; ++i) {
+        const int64_t chunk = chunk0 + i;          // uniform over the workgroup
+        const int64_t t = chunk / L.C, c = chunk % L.C;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int64_t g = 2 * c + half;
+            w[i][half] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (chunk < n_chunks && g < L.G)
+                w[i][half] = reinterpret_cast<const float4*>(W + ((t * kTileN + r) * L.G + g) * kGroup)[li];
         }
     }
-    store_group(packed, L, n, g, li, c0, c1, c2, c3, scale, mn, zero);
+#pragma unroll
+    for (int i = 0; i < kPackChunks; ++i) {
+        const int64_t chunk = chunk0 + i;
+        const int64_t c = chunk % L.C;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const float4 v4 = w[i][half];
+            float scale = 0.0f, zero = 0.0f, mn = 0.0f;
+            uint32_t c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+            // (an odd number of groups: the second half of the last chunk is padding that contributes nothing -
+            // codes 0, scale 0, zero / minimum 0)
+            if (chunk < n_chunks && 2 * c + half < L.G) {
+                mn = fminf(fminf(v4.x, v4.y), fminf(v4.z, v4.w));
+                float mx = fmaxf(fmaxf(v4.x, v4.y), fmaxf(v4.z, v4.w));
+#pragma unroll
+                for (int o = 1; o < kTeam; o <<= 1) {
+                    mn = fminf(mn, __shfl_xor(mn, o, kTeam));
+                    mx = fmaxf(mx, __shfl_xor(mx, o, kTeam));
+                }
+                if (!minf) {
+                    // Integer zero point: a group that does not straddle zero gets its range widened to contain it.
+                    mn = fminf(mn, 0.0f);
+                    mx = fmaxf(mx, 0.0f);
+                }
+                scale = 1.0f;
+                if (mx != mn) {
+                    scale = (mx - mn) / 15.0f;
+                    if (minf) {
+                        // Eq. 1 as printed: the minimum is subtracted before the division.
+                        c0 = (uint32_t)fminf(fmaxf(rintf((v4.x - mn) / scale), 0.0f), 15.0f);
+                        c1 = (uint32_t)fminf(fmaxf(rintf((v4.y - mn) / scale), 0.0f), 15.0f);
+                        c2 = (uint32_t)fminf(fmaxf(rintf((v4.z - mn) / scale), 0.0f), 15.0f);
+                        c3 = (uint32_t)fminf(fmaxf(rintf((v4.w - mn) / scale), 0.0f), 15.0f);
+                    } else {
+                        zero = rintf((-mn) / scale);
+                        c0 = (uint32_t)fminf(fmaxf(rintf(v4.x / scale) + zero, 0.0f), 15.0f);
+                        c1 = (uint32_t)fminf(fmaxf(rintf(v4.y / scale) + zero, 0.0f), 15.0f);
+                        c2 = (uint32_t)fminf(fmaxf(rintf(v4.z / scale) + zero, 0.0f), 15.0f);
+                        c3 = (uint32_t)fminf(fmaxf(rintf(v4.w / scale) + zero, 0.0f), 15.0f);
+                    }
+                }
+            }
+            // Lane li holds codes j = 4 (li % 4) .. +3 of k-block kb = li / 4.  Codes j % 8 < 4 go to low
+            // nibbles, the others to high nibbles of the same bytes.
+            uint32_t v = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+            if (li & 1) v <<= 4;
+            v |= __shfl_xor(v, 1, kTeam);
+            const int kb = li / 4, d = (li % 4) / 2;
+            if ((li & 1) == 0) img[i * 256 + (16 * kb + r) * 4 + half * 2 + d] = v;
+            if (li == 0) {
+                sc_s[i * 32 + r * 2 + half] = scale;
+                mn_s[i * 32 + r * 2 + half] = mn;
+                z_s[i * 32 + r * 2 + half] = (uint8_t)zero;
+            }
+        }
+    }
+    __syncthreads();
+    // kPackChunks consecutive chunks are consecutive in all three arrays of the layout
+    const int live = (int)((n_chunks - chunk0 < kPackChunks) ? (n_chunks - chunk0) : kPackChunks);
+    if (tid < live * 64) reinterpret_cast<uint4*>(packed + chunk0 * kChunkBytes)[tid] = reinterpret_cast<const uint4*>(img)[tid];
+    if (tid < live * 32) {
+        (reinterpret_cast<float*>(packed + L.scales_off()) + chunk0 * 32)[tid] = sc_s[tid];
+        if (minf) (reinterpret_cast<float*>(packed + L.zeros_off()) + chunk0 * 32)[tid] = mn_s[tid];
+        else (packed + L.zeros_off() + chunk0 * 32)[tid] = z_s[tid];
+    }
 }
 
 // int8 weights: Eq. 1 with clip range 0..255 and a float minimum, stored as two 4-bit
@@ -273,7 +326,8 @@ int launch_pack(const float* W, const Layout& L, uint8_t* packed, hipStream_t st
     if (L.mode == MNNQ_W8_MIN_FLOAT)
         hipLaunchKernelGGL(pack8_kernel, dim3((unsigned)blocks), dim3(kPackThreads), 0, st, W, L, packed);
     else
-        hipLaunchKernelGGL(pack_kernel, dim3((unsigned)blocks), dim3(kPackThreads), 0, st, W, L, packed);
+        hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((L.T * L.C + kPackChunks - 1) / kPackChunks)), dim3(kPackThreads), 0, st,
+                           W, L, packed);
     MNNQ_HIP_TRY(hipGetLastError());
     return MNNQ_OK;
 }
