@@ -105,7 +105,7 @@ def main() -> int:
     ap.add_argument("--two-call-decode", action="store_true",
                     help="decode pass calls mnnq_quant_act + mnnq_linear_decode per layer instead of the fused call")
     ap.add_argument("--lm-head-prefill", action="store_true", help="also time the LM head through the prefill GEMM")
-    ap.add_argument("--prefill-plan", type=int, default=None, choices=[0, 1, 2, 3, 4],
+    ap.add_argument("--prefill-plan", type=int, default=None, choices=[0, 1, 2, 3, 4, 5],
                     help="force one tile plan of the fp6 GEMM for every layer (tuning; default: the library's choice)")
     ap.add_argument("--peaks", action="store_true", help="also measure what this GPU sustains (`achievable`)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -652,7 +652,7 @@ def main() -> int:
             shapes.setdefault((N, K), [0, p_])[0] += 1
         rows_cap = 4096          # a layer is timed on its first rows_cap output rows and scaled by N / rows
         budget = {"dec1": 0.0, "decN": 0.0, "pre1": 0.0, "preN": 0.0}
-        m1, mN = 2, 16           # token rows of the prefill samples (1 thread / all cores), scaled by M / rows
+        m1, mN = 4, 48           # token rows of the prefill samples (1 thread / all cores), scaled by M / rows
         sample_s = 0.0
         for (N, K), (cnt, p_) in shapes.items():
             rows = min(N, rows_cap)

@@ -31,6 +31,8 @@
 //   D: lane l holds column l % 32, rows 8 (r / 4) + 4 (l / 32) + r % 4 for r = 0..15.
 #include "mnnq_common.h"
 
+#include <type_traits>
+
 namespace mnnq {
 
 namespace {
@@ -186,12 +188,15 @@ template <int BM, int BN>
 struct Stage {
     static constexpr int A_BYTES = BM * 96;
     static constexpr int B_BYTES = BN * 48;
-    static constexpr int S_BYTES = 1024;             // BN <= 256 scales, one wave-wide load
-    static constexpr int B_OFF = A_BYTES;
-    static constexpr int S_OFF = A_BYTES + B_BYTES;
-    static constexpr int BYTES = A_BYTES + B_BYTES + S_BYTES;
-    static constexpr int NA = A_BYTES / 1024, NB = B_BYTES / 1024;
-    static_assert(A_BYTES % 1024 == 0 && B_BYTES % 1024 == 0 && BN <= 256, "whole wave-wide loads");
+    static constexpr int S_BYTES = (BN * 4 + 1023) / 1024 * 1024;   // BN scales in whole wave-wide loads
+    static constexpr int W_BYTES = B_BYTES + S_BYTES;                // weight side of a stage: codes, then scales
+    // The activation side is a ring of two, the weight side a ring of two or - for wave tiles of more than
+    // four column tiles, whose weight fragments are still read while their group is contracted - of three.
+    static constexpr int NRING_W = (BN / 32 > 8) ? 3 : 2;
+    static constexpr int W_RING_OFF = 2 * A_BYTES;
+    static constexpr int BYTES = 2 * A_BYTES + NRING_W * W_BYTES;    // all stages of one K part
+    static constexpr int NA = A_BYTES / 1024, NB = B_BYTES / 1024, NSC = S_BYTES / 1024;
+    static_assert(A_BYTES % 1024 == 0 && B_BYTES % 1024 == 0, "whole wave-wide loads");
 };
 
 // LDS of a workgroup: two stages per K part and the junk kilobyte, or the K parts' sums when those
@@ -199,7 +204,7 @@ struct Stage {
 template <int BM, int BN, int KS>
 constexpr size_t lds_bytes6()
 {
-    const size_t stages = (size_t)KS * 2 * Stage<BM, BN>::BYTES + 1024;
+    const size_t stages = (size_t)KS * Stage<BM, BN>::BYTES + 1024;
     const size_t sums = KS > 1 ? (size_t)(BM / 32) * (BN / 32) * 16 * 64 * 4 : 0;
     return stages > sums ? stages : sums;
 }
@@ -230,7 +235,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
     using St = Stage<BM, BN>;
     constexpr int W = WM * WN;                        // waves per K part
     constexpr int TMW = BM / WM / 32, TNW = BN / WN / 32;
-    constexpr int NL = (St::NA + St::NB + 1 + W - 1) / W;   // direct loads per wave and stage
+    constexpr int NL = (St::NA + St::NB + St::NSC + W - 1) / W;   // direct loads per wave and stage
     static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "whole 32 x 32 tiles per wave");
 
     extern __shared__ __align__(16) uint8_t lds_all[];
@@ -241,8 +246,11 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
     const int part = wave_id / W;                    // K part of this wave
     const int w = wave_id % W;
     const int wm = w / WN, wn = w % WN;
-    uint8_t* const lds = lds_all + part * (2 * St::BYTES);
-    uint8_t* const junk = lds_all + KS * 2 * St::BYTES;
+    uint8_t* const lds = lds_all + part * St::BYTES;
+    uint8_t* const junk = lds_all + KS * St::BYTES;
+    // stage of group k (counted from this part's first group): activation side, weight side
+    auto stage_a = [&](int k) { return lds + (k & 1) * St::A_BYTES; };
+    auto stage_w = [&](int k) { return lds + St::W_RING_OFF + (St::NRING_W == 2 ? (k & 1) : k % 3) * St::W_BYTES; };
 
     // Workgroups are dealt to the 8 XCDs round-robin by their linear id: each XCD gets whole columns
     // of output tiles, so that a block of weights is fetched into one L2 only.
@@ -265,11 +273,13 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
     const int s_base = (int)L.plane_codes_bytes() + tile_n * (BN / 32) * 128, s_step = (int)L.T32p * 128;
     const int voff = lane * 16;
 
-    // Stage `buf` <- group g: this wave's NL pieces of 1 KiB (slots past the stage's pieces go to a
-    // junk kilobyte with an out-of-range source, so that every wave issues the same number of loads).
-    // Groups past the end of the matrix lie outside the buffers and arrive as zeros.
-    auto issue_stage = [&](int g, int buf) {
-        uint8_t* st = lds + buf * St::BYTES;
+    // Stage of the part's group k <- group gb + k: this wave's NL pieces of 1 KiB (slots past the stage's
+    // pieces go to a junk kilobyte with an out-of-range source, so that every wave issues the same number
+    // of loads).  Groups past the end of the matrix lie outside the buffers and arrive as zeros.
+    auto issue_stage = [&](int k) {
+        const int g = gb + k;
+        uint8_t* sta = stage_a(k);
+        uint8_t* stw = stage_w(k);
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int s = w + W * i;   // wave-uniform
@@ -277,14 +287,14 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
             // load's argument list this toolchain's host pass drops the kernel without a message)
             const int so_a = uniform(a_base + g * a_step + s * 1024);
             const int so_w = uniform(w_base + g * w_step + (s - St::NA) * 1024);
-            const int so_s = uniform(s_base + g * s_step);
+            // (scales: a kilobyte past the tile's own columns holds the next tiles' scales or lies outside the
+            // buffer; nobody reads that part of the stage)
+            const int so_s = uniform(s_base + g * s_step + (s - St::NA - St::NB) * 1024);
+            const int so_ws = s < St::NA + St::NB ? so_w : so_s;
             if (s < St::NA)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, MNNQ_LDS(st + s * 1024), 16, voff, so_a, 0, 0);
-            else if (s < St::NA + St::NB)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(st + St::B_OFF + (s - St::NA) * 1024), 16, voff,
-                                                         so_w, 0, 0);
-            else if (s == St::NA + St::NB)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(st + St::S_OFF), 16, voff, so_s, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, MNNQ_LDS(sta + s * 1024), 16, voff, so_a, 0, 0);
+            else if (s < St::NA + St::NB + St::NSC)   // codes, then scales: consecutive in the stage
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(stw + (s - St::NA) * 1024), 16, voff, so_ws, 0, 0);
             else
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(junk), 16, voff, kOutOfRange, 0, 0);
         }
@@ -302,16 +312,20 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
     const v16f zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     // this wave's fragments inside a stage
-    const int a_frag = (wm * TMW) * 2 * kPlaneBlockBytes;
-    const int b_frag = St::B_OFF + (wn * TNW) * kPlaneBlockBytes;
-    const int s_frag = St::S_OFF + (wn * TNW) * 128 + (lane & 31) * 4;
+    const int a_frag = (wm * TMW) * 2 * kPlaneBlockBytes;                    // in the activation side
+    const int b_frag = (wn * TNW) * kPlaneBlockBytes;                        // in the weight side
+    const int s_frag = St::B_BYTES + (wn * TNW) * 128 + (lane & 31) * 4;
 
     const int off16 = lane * 16, off8 = lane * 8;
     int off8x = off8;
     asm volatile("" : "+v"(off8x));   // the same value, unknown to the compiler (see frag6)
 
-    v8i ahi[TMW], alo[TMW], b[TNW];
-    float sc[TNW], scn[TNW];
+    // Wide wave tiles (more than four column tiles): the column-major loop below, which holds two weight
+    // fragments at a time instead of all TNW - all of them plus the accumulators would not fit 256 registers.
+    constexpr bool JO = TNW > 4;
+    static_assert(!JO || (KS == 1 && !ACC), "the column-major loop is built for one K part");
+    v8i ahi[TMW], alo[TMW], b[JO ? 2 : TNW];
+    float sc[JO ? 2 : TNW], scn[JO ? 1 : TNW];
     auto read_a = [&](const uint8_t* st, int i) {
         ahi[i] = frag6(st + a_frag + i * 2 * kPlaneBlockBytes, off16, off8);
         alo[i] = frag6(st + a_frag + i * 2 * kPlaneBlockBytes + kPlaneBlockBytes, off16, off8x);
@@ -320,47 +334,131 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
         b[j] = frag6(st + b_frag + j * kPlaneBlockBytes, off16, (j & 1) ? off8x : off8);
     };
 
-    issue_stage(gb, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-    __builtin_amdgcn_s_barrier();
-    issue_stage(gb + 1, 1);
-#pragma unroll
-    for (int j = 0; j < TNW; ++j) {
-        read_b(lds, j);
-        sc[j] = *reinterpret_cast<const float*>(lds + s_frag + j * 128);
-    }
-#pragma unroll
-    for (int i = 0; i < TMW; ++i) read_a(lds, i);
-
-    for (int it = 0; it < n_iter; ++it) {
-        const int g = gb + it;
-        // Top of group g: its fragments are in registers (or on their way).  Once this wave's reads of
-        // the stage they came from and its pieces of the next stage are complete, and every other
-        // wave's too, the old stage can be loaded over and the next one read.
-        __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+    if constexpr (JO) {
+        // Column-major order over the wave's tiles: column j's fragment sits in slot (j + PAR) & 1 and is
+        // replaced, after its last use, by the fragment two columns further on - of this group or of the next
+        // one (stage g + 1).  With an odd TNW the slot of column 0 alternates from group to group, hence two
+        // copies of the group body (PAR = 0, 1).  The multiply-adds of a tile run behind the matrix
+        // instructions of the next one, so a column's scale is replaced only after the multiply-adds of its
+        // last tile.
+        auto read_bs = [&](const uint8_t* st, int j, int slot) {
+            b[slot] = frag6(st + b_frag + j * kPlaneBlockBytes, off16, (slot & 1) ? off8x : off8);
+        };
+        auto read_sc = [&](const uint8_t* st, int j) { return *reinterpret_cast<const float*>(st + s_frag + j * 128); };
+        issue_stage(0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         __builtin_amdgcn_s_barrier();
-        issue_stage(g + 2, it & 1);
-        if (KS > 1 && g >= ge) continue;      // the shorter share idles through the last round
-        const uint8_t* nx = lds + ((it + 1) & 1) * St::BYTES;   // stage of group g + 1
-
-        v16f d[2];
+        issue_stage(1);
+        read_bs(stage_w(0), 0, 0);
+        read_bs(stage_w(0), 1, 1);
+        sc[0] = read_sc(stage_w(0), 0);
+        sc[1] = read_sc(stage_w(0), 1);
 #pragma unroll
-        for (int t = 0; t < TMW * TNW; ++t) {
-            const int i = t / TNW, j = t % TNW;
-            d[t & 1] = mfma6(ahi[i], b[j], zero16, scale_hi, scale_b);
-            d[t & 1] = mfma6(alo[i], b[j], d[t & 1], scale_lo, scale_b);
-            // fragments used for the last time in this group: fetch their successors
-            if (j == TNW - 1) read_a(nx, i);
-            if (i == TMW - 1) {
-                read_b(nx, j);
-                scn[j] = *reinterpret_cast<const float*>(nx + s_frag + j * 128);
+        for (int i = 0; i < TMW; ++i) read_a(stage_a(0), i);
+
+        auto group = [&](auto par_c, int it) {
+            constexpr int PAR = decltype(par_c)::value;
+            __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+            __builtin_amdgcn_s_barrier();
+            // Top of group `it`: its activation fragments and the weight fragments of its first two columns
+            // are in registers (or on their way); its other columns are read from its weight stage as it
+            // goes, which therefore stays untouched until the next barrier - the loads of group it + 2 go to the
+            // third stage of the weight ring and to the activation stage this group has been read out of.
+            issue_stage(it + 2);
+            const uint8_t* cu = stage_w(it);          // weight side of this group
+            const uint8_t* nx = stage_w(it + 1);      // ... and of the next one
+            const uint8_t* nxa = stage_a(it + 1);
+            v16f d[2];
+#pragma unroll
+            for (int t = 0; t < TMW * TNW; ++t) {
+                const int j = t / TMW, i = t % TMW;
+                const int slot = (j + PAR) & 1;
+                d[t & 1] = mfma6(ahi[i], b[slot], zero16, scale_hi, scale_b);
+                d[t & 1] = mfma6(alo[i], b[slot], d[t & 1], scale_lo, scale_b);
+                if (j == TNW - 1) read_a(nxa, i);
+                if (i == TMW - 1) {
+                    if (j + 2 < TNW) read_bs(cu, j + 2, slot);
+                    else read_bs(nx, j + 2 - TNW, slot);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (t > 0) {
+                    const int tp = t - 1, jp = tp / TMW, ip = tp % TMW, sp = (jp + PAR) & 1;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) yacc[ip * TNW + jp][r] = fmaf(sc[sp], d[tp & 1][r], yacc[ip * TNW + jp][r]);
+                    if (ip == TMW - 1) sc[sp] = (jp + 2 < TNW) ? read_sc(cu, jp + 2) : read_sc(nx, jp + 2 - TNW);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
-            // the multiply-adds of the tile before, behind this tile's matrix instructions
-            if (t > 0) {
-                const int tp = t - 1, jp = (t - 1) % TNW;
+            {
+                constexpr int tp = TMW * TNW - 1, jp = tp / TMW, ip = tp % TMW, sp = (jp + PAR) & 1;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) yacc[ip * TNW + jp][r] = fmaf(sc[sp], d[tp & 1][r], yacc[ip * TNW + jp][r]);
+                sc[sp] = read_sc(nx, jp + 2 - TNW);
+            }
+        };
+        for (int it = 0; it < n_iter; it += 2) {
+            group(std::integral_constant<int, 0>{}, it);
+            if (it + 1 < n_iter) group(std::integral_constant<int, (TNW & 1)>{}, it + 1);
+        }
+    } else {
+        issue_stage(0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        issue_stage(1);
+#pragma unroll
+        for (int j = 0; j < TNW; ++j) {
+            read_b(stage_w(0), j);
+            sc[j] = *reinterpret_cast<const float*>(stage_w(0) + s_frag + j * 128);
+        }
+#pragma unroll
+        for (int i = 0; i < TMW; ++i) read_a(stage_a(0), i);
+
+        for (int it = 0; it < n_iter; ++it) {
+            const int g = gb + it;
+            // Top of group g: its fragments are in registers (or on their way).  Once this wave's reads of
+            // the stage they came from and its pieces of the next stage are complete, and every other
+            // wave's too, the old stage can be loaded over and the next one read.
+            __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+            __builtin_amdgcn_s_barrier();
+            issue_stage(it + 2);
+            if (KS > 1 && g >= ge) continue;      // the shorter share idles through the last round
+            const uint8_t* nx = stage_w(it + 1);   // stage of group g + 1: weight side
+            const uint8_t* nxa = stage_a(it + 1);  // ... and activation side
+
+            v16f d[2];
+#pragma unroll
+            for (int t = 0; t < TMW * TNW; ++t) {
+                const int i = t / TNW, j = t % TNW;
+                d[t & 1] = mfma6(ahi[i], b[j], zero16, scale_hi, scale_b);
+                d[t & 1] = mfma6(alo[i], b[j], d[t & 1], scale_lo, scale_b);
+                // fragments used for the last time in this group: fetch their successors
+                if (j == TNW - 1) read_a(nxa, i);
+                if (i == TMW - 1) {
+                    read_b(nx, j);
+                    scn[j] = *reinterpret_cast<const float*>(nx + s_frag + j * 128);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                // the multiply-adds of the tile before, behind this tile's matrix instructions
+                if (t > 0) {
+                    const int tp = t - 1, jp = (t - 1) % TNW;
+                    if (ACC) {
+                        const int ip = tp / TNW;
+                        const int64_t n = (int64_t)tile_n * BN + (wn * TNW + jp) * 32 + (lane & 31);
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int64_t m = (int64_t)tile_m * BM + (wm * TMW + ip) * 32 + 8 * (r / 4) + 4 * (lane >> 5) + r % 4;
+                            if (m < M && n < L.N) acc_out[(m * L.N + n) * G + g] = (int32_t)d[tp & 1][r];
+                        }
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) yacc[tp][r] = fmaf(sc[jp], d[tp & 1][r], yacc[tp][r]);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            {
+                constexpr int tp = TMW * TNW - 1, jp = tp % TNW, ip = tp / TNW;
                 if (ACC) {
-                    const int ip = tp / TNW;
                     const int64_t n = (int64_t)tile_n * BN + (wn * TNW + jp) * 32 + (lane & 31);
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
@@ -372,24 +470,9 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
                     for (int r = 0; r < 16; ++r) yacc[tp][r] = fmaf(sc[jp], d[tp & 1][r], yacc[tp][r]);
                 }
             }
-            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < TNW; ++j) sc[j] = scn[j];
         }
-        {
-            constexpr int tp = TMW * TNW - 1, jp = tp % TNW, ip = tp / TNW;
-            if (ACC) {
-                const int64_t n = (int64_t)tile_n * BN + (wn * TNW + jp) * 32 + (lane & 31);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t m = (int64_t)tile_m * BM + (wm * TMW + ip) * 32 + 8 * (r / 4) + 4 * (lane >> 5) + r % 4;
-                    if (m < M && n < L.N) acc_out[(m * L.N + n) * G + g] = (int32_t)d[tp & 1][r];
-                }
-            } else {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) yacc[tp][r] = fmaf(sc[jp], d[tp & 1][r], yacc[tp][r]);
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < TNW; ++j) sc[j] = scn[j];
     }
     if (ACC) return;
 
@@ -480,11 +563,12 @@ int tmp_tiles(int64_t M) { return (int)(((M + 31) / 32 + kPlaneTilePad - 1) / kP
 
 // Tile plans (all waves own 64 rows): 0 = 128 x 128 tiles of four waves (two workgroups per CU),
 // 1 = 128 x 128 with the K range in two parts (eight waves), 2 = 128 x 256 of four waves (64 x 128
-// outputs per wave, two workgroups per CU), 3 = 128 x 256 with two K parts, 4 = 256 x 256 of eight waves.
+// outputs per wave, two workgroups per CU), 3 = 128 x 256 with two K parts, 4 = 256 x 256 of eight waves,
+// 5 = 128 x 320 of four waves (64 x 160 outputs per wave, the column-major loop, two workgroups per CU).
 int choose_plan6(const Layout& L, int64_t M)
 {
     if (const char* e = debug_option(kDbgPrefill6Plan))   // tests and tuning
-        if (e[0] >= '0' && e[0] <= '4') return e[0] - '0';
+        if (e[0] >= '0' && e[0] <= '5') return e[0] - '0';
     const int64_t cus = num_cus();
     auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((L.N + bn - 1) / bn); };
     auto rounds = [&](int64_t t, int64_t slots) { return (double)((t + slots - 1) / slots); };
@@ -498,10 +582,14 @@ int choose_plan6(const Layout& L, int64_t M)
     // all come at the end, with nothing left to overlap them).
     // (The K-split forms of these sizes lost everywhere they were measured: their loops are short and the
     // exchange of the sums is a fixed cost per tile.)
-    const double r2 = rounds(tiles(128, 256), 2 * cus);
+    // A 128 x 320 tile (column-major loop) takes 2.21 times a 128 x 128 one for 2.5 times the outputs:
+    // worth it where it saves a round (Qwen2-7B's gate|up: two rounds instead of three of 128 x 256).
+    const double r2 = rounds(tiles(128, 256), 2 * cus), r5 = rounds(tiles(128, 320), 2 * cus);
     const double c0 = rounds(t0, 2 * cus) * 1.0;
-    const double c2 = r2 * 1.54;
-    return (r2 >= 2 && c2 < c0) ? 2 : 0;
+    const double c2 = r2 >= 2 ? r2 * 1.54 : 1e30;
+    const double c5 = r5 >= 2 ? r5 * 2.21 : 1e30;
+    if (c5 < c2 && c5 < c0) return 5;
+    return c2 < c0 ? 2 : 0;
 }
 
 struct Plan6Info {
@@ -516,6 +604,7 @@ Plan6Info plan6_info(int plan)
         case 2: return {128, 256, 1, 4, lds_bytes6<128, 256, 1>()};
         case 3: return {128, 256, 2, 8, lds_bytes6<128, 256, 2>()};
         case 4: return {256, 256, 1, 8, lds_bytes6<256, 256, 1>()};
+        case 5: return {128, 320, 1, 4, lds_bytes6<128, 320, 1>()};
         default: return {128, 128, 1, 4, lds_bytes6<128, 128, 1>()};
     }
 }
@@ -585,6 +674,7 @@ int launch_prefill6(const uint8_t* packed, const Layout& L, int64_t M, const voi
         case 2: return launch6<128, 256, 2, 2, 1, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
         case 3: return launch6<128, 256, 2, 2, 2, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
         case 4: return launch6<256, 256, 4, 2, 1, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
+        case 5: return launch6<128, 320, 2, 2, 1, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
         default: return launch6<128, 128, 2, 2, 1, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
     }
 }

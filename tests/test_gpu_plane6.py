@@ -62,8 +62,8 @@ def test_plane_leaves_the_chunk_layout_alone():
     assert torch.equal(p2, p1)
 
 
-@pytest.mark.parametrize("plan", [0, 1, 2, 3, 4])
-@pytest.mark.parametrize("M,N,K", [(200, 400 - 400 % 16, 1536), (129, 592, 448), (40, 48, 64), (333, 1024, 192)])
+@pytest.mark.parametrize("plan", [0, 1, 2, 3, 4, 5])
+@pytest.mark.parametrize("M,N,K", [(200, 400 - 400 % 16, 1536), (129, 592, 448), (40, 48, 64), (333, 1024, 192), (150, 704, 320)])
 def test_prefill6_every_plan(plan, M, N, K):
     note("prefill6 plan", plan, "M", M, "N", N, "K", K)
     W, x, q, s, z, xq, sx = make(N, K, M, 4200 + plan, special=True)
