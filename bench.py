@@ -34,8 +34,8 @@ FP16_PEAK_TFLOPS = 2500.0    # MI355X dense fp16 MFMA, published
 G = 64
 
 # bytes of group parameters and of codes per two weights, by weight mode
-GROUP_PARAM_BYTES = {"zp": 5, "minfloat": 8, "int8": 16}
-CODE_BYTES_X2 = {"zp": 1, "minfloat": 1, "int8": 2}
+GROUP_PARAM_BYTES = {"zp": 5, "minfloat": 8, "int8": 16, "int8n": 8}
+CODE_BYTES_X2 = {"zp": 1, "minfloat": 1, "int8": 2, "int8n": 2}
 
 
 def decode_bytes(N, K, wm="zp", act_bytes=1):
@@ -96,9 +96,10 @@ def main() -> int:
                     help="skip the other BASELINE configurations (config 1, Qwen2-1.5B, Llama-3-8B W4A8 / W4A16)")
     ap.add_argument("--no-plane", action="store_true",
                     help="pack without the matrix-core plane: the prefill runs the int8 GEMM on the chunk layout")
-    ap.add_argument("--weight-mode", default="zp", choices=["zp", "minfloat", "int8"],
+    ap.add_argument("--weight-mode", default="zp", choices=["zp", "minfloat", "int8", "int8n"],
                     help="weight quantizer: int4 with an integer zero point (the benchmark configuration), int4 "
-                         "as Eq. 1 is printed (float group minimum), or int8 weights (float group minimum)")
+                         "as Eq. 1 is printed (float group minimum), int8 weights (float group minimum) as two 4-bit "
+                         "planes, or int8 weights as bytes (int8n)")
     ap.add_argument("--act16", action="store_true", help="also time the fp16-activation entry points per layer")
     ap.add_argument("--separate-projections", action="store_true",
                     help="run q, k, v and gate, up as launches of their own instead of concatenated along N")
@@ -107,6 +108,8 @@ def main() -> int:
     ap.add_argument("--lm-head-prefill", action="store_true", help="also time the LM head through the prefill GEMM")
     ap.add_argument("--prefill-plan", type=int, default=None, choices=[0, 1, 2, 3, 4, 5],
                     help="force one tile plan of the fp6 GEMM for every layer (tuning; default: the library's choice)")
+    ap.add_argument("--debug-set", action="append", default=[], metavar="KEY=VALUE",
+                    help="a test / tuning switch of the library for the whole run (mnnq_debug_set), e.g. MNNQ_PREFILL_TILE=v1")
     ap.add_argument("--peaks", action="store_true", help="also measure what this GPU sustains (`achievable`)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -137,6 +140,9 @@ def main() -> int:
     B.lib()
     if args.prefill_plan is not None:
         B.mnnq_debug_set("MNNQ_PREFILL6_PLAN", args.prefill_plan)
+    for kv in args.debug_set:
+        key, _, val = kv.partition("=")
+        B.mnnq_debug_set(key, val)
     bench_lib = []
 
     def BL():
@@ -209,7 +215,8 @@ def main() -> int:
             self.n_blocks = spec["blocks"] if n_blocks is None else n_blocks
             self.M = spec["prefill_m"]
             self.layers = synth.block_layers(model, fused=fused_proj)
-            base = {"zp": B.MODE_W4_ZP_INT, "minfloat": B.MODE_W4_MIN_FLOAT, "int8": B.MODE_W8_MIN_FLOAT}[wm]
+            base = {"zp": B.MODE_W4_ZP_INT, "minfloat": B.MODE_W4_MIN_FLOAT, "int8": B.MODE_W8_MIN_FLOAT,
+                    "int8n": B.MODE_W8_MIN_FLOAT | B.NATIVE_8BIT}[wm]
             self.mode = base | (B.WITH_MATRIX_PLANE if (plane and wm == "zp") else 0)
             self.plane = bool(self.mode & B.WITH_MATRIX_PLANE)
             t0 = time.time()
@@ -540,7 +547,7 @@ def main() -> int:
     note("load-time kernels")
     name_p, N_p, K_p = max(mdl.layers, key=lambda l: l[1] * l[2])
     srcs = [torch.randn((N_p, K_p), dtype=torch.float32, device=dev) * 0.02 for _ in range(2)]
-    mode_c = mdl.mode & 15
+    mode_c = mdl.mode & ~B.WITH_MATRIX_PLANE      # the chunk layout alone
     dsts = [torch.empty(B.mnnq_packed_size(N_p, K_p, 64, mode_c), dtype=torch.uint8, device=dev) for _ in range(2)]
     t_pack = time_run(lambda: [B.mnnq_pack_weights(s, out=d, mode=mode_c) for s, d in zip(srcs, dsts)], 5) / 2
     pack = {"layer": name_p, "quantize_and_store_us": round(t_pack * 1e3, 1),

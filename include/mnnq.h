@@ -80,7 +80,15 @@ typedef enum {
      * then run on those instructions when they are also given a workspace for the activations'
      * counterpart (mnnq_workspace_size); every other call reads the chunk layout in front as before.
      * Results are those of the unflagged mode: the plane holds the same integers q - zero. */
-    MNNQ_WITH_MATRIX_PLANE = 16
+    MNNQ_WITH_MATRIX_PLANE = 16,
+    /* Flag, to be OR-ed to MNNQ_W8_MIN_FLOAT in every call that takes a mode: the 8-bit codes are stored
+     * as bytes (q - 128, the operand of the int8 dot and matrix instructions as it stands; 1.125 bytes
+     * per weight: Section 5.1's rearrangement for the instruction that consumes the data) instead of two
+     * 4-bit planes.  Same quantizer, same results up to the order of the fp32 sums.  Supported by the
+     * pack / unpack / import calls and the W8A8 linear calls (decode, prefill, their fused and binary16
+     * forms; a few tokens at once run through the tiled GEMM); the fp16-activation calls and the
+     * accumulator dumps return MNNQ_ERR_UNSUPPORTED for it - they read the plane form. */
+    MNNQ_NATIVE_8BIT = 32
 } mnnq_mode;
 
 /* Text for a status code (static storage). */

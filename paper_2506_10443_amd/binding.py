@@ -17,6 +17,7 @@ MODE_W4_ZP_INT = 0      # integer zero point per (row, group)
 MODE_W4_MIN_FLOAT = 1   # Eq. 1 as printed: fp32 group minimum per (row, group)
 MODE_W8_MIN_FLOAT = 2   # int8 weights (codes 0..255), fp32 group minimum; K must be a multiple of 128
 WITH_MATRIX_PLANE = 16  # flag for MODE_W4_ZP_INT: the packed buffer also holds the fp6 matrix-core plane
+NATIVE_8BIT = 32        # flag for MODE_W8_MIN_FLOAT: the codes as bytes q8 - 128 instead of two 4-bit planes
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "lib", "libmnnq.so")

@@ -47,7 +47,10 @@ int check_shape(int64_t N, int64_t K, int group, int mode_and_flags)
 {
     if (N <= 0 || K <= 0) return MNNQ_ERR_SHAPE;
     const int mode = mode_and_flags & kModeMask;
-    if (mode_and_flags < 0 || (mode_and_flags & ~(kModeMask | MNNQ_WITH_MATRIX_PLANE))) return MNNQ_ERR_UNSUPPORTED;
+    if (mode_and_flags < 0 || (mode_and_flags & ~(kModeMask | MNNQ_WITH_MATRIX_PLANE | MNNQ_NATIVE_8BIT)))
+        return MNNQ_ERR_UNSUPPORTED;
+    // the byte form is a form of the int8 weights
+    if ((mode_and_flags & MNNQ_NATIVE_8BIT) && mode != MNNQ_W8_MIN_FLOAT) return MNNQ_ERR_UNSUPPORTED;
     // the matrix-core plane holds q - zero: integer zero point form only
     if ((mode_and_flags & MNNQ_WITH_MATRIX_PLANE) && mode != MNNQ_W4_ZP_INT) return MNNQ_ERR_UNSUPPORTED;
     if (group != kGroup || mode < MNNQ_W4_ZP_INT || mode > MNNQ_W8_MIN_FLOAT) return MNNQ_ERR_UNSUPPORTED;
@@ -152,7 +155,7 @@ int prefill_impl(const void* packed, int64_t M, int64_t N, int64_t K, int group,
         return launch_prefill6(static_cast<const uint8_t*>(packed), L, M, workspace, sx, bias, static_cast<float*>(y),
                                nullptr, static_cast<hipStream_t>(stream));
     }
-    if (M <= 16 && !debug_option(kDbgNoSkinny))
+    if (M <= 16 && !debug_option(kDbgNoSkinny) && !L.native8)   // (the byte form: a few tokens through the tiled GEMM)
         return launch_skinny(static_cast<const uint8_t*>(packed), L, M, xq, sx, bias, static_cast<float*>(y),
                              static_cast<hipStream_t>(stream));
     return launch_prefill(static_cast<const uint8_t*>(packed), L, M, xq, sx, bias, static_cast<float*>(y), nullptr,
@@ -165,6 +168,7 @@ int decode_f16_impl(const void* packed, int64_t N, int64_t K, int group, int mod
     if (!packed || !x16 || !y) return MNNQ_ERR_NULL;
     if (int s = check_shape(N, K, group, mode)) return s;
     const Layout L = layout_for(N, K, mode, out16);   // the packed reduction axis is what is staged
+    if (L.native8) return MNNQ_ERR_UNSUPPORTED;      // the fp16-activation kernels read the plane form
     if (L.K > (L.minf ? kMaxDecodeKF16Min : kMaxDecodeKF16)) return MNNQ_ERR_UNSUPPORTED;
     if (misaligned(packed) || misaligned(x16) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
     return launch_decode_f16(static_cast<const uint8_t*>(packed), L, x16, bias, static_cast<float*>(y),
@@ -177,6 +181,7 @@ int prefill_f16_impl(const void* packed, int64_t M, int64_t N, int64_t K, int gr
     if (!packed || !x16 || !y) return MNNQ_ERR_NULL;
     if (M <= 0) return MNNQ_ERR_SHAPE;
     if (int s = check_shape(N, K, group, mode)) return s;
+    if (mode & MNNQ_NATIVE_8BIT) return MNNQ_ERR_UNSUPPORTED;   // the fp16-activation kernels read the plane form
     const int64_t slab = prefill_fits(M, N, K, mode, 2) ? M : prefill_slab_rows(N, K, mode, 2);   // byte offsets of fp16 rows
     if (slab <= 0) return MNNQ_ERR_UNSUPPORTED;
     if (misaligned(packed) || misaligned(x16) || misaligned(y) || misaligned(bias)) return MNNQ_ERR_ALIGN;
@@ -541,7 +546,7 @@ int mnnq_linear_acc_debug(const void* packed, int64_t M, int64_t N, int64_t K, i
     if (!packed || !xq || !acc) return MNNQ_ERR_NULL;
     if (M <= 0) return MNNQ_ERR_SHAPE;
     if (int s = check_shape(N, K, group, mode)) return s;
-    if (M > kMaxM) return MNNQ_ERR_UNSUPPORTED;
+    if (M > kMaxM || (mode & MNNQ_NATIVE_8BIT)) return MNNQ_ERR_UNSUPPORTED;   // (no dump in the byte form)
     if (!use_prefill_kernel && make_layout(N, K, mode).K > kMaxDecodeK) return MNNQ_ERR_UNSUPPORTED;
     if (use_prefill_kernel && !prefill_fits(M, N, K, mode)) return MNNQ_ERR_UNSUPPORTED;
     if (misaligned(packed) || misaligned(xq) || misaligned(acc)) return MNNQ_ERR_ALIGN;

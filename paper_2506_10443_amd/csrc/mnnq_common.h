@@ -44,6 +44,11 @@ constexpr int kChunkBytes = 1024;
 // 0..G-1 hold the high nibbles with step 16 s and the group minimum, groups G..2G-1 the low
 // nibbles with step s and minimum 0 - so that q8 s + min = hi (16 s) + min + lo s.  The
 // activation row is not doubled: chunk c of the packed matrix meets chunk c % Cx of the row.
+// Byte form of int8 weights (mode flag MNNQ_NATIVE_8BIT): the reduction axis is not doubled; chunk
+// (t, c) is two kilobytes, one per group - lane l of kilobyte h holds the 16 codes k = 64 (2 c + h) +
+// 16 (l / 16) + j of row 16 t + l % 16 as bytes q8 - 128, i.e. the B operand of v_mfma_i32_16x16x64_i8 and
+// of four v_dot4_i32_i8 as it stands; scales (the step s) and minima [T][C][16][2] fp32 as in the float
+// minimum form.  With D = sum xq (q8 - 128) and xs = sum xq a group's term is  s D + (min + 128 s) xs.
 // Matrix-core plane (mode flag MNNQ_WITH_MATRIX_PLANE): a second copy of the int4 weights behind the
 // chunk layout, as the B operand of the fp6 matrix instruction v_mfma_scale_f32_32x32x64_f8f6f4 -
 // every q - zero (|q - zero| <= 15) is the e2m3 value (q - zero) / 8 exactly, and its code is the
@@ -68,6 +73,7 @@ struct Layout {
     int64_t G;  // groups per row
     int64_t C;  // chunks per row tile
     size_t codes_bytes, scales_bytes, zeros_bytes;
+    bool native8;     // int8 weights as bytes: a chunk is two kilobytes, one per group (see below)
     bool plane;       // the packed buffer carries the matrix-core plane behind the chunk layout
     int64_t T32p;     // column tiles of 32 in the plane (padded to a multiple of 8)
     int64_t Gx;       // quantization groups of an activation row (= groups of the plane)
@@ -93,8 +99,9 @@ inline __host__ __device__ Layout make_layout(int64_t N, int64_t K, int mode_and
     L.T32p = ((N + 31) / 32 + kPlaneTilePad - 1) / kPlaneTilePad * kPlaneTilePad;
     L.Gx = K / kGroup;
     L.N = N;
+    L.native8 = mode == MNNQ_W8_MIN_FLOAT && (mode_and_flags & MNNQ_NATIVE_8BIT) != 0;
     L.Kx = K;
-    L.K = (mode == MNNQ_W8_MIN_FLOAT) ? 2 * K : K;
+    L.K = (mode == MNNQ_W8_MIN_FLOAT && !L.native8) ? 2 * K : K;
     L.mode = mode;
     L.minf = (mode != MNNQ_W4_ZP_INT);
     L.out16 = false;
@@ -102,7 +109,7 @@ inline __host__ __device__ Layout make_layout(int64_t N, int64_t K, int mode_and
     L.G = L.K / kGroup;
     L.C = (L.G + 1) / 2;
     L.Cx = (K / kGroup + 1) / 2;
-    L.codes_bytes = (size_t)L.T * L.C * kChunkBytes;
+    L.codes_bytes = (size_t)L.T * L.C * kChunkBytes * (L.native8 ? 2 : 1);
     L.scales_bytes = (size_t)L.T * L.C * 32 * sizeof(float);
     L.zeros_bytes = (size_t)L.T * L.C * 32 * (L.minf ? sizeof(float) : 1);
     return L;

@@ -382,6 +382,176 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const uint8_t* __res
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Byte form of int8 weights (Layout::native8): a chunk is two kilobytes, one per group, lane l
+// holding the 16 bytes q8 - 128 of row l % 16 and k-block l / 16 - four v_dot4_i32_i8 against the
+// int8 row per group, no unpacking.  With D = sum xq (q8 - 128) and xs = sum xq (the block sums
+// staged with the row) a group's term is  s (D + 128 xs) + min xs.  Same work split, same LDS image
+// of the activation row and same order of operations as decode_kernel: all of a wave's loads
+// first (UNROLL chunks; a rolling window for longer ranges), then the row, then the dot products.
+struct Chunk8Regs {
+    u32x4 w0, w1;   // groups 2c and 2c + 1
+    float2 s, mn;   // steps and minima of the lane's row for both groups
+};
+
+__device__ __forceinline__ Chunk8Regs load_chunk8(const u32x4* wp, const float2* sp, const float2* mp, int64_t i)
+{
+    Chunk8Regs r;
+    r.w0 = __builtin_nontemporal_load(wp + i * 128);
+    r.w1 = __builtin_nontemporal_load(wp + i * 128 + 64);
+    r.s = sp[i * 16];
+    r.mn = mp[i * 16];
+    return r;
+}
+
+__device__ __forceinline__ int dot16_bytes(const u32x4 w, const int4& x)
+{
+    int d = __builtin_amdgcn_sdot4((int)w.x, x.x, 0, false);
+    d = __builtin_amdgcn_sdot4((int)w.y, x.y, d, false);
+    d = __builtin_amdgcn_sdot4((int)w.z, x.z, d, false);
+    d = __builtin_amdgcn_sdot4((int)w.w, x.w, d, false);
+    return d;
+}
+
+template <int WAVES, int KSPLIT, int UNROLL, int MODE, bool PREFETCH>
+__global__ __launch_bounds__(WAVES * 64) void decode8_kernel(const uint8_t* __restrict__ packed, Layout L,
+                                                             const void* __restrict__ xin,
+                                                             const float* __restrict__ sx,
+                                                             const float* __restrict__ bias,
+                                                             float* __restrict__ y, int PW)
+{
+    static_assert(MODE == kXQ || MODE == kFused, "no accumulator dump in the byte form");
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int64_t C = L.C;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = (MODE == kFused) ? __builtin_amdgcn_readfirstlane(tid >> 6) : (tid >> 6);
+    const int row = lane & 15;
+    const int kb = lane >> 4;
+    constexpr int TILES_PER_WG = WAVES / KSPLIT;
+    const int64_t tile = (int64_t)blockIdx.x * TILES_PER_WG + wave / KSPLIT;
+    const int ks = wave % KSPLIT;
+    const bool active = tile < L.T;
+
+    constexpr bool SHARED = (MODE == kFused);
+    const size_t x_bytes = SHARED ? (size_t)C * 160 : (size_t)WAVES * PW * 160;
+    uint8_t* xbase = SHARED ? smem : smem + (size_t)wave * PW * 160;
+    const size_t xs_off = SHARED ? (size_t)C * 128 : (size_t)PW * 128;
+    int* lds_xd = reinterpret_cast<int*>(xbase);
+    const int4* lds_x = reinterpret_cast<const int4*>(xbase);
+    int* lds_xs = reinterpret_cast<int*>(xbase + xs_off);
+    float* lds_part = reinterpret_cast<float*>(smem + x_bytes);         // [WAVES][16]
+    float* lds_amax = lds_part + WAVES * 16;                            // [WAVES]
+
+    const int64_t c0 = C * ks / KSPLIT;
+    const int64_t c1 = C * (ks + 1) / KSPLIT;
+    const int64_t n_chunks = active ? (c1 - c0) : 0;
+    // (a wave without chunks points at the first chunk of the matrix and loads nothing)
+    const int64_t first = n_chunks > 0 ? tile * C + c0 : 0;
+    const u32x4* wp = reinterpret_cast<const u32x4*>(packed) + first * 128 + lane;
+    const float2* sp = reinterpret_cast<const float2*>(packed + L.scales_off()) + first * 16 + row;
+    const float2* mp = reinterpret_cast<const float2*>(packed + L.zeros_off()) + first * 16 + row;
+
+    float4 xr[kRowRegs];
+    if (MODE == kFused) preload_row<WAVES>(static_cast<const float*>(xin), L, xr);
+    // Start the weight stream before the activation row is touched: it does not depend on x.
+    Chunk8Regs cur[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        if (u < n_chunks) cur[u] = load_chunk8(wp, sp, mp, u);
+        else cur[u] = Chunk8Regs{};
+    }
+
+    // ---- activation row -> LDS (the image of decode_kernel)
+    float scale = 0.0f;
+    if (MODE == kFused) {
+        scale = quantize_row_to_lds<WAVES>(static_cast<const float*>(xin), xr, L, lds_xd, lds_xs, lds_amax);
+    } else {
+        // This wave's chunks only; the region is private to the wave, whose LDS operations complete in order.
+        const int4* xq16 = reinterpret_cast<const int4*>(static_cast<const int8_t*>(xin));
+        const int64_t valid = L.K / 4;
+        const int64_t own = n_chunks * 8;
+        int4* lds_xw = reinterpret_cast<int4*>(xbase);
+        for (int64_t u = lane; u < own; u += 64) {
+            const int64_t gu = c0 * 8 + u;
+            int4 v = make_int4(0, 0, 0, 0);
+            if (gu * 4 < valid) v = xq16[gu];
+            lds_xw[u] = v;
+            int sum = __builtin_amdgcn_sdot4(v.x, 0x01010101, 0, false);
+            sum = __builtin_amdgcn_sdot4(v.y, 0x01010101, sum, false);
+            sum = __builtin_amdgcn_sdot4(v.z, 0x01010101, sum, false);
+            sum = __builtin_amdgcn_sdot4(v.w, 0x01010101, sum, false);
+            lds_xs[(u / 8) * 8 + (int)(u % 4) * 2 + (int)(u % 8) / 4] = sum;
+        }
+    }
+    const int64_t cbase = SHARED ? c0 : 0;    // chunk index of the wave's first chunk inside its LDS image
+
+    float accf = 0.0f;
+    for (int64_t i = 0; i < n_chunks; i += UNROLL) {
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const Chunk8Regs& r = cur[u];
+            if (i + u < n_chunks) {
+                const int64_t cl = cbase + i + u;
+                const int4 xa = lds_x[cl * 8 + kb];
+                const int4 xb = lds_x[cl * 8 + 4 + kb];
+                const int2 xs = *reinterpret_cast<const int2*>(lds_xs + cl * 8 + kb * 2);
+                // sum xq q8 = D + 128 xs as an integer (below 2^22: exact in fp32), then the group's two terms as
+                // the definition has them - folding the 128 into the minimum instead would add and subtract
+                // 128 s xs in fp32, which cancels badly where s is large against min (a constant group: s = 1)
+                const int i0 = dot16_bytes(r.w0, xa) + (xs.x << 7);
+                const int i1 = dot16_bytes(r.w1, xb) + (xs.y << 7);
+                accf = fmaf(r.s.x, (float)i0, accf);
+                accf = fmaf(r.s.y, (float)i1, accf);
+                accf = fmaf(r.mn.x, (float)xs.x, accf);
+                accf = fmaf(r.mn.y, (float)xs.y, accf);
+            }
+            if (PREFETCH) {
+                // a rolling window: the registers of the chunk just consumed take the chunk UNROLL further on
+                // (past the wave's range its first chunk again, never used - no branch around the load, so that
+                // the compiler waits by count)
+                const bool have = i + UNROLL + u < n_chunks;
+                cur[u] = load_chunk8(have ? wp : wp - lane, sp, mp, have ? i + UNROLL + u : 0);
+            }
+        }
+        if (!PREFETCH) break;   // the host guarantees n_chunks <= UNROLL
+    }
+
+    // Sum over the four k-blocks of the row, then over the KSPLIT waves (fixed order).
+    accf += __shfl_xor(accf, 16, 64);
+    accf += __shfl_xor(accf, 32, 64);
+    if (KSPLIT > 1) {
+        if (kb == 0) lds_part[wave * 16 + row] = accf;
+        __syncthreads();
+        if (ks != 0) return;
+        accf = lds_part[wave * 16 + row];
+#pragma unroll
+        for (int j = 1; j < KSPLIT; ++j) accf += lds_part[(wave + j) * 16 + row];
+    }
+    if (active && kb == 0) {
+        const int64_t n = tile * kTileN + row;
+        float r = accf * ((MODE == kFused) ? scale : sx[0]);
+        if (bias) r += bias[n];
+        store_out(y, n, r, L.out16);
+    }
+}
+
+template <int WAVES, int KSPLIT, int UNROLL, int MODE, bool PREFETCH>
+int launch_cfg8(const uint8_t* packed, const Layout& L, const void* xin, const float* sx, const float* bias, float* y,
+                hipStream_t st)
+{
+    constexpr int tiles_per_wg = WAVES / KSPLIT;
+    const int64_t blocks = (L.T + tiles_per_wg - 1) / tiles_per_wg;
+    const int PW = (int)((L.C + KSPLIT - 1) / KSPLIT);
+    const size_t smem = (MODE == kFused ? (size_t)L.C * 160 : (size_t)WAVES * PW * 160) + WAVES * 17 * sizeof(float);
+    static thread_local int allowed = -1;
+    auto kern = decode8_kernel<WAVES, KSPLIT, UNROLL, MODE, PREFETCH>;
+    if (int s = allow_large_lds(kern, smem, allowed)) return s;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(WAVES * 64), smem, st, packed, L, xin, sx, bias, y, PW);
+    MNNQ_HIP_TRY(hipGetLastError());
+    return MNNQ_OK;
+}
+
 template <int WAVES, int KSPLIT, int UNROLL, int MODE, bool PREFETCH, bool EARLY = false>
 int launch_cfg(const uint8_t* packed, const Layout& L, int64_t M, const void* xin, const float* sx,
                const float* bias, float* y, int32_t* acc, hipStream_t st)
@@ -466,10 +636,48 @@ size_t decode_lds_bytes(const Layout& L, const DecodeCfg& c, bool fused)
     return (fused ? (size_t)L.C * 160 : (size_t)c.waves * pw * 160) + c.waves * 17 * sizeof(float);
 }
 
+// Byte form of int8 weights: seven chunks (of two kilobytes) per wave in registers - the smallest power of
+// two of waves per row tile that gets there; beyond sixteen waves a rolling window of seven.
+DecodeCfg decode8_config(const Layout& L, bool fused)
+{
+    int ks = 1;
+    while (ks < 16 && (L.C + ks - 1) / ks > 7) ks *= 2;
+    if (const char* e = debug_option(kDbgDecodeKsplit)) {   // tests and tuning: force the split
+        const int v = atoi(e);
+        if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16) ks = v;
+    }
+    const int prefetch = (L.C + ks - 1) / ks > 7;
+    const int waves = fused ? (ks > 8 ? 16 : 8) : (ks > 4 ? ks : 4);
+    return DecodeCfg{waves, ks, 7, prefetch, 0};
+}
+
+template <int MODE>
+int dispatch8(const uint8_t* packed, const Layout& L, const void* xin, const float* sx, const float* bias, float* y,
+              hipStream_t st)
+{
+    const DecodeCfg c = decode8_config(L, MODE == kFused);
+#define MNNQ_CFG8(W, K)                                                                                   \
+    if (c.waves == W && c.ks == K) {                                                                      \
+        if (c.prefetch) return launch_cfg8<W, K, 7, MODE, true>(packed, L, xin, sx, bias, y, st);         \
+        return launch_cfg8<W, K, 7, MODE, false>(packed, L, xin, sx, bias, y, st);                        \
+    }
+    if constexpr (MODE == kFused) {
+        MNNQ_CFG8(8, 1) MNNQ_CFG8(8, 2) MNNQ_CFG8(8, 4) MNNQ_CFG8(8, 8) MNNQ_CFG8(16, 16)
+    } else {
+        MNNQ_CFG8(4, 1) MNNQ_CFG8(4, 2) MNNQ_CFG8(4, 4) MNNQ_CFG8(8, 8) MNNQ_CFG8(16, 16)
+    }
+#undef MNNQ_CFG8
+    return MNNQ_ERR_UNSUPPORTED;
+}
+
 template <int MODE>
 int dispatch(const uint8_t* packed, const Layout& L, int64_t M, const void* xin, const float* sx,
              const float* bias, float* y, int32_t* acc, hipStream_t st)
 {
+    if (L.native8) {
+        if constexpr (MODE == kAcc) return MNNQ_ERR_UNSUPPORTED;
+        else return dispatch8<MODE>(packed, L, xin, sx, bias, y, st);
+    }
     const DecodeCfg c = decode_config(L, MODE == kFused);
     const int waves = c.waves, ks = c.ks, unroll = c.unroll, prefetch = c.prefetch;
 #define MNNQ_CFG(W, K, U, P)                                                    \
@@ -493,7 +701,7 @@ int dispatch(const uint8_t* packed, const Layout& L, int64_t M, const void* xin,
 
 void describe_decode(const Layout& L, bool fused, int32_t out[8])
 {
-    const DecodeCfg c = decode_config(L, fused);
+    const DecodeCfg c = L.native8 ? decode8_config(L, fused) : decode_config(L, fused);
     const int tiles_per_wg = c.waves / c.ks;
     out[0] = c.waves;
     out[1] = c.ks;

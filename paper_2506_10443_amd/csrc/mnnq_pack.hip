@@ -158,9 +158,23 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const float* __restr
     }
 }
 
+// Byte form of int8 weights (Layout::native8): the 16 bytes of row n, group g, k-block kb.
+__device__ __forceinline__ size_t native8_codes_off(const Layout& L, int64_t n, int64_t g, int kb)
+{
+    const int64_t chunk = (n / kTileN) * L.C + g / 2;
+    return (size_t)chunk * (2 * kChunkBytes) + (size_t)(g & 1) * kChunkBytes + (16 * kb + (int)(n % kTileN)) * 16;
+}
+
+// Index of the per-group parameters (scale, zero / minimum) of group g, row n.
+__device__ __forceinline__ int64_t param_index(const Layout& L, int64_t n, int64_t g)
+{
+    return (((n / kTileN) * L.C + g / 2) * 16 + n % kTileN) * 2 + (g & 1);
+}
+
 // int8 weights: Eq. 1 with clip range 0..255 and a float minimum, stored as two 4-bit
 // planes along the doubled reduction axis (see Layout): group g holds the high nibbles
-// with step 16 s and the minimum, group G8 + g the low nibbles with step s and minimum 0.
+// with step 16 s and the minimum, group G8 + g the low nibbles with step s and minimum 0;
+// or, in the byte form, as the bytes q8 - 128 with step s and the minimum.
 __global__ __launch_bounds__(kPackThreads) void pack8_kernel(const float* __restrict__ W, Layout L,
                                                              uint8_t* __restrict__ packed)
 {
@@ -188,6 +202,16 @@ __global__ __launch_bounds__(kPackThreads) void pack8_kernel(const float* __rest
         c2 = (uint32_t)fminf(fmaxf(rintf((w.z - mn) / step), 0.0f), 255.0f);
         c3 = (uint32_t)fminf(fmaxf(rintf((w.w - mn) / step), 0.0f), 255.0f);
     }
+    if (L.native8) {
+        // lane li holds k = 4 li .. 4 li + 3: dword li % 4 of k-block li / 4
+        const uint32_t v = (c0 | (c1 << 8) | (c2 << 16) | (c3 << 24)) ^ 0x80808080u;
+        *reinterpret_cast<uint32_t*>(packed + native8_codes_off(L, n, g, li / 4) + (li % 4) * 4) = v;
+        if (li == 0) {
+            reinterpret_cast<float*>(packed + L.scales_off())[param_index(L, n, g)] = step;
+            reinterpret_cast<float*>(packed + L.zeros_off())[param_index(L, n, g)] = mn;
+        }
+        return;
+    }
     store_group(packed, L, n, g, li, c0 >> 4, c1 >> 4, c2 >> 4, c3 >> 4, 16.0f * step, mn, 0.0f);
     store_group(packed, L, n, G8 + g, li, c0 & 15u, c1 & 15u, c2 & 15u, c3 & 15u, step, 0.0f, 0.0f);
 }
@@ -207,11 +231,6 @@ __device__ __forceinline__ uint4 read_codes(const uint8_t* __restrict__ packed, 
     return o;
 }
 
-// Index of the per-group parameters (scale, zero / minimum) of group g, row n.
-__device__ __forceinline__ int64_t param_index(const Layout& L, int64_t n, int64_t g)
-{
-    return (((n / kTileN) * L.C + g / 2) * 16 + n % kTileN) * 2 + (g & 1);
-}
 
 __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t* __restrict__ packed, Layout L,
                                                      uint8_t* __restrict__ q, float* __restrict__ scale,
@@ -224,6 +243,19 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t* __restrict__
     const int kb = (int)(idx % 4);
     const int64_t g = (idx / 4) % G;
     const int64_t n = idx / (4 * G);
+    if (L.native8) {   // byte form: q8 - 128 as stored, step and minimum of the group itself
+        if (q) {
+            uint4 o = *reinterpret_cast<const uint4*>(packed + native8_codes_off(L, n, g, kb));
+            o.x ^= 0x80808080u; o.y ^= 0x80808080u; o.z ^= 0x80808080u; o.w ^= 0x80808080u;
+            *reinterpret_cast<uint4*>(q + n * L.Kx + g * kGroup + 16 * kb) = o;
+        }
+        if (kb == 0) {
+            if (scale) scale[n * G + g] = reinterpret_cast<const float*>(packed + L.scales_off())[param_index(L, n, g)];
+            if (zero) static_cast<float*>(zero)[n * G + g] =
+                          reinterpret_cast<const float*>(packed + L.zeros_off())[param_index(L, n, g)];
+        }
+        return;
+    }
     const bool w8 = (L.mode == MNNQ_W8_MIN_FLOAT);   // high nibbles in group g, low nibbles in group G + g
     if (q) {
         uint4 o = read_codes(packed, L, n, g, kb);
@@ -294,7 +326,15 @@ __global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__
     const int64_t n = idx / (4 * G);
     const uint4 o = *reinterpret_cast<const uint4*>(q + n * L.Kx + g * kGroup + 16 * kb);
     const float s = scale[n * G + g];
-    if (L.mode == MNNQ_W8_MIN_FLOAT) {
+    if (L.native8) {
+        uint4 v = o;
+        v.x ^= 0x80808080u; v.y ^= 0x80808080u; v.z ^= 0x80808080u; v.w ^= 0x80808080u;
+        *reinterpret_cast<uint4*>(packed + native8_codes_off(L, n, g, kb)) = v;
+        if (kb == 0) {
+            reinterpret_cast<float*>(packed + L.scales_off())[param_index(L, n, g)] = s;
+            reinterpret_cast<float*>(packed + L.zeros_off())[param_index(L, n, g)] = static_cast<const float*>(zero)[n * G + g];
+        }
+    } else if (L.mode == MNNQ_W8_MIN_FLOAT) {
         const float mn = static_cast<const float*>(zero)[n * G + g];
         uint4 hi;
         hi.x = o.x >> 4; hi.y = o.y >> 4; hi.z = o.z >> 4; hi.w = o.w >> 4;

@@ -83,7 +83,7 @@ __device__ __forceinline__ v4i unpack_b(uint32_t w0, uint32_t w1, uint32_t c4)
 // the next chunk is loaded over it.
 // W8: the packed matrix holds 8-bit codes as two nibble planes; the low plane's chunk gets a B
 // tile of its own behind the high plane's.
-template <int BM, int BN, bool MINF, bool W8 = false>
+template <int BM, int BN, bool MINF, int W8 = 0>
 struct Lds {
     static constexpr int NT16 = BN / 16;                 // row tiles of B per workgroup
     static constexpr int A_BYTES = BM * 128;             // [BM][128] int8, swizzled
@@ -111,7 +111,7 @@ struct Lds {
 // WNW: waves along N per K part (2 x WNW waves work on a tile).  With WNW = 4 a wave owns 128 x 32
 // outputs of a 256 x 128 tile: half the accumulators, so that four waves fit on a SIMD (two
 // workgroups of eight waves per CU) while a B unpack is still shared by eight MFMAs.
-template <int BM, int BN, int KS, bool ACC, bool MINF, bool W8 = false, int WNW = 2>
+template <int BM, int BN, int KS, bool ACC, bool MINF, int W8 = 0, int WNW = 2>
 __global__ __launch_bounds__(128 * WNW * KS, (ACC || KS > 1) ? 1 : 2) void prefill_kernel(const uint8_t* __restrict__ packed, Layout L, int64_t M,
                                                          const int8_t* __restrict__ xq,
                                                          const float* __restrict__ sx,
@@ -206,10 +206,11 @@ __global__ __launch_bounds__(128 * WNW * KS, (ACC || KS > 1) ? 1 : 2) void prefi
             for (int i = 0; i < B_INSTR; ++i) {
                 const int j = wave * B_INSTR + i;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::B_OFF + j * 1024), 16, b_voff,
-                                                         uniform(((rt0 + j) * C + c) * 1024), 0, 0);
-                if (W8)   // the low nibble plane of the same weights
+                                                         uniform(((rt0 + j) * C + c) * (W8 == 2 ? 2048 : 1024)), 0, 0);
+                if (W8)   // the low nibble plane of the same weights (byte form: the chunk's second group)
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(lds + St::B2_OFF + j * 1024), 16, b_voff,
-                                                             uniform(((rt0 + j) * C + c + Cx) * 1024), 0, 0);
+                                                             uniform(W8 == 2 ? ((rt0 + j) * C + c) * 2048 + 1024
+                                                                             : ((rt0 + j) * C + c + Cx) * 1024), 0, 0);
             }
             // Scales: one load covers two row tiles (2 x 128 B), four loads in all; zeros: one load covers
             // all eight row tiles (8 x 32 B).  (wave is uniform: these are scalar branches.)
@@ -278,7 +279,11 @@ __global__ __launch_bounds__(128 * WNW * KS, (ACC || KS > 1) ? 1 : 2) void prefi
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const uint32_t w0 = (uint32_t)(h ? bw[j].z : bw[j].x), w1 = (uint32_t)(h ? bw[j].w : bw[j].y);
-                    if (W8) {
+                    if (W8 == 2) {
+                        // byte form: the sixteen bytes q8 - 128 are the operand
+                        b[j] = h ? bw2[j] : bw[j];
+                        mnv[j] = __int_as_float(h ? bmn[j].y : bmn[j].x);
+                    } else if (W8) {
                         // q8 - 128 per byte: high plane nibble above low plane nibble, top bit flipped
                         const uint32_t l0 = (uint32_t)(h ? bw2[j].z : bw2[j].x), l1 = (uint32_t)(h ? bw2[j].w : bw2[j].y);
                         b[j].x = (int)((((w0 << 4) & 0xf0f0f0f0u) | (l0 & 0x0f0f0f0fu)) ^ 0x80808080u);
@@ -301,7 +306,7 @@ __global__ __launch_bounds__(128 * WNW * KS, (ACC || KS > 1) ? 1 : 2) void prefi
                     }
                     sc[j] = __int_as_float(h ? bsv[j].y : bsv[j].x);
                     if (W8) {
-                        sc[j] *= 0.0625f;                         // the high plane stores 16 s (exact)
+                        if (W8 == 1) sc[j] *= 0.0625f;            // the high plane stores 16 s (exact)
                         mnv[j] = fmaf(sc[j], 128.0f, mnv[j]);     // min + 128 s
                     }
                 }
@@ -517,7 +522,7 @@ __global__ void zero_f4_kernel(float4* p, int64_t n4)
     if (i < n4) p[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 }
 
-template <int BM, int BN, int KS, bool ACC, bool MINF, bool W8 = false, int WNW = 2>
+template <int BM, int BN, int KS, bool ACC, bool MINF, int W8 = 0, int WNW = 2>
 int launch_tiles_m(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
                  const float* bias, float* y, int32_t* acc, int S, hipStream_t st)
 {
@@ -677,7 +682,7 @@ PrefillLaunch resolve_prefill(const Layout& L, int64_t M)
     // 8-bit weights: both nibble planes of a chunk in one MFMA (128-row tiles: two B tiles need the LDS
     // of the larger A tile).  MNNQ_W8_PLANES=1 (tests, comparisons) keeps one MFMA per plane instead.
     const char* planes = debug_option(kDbgW8Planes);
-    if (L.mode == MNNQ_W8_MIN_FLOAT && !(planes && planes[0] == '1')) {
+    if (L.mode == MNNQ_W8_MIN_FLOAT && (L.native8 || !(planes && planes[0] == '1'))) {
         r.w8 = true;
         r.BM = 128;
         const int64_t tiles128 = ((M + 127) / 128) * ((L.N + 127) / 128), cus = num_cus();
@@ -719,7 +724,7 @@ void describe_prefill(const Layout& L, int64_t M, int32_t out[8])
     out[4] = 2 * r.WNW * r.KS;                                   // waves per workgroup
     out[5] = (int32_t)prefill_lds_bytes(r, L.minf);
     out[6] = (int32_t)(MT * r.S * ((NT + 7) / 8) * 8);           // workgroups
-    out[7] = r.w8 ? 1 : 0;
+    out[7] = r.w8 ? (L.native8 ? 2 : 1) : 0;   // int8 weights: merged nibble planes / byte form
 }
 
 int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8_t* xq, const float* sx,
@@ -731,6 +736,12 @@ int launch_prefill(const uint8_t* packed, const Layout& L, int64_t M, const int8
     }
     const PrefillLaunch r = resolve_prefill(L, M);
 #define MNNQ_ARGS packed, L, M, xq, sx, bias, y, nullptr, r.S, st
+    if (r.w8 && L.native8) {   // byte form: the chunk's two kilobytes are the two groups' operands
+        if (r.KS == 2 && r.WNW == 4) return launch_tiles_m<128, 128, 2, false, true, 2, 4>(MNNQ_ARGS);
+        if (r.WNW == 4) return launch_tiles_m<128, 128, 1, false, true, 2, 4>(MNNQ_ARGS);
+        if (r.KS == 2) return launch_tiles_m<128, 128, 2, false, true, 2>(MNNQ_ARGS);
+        return launch_tiles_m<128, 128, 1, false, true, 2>(MNNQ_ARGS);
+    }
     if (r.w8) {
         if (r.KS == 2 && r.WNW == 4) return launch_tiles_m<128, 128, 2, false, true, true, 4>(MNNQ_ARGS);
         if (r.WNW == 4) return launch_tiles_m<128, 128, 1, false, true, true, 4>(MNNQ_ARGS);

@@ -186,6 +186,22 @@ def test_argument_validation_precedes_hip(L):
     assert pq(FAKE, FAKE, FAKE, 16, 128, 64, 0, FAKE, binding.mnnq_packed_size(16, 128) - 1, None) == SIZE
     assert L.mnnq_unpack_weights(None, 16, 128, 64, 0, FAKE, FAKE, FAKE, None) == NULL
     assert L.mnnq_unpack_weights(FAKE, 16, 128, 64, 0, None, None, None, None) == OK  # nothing asked for
+    # byte form of int8 weights: a flag of mode 2 only; the calls that read the plane form refuse it
+    NB = 2 | 32
+    assert binding.mnnq_packed_size(16, 128, 64, NB) == 16 * 128 + 8 * 16 * 2
+    assert binding.mnnq_packed_size(152064, 3584, 64, NB) == 152064 * 3584 + 8 * 152064 * 56
+    assert binding.mnnq_packed_size(16, 192, 64, NB) == 0                      # K a multiple of 128
+    assert binding.mnnq_packed_size(16, 128, 64, 0 | 32) == 0 and binding.mnnq_packed_size(16, 128, 64, 1 | 32) == 0
+    assert binding.mnnq_packed_size(16, 128, 64, NB | 16) == 0                 # the fp6 plane belongs to mode 0
+    assert binding.mnnq_workspace_size(4, 16, 128, 64, NB) == 4 * 128 + 16
+    assert L.mnnq_linear_decode(FAKE, 16, 128, 64, NB, FAKE, FAKE, None, None, None, 0, None) == NULL
+    assert L.mnnq_linear_decode(FAKE, 16, 128, 64, NB, FAKE, FAKE, None, ODD, None, 0, None) == ALIGN
+    assert L.mnnq_linear_decode_f16(FAKE, 16, 128, 64, NB, FAKE, None, FAKE, None, 0, None) == UNSUP
+    assert L.mnnq_linear_prefill_f16(FAKE, 4, 16, 128, 64, NB, FAKE, None, None, FAKE, None, 0, None) == UNSUP
+    assert L.mnnq_linear_decode_f16_o16(FAKE, 16, 128, 64, NB, FAKE, None, FAKE, None) == UNSUP
+    assert L.mnnq_linear_acc_debug(FAKE, 1, 16, 128, 64, NB, FAKE, FAKE, 0, None) == UNSUP
+    assert L.mnnq_linear_acc_debug(FAKE, 40, 16, 128, 64, NB, FAKE, FAKE, 1, None) == UNSUP
+    assert L.mnnq_linear_prefill(FAKE, 4, 16, 128, 64, NB, FAKE, FAKE, None, ODD, None, 0, None) == ALIGN
     assert L.mnnq_last_hip_error() == 0
     del i64
 

@@ -87,6 +87,29 @@ def test_documented_plans_of_the_qwen2_7b_block():
     assert early(1, 1536, 8960) == 0 and early(1, 2048, 1536) == 1  # Qwen2-1.5B down (4 - 5 of 8 chunks) and q|k|v
 
 
+def test_plans_of_the_byte_form_of_int8_weights():
+    """mode MNNQ_W8_MIN_FLOAT | MNNQ_NATIVE_8BIT: the GEMV keeps seven chunks of two kilobytes per wave in
+    registers (a rolling window beyond sixteen waves per row tile), the GEMM runs 128 x 128 tiles."""
+    NB = B.MODE_W8_MIN_FLOAT | B.NATIVE_8BIT
+    for model, name, M, N, K in shapes():
+        if K % 128:
+            continue
+        chunks = K // 128
+        for what in (1, 2):
+            waves, ks, unroll, prefetch, lds, wgs, tiles_per_wg, early = B.mnnq_plan_debug(what, 1, N, K, NB)
+            assert unroll == 7 and early == 0 and waves % ks == 0 and tiles_per_wg == waves // ks
+            assert ks == 16 or -(-chunks // ks) <= 7
+            assert prefetch == (1 if -(-chunks // ks) > 7 else 0)
+            assert (waves, ks) in (((4, 1), (4, 2), (4, 4), (8, 8), (16, 16)) if what == 1 else
+                                   ((8, 1), (8, 2), (8, 4), (8, 8), (16, 16)))
+            assert lds <= LDS_GEMV and wgs * tiles_per_wg >= N // 16
+        bm, bn, kparts, s, w, lds, wgs, form = B.mnnq_plan_debug(0, M, N, K, NB)
+        assert (bm, bn, form) == (128, 128, 2) and kparts in (1, 2) and lds <= LDS_GEMM
+        assert wgs >= -(-M // 128) * s * -(-N // 128)
+    assert B.mnnq_plan_debug(1, 1, 152064, 3584, NB)[:4] == [4, 4, 7, 0]     # LM head: 28 chunks on four waves
+    assert B.mnnq_plan_debug(1, 1, 3584, 18944, NB)[:4] == [16, 16, 7, 1]    # down: 148 chunks, a window of seven
+
+
 def test_documented_plans_for_few_tokens():
     """Batched decoding (17 .. 128 tokens): 64-row tiles, 64 columns wide unless there are very many,
     the K range in more parts the fewer workgroups there are; very many tiles beyond 64 tokens take
