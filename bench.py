@@ -676,7 +676,7 @@ def main() -> int:
                 oracle.set_threads(threads)
                 oracle.linear_w4a8(xq_o[:xr], sx_o[:xr], q, s, z, want_acc=False)   # warm
                 t1 = time.perf_counter(); reps = 0
-                while reps < 1 or time.perf_counter() - t1 < 0.4:
+                while reps < 1 or time.perf_counter() - t1 < 1.0:
                     oracle.linear_w4a8(xq_o[:xr], sx_o[:xr], q, s, z, want_acc=False); reps += 1
                 dt = (time.perf_counter() - t1) / reps
                 sample_s += dt * reps
