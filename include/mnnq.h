@@ -273,7 +273,7 @@ int mnnq_linear_acc_debug_planes(const void *packed, int64_t M, int64_t N, int64
  * library never reads the environment).  key: one of MNNQ_DECODE_KSPLIT (waves per row tile of the GEMV:
  * 1, 2, 4, 8, 16), MNNQ_DECODE_WAVES (4, 8, 16), MNNQ_DECODE_EARLY (0/1), MNNQ_PREFILL_TILE (tile letter,
  * K split digit, k/q), MNNQ_NO_SKINNY, MNNQ_SKINNY_STAGED (0/1), MNNQ_W8_PLANES (1), MNNQ_FUSED_TWO_KERNEL_MIB,
- * MNNQ_PREFILL6_PLAN (0..5: tile plan of the fp6 GEMM); value: a string of at most 15 characters, or NULL to
+ * MNNQ_PREFILL6_PLAN (0..5: tile plan of the fp6 GEMM), MNNQ_PREFILL6_STAGES (2..4: depth of its LDS rings); value: a string of at most 15 characters, or NULL to
  * clear the override.  Applies to all later calls of the process; not thread safe.  MNNQ_ERR_UNSUPPORTED
  * for an unknown key. */
 int mnnq_debug_set(const char *key, const char *value);

@@ -26,7 +26,8 @@ struct DebugSlot {
 DebugSlot g_debug[kDbgCount] = {
     {"MNNQ_DECODE_KSPLIT", "", false},  {"MNNQ_DECODE_WAVES", "", false},   {"MNNQ_DECODE_EARLY", "", false},
     {"MNNQ_PREFILL_TILE", "", false},   {"MNNQ_NO_SKINNY", "", false},      {"MNNQ_SKINNY_STAGED", "", false},
-    {"MNNQ_W8_PLANES", "", false},      {"MNNQ_FUSED_TWO_KERNEL_MIB", "", false}, {"MNNQ_PREFILL6_PLAN", "", false}};
+    {"MNNQ_W8_PLANES", "", false},      {"MNNQ_FUSED_TWO_KERNEL_MIB", "", false}, {"MNNQ_PREFILL6_PLAN", "", false},
+    {"MNNQ_PREFILL6_STAGES", "", false}};
 }  // namespace
 
 const char* debug_option(DebugKey key) { return g_debug[key].set ? g_debug[key].value : nullptr; }

@@ -204,7 +204,7 @@ __device__ __forceinline__ float quant_fast_limit(float scale, float inv)
 // on the shapes alone otherwise; the environment is never read.
 enum DebugKey {
     kDbgDecodeKsplit, kDbgDecodeWaves, kDbgDecodeEarly, kDbgPrefillTile, kDbgNoSkinny, kDbgSkinnyStaged,
-    kDbgW8Planes, kDbgFusedTwoKernelMib, kDbgPrefill6Plan, kDbgCount
+    kDbgW8Planes, kDbgFusedTwoKernelMib, kDbgPrefill6Plan, kDbgPrefill6Stages, kDbgCount
 };
 const char* debug_option(DebugKey key);
 

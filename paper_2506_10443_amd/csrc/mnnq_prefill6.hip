@@ -184,27 +184,29 @@ __global__ __launch_bounds__(256) void planes_kernel(const int8_t* __restrict__ 
 // matrix instruction that used it last, so the LDS reads run between the matrix instructions; at the
 // top of a group one barrier makes the stage of g + 1 visible and frees the stage of g for the direct
 // loads of g + 2.
-template <int BM, int BN>
+template <int BM, int BN, int NS = 2>
 struct Stage {
     static constexpr int A_BYTES = BM * 96;
     static constexpr int B_BYTES = BN * 48;
     static constexpr int S_BYTES = (BN * 4 + 1023) / 1024 * 1024;   // BN scales in whole wave-wide loads
     static constexpr int W_BYTES = B_BYTES + S_BYTES;                // weight side of a stage: codes, then scales
-    // The activation side is a ring of two, the weight side a ring of two or - for wave tiles of more than
-    // four column tiles, whose weight fragments are still read while their group is contracted - of three.
-    static constexpr int NRING_W = (BN / 32 > 8) ? 3 : 2;
-    static constexpr int W_RING_OFF = 2 * A_BYTES;
-    static constexpr int BYTES = 2 * A_BYTES + NRING_W * W_BYTES;    // all stages of one K part
+    // The activation side is a ring of NS stages (NS - 1 groups in flight or ready beside the one whose
+    // fragments are in registers), the weight side a ring of NS or - for wave tiles of more than four column
+    // tiles, whose weight fragments are still read while their group is contracted - of NS + 1.
+    static constexpr int NRING_A = NS;
+    static constexpr int NRING_W = (BN / 32 > 8) ? NS + 1 : NS;
+    static constexpr int W_RING_OFF = NRING_A * A_BYTES;
+    static constexpr int BYTES = NRING_A * A_BYTES + NRING_W * W_BYTES;    // all stages of one K part
     static constexpr int NA = A_BYTES / 1024, NB = B_BYTES / 1024, NSC = S_BYTES / 1024;
     static_assert(A_BYTES % 1024 == 0 && B_BYTES % 1024 == 0, "whole wave-wide loads");
 };
 
 // LDS of a workgroup: two stages per K part and the junk kilobyte, or the K parts' sums when those
 // need more (they are exchanged after the last stage is dead).
-template <int BM, int BN, int KS>
+template <int BM, int BN, int KS, int NS = 2>
 constexpr size_t lds_bytes6()
 {
-    const size_t stages = (size_t)KS * Stage<BM, BN>::BYTES + 1024;
+    const size_t stages = (size_t)KS * Stage<BM, BN, NS>::BYTES + 1024;
     const size_t sums = KS > 1 ? (size_t)(BM / 32) * (BN / 32) * 16 * 64 * 4 : 0;
     return stages > sums ? stages : sums;
 }
@@ -226,13 +228,13 @@ __device__ __forceinline__ v16f mfma6(v8i a, v8i b, v16f c, int scale_a, int sca
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 2, 2, 0, scale_a, 0, scale_b);
 }
 
-template <int BM, int BN, int WM, int WN, int KS, bool ACC>
+template <int BM, int BN, int WM, int WN, int KS, bool ACC, int NS = 2>
 __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
     const uint8_t* __restrict__ plane, const uint8_t* __restrict__ a6, Layout L, int64_t M, int TMp,
     const float* __restrict__ sx, const float* __restrict__ bias, float* __restrict__ y,
     int32_t* __restrict__ acc_out, int MT, int NT)
 {
-    using St = Stage<BM, BN>;
+    using St = Stage<BM, BN, NS>;
     constexpr int W = WM * WN;                        // waves per K part
     constexpr int TMW = BM / WM / 32, TNW = BN / WN / 32;
     constexpr int NL = (St::NA + St::NB + St::NSC + W - 1) / W;   // direct loads per wave and stage
@@ -249,8 +251,14 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
     uint8_t* const lds = lds_all + part * St::BYTES;
     uint8_t* const junk = lds_all + KS * St::BYTES;
     // stage of group k (counted from this part's first group): activation side, weight side
-    auto stage_a = [&](int k) { return lds + (k & 1) * St::A_BYTES; };
-    auto stage_w = [&](int k) { return lds + St::W_RING_OFF + (St::NRING_W == 2 ? (k & 1) : k % 3) * St::W_BYTES; };
+    auto stage_a = [&](int k) { return lds + (k % St::NRING_A) * St::A_BYTES; };
+    auto stage_w = [&](int k) { return lds + St::W_RING_OFF + (k % St::NRING_W) * St::W_BYTES; };
+    // s_waitcnt for "at most n of this wave's vector-memory operations outstanding, no LDS operation":
+    // vmcnt in bits 3:0 and 15:14, lgkmcnt(0), expcnt left alone - the loads of the NS - 2 youngest stages
+    // may stay in flight at the top of a group
+    constexpr int kInFlight = (NS - 2) * NL;
+    static_assert(kInFlight < 64, "six bits of vmcnt");
+    constexpr int kWaitTop = 0x0070 | (kInFlight & 15) | ((kInFlight >> 4) << 14);
 
     // Workgroups are dealt to the 8 XCDs round-robin by their linear id: each XCD gets whole columns
     // of output tiles, so that a block of weights is fetched into one L2 only.
@@ -348,7 +356,8 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
         issue_stage(0);
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         __builtin_amdgcn_s_barrier();
-        issue_stage(1);
+#pragma unroll
+        for (int s = 1; s < NS; ++s) issue_stage(s);
         read_bs(stage_w(0), 0, 0);
         read_bs(stage_w(0), 1, 1);
         sc[0] = read_sc(stage_w(0), 0);
@@ -358,13 +367,13 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
 
         auto group = [&](auto par_c, int it) {
             constexpr int PAR = decltype(par_c)::value;
-            __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+            __builtin_amdgcn_s_waitcnt(kWaitTop);   // stage it + 1 has landed; no LDS read of this wave is open
             __builtin_amdgcn_s_barrier();
             // Top of group `it`: its activation fragments and the weight fragments of its first two columns
             // are in registers (or on their way); its other columns are read from its weight stage as it
-            // goes, which therefore stays untouched until the next barrier - the loads of group it + 2 go to the
-            // third stage of the weight ring and to the activation stage this group has been read out of.
-            issue_stage(it + 2);
+            // goes, which therefore stays untouched until the next barrier - the loads of group it + NS go to the
+            // extra stage of the weight ring and to the activation stage this group has been read out of.
+            issue_stage(it + NS);
             const uint8_t* cu = stage_w(it);          // weight side of this group
             const uint8_t* nx = stage_w(it + 1);      // ... and of the next one
             const uint8_t* nxa = stage_a(it + 1);
@@ -404,7 +413,8 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
         issue_stage(0);
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         __builtin_amdgcn_s_barrier();
-        issue_stage(1);
+#pragma unroll
+        for (int s = 1; s < NS; ++s) issue_stage(s);
 #pragma unroll
         for (int j = 0; j < TNW; ++j) {
             read_b(stage_w(0), j);
@@ -417,10 +427,10 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
             const int g = gb + it;
             // Top of group g: its fragments are in registers (or on their way).  Once this wave's reads of
             // the stage they came from and its pieces of the next stage are complete, and every other
-            // wave's too, the old stage can be loaded over and the next one read.
-            __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+            // wave's too, the old stage can be loaded over (with group g + NS) and the next one read.
+            __builtin_amdgcn_s_waitcnt(kWaitTop);   // all but the loads of the NS - 2 youngest stages, and the LDS reads
             __builtin_amdgcn_s_barrier();
-            issue_stage(it + 2);
+            issue_stage(it + NS);
             if (KS > 1 && g >= ge) continue;      // the shorter share idles through the last round
             const uint8_t* nx = stage_w(it + 1);   // stage of group g + 1: weight side
             const uint8_t* nxa = stage_a(it + 1);  // ... and activation side
@@ -541,15 +551,15 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
     }
 }
 
-template <int BM, int BN, int WM, int WN, int KS, bool ACC>
+template <int BM, int BN, int WM, int WN, int KS, bool ACC, int NS = 2>
 int launch6(const uint8_t* packed, const Layout& L, int64_t M, const uint8_t* a6, int TMp, const float* sx,
             const float* bias, float* y, int32_t* acc, hipStream_t st)
 {
     const int MT = (int)((M + BM - 1) / BM);
     const int NT = (int)((L.N + BN - 1) / BN);
-    constexpr size_t smem = lds_bytes6<BM, BN, KS>();
+    constexpr size_t smem = lds_bytes6<BM, BN, KS, NS>();
     static_assert(smem <= kLdsPerWorkgroup, "LDS of a workgroup");
-    auto kern = prefill6_kernel<BM, BN, WM, WN, KS, ACC>;
+    auto kern = prefill6_kernel<BM, BN, WM, WN, KS, ACC, NS>;
     static thread_local int allowed_dev = -1;
     if (int s = allow_large_lds(kern, smem, allowed_dev)) return s;
     const int64_t blocks = (int64_t)MT * ((NT + 7) / 8) * 8;
@@ -592,20 +602,40 @@ int choose_plan6(const Layout& L, int64_t M)
     return c2 < c0 ? 2 : 0;
 }
 
+// Stages of the LDS rings for a plan (groups in flight or ready beside the one being contracted, plus one):
+// the small tiles spend little time per group and need their loads issued further ahead.
+int choose_stages6(int plan, const Layout& L, int64_t M)
+{
+    // measured on the Qwen2-7B shapes (two -> four stages): down 129 -> 107 us, o 31.6 -> 28.0, q|k|v 44.1 -> 41.6;
+    // the 128 x 256 tiles gain nothing from a third stage (a group keeps them busy for longer than a load takes).
+    // Four stages of the four-wave 128 x 128 form leave room for two workgroups per CU where two stages
+    // leave room for three: with more tiles than two per CU the third workgroup is worth more than the
+    // deeper ring (Llama-3-8B's q|k|v, 768 tiles: 82.6 us with two stages, 92.8 with four).
+    const int64_t t0 = ((M + 127) / 128) * ((L.N + 127) / 128);
+    int ns = plan == 1 ? 4 : (plan == 0 && t0 <= 2 * (int64_t)num_cus()) ? 4 : 2;
+    if (const char* e = debug_option(kDbgPrefill6Stages)) {   // tests and tuning
+        const int v = e[0] - '0';
+        if (v >= 2 && v <= 4) ns = v;
+    }
+    if (plan >= 4 || (plan >= 2 && ns > 3)) ns = 2;   // what fits the LDS: 4 for the 128 x 128 tiles, 3 for 128 x 256
+    return ns;
+}
+
 struct Plan6Info {
     int BM, BN, KS, waves;
     size_t lds;
 };
 
-Plan6Info plan6_info(int plan)
+Plan6Info plan6_info(int plan, const Layout& L, int64_t M)
 {
+    const int ns = choose_stages6(plan, L, M);
     switch (plan) {
-        case 1: return {128, 128, 2, 8, lds_bytes6<128, 128, 2>()};
-        case 2: return {128, 256, 1, 4, lds_bytes6<128, 256, 1>()};
-        case 3: return {128, 256, 2, 8, lds_bytes6<128, 256, 2>()};
+        case 1: return {128, 128, 2, 8, ns == 4 ? lds_bytes6<128, 128, 2, 4>() : ns == 3 ? lds_bytes6<128, 128, 2, 3>() : lds_bytes6<128, 128, 2>()};
+        case 2: return {128, 256, 1, 4, ns == 3 ? lds_bytes6<128, 256, 1, 3>() : lds_bytes6<128, 256, 1>()};
+        case 3: return {128, 256, 2, 8, ns == 3 ? lds_bytes6<128, 256, 2, 3>() : lds_bytes6<128, 256, 2>()};
         case 4: return {256, 256, 1, 8, lds_bytes6<256, 256, 1>()};
         case 5: return {128, 320, 1, 4, lds_bytes6<128, 320, 1>()};
-        default: return {128, 128, 1, 4, lds_bytes6<128, 128, 1>()};
+        default: return {128, 128, 1, 4, ns == 4 ? lds_bytes6<128, 128, 1, 4>() : ns == 3 ? lds_bytes6<128, 128, 1, 3>() : lds_bytes6<128, 128, 1>()};
     }
 }
 
@@ -632,7 +662,7 @@ bool prefill6_wanted(const Layout& L, int64_t M)
 
 void describe_prefill6(const Layout& L, int64_t M, int32_t out[8])
 {
-    const Plan6Info p = plan6_info(choose_plan6(L, M));
+    const Plan6Info p = plan6_info(choose_plan6(L, M), L, M);
     const int64_t MT = (M + p.BM - 1) / p.BM, NT = (L.N + p.BN - 1) / p.BN;
     out[0] = p.BM;
     out[1] = p.BN;
@@ -668,8 +698,21 @@ int launch_prefill6(const uint8_t* packed, const Layout& L, int64_t M, const voi
 {
     const int TMp = tmp_tiles(M);
     const uint8_t* a6 = static_cast<const uint8_t*>(planes);
-    if (acc_debug) return launch6<128, 128, 2, 2, 1, true>(packed, L, M, a6, TMp, sx, bias, y, acc_debug, st);
-    switch (choose_plan6(L, M)) {
+    if (acc_debug) return launch6<128, 128, 2, 2, 1, true, 4>(packed, L, M, a6, TMp, sx, bias, y, acc_debug, st);   // plan 0 as it runs
+    const int plan = choose_plan6(L, M), ns = choose_stages6(plan, L, M);
+#define MNNQ_ARGS6 packed, L, M, a6, TMp, sx, bias, y, nullptr, st
+    if (ns == 4) {
+        if (plan == 1) return launch6<128, 128, 2, 2, 2, false, 4>(MNNQ_ARGS6);
+        if (plan == 0) return launch6<128, 128, 2, 2, 1, false, 4>(MNNQ_ARGS6);
+    }
+    if (ns == 3) {
+        if (plan == 0) return launch6<128, 128, 2, 2, 1, false, 3>(MNNQ_ARGS6);
+        if (plan == 1) return launch6<128, 128, 2, 2, 2, false, 3>(MNNQ_ARGS6);
+        if (plan == 2) return launch6<128, 256, 2, 2, 1, false, 3>(MNNQ_ARGS6);
+        if (plan == 3) return launch6<128, 256, 2, 2, 2, false, 3>(MNNQ_ARGS6);
+    }
+#undef MNNQ_ARGS6
+    switch (plan) {
         case 1: return launch6<128, 128, 2, 2, 2, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
         case 2: return launch6<128, 256, 2, 2, 1, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);
         case 3: return launch6<128, 256, 2, 2, 2, false>(packed, L, M, a6, TMp, sx, bias, y, nullptr, st);

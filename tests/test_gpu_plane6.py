@@ -81,6 +81,24 @@ def test_prefill6_every_plan(plan, M, N, K):
 
 
 @pytest.mark.parametrize("M,N,K", [(200, 400 - 400 % 16, 1536), (129, 592, 448), (40, 48, 64)])
+def test_prefill6_deeper_rings(M, N, K):
+    """Three and four stages in the LDS rings (MNNQ_PREFILL6_STAGES) for the plans that have them."""
+    W, x, q, s, z, xq, sx = make(N, K, M, 4250, special=True)
+    _, y_o = oracle.linear_w4a8(xq, sx, q, s, z)
+    packed = B.mnnq_pack_weights(dev(W), mode=MODE)
+    ws = torch.empty(B.mnnq_workspace_size(M, N, K, 64, MODE), dtype=torch.uint8, device="cuda:0")
+    try:
+        for plan, stages in ((0, 3), (0, 4), (1, 3), (1, 4), (2, 3), (3, 3)):
+            note("prefill6 plan", plan, "stages", stages, "M", M, "N", N, "K", K)
+            B.mnnq_debug_set("MNNQ_PREFILL6_PLAN", plan)
+            B.mnnq_debug_set("MNNQ_PREFILL6_STAGES", stages)
+            y = B.mnnq_linear_prefill(packed, N, K, dev(xq), dev(sx), mode=MODE, workspace=ws).cpu().numpy()
+            assert np.abs(y - y_o).max() <= TOL_A8 * np.abs(y_o).max(), (plan, stages)
+    finally:
+        B.mnnq_debug_set("MNNQ_PREFILL6_STAGES", None)
+
+
+@pytest.mark.parametrize("M,N,K", [(200, 400 - 400 % 16, 1536), (129, 592, 448), (40, 48, 64)])
 def test_prefill6_accumulators_bit_exact(M, N, K):
     note("prefill6 acc", "M", M, "N", N, "K", K)
     W, x, q, s, z, xq, sx = make(N, K, M, 4300, special=True)
