@@ -110,7 +110,8 @@ def main() -> int:
                     help="force one tile plan of the fp6 GEMM for every layer (tuning; default: the library's choice)")
     ap.add_argument("--debug-set", action="append", default=[], metavar="KEY=VALUE",
                     help="a test / tuning switch of the library for the whole run (mnnq_debug_set), e.g. MNNQ_PREFILL_TILE=v1")
-    ap.add_argument("--peaks", action="store_true", help="also measure what this GPU sustains (`achievable`)")
+    ap.add_argument("--peaks", action="store_true", help="(default) measure what this GPU sustains (`achievable`)")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the measurement of what this GPU sustains")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -511,7 +512,8 @@ def main() -> int:
         del src, dst
 
     achievable = None
-    if args.peaks:
+    if not args.no_peaks:
+        note("what the GPU sustains (streaming read, matrix loops)")
         sink = torch.zeros(4, dtype=torch.float32, device=dev)
         big = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)       # 1 GiB: 4x the Infinity Cache
         t = time_run(lambda: BL().L.mnnqb_peak_read(big.data_ptr(), big.numel(), sink.data_ptr(), stream_ptr()), 10) * 1e-3
