@@ -257,7 +257,8 @@ int mnnq_pack_from_quantized(const uint8_t *q, const float *scale, const void *z
 
 /* Integer group accumulators of the W4A8 kernels, for bit-exact checks:
  *   acc[m, n, g] = sum_{k in g} xq[m,k] * (q[n,k] - zero[n,g])      (int32 [M, N, G]);
- * in mode MNNQ_W4_MIN_FLOAT there is no zero point: acc = sum_{k in g} xq[m,k] * q[n,k].
+ * in mode MNNQ_W4_MIN_FLOAT there is no zero point: acc = sum_{k in g} xq[m,k] * q[n,k]
+ * (MNNQ_W8_MIN_FLOAT: per nibble plane, see there; MNNQ_ERR_UNSUPPORTED with MNNQ_NATIVE_8BIT).
  * use_prefill_kernel = 0 runs the decode kernel's inner loop row by row (any M),
  * 1 runs the prefill kernel's MFMA loop. */
 int mnnq_linear_acc_debug(const void *packed, int64_t M, int64_t N, int64_t K, int group, int mode,
@@ -273,8 +274,8 @@ int mnnq_linear_acc_debug_planes(const void *packed, int64_t M, int64_t N, int64
  * library never reads the environment).  key: one of MNNQ_DECODE_KSPLIT (waves per row tile of the GEMV:
  * 1, 2, 4, 8, 16), MNNQ_DECODE_WAVES (4, 8, 16), MNNQ_DECODE_EARLY (0/1), MNNQ_PREFILL_TILE (tile letter,
  * K split digit, k/q), MNNQ_NO_SKINNY, MNNQ_SKINNY_STAGED (0/1), MNNQ_W8_PLANES (1), MNNQ_FUSED_TWO_KERNEL_MIB,
- * MNNQ_PREFILL6_PLAN (0..5: tile plan of the fp6 GEMM), MNNQ_PREFILL6_STAGES (2..4: depth of its LDS rings); value: a string of at most 15 characters, or NULL to
- * clear the override.  Applies to all later calls of the process; not thread safe.  MNNQ_ERR_UNSUPPORTED
+ * MNNQ_PREFILL6_PLAN (0..5: tile plan of the fp6 GEMM), MNNQ_PREFILL6_STAGES (2..4: depth of its LDS rings);
+ * value: a string of at most 15 characters, or NULL to clear the override.  Applies to all later calls of the process; not thread safe.  MNNQ_ERR_UNSUPPORTED
  * for an unknown key. */
 int mnnq_debug_set(const char *key, const char *value);
 
@@ -282,7 +283,9 @@ int mnnq_debug_set(const char *key, const char *value);
  * which kernel configuration a call would launch).  Nothing is launched and no device is needed.
  * what = 0: mnnq_linear_prefill with M > 16 tokens (the tiled GEMM); out8 = {tile rows, tile columns,
  *           K parts inside a workgroup, K split over workgroups, waves per workgroup, LDS bytes per
- *           workgroup, workgroups, 1 if the two nibble planes of int8 weights are merged in registers};
+ *           workgroup, workgroups, form: 0 int4 on the int8 matrix instruction, 1 int8 weights with the two
+ *           nibble planes merged in registers, 2 int8 weights in the byte form, 6 the GEMM on the fp6 matrix
+ *           instructions (what a call with a workspace runs for a buffer with the matrix-core plane)};
  * what = 1: mnnq_linear_decode; what = 2: mnnq_linear_decode_fused without workspace; out8 = {waves per
  *           workgroup, waves per row tile, weight chunks a wave holds in registers, 1 if it loops with a
  *           prefetch, LDS bytes per workgroup, workgroups, row tiles per workgroup, 1 if the activation
