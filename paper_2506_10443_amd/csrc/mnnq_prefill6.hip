@@ -514,6 +514,11 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
 
     // Output: y = yacc * sx[m] + bias[n].  Buffer accesses: rows past M fall outside the buffers (loads
     // give 0, stores are dropped), columns past N are sent out of range, a NULL bias is an empty buffer.
+    // A wave's 8 rows x 32 TNW columns at a time go through a private LDS patch (rows padded by four floats)
+    // and leave as 128-bit stores of whole row segments: a quarter of the store instructions of the direct
+    // form, whose lanes hold single columns.  The patch lies where the stages were (one K part: after every
+    // wave's loads have landed and every wave has left the loop) or in the wave's own slots of the K parts'
+    // sums (which it has read by then; LDS operations of one wave complete in order).
     const __amdgpu_buffer_rsrc_t rs_sx =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(sx), 0, (int)(M * 4), kBufFlags);
     const __amdgpu_buffer_rsrc_t rs_bias =
@@ -524,27 +529,51 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
     const int row0 = tile_m * BM + wm * TMW * 32;
     const int col0 = tile_n * BN + wn * TNW * 32;
     const int esz = L.out16 ? 2 : 4;
+    constexpr int RS = TNW * 32 + 4;                  // floats per patch row
+    constexpr int UPR = TNW * 8;                      // 16-byte units per row segment
+    constexpr int PATCH_STRIDE = KS > 1 ? TMW * TNW * 16 * 64 : 8 * RS;   // floats between the waves' patches
+    static_assert(8 * RS <= PATCH_STRIDE, "the patch fits the wave's slots");
+    if (KS == 1) {
+        __builtin_amdgcn_s_waitcnt(0x0070);           // vmcnt(0) lgkmcnt(0): this wave's direct loads have landed
+        __builtin_amdgcn_s_barrier();                 // ... and everybody's; nobody reads a stage any more
+    }
+    float* patch = reinterpret_cast<float*>(lds_all) + w * PATCH_STRIDE;
+    float* wr = patch + (4 * (lane >> 5)) * RS + (lane & 31);
+    float bj[TNW];
 #pragma unroll
-    for (int j = 0; j < TNW; ++j) {
-        const int n = col0 + j * 32 + (lane & 31);
-        const float bj = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_bias, (lane & 31) * 4, (col0 + j * 32) * 4, 0));
-        const int y_voff = n < N ? ((lane >> 5) * 4 * N + (lane & 31)) * esz : kOutOfRange;
+    for (int j = 0; j < TNW; ++j)
+        bj[j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_bias, (lane & 31) * 4, (col0 + j * 32) * 4, 0));
 #pragma unroll
-        for (int i = 0; i < TMW; ++i) {
+    for (int i = 0; i < TMW; ++i) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int mrow = row0 + i * 32 + 8 * q;     // + 4 (lane / 32) + r % 4
-                const v4i s4 = __builtin_amdgcn_raw_buffer_load_b128(rs_sx, (lane >> 5) * 16, mrow * 4, 0);
+        for (int q = 0; q < 4; ++q) {
+            const int mrow = row0 + i * 32 + 8 * q;   // the patch's first row; this lane wrote rows + 4 (lane / 32) + rr
+            const v4i s4 = __builtin_amdgcn_raw_buffer_load_b128(rs_sx, (lane >> 5) * 16, mrow * 4, 0);
 #pragma unroll
-                for (int rr = 0; rr < 4; ++rr) {
-                    const float v = fmaf(yacc[i * TNW + j][q * 4 + rr], __int_as_float(s4[rr]), bj);
-                    const int soff = ((mrow + rr) * N + col0 + j * 32) * esz;
-                    if (L.out16) {
-                        const _Float16 hv = (_Float16)v;
-                        __builtin_amdgcn_raw_buffer_store_b16(*reinterpret_cast<const short*>(&hv), rs_y, y_voff, soff, 0);
-                    } else {
-                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs_y, y_voff, soff, 0);
-                    }
+            for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+                for (int j = 0; j < TNW; ++j)
+                    wr[rr * RS + j * 32] = fmaf(yacc[i * TNW + j][q * 4 + rr], __int_as_float(s4[rr]), bj[j]);
+#pragma unroll
+            for (int p = 0; p < TNW; ++p) {
+                const int u = p * 64 + lane;          // unit of the patch: row u / UPR, columns 4 (u % UPR) ..
+                const int r = u / UPR, c4 = u % UPR;
+                // (read as a struct of floats: the same scalar type as the writes for alias analysis)
+                const float4 f = *reinterpret_cast<const float4*>(patch + r * RS + c4 * 4);
+                const int n = col0 + c4 * 4;          // N is a multiple of 16: a unit lies inside the row or past it
+                const int voff = n < N ? (r * N + c4 * 4) * esz : kOutOfRange;
+                const int soff = (mrow * N + col0) * esz;
+                if (L.out16) {
+                    const _Float16 h0 = (_Float16)f.x, h1 = (_Float16)f.y, h2 = (_Float16)f.z, h3 = (_Float16)f.w;
+                    const v2i v = {(int)((uint32_t) * reinterpret_cast<const uint16_t*>(&h0) |
+                                         ((uint32_t) * reinterpret_cast<const uint16_t*>(&h1) << 16)),
+                                   (int)((uint32_t) * reinterpret_cast<const uint16_t*>(&h2) |
+                                         ((uint32_t) * reinterpret_cast<const uint16_t*>(&h3) << 16))};
+                    __builtin_amdgcn_raw_buffer_store_b64(v, rs_y, voff, soff, 0);
+                } else {
+                    const v4i v = {(int)__float_as_uint(f.x), (int)__float_as_uint(f.y), (int)__float_as_uint(f.z),
+                                   (int)__float_as_uint(f.w)};
+                    __builtin_amdgcn_raw_buffer_store_b128(v, rs_y, voff, soff, 0);
                 }
             }
         }

@@ -153,6 +153,24 @@ def test_prefill6_bias_fused_and_fallbacks():
     assert np.array_equal(ys, yf)
 
 
+@pytest.mark.parametrize("plan", [0, 1, 2, 5])
+def test_prefill6_binary16_output_and_bias(plan):
+    """The output stage of the fp6 GEMM (row segments through an LDS patch, 128-bit stores; 64-bit ones for
+    binary16) on ragged shapes: the binary16 call must give the fp32 result rounded once."""
+    for M, N, K in ((150, 512, 1536), (333, 1040, 192), (77, 336, 320)):
+        note("prefill6 out16 plan", plan, M, N, K)
+        W, x, q, s, z, xq, sx = make(N, K, M, 4600 + plan)
+        bias = (0.5 * np.random.default_rng(4601).standard_normal(N)).astype(np.float32)
+        _, y_o = oracle.linear_w4a8(xq, sx, q, s, z, bias=bias)
+        packed = B.mnnq_pack_weights(dev(W), mode=MODE)
+        B.mnnq_debug_set("MNNQ_PREFILL6_PLAN", plan)
+        assert B.mnnq_plan_debug(0, M, N, K, mode=MODE)[7] == 6
+        y32 = B.mnnq_linear_prefill_fused(packed, N, K, dev(x), bias=dev(bias), mode=MODE).cpu().numpy()
+        assert np.abs(y32 - y_o).max() <= TOL_A8 * np.abs(y_o).max()
+        y16 = B.mnnq_linear_prefill_fused_o16(packed, N, K, dev(x), bias=dev(bias), mode=MODE).cpu().numpy()
+        assert y16.dtype == np.float16 and np.array_equal(y16, y32.astype(np.float16))
+
+
 def test_few_output_tiles_take_the_int8_gemm_unless_a_plan_is_forced():
     M, N, K = 150, 512, 4096
     assert B.mnnq_plan_debug(0, M, N, K, mode=MODE)[7] != 6
