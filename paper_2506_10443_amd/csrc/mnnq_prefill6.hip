@@ -259,6 +259,9 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
     constexpr int kInFlight = (NS - 2) * NL;
     static_assert(kInFlight < 64, "six bits of vmcnt");
     constexpr int kWaitTop = 0x0070 | (kInFlight & 15) | ((kInFlight >> 4) << 14);
+    constexpr int kFirst = (NS - 1) * NL;             // prologue: all but the first stage may still be in flight
+    static_assert(kFirst < 64, "six bits of vmcnt");
+    constexpr int kWaitFirst = 0x0F70 | (kFirst & 15) | ((kFirst >> 4) << 14);
 
     // Workgroups are dealt to the 8 XCDs round-robin by their linear id: each XCD gets whole columns
     // of output tiles, so that a block of weights is fetched into one L2 only.
@@ -353,11 +356,11 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
             b[slot] = frag6(st + b_frag + j * kPlaneBlockBytes, off16, (slot & 1) ? off8x : off8);
         };
         auto read_sc = [&](const uint8_t* st, int j) { return *reinterpret_cast<const float*>(st + s_frag + j * 128); };
-        issue_stage(0);
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-        __builtin_amdgcn_s_barrier();
+        // all NS stages are requested at once; the first one is waited for
 #pragma unroll
-        for (int s = 1; s < NS; ++s) issue_stage(s);
+        for (int s = 0; s < NS; ++s) issue_stage(s);
+        __builtin_amdgcn_s_waitcnt(kWaitFirst);
+        __builtin_amdgcn_s_barrier();
         read_bs(stage_w(0), 0, 0);
         read_bs(stage_w(0), 1, 1);
         sc[0] = read_sc(stage_w(0), 0);
@@ -410,11 +413,11 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
             if (it + 1 < n_iter) group(std::integral_constant<int, (TNW & 1)>{}, it + 1);
         }
     } else {
-        issue_stage(0);
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-        __builtin_amdgcn_s_barrier();
+        // all NS stages are requested at once; the first one is waited for
 #pragma unroll
-        for (int s = 1; s < NS; ++s) issue_stage(s);
+        for (int s = 0; s < NS; ++s) issue_stage(s);
+        __builtin_amdgcn_s_waitcnt(kWaitFirst);
+        __builtin_amdgcn_s_barrier();
 #pragma unroll
         for (int j = 0; j < TNW; ++j) {
             read_b(stage_w(0), j);
