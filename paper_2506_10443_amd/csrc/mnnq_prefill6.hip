@@ -284,9 +284,9 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
     const int s_base = (int)L.plane_codes_bytes() + tile_n * (BN / 32) * 128, s_step = (int)L.T32p * 128;
     const int voff = lane * 16;
 
-    // Stage of the part's group k <- group gb + k: this wave's NL pieces of 1 KiB (slots past the stage's
-    // pieces go to a junk kilobyte with an out-of-range source, so that every wave issues the same number
-    // of loads).  Groups past the end of the matrix lie outside the buffers and arrive as zeros.
+    // Stage of the part's group k <- group gb + k: this wave's NL pieces of 1 KiB (with more than two stages,
+    // whose waits count loads, slots past the stage's pieces go to a junk kilobyte with an out-of-range
+    // source, so that every wave issues the same number of loads).  Groups past the end of the matrix lie outside the buffers and arrive as zeros.
     auto issue_stage = [&](int k) {
         const int g = gb + k;
         uint8_t* sta = stage_a(k);
@@ -306,7 +306,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, MNNQ_LDS(sta + s * 1024), 16, voff, so_a, 0, 0);
             else if (s < St::NA + St::NB + St::NSC)   // codes, then scales: consecutive in the stage
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(stw + (s - St::NA) * 1024), 16, voff, so_ws, 0, 0);
-            else
+            else if (NS > 2)   // (two stages: the waits are for all loads, nothing is counted)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, MNNQ_LDS(junk), 16, voff, kOutOfRange, 0, 0);
         }
     };
@@ -356,11 +356,19 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
             b[slot] = frag6(st + b_frag + j * kPlaneBlockBytes, off16, (slot & 1) ? off8x : off8);
         };
         auto read_sc = [&](const uint8_t* st, int j) { return *reinterpret_cast<const float*>(st + s_frag + j * 128); };
-        // all NS stages are requested at once; the first one is waited for
+        if (NS > 2) {
+            // all NS stages are requested at once; the first one is waited for (by count: every wave issues NL
+            // loads per stage)
 #pragma unroll
-        for (int s = 0; s < NS; ++s) issue_stage(s);
-        __builtin_amdgcn_s_waitcnt(kWaitFirst);
-        __builtin_amdgcn_s_barrier();
+            for (int s = 0; s < NS; ++s) issue_stage(s);
+            __builtin_amdgcn_s_waitcnt(kWaitFirst);
+            __builtin_amdgcn_s_barrier();
+        } else {
+            issue_stage(0);
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+            __builtin_amdgcn_s_barrier();
+            issue_stage(1);
+        }
         read_bs(stage_w(0), 0, 0);
         read_bs(stage_w(0), 1, 1);
         sc[0] = read_sc(stage_w(0), 0);
@@ -413,11 +421,19 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void prefill6_kernel(
             if (it + 1 < n_iter) group(std::integral_constant<int, (TNW & 1)>{}, it + 1);
         }
     } else {
-        // all NS stages are requested at once; the first one is waited for
+        if (NS > 2) {
+            // all NS stages are requested at once; the first one is waited for (by count: every wave issues NL
+            // loads per stage)
 #pragma unroll
-        for (int s = 0; s < NS; ++s) issue_stage(s);
-        __builtin_amdgcn_s_waitcnt(kWaitFirst);
-        __builtin_amdgcn_s_barrier();
+            for (int s = 0; s < NS; ++s) issue_stage(s);
+            __builtin_amdgcn_s_waitcnt(kWaitFirst);
+            __builtin_amdgcn_s_barrier();
+        } else {
+            issue_stage(0);
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+            __builtin_amdgcn_s_barrier();
+            issue_stage(1);
+        }
 #pragma unroll
         for (int j = 0; j < TNW; ++j) {
             read_b(stage_w(0), j);
